@@ -1,0 +1,109 @@
+"""Acceptance rule for a retrieval result against the fp64 oracle (test infrastructure).
+
+A result G = (index int32[Q,k], score float32[Q,k]) is accepted for query r, with tolerance tau, iff
+  1. structure  : exactly m = min(k, |C_r|) valid entries, then padding (-1, -inf); valid indices are
+                  unique, inside [0, N) and every one passes the tag filter (never tolerance-relaxed);
+  2. scores     : |G.score[p] - s*(G.index[p])| <= tau and |G.score[p] - O.score[p]| <= tau (rank-wise);
+  3. membership : every i with s*(i) > theta + tau is in G, every i in G has s*(i) >= theta - tau, where
+                  theta is the oracle's k-th best qualifying score; if the oracle's k-th and (k+1)-th
+                  scores differ by more than tau the index sets must be equal;
+  4. order      : G is sorted by (own score desc, index asc), and no later entry beats an earlier one by
+                  more than 2 tau in oracle score.
+s*(i) are the oracle's fp64 scores; O is the oracle's own top-k.
+"""
+from __future__ import annotations
+
+import dataclasses
+
+import numpy as np
+
+from . import kb_oracle
+
+
+@dataclasses.dataclass
+class Report:
+    queries: int = 0
+    strict: int = 0          # queries decided by exact index-set equality
+    near_tie: int = 0        # queries where the k-th/(k+1)-th oracle gap was <= tau
+    max_score_err: float = 0.0
+    exact_order: int = 0     # queries whose index sequence equals the oracle's
+
+
+def check_query(g_index, g_score, s_star, k, tau, tags=None, qmask=None, report: Report | None = None, label=""):
+    g_index = np.asarray(g_index).astype(np.int64)
+    g_score = np.asarray(g_score).astype(np.float64)
+    s_star = np.asarray(s_star, dtype=np.float64)
+    N = s_star.shape[0]
+    assert g_index.shape == (k,) and g_score.shape == (k,), f"{label}: bad output shape"
+    o_index, o_score, n_cand = kb_oracle.select(s_star, k, tags=tags, qmask=qmask)
+    m = min(k, n_cand)
+
+    # 1. structure
+    valid = g_index >= 0
+    assert valid[:m].all() and not valid[m:].any(), (
+        f"{label}: expected {m} valid entries then padding, got index={g_index.tolist()}")
+    assert np.all(np.isneginf(g_score[m:])), f"{label}: padding scores must be -inf"
+    gi = g_index[:m]
+    assert np.all(gi < N), f"{label}: index out of range"
+    assert len(np.unique(gi)) == m, f"{label}: duplicate indices {gi.tolist()}"
+    if qmask is not None:
+        ok = (np.asarray(tags, dtype=np.uint64)[gi] & np.uint64(qmask)) != 0
+        assert ok.all(), f"{label}: filtered-out entries returned: {gi[~ok].tolist()}"
+    if m == 0:
+        if report is not None:
+            report.queries += 1
+            report.strict += 1
+            report.exact_order += 1
+        return
+
+    # 2. scores
+    err_own = np.abs(g_score[:m] - s_star[gi])
+    err_rank = np.abs(g_score[:m] - o_score[:m])
+    assert err_own.max() <= tau, f"{label}: score error {err_own.max():.3e} > {tau:.1e}"
+    assert err_rank.max() <= tau, f"{label}: rank-wise score error {err_rank.max():.3e} > {tau:.1e}"
+
+    # 3. membership
+    if qmask is not None:
+        cand = (np.asarray(tags, dtype=np.uint64) & np.uint64(qmask)) != 0
+    else:
+        cand = np.ones(N, dtype=bool)
+    strict_case = True
+    if n_cand > k:
+        theta = o_score[k - 1]
+        must = np.flatnonzero(cand & (s_star > theta + tau))
+        missing = np.setdiff1d(must, gi)
+        assert missing.size == 0, f"{label}: entries clearly above the k-th score are missing: {missing[:8].tolist()}"
+        assert np.all(s_star[gi] >= theta - tau), f"{label}: returned an entry clearly below the k-th score"
+        # (k+1)-th best qualifying oracle score
+        sc = np.where(cand, s_star, -np.inf)
+        kth1 = np.partition(sc, N - (k + 1))[N - (k + 1)]
+        strict_case = (theta - kth1) > tau
+    if strict_case:
+        assert set(gi.tolist()) == set(o_index[:m].tolist()), (
+            f"{label}: index set differs from the oracle's although the k-th gap exceeds tau")
+
+    # 4. order
+    for p in range(m - 1):
+        a, b = g_score[p], g_score[p + 1]
+        assert a > b or (a == b and g_index[p] < g_index[p + 1]), (
+            f"{label}: output not sorted by (score desc, index asc) at position {p}")
+    so = s_star[gi]
+    run_min = np.minimum.accumulate(so)          # lowest oracle score among earlier positions
+    assert np.all(so[1:] - run_min[:-1] <= 2 * tau), f"{label}: order contradicts the oracle by more than 2 tau"
+
+    if report is not None:
+        report.queries += 1
+        report.strict += int(strict_case)
+        report.near_tie += int(not strict_case)
+        report.max_score_err = max(report.max_score_err, float(err_own.max()))
+        report.exact_order += int(np.array_equal(gi, o_index[:m]))
+
+
+def check(g_index, g_score, s_star, k, tau, tags=None, qmask=None, label="") -> Report:
+    """All queries.  s_star is the oracle's [Q, N] score matrix."""
+    rep = Report()
+    Q = s_star.shape[0]
+    for r in range(Q):
+        check_query(g_index[r], g_score[r], s_star[r], k, tau, tags=tags,
+                    qmask=None if qmask is None else qmask[r], report=rep, label=f"{label} query {r}")
+    return rep

@@ -1,0 +1,249 @@
+/*
+ * TEST INFRASTRUCTURE ONLY -- brute-force fp64 definition of knowledge-base
+ * retrieval.  Nothing in the product path may link, load or call this file.
+ *
+ * What is defined here.  The paper's State Selector "retrieves relevant
+ * (state, optimization) pairs" from a store of <state, <optimization, score>>
+ * entries and the Optimization Selector keeps the top-k of them (Section 3,
+ * component list and the paragraph that walks through one task).  The paper
+ * gives no numeric form for that step; the numeric model used throughout this
+ * repository is: every entry i has a key vector K_i, a query state is a vector
+ * Q_r, relevance is the cosine of the two, an optional 64-bit tag filter keeps
+ * entry i for query r iff (qmask_r & tag_i) != 0, and the k best survivors are
+ * returned ordered by (score descending, index ascending).
+ *
+ * Fidelity to the paper is therefore unpinned (the paper prints no worked
+ * retrieval example); fidelity to the plain definition above is pinned by the
+ * CPU tests: a hand-computed cosine example, self-query / permutation /
+ * scaling invariants, an independent numpy formulation, an O(N^2) rank count
+ * on tiny inputs, and an independent library decode of every bf16 / e4m3 code.
+ *
+ * Everything is fp64, plain loops, full sort.  No blocking, no partial
+ * selection, no shared code with the GPU path.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_FP8_E4M3 = 2 };
+
+/* bf16 = the upper 16 bits of an IEEE binary32; the value is exact in fp64. */
+double oracle_decode_bf16(uint16_t bits)
+{
+    uint32_t w = (uint32_t)bits << 16;
+    float f;
+    memcpy(&f, &w, sizeof f);
+    return (double)f;
+}
+
+/* OCP 8-bit float E4M3 ("FN" flavour): 1 sign, 4 exponent (bias 7), 3 mantissa
+ * bits; exponent field 0 is subnormal m/8 * 2^-6; there is no infinity and the
+ * single NaN pattern per sign is S.1111.111; the largest finite value is 448. */
+double oracle_decode_e4m3(uint8_t code)
+{
+    int s = (code >> 7) & 1;
+    int e = (code >> 3) & 15;
+    int m = code & 7;
+    double v;
+    if (e == 15 && m == 7)
+        return NAN;
+    if (e == 0)
+        v = ldexp((double)m / 8.0, -6);
+    else
+        v = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return s ? -v : v;
+}
+
+static size_t elem_bytes(int dtype)
+{
+    return dtype == ORACLE_F32 ? 4 : dtype == ORACLE_BF16 ? 2 : 1;
+}
+
+/* Decode row `row` of a row-major [rows, d] array of stored bits into fp64.
+ * For e4m3 keys the stored value is row_scale[row] * decode(code). */
+static void decode_row(const void *base, int dtype, const float *row_scale, int64_t row, int64_t d, double *out)
+{
+    const uint8_t *p = (const uint8_t *)base + (size_t)row * (size_t)d * elem_bytes(dtype);
+    for (int64_t j = 0; j < d; ++j) {
+        if (dtype == ORACLE_F32) {
+            float f;
+            memcpy(&f, p + 4 * j, 4);
+            out[j] = (double)f;
+        } else if (dtype == ORACLE_BF16) {
+            uint16_t h;
+            memcpy(&h, p + 2 * j, 2);
+            out[j] = oracle_decode_bf16(h);
+        } else {
+            double sc = row_scale ? (double)row_scale[row] : 1.0;
+            out[j] = sc * oracle_decode_e4m3(p[j]);
+        }
+    }
+}
+
+static double l2norm(const double *v, int64_t d)
+{
+    double s = 0.0;
+    for (int64_t j = 0; j < d; ++j)
+        s += v[j] * v[j];
+    return sqrt(s);
+}
+
+/*
+ * scores[r*N + i] = <Q_r, K_i> / (|Q_r| |K_i|), or 0 when either norm is 0.
+ * Returns 0 on success, 1 on bad arguments, 2 when out of memory.
+ */
+int oracle_score_matrix(const void *keys, int key_dtype, const float *row_scale, int64_t N, int64_t d,
+                        const void *queries, int q_dtype, int64_t Q, double *scores)
+{
+    if (!keys || !queries || !scores || N < 0 || Q < 0 || d <= 0)
+        return 1;
+    if (key_dtype < 0 || key_dtype > 2 || q_dtype < 0 || q_dtype > 1)
+        return 1;
+    double *qd = (double *)malloc(sizeof(double) * (size_t)(Q > 0 ? Q : 1) * (size_t)d);
+    double *qn = (double *)malloc(sizeof(double) * (size_t)(Q > 0 ? Q : 1));
+    if (!qd || !qn) {
+        free(qd);
+        free(qn);
+        return 2;
+    }
+    for (int64_t r = 0; r < Q; ++r) {
+        decode_row(queries, q_dtype, NULL, r, d, qd + r * d);
+        qn[r] = l2norm(qd + r * d, d);
+    }
+    int failed = 0;
+#pragma omp parallel
+    {
+        double *kd = (double *)malloc(sizeof(double) * (size_t)d);
+        if (!kd) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(static)
+        for (int64_t i = 0; i < N; ++i) {
+            if (!kd)
+                continue;
+            decode_row(keys, key_dtype, row_scale, i, d, kd);
+            double kn = l2norm(kd, d);
+            for (int64_t r = 0; r < Q; ++r) {
+                const double *q = qd + r * d;
+                double dot = 0.0;
+                for (int64_t j = 0; j < d; ++j)
+                    dot += q[j] * kd[j];
+                double denom = qn[r] * kn;
+                scores[r * N + i] = (qn[r] == 0.0 || kn == 0.0) ? 0.0 : dot / denom;
+            }
+        }
+        free(kd);
+    }
+    free(qd);
+    free(qn);
+    return failed ? 2 : 0;
+}
+
+typedef struct {
+    double score;
+    int64_t index;
+} pair_t;
+
+/* Strict total order: higher score first, then lower index.  -0.0 == 0.0. */
+static int pair_cmp(const void *a, const void *b)
+{
+    const pair_t *x = (const pair_t *)a, *y = (const pair_t *)b;
+    if (x->score > y->score)
+        return -1;
+    if (x->score < y->score)
+        return 1;
+    if (x->index < y->index)
+        return -1;
+    if (x->index > y->index)
+        return 1;
+    return 0;
+}
+
+/*
+ * Selection for one query from its N scores: candidate set = all i (tags or
+ * qmask absent) or { i : (qmask & tags[i]) != 0 }; the candidates are sorted
+ * in full by (score desc, index asc); the first min(k, |C|) are written, the
+ * rest of the k slots are padded with index -1 and score -infinity.
+ * `use_mask` = 0 means "no filter" (then tags may be NULL and qmask is
+ * ignored).  Returns the number of candidates, or -1 on error.
+ */
+int64_t oracle_select(const double *scores, int64_t N, const uint64_t *tags, int use_mask, uint64_t qmask,
+                      int64_t k, int64_t *out_index, double *out_score)
+{
+    if (!scores || !out_index || !out_score || N < 0 || k < 0 || (use_mask && !tags))
+        return -1;
+    pair_t *c = (pair_t *)malloc(sizeof(pair_t) * (size_t)(N > 0 ? N : 1));
+    if (!c)
+        return -1;
+    int64_t n = 0;
+    for (int64_t i = 0; i < N; ++i) {
+        if (use_mask && (qmask & tags[i]) == 0)
+            continue;
+        c[n].score = scores[i];
+        c[n].index = i;
+        ++n;
+    }
+    qsort(c, (size_t)n, sizeof(pair_t), pair_cmp);
+    for (int64_t p = 0; p < k; ++p) {
+        if (p < n) {
+            out_index[p] = c[p].index;
+            out_score[p] = c[p].score;
+        } else {
+            out_index[p] = -1;
+            out_score[p] = -INFINITY;
+        }
+    }
+    free(c);
+    return n;
+}
+
+/*
+ * The whole query: score matrix, then one selection per query.
+ * qmask == NULL means no filtering for any query.  If scores_out is not NULL
+ * it receives the full [Q, N] fp64 score matrix (the comparator needs it).
+ * Returns 0 on success.
+ */
+int oracle_query(const void *keys, int key_dtype, const float *row_scale, const uint64_t *tags, int64_t N,
+                 int64_t d, const void *queries, int q_dtype, int64_t Q, const uint64_t *qmask, int64_t k,
+                 int64_t *out_index, double *out_score, double *scores_out)
+{
+    if (k < 0 || !out_index || !out_score || (qmask && !tags))
+        return 1;
+    double *scores = scores_out;
+    if (!scores) {
+        scores = (double *)malloc(sizeof(double) * (size_t)(Q * N > 0 ? Q * N : 1));
+        if (!scores)
+            return 2;
+    }
+    int rc = oracle_score_matrix(keys, key_dtype, row_scale, N, d, queries, q_dtype, Q, scores);
+    int bad = 0;
+    if (rc == 0) {
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int64_t r = 0; r < Q; ++r) {
+            int64_t n = oracle_select(scores + r * N, N, tags, qmask != NULL, qmask ? qmask[r] : 0, k,
+                                      out_index + r * k, out_score + r * k);
+            if (n < 0) {
+#pragma omp atomic write
+                bad = 1;
+            }
+        }
+    }
+    if (!scores_out)
+        free(scores);
+    return rc ? rc : (bad ? 2 : 0);
+}
+
+/* Threads the parallel regions above will use (reported beside timings). */
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -1,0 +1,143 @@
+"""ctypes binding of the plain-C fp64 oracle (test infrastructure, not product code).
+
+The oracle is the plain definition of the modelled retrieval step of the paper's
+State Selector / Optimization Selector (Section 3): cosine of the decoded stored bits,
+optional tag filter ``(qmask & tag) != 0``, full sort by (score desc, index asc),
+first k, padded with (-1, -inf).  All arithmetic lives in ``kb_oracle.c``; this file
+only marshals numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "kb_oracle.c")
+_LIB = os.path.join(_HERE, "libkb_oracle.so")
+
+F32, BF16, FP8_E4M3 = 0, 1, 2
+_ELEM_BYTES = {F32: 4, BF16: 2, FP8_E4M3: 1}
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile kb_oracle.c with gcc into libkb_oracle.so beside it."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        )
+    return _LIB
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        vp, i64, i32, dbl = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_double
+        L.oracle_decode_bf16.restype = dbl
+        L.oracle_decode_bf16.argtypes = [ctypes.c_uint16]
+        L.oracle_decode_e4m3.restype = dbl
+        L.oracle_decode_e4m3.argtypes = [ctypes.c_uint8]
+        L.oracle_score_matrix.restype = i32
+        L.oracle_score_matrix.argtypes = [vp, i32, vp, i64, i64, vp, i32, i64, vp]
+        L.oracle_select.restype = i64
+        L.oracle_select.argtypes = [vp, i64, vp, i32, ctypes.c_uint64, i64, vp, vp]
+        L.oracle_query.restype = i32
+        L.oracle_query.argtypes = [vp, i32, vp, vp, i64, i64, vp, i32, i64, vp, i64, vp, vp, vp]
+        L.oracle_num_threads.restype = i32
+        L.oracle_num_threads.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _bits(a: np.ndarray, dtype: int, name: str) -> np.ndarray:
+    """Stored bits as a C-contiguous array of the right element width (no value conversion)."""
+    want = {F32: (np.float32,), BF16: (np.uint16,), FP8_E4M3: (np.uint8,)}[dtype]
+    a = np.ascontiguousarray(a)
+    if a.dtype.type not in want:
+        raise TypeError(f"{name}: dtype code {dtype} needs {want[0].__name__} bits, got {a.dtype}")
+    if a.ndim != 2:
+        raise ValueError(f"{name} must be 2-D")
+    return a
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def decode_bf16(bits: int) -> float:
+    return lib().oracle_decode_bf16(int(bits))
+
+
+def decode_e4m3(code: int) -> float:
+    return lib().oracle_decode_e4m3(int(code))
+
+
+def num_threads() -> int:
+    return lib().oracle_num_threads()
+
+
+def score_matrix(keys, key_dtype, queries, q_dtype, row_scale=None) -> np.ndarray:
+    """[Q, N] fp64 cosine scores of the stored bits."""
+    keys = _bits(keys, key_dtype, "keys")
+    queries = _bits(queries, q_dtype, "queries")
+    N, d = keys.shape
+    Q, dq = queries.shape
+    if d != dq:
+        raise ValueError("keys and queries disagree on d")
+    if row_scale is not None:
+        row_scale = np.ascontiguousarray(row_scale, dtype=np.float32)
+        assert row_scale.shape == (N,)
+    out = np.empty((Q, N), dtype=np.float64)
+    rc = lib().oracle_score_matrix(_ptr(keys), key_dtype, _ptr(row_scale), N, d, _ptr(queries), q_dtype, Q, _ptr(out))
+    if rc:
+        raise RuntimeError(f"oracle_score_matrix failed ({rc})")
+    return out
+
+
+def select(scores, k, tags=None, qmask=None):
+    """Top-k of one query's score vector; returns (index int64[k], score float64[k], n_candidates)."""
+    scores = np.ascontiguousarray(scores, dtype=np.float64)
+    assert scores.ndim == 1
+    use_mask = qmask is not None
+    if use_mask:
+        tags = np.ascontiguousarray(tags, dtype=np.uint64)
+        assert tags.shape == scores.shape
+    idx = np.empty(k, dtype=np.int64)
+    sc = np.empty(k, dtype=np.float64)
+    n = lib().oracle_select(_ptr(scores), scores.shape[0], _ptr(tags) if use_mask else None, int(use_mask),
+                            int(qmask) if use_mask else 0, k, _ptr(idx), _ptr(sc))
+    if n < 0:
+        raise RuntimeError("oracle_select failed")
+    return idx, sc, int(n)
+
+
+def query(keys, key_dtype, queries, q_dtype, k, row_scale=None, tags=None, qmask=None, return_scores=False):
+    """Full retrieval.  Returns (index int64[Q,k], score float64[Q,k][, scores float64[Q,N]])."""
+    keys = _bits(keys, key_dtype, "keys")
+    queries = _bits(queries, q_dtype, "queries")
+    N, d = keys.shape
+    Q, dq = queries.shape
+    if d != dq:
+        raise ValueError("keys and queries disagree on d")
+    if row_scale is not None:
+        row_scale = np.ascontiguousarray(row_scale, dtype=np.float32)
+        assert row_scale.shape == (N,)
+    if qmask is not None:
+        if tags is None:
+            raise ValueError("qmask given for an untagged knowledge base")
+        tags = np.ascontiguousarray(tags, dtype=np.uint64)
+        qmask = np.ascontiguousarray(qmask, dtype=np.uint64)
+        assert tags.shape == (N,) and qmask.shape == (Q,)
+    idx = np.empty((Q, k), dtype=np.int64)
+    sc = np.empty((Q, k), dtype=np.float64)
+    full = np.empty((Q, N), dtype=np.float64) if return_scores else None
+    rc = lib().oracle_query(_ptr(keys), key_dtype, _ptr(row_scale), _ptr(tags) if qmask is not None else None, N, d,
+                            _ptr(queries), q_dtype, Q, _ptr(qmask), k, _ptr(idx), _ptr(sc), _ptr(full))
+    if rc:
+        raise RuntimeError(f"oracle_query failed ({rc})")
+    return (idx, sc, full) if return_scores else (idx, sc)

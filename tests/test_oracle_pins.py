@@ -1,0 +1,289 @@
+"""Pins for the fp64 oracle: everything here is CPU-only and checks the oracle against something
+other than itself (hand-computed values, invariants, library routines, brute-force rank counts)."""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import compare
+from paper_2602_14293_amd import workloads as W
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+F32, BF16, FP8 = 0, 1, 2
+
+
+def _f(x):
+    return -math.inf if x == "-inf" else float(x)
+
+
+# ---------------- P1: hand-computed worked example -------------------------------------------
+
+@pytest.mark.parametrize("pad_d", [2, 64])
+def test_worked_example(oracle, pad_d):
+    g = json.load(open(os.path.join(GOLD, "worked_example.json")))
+    keys = np.zeros((len(g["keys"]), pad_d), dtype=np.float32)
+    keys[:, :2] = np.array(g["keys"], dtype=np.float32)
+    tags = np.array(g["tags"], dtype=np.uint64)
+    for case in g["cases"]:
+        q = np.zeros((1, pad_d), dtype=np.float32)
+        q[0, :2] = case["query"]
+        qmask = None if case["qmask"] is None else np.array([case["qmask"]], dtype=np.uint64)
+        idx, sc = oracle.query(keys, F32, q, F32, case["k"], tags=tags if qmask is not None else None, qmask=qmask)
+        assert idx[0].tolist() == case["index"], case["name"]
+        want = np.array([_f(s) for s in case["score"]])
+        assert np.allclose(sc[0], want, rtol=0, atol=1e-15, equal_nan=False), case["name"]
+
+
+def test_worked_example_bf16_keys(oracle):
+    # the example's coordinates are exactly representable in bf16: same answers from bf16 storage
+    g = json.load(open(os.path.join(GOLD, "worked_example.json")))
+    keys = torch.zeros(6, 64)
+    keys[:, :2] = torch.tensor(g["keys"], dtype=torch.float32)
+    kb = W.key_bits(keys.to(torch.bfloat16))
+    q = torch.zeros(1, 64)
+    q[0, :2] = torch.tensor([1.0, 0.0])
+    idx, sc = oracle.query(kb, BF16, W.key_bits(q.to(torch.bfloat16)), BF16, 3)
+    assert idx[0].tolist() == [0, 5, 2]
+    assert abs(sc[0, 2] - 1 / math.sqrt(2)) < 1e-15
+
+
+# ---------------- decode tables vs an independent library conversion --------------------------
+
+def test_bf16_decode_all_codes(oracle):
+    codes = np.arange(65536, dtype=np.uint16)
+    lib = torch.from_numpy(codes.view(np.int16)).view(torch.bfloat16).to(torch.float64).numpy()
+    mine = np.array([oracle.decode_bf16(int(c)) for c in codes])
+    both_nan = np.isnan(lib) & np.isnan(mine)
+    assert np.all((lib == mine) | both_nan)
+    assert np.array_equal(np.signbit(lib[~both_nan]), np.signbit(mine[~both_nan]))
+
+
+def test_e4m3_decode_all_codes(oracle):
+    codes = np.arange(256, dtype=np.uint8)
+    lib = torch.from_numpy(codes).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    mine = np.array([oracle.decode_e4m3(int(c)) for c in codes])
+    both_nan = np.isnan(lib) & np.isnan(mine)
+    assert both_nan.sum() == 2
+    assert np.all((lib == mine) | both_nan)
+
+
+def test_e4m3_spot_values(oracle):
+    g = json.load(open(os.path.join(GOLD, "e4m3_spot_values.json")))
+    for code, val in g["values"].items():
+        assert oracle.decode_e4m3(int(code)) == val, code
+    assert math.isnan(oracle.decode_e4m3(0x7F)) and math.isnan(oracle.decode_e4m3(0xFF))
+
+
+# ---------------- P3: independent library formulation ----------------------------------------
+
+def _numpy_reference(K, Qm, k, cand=None):
+    """normalize(Q) @ normalize(K).T in fp64, stable argsort of -score."""
+    Kn = K / np.linalg.norm(K, axis=1, keepdims=True)
+    Qn = Qm / np.linalg.norm(Qm, axis=1, keepdims=True)
+    S = Qn @ Kn.T
+    out_i, out_s = [], []
+    for r in range(S.shape[0]):
+        ids = np.arange(S.shape[1]) if cand is None else np.flatnonzero(cand[r])
+        order = ids[np.argsort(-S[r, ids], kind="stable")][:k]
+        out_i.append(order)
+        out_s.append(S[r, order])
+    return S, out_i, out_s
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_matches_numpy_formulation_f32(oracle, seed):
+    rng = np.random.default_rng(seed)
+    N, d, Q, k = 257, 96, 5, 9
+    K = rng.standard_normal((N, d)).astype(np.float32)
+    Qm = rng.standard_normal((Q, d)).astype(np.float32)
+    S, ri, rs = _numpy_reference(K.astype(np.float64), Qm.astype(np.float64), k)
+    idx, sc, full = oracle.query(K, F32, Qm, F32, k, return_scores=True)
+    assert np.abs(full - S).max() < 1e-12
+    for r in range(Q):
+        assert idx[r].tolist() == ri[r].tolist()
+        assert np.abs(sc[r] - rs[r]).max() < 1e-12
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_matches_numpy_formulation_bf16_and_fp8_with_mask(oracle, seed):
+    g = torch.Generator().manual_seed(seed)
+    N, d, Q, k = 300, 128, 7, 11
+    x = torch.randn(N, d, generator=g)
+    qf = torch.randn(Q, d, generator=g).to(torch.bfloat16)
+    tags = W.random_bits64(N, 0.05, g, "cpu")
+    qmask = W.random_bits64(Q, 0.2, g, "cpu")
+    cand = (W.word_bits(tags)[None, :] & W.word_bits(qmask)[:, None]) != 0
+    # bf16 keys
+    kb16 = x.to(torch.bfloat16)
+    S, ri, rs = _numpy_reference(kb16.double().numpy(), qf.double().numpy(), k, cand)
+    idx, sc, full = oracle.query(W.key_bits(kb16), BF16, W.key_bits(qf), BF16, k, tags=W.word_bits(tags),
+                                 qmask=W.word_bits(qmask), return_scores=True)
+    assert np.abs(full - S).max() < 1e-12
+    for r in range(Q):
+        m = len(ri[r])
+        assert idx[r, :m].tolist() == ri[r].tolist() and np.all(idx[r, m:] == -1)
+        assert np.abs(sc[r, :m] - rs[r]).max() < 1e-12 and np.all(np.isneginf(sc[r, m:]))
+    # fp8 keys with a per-row scale: stored value = scale * code value
+    k8, scale = W.quantize_e4m3_rows(x)
+    Kval = k8.to(torch.float64).numpy() * scale.double().numpy()[:, None]
+    S, ri, rs = _numpy_reference(Kval, qf.double().numpy(), k)
+    idx, sc, full = oracle.query(W.key_bits(k8), FP8, W.key_bits(qf), BF16, k, row_scale=scale.numpy(),
+                                 return_scores=True)
+    assert np.abs(full - S).max() < 1e-12
+    for r in range(Q):
+        assert idx[r].tolist() == ri[r].tolist()
+
+
+# ---------------- P4: brute-force rank count on tiny inputs ----------------------------------
+
+@pytest.mark.parametrize("seed", range(5))
+def test_selection_against_rank_count(oracle, seed):
+    rng = np.random.default_rng(100 + seed)
+    N, d, k = int(rng.integers(1, 48)), 8, int(rng.integers(1, 12))
+    K = rng.integers(-2, 3, size=(N, d)).astype(np.float32)   # small integers -> many exact ties
+    q = rng.integers(-2, 3, size=(1, d)).astype(np.float32)
+    q[0, 0] = 1 if not q.any() else q[0, 0]
+    tags = rng.integers(0, 8, size=N).astype(np.uint64)
+    qm = np.uint64(rng.integers(1, 8))
+    idx, sc, full = oracle.query(K, F32, q, F32, k, tags=tags, qmask=np.array([qm], dtype=np.uint64), return_scores=True)
+    s = full[0]
+    cand = [i for i in range(N) if (tags[i] & qm) != 0]
+    # rank(i) = number of candidates that beat i under (score desc, index asc)
+    rank = {i: sum(1 for j in cand if (s[j] > s[i]) or (s[j] == s[i] and j < i)) for i in cand}
+    expect = sorted(cand, key=lambda i: rank[i])[:k]
+    m = len(expect)
+    assert idx[0, :m].tolist() == expect and np.all(idx[0, m:] == -1)
+    assert sorted(rank.values()) == list(range(len(cand)))    # the order is total
+    for p, i in enumerate(expect):
+        assert sc[0, p] == s[i]
+
+
+# ---------------- P2: invariants ------------------------------------------------------------
+
+def test_self_query_is_rank_one(oracle):
+    w = W.tiny(seed=3, N=512, d=64, Q=4, k=4)
+    K = W.key_bits(w.keys)
+    q = K[[5, 100, 301, 511]]
+    idx, sc = oracle.query(K, F32, q, F32, 4)
+    assert idx[:, 0].tolist() == [5, 100, 301, 511]
+    assert np.abs(sc[:, 0] - 1.0).max() <= 1e-12
+    assert np.all(sc[:, 1] < 1.0 - 1e-6)
+
+
+def test_permutation_equivariance(oracle):
+    w = W.clustered(seed=4, N=1000, d=64, Q=6, k=10, centers=16)
+    K, Qb = W.key_bits(w.keys), W.key_bits(w.queries)
+    idx, sc = oracle.query(K, BF16, Qb, BF16, 10)
+    perm = np.random.default_rng(0).permutation(1000)      # new row j holds old row perm[j]
+    idx2, sc2 = oracle.query(K[perm], BF16, Qb, BF16, 10)
+    assert np.array_equal(perm[idx2], idx)
+    assert np.array_equal(sc2, sc)
+
+
+def test_positive_scaling_changes_nothing(oracle):
+    w = W.tiny(seed=5, N=300, d=32, Q=3, k=5)
+    K, Qf = W.key_bits(w.keys).copy(), W.key_bits(w.queries).copy()
+    idx, sc = oracle.query(K, F32, Qf, F32, 5)
+    K2 = K * np.exp2(np.arange(300) % 7 - 3).astype(np.float32)[:, None]   # exact power-of-two scalings
+    idx2, sc2 = oracle.query(K2, F32, Qf * np.float32(8.0), F32, 5)
+    assert np.array_equal(idx, idx2) and np.abs(sc - sc2).max() < 1e-15
+    # fp8 row scale is a positive per-row factor: it cancels in the cosine
+    k8, scale = W.quantize_e4m3_rows(w.keys)
+    qb = W.key_bits(w.queries.to(torch.bfloat16))
+    a = oracle.query(W.key_bits(k8), FP8, qb, BF16, 5, row_scale=scale.numpy())
+    b = oracle.query(W.key_bits(k8), FP8, qb, BF16, 5, row_scale=(scale * 3.0).numpy())
+    assert np.array_equal(a[0], b[0]) and np.abs(a[1] - b[1]).max() < 1e-12
+
+
+def test_zero_rows_and_zero_query_score_zero(oracle):
+    K = np.zeros((4, 8), dtype=np.float32)
+    K[1, 0] = 1.0
+    K[3, 0] = -1.0
+    q = np.zeros((2, 8), dtype=np.float32)
+    q[0, 0] = 2.0
+    idx, sc, full = oracle.query(K, F32, q, F32, 4, return_scores=True)
+    assert full[0].tolist() == [0.0, 1.0, 0.0, -1.0]
+    assert idx[0].tolist() == [1, 0, 2, 3]
+    assert full[1].tolist() == [0.0, 0.0, 0.0, 0.0] and idx[1].tolist() == [0, 1, 2, 3]
+    assert not np.isnan(full).any()
+
+
+def test_masked_out_entries_never_returned(oracle):
+    w = W.filtered(seed=6, N=2000, d=64, Q=16, k=32, centers=8, p_tag=0.02, single_bit_qmask=True)
+    tags, qm = W.word_bits(w.tags), W.word_bits(w.qmask)
+    idx, sc = oracle.query(W.key_bits(w.keys), BF16, W.key_bits(w.queries), BF16, 32, tags=tags, qmask=qm)
+    saw_padding = False
+    for r in range(16):
+        valid = idx[r] >= 0
+        assert np.all((tags[idx[r][valid]] & qm[r]) != 0)
+        assert valid.sum() == min(32, int(((tags & qm[r]) != 0).sum()))
+        saw_padding |= not valid.all()
+    assert saw_padding      # the sparse variant really exercises padding
+
+
+def test_append_does_not_change_old_scores(oracle):
+    w = W.clustered(seed=7, N=600, d=64, Q=4, k=8, centers=8)
+    K, Qb = W.key_bits(w.keys), W.key_bits(w.queries)
+    _, _, full_a = oracle.query(K[:400], BF16, Qb, BF16, 8, return_scores=True)
+    _, _, full_b = oracle.query(K, BF16, Qb, BF16, 8, return_scores=True)
+    assert np.array_equal(full_a, full_b[:, :400])
+
+
+# ---------------- the acceptance rule itself: planted mistakes must be rejected --------------
+
+def _oracle_result(oracle, w, k):
+    idx, sc, full = oracle.query(W.key_bits(w.keys), BF16, W.key_bits(w.queries), BF16, k,
+                                 tags=W.word_bits(w.tags), qmask=W.word_bits(w.qmask), return_scores=True)
+    return idx.astype(np.int32), sc.astype(np.float32), full
+
+
+def test_compare_accepts_oracle_and_rejects_planted_mistakes(oracle):
+    w = W.filtered(seed=8, N=3000, d=64, Q=6, k=8, centers=4, p_tag=0.3)
+    tags, qm = W.word_bits(w.tags), W.word_bits(w.qmask)
+    idx, sc, full = _oracle_result(oracle, w, 8)
+    rep = compare.check(idx, sc, full, 8, 1e-5, tags=tags, qmask=qm)
+    assert rep.queries == 6 and rep.exact_order == 6
+
+    def rejected(i2, s2):
+        with pytest.raises(AssertionError):
+            compare.check(i2, s2, full, 8, 1e-5, tags=tags, qmask=qm)
+
+    i2 = idx.copy(); i2[0, [0, 1]] = i2[0, [1, 0]]              # wrong order
+    rejected(i2, sc)
+    i2 = idx.copy(); s2 = sc.copy()                             # best entry dropped, list shifted
+    i2[1, :-1] = idx[1, 1:]; s2[1, :-1] = sc[1, 1:]
+    worse = np.argsort(-np.where((tags & qm[1]) != 0, full[1], -np.inf))[8]
+    i2[1, -1] = worse; s2[1, -1] = full[1, worse]
+    rejected(i2, s2)
+    s2 = sc.copy(); s2[2, 3] += 1e-3                            # score off by more than tau
+    rejected(idx, s2)
+    i2 = idx.copy(); i2[3, 5] = i2[3, 4]                        # duplicate index
+    rejected(i2, sc)
+    bad = np.flatnonzero((tags & qm[4]) == 0)[0]                # filtered-out entry returned
+    i2 = idx.copy(); i2[4, 7] = bad
+    rejected(i2, sc)
+    i2 = idx.copy(); s2 = sc.copy(); i2[5, 7] = -1; s2[5, 7] = -np.inf   # padding although enough qualify
+    rejected(i2, s2)
+
+
+def test_compare_near_tie_rule(oracle):
+    # two entries whose oracle scores differ by far less than tau may swap at the k boundary
+    d = 64
+    K = np.zeros((5, d), dtype=np.float32)
+    K[0, 0] = 1.0
+    K[1, :2] = [1.0, 0.5]
+    K[2, :2] = [1.0, 0.5 + 1e-6]
+    K[3, :2] = [1.0, 3.0]
+    K[4, 1] = 1.0
+    q = np.zeros((1, d), dtype=np.float32); q[0, 0] = 1.0
+    idx, sc, full = oracle.query(K, F32, q, F32, 2, return_scores=True)
+    assert idx[0].tolist() == [0, 1]
+    swapped_i = np.array([[0, 2]], dtype=np.int32)
+    swapped_s = np.array([[1.0, full[0, 2]]], dtype=np.float32)
+    rep = compare.check(swapped_i, swapped_s, full, 2, 1e-5)
+    assert rep.near_tie == 1
+    with pytest.raises(AssertionError):                         # but a clearly worse entry may not
+        compare.check(np.array([[0, 3]], dtype=np.int32), np.array([[1.0, full[0, 3]]], dtype=np.float32), full, 2, 1e-5)
