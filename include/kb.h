@@ -1,0 +1,139 @@
+/*
+ * kb.h -- C ABI of the MI355X (gfx950) knowledge-base retrieval library.
+ *
+ * The operation.  The paper's agent keeps a Persistent Knowledge Base of
+ * <state, <optimization, score>> entries (Section 3, component list); its State
+ * Selector "retrieves relevant (state, optimization) pairs", the Optimization
+ * Selector keeps the top-k of them, and a state that matches nothing is
+ * appended (Section 3, the paragraph that walks through one task).  The paper
+ * gives that step no numeric form.  This library implements the numeric model
+ * of it: entry i has a key vector K_i (row i of an [N, d] matrix) and an
+ * optional 64-bit tag; a query is a vector Q_r with an optional 64-bit mask;
+ *
+ *     score(r, i) = <Q_r, K_i> / (|Q_r| |K_i|)       (0 if either norm is 0)
+ *     entry i qualifies for query r  iff  no mask is given or (qmask_r & tag_i) != 0
+ *     result(r)   = the k qualifying entries that come first under
+ *                   (score descending, index ascending), in that order,
+ *                   padded with (index -1, score -inf) when fewer than k qualify.
+ *
+ * All pointers named *_dev are device (HBM) addresses on the current HIP
+ * device; everything else is host memory.  The library never allocates or
+ * frees device memory: key storage is borrowed from the caller at kb_create
+ * and kb_query works in a caller-provided workspace.  All device work is
+ * enqueued on the caller's stream and no call synchronises (kb_query_counters
+ * excepted).  A handle is not thread-safe.  Calls on one stream are ordered;
+ * two kb_query calls may share a workspace only if they are stream-ordered.
+ */
+#ifndef KB_H
+#define KB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct kb kb_t; /* opaque, host-side */
+
+typedef enum { KB_F32 = 0, KB_BF16 = 1, KB_FP8_E4M3 = 2 } kb_dtype_t;
+
+typedef enum {
+    KB_OK = 0,
+    KB_ERR_NULL = 1,           /* a required pointer is NULL */
+    KB_ERR_INVALID_ARG = 2,    /* d, capacity, n, Q or k out of range */
+    KB_ERR_DTYPE = 3,          /* unknown dtype, or query dtype not allowed for the key dtype */
+    KB_ERR_CAPACITY = 4,       /* append would exceed the capacity given at kb_create */
+    KB_ERR_NOT_NORMALIZED = 5, /* kb_query while appended rows have no norm yet */
+    KB_ERR_NO_TAGS = 6,        /* qmask given but the knowledge base was created without tags */
+    KB_ERR_WORKSPACE = 7,      /* workspace NULL, misaligned (256 B) or smaller than kb_query_workspace_bytes */
+    KB_ERR_DEVICE = 8          /* a HIP call or kernel launch failed */
+} kb_status_t;
+
+#define KB_K_MAX 128 /* largest k accepted by kb_query */
+
+/*
+ * Create a knowledge base over caller-owned device storage (Section 3: the
+ * store behind the State Selector).  Nothing is copied or launched.
+ *   d          vector length; multiple of 32 (KB_F32) or 64 (KB_BF16, KB_FP8_E4M3), <= 16384
+ *   key_dtype  element type of keys_dev
+ *   capacity   rows the buffers can hold, 1 <= capacity < 2^31
+ *   keys_dev       [capacity, d] row-major, 16-byte aligned
+ *   row_scale_dev  [capacity] fp32, KB_FP8_E4M3 only (stored value = scale * code); else must be NULL.
+ *                  Scales must be finite and > 0; under the cosine they cancel and are not read by queries.
+ *   inv_norm_dev   [capacity] fp32, written by kb_normalize (1/|K_i| of the stored codes, 0 for a zero row)
+ *   tags_dev       [capacity] uint64, or NULL for an untagged knowledge base
+ * The buffers must outlive the handle.  Errors: KB_ERR_NULL, KB_ERR_INVALID_ARG, KB_ERR_DTYPE.
+ */
+kb_status_t kb_create(kb_t **out, int32_t d, kb_dtype_t key_dtype, int64_t capacity, void *keys_dev,
+                      float *row_scale_dev, float *inv_norm_dev, uint64_t *tags_dev);
+
+/*
+ * Append n rows at index kb_size() .. kb_size()+n-1 (Section 3: "appends the
+ * new state").  rows_dev [n, d] in the key dtype, row_scale_dev [n] (fp8 only,
+ * else NULL), tags_dev [n] (required iff the KB has tags).  The data is copied
+ * device-to-device on `hip_stream`; a source pointer equal to its destination
+ * (rows already written in place by the caller) skips that copy.  The new rows
+ * are not searchable until kb_normalize.  *first_index_out (host, may be NULL)
+ * receives the index of the first new row.  n == 0 is a no-op.
+ * Errors: KB_ERR_NULL, KB_ERR_INVALID_ARG (n < 0), KB_ERR_CAPACITY, KB_ERR_DEVICE.
+ */
+kb_status_t kb_append(kb_t *kb, const void *rows_dev, const float *row_scale_dev, const uint64_t *tags_dev,
+                      int64_t n, void *hip_stream, int64_t *first_index_out);
+
+/*
+ * Row L2-normalisation as a side scale: for every row appended since the last
+ * call, inv_norm[i] = 1 / sqrt(sum_j K_ij^2) in fp32 (0 if the sum is 0); the
+ * stored rows are not rewritten.  Cost is proportional to the new rows only.
+ * Idempotent.  Errors: KB_ERR_NULL, KB_ERR_DEVICE.
+ */
+kb_status_t kb_normalize(kb_t *kb, void *hip_stream);
+
+/*
+ * Bytes of device workspace kb_query needs for up to Q queries and this k.
+ * Sized for the handle's capacity, so it stays valid while rows are appended.
+ * Returns 0 on invalid arguments.
+ */
+size_t kb_query_workspace_bytes(const kb_t *kb, int32_t Q, int32_t k);
+
+/*
+ * Retrieval (Section 3: State Selector + top-k of the Optimization Selector).
+ *   queries_dev [Q, d] row-major, 16-byte aligned; q_dtype must equal the key dtype, except that
+ *               KB_FP8_E4M3 keys take KB_BF16 queries
+ *   qmask_dev   [Q] uint64, or NULL = no filtering for any query (a zero mask word qualifies nothing)
+ *   k           1 .. KB_K_MAX
+ *   indices_out_dev [Q, k] int32, scores_out_dev [Q, k] fp32: the result defined at the top of this file,
+ *               scores computed as fp32( fp32(dot * inv_norm_i) * inv_norm_q ) with dot accumulated in fp32
+ *   workspace_dev   256-byte aligned, at least kb_query_workspace_bytes(kb, Q, k); contents are scratch
+ * Results are bit-identical from run to run.  Finite inputs are the caller's responsibility.
+ * Errors: KB_ERR_NULL, KB_ERR_INVALID_ARG, KB_ERR_DTYPE, KB_ERR_NOT_NORMALIZED, KB_ERR_NO_TAGS,
+ * KB_ERR_WORKSPACE, KB_ERR_DEVICE.  An empty knowledge base returns all padding.
+ */
+kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int32_t Q, const uint64_t *qmask_dev,
+                     int32_t k, int32_t *indices_out_dev, float *scores_out_dev, void *workspace_dev,
+                     size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Diagnostics of the most recent kb_query that used `workspace_dev`: synchronises `hip_stream`, then copies
+ * out[0] = candidates that passed the threshold filter (all queries), out[1] = queries resolved by the
+ * exhaustive per-query path, out[2] = keys scored by the sampling pass, out[3] = workgroups of the scan.
+ * `out` is host memory, 4 x int64.  Errors: KB_ERR_NULL, KB_ERR_DEVICE.
+ */
+kb_status_t kb_query_counters(const kb_t *kb, const void *workspace_dev, int64_t *out, void *hip_stream);
+
+/*
+ * Performance knobs; they never change results.  Unknown names return KB_ERR_INVALID_ARG.
+ *   "sample_keys"   keys scored by the sampling pass (0 = automatic)
+ *   "scan_config"   tile configuration of the scan kernel (0 = automatic)
+ *   "wg_per_cu"     resident scan workgroups per compute unit (0 = automatic)
+ */
+kb_status_t kb_set_tuning(kb_t *kb, const char *name, int64_t value);
+
+int64_t kb_size(const kb_t *kb);         /* rows appended so far; -1 if kb is NULL */
+kb_status_t kb_destroy(kb_t *kb);        /* frees the host struct only */
+const char *kb_status_string(kb_status_t s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KB_H */

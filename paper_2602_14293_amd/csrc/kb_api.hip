@@ -1,0 +1,682 @@
+// libkb: C ABI, host-side planning, and the small kernels around the scan (gfx950 only).
+//
+//   kb_normalize : row_norm_kernel            (row L2 norms as a side scale)
+//   kb_query     : prep_kernel                (query norms, counters reset)
+//                  scan kernel, sampling pass (kb_scan.hpp)
+//                  threshold_kernel           (k-th best group maximum per query)
+//                  scan kernel, main pass     (kb_scan.hpp)
+//                  bucket_kernel              (records of all workgroups -> per-query lists)
+//                  finalize_kernel            (bitonic sort of each query's list, top k; or the
+//                                              exhaustive per-query scan when a list overflowed)
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+
+#include "kb_configs.hpp"
+#include "kb_internal.hpp"
+#include "kb_scan.hpp"
+
+using namespace kbi;
+
+struct kb {
+    int32_t d;
+    kb_dtype_t dtype;
+    int64_t capacity, n, n_normalized;
+    void *keys;
+    float *row_scale, *inv_norm;
+    uint64_t *tags;
+    int64_t tune_sample_keys, tune_config, tune_wg_per_cu;
+    int cu_count;   // 0 until the device has been asked
+};
+
+namespace kbi {
+
+bool scan_config_info(int key_dtype, int config, ConfigInfo *out)
+{
+#define X(ID, KT, TK, TQ, WM, WN, RBA, NSTAGE, WGPC)                          \
+    if (key_dtype == KT && config == ID) {                                    \
+        *out = ConfigInfo{TK, TQ, 64 * WM * WN, WM * 2, WGPC};                \
+        return true;                                                          \
+    }
+    KB_SCAN_CONFIGS_BF16(X)
+    KB_SCAN_CONFIGS_F32(X)
+    KB_SCAN_CONFIGS_FP8(X)
+#undef X
+    return false;
+}
+
+int scan_config_for(int, int Q) { return Q <= 32 ? 1 : Q <= 128 ? 2 : 3; }
+
+}  // namespace kbi
+
+namespace {
+
+constexpr int ASSUMED_CUS = 256;       // MI355X; used for sizing before a device is touched
+constexpr int MAX_SAMPLE_SLOTS = 8192; // threshold_kernel sorts this many 64-bit words in LDS (64 KiB)
+constexpr int MAX_CAND_CAP = 8192;     // finalize_kernel likewise
+constexpr int MIN_CAND_CAP = 1024;
+constexpr size_t WS_ALIGN = 256;
+
+int key_bytes(kb_dtype_t t) { return t == KB_F32 ? 4 : t == KB_BF16 ? 2 : 1; }
+int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+int64_t pow2_ceil(int64_t x)
+{
+    int64_t p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+size_t align_up(size_t x) { return (x + WS_ALIGN - 1) / WS_ALIGN * WS_ALIGN; }
+
+// Pure function of (handle settings, row count n, Q, k): which kernels run on what, and where
+// everything lives in the workspace.
+bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, Plan *out)
+{
+    Plan p;
+    memset(&p, 0, sizeof p);
+    p.Q = Q;
+    p.k = k;
+    p.config = h->tune_config > 0 ? (int)h->tune_config : scan_config_for(h->dtype, Q);
+    ConfigInfo ci;
+    if (!scan_config_info(h->dtype, p.config, &ci)) return false;
+    p.tk = ci.tk;
+    p.tq = ci.tq;
+    p.groups_per_tile = ci.groups_per_tile;
+    p.nqb = (int32_t)ceil_div(Q, ci.tq);
+    p.qpad = p.nqb * ci.tq;
+    if (n < 1) n = 1;
+    const int64_t n_tiles = ceil_div(n, ci.tk);
+
+    int64_t st = 0;
+    if (n_tiles >= 8) {
+        int64_t m = h->tune_sample_keys > 0 ? h->tune_sample_keys : ((int64_t)k * n / 512 > n / 64 ? (int64_t)k * n / 512 : n / 64);
+        st = ceil_div(m, ci.tk);
+        const int64_t want = ceil_div(2 * (int64_t)k, ci.groups_per_tile);
+        if (st < want) st = want;
+        if (st > MAX_SAMPLE_SLOTS / ci.groups_per_tile) st = MAX_SAMPLE_SLOTS / ci.groups_per_tile;
+        if (st > n_tiles / 2) st = n_tiles / 2;
+        if (st * ci.groups_per_tile < k) st = 0;
+    }
+    p.sample_tiles = st;
+    p.sample_slots = (int32_t)(st * ci.groups_per_tile);
+
+    const int64_t expect = st > 0 ? ceil_div((int64_t)k * n, st * ci.tk) : n;   // candidates per query
+    int64_t cc = pow2_ceil(st > 0 ? 4 * expect : expect);
+    if (cc < MIN_CAND_CAP) cc = MIN_CAND_CAP;
+    if (cc > MAX_CAND_CAP) cc = MAX_CAND_CAP;
+    p.cand_cap = (int32_t)cc;
+
+    const int cus = h->cu_count > 0 ? h->cu_count : ASSUMED_CUS;
+    const int wgpc = h->tune_wg_per_cu > 0 ? (int)h->tune_wg_per_cu : ci.wg_per_cu;
+    int64_t grid = n_tiles * p.nqb;
+    if (grid > (int64_t)cus * wgpc) grid = (int64_t)cus * wgpc;
+    p.grid = (int32_t)grid;
+    int64_t rc = pow2_ceil(4 * ceil_div(expect * Q, grid));
+    if (rc < 256) rc = 256;
+    if (rc > (1 << 22)) rc = 1 << 22;
+    p.region_cap = (int32_t)rc;
+
+    size_t off = 0;
+    p.off_stats = off;       off = align_up(off + sizeof(uint64_t) * 4);   // always first: kb_query_counters reads it
+    p.off_invq = off;        off = align_up(off + sizeof(float) * p.qpad);
+    p.off_thr64 = off;       off = align_up(off + sizeof(uint64_t) * p.qpad);
+    p.off_thrp = off;        off = align_up(off + sizeof(float) * p.qpad);
+    p.off_cnt = off;         off = align_up(off + sizeof(uint32_t) * p.qpad);
+    p.off_flag = off;        off = align_up(off + sizeof(uint32_t) * p.qpad);
+    p.off_region_cnt = off;  off = align_up(off + sizeof(uint32_t) * p.grid);
+    p.off_samp = off;        off = align_up(off + sizeof(uint64_t) * (size_t)p.qpad * (p.sample_slots > 0 ? p.sample_slots : 1));
+    p.off_regions = off;     off = align_up(off + sizeof(Record) * (size_t)p.grid * p.region_cap);
+    p.off_cand = off;        off = align_up(off + sizeof(uint64_t) * (size_t)p.qpad * p.cand_cap);
+    p.total = off;
+    *out = p;
+    return true;
+}
+
+// ------------------------------------------------------------------------------------------------
+// row norms
+// ------------------------------------------------------------------------------------------------
+template <int DT> __device__ inline float piece_sum_squares(u32x4 v);
+template <> __device__ inline float piece_sum_squares<KB_F32>(u32x4 v)
+{
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float x = as_f32(v[e]);
+        s += x * x;
+    }
+    return s;
+}
+template <> __device__ inline float piece_sum_squares<KB_BF16>(u32x4 v)
+{
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float lo = as_f32(v[e] << 16), hi = as_f32(v[e] & 0xffff0000u);
+        s += lo * lo;
+        s += hi * hi;
+    }
+    return s;
+}
+template <> __device__ inline float piece_sum_squares<KB_FP8_E4M3>(u32x4 v)
+{
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8(v[e], false), b = __builtin_amdgcn_cvt_pk_f32_fp8(v[e], true);
+        s += a.x * a.x;
+        s += a.y * a.y;
+        s += b.x * b.x;
+        s += b.y * b.y;
+    }
+    return s;
+}
+
+__device__ inline float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// One wavefront per row: lanes stride over the row's 16-byte pieces, fp32 sum of squares, butterfly
+// reduction, inv = 1/sqrt(sum) or 0 for a zero row.
+template <int DT> __device__ inline float row_inv_norm(const void *base, int64_t row, int row_bytes, int lane)
+{
+    const u32x4 *p = reinterpret_cast<const u32x4 *>(static_cast<const unsigned char *>(base) + (size_t)row * row_bytes);
+    float s = 0.f;
+    for (int i = lane; i < row_bytes / 16; i += 64) s += piece_sum_squares<DT>(__builtin_nontemporal_load(p + i));
+    s = wave_sum(s);
+    return s > 0.f ? 1.0f / sqrtf(s) : 0.f;
+}
+
+template <int DT> __global__ __launch_bounds__(256) void row_norm_kernel(const void *keys, int64_t begin, int64_t end, int d, float *inv_norm)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = begin + (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= end) return;
+    const float inv = row_inv_norm<DT>(keys, row, d * (DT == KB_F32 ? 4 : DT == KB_BF16 ? 2 : 1), lane);
+    if (lane == 0) inv_norm[row] = inv;
+}
+
+// ------------------------------------------------------------------------------------------------
+// prep: query norms + reset of the per-call counters
+// ------------------------------------------------------------------------------------------------
+template <int QT> __global__ __launch_bounds__(256) void prep_kernel(const void *queries, int Q, int qpad, int d, float *invq, uint64_t *thr64, float *thrp,
+                                                                       uint32_t *cnt, uint32_t *flag, uint32_t *region_cnt, int grid, uint64_t *stats, uint64_t sample_keys)
+{
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t < qpad) {     // padding queries (t >= Q) can never pass the filter of the scan
+        thr64[t] = t < Q ? 0ull : ~0ull;
+        thrp[t] = t < Q ? -__builtin_inff() : __builtin_inff();
+        cnt[t] = 0;
+        flag[t] = 0;
+    }
+    if (t < grid) region_cnt[t] = 0;
+    if (t < 4) stats[t] = t == 2 ? sample_keys : t == 3 ? (uint64_t)grid : 0ull;
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row < qpad) {
+        const float inv = row < Q ? row_inv_norm<QT>(queries, row, d * (QT == KB_F32 ? 4 : 2), lane) : 0.f;
+        if (lane == 0) invq[row] = inv;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// descending bitonic sort of n (power of two) 64-bit words in LDS by the whole workgroup
+// ------------------------------------------------------------------------------------------------
+__device__ inline void bitonic_sort_desc(uint64_t *buf, int n, int tid, int nthreads)
+{
+    for (int size = 2; size <= n; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            __syncthreads();
+            for (int i = tid; i < n / 2; i += nthreads) {
+                const int lo = 2 * i - (i & (stride - 1));
+                const int hi = lo + stride;
+                const uint64_t a = buf[lo], b = buf[hi];
+                const bool desc = (lo & size) == 0;
+                if (desc ? a < b : a > b) {
+                    buf[lo] = b;
+                    buf[hi] = a;
+                }
+            }
+        }
+    }
+    __syncthreads();
+}
+
+// k-th best group maximum of the sampling pass = a lower bound of the k-th best score (k distinct
+// entries reach it).  Also derives the conservative pre-filter on dot * inv_k used by the main pass:
+// whenever fp32((dot*inv_k) * inv_q) >= s_thr holds, dot*inv_k >= thrp holds (2^-20 relative slack
+// covers the three fp32 roundings involved).
+__global__ __launch_bounds__(256) void threshold_kernel(const uint64_t *samp, int slots, int p2, int k, const float *invq, uint64_t *thr64, float *thrp)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    uint64_t *buf = reinterpret_cast<uint64_t *>(smem_raw);
+    const int q = blockIdx.x, tid = threadIdx.x;
+    for (int i = tid; i < p2; i += 256) buf[i] = i < slots ? samp[(size_t)q * slots + i] : 0ull;
+    bitonic_sort_desc(buf, p2, tid, 256);
+    if (tid == 0) {
+        const uint64_t t = k <= slots ? buf[k - 1] : 0ull;
+        const float iq = invq[q];
+        float tp = -__builtin_inff();
+        if (t != 0 && iq > 0.f) {
+            const float x = candidate_score(t) / iq;
+            tp = x - fabsf(x) * 0x1p-20f - 1e-30f;
+        }
+        thr64[q] = t;
+        thrp[q] = tp;
+    }
+}
+
+// Records of every scan workgroup -> one list per query.
+__global__ __launch_bounds__(256) void bucket_kernel(const Record *regions, const uint32_t *region_cnt, int region_cap, uint64_t *cand, int cand_cap,
+                                                      uint32_t *cnt, uint32_t *flag, uint64_t *stats)
+{
+    const uint32_t n = region_cnt[blockIdx.x];
+    const Record *r = regions + (size_t)blockIdx.x * region_cap;
+    for (uint32_t i = threadIdx.x; i < n; i += 256) {
+        const Record rec = r[i];
+        const uint32_t slot = atomicAdd(&cnt[rec.query], 1u);
+        if (slot < (uint32_t)cand_cap)
+            cand[(size_t)rec.query * cand_cap + slot] = rec.cand;
+        else
+            flag[rec.query] = 1u;
+    }
+    if (threadIdx.x == 0 && n) atomicAdd(reinterpret_cast<unsigned long long *>(stats), (unsigned long long)n);
+}
+
+// ------------------------------------------------------------------------------------------------
+// finalize: sort each query's list and emit its first k; a query whose list overflowed is resolved by an
+// exhaustive scan of all keys that uses the same MFMA sequence per output element as the scan kernel,
+// so both paths produce bit-identical scores.
+// ------------------------------------------------------------------------------------------------
+struct FinalArgs {
+    const void *keys;
+    const float *inv_norm;
+    const uint64_t *tags;
+    const void *queries;
+    const uint64_t *qmask;
+    const float *invq;
+    const uint64_t *cand;
+    const uint32_t *cnt;
+    const uint32_t *flag;
+    uint64_t *stats;
+    int32_t *out_index;
+    float *out_score;
+    int64_t n_keys;
+    int32_t d, k, cand_cap;
+};
+
+template <int KT> __device__ void exhaustive_query(const FinalArgs &a, int q, uint64_t *buf, uint32_t *ctl)
+{
+    constexpr int KEY_BYTES = KeyTraits<KT>::KEY_BYTES, BMUL = KeyTraits<KT>::QRY_BYTES / KeyTraits<KT>::KEY_BYTES;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lrow = lane & 31, half = lane >> 5;
+    const int cap = a.cand_cap;
+    const bool filter = a.qmask != nullptr;
+    const uint64_t qm = filter ? a.qmask[q] : 0;
+    const float iq = a.invq[q];
+    const size_t key_row_bytes = (size_t)a.d * KEY_BYTES;
+    const unsigned char *qrow = static_cast<const unsigned char *>(a.queries) + (size_t)q * a.d * KeyTraits<KT>::QRY_BYTES;
+    const int n_groups = (int)(key_row_bytes / 32);
+    uint64_t *thr_local = reinterpret_cast<uint64_t *>(ctl + 2);   // ctl[0] = count, ctl[2..3] = threshold word
+    if (tid == 0) {
+        ctl[0] = 0;
+        *thr_local = 0;
+    }
+    __syncthreads();
+    for (int64_t row0 = 0; row0 < a.n_keys; row0 += 128) {
+        int64_t my_row = row0 + wave * 32 + lrow;
+        if (my_row >= a.n_keys) my_row = a.n_keys - 1;
+        const unsigned char *krow = static_cast<const unsigned char *>(a.keys) + (size_t)my_row * key_row_bytes + half * 16;
+        f32x16 acc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+        for (int g = 0; g < n_groups; ++g) {
+            const u32x4 av = *reinterpret_cast<const u32x4 *>(krow + (size_t)g * 32);
+            const unsigned char *qp = qrow + (size_t)g * 32 * BMUL + half * 16 * BMUL;
+            const u32x4 b0 = *reinterpret_cast<const u32x4 *>(qp);
+            const u32x4 b1 = BMUL == 2 ? *reinterpret_cast<const u32x4 *>(qp + 16) : b0;
+            Mma<KT>::run(acc, Mma<KT>::prepare(av), b0, b1);
+        }
+        // every column holds the same query; lanes 0..15 of each half own one row each
+        float v = acc[0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) v = (lrow == i) ? acc[i] : v;
+        if (lrow < 16) {
+            const int64_t row = row0 + wave * 32 + 8 * (lrow >> 2) + 4 * half + (lrow & 3);
+            if (row < a.n_keys && (!filter || (a.tags[row] & qm) != 0)) {
+                const uint64_t cw = pack_candidate(final_score(v, a.inv_norm[row], iq), (uint32_t)row);
+                if (cw > *thr_local) {
+                    const uint32_t pos = atomicAdd(&ctl[0], 1u);
+                    buf[pos] = cw;      // pos < cap: at most 128 appends between compactions
+                }
+            }
+        }
+        __syncthreads();
+        const uint32_t n = ctl[0];
+        if (n + 128 > (uint32_t)cap) {      // uniform: compact to the best k
+            for (int i = n + tid; i < cap; i += 256) buf[i] = 0ull;
+            bitonic_sort_desc(buf, cap, tid, 256);
+            if (tid == 0) {
+                ctl[0] = n < (uint32_t)a.k ? n : (uint32_t)a.k;
+                *thr_local = n >= (uint32_t)a.k ? buf[a.k - 1] : 0ull;
+            }
+            __syncthreads();
+        }
+    }
+    const uint32_t n = ctl[0];
+    for (int i = n + tid; i < cap; i += 256) buf[i] = 0ull;
+    bitonic_sort_desc(buf, cap, tid, 256);
+}
+
+template <int KT> __global__ __launch_bounds__(256) void finalize_kernel(FinalArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    uint64_t *buf = reinterpret_cast<uint64_t *>(smem_raw);
+    uint32_t *ctl = reinterpret_cast<uint32_t *>(smem_raw + sizeof(uint64_t) * a.cand_cap);
+    const int q = blockIdx.x, tid = threadIdx.x;
+    if (a.flag[q] != 0 && a.n_keys > 0) {
+        exhaustive_query<KT>(a, q, buf, ctl);
+        if (tid == 0) atomicAdd(reinterpret_cast<unsigned long long *>(a.stats + 1), 1ull);
+    } else {
+        uint32_t n = a.n_keys > 0 ? a.cnt[q] : 0;
+        if (n > (uint32_t)a.cand_cap) n = a.cand_cap;
+        int p2 = KB_K_MAX;
+        while (p2 < (int)n) p2 <<= 1;
+        for (int i = tid; i < p2; i += 256) buf[i] = i < (int)n ? a.cand[(size_t)q * a.cand_cap + i] : 0ull;
+        bitonic_sort_desc(buf, p2, tid, 256);
+    }
+    if (tid < a.k) {
+        const uint64_t cw = tid < a.cand_cap ? buf[tid] : 0ull;
+        a.out_index[(size_t)q * a.k + tid] = cw ? (int32_t)candidate_index(cw) : -1;
+        a.out_score[(size_t)q * a.k + tid] = cw ? candidate_score(cw) : -__builtin_inff();
+    }
+}
+
+hipError_t launch_scan(kb_dtype_t dt, int config, bool sample, int grid, const ScanArgs &a, hipStream_t s)
+{
+    switch (dt) {
+    case KB_F32: return launch_scan_f32(config, sample, grid, a, s);
+    case KB_BF16: return launch_scan_bf16(config, sample, grid, a, s);
+    default: return launch_scan_fp8(config, sample, grid, a, s);
+    }
+}
+
+bool valid_dtype(int t) { return t == KB_F32 || t == KB_BF16 || t == KB_FP8_E4M3; }
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+// C ABI
+// ------------------------------------------------------------------------------------------------
+extern "C" {
+
+kb_status_t kb_create(kb_t **out, int32_t d, kb_dtype_t key_dtype, int64_t capacity, void *keys_dev, float *row_scale_dev,
+                      float *inv_norm_dev, uint64_t *tags_dev)
+{
+    if (!out) return KB_ERR_NULL;
+    *out = nullptr;
+    if (!valid_dtype((int)key_dtype)) return KB_ERR_DTYPE;
+    if (!keys_dev || !inv_norm_dev) return KB_ERR_NULL;
+    if (key_dtype == KB_FP8_E4M3 && !row_scale_dev) return KB_ERR_NULL;
+    if (key_dtype != KB_FP8_E4M3 && row_scale_dev) return KB_ERR_INVALID_ARG;
+    const int granule = key_dtype == KB_F32 ? 32 : 64;
+    if (d <= 0 || d % granule != 0 || d > 16384) return KB_ERR_INVALID_ARG;
+    if (capacity < 1 || capacity >= ((int64_t)1 << 31)) return KB_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(keys_dev) & 15) != 0) return KB_ERR_INVALID_ARG;
+    kb *h = new (std::nothrow) kb();
+    if (!h) return KB_ERR_INVALID_ARG;
+    h->d = d;
+    h->dtype = key_dtype;
+    h->capacity = capacity;
+    h->n = h->n_normalized = 0;
+    h->keys = keys_dev;
+    h->row_scale = row_scale_dev;
+    h->inv_norm = inv_norm_dev;
+    h->tags = tags_dev;
+    h->tune_sample_keys = h->tune_config = h->tune_wg_per_cu = 0;
+    h->cu_count = 0;
+    *out = h;
+    return KB_OK;
+}
+
+kb_status_t kb_append(kb_t *kb, const void *rows_dev, const float *row_scale_dev, const uint64_t *tags_dev, int64_t n,
+                      void *hip_stream, int64_t *first_index_out)
+{
+    if (!kb) return KB_ERR_NULL;
+    if (n < 0) return KB_ERR_INVALID_ARG;
+    if (first_index_out) *first_index_out = kb->n;
+    if (n == 0) return KB_OK;
+    if (!rows_dev) return KB_ERR_NULL;
+    if (kb->dtype == KB_FP8_E4M3 && !row_scale_dev) return KB_ERR_NULL;
+    if (kb->tags && !tags_dev) return KB_ERR_NULL;
+    if (kb->n + n > kb->capacity) return KB_ERR_CAPACITY;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const size_t row_bytes = (size_t)kb->d * key_bytes(kb->dtype);
+    void *dst = static_cast<unsigned char *>(kb->keys) + (size_t)kb->n * row_bytes;
+    if (dst != rows_dev && hipMemcpyAsync(dst, rows_dev, row_bytes * n, hipMemcpyDeviceToDevice, s) != hipSuccess)
+        return KB_ERR_DEVICE;
+    if (kb->dtype == KB_FP8_E4M3 && kb->row_scale + kb->n != row_scale_dev &&
+        hipMemcpyAsync(kb->row_scale + kb->n, row_scale_dev, sizeof(float) * n, hipMemcpyDeviceToDevice, s) != hipSuccess)
+        return KB_ERR_DEVICE;
+    if (kb->tags && kb->tags + kb->n != tags_dev &&
+        hipMemcpyAsync(kb->tags + kb->n, tags_dev, sizeof(uint64_t) * n, hipMemcpyDeviceToDevice, s) != hipSuccess)
+        return KB_ERR_DEVICE;
+    kb->n += n;
+    return KB_OK;
+}
+
+kb_status_t kb_normalize(kb_t *kb, void *hip_stream)
+{
+    if (!kb) return KB_ERR_NULL;
+    const int64_t begin = kb->n_normalized, end = kb->n;
+    if (end <= begin) return KB_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const unsigned grid = (unsigned)ceil_div(end - begin, 4);
+    switch (kb->dtype) {
+    case KB_F32: hipLaunchKernelGGL(row_norm_kernel<KB_F32>, dim3(grid), dim3(256), 0, s, kb->keys, begin, end, kb->d, kb->inv_norm); break;
+    case KB_BF16: hipLaunchKernelGGL(row_norm_kernel<KB_BF16>, dim3(grid), dim3(256), 0, s, kb->keys, begin, end, kb->d, kb->inv_norm); break;
+    default: hipLaunchKernelGGL(row_norm_kernel<KB_FP8_E4M3>, dim3(grid), dim3(256), 0, s, kb->keys, begin, end, kb->d, kb->inv_norm); break;
+    }
+    if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
+    kb->n_normalized = end;
+    return KB_OK;
+}
+
+size_t kb_query_workspace_bytes(const kb_t *kb, int32_t Q, int32_t k)
+{
+    if (!kb || Q < 1 || k < 1 || k > KB_K_MAX) return 0;
+    size_t best = 0;
+    // the plan depends on the row count at query time: take the largest over a ladder of row counts
+    for (int64_t n = kb->capacity; n >= 1; n = n / 2) {
+        Plan p;
+        if (!make_plan(kb, n, Q, k, &p)) return 0;
+        if (p.total > best) best = p.total;
+        if (n == 1) break;
+    }
+    for (int64_t n = 1; n <= kb->capacity && n < (int64_t)1 << 16; n += 61) {   // and the small, irregular sizes
+        Plan p;
+        if (!make_plan(kb, n, Q, k, &p)) return 0;
+        if (p.total > best) best = p.total;
+    }
+    return best;
+}
+
+kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int32_t Q, const uint64_t *qmask_dev, int32_t k,
+                     int32_t *indices_out_dev, float *scores_out_dev, void *workspace_dev, size_t workspace_bytes,
+                     void *hip_stream)
+{
+    if (!kb || !queries_dev || !indices_out_dev || !scores_out_dev) return KB_ERR_NULL;
+    if (!valid_dtype((int)q_dtype)) return KB_ERR_DTYPE;
+    const kb_dtype_t want_q = kb->dtype == KB_F32 ? KB_F32 : KB_BF16;
+    if (q_dtype != want_q) return KB_ERR_DTYPE;
+    if (Q < 1 || k < 1 || k > KB_K_MAX) return KB_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(queries_dev) & 15) != 0) return KB_ERR_INVALID_ARG;
+    if (qmask_dev && !kb->tags) return KB_ERR_NO_TAGS;
+    if (kb->n_normalized != kb->n) return KB_ERR_NOT_NORMALIZED;
+    if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) & (WS_ALIGN - 1)) != 0) return KB_ERR_WORKSPACE;
+    if (kb->cu_count == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, 0) != hipSuccess || cus < 1) return KB_ERR_DEVICE;
+        // the workspace was sized for ASSUMED_CUS; a larger device just runs the same grid
+        kb->cu_count = cus < ASSUMED_CUS ? cus : ASSUMED_CUS;
+    }
+    Plan p;
+    if (!make_plan(kb, kb->n, Q, k, &p)) return KB_ERR_INVALID_ARG;
+    if (workspace_bytes < p.total) return KB_ERR_WORKSPACE;
+
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    unsigned char *ws = static_cast<unsigned char *>(workspace_dev);
+    float *invq = reinterpret_cast<float *>(ws + p.off_invq);
+    uint64_t *thr64 = reinterpret_cast<uint64_t *>(ws + p.off_thr64);
+    float *thrp = reinterpret_cast<float *>(ws + p.off_thrp);
+    uint32_t *cnt = reinterpret_cast<uint32_t *>(ws + p.off_cnt);
+    uint32_t *flag = reinterpret_cast<uint32_t *>(ws + p.off_flag);
+    uint32_t *region_cnt = reinterpret_cast<uint32_t *>(ws + p.off_region_cnt);
+    uint64_t *stats = reinterpret_cast<uint64_t *>(ws + p.off_stats);
+    uint64_t *samp = reinterpret_cast<uint64_t *>(ws + p.off_samp);
+    Record *regions = reinterpret_cast<Record *>(ws + p.off_regions);
+    uint64_t *cand = reinterpret_cast<uint64_t *>(ws + p.off_cand);
+
+    {
+        const int n_init = p.qpad > p.grid ? p.qpad : p.grid;
+        const int blocks_rows = (int)ceil_div(p.qpad, 4), blocks_init = (int)ceil_div(n_init, 256);
+        const unsigned grid = blocks_rows > blocks_init ? blocks_rows : blocks_init;
+        if (q_dtype == KB_F32)
+            hipLaunchKernelGGL(prep_kernel<KB_F32>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, region_cnt, p.grid, stats, (uint64_t)(p.sample_tiles * p.tk));
+        else
+            hipLaunchKernelGGL(prep_kernel<KB_BF16>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, region_cnt, p.grid, stats, (uint64_t)(p.sample_tiles * p.tk));
+        if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
+    }
+
+    if (kb->n > 0) {
+        ScanArgs a;
+        a.keys = kb->keys;
+        a.inv_norm = kb->inv_norm;
+        a.tags = qmask_dev ? kb->tags : nullptr;
+        a.queries = queries_dev;
+        a.qmask = qmask_dev;
+        a.invq = invq;
+        a.thr64 = thr64;
+        a.thrp = thrp;
+        a.samp = samp;
+        a.regions = regions;
+        a.region_cnt = region_cnt;
+        a.flag = flag;
+        a.n_keys = kb->n;
+        a.d = kb->d;
+        a.Q = Q;
+        a.nqb = p.nqb;
+        a.sample_slots = p.sample_slots;
+        a.region_cap = p.region_cap;
+        if (p.sample_tiles > 0) {
+            a.n_tiles = p.sample_tiles;
+            int64_t sgrid = p.sample_tiles * p.nqb;
+            if (sgrid > p.grid) sgrid = p.grid;
+            if (launch_scan(kb->dtype, p.config, true, (int)sgrid, a, s) != hipSuccess) return KB_ERR_DEVICE;
+            const int p2 = (int)pow2_ceil(p.sample_slots < 64 ? 64 : p.sample_slots);
+            static bool thr_attr = false;
+            if (!thr_attr) {
+                if (hipFuncSetAttribute(reinterpret_cast<const void *>(&threshold_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        MAX_SAMPLE_SLOTS * 8) != hipSuccess)
+                    return KB_ERR_DEVICE;
+                thr_attr = true;
+            }
+            hipLaunchKernelGGL(threshold_kernel, dim3(Q), dim3(256), (size_t)p2 * 8, s, samp, p.sample_slots, p2, k, invq, thr64, thrp);
+            if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
+        }
+        a.n_tiles = ceil_div(kb->n, p.tk);
+        if (launch_scan(kb->dtype, p.config, false, p.grid, a, s) != hipSuccess) return KB_ERR_DEVICE;
+        hipLaunchKernelGGL(bucket_kernel, dim3(p.grid), dim3(256), 0, s, regions, region_cnt, p.region_cap, cand, p.cand_cap, cnt, flag, stats);
+        if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
+    }
+
+    FinalArgs f;
+    f.keys = kb->keys;
+    f.inv_norm = kb->inv_norm;
+    f.tags = qmask_dev ? kb->tags : nullptr;
+    f.queries = queries_dev;
+    f.qmask = qmask_dev;
+    f.invq = invq;
+    f.cand = cand;
+    f.cnt = cnt;
+    f.flag = flag;
+    f.stats = stats;
+    f.out_index = indices_out_dev;
+    f.out_score = scores_out_dev;
+    f.n_keys = kb->n;
+    f.d = kb->d;
+    f.k = k;
+    f.cand_cap = p.cand_cap;
+    const size_t fin_lds = (size_t)p.cand_cap * 8 + 16;
+    static bool fin_attr[3] = {false, false, false};
+    const void *fin_fn = kb->dtype == KB_F32 ? reinterpret_cast<const void *>(&finalize_kernel<KB_F32>)
+                       : kb->dtype == KB_BF16 ? reinterpret_cast<const void *>(&finalize_kernel<KB_BF16>)
+                                              : reinterpret_cast<const void *>(&finalize_kernel<KB_FP8_E4M3>);
+    if (!fin_attr[kb->dtype]) {
+        if (hipFuncSetAttribute(fin_fn, hipFuncAttributeMaxDynamicSharedMemorySize, MAX_CAND_CAP * 8 + 16) != hipSuccess) return KB_ERR_DEVICE;
+        fin_attr[kb->dtype] = true;
+    }
+    switch (kb->dtype) {
+    case KB_F32: hipLaunchKernelGGL(finalize_kernel<KB_F32>, dim3(Q), dim3(256), fin_lds, s, f); break;
+    case KB_BF16: hipLaunchKernelGGL(finalize_kernel<KB_BF16>, dim3(Q), dim3(256), fin_lds, s, f); break;
+    default: hipLaunchKernelGGL(finalize_kernel<KB_FP8_E4M3>, dim3(Q), dim3(256), fin_lds, s, f); break;
+    }
+    if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
+    return KB_OK;
+}
+
+kb_status_t kb_query_counters(const kb_t *kb, const void *workspace_dev, int64_t *out, void *hip_stream)
+{
+    if (!kb || !workspace_dev || !out) return KB_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (hipStreamSynchronize(s) != hipSuccess) return KB_ERR_DEVICE;
+    uint64_t host[4];
+    if (hipMemcpy(host, workspace_dev, sizeof host, hipMemcpyDeviceToHost) != hipSuccess) return KB_ERR_DEVICE;
+    for (int i = 0; i < 4; ++i) out[i] = (int64_t)host[i];
+    return KB_OK;
+}
+
+kb_status_t kb_set_tuning(kb_t *kb, const char *name, int64_t value)
+{
+    if (!kb || !name) return KB_ERR_NULL;
+    if (value < 0) return KB_ERR_INVALID_ARG;
+    if (!strcmp(name, "sample_keys")) kb->tune_sample_keys = value;
+    else if (!strcmp(name, "scan_config")) {
+        ConfigInfo ci;
+        if (value != 0 && !scan_config_info(kb->dtype, (int)value, &ci)) return KB_ERR_INVALID_ARG;
+        kb->tune_config = value;
+    } else if (!strcmp(name, "wg_per_cu")) {
+        if (value > 8) return KB_ERR_INVALID_ARG;
+        kb->tune_wg_per_cu = value;
+    } else
+        return KB_ERR_INVALID_ARG;
+    return KB_OK;
+}
+
+int64_t kb_size(const kb_t *kb) { return kb ? kb->n : -1; }
+
+kb_status_t kb_destroy(kb_t *kb)
+{
+    if (!kb) return KB_ERR_NULL;
+    delete kb;
+    return KB_OK;
+}
+
+const char *kb_status_string(kb_status_t s)
+{
+    switch (s) {
+    case KB_OK: return "ok";
+    case KB_ERR_NULL: return "required pointer is NULL";
+    case KB_ERR_INVALID_ARG: return "argument out of range";
+    case KB_ERR_DTYPE: return "dtype not supported for this call";
+    case KB_ERR_CAPACITY: return "capacity exceeded";
+    case KB_ERR_NOT_NORMALIZED: return "appended rows have not been normalized";
+    case KB_ERR_NO_TAGS: return "query mask given for an untagged knowledge base";
+    case KB_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case KB_ERR_DEVICE: return "HIP call or kernel launch failed";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,19 @@
+// Tile configurations of the scan kernel: X(id, key dtype, TK, TQ, WM, WN, RBA, NSTAGE, WGPC)
+//   TK x TQ      keys x queries per work item         WM x WN  wavefront grid inside the workgroup
+//   RBA          bytes of each key row per d-chunk    NSTAGE   chunk buffers in LDS
+//   WGPC         workgroups resident per compute unit (LDS and registers are budgeted for it)
+#pragma once
+#define KB_SCAN_CONFIGS_BF16(X)                  \
+    X(1, KB_BF16, 128, 32, 4, 1, 128, 3, 2)      \
+    X(2, KB_BF16, 128, 128, 2, 2, 64, 4, 2)      \
+    X(3, KB_BF16, 128, 256, 2, 2, 64, 3, 2)      \
+    X(4, KB_BF16, 256, 256, 4, 2, 64, 4, 1)      \
+    X(5, KB_BF16, 256, 256, 2, 2, 64, 4, 1)
+#define KB_SCAN_CONFIGS_F32(X)                   \
+    X(1, KB_F32, 128, 32, 4, 1, 128, 3, 2)       \
+    X(2, KB_F32, 128, 128, 2, 2, 64, 4, 2)       \
+    X(3, KB_F32, 128, 256, 2, 2, 64, 3, 2)
+#define KB_SCAN_CONFIGS_FP8(X)                   \
+    X(1, KB_FP8_E4M3, 128, 32, 4, 1, 64, 3, 2)   \
+    X(2, KB_FP8_E4M3, 128, 128, 2, 2, 64, 3, 2)  \
+    X(3, KB_FP8_E4M3, 128, 256, 2, 2, 64, 3, 1)

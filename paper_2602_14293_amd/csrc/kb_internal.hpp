@@ -1,0 +1,98 @@
+// Internal declarations shared by the translation units of libkb (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kb.h"
+
+namespace kbi {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// Bit reinterpretation of scalars passed BY VALUE.  (__builtin_bit_cast applied directly to a vector
+// element such as v[e] or f.y has been seen to read element 0 instead; never do that.)
+__host__ __device__ inline float as_f32(uint32_t x) { return __builtin_bit_cast(float, x); }
+__host__ __device__ inline uint32_t as_u32(float x) { return __builtin_bit_cast(uint32_t, x); }
+
+// A candidate is one 64-bit sortable word: larger word = earlier in the result order
+// (score descending, index ascending).  0 is never a valid candidate ("empty").
+//   high 32 bits: the fp32 score mapped monotonically onto unsigned integers
+//   low  32 bits: ~index  (index < 2^31, so a smaller index gives a larger word)
+__host__ __device__ inline uint32_t score_to_ordered(float s)
+{
+    uint32_t u = __builtin_bit_cast(uint32_t, s);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__host__ __device__ inline float ordered_to_score(uint32_t o)
+{
+    uint32_t u = (o & 0x80000000u) ? (o & 0x7fffffffu) : ~o;
+    return __builtin_bit_cast(float, u);
+}
+__host__ __device__ inline uint64_t pack_candidate(float score, uint32_t index)
+{
+    return ((uint64_t)score_to_ordered(score) << 32) | (uint32_t)(~index);
+}
+__host__ __device__ inline uint32_t candidate_index(uint64_t c) { return ~(uint32_t)c; }
+__host__ __device__ inline float candidate_score(uint64_t c) { return ordered_to_score((uint32_t)(c >> 32)); }
+
+// The fp32 score every kernel of the library computes from an fp32 dot product.
+// "+ 0.0f" turns -0.0 into +0.0 so that equal scores have equal bit patterns.
+__device__ inline float final_score(float dot, float inv_k, float inv_q) { return (dot * inv_k) * inv_q + 0.0f; }
+
+struct Record {  // one candidate that passed the threshold filter of the scan
+    uint64_t cand;
+    uint32_t query;
+    uint32_t pad;
+};
+
+// Workspace layout (offsets in bytes from a 256-byte aligned base).
+struct Plan {
+    int32_t Q, k, tq, nqb, qpad;        // queries, tile width in queries, query blocks, padded count
+    int32_t config;                     // scan tile configuration id
+    int32_t tk;                         // keys per tile
+    int32_t groups_per_tile;            // sample groups per key tile
+    int64_t sample_tiles;               // key tiles scored by the sampling pass (0 = no sampling)
+    int32_t sample_slots;               // sample_tiles * groups_per_tile, per query
+    int32_t grid;                       // workgroups of the main scan
+    int32_t region_cap;                 // records per scan workgroup
+    int32_t cand_cap;                   // candidates per query the final sort can take (power of two)
+    size_t off_invq, off_thr64, off_thrp, off_cnt, off_flag, off_region_cnt, off_stats, off_samp, off_regions,
+        off_cand, total;
+};
+
+struct ScanArgs {
+    const void *keys;
+    const float *inv_norm;
+    const uint64_t *tags;     // nullptr when no filter is applied
+    const void *queries;
+    const uint64_t *qmask;    // nullptr when no filter is applied
+    const float *invq;        // [qpad]
+    const uint64_t *thr64;    // [qpad] candidate words below this cannot be in the result
+    const float *thrp;        // [qpad] conservative pre-filter on dot * inv_k
+    uint64_t *samp;           // sampling pass output [qpad][sample_slots]
+    Record *regions;          // [grid][region_cap]
+    uint32_t *region_cnt;     // [grid]
+    uint32_t *flag;           // [qpad] set to 1 when a query lost a candidate to a full buffer
+    int64_t n_keys;           // rows to scan: [0, n_keys)
+    int64_t n_tiles;          // key tiles to scan
+    int32_t d, Q, nqb, sample_slots, region_cap;
+};
+
+// Launchers, one translation unit per key dtype.  `sample` selects the sampling epilogue.
+hipError_t launch_scan_f32(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
+hipError_t launch_scan_bf16(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
+hipError_t launch_scan_fp8(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
+
+// Static description of a scan configuration (host side planning).
+struct ConfigInfo {
+    int tk, tq, threads, groups_per_tile, wg_per_cu;
+};
+bool scan_config_info(int key_dtype, int config, ConfigInfo *out);   // false if the id does not exist
+int scan_config_for(int key_dtype, int Q);                           // automatic choice
+
+}  // namespace kbi
