@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Benchmark of the knowledge-base retrieval hot path on one MI355X.
+
+A step is one kb_query over one batch of synthetic queries (query norms, sampling pass, threshold,
+scan with fused scale / tag filter / threshold filter, bucket, final top-k) with the knowledge base and
+the queries already resident in HBM.  The default workload is the filtered knowledge base the metric is
+quoted on: N = 2^20 keys, d = 1024, bf16, 256 masked queries, k = 32.
+
+Prints ONE JSON line.  `roofline` describes the scan kernel: achieved = algorithmic bytes per launch /
+average launch duration (HIP events recorded around the scan launch on its own stream, inside the timed
+region).  `cpu_baseline` is the fp64 oracle timed on the host cores on a bounded sample of the same
+batch; the same sample is used to check the GPU result, and no throughput is printed if that check fails.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def make_workload(name: str, seed: int, device):
+    from paper_2602_14293_amd import workloads as W
+
+    if name == "filtered":
+        return W.filtered(seed=seed, device=device), "filtered KB: N=1048576 d=1024 bf16, Q=256 masked queries, k=32"
+    if name == "filtered-q128":
+        return (W.filtered(seed=seed, Q=128, k=16, device=device),
+                "growing-KB query shape: N=1048576 d=1024 bf16, Q=128 masked queries, k=16")
+    if name == "clustered":
+        return W.clustered(seed=seed, device=device), "clustered KB: N=65536 d=768 bf16, Q=64, k=16"
+    if name == "tiny":
+        return W.tiny(seed=seed, device=device), "tiny KB: N=4096 d=256 fp32, Q=8, k=8"
+    if name == "compressed":
+        return (W.compressed(seed=seed, device=device),
+                "compressed KB: N=4194304 d=768 fp8-e4m3 + row scale, Q=1024 bf16 queries, k=64")
+    raise SystemExit(f"unknown workload {name}")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="filtered")
+    ap.add_argument("--seed", type=int, default=2000)
+    ap.add_argument("--oracle-queries", type=int, default=256, help="queries of the batch given to the CPU oracle")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tune", action="append", default=[], help="name=value performance knob (repeatable)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures one GPU: the retrieval path is built and measured on a single MI355X "
+                         "(--gpus must be 1).")
+
+    import numpy as np
+    import torch
+
+    from paper_2602_14293_amd import kb as kbmod
+    from paper_2602_14293_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    kbmod.lib()     # raises if libkb.so has not been built: there is no fallback path
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    w, desc = make_workload(args.workload, args.seed, dev)
+    code = {torch.float32: kbmod.KB_F32, torch.bfloat16: kbmod.KB_BF16, torch.float8_e4m3fn: kbmod.KB_FP8_E4M3}[w.keys.dtype]
+    kb = kbmod.KnowledgeBase(w.d, code, w.N, tagged=w.tags is not None)
+    kb.keys.copy_(w.keys)
+    if w.scale is not None:
+        kb.scale.copy_(w.scale)
+    if w.tags is not None:
+        kb.tags.copy_(w.tags)
+    kb.append_in_place(w.N)
+    kb.normalize()
+    for t in args.tune:
+        name, val = t.split("=")
+        kb.set_tuning(name, int(val))
+    queries = w.queries.contiguous()
+    qmask = w.qmask
+    Q, k, N, d = w.Q, w.k, w.N, w.d
+    out_i = torch.empty((Q, k), dtype=torch.int32, device=dev)
+    out_s = torch.empty((Q, k), dtype=torch.float32, device=dev)
+
+    for _ in range(args.warmup):
+        kb.query(queries, k, qmask, out_i, out_s)
+    torch.cuda.synchronize()
+
+    kb.profile_begin(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        kb.query(queries, k, qmask, out_i, out_s)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    scan_ms_total, scan_calls = kb.profile_end()
+    counters = kb.counters()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    qps = Q / (ms_per_step * 1e-3)
+    key_bytes = N * d * w.keys.element_size()
+    # algorithmic bytes of one scan launch: every key row once (+ its fp32 norm, + its 64-bit tag when a
+    # mask is given) and the query block once
+    scan_bytes = N * (d * w.keys.element_size() + 4 + (8 if qmask is not None else 0)) + Q * d * queries.element_size()
+    scan_ms = scan_ms_total / max(scan_calls, 1)
+    achieved = scan_bytes / (scan_ms * 1e-3) / 1e9
+    flops = 2.0 * Q * N * d
+    result = {
+        "metric": "KB top-k queries/sec + key-scan HBM GB/s (% of peak), N=1M d=1024 bf16",
+        "value": qps,
+        "unit": "queries/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": {kbmod.KB_F32: "f32", kbmod.KB_BF16: "bf16", kbmod.KB_FP8_E4M3: "fp8_e4m3"}[code],
+        "data": "synthetic",
+        "config": {"workload": desc, "seed": args.seed, "checksum": W.checksum(w.keys[:4096], w.queries)},
+        "key_scan_GBps": key_bytes / (ms_per_step * 1e-3) / 1e9,
+        "key_scan_frac_of_hbm_peak": key_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "mfma_TFLOPs": flops / (ms_per_step * 1e-3) / 1e12,
+        "counters": counters,
+        "roofline": {"bound": "hbm", "kernel": "kb_scan_kernel (main pass)", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel_ms": scan_ms, "algorithmic_bytes": scan_bytes, "launches_timed": scan_calls},
+    }
+
+    if not args.no_cpu_baseline:
+        # the oracle, as it stands, on the first `oracle_queries` queries of the same batch against all N keys
+        from oracle import compare, kb_oracle
+
+        nq = min(args.oracle_queries, Q)
+        gi, gs = out_i.cpu().numpy(), out_s.cpu().numpy()
+        key_bits = W.key_bits(w.keys)
+        q_bits = W.key_bits(w.queries[:nq])
+        tags = W.word_bits(w.tags) if qmask is not None else None
+        qm = W.word_bits(w.qmask[:nq]) if qmask is not None else None
+        okind = {kbmod.KB_F32: kb_oracle.F32, kbmod.KB_BF16: kb_oracle.BF16, kbmod.KB_FP8_E4M3: kb_oracle.FP8_E4M3}[code]
+        c0 = time.perf_counter()
+        oi, osc, full = kb_oracle.query(key_bits, okind, q_bits, kb_oracle.F32 if code == kbmod.KB_F32 else kb_oracle.BF16, k,
+                                        row_scale=None if w.scale is None else w.scale.cpu().numpy(), tags=tags, qmask=qm,
+                                        return_scores=True)
+        c1 = time.perf_counter()
+        tau = {kbmod.KB_F32: 1e-5, kbmod.KB_BF16: 2e-3, kbmod.KB_FP8_E4M3: 2e-2}[code]
+        rep = compare.check(gi[:nq], gs[:nq], full, k, tau, tags=tags, qmask=qm, label="bench parity")   # raises on mismatch
+        result["cpu_baseline"] = {"value": nq / (c1 - c0), "unit": "queries/s", "cores": kb_oracle.num_threads(), "kind": "oracle",
+                                  "sample": f"first {nq} of the {Q} queries against all {N} keys (fp64 brute force + full sort), "
+                                            f"{c1 - c0:.1f} s"}
+        result["parity"] = {"queries_checked": rep.queries, "strict": rep.strict, "near_tie": rep.near_tie,
+                            "max_score_err": rep.max_score_err}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

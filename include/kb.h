@@ -129,6 +129,16 @@ kb_status_t kb_query_counters(const kb_t *kb, const void *workspace_dev, int64_t
  */
 kb_status_t kb_set_tuning(kb_t *kb, const char *name, int64_t value);
 
+/*
+ * Kernel timing for roofline reports.  After kb_profile_begin, each kb_query records a HIP event pair
+ * around its main scan kernel on the query's stream (up to max_calls queries, 1..4096; later ones are not
+ * recorded).  kb_profile_end synchronises `hip_stream`, writes the summed duration of the recorded scan
+ * launches in milliseconds and their number, destroys the events and stops recording.
+ * Errors: KB_ERR_NULL, KB_ERR_INVALID_ARG (bad max_calls, or end without begin), KB_ERR_DEVICE.
+ */
+kb_status_t kb_profile_begin(kb_t *kb, int32_t max_calls);
+kb_status_t kb_profile_end(kb_t *kb, void *hip_stream, double *scan_ms_total, int32_t *calls);
+
 int64_t kb_size(const kb_t *kb);         /* rows appended so far; -1 if kb is NULL */
 kb_status_t kb_destroy(kb_t *kb);        /* frees the host struct only */
 const char *kb_status_string(kb_status_t s);

@@ -28,6 +28,8 @@ struct kb {
     uint64_t *tags;
     int64_t tune_sample_keys, tune_config, tune_wg_per_cu;
     int cu_count;   // 0 until the device has been asked
+    hipEvent_t *prof_events;   // 2 * prof_max events while profiling, else nullptr
+    int prof_max, prof_used;
 };
 
 namespace kbi {
@@ -436,6 +438,8 @@ kb_status_t kb_create(kb_t **out, int32_t d, kb_dtype_t key_dtype, int64_t capac
     h->tags = tags_dev;
     h->tune_sample_keys = h->tune_config = h->tune_wg_per_cu = 0;
     h->cu_count = 0;
+    h->prof_events = nullptr;
+    h->prof_max = h->prof_used = 0;
     *out = h;
     return KB_OK;
 }
@@ -586,7 +590,13 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
             if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
         }
         a.n_tiles = ceil_div(kb->n, p.tk);
+        const bool timed = kb->prof_events && kb->prof_used < kb->prof_max;
+        if (timed && hipEventRecord(kb->prof_events[2 * kb->prof_used], s) != hipSuccess) return KB_ERR_DEVICE;
         if (launch_scan(kb->dtype, p.config, false, p.grid, a, s) != hipSuccess) return KB_ERR_DEVICE;
+        if (timed) {
+            if (hipEventRecord(kb->prof_events[2 * kb->prof_used + 1], s) != hipSuccess) return KB_ERR_DEVICE;
+            ++kb->prof_used;
+        }
         hipLaunchKernelGGL(bucket_kernel, dim3(p.grid), dim3(256), 0, s, regions, region_cnt, p.region_cap, cand, p.cand_cap, cnt, flag, stats);
         if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
     }
@@ -654,11 +664,57 @@ kb_status_t kb_set_tuning(kb_t *kb, const char *name, int64_t value)
     return KB_OK;
 }
 
+static void drop_events(kb_t *kb)
+{
+    if (kb->prof_events) {
+        for (int i = 0; i < 2 * kb->prof_max; ++i)
+            if (kb->prof_events[i]) (void)hipEventDestroy(kb->prof_events[i]);
+        free(kb->prof_events);
+    }
+    kb->prof_events = nullptr;
+    kb->prof_max = kb->prof_used = 0;
+}
+
+kb_status_t kb_profile_begin(kb_t *kb, int32_t max_calls)
+{
+    if (!kb) return KB_ERR_NULL;
+    if (max_calls < 1 || max_calls > 4096) return KB_ERR_INVALID_ARG;
+    drop_events(kb);
+    kb->prof_events = static_cast<hipEvent_t *>(calloc(2 * (size_t)max_calls, sizeof(hipEvent_t)));
+    if (!kb->prof_events) return KB_ERR_INVALID_ARG;
+    kb->prof_max = max_calls;
+    for (int i = 0; i < 2 * max_calls; ++i)
+        if (hipEventCreate(&kb->prof_events[i]) != hipSuccess) {
+            drop_events(kb);
+            return KB_ERR_DEVICE;
+        }
+    return KB_OK;
+}
+
+kb_status_t kb_profile_end(kb_t *kb, void *hip_stream, double *scan_ms_total, int32_t *calls)
+{
+    if (!kb || !scan_ms_total || !calls) return KB_ERR_NULL;
+    if (!kb->prof_events) return KB_ERR_INVALID_ARG;
+    kb_status_t st = KB_OK;
+    if (hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)) != hipSuccess) st = KB_ERR_DEVICE;
+    double total = 0.0;
+    for (int i = 0; st == KB_OK && i < kb->prof_used; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, kb->prof_events[2 * i], kb->prof_events[2 * i + 1]) != hipSuccess) st = KB_ERR_DEVICE;
+        total += ms;
+    }
+    *scan_ms_total = total;
+    *calls = kb->prof_used;
+    drop_events(kb);
+    return st;
+}
+
 int64_t kb_size(const kb_t *kb) { return kb ? kb->n : -1; }
 
 kb_status_t kb_destroy(kb_t *kb)
 {
     if (!kb) return KB_ERR_NULL;
+    drop_events(kb);
     delete kb;
     return KB_OK;
 }

@@ -54,6 +54,10 @@ def lib() -> ctypes.CDLL:
         L.kb_query_counters.argtypes = [vp, vp, ctypes.POINTER(i64), vp]
         L.kb_set_tuning.restype = i32
         L.kb_set_tuning.argtypes = [vp, ctypes.c_char_p, i64]
+        L.kb_profile_begin.restype = i32
+        L.kb_profile_begin.argtypes = [vp, i32]
+        L.kb_profile_end.restype = i32
+        L.kb_profile_end.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
         L.kb_size.restype = i64
         L.kb_size.argtypes = [vp]
         L.kb_destroy.restype = i32
@@ -137,6 +141,15 @@ class KnowledgeBase:
         out = (ctypes.c_int64 * 4)()
         _check(lib().kb_query_counters(self._h, _ptr(self._workspace), out, _stream()), "kb_query_counters")
         return {"candidates": out[0], "exhaustive_queries": out[1], "sample_keys": out[2], "scan_workgroups": out[3]}
+
+    def profile_begin(self, max_calls: int):
+        _check(lib().kb_profile_begin(self._h, max_calls), "kb_profile_begin")
+
+    def profile_end(self):
+        """(summed main-scan kernel milliseconds, number of recorded launches)"""
+        ms, n = ctypes.c_double(0.0), ctypes.c_int32(0)
+        _check(lib().kb_profile_end(self._h, _stream(), ctypes.byref(ms), ctypes.byref(n)), "kb_profile_end")
+        return ms.value, n.value
 
     def set_tuning(self, name: str, value: int):
         _check(lib().kb_set_tuning(self._h, name.encode(), value), "kb_set_tuning")

@@ -1,0 +1,117 @@
+"""CPU-only checks of the C ABI: the library loads, exports what include/kb.h declares, and every
+argument error that is decided on the host comes back as the documented status (no device work)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2602_14293_amd import kb as kbmod
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = ctypes.c_void_p(1 << 20)          # a 256-byte aligned non-NULL "device pointer"; never dereferenced on the host
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(kbmod.LIB_PATH):
+        from paper_2602_14293_amd import build
+
+        build.build(verbose=False)
+    return kbmod.lib()
+
+
+def _create(L, d=128, dtype=kbmod.KB_BF16, cap=1000, scale=None, tags=None, keys=FAKE, inv=FAKE):
+    h = ctypes.c_void_p()
+    st = L.kb_create(ctypes.byref(h), d, dtype, cap, keys, scale, inv, tags)
+    return st, h
+
+
+def test_every_declared_symbol_is_exported(L):
+    header = open(os.path.join(ROOT, "include", "kb.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(kb_[a-z_]+)\s*\(", header))
+    assert {"kb_create", "kb_append", "kb_normalize", "kb_query_workspace_bytes", "kb_query", "kb_size",
+            "kb_destroy", "kb_status_string", "kb_query_counters", "kb_set_tuning"} <= names
+    for n in names:
+        assert hasattr(L, n), f"{n} is declared in kb.h but not exported by libkb.so"
+
+
+def test_status_strings(L):
+    seen = {L.kb_status_string(i) for i in range(9)}
+    assert len(seen) == 9 and all(seen)
+
+
+def test_create_argument_errors(L):
+    assert L.kb_create(None, 128, 1, 10, FAKE, None, FAKE, None) == 1                 # KB_ERR_NULL
+    assert _create(L, keys=None)[0] == 1
+    assert _create(L, inv=None)[0] == 1
+    assert _create(L, dtype=7)[0] == 3                                               # KB_ERR_DTYPE
+    assert _create(L, d=0)[0] == 2 and _create(L, d=100)[0] == 2 and _create(L, d=-64)[0] == 2
+    assert _create(L, d=32, dtype=kbmod.KB_F32)[0] == 0 and _create(L, d=32, dtype=kbmod.KB_BF16)[0] == 2
+    assert _create(L, cap=0)[0] == 2 and _create(L, cap=1 << 31)[0] == 2
+    assert _create(L, dtype=kbmod.KB_FP8_E4M3)[0] == 1                               # fp8 needs a row scale
+    assert _create(L, dtype=kbmod.KB_FP8_E4M3, scale=FAKE)[0] == 0
+    assert _create(L, dtype=kbmod.KB_BF16, scale=FAKE)[0] == 2                       # and the others must not have one
+    assert _create(L, keys=ctypes.c_void_p((1 << 20) + 4))[0] == 2                   # misaligned keys
+
+
+def test_append_and_query_argument_errors(L):
+    st, h = _create(L, cap=100, tags=FAKE)
+    assert st == 0 and L.kb_size(h) == 0 and L.kb_size(None) == -1
+    first = ctypes.c_int64(-5)
+    assert L.kb_append(None, FAKE, None, FAKE, 1, None, None) == 1
+    assert L.kb_append(h, FAKE, None, FAKE, -1, None, None) == 2
+    assert L.kb_append(h, FAKE, None, FAKE, 0, None, ctypes.byref(first)) == 0 and first.value == 0
+    assert L.kb_append(h, None, None, FAKE, 5, None, None) == 1
+    assert L.kb_append(h, FAKE, None, None, 5, None, None) == 1                      # tagged KB needs tags
+    assert L.kb_append(h, FAKE, None, FAKE, 101, None, None) == 4                    # KB_ERR_CAPACITY
+    assert L.kb_normalize(None, None) == 1 and L.kb_normalize(h, None) == 0          # nothing appended: no-op
+
+    ws = L.kb_query_workspace_bytes(h, 8, 4)
+    assert ws > 0 and ws % 256 == 0
+    assert L.kb_query_workspace_bytes(h, 0, 4) == 0 and L.kb_query_workspace_bytes(h, 8, 129) == 0
+    assert L.kb_query_workspace_bytes(None, 8, 4) == 0
+
+    def q(handle=h, queries=FAKE, qd=kbmod.KB_BF16, Q=8, qmask=None, k=4, oi=FAKE, os_=FAKE, w=FAKE, wb=ws):
+        return L.kb_query(handle, queries, qd, Q, qmask, k, oi, os_, w, wb, None)
+
+    assert q(handle=None) == 1 and q(queries=None) == 1 and q(oi=None) == 1 and q(os_=None) == 1
+    assert q(qd=kbmod.KB_F32) == 3 and q(qd=kbmod.KB_FP8_E4M3) == 3 and q(qd=9) == 3
+    assert q(Q=0) == 2 and q(k=0) == 2 and q(k=129) == 2
+    assert q(queries=ctypes.c_void_p((1 << 20) + 8)) == 2
+    assert q(w=None) == 7 and q(w=ctypes.c_void_p((1 << 20) + 64)) == 7             # KB_ERR_WORKSPACE
+    assert L.kb_destroy(h) == 0 and L.kb_destroy(None) == 1
+
+    st, h2 = _create(L, cap=100)                                                      # untagged
+    assert q(handle=h2, qmask=FAKE) == 6                                             # KB_ERR_NO_TAGS
+    L.kb_destroy(h2)
+
+
+def test_fp8_takes_bf16_queries_only(L):
+    st, h = _create(L, dtype=kbmod.KB_FP8_E4M3, scale=FAKE)
+    ws = L.kb_query_workspace_bytes(h, 4, 4)
+    assert L.kb_query(h, FAKE, kbmod.KB_FP8_E4M3, 4, None, 4, FAKE, FAKE, FAKE, ws, None) == 3
+    assert L.kb_query(h, FAKE, kbmod.KB_F32, 4, None, 4, FAKE, FAKE, FAKE, ws, None) == 3
+    L.kb_destroy(h)
+
+
+def test_tuning_knobs(L):
+    st, h = _create(L)
+    assert L.kb_set_tuning(h, b"sample_keys", 4096) == 0
+    assert L.kb_set_tuning(h, b"scan_config", 3) == 0 and L.kb_set_tuning(h, b"scan_config", 99) == 2
+    assert L.kb_set_tuning(h, b"wg_per_cu", 2) == 0 and L.kb_set_tuning(h, b"wg_per_cu", 64) == 2
+    assert L.kb_set_tuning(h, b"nonsense", 1) == 2 and L.kb_set_tuning(h, None, 1) == 1
+    L.kb_destroy(h)
+
+
+def test_workspace_size_covers_every_smaller_row_count(L):
+    # sized at capacity; must stay sufficient while the KB grows from empty (checked via the size at smaller capacities)
+    for dtype, scale in ((kbmod.KB_BF16, None), (kbmod.KB_F32, None), (kbmod.KB_FP8_E4M3, FAKE)):
+        st, big = _create(L, d=256, dtype=dtype, cap=1 << 21, scale=scale)
+        need_big = L.kb_query_workspace_bytes(big, 128, 16)
+        for cap in (1, 100, 1000, 5000, 70000, 1 << 20, (1 << 21) - 1):
+            st, small = _create(L, d=256, dtype=dtype, cap=cap, scale=scale)
+            assert L.kb_query_workspace_bytes(small, 128, 16) <= need_big
+            L.kb_destroy(small)
+        L.kb_destroy(big)
