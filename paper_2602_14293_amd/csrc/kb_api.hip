@@ -38,17 +38,28 @@ bool scan_config_info(int key_dtype, int config, ConfigInfo *out)
 {
 #define X(ID, KT, TK, TQ, WM, WN, RBA, NSTAGE, WGPC)                          \
     if (key_dtype == KT && config == ID) {                                    \
-        *out = ConfigInfo{TK, TQ, 64 * WM * WN, WM * 2, WGPC};                \
+        *out = ConfigInfo{TK, TQ, 64 * WM * WN, WM * 2, WGPC, RBA, false};    \
         return true;                                                          \
     }
     KB_SCAN_CONFIGS_BF16(X)
     KB_SCAN_CONFIGS_F32(X)
     KB_SCAN_CONFIGS_FP8(X)
 #undef X
+#define XP(ID, KT, TQ, NSTAGE)                                                \
+    if (key_dtype == KT && config == ID) {                                    \
+        *out = ConfigInfo{256, TQ, 512, 8, 1, 64 * 2 * NSTAGE, true};         \
+        return true;                                                          \
+    }
+    KB_SCAN_PP_CONFIGS_BF16(XP)
+#undef XP
     return false;
 }
 
-int scan_config_for(int, int Q) { return Q <= 32 ? 1 : Q <= 128 ? 2 : 3; }
+int scan_config_for(int key_dtype, int Q, int d)
+{
+    if (key_dtype == KB_BF16 && Q > 128 && d * 2 >= 512) return 6;
+    return Q <= 32 ? 1 : Q <= 128 ? 2 : 3;
+}
 
 }  // namespace kbi
 
@@ -78,9 +89,14 @@ bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, Plan *out)
     memset(&p, 0, sizeof p);
     p.Q = Q;
     p.k = k;
-    p.config = h->tune_config > 0 ? (int)h->tune_config : scan_config_for(h->dtype, Q);
+    p.config = h->tune_config > 0 ? (int)h->tune_config : scan_config_for(h->dtype, Q, h->d);
     ConfigInfo ci;
     if (!scan_config_info(h->dtype, p.config, &ci)) return false;
+    if (h->d * key_bytes(h->dtype) < ci.min_row_bytes) {     // a forced configuration the rows are too short for
+        p.config = Q <= 32 ? 1 : Q <= 128 ? 2 : 3;
+        if (!scan_config_info(h->dtype, p.config, &ci)) return false;
+    }
+    p.ping_pong = ci.ping_pong;
     p.tk = ci.tk;
     p.tq = ci.tq;
     p.groups_per_tile = ci.groups_per_tile;
@@ -113,7 +129,9 @@ bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, Plan *out)
     int64_t grid = n_tiles * p.nqb;
     if (grid > (int64_t)cus * wgpc) grid = (int64_t)cus * wgpc;
     p.grid = (int32_t)grid;
-    int64_t rc = pow2_ceil(4 * ceil_div(expect * Q, grid));
+    const int waves = ci.threads / 64;
+    p.regions = (int32_t)(grid * waves);
+    int64_t rc = pow2_ceil(8 * ceil_div(expect * Q, grid * waves));     // per wavefront, 8x the even share
     if (rc < 256) rc = 256;
     if (rc > (1 << 22)) rc = 1 << 22;
     p.region_cap = (int32_t)rc;
@@ -125,9 +143,10 @@ bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, Plan *out)
     p.off_thrp = off;        off = align_up(off + sizeof(float) * p.qpad);
     p.off_cnt = off;         off = align_up(off + sizeof(uint32_t) * p.qpad);
     p.off_flag = off;        off = align_up(off + sizeof(uint32_t) * p.qpad);
-    p.off_region_cnt = off;  off = align_up(off + sizeof(uint32_t) * p.grid);
+    p.off_region_cnt = off;  off = align_up(off + sizeof(uint32_t) * p.regions);
+    p.off_qmask = off;       off = align_up(off + sizeof(uint64_t) * p.qpad);
     p.off_samp = off;        off = align_up(off + sizeof(uint64_t) * (size_t)p.qpad * (p.sample_slots > 0 ? p.sample_slots : 1));
-    p.off_regions = off;     off = align_up(off + sizeof(Record) * (size_t)p.grid * p.region_cap);
+    p.off_regions = off;     off = align_up(off + sizeof(Record) * (size_t)p.regions * p.region_cap);
     p.off_cand = off;        off = align_up(off + sizeof(uint64_t) * (size_t)p.qpad * p.cand_cap);
     p.total = off;
     *out = p;
@@ -204,7 +223,8 @@ template <int DT> __global__ __launch_bounds__(256) void row_norm_kernel(const v
 // prep: query norms + reset of the per-call counters
 // ------------------------------------------------------------------------------------------------
 template <int QT> __global__ __launch_bounds__(256) void prep_kernel(const void *queries, int Q, int qpad, int d, float *invq, uint64_t *thr64, float *thrp,
-                                                                       uint32_t *cnt, uint32_t *flag, uint32_t *region_cnt, int grid, uint64_t *stats, uint64_t sample_keys)
+                                                                       uint32_t *cnt, uint32_t *flag, uint32_t *region_cnt, int regions, uint64_t *stats, uint64_t sample_keys,
+                                                                       const uint64_t *qmask, uint64_t *qmask_pad, int grid)
 {
     const int t = blockIdx.x * 256 + threadIdx.x;
     if (t < qpad) {     // padding queries (t >= Q) can never pass the filter of the scan
@@ -212,8 +232,9 @@ template <int QT> __global__ __launch_bounds__(256) void prep_kernel(const void 
         thrp[t] = t < Q ? -__builtin_inff() : __builtin_inff();
         cnt[t] = 0;
         flag[t] = 0;
+        qmask_pad[t] = (qmask && t < Q) ? qmask[t] : 0ull;
     }
-    if (t < grid) region_cnt[t] = 0;
+    if (t < regions) region_cnt[t] = 0;
     if (t < 4) stats[t] = t == 2 ? sample_keys : t == 3 ? (uint64_t)grid : 0ull;
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -395,8 +416,9 @@ template <int KT> __global__ __launch_bounds__(256) void finalize_kernel(FinalAr
     }
 }
 
-hipError_t launch_scan(kb_dtype_t dt, int config, bool sample, int grid, const ScanArgs &a, hipStream_t s)
+hipError_t launch_scan(kb_dtype_t dt, int config, bool ping_pong, bool sample, int grid, const ScanArgs &a, hipStream_t s)
 {
+    if (ping_pong) return dt == KB_BF16 ? launch_scan_pp_bf16(config, sample, grid, a, s) : hipErrorInvalidValue;
     switch (dt) {
     case KB_F32: return launch_scan_f32(config, sample, grid, a, s);
     case KB_BF16: return launch_scan_bf16(config, sample, grid, a, s);
@@ -538,18 +560,19 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
     uint32_t *flag = reinterpret_cast<uint32_t *>(ws + p.off_flag);
     uint32_t *region_cnt = reinterpret_cast<uint32_t *>(ws + p.off_region_cnt);
     uint64_t *stats = reinterpret_cast<uint64_t *>(ws + p.off_stats);
+    uint64_t *qmask_pad = reinterpret_cast<uint64_t *>(ws + p.off_qmask);
     uint64_t *samp = reinterpret_cast<uint64_t *>(ws + p.off_samp);
     Record *regions = reinterpret_cast<Record *>(ws + p.off_regions);
     uint64_t *cand = reinterpret_cast<uint64_t *>(ws + p.off_cand);
 
     {
-        const int n_init = p.qpad > p.grid ? p.qpad : p.grid;
+        const int n_init = p.qpad > p.regions ? p.qpad : p.regions;
         const int blocks_rows = (int)ceil_div(p.qpad, 4), blocks_init = (int)ceil_div(n_init, 256);
         const unsigned grid = blocks_rows > blocks_init ? blocks_rows : blocks_init;
         if (q_dtype == KB_F32)
-            hipLaunchKernelGGL(prep_kernel<KB_F32>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, region_cnt, p.grid, stats, (uint64_t)(p.sample_tiles * p.tk));
+            hipLaunchKernelGGL(prep_kernel<KB_F32>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, region_cnt, p.regions, stats, (uint64_t)(p.sample_tiles * p.tk), qmask_dev, qmask_pad, p.grid);
         else
-            hipLaunchKernelGGL(prep_kernel<KB_BF16>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, region_cnt, p.grid, stats, (uint64_t)(p.sample_tiles * p.tk));
+            hipLaunchKernelGGL(prep_kernel<KB_BF16>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, region_cnt, p.regions, stats, (uint64_t)(p.sample_tiles * p.tk), qmask_dev, qmask_pad, p.grid);
         if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
     }
 
@@ -560,6 +583,7 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
         a.tags = qmask_dev ? kb->tags : nullptr;
         a.queries = queries_dev;
         a.qmask = qmask_dev;
+        a.qmask_pad = qmask_pad;
         a.invq = invq;
         a.thr64 = thr64;
         a.thrp = thrp;
@@ -577,7 +601,7 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
             a.n_tiles = p.sample_tiles;
             int64_t sgrid = p.sample_tiles * p.nqb;
             if (sgrid > p.grid) sgrid = p.grid;
-            if (launch_scan(kb->dtype, p.config, true, (int)sgrid, a, s) != hipSuccess) return KB_ERR_DEVICE;
+            if (launch_scan(kb->dtype, p.config, p.ping_pong, true, (int)sgrid, a, s) != hipSuccess) return KB_ERR_DEVICE;
             const int p2 = (int)pow2_ceil(p.sample_slots < 64 ? 64 : p.sample_slots);
             static bool thr_attr = false;
             if (!thr_attr) {
@@ -592,12 +616,12 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
         a.n_tiles = ceil_div(kb->n, p.tk);
         const bool timed = kb->prof_events && kb->prof_used < kb->prof_max;
         if (timed && hipEventRecord(kb->prof_events[2 * kb->prof_used], s) != hipSuccess) return KB_ERR_DEVICE;
-        if (launch_scan(kb->dtype, p.config, false, p.grid, a, s) != hipSuccess) return KB_ERR_DEVICE;
+        if (launch_scan(kb->dtype, p.config, p.ping_pong, false, p.grid, a, s) != hipSuccess) return KB_ERR_DEVICE;
         if (timed) {
             if (hipEventRecord(kb->prof_events[2 * kb->prof_used + 1], s) != hipSuccess) return KB_ERR_DEVICE;
             ++kb->prof_used;
         }
-        hipLaunchKernelGGL(bucket_kernel, dim3(p.grid), dim3(256), 0, s, regions, region_cnt, p.region_cap, cand, p.cand_cap, cnt, flag, stats);
+        hipLaunchKernelGGL(bucket_kernel, dim3(p.regions), dim3(256), 0, s, regions, region_cnt, p.region_cap, cand, p.cand_cap, cnt, flag, stats);
         if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
     }
 

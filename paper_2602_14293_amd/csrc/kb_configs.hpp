@@ -8,7 +8,7 @@
     X(2, KB_BF16, 128, 128, 2, 2, 64, 4, 2)      \
     X(3, KB_BF16, 128, 256, 2, 2, 64, 3, 2)      \
     X(4, KB_BF16, 256, 256, 4, 2, 64, 4, 1)      \
-    X(5, KB_BF16, 256, 256, 2, 2, 64, 4, 1)
+    X(5, KB_BF16, 128, 256, 2, 2, 64, 3, 1)
 #define KB_SCAN_CONFIGS_F32(X)                   \
     X(1, KB_F32, 128, 32, 4, 1, 128, 3, 2)       \
     X(2, KB_F32, 128, 128, 2, 2, 64, 4, 2)       \
@@ -17,3 +17,6 @@
     X(1, KB_FP8_E4M3, 128, 32, 4, 1, 64, 3, 2)   \
     X(2, KB_FP8_E4M3, 128, 128, 2, 2, 64, 3, 2)  \
     X(3, KB_FP8_E4M3, 128, 256, 2, 2, 64, 3, 1)
+
+// Ping-pong configurations (kb_scan_pp.hpp): XP(id, key dtype, TQ, NSTAGE); 256-row tiles, 512 threads.
+#define KB_SCAN_PP_CONFIGS_BF16(XP) XP(6, KB_BF16, 256, 4)

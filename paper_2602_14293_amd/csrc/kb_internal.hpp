@@ -54,14 +54,16 @@ struct Record {  // one candidate that passed the threshold filter of the scan
 struct Plan {
     int32_t Q, k, tq, nqb, qpad;        // queries, tile width in queries, query blocks, padded count
     int32_t config;                     // scan tile configuration id
+    bool ping_pong;                     // which kernel family the configuration belongs to
     int32_t tk;                         // keys per tile
     int32_t groups_per_tile;            // sample groups per key tile
     int64_t sample_tiles;               // key tiles scored by the sampling pass (0 = no sampling)
     int32_t sample_slots;               // sample_tiles * groups_per_tile, per query
     int32_t grid;                       // workgroups of the main scan
-    int32_t region_cap;                 // records per scan workgroup
+    int32_t region_cap;                 // records per scan wavefront
+    int32_t regions;                    // grid * wavefronts per workgroup
     int32_t cand_cap;                   // candidates per query the final sort can take (power of two)
-    size_t off_invq, off_thr64, off_thrp, off_cnt, off_flag, off_region_cnt, off_stats, off_samp, off_regions,
+    size_t off_invq, off_thr64, off_thrp, off_cnt, off_flag, off_region_cnt, off_stats, off_qmask, off_samp, off_regions,
         off_cand, total;
 };
 
@@ -71,12 +73,13 @@ struct ScanArgs {
     const uint64_t *tags;     // nullptr when no filter is applied
     const void *queries;
     const uint64_t *qmask;    // nullptr when no filter is applied
+    const uint64_t *qmask_pad; // [qpad] copy of qmask padded with zero words (library workspace)
     const float *invq;        // [qpad]
     const uint64_t *thr64;    // [qpad] candidate words below this cannot be in the result
     const float *thrp;        // [qpad] conservative pre-filter on dot * inv_k
     uint64_t *samp;           // sampling pass output [qpad][sample_slots]
-    Record *regions;          // [grid][region_cap]
-    uint32_t *region_cnt;     // [grid]
+    Record *regions;          // [grid * waves per workgroup][region_cap]: one private region per wavefront
+    uint32_t *region_cnt;     // [grid * waves per workgroup]
     uint32_t *flag;           // [qpad] set to 1 when a query lost a candidate to a full buffer
     int64_t n_keys;           // rows to scan: [0, n_keys)
     int64_t n_tiles;          // key tiles to scan
@@ -87,12 +90,15 @@ struct ScanArgs {
 hipError_t launch_scan_f32(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
 hipError_t launch_scan_bf16(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
 hipError_t launch_scan_fp8(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
+hipError_t launch_scan_pp_bf16(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
 
 // Static description of a scan configuration (host side planning).
 struct ConfigInfo {
     int tk, tq, threads, groups_per_tile, wg_per_cu;
+    int min_row_bytes;      // smallest key row (bytes) the configuration's pipeline is valid for
+    bool ping_pong;         // kb_scan_pp.hpp kernel instead of kb_scan.hpp
 };
 bool scan_config_info(int key_dtype, int config, ConfigInfo *out);   // false if the id does not exist
-int scan_config_for(int key_dtype, int Q);                           // automatic choice
+int scan_config_for(int key_dtype, int Q, int d);                    // automatic choice
 
 }  // namespace kbi

@@ -23,6 +23,7 @@
 // candidate compare, append to the workgroup's private record region (slot from an LDS counter, plain
 // global store).
 #pragma once
+#include "kb_epilogue.hpp"
 #include "kb_internal.hpp"
 
 namespace kbi {
@@ -118,7 +119,8 @@ struct ScanCfg {
     static constexpr int OFF_THR64 = OFF_TAG + TK * 8;
     static constexpr int OFF_QMASK = OFF_THR64 + TQ * 8;
     static constexpr int OFF_INVQ = OFF_QMASK + TQ * 8;
-    static constexpr int OFF_CNT = OFF_INVQ + TQ * 4;
+    static constexpr int OFF_THRP = OFF_INVQ + TQ * 4;
+    static constexpr int OFF_CNT = OFF_THRP + TQ * 4;
     static constexpr int SMEM_BYTES = OFF_CNT + 16;
     static constexpr int GROUPS_PER_TILE = WM * 2;
     static_assert(TK % (WM * 32) == 0 && TQ % (WN * 32) == 0, "wave tiles are made of 32x32 blocks");
@@ -162,7 +164,6 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
     uint64_t *aux_thr64 = reinterpret_cast<uint64_t *>(smem + C::OFF_THR64);
     uint64_t *aux_qmask = reinterpret_cast<uint64_t *>(smem + C::OFF_QMASK);
     float *aux_invq = reinterpret_cast<float *>(smem + C::OFF_INVQ);
-    uint32_t *lds_cnt = reinterpret_cast<uint32_t *>(smem + C::OFF_CNT);
 
     // items: (tile, qb) with qb fastest; this workgroup takes items blockIdx.x + i * gridDim.x
     const int nqb = p.nqb;
@@ -173,7 +174,8 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
     const uint32_t key_row_bytes = (uint32_t)p.d * C::KEY_BYTES, qry_row_bytes = (uint32_t)p.d * C::QRY_BYTES;
     const int step_tile = gridDim.x / nqb, step_qb = gridDim.x % nqb;
 
-    if (tid == 0) *lds_cnt = 0;
+    Record *my_region = p.regions + ((size_t)blockIdx.x * NW + wave) * p.region_cap;
+    uint32_t wave_cnt = 0;       // wave-uniform
 
     // ---- the load stream: chunk after chunk, item after item ------------------------------------
     // lane -> (row, 16-byte slot) of the 1 KiB block a wave instruction fills; same slot for all of them
@@ -247,9 +249,7 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
     // per-item side data, fetched into registers while the item's last chunks are computed
     float my_invk = 0.f, my_invq = 0.f;
     uint64_t my_tag = 0, my_thr64 = 0, my_qmask = 0;
-    float thrp[JB];
-#pragma unroll
-    for (int jb = 0; jb < JB; ++jb) thrp[jb] = __builtin_inff();
+    float my_thrp = __builtin_inff();
     const int aux_chunk = NC >= 2 ? NC - 2 : 0;
 
     for (int g = 0; g < total; ++g) {
@@ -273,12 +273,11 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
             if (tid < TQ) {
                 const int q = qb * TQ + tid;            // < qpad: invq, thr64 and thrp are padded arrays
                 my_invq = p.invq[q];
-                if (!SAMPLE) my_thr64 = p.thr64[q];
+                if (!SAMPLE) {
+                    my_thr64 = p.thr64[q];
+                    my_thrp = p.thrp[q];
+                }
                 if (filter) my_qmask = p.qmask[q < p.Q ? q : p.Q - 1];
-            }
-            if (!SAMPLE) {
-#pragma unroll
-                for (int jb = 0; jb < JB; ++jb) thrp[jb] = p.thrp[qb * TQ + rowB + jb * 32];
             }
         }
 
@@ -323,89 +322,17 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
                 aux_invq[tid] = my_invq;
                 aux_qmask[tid] = my_qmask;
                 aux_thr64[tid] = my_thr64;
+                reinterpret_cast<float *>(smem + C::OFF_THRP)[tid] = my_thrp;
             }
             __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
             bare_barrier();
             const int64_t row0 = (int64_t)tile * TK;
-
-            if (SAMPLE) {
-#pragma unroll
-                for (int jb = 0; jb < JB; ++jb) {
-                    const int ql = rowB + jb * 32;
-                    const int q = qb * TQ + ql;
-                    const float iq = aux_invq[ql];
-                    const uint64_t qm = aux_qmask[ql];
-                    float best = -__builtin_inff();
-                    int best_rl = -1;
-#pragma unroll
-                    for (int ib = 0; ib < IB; ++ib) {
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            const int rl = rowA - lrow + ib * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-                            const float s = final_score(acc[ib][jb][i], aux_invk[rl], iq);
-                            bool ok = row0 + rl < p.n_keys;
-                            if (filter) ok = ok && (aux_tag[rl] & qm) != 0;
-                            if (ok && s > best) {       // rows ascend, so the first maximum is the lowest index
-                                best = s;
-                                best_rl = rl;
-                            }
-                        }
-                    }
-                    if (q < p.Q) {
-                        const uint64_t cw = best_rl >= 0 ? pack_candidate(best, (uint32_t)(row0 + best_rl)) : 0ull;
-                        p.samp[(size_t)q * p.sample_slots + tile * C::GROUPS_PER_TILE + wm * 2 + half] = cw;
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int ib = 0; ib < IB; ++ib) {
-                    const int rl0 = rowA - lrow + ib * 32 + 4 * half;
-                    const f32x4 ik0 = *reinterpret_cast<const f32x4 *>(aux_invk + rl0);
-                    const f32x4 ik1 = *reinterpret_cast<const f32x4 *>(aux_invk + rl0 + 8);
-                    const f32x4 ik2 = *reinterpret_cast<const f32x4 *>(aux_invk + rl0 + 16);
-                    const f32x4 ik3 = *reinterpret_cast<const f32x4 *>(aux_invk + rl0 + 24);
-                    const float ik[16] = {ik0.x, ik0.y, ik0.z, ik0.w, ik1.x, ik1.y, ik1.z, ik1.w,
-                                          ik2.x, ik2.y, ik2.z, ik2.w, ik3.x, ik3.y, ik3.z, ik3.w};
-#pragma unroll
-                    for (int jb = 0; jb < JB; ++jb) {
-                        const float nt = -thrp[jb];
-                        float m = __builtin_fmaf(acc[ib][jb][0], ik[0], nt);
-#pragma unroll
-                        for (int i = 1; i < 16; ++i) m = __builtin_fmaxf(m, __builtin_fmaf(acc[ib][jb][i], ik[i], nt));
-                        const bool hit = m >= 0.f;
-                        if (__builtin_amdgcn_ballot_w64(hit) != 0) {
-                            if (hit) {
-                                const int ql = rowB + jb * 32;
-                                const uint32_t q = (uint32_t)(qb * TQ + ql);
-                                const float iq = aux_invq[ql];
-                                const uint64_t t64 = aux_thr64[ql];
-                                const uint64_t qm = aux_qmask[ql];
-#pragma unroll
-                                for (int i = 0; i < 16; ++i) {
-                                    const int rl = rl0 + 8 * (i >> 2) + (i & 3);
-                                    const int64_t row = row0 + rl;
-                                    const float s = final_score(acc[ib][jb][i], ik[i], iq);
-                                    const uint64_t cw = pack_candidate(s, (uint32_t)row);
-                                    bool ok = row < p.n_keys && cw >= t64;
-                                    if (filter) ok = ok && (aux_tag[rl] & qm) != 0;
-                                    if (ok) {
-                                        const uint32_t pos = atomicAdd(lds_cnt, 1u);
-                                        if (pos < (uint32_t)p.region_cap) {
-                                            Record rec;
-                                            rec.cand = cw;
-                                            rec.query = q;
-                                            rec.pad = 0;
-                                            p.regions[(size_t)blockIdx.x * p.region_cap + pos] = rec;
-                                        } else {
-                                            p.flag[q] = 1u;
-                                        }
-                                    }
-                                }
-                            }
-                        }
-                    }
-                }
-            }
+            const EpiSide sd{aux_invk, aux_tag, reinterpret_cast<const float *>(smem + C::OFF_THRP), aux_invq, aux_thr64, aux_qmask};
+            if (SAMPLE)
+                sample_epilogue<IB, JB>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p,
+                                        (int64_t)tile * C::GROUPS_PER_TILE + wm * 2 + half);
+            else
+                main_epilogue<IB, JB>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p, my_region, wave_cnt);
 #pragma unroll
             for (int ib = 0; ib < IB; ++ib)
 #pragma unroll
@@ -422,12 +349,9 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
         }
     }
 
-    if (!SAMPLE) {
-        __syncthreads();
-        if (tid == 0) {
-            const uint32_t n = *lds_cnt;
-            p.region_cnt[blockIdx.x] = n < (uint32_t)p.region_cap ? n : (uint32_t)p.region_cap;
-        }
+    if (!SAMPLE && lane == 0) {
+        const uint32_t cap = (uint32_t)p.region_cap;
+        p.region_cnt[blockIdx.x * NW + wave] = wave_cnt < cap ? wave_cnt : cap;
     }
 }
 

@@ -1,0 +1,319 @@
+// The large-batch scan kernel: 8 wavefronts per workgroup in two groups that alternate between
+// "fetch fragments from LDS" and "issue MFMAs", so that each SIMD always has one wavefront feeding its
+// matrix core while the other refills its operand registers (gfx950 only).
+//
+// Tile: 256 key rows x TQ queries x all of d per work item, one workgroup (512 threads) per compute unit.
+// Wave w: SIMD w % 4, group w / 4.  Rows [64 * (w % 4), +64) of the tile, query columns
+// [(TQ/2) * (w / 4), +TQ/2): every SIMD hosts one wave of each group.  Work decomposition, operand
+// layout (S^T = K * Q^T, a lane owns one query column), swizzled direct-to-LDS staging, candidate words,
+// sampling and threshold filter are those of kb_scan.hpp; what differs is the schedule:
+//
+//   barrier index      0     1      2      3      4
+//   group 0            | L0  |  C0  |  L1  |  C1  | ...          L = 12 x ds_read_b128 (one d-chunk of
+//   group 1            |  -  |  L0  |  C0  |  L1  | ...              fragments) + the wave's share of the
+//                                                                    direct-to-LDS loads of chunk c+D
+//                                                                C = 16 MFMAs from registers
+// Both groups run the same instruction stream, shifted by one barrier.  The epilogue of a tile runs at
+// the start of the next L phase, i.e. while the other group's MFMAs keep the matrix cores busy.
+// Per-tile side data (1/|k|, tags) and per-query data (thresholds, 1/|q|, mask words) arrive by
+// direct-to-LDS loads as well, double-buffered by item parity.
+#pragma once
+#include "kb_scan.hpp"
+
+namespace kbi {
+
+template <int KT_, int TQ_, int NSTAGE_> struct PPCfg {
+    static constexpr int KT = KT_, TQ = TQ_, NSTAGE = NSTAGE_;
+    static constexpr int TK = 256, THREADS = 512, NW = 8, RBA = 64;
+    static constexpr int KEY_BYTES = KeyTraits<KT>::KEY_BYTES, QRY_BYTES = KeyTraits<KT>::QRY_BYTES;
+    static constexpr int BMUL = QRY_BYTES / KEY_BYTES;
+    static constexpr int RBB = RBA * BMUL;
+    static constexpr int PPRA = RBA / 16, PPRB = RBB / 16;
+    static constexpr int KG = RBA / 32;
+    static constexpr int IB = 2, JB = TQ / 2 / 32;
+    static constexpr int A_BYTES = TK * RBA, B_BYTES = TQ * RBB, STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int LA = A_BYTES / 1024 / NW, LB = B_BYTES / 1024 / NW;    // load instructions per wave per chunk
+    static constexpr int LPC = LA + LB;
+    static constexpr int D = NSTAGE - 1;                                         // prefetch distance in chunks
+    // side data, two copies (item parity)
+    static constexpr int AUX_INVK = 0;                       // float  [TK]
+    static constexpr int AUX_TAG = AUX_INVK + TK * 4;        // uint64 [TK]
+    static constexpr int AUX_THRP = AUX_TAG + TK * 8;        // float  [TQ]
+    static constexpr int AUX_INVQ = AUX_THRP + TQ * 4;       // float  [TQ]
+    static constexpr int AUX_THR64 = AUX_INVQ + TQ * 4;      // uint64 [TQ]
+    static constexpr int AUX_QMASK = AUX_THR64 + TQ * 8;     // uint64 [TQ]
+    static constexpr int AUX_BYTES = AUX_QMASK + TQ * 8;
+    static constexpr int OFF_AUX = NSTAGE * STAGE_BYTES;
+    static constexpr int OFF_CNT = OFF_AUX + 2 * AUX_BYTES;
+    static constexpr int SMEM_BYTES = OFF_CNT + 16;
+    static constexpr int GROUPS_PER_TILE = 8;                // sampling groups: 4 row blocks x 2 lane halves
+    static_assert(TQ == 256, "query block of 256");
+    static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "every wave issues the same loads");
+    static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget");
+    static_assert(LPC * (D - 1) < 64, "vmcnt is a 6-bit counter");
+    static_assert((TQ * 4) % 1024 == 0, "per-query side data is loaded 1 KiB per wave instruction");
+};
+
+template <class C, bool SAMPLE>
+__global__ __launch_bounds__(512, 1) void kb_scan_pp_kernel(ScanArgs p)
+{
+    constexpr int TK = C::TK, TQ = C::TQ, RBA = C::RBA, RBB = C::RBB, IB = C::IB, JB = C::JB, NW = C::NW;
+    constexpr int LA = C::LA, LB = C::LB, D = C::D;
+    constexpr int RSTEP_A = NW * 64 / C::PPRA, RSTEP_B = NW * 64 / C::PPRB;
+    static_assert(RSTEP_A % 32 == 0 && RSTEP_B % 32 == 0, "the swizzle must not change between instructions");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    typedef __attribute__((address_space(3))) void *lds_ptr;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave & 3, group = wave >> 2;
+    const int lrow = lane & 31, half = lane >> 5;
+    const bool filter = p.qmask != nullptr;
+
+    const int nqb = p.nqb;
+    const int64_t n_items = p.n_tiles * nqb;
+    const int my_items = (int64_t)blockIdx.x < n_items ? (int)((n_items - blockIdx.x + gridDim.x - 1) / gridDim.x) : 0;
+    const int NC = p.d * C::KEY_BYTES / RBA;
+    const int total = my_items * NC;
+    const uint32_t key_row_bytes = (uint32_t)p.d * C::KEY_BYTES, qry_row_bytes = (uint32_t)p.d * C::QRY_BYTES;
+    const int step_tile = gridDim.x / nqb, step_qb = gridDim.x % nqb;
+
+    Record *my_region = p.regions + ((size_t)blockIdx.x * NW + wave) * p.region_cap;
+    uint32_t wave_cnt = 0;       // wave-uniform
+
+    // ---- the load stream -----------------------------------------------------------------------
+    const int ldA_row = (wave * 64 + lane) / C::PPRA, ldB_row = (wave * 64 + lane) / C::PPRB;
+    const uint32_t ldA_piece = (uint32_t)((((wave * 64 + lane) % C::PPRA) ^ swizzle<C::PPRA>(ldA_row)) * 16);
+    const uint32_t ldB_piece = (uint32_t)((((wave * 64 + lane) % C::PPRB) ^ swizzle<C::PPRB>(ldB_row)) * 16);
+    int ld_tile = blockIdx.x / nqb, ld_qb = blockIdx.x % nqb;
+    int ld_c = 0, ld_stage = 0, ld_par = 0;
+    uint32_t offA[LA], offB[LB];
+    auto ld_setup = [&]() {
+        const int64_t left = p.n_keys - (int64_t)ld_tile * TK;
+        const int last = left < TK ? (int)left - 1 : TK - 1;
+#pragma unroll
+        for (int j = 0; j < LA; ++j) {
+            const int r = ldA_row + j * RSTEP_A;
+            offA[j] = (uint32_t)(r < last ? r : last) * key_row_bytes + ldA_piece;
+        }
+        const int qlast = p.Q - 1 - ld_qb * TQ;
+#pragma unroll
+        for (int j = 0; j < LB; ++j) {
+            const int r = ldB_row + j * RSTEP_B;
+            offB[j] = (uint32_t)(ld_qb * TQ + (r < qlast ? r : qlast)) * qry_row_bytes + ldB_piece;
+        }
+    };
+    // side data of the item the load stream is at: 4-byte loads with clamped rows for the caller's arrays
+    // (inv_norm, tags), 16-byte loads for the library's padded per-query arrays
+    auto issue_aux = [&]() {
+        unsigned char *aux = smem + C::OFF_AUX + ld_par * C::AUX_BYTES;
+        const int64_t row0 = (int64_t)ld_tile * TK;
+        if (wave < 4) {
+            int64_t r = row0 + wave * 64 + lane;
+            r = r < p.n_keys ? r : p.n_keys - 1;
+            __builtin_amdgcn_global_load_lds((const void *)(p.inv_norm + r), (lds_ptr)(aux + C::AUX_INVK + wave * 256), 4, 0, 0);
+        }
+        if (filter) {
+            // tags as dwords: wave w covers dwords [64w, 64w+64) = rows [32w, 32w+32)
+            int64_t r = row0 + wave * 32 + (lane >> 1);
+            r = r < p.n_keys ? r : p.n_keys - 1;
+            __builtin_amdgcn_global_load_lds((const void *)(reinterpret_cast<const uint32_t *>(p.tags + r) + (lane & 1)),
+                                             (lds_ptr)(aux + C::AUX_TAG + wave * 256), 4, 0, 0);
+        }
+        const int q0 = ld_qb * TQ;
+        constexpr int NI4 = TQ * 4 / 1024, NI8 = TQ * 8 / 1024;     // wave instructions per array
+        // wave-uniform dispatch of the per-query arrays over the eight waves
+        int slot = wave;
+        if (slot < NI4) {
+            __builtin_amdgcn_global_load_lds((const void *)(p.invq + q0 + slot * 256 + lane * 4),
+                                             (lds_ptr)(aux + C::AUX_INVQ + slot * 1024), 16, 0, 0);
+            if (!SAMPLE)
+                __builtin_amdgcn_global_load_lds((const void *)(p.thrp + q0 + slot * 256 + lane * 4),
+                                                 (lds_ptr)(aux + C::AUX_THRP + slot * 1024), 16, 0, 0);
+        }
+        slot = wave - 2;
+        if (slot >= 0 && slot < NI8) {
+            if (!SAMPLE)
+                __builtin_amdgcn_global_load_lds((const void *)(p.thr64 + q0 + slot * 128 + lane * 2),
+                                                 (lds_ptr)(aux + C::AUX_THR64 + slot * 1024), 16, 0, 0);
+        }
+        slot = wave - 4;
+        if (slot >= 0 && slot < NI8 && filter)
+            __builtin_amdgcn_global_load_lds((const void *)(p.qmask_pad + q0 + slot * 128 + lane * 2),
+                                             (lds_ptr)(aux + C::AUX_QMASK + slot * 1024), 16, 0, 0);
+    };
+    auto issue_next = [&]() {
+        if (ld_c == 0) issue_aux();
+        unsigned char *sA = smem + ld_stage * C::STAGE_BYTES + wave * 1024;
+        unsigned char *sB = sA + C::A_BYTES;
+        const unsigned char *gA = static_cast<const unsigned char *>(p.keys) + (size_t)ld_tile * TK * key_row_bytes + (size_t)ld_c * RBA;
+        const unsigned char *gB = static_cast<const unsigned char *>(p.queries) + (size_t)ld_c * RBB;
+#pragma unroll
+        for (int j = 0; j < LA; ++j)
+            __builtin_amdgcn_global_load_lds((const void *)(gA + offA[j]), (lds_ptr)(sA + j * NW * 1024), 16, 0, 0);
+#pragma unroll
+        for (int j = 0; j < LB; ++j)
+            __builtin_amdgcn_global_load_lds((const void *)(gB + offB[j]), (lds_ptr)(sB + j * NW * 1024), 16, 0, 0);
+        if (++ld_c == NC) {
+            ld_c = 0;
+            ld_par ^= 1;
+            ld_tile += step_tile;
+            ld_qb += step_qb;
+            if (ld_qb >= nqb) {
+                ld_qb -= nqb;
+                ++ld_tile;
+            }
+            if (ld_tile < p.n_tiles) ld_setup();
+        }
+        ld_stage = ld_stage + 1 == C::NSTAGE ? 0 : ld_stage + 1;
+    };
+
+    // ---- fragment addresses ----------------------------------------------------------------------
+    const int rowA = wm * 64 + lrow;
+    const int rowB = group * (TQ / 2) + lrow;
+    const int baseA = rowA * RBA | ((half ^ swizzle<C::PPRA>(rowA)) << 4);
+    const int baseB = C::BMUL == 1 ? (rowB * RBB | ((half ^ swizzle<C::PPRB>(rowB)) << 4))
+                                   : (rowB * RBB | (((2 * half) ^ swizzle<C::PPRB>(rowB)) << 4));
+
+    f32x16 acc[IB][JB];
+#pragma unroll
+    for (int ib = 0; ib < IB; ++ib)
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[ib][jb][i] = 0.f;
+
+    // ---- the epilogue of one item (runs at the start of the following fetch phase) ----------------
+    auto epilogue = [&](int tile, int qb, int par) {
+        const unsigned char *aux = smem + C::OFF_AUX + par * C::AUX_BYTES;
+        const float *aux_invk = reinterpret_cast<const float *>(aux + C::AUX_INVK);
+        const uint64_t *aux_tag = reinterpret_cast<const uint64_t *>(aux + C::AUX_TAG);
+        const float *aux_thrp = reinterpret_cast<const float *>(aux + C::AUX_THRP);
+        const float *aux_invq = reinterpret_cast<const float *>(aux + C::AUX_INVQ);
+        const uint64_t *aux_thr64 = reinterpret_cast<const uint64_t *>(aux + C::AUX_THR64);
+        const uint64_t *aux_qmask = reinterpret_cast<const uint64_t *>(aux + C::AUX_QMASK);
+        const int64_t row0 = (int64_t)tile * TK;
+        const EpiSide sd{aux_invk, aux_tag, aux_thrp, aux_invq, aux_thr64, aux_qmask};
+        if (SAMPLE)
+            sample_epilogue<IB, JB>(acc, sd, filter, wm * 64, rowB, half, row0, qb * TQ, p,
+                                    (int64_t)tile * C::GROUPS_PER_TILE + wm * 2 + half);
+        else
+            main_epilogue<IB, JB>(acc, sd, filter, wm * 64, rowB, half, row0, qb * TQ, p, my_region, wave_cnt);
+#pragma unroll
+        for (int ib = 0; ib < IB; ++ib)
+#pragma unroll
+            for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[ib][jb][i] = 0.f;
+    };
+
+    // ---- prologue: D chunks in flight, chunk 0 landed ------------------------------------------------
+    if (total > 0) ld_setup();
+#pragma unroll
+    for (int s = 0; s < D; ++s)
+        if (s < total) issue_next();
+    if (total > D - 1)
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(C::LPC * (D - 1)));
+    else
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+    __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
+    bare_barrier();                         // barrier 0
+    if (group == 1) bare_barrier();         // group 1 runs one barrier behind
+
+    int tile = blockIdx.x / nqb, qb = blockIdx.x % nqb, par = 0;
+    int c = 0, stage = 0;
+    bool pending = false;                   // an item is complete and waits for its epilogue
+    int e_tile = 0, e_qb = 0, e_par = 0;
+
+    for (int g = 0; g < total; ++g) {
+        // ================= fetch phase =================
+        if (pending) {
+            epilogue(e_tile, e_qb, e_par);
+            pending = false;
+        }
+        typename Mma<C::KT>::PrepA fa[C::KG][IB];
+        u32x4 fb0[C::KG][JB], fb1[C::KG][JB];
+        {
+            const unsigned char *sA = smem + stage * C::STAGE_BYTES;
+            const unsigned char *sB = sA + C::A_BYTES;
+#pragma unroll
+            for (int kg = 0; kg < C::KG; ++kg) {
+#pragma unroll
+                for (int ib = 0; ib < IB; ++ib)
+                    fa[kg][ib] = Mma<C::KT>::prepare(*reinterpret_cast<const u32x4 *>(sA + ((baseA ^ (kg << 5)) + ib * 32 * RBA)));
+#pragma unroll
+                for (int jb = 0; jb < JB; ++jb) {
+                    if (C::BMUL == 1) {
+                        fb0[kg][jb] = *reinterpret_cast<const u32x4 *>(sB + ((baseB ^ (kg << 5)) + jb * 32 * RBB));
+                        fb1[kg][jb] = fb0[kg][jb];
+                    } else {
+                        fb0[kg][jb] = *reinterpret_cast<const u32x4 *>(sB + ((baseB ^ (kg << 6)) + jb * 32 * RBB));
+                        fb1[kg][jb] = *reinterpret_cast<const u32x4 *>(sB + ((baseB ^ (kg << 6) ^ 16) + jb * 32 * RBB));
+                    }
+                }
+            }
+        }
+        if (g + D < total) issue_next();        // refills the buffer of chunk g-1, which both groups have fetched
+        // my share of chunk g+1 must have landed before the next barrier (the other group fetches it first)
+        // (the side data of the item being computed is older than every chunk load still in flight: the load
+        //  stream runs D chunks ahead and the host only picks this kernel when a row has at least NSTAGE chunks)
+        if (g + D < total)
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm(C::LPC * (D - 1)));
+        else
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+        __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
+        __builtin_amdgcn_sched_barrier(0);
+        bare_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ================= MFMA phase =================
+        __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+        for (int kg = 0; kg < C::KG; ++kg)
+#pragma unroll
+            for (int ib = 0; ib < IB; ++ib)
+#pragma unroll
+                for (int jb = 0; jb < JB; ++jb) Mma<C::KT>::run(acc[ib][jb], fa[kg][ib], fb0[kg][jb], fb1[kg][jb]);
+        __builtin_amdgcn_s_setprio(0);
+        stage = stage + 1 == C::NSTAGE ? 0 : stage + 1;
+        if (++c == NC) {
+            pending = true;
+            e_tile = tile;
+            e_qb = qb;
+            e_par = par;
+            c = 0;
+            par ^= 1;
+            tile += step_tile;
+            qb += step_qb;
+            if (qb >= nqb) {
+                qb -= nqb;
+                ++tile;
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        bare_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if (pending) epilogue(e_tile, e_qb, e_par);
+    if (group == 0) bare_barrier();         // matches the extra barrier group 1 took at the start
+
+    if (!SAMPLE && lane == 0) {
+        const uint32_t cap = (uint32_t)p.region_cap;
+        p.region_cnt[blockIdx.x * NW + wave] = wave_cnt < cap ? wave_cnt : cap;
+    }
+}
+
+template <class C> hipError_t launch_scan_pp_cfg(bool sample, int grid, const ScanArgs &a, hipStream_t s)
+{
+    static bool attr_done[2] = {false, false};
+    auto *fn = sample ? &kb_scan_pp_kernel<C, true> : &kb_scan_pp_kernel<C, false>;
+    if (!attr_done[sample]) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM_BYTES);
+        if (e != hipSuccess) return e;
+        attr_done[sample] = true;
+    }
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(C::THREADS), C::SMEM_BYTES, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace kbi
