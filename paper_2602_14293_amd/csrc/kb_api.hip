@@ -45,9 +45,9 @@ bool scan_config_info(int key_dtype, int config, ConfigInfo *out)
     KB_SCAN_CONFIGS_F32(X)
     KB_SCAN_CONFIGS_FP8(X)
 #undef X
-#define XP(ID, KT, TQ, NSTAGE)                                                \
+#define XP(ID, KT, TQ, NSA, NSB)                                              \
     if (key_dtype == KT && config == ID) {                                    \
-        *out = ConfigInfo{256, TQ, 512, 8, 1, 64 * 2 * NSTAGE, true};         \
+        *out = ConfigInfo{256, TQ, 512, 8, 1, 64 * 2 * NSA, true};            \
         return true;                                                          \
     }
     KB_SCAN_PP_CONFIGS_BF16(XP)

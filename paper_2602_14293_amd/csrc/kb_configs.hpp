@@ -18,5 +18,9 @@
     X(2, KB_FP8_E4M3, 128, 128, 2, 2, 64, 3, 2)  \
     X(3, KB_FP8_E4M3, 128, 256, 2, 2, 64, 3, 1)
 
-// Ping-pong configurations (kb_scan_pp.hpp): XP(id, key dtype, TQ, NSTAGE); 256-row tiles, 512 threads.
-#define KB_SCAN_PP_CONFIGS_BF16(XP) XP(6, KB_BF16, 256, 4)
+// Ping-pong configurations (kb_scan_pp.hpp): XP(id, key dtype, TQ, NSA, NSB); 256-row tiles, 512 threads,
+// NSA / NSB = ring depth of key / query chunks in LDS.
+#define KB_SCAN_PP_CONFIGS_BF16(XP) \
+    XP(6, KB_BF16, 256, 5, 3)       \
+    XP(7, KB_BF16, 256, 4, 4)       \
+    XP(8, KB_BF16, 256, 4, 3)

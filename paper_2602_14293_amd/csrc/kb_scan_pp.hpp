@@ -22,8 +22,8 @@
 
 namespace kbi {
 
-template <int KT_, int TQ_, int NSTAGE_> struct PPCfg {
-    static constexpr int KT = KT_, TQ = TQ_, NSTAGE = NSTAGE_;
+template <int KT_, int TQ_, int NSA_, int NSB_> struct PPCfg {
+    static constexpr int KT = KT_, TQ = TQ_, NSA = NSA_, NSB = NSB_;     // ring depths: key chunks, query chunks
     static constexpr int TK = 256, THREADS = 512, NW = 8, RBA = 64;
     static constexpr int KEY_BYTES = KeyTraits<KT>::KEY_BYTES, QRY_BYTES = KeyTraits<KT>::QRY_BYTES;
     static constexpr int BMUL = QRY_BYTES / KEY_BYTES;
@@ -31,10 +31,12 @@ template <int KT_, int TQ_, int NSTAGE_> struct PPCfg {
     static constexpr int PPRA = RBA / 16, PPRB = RBB / 16;
     static constexpr int KG = RBA / 32;
     static constexpr int IB = 2, JB = TQ / 2 / 32;
-    static constexpr int A_BYTES = TK * RBA, B_BYTES = TQ * RBB, STAGE_BYTES = A_BYTES + B_BYTES;
-    static constexpr int LA = A_BYTES / 1024 / NW, LB = B_BYTES / 1024 / NW;    // load instructions per wave per chunk
-    static constexpr int LPC = LA + LB;
-    static constexpr int D = NSTAGE - 1;                                         // prefetch distance in chunks
+    static constexpr int A_BYTES = TK * RBA, B_BYTES = TQ * RBB;
+    // Even waves load key chunks, odd waves load query chunks.  vmcnt counts per wave and completes in order, so
+    // separate issuers let the key stream (HBM latency) run deeper than the query stream (L2 hits).
+    static constexpr int LA = A_BYTES / 1024 / 4, LB = B_BYTES / 1024 / 4;      // load instructions per loading wave per chunk
+    static constexpr int DA = NSA - 1, DB = NSB - 1;                             // prefetch distances in chunks
+    static constexpr int OFF_B = NSA * A_BYTES;
     // side data, two copies (item parity)
     static constexpr int AUX_INVK = 0;                       // float  [TK]
     static constexpr int AUX_TAG = AUX_INVK + TK * 4;        // uint64 [TK]
@@ -43,14 +45,15 @@ template <int KT_, int TQ_, int NSTAGE_> struct PPCfg {
     static constexpr int AUX_THR64 = AUX_INVQ + TQ * 4;      // uint64 [TQ]
     static constexpr int AUX_QMASK = AUX_THR64 + TQ * 8;     // uint64 [TQ]
     static constexpr int AUX_BYTES = AUX_QMASK + TQ * 8;
-    static constexpr int OFF_AUX = NSTAGE * STAGE_BYTES;
+    static constexpr int OFF_AUX = NSA * A_BYTES + NSB * B_BYTES;
     static constexpr int OFF_CNT = OFF_AUX + 2 * AUX_BYTES;
     static constexpr int SMEM_BYTES = OFF_CNT + 16;
     static constexpr int GROUPS_PER_TILE = 8;                // sampling groups: 4 row blocks x 2 lane halves
     static_assert(TQ == 256, "query block of 256");
-    static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "every wave issues the same loads");
+    static_assert(A_BYTES % 4096 == 0 && B_BYTES % 4096 == 0, "four waves share each chunk evenly");
+    static_assert(NSA >= 3 && NSB >= 3, "a chunk is awaited up to one iteration before it is fetched");
     static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget");
-    static_assert(LPC * (D - 1) < 64, "vmcnt is a 6-bit counter");
+    static_assert(LA * (DA - 1) < 64 && LB * (DB - 1) < 64, "vmcnt is a 6-bit counter");
     static_assert((TQ * 4) % 1024 == 0, "per-query side data is loaded 1 KiB per wave instruction");
 };
 
@@ -58,8 +61,8 @@ template <class C, bool SAMPLE>
 __global__ __launch_bounds__(512, 1) void kb_scan_pp_kernel(ScanArgs p)
 {
     constexpr int TK = C::TK, TQ = C::TQ, RBA = C::RBA, RBB = C::RBB, IB = C::IB, JB = C::JB, NW = C::NW;
-    constexpr int LA = C::LA, LB = C::LB, D = C::D;
-    constexpr int RSTEP_A = NW * 64 / C::PPRA, RSTEP_B = NW * 64 / C::PPRB;
+    constexpr int LA = C::LA, LB = C::LB, DA = C::DA, DB = C::DB;
+    constexpr int RSTEP_A = 256 / C::PPRA, RSTEP_B = 256 / C::PPRB;      // rows between a loading wave's instructions
     static_assert(RSTEP_A % 32 == 0 && RSTEP_B % 32 == 0, "the swizzle must not change between instructions");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     typedef __attribute__((address_space(3))) void *lds_ptr;
@@ -81,26 +84,31 @@ __global__ __launch_bounds__(512, 1) void kb_scan_pp_kernel(ScanArgs p)
     Record *my_region = p.regions + ((size_t)blockIdx.x * NW + wave) * p.region_cap;
     uint32_t wave_cnt = 0;       // wave-uniform
 
-    // ---- the load stream -----------------------------------------------------------------------
-    const int ldA_row = (wave * 64 + lane) / C::PPRA, ldB_row = (wave * 64 + lane) / C::PPRB;
-    const uint32_t ldA_piece = (uint32_t)((((wave * 64 + lane) % C::PPRA) ^ swizzle<C::PPRA>(ldA_row)) * 16);
-    const uint32_t ldB_piece = (uint32_t)((((wave * 64 + lane) % C::PPRB) ^ swizzle<C::PPRB>(ldB_row)) * 16);
+    // ---- the load stream of this wave: key chunks (role 0) or query chunks (role 1) ---------------
+    const int role = wave & 1, ridx = wave >> 1;
+    const int ld_row = (ridx * 64 + lane) / (role ? C::PPRB : C::PPRA);
+    const uint32_t ld_piece = role ? (uint32_t)((((ridx * 64 + lane) % C::PPRB) ^ swizzle<C::PPRB>(ld_row)) * 16)
+                                   : (uint32_t)((((ridx * 64 + lane) % C::PPRA) ^ swizzle<C::PPRA>(ld_row)) * 16);
     int ld_tile = blockIdx.x / nqb, ld_qb = blockIdx.x % nqb;
     int ld_c = 0, ld_stage = 0, ld_par = 0;
-    uint32_t offA[LA], offB[LB];
+    constexpr int LMAX = LA > LB ? LA : LB;
+    uint32_t off[LMAX];
     auto ld_setup = [&]() {
-        const int64_t left = p.n_keys - (int64_t)ld_tile * TK;
-        const int last = left < TK ? (int)left - 1 : TK - 1;
+        if (role == 0) {
+            const int64_t left = p.n_keys - (int64_t)ld_tile * TK;
+            const int last = left < TK ? (int)left - 1 : TK - 1;
 #pragma unroll
-        for (int j = 0; j < LA; ++j) {
-            const int r = ldA_row + j * RSTEP_A;
-            offA[j] = (uint32_t)(r < last ? r : last) * key_row_bytes + ldA_piece;
-        }
-        const int qlast = p.Q - 1 - ld_qb * TQ;
+            for (int j = 0; j < LA; ++j) {
+                const int r = ld_row + j * RSTEP_A;
+                off[j] = (uint32_t)(r < last ? r : last) * key_row_bytes + ld_piece;
+            }
+        } else {
+            const int qlast = p.Q - 1 - ld_qb * TQ;
 #pragma unroll
-        for (int j = 0; j < LB; ++j) {
-            const int r = ldB_row + j * RSTEP_B;
-            offB[j] = (uint32_t)(ld_qb * TQ + (r < qlast ? r : qlast)) * qry_row_bytes + ldB_piece;
+            for (int j = 0; j < LB; ++j) {
+                const int r = ld_row + j * RSTEP_B;
+                off[j] = (uint32_t)(ld_qb * TQ + (r < qlast ? r : qlast)) * qry_row_bytes + ld_piece;
+            }
         }
     };
     // side data of the item the load stream is at: 4-byte loads with clamped rows for the caller's arrays
@@ -142,18 +150,26 @@ __global__ __launch_bounds__(512, 1) void kb_scan_pp_kernel(ScanArgs p)
             __builtin_amdgcn_global_load_lds((const void *)(p.qmask_pad + q0 + slot * 128 + lane * 2),
                                              (lds_ptr)(aux + C::AUX_QMASK + slot * 1024), 16, 0, 0);
     };
-    auto issue_next = [&]() {
-        if (ld_c == 0) issue_aux();
-        unsigned char *sA = smem + ld_stage * C::STAGE_BYTES + wave * 1024;
-        unsigned char *sB = sA + C::A_BYTES;
-        const unsigned char *gA = static_cast<const unsigned char *>(p.keys) + (size_t)ld_tile * TK * key_row_bytes + (size_t)ld_c * RBA;
-        const unsigned char *gB = static_cast<const unsigned char *>(p.queries) + (size_t)ld_c * RBB;
-#pragma unroll
-        for (int j = 0; j < LA; ++j)
-            __builtin_amdgcn_global_load_lds((const void *)(gA + offA[j]), (lds_ptr)(sA + j * NW * 1024), 16, 0, 0);
-#pragma unroll
-        for (int j = 0; j < LB; ++j)
-            __builtin_amdgcn_global_load_lds((const void *)(gB + offB[j]), (lds_ptr)(sB + j * NW * 1024), 16, 0, 0);
+    // One chunk of this wave's stream = LD loads; issue_one(j) is called LD times (interleaved with the MFMAs of
+    // the compute phase), then issue_end() advances the stream.
+    auto issue_one = [&](int j) {
+        if (j == 0 && ld_c == 0) issue_aux();
+        if (role == 0) {
+            if (j < LA) {
+                unsigned char *dst = smem + ld_stage * C::A_BYTES + ridx * 1024;
+                const unsigned char *g = static_cast<const unsigned char *>(p.keys) + (size_t)ld_tile * TK * key_row_bytes + (size_t)ld_c * RBA;
+                __builtin_amdgcn_global_load_lds((const void *)(g + off[j]), (lds_ptr)(dst + j * 4096), 16, 0, 0);
+            }
+        } else {
+            if (j < LB) {
+                unsigned char *dst = smem + C::OFF_B + ld_stage * C::B_BYTES + ridx * 1024;
+                const unsigned char *g = static_cast<const unsigned char *>(p.queries) + (size_t)ld_c * RBB;
+                __builtin_amdgcn_global_load_lds((const void *)(g + off[j]), (lds_ptr)(dst + j * 4096), 16, 0, 0);
+            }
+        }
+    };
+    auto issue_end = [&]() {
+        ld_stage = ld_stage + 1 == (role ? C::NSB : C::NSA) ? 0 : ld_stage + 1;
         if (++ld_c == NC) {
             ld_c = 0;
             ld_par ^= 1;
@@ -165,8 +181,24 @@ __global__ __launch_bounds__(512, 1) void kb_scan_pp_kernel(ScanArgs p)
             }
             if (ld_tile < p.n_tiles) ld_setup();
         }
-        ld_stage = ld_stage + 1 == C::NSTAGE ? 0 : ld_stage + 1;
     };
+    auto issue_next = [&]() {
+#pragma unroll
+        for (int j = 0; j < LMAX; ++j) issue_one(j);
+        issue_end();
+    };
+    // my share of a chunk has landed once at most the loads of `younger` younger chunks of my stream are outstanding
+    // (younger = 0: everything has landed); compile-time immediates, so the cases are spelled out
+    auto wait_landed = [&](int younger) {
+        const int n = younger * (role ? LB : LA);
+        if (n <= 0) __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+        else if (n == LA * (DA - 1) && role == 0) __builtin_amdgcn_s_waitcnt(waitcnt_vm(LA * (DA - 1)));
+        else if (n == LA * (DA - 2) && role == 0) __builtin_amdgcn_s_waitcnt(waitcnt_vm(LA * (DA - 2) > 0 ? LA * (DA - 2) : 0));
+        else if (n == LB * (DB - 1) && role == 1) __builtin_amdgcn_s_waitcnt(waitcnt_vm(LB * (DB - 1)));
+        else if (n == LB * (DB - 2) && role == 1) __builtin_amdgcn_s_waitcnt(waitcnt_vm(LB * (DB - 2) > 0 ? LB * (DB - 2) : 0));
+        else __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+    };
+    const int D = role ? DB : DA;
 
     // ---- fragment addresses ----------------------------------------------------------------------
     const int rowA = wm * 64 + lrow;
@@ -207,21 +239,17 @@ __global__ __launch_bounds__(512, 1) void kb_scan_pp_kernel(ScanArgs p)
                 for (int i = 0; i < 16; ++i) acc[ib][jb][i] = 0.f;
     };
 
-    // ---- prologue: D chunks in flight, chunk 0 landed ------------------------------------------------
+    // ---- prologue: D chunks in flight per stream, chunk 0 landed -----------------------------------
     if (total > 0) ld_setup();
-#pragma unroll
     for (int s = 0; s < D; ++s)
         if (s < total) issue_next();
-    if (total > D - 1)
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm(C::LPC * (D - 1)));
-    else
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+    wait_landed(total >= D ? D - 1 : 0);
     __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
     bare_barrier();                         // barrier 0
     if (group == 1) bare_barrier();         // group 1 runs one barrier behind
 
     int tile = blockIdx.x / nqb, qb = blockIdx.x % nqb, par = 0;
-    int c = 0, stage = 0;
+    int c = 0, stageA = 0, stageB = 0;
     bool pending = false;                   // an item is complete and waits for its epilogue
     int e_tile = 0, e_qb = 0, e_par = 0;
 
@@ -234,8 +262,8 @@ __global__ __launch_bounds__(512, 1) void kb_scan_pp_kernel(ScanArgs p)
         typename Mma<C::KT>::PrepA fa[C::KG][IB];
         u32x4 fb0[C::KG][JB], fb1[C::KG][JB];
         {
-            const unsigned char *sA = smem + stage * C::STAGE_BYTES;
-            const unsigned char *sB = sA + C::A_BYTES;
+            const unsigned char *sA = smem + stageA * C::A_BYTES;
+            const unsigned char *sB = smem + C::OFF_B + stageB * C::B_BYTES;
 #pragma unroll
             for (int kg = 0; kg < C::KG; ++kg) {
 #pragma unroll
@@ -253,29 +281,40 @@ __global__ __launch_bounds__(512, 1) void kb_scan_pp_kernel(ScanArgs p)
                 }
             }
         }
-        if (g + D < total) issue_next();        // refills the buffer of chunk g-1, which both groups have fetched
-        // my share of chunk g+1 must have landed before the next barrier (the other group fetches it first)
-        // (the side data of the item being computed is older than every chunk load still in flight: the load
-        //  stream runs D chunks ahead and the host only picks this kernel when a row has at least NSTAGE chunks)
-        if (g + D < total)
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm(C::LPC * (D - 1)));
-        else
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+        // Group 1 fetches chunk g+1 only after group 0 did, but group 0 fetches it right after the next barrier:
+        // group 1's share of chunk g+1 must have landed by the end of this fetch phase.  It has issued chunks up to
+        // g-1+D so far.  (The side data of the item being computed is older than every chunk load in flight.)
+        if (group == 1) wait_landed(g + D <= total ? D - 2 : 0);
         __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
         __builtin_amdgcn_sched_barrier(0);
         bare_barrier();
         __builtin_amdgcn_sched_barrier(0);
 
         // ================= MFMA phase =================
+        // 16 MFMAs from registers; this wave's loads of chunk g+D (they refill the ring slot of chunk g-1, which
+        // both groups have fetched) are issued between them, off the critical path of the fetch phase
         __builtin_amdgcn_s_setprio(1);
+        {
+            constexpr int NM = C::KG * IB * JB, EVERY = NM / LMAX;
+            static_assert(NM % LMAX == 0, "loads spread evenly over the MFMAs");
+            const bool more = g + D < total;
 #pragma unroll
-        for (int kg = 0; kg < C::KG; ++kg)
-#pragma unroll
-            for (int ib = 0; ib < IB; ++ib)
-#pragma unroll
-                for (int jb = 0; jb < JB; ++jb) Mma<C::KT>::run(acc[ib][jb], fa[kg][ib], fb0[kg][jb], fb1[kg][jb]);
+            for (int m = 0; m < NM; ++m) {
+                const int kg = m / (IB * JB), ib = (m / JB) % IB, jb = m % JB;
+                Mma<C::KT>::run(acc[ib][jb], fa[kg][ib], fb0[kg][jb], fb1[kg][jb]);
+                if ((m + 1) % EVERY == 0) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (more) issue_one((m + 1) / EVERY - 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            if (more) issue_end();
+        }
         __builtin_amdgcn_s_setprio(0);
-        stage = stage + 1 == C::NSTAGE ? 0 : stage + 1;
+        // group 0 fetches chunk g+1 right after the next barrier; it has issued chunks up to g+D
+        if (group == 0) wait_landed(g + D < total ? D - 1 : 0);
+        stageA = stageA + 1 == C::NSA ? 0 : stageA + 1;
+        stageB = stageB + 1 == C::NSB ? 0 : stageB + 1;
         if (++c == NC) {
             pending = true;
             e_tile = tile;

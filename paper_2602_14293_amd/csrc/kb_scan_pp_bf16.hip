@@ -7,8 +7,8 @@ namespace kbi {
 hipError_t launch_scan_pp_bf16(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s)
 {
     switch (config) {
-#define XP(ID, KT, TQ, NSTAGE) \
-    case ID: return launch_scan_pp_cfg<PPCfg<KT, TQ, NSTAGE>>(sample, grid, a, s);
+#define XP(ID, KT, TQ, NSA, NSB) \
+    case ID: return launch_scan_pp_cfg<PPCfg<KT, TQ, NSA, NSB>>(sample, grid, a, s);
         KB_SCAN_PP_CONFIGS_BF16(XP)
 #undef XP
     default: return hipErrorInvalidValue;
