@@ -21,6 +21,6 @@
 // Ping-pong configurations (kb_scan_pp.hpp): XP(id, key dtype, TQ, NSA, NSB); 256-row tiles, 512 threads,
 // NSA / NSB = ring depth of key / query chunks in LDS.
 #define KB_SCAN_PP_CONFIGS_BF16(XP) \
-    XP(6, KB_BF16, 256, 5, 3)       \
-    XP(7, KB_BF16, 256, 4, 4)       \
-    XP(8, KB_BF16, 256, 4, 3)
+    XP(6, KB_BF16, 256, 4, 4)       \
+    XP(7, KB_BF16, 256, 5, 3)       \
+    XP(8, KB_BF16, 256, 3, 5)

@@ -259,18 +259,25 @@ __global__ __launch_bounds__(512, 1) void kb_scan_pp_kernel(ScanArgs p)
             epilogue(e_tile, e_qb, e_par);
             pending = false;
         }
+        // 12 fragment reads (LDS-bandwidth bound: four waves x 12 KiB per phase) with this wave's loads of chunk
+        // g+D in between: a direct-to-LDS load holds the issuing wave for 50-90 cycles while the texture-address
+        // unit takes its 64 addresses, and the LDS keeps serving the reads already issued meanwhile.  The loads
+        // refill the ring slot of chunk g-1, which both groups have fetched.
         typename Mma<C::KT>::PrepA fa[C::KG][IB];
         u32x4 fb0[C::KG][JB], fb1[C::KG][JB];
         {
             const unsigned char *sA = smem + stageA * C::A_BYTES;
             const unsigned char *sB = smem + C::OFF_B + stageB * C::B_BYTES;
+            constexpr int PER_KG = IB + JB, NR = C::KG * PER_KG, EVERY = NR / LMAX;
+            static_assert(NR % LMAX == 0, "loads spread evenly over the fragment reads");
+            const bool more = g + D < total;
 #pragma unroll
-            for (int kg = 0; kg < C::KG; ++kg) {
-#pragma unroll
-                for (int ib = 0; ib < IB; ++ib)
-                    fa[kg][ib] = Mma<C::KT>::prepare(*reinterpret_cast<const u32x4 *>(sA + ((baseA ^ (kg << 5)) + ib * 32 * RBA)));
-#pragma unroll
-                for (int jb = 0; jb < JB; ++jb) {
+            for (int r = 0; r < NR; ++r) {
+                const int kg = r / PER_KG, x = r % PER_KG;
+                if (x < IB) {
+                    fa[kg][x] = Mma<C::KT>::prepare(*reinterpret_cast<const u32x4 *>(sA + ((baseA ^ (kg << 5)) + x * 32 * RBA)));
+                } else {
+                    const int jb = x - IB;
                     if (C::BMUL == 1) {
                         fb0[kg][jb] = *reinterpret_cast<const u32x4 *>(sB + ((baseB ^ (kg << 5)) + jb * 32 * RBB));
                         fb1[kg][jb] = fb0[kg][jb];
@@ -279,40 +286,31 @@ __global__ __launch_bounds__(512, 1) void kb_scan_pp_kernel(ScanArgs p)
                         fb1[kg][jb] = *reinterpret_cast<const u32x4 *>(sB + ((baseB ^ (kg << 6) ^ 16) + jb * 32 * RBB));
                     }
                 }
-            }
-        }
-        // Group 1 fetches chunk g+1 only after group 0 did, but group 0 fetches it right after the next barrier:
-        // group 1's share of chunk g+1 must have landed by the end of this fetch phase.  It has issued chunks up to
-        // g-1+D so far.  (The side data of the item being computed is older than every chunk load in flight.)
-        if (group == 1) wait_landed(g + D <= total ? D - 2 : 0);
-        __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
-        __builtin_amdgcn_sched_barrier(0);
-        bare_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-
-        // ================= MFMA phase =================
-        // 16 MFMAs from registers; this wave's loads of chunk g+D (they refill the ring slot of chunk g-1, which
-        // both groups have fetched) are issued between them, off the critical path of the fetch phase
-        __builtin_amdgcn_s_setprio(1);
-        {
-            constexpr int NM = C::KG * IB * JB, EVERY = NM / LMAX;
-            static_assert(NM % LMAX == 0, "loads spread evenly over the MFMAs");
-            const bool more = g + D < total;
-#pragma unroll
-            for (int m = 0; m < NM; ++m) {
-                const int kg = m / (IB * JB), ib = (m / JB) % IB, jb = m % JB;
-                Mma<C::KT>::run(acc[ib][jb], fa[kg][ib], fb0[kg][jb], fb1[kg][jb]);
-                if ((m + 1) % EVERY == 0) {
+                if ((r + 1) % EVERY == 0) {
                     __builtin_amdgcn_sched_barrier(0);
-                    if (more) issue_one((m + 1) / EVERY - 1);
+                    if (more) issue_one((r + 1) / EVERY - 1);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
             if (more) issue_end();
         }
+        // My share of chunk g+1 must have landed before the next barrier (the other group fetches it first); I have
+        // issued chunks up to g+D.  The side data of the item being computed is older than every chunk load in flight.
+        wait_landed(g + D < total ? D - 1 : 0);
+        __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
+        __builtin_amdgcn_sched_barrier(0);
+        bare_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ================= MFMA phase: 16 MFMAs from registers =================
+        __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+        for (int kg = 0; kg < C::KG; ++kg)
+#pragma unroll
+            for (int ib = 0; ib < IB; ++ib)
+#pragma unroll
+                for (int jb = 0; jb < JB; ++jb) Mma<C::KT>::run(acc[ib][jb], fa[kg][ib], fb0[kg][jb], fb1[kg][jb]);
         __builtin_amdgcn_s_setprio(0);
-        // group 0 fetches chunk g+1 right after the next barrier; it has issued chunks up to g+D
-        if (group == 0) wait_landed(g + D < total ? D - 1 : 0);
         stageA = stageA + 1 == C::NSA ? 0 : stageA + 1;
         stageB = stageB + 1 == C::NSB ? 0 : stageB + 1;
         if (++c == NC) {
