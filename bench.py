@@ -52,6 +52,9 @@ def main():
     ap.add_argument("--seed", type=int, default=2000)
     ap.add_argument("--oracle-queries", type=int, default=256, help="queries of the batch given to the CPU oracle")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one 1 GiB device-to-device elementwise copy (a dispatch of known traffic that "
+                         "calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--tune", action="append", default=[], help="name=value performance knob (repeatable)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -92,6 +95,12 @@ def main():
     for _ in range(args.warmup):
         kb.query(queries, k, qmask, out_i, out_s)
     torch.cuda.synchronize()
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     kb.profile_begin(args.steps)
     torch.cuda.synchronize()

@@ -69,6 +69,7 @@ constexpr int ASSUMED_CUS = 256;       // MI355X; used for sizing before a devic
 constexpr int MAX_SAMPLE_SLOTS = 8192; // threshold_kernel sorts this many 64-bit words in LDS (64 KiB)
 constexpr int MAX_CAND_CAP = 8192;     // finalize_kernel likewise
 constexpr int MIN_CAND_CAP = 1024;
+constexpr int CAND_SEGMENTS = 16;     // per-query candidate list = this many independently counted segments
 constexpr size_t WS_ALIGN = 256;
 
 int key_bytes(kb_dtype_t t) { return t == KB_F32 ? 4 : t == KB_BF16 ? 2 : 1; }
@@ -141,7 +142,7 @@ bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, Plan *out)
     p.off_invq = off;        off = align_up(off + sizeof(float) * p.qpad);
     p.off_thr64 = off;       off = align_up(off + sizeof(uint64_t) * p.qpad);
     p.off_thrp = off;        off = align_up(off + sizeof(float) * p.qpad);
-    p.off_cnt = off;         off = align_up(off + sizeof(uint32_t) * p.qpad);
+    p.off_cnt = off;         off = align_up(off + sizeof(uint32_t) * p.qpad * CAND_SEGMENTS);
     p.off_flag = off;        off = align_up(off + sizeof(uint32_t) * p.qpad);
     p.off_region_cnt = off;  off = align_up(off + sizeof(uint32_t) * p.regions);
     p.off_qmask = off;       off = align_up(off + sizeof(uint64_t) * p.qpad);
@@ -230,7 +231,7 @@ template <int QT> __global__ __launch_bounds__(256) void prep_kernel(const void 
     if (t < qpad) {     // padding queries (t >= Q) can never pass the filter of the scan
         thr64[t] = t < Q ? 0ull : ~0ull;
         thrp[t] = t < Q ? -__builtin_inff() : __builtin_inff();
-        cnt[t] = 0;
+        for (int sg = 0; sg < CAND_SEGMENTS; ++sg) cnt[t * CAND_SEGMENTS + sg] = 0;
         flag[t] = 0;
         qmask_pad[t] = (qmask && t < Q) ? qmask[t] : 0ull;
     }
@@ -249,9 +250,19 @@ template <int QT> __global__ __launch_bounds__(256) void prep_kernel(const void 
 // ------------------------------------------------------------------------------------------------
 __device__ inline void bitonic_sort_desc(uint64_t *buf, int n, int tid, int nthreads)
 {
+    // Thread t handles compare-exchange pairs t, t + nthreads, ...; the 64 consecutive pairs of a wavefront touch
+    // one aligned block of 128 elements whenever stride <= 64.  Runs of such stages therefore need no workgroup
+    // barrier: a wave's LDS operations execute in order, so waiting for its own to finish is enough.
+    int prev_stride = 1 << 30;
     for (int size = 2; size <= n; size <<= 1) {
         for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            __syncthreads();
+            if (stride >= 128 || prev_stride >= 128) {
+                __syncthreads();
+            } else {
+                __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0)
+                asm volatile("" ::: "memory");
+            }
+            prev_stride = stride;
             for (int i = tid; i < n / 2; i += nthreads) {
                 const int lo = 2 * i - (i & (stride - 1));
                 const int hi = lo + stride;
@@ -291,17 +302,20 @@ __global__ __launch_bounds__(256) void threshold_kernel(const uint64_t *samp, in
     }
 }
 
-// Records of every scan workgroup -> one list per query.
+// Records of every scan wavefront -> one list per query.  A query's list is CAND_SEGMENTS segments with a
+// counter each (region r feeds segment r % CAND_SEGMENTS), so that the slot-claiming atomics of one query are
+// spread over that many addresses instead of serialising on one.
 __global__ __launch_bounds__(256) void bucket_kernel(const Record *regions, const uint32_t *region_cnt, int region_cap, uint64_t *cand, int cand_cap,
                                                       uint32_t *cnt, uint32_t *flag, uint64_t *stats)
 {
     const uint32_t n = region_cnt[blockIdx.x];
     const Record *r = regions + (size_t)blockIdx.x * region_cap;
+    const uint32_t seg = blockIdx.x % CAND_SEGMENTS, seg_cap = (uint32_t)cand_cap / CAND_SEGMENTS;
     for (uint32_t i = threadIdx.x; i < n; i += 256) {
         const Record rec = r[i];
-        const uint32_t slot = atomicAdd(&cnt[rec.query], 1u);
-        if (slot < (uint32_t)cand_cap)
-            cand[(size_t)rec.query * cand_cap + slot] = rec.cand;
+        const uint32_t slot = atomicAdd(&cnt[rec.query * CAND_SEGMENTS + seg], 1u);
+        if (slot < seg_cap)
+            cand[(size_t)rec.query * cand_cap + seg * seg_cap + slot] = rec.cand;
         else
             flag[rec.query] = 1u;
     }
@@ -402,11 +416,23 @@ template <int KT> __global__ __launch_bounds__(256) void finalize_kernel(FinalAr
         exhaustive_query<KT>(a, q, buf, ctl);
         if (tid == 0) atomicAdd(reinterpret_cast<unsigned long long *>(a.stats + 1), 1ull);
     } else {
-        uint32_t n = a.n_keys > 0 ? a.cnt[q] : 0;
-        if (n > (uint32_t)a.cand_cap) n = a.cand_cap;
+        // gather the query's segments into one contiguous list
+        const uint32_t seg_cap = (uint32_t)a.cand_cap / CAND_SEGMENTS;
+        uint32_t seg_n[CAND_SEGMENTS], seg_off[CAND_SEGMENTS], n = 0;
+#pragma unroll
+        for (int sg = 0; sg < CAND_SEGMENTS; ++sg) {
+            uint32_t c = a.n_keys > 0 ? a.cnt[q * CAND_SEGMENTS + sg] : 0;
+            seg_n[sg] = c < seg_cap ? c : seg_cap;
+            seg_off[sg] = n;
+            n += seg_n[sg];
+        }
         int p2 = KB_K_MAX;
         while (p2 < (int)n) p2 <<= 1;
-        for (int i = tid; i < p2; i += 256) buf[i] = i < (int)n ? a.cand[(size_t)q * a.cand_cap + i] : 0ull;
+        for (int i = n + tid; i < p2; i += 256) buf[i] = 0ull;
+#pragma unroll
+        for (int sg = 0; sg < CAND_SEGMENTS; ++sg)
+            for (uint32_t i = tid; i < seg_n[sg]; i += 256)
+                buf[seg_off[sg] + i] = a.cand[(size_t)q * a.cand_cap + sg * seg_cap + i];
         bitonic_sort_desc(buf, p2, tid, 256);
     }
     if (tid < a.k) {
