@@ -120,7 +120,7 @@ bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, Plan *out)
     p.sample_slots = (int32_t)(st * ci.groups_per_tile);
 
     const int64_t expect = st > 0 ? ceil_div((int64_t)k * n, st * ci.tk) : n;   // candidates per query
-    int64_t cc = pow2_ceil(st > 0 ? 4 * expect : expect);
+    int64_t cc = pow2_ceil(st > 0 ? 8 * expect : expect);
     if (cc < MIN_CAND_CAP) cc = MIN_CAND_CAP;
     if (cc > MAX_CAND_CAP) cc = MAX_CAND_CAP;
     p.cand_cap = (int32_t)cc;
@@ -303,14 +303,15 @@ __global__ __launch_bounds__(256) void threshold_kernel(const uint64_t *samp, in
 }
 
 // Records of every scan wavefront -> one list per query.  A query's list is CAND_SEGMENTS segments with a
-// counter each (region r feeds segment r % CAND_SEGMENTS), so that the slot-claiming atomics of one query are
+// counter each (the regions of scan workgroup w feed segment w % CAND_SEGMENTS), so that the slot-claiming atomics of one query are
 // spread over that many addresses instead of serialising on one.
 __global__ __launch_bounds__(256) void bucket_kernel(const Record *regions, const uint32_t *region_cnt, int region_cap, uint64_t *cand, int cand_cap,
-                                                      uint32_t *cnt, uint32_t *flag, uint64_t *stats)
+                                                      uint32_t *cnt, uint32_t *flag, uint64_t *stats, int waves_per_wg)
 {
     const uint32_t n = region_cnt[blockIdx.x];
     const Record *r = regions + (size_t)blockIdx.x * region_cap;
-    const uint32_t seg = blockIdx.x % CAND_SEGMENTS, seg_cap = (uint32_t)cand_cap / CAND_SEGMENTS;
+    // all regions of a scan workgroup feed one segment (a query column is only seen by some of its waves)
+    const uint32_t seg = (blockIdx.x / waves_per_wg) % CAND_SEGMENTS, seg_cap = (uint32_t)cand_cap / CAND_SEGMENTS;
     for (uint32_t i = threadIdx.x; i < n; i += 256) {
         const Record rec = r[i];
         const uint32_t slot = atomicAdd(&cnt[rec.query * CAND_SEGMENTS + seg], 1u);
@@ -647,7 +648,7 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
             if (hipEventRecord(kb->prof_events[2 * kb->prof_used + 1], s) != hipSuccess) return KB_ERR_DEVICE;
             ++kb->prof_used;
         }
-        hipLaunchKernelGGL(bucket_kernel, dim3(p.regions), dim3(256), 0, s, regions, region_cnt, p.region_cap, cand, p.cand_cap, cnt, flag, stats);
+        hipLaunchKernelGGL(bucket_kernel, dim3(p.regions), dim3(256), 0, s, regions, region_cnt, p.region_cap, cand, p.cand_cap, cnt, flag, stats, p.regions / p.grid);
         if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
     }
 

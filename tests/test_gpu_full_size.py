@@ -1,0 +1,117 @@
+"""GPU parity at the full sizes of the five workloads, in the launch configuration bench.py times.
+
+The oracle cannot score every query at these sizes in test time, so a seeded sample of query rows is checked
+against the fp64 oracle on all keys (the acceptance rule is per query), plus properties that hold at any size:
+self-queries come back first with score 1, results are sorted, indices are unique and in range."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_14293_amd import kb as kbmod
+from paper_2602_14293_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def T():
+    import kb_testlib
+
+    return kb_testlib
+
+
+def _resident_kb(w, capacity=None):
+    code = {torch.float32: kbmod.KB_F32, torch.bfloat16: kbmod.KB_BF16, torch.float8_e4m3fn: kbmod.KB_FP8_E4M3}[w.keys.dtype]
+    kb = kbmod.KnowledgeBase(w.d, code, capacity or w.N, tagged=w.tags is not None)
+    kb.append(w.keys, w.scale, w.tags)
+    kb.normalize()
+    return kb
+
+
+def _properties(gi, gs, N):
+    valid = gi >= 0
+    assert (gi[valid] < N).all()
+    for r in range(gi.shape[0]):
+        row = gi[r][valid[r]]
+        assert len(np.unique(row)) == len(row)
+        s = gs[r][valid[r]]
+        assert np.all((s[:-1] > s[1:]) | ((s[:-1] == s[1:]) & (row[:-1] < row[1:])))
+
+
+def _check_sample(T, w, gi, gs, rows, label):
+    w_cpu = W.Workload(w.name, w.keys.cpu(), w.queries.cpu(), w.k, scale=None if w.scale is None else w.scale.cpu(),
+                       tags=None if w.tags is None else w.tags.cpu(), qmask=None if w.qmask is None else w.qmask.cpu())
+    return T.check_against_oracle(w_cpu, gi, gs, rows=rows, label=label)
+
+
+def test_clustered_full(T):
+    w = W.clustered(seed=1000, device="cuda")                  # N=65536 d=768 bf16 Q=64 k=16
+    kb = _resident_kb(w)
+    gi, gs = kb.query(w.queries, w.k)
+    torch.cuda.synchronize()
+    gi, gs = gi.cpu().numpy(), gs.cpu().numpy()
+    _properties(gi, gs, w.N)
+    rep = _check_sample(T, w, gi, gs, None, "clustered full")
+    assert rep.queries == 64 and kb.counters()["exhaustive_queries"] == 0
+    kb.close()
+
+
+def test_filtered_full(T):
+    w = W.filtered(seed=2001, device="cuda")                   # N=2^20 d=1024 bf16 Q=256 k=32, masked
+    kb = _resident_kb(w)
+    gi, gs = kb.query(w.queries, w.k, w.qmask)
+    torch.cuda.synchronize()
+    gi, gs = gi.cpu().numpy(), gs.cpu().numpy()
+    _properties(gi, gs, w.N)
+    rows = np.random.default_rng(0).choice(256, size=24, replace=False)
+    _check_sample(T, w, gi, gs, np.sort(rows), "filtered full")
+    assert kb.counters()["exhaustive_queries"] == 0
+    # self-queries at full size: stored rows as queries come back first with score 1
+    pick = torch.tensor([0, 255, 256, 65535, 65536, 524287, 1048575], device="cuda")
+    q2 = w.keys[pick].contiguous()
+    gi2, gs2 = kb.query(q2, 4)
+    torch.cuda.synchronize()
+    assert gi2[:, 0].cpu().tolist() == pick.cpu().tolist() and (gs2[:, 0].cpu() - 1.0).abs().max() <= 1e-6
+    kb.close()
+
+
+def test_compressed_full(T):
+    w = W.compressed(seed=3000, device="cuda")                 # N=2^22 d=768 e4m3 + scale, Q=1024 bf16, k=64
+    kb = _resident_kb(w)
+    gi, gs = kb.query(w.queries, w.k)
+    torch.cuda.synchronize()
+    gi, gs = gi.cpu().numpy(), gs.cpu().numpy()
+    _properties(gi, gs, w.N)
+    rows = np.sort(np.random.default_rng(1).choice(1024, size=8, replace=False))
+    _check_sample(T, w, gi, gs, rows, "compressed full")
+    assert kb.counters()["exhaustive_queries"] == 0
+    kb.close()
+
+
+def test_growing_full(T):
+    # 2^20 rows, then rounds of +16384 up to the capacity of 2^21; rounds 0, 31 and 63 are checked
+    seed, d, Q, k = 4000, 1024, 128, 16
+    keys0, tags0, centers = W.growing_base(seed=seed, device="cuda")
+    cap = 1 << 21
+    kb = kbmod.KnowledgeBase(d, kbmod.KB_BF16, cap, tagged=True)
+    kb.append(keys0, None, tags0)
+    kb.normalize()
+    del keys0, tags0
+    for r in range(64):
+        rows, tags, queries, qmask = W.growing_round(seed, r, 16384, d, Q, centers, device="cuda")
+        first = kb.append(rows, None, tags)
+        assert first == (1 << 20) + r * 16384
+        kb.normalize()
+        gi, gs = kb.query(queries, k, qmask)
+        if r in (0, 31, 63):
+            torch.cuda.synchronize()
+            n = kb.size
+            gi, gs = gi.cpu().numpy(), gs.cpu().numpy()
+            _properties(gi, gs, n)
+            w = W.Workload("growing", kb.keys[:n], queries, k, tags=kb.tags[:n], qmask=qmask)
+            sample = np.array([0, 17, 64, 127])
+            _check_sample(T, w, gi, gs, sample, f"growing round {r}")
+            # every query is a perturbed row of the newest block: that row must be rank 1
+            assert (gi[:, 0] >= first).mean() > 0.9
+    assert kb.size == cap
+    kb.close()
