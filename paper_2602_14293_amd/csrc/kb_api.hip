@@ -38,7 +38,7 @@ bool scan_config_info(int key_dtype, int config, ConfigInfo *out)
 {
 #define X(ID, KT, TK, TQ, WM, WN, RBA, NSTAGE, WGPC)                          \
     if (key_dtype == KT && config == ID) {                                    \
-        *out = ConfigInfo{TK, TQ, 64 * WM * WN, WM * 2, WGPC, RBA, false};    \
+        *out = ConfigInfo{TK, TQ, 64 * WM * WN, WM * 2, WGPC, RBA, 0};    \
         return true;                                                          \
     }
     KB_SCAN_CONFIGS_BF16(X)
@@ -47,11 +47,18 @@ bool scan_config_info(int key_dtype, int config, ConfigInfo *out)
 #undef X
 #define XP(ID, KT, TQ, NSA, NSB)                                              \
     if (key_dtype == KT && config == ID) {                                    \
-        *out = ConfigInfo{256, TQ, 512, 8, 1, 64 * 2 * NSA, true};            \
+        *out = ConfigInfo{256, TQ, 512, 8, 1, 64 * 2 * NSA, 1};               \
         return true;                                                          \
     }
     KB_SCAN_PP_CONFIGS_BF16(XP)
 #undef XP
+#define XB(ID, KT, NSA, NSB)                                                  \
+    if (key_dtype == KT && config == ID) {                                    \
+        *out = ConfigInfo{256, 256, 256, 4, 1, 64 * 2 * (NSA > NSB ? NSA : NSB), 2}; \
+        return true;                                                          \
+    }
+    KB_SCAN_BIG_CONFIGS_BF16(XB)
+#undef XB
     return false;
 }
 
@@ -97,7 +104,7 @@ bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, Plan *out)
         p.config = Q <= 32 ? 1 : Q <= 128 ? 2 : 3;
         if (!scan_config_info(h->dtype, p.config, &ci)) return false;
     }
-    p.ping_pong = ci.ping_pong;
+    p.family = ci.family;
     p.tk = ci.tk;
     p.tq = ci.tq;
     p.groups_per_tile = ci.groups_per_tile;
@@ -106,20 +113,28 @@ bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, Plan *out)
     if (n < 1) n = 1;
     const int64_t n_tiles = ceil_div(n, ci.tk);
 
+    // The sampling pass may run another scan configuration than the main pass (same query block width; every
+    // kernel produces bit-identical scores, so thresholds carry over).  Today it uses the same one.
+    ConfigInfo sci = ci;
+    p.sample_config = p.config;
+    p.sample_family = sci.family;
+    p.sample_wgpc = sci.wg_per_cu;
+    const int64_t s_tiles_all = ceil_div(n, sci.tk);
     int64_t st = 0;
     if (n_tiles >= 8) {
         int64_t m = h->tune_sample_keys > 0 ? h->tune_sample_keys : ((int64_t)k * n / 512 > n / 64 ? (int64_t)k * n / 512 : n / 64);
-        st = ceil_div(m, ci.tk);
-        const int64_t want = ceil_div(2 * (int64_t)k, ci.groups_per_tile);
+        st = ceil_div(m, sci.tk);
+        const int64_t want = ceil_div(2 * (int64_t)k, sci.groups_per_tile);
         if (st < want) st = want;
-        if (st > MAX_SAMPLE_SLOTS / ci.groups_per_tile) st = MAX_SAMPLE_SLOTS / ci.groups_per_tile;
-        if (st > n_tiles / 2) st = n_tiles / 2;
-        if (st * ci.groups_per_tile < k) st = 0;
+        if (st > MAX_SAMPLE_SLOTS / sci.groups_per_tile) st = MAX_SAMPLE_SLOTS / sci.groups_per_tile;
+        if (st > s_tiles_all / 2) st = s_tiles_all / 2;
+        if (st * sci.groups_per_tile < k) st = 0;
     }
     p.sample_tiles = st;
-    p.sample_slots = (int32_t)(st * ci.groups_per_tile);
+    p.sample_slots = (int32_t)(st * sci.groups_per_tile);
+    p.sample_keys = st * sci.tk;
 
-    const int64_t expect = st > 0 ? ceil_div((int64_t)k * n, st * ci.tk) : n;   // candidates per query
+    const int64_t expect = st > 0 ? ceil_div((int64_t)k * n, st * sci.tk) : n;   // candidates per query
     int64_t cc = pow2_ceil(st > 0 ? 8 * expect : expect);
     if (cc < MIN_CAND_CAP) cc = MIN_CAND_CAP;
     if (cc > MAX_CAND_CAP) cc = MAX_CAND_CAP;
@@ -282,13 +297,13 @@ __device__ inline void bitonic_sort_desc(uint64_t *buf, int n, int tid, int nthr
 // entries reach it).  Also derives the conservative pre-filter on dot * inv_k used by the main pass:
 // whenever fp32((dot*inv_k) * inv_q) >= s_thr holds, dot*inv_k >= thrp holds (2^-20 relative slack
 // covers the three fp32 roundings involved).
-__global__ __launch_bounds__(256) void threshold_kernel(const uint64_t *samp, int slots, int p2, int k, const float *invq, uint64_t *thr64, float *thrp)
+__global__ __launch_bounds__(1024) void threshold_kernel(const uint64_t *samp, int slots, int p2, int k, const float *invq, uint64_t *thr64, float *thrp)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     uint64_t *buf = reinterpret_cast<uint64_t *>(smem_raw);
     const int q = blockIdx.x, tid = threadIdx.x;
-    for (int i = tid; i < p2; i += 256) buf[i] = i < slots ? samp[(size_t)q * slots + i] : 0ull;
-    bitonic_sort_desc(buf, p2, tid, 256);
+    for (int i = tid; i < p2; i += (int)blockDim.x) buf[i] = i < slots ? samp[(size_t)q * slots + i] : 0ull;
+    bitonic_sort_desc(buf, p2, tid, (int)blockDim.x);
     if (tid == 0) {
         const uint64_t t = k <= slots ? buf[k - 1] : 0ull;
         const float iq = invq[q];
@@ -443,9 +458,10 @@ template <int KT> __global__ __launch_bounds__(256) void finalize_kernel(FinalAr
     }
 }
 
-hipError_t launch_scan(kb_dtype_t dt, int config, bool ping_pong, bool sample, int grid, const ScanArgs &a, hipStream_t s)
+hipError_t launch_scan(kb_dtype_t dt, int config, int family, bool sample, int grid, const ScanArgs &a, hipStream_t s)
 {
-    if (ping_pong) return dt == KB_BF16 ? launch_scan_pp_bf16(config, sample, grid, a, s) : hipErrorInvalidValue;
+    if (family == 1) return dt == KB_BF16 ? launch_scan_pp_bf16(config, sample, grid, a, s) : hipErrorInvalidValue;
+    if (family == 2) return dt == KB_BF16 ? launch_scan_big_bf16(config, sample, grid, a, s) : hipErrorInvalidValue;
     switch (dt) {
     case KB_F32: return launch_scan_f32(config, sample, grid, a, s);
     case KB_BF16: return launch_scan_bf16(config, sample, grid, a, s);
@@ -597,9 +613,9 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
         const int blocks_rows = (int)ceil_div(p.qpad, 4), blocks_init = (int)ceil_div(n_init, 256);
         const unsigned grid = blocks_rows > blocks_init ? blocks_rows : blocks_init;
         if (q_dtype == KB_F32)
-            hipLaunchKernelGGL(prep_kernel<KB_F32>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, region_cnt, p.regions, stats, (uint64_t)(p.sample_tiles * p.tk), qmask_dev, qmask_pad, p.grid);
+            hipLaunchKernelGGL(prep_kernel<KB_F32>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, region_cnt, p.regions, stats, (uint64_t)p.sample_keys, qmask_dev, qmask_pad, p.grid);
         else
-            hipLaunchKernelGGL(prep_kernel<KB_BF16>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, region_cnt, p.regions, stats, (uint64_t)(p.sample_tiles * p.tk), qmask_dev, qmask_pad, p.grid);
+            hipLaunchKernelGGL(prep_kernel<KB_BF16>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, region_cnt, p.regions, stats, (uint64_t)p.sample_keys, qmask_dev, qmask_pad, p.grid);
         if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
     }
 
@@ -627,8 +643,9 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
         if (p.sample_tiles > 0) {
             a.n_tiles = p.sample_tiles;
             int64_t sgrid = p.sample_tiles * p.nqb;
-            if (sgrid > p.grid) sgrid = p.grid;
-            if (launch_scan(kb->dtype, p.config, p.ping_pong, true, (int)sgrid, a, s) != hipSuccess) return KB_ERR_DEVICE;
+            const int64_t smax = (int64_t)(kb->cu_count > 0 ? kb->cu_count : ASSUMED_CUS) * p.sample_wgpc;
+            if (sgrid > smax) sgrid = smax;
+            if (launch_scan(kb->dtype, p.sample_config, p.sample_family, true, (int)sgrid, a, s) != hipSuccess) return KB_ERR_DEVICE;
             const int p2 = (int)pow2_ceil(p.sample_slots < 64 ? 64 : p.sample_slots);
             static bool thr_attr = false;
             if (!thr_attr) {
@@ -637,13 +654,13 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
                     return KB_ERR_DEVICE;
                 thr_attr = true;
             }
-            hipLaunchKernelGGL(threshold_kernel, dim3(Q), dim3(256), (size_t)p2 * 8, s, samp, p.sample_slots, p2, k, invq, thr64, thrp);
+            hipLaunchKernelGGL(threshold_kernel, dim3(Q), dim3(p2 >= 2048 ? 1024 : p2 >= 1024 ? 512 : 256), (size_t)p2 * 8, s, samp, p.sample_slots, p2, k, invq, thr64, thrp);
             if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
         }
         a.n_tiles = ceil_div(kb->n, p.tk);
         const bool timed = kb->prof_events && kb->prof_used < kb->prof_max;
         if (timed && hipEventRecord(kb->prof_events[2 * kb->prof_used], s) != hipSuccess) return KB_ERR_DEVICE;
-        if (launch_scan(kb->dtype, p.config, p.ping_pong, false, p.grid, a, s) != hipSuccess) return KB_ERR_DEVICE;
+        if (launch_scan(kb->dtype, p.config, p.family, false, p.grid, a, s) != hipSuccess) return KB_ERR_DEVICE;
         if (timed) {
             if (hipEventRecord(kb->prof_events[2 * kb->prof_used + 1], s) != hipSuccess) return KB_ERR_DEVICE;
             ++kb->prof_used;

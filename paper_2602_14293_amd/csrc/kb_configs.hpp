@@ -24,3 +24,8 @@
     XP(6, KB_BF16, 256, 4, 4)       \
     XP(7, KB_BF16, 256, 5, 3)       \
     XP(8, KB_BF16, 256, 3, 5)
+
+// Register-tile configurations (kb_scan_big.hpp): XB(id, key dtype, NSA, NSB); 256 x 256 tiles, 256 threads.
+#define KB_SCAN_BIG_CONFIGS_BF16(XB) \
+    XB(9, KB_BF16, 4, 4)             \
+    XB(10, KB_BF16, 5, 3)

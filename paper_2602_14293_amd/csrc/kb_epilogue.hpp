@@ -28,7 +28,84 @@ __device__ inline float select16(const f32x16 &a, int i)
 // do build the 16-bit mask of elements passing the exact pre-filter (sign bit of fma(dot, inv_k, -thrp),
 // collected with one v_alignbit each) and walk its set bits: final score, candidate word, threshold word,
 // tag predicate, append to the wave's private record region (no atomics: slot = the wave's running
-// count + the lane's rank among the appending lanes).  Nothing below is unrolled over elements except the mask, so the code stays small.
+// count + the lane's rank among the appending lanes).  Nothing below is unrolled over elements except the
+// mask, so the code stays small.
+struct EpiRows {               // 1/|k| of the 16 key rows a lane holds in one 32-row block
+    float ik[16];
+    float ikmax;
+    int rl0;                   // tile-local row of element 0
+};
+
+__device__ inline EpiRows load_rows(const EpiSide &sd, int rl0)
+{
+    EpiRows r;
+    const f32x4 ik0 = *reinterpret_cast<const f32x4 *>(sd.invk + rl0);
+    const f32x4 ik1 = *reinterpret_cast<const f32x4 *>(sd.invk + rl0 + 8);
+    const f32x4 ik2 = *reinterpret_cast<const f32x4 *>(sd.invk + rl0 + 16);
+    const f32x4 ik3 = *reinterpret_cast<const f32x4 *>(sd.invk + rl0 + 24);
+    const float ik[16] = {ik0.x, ik0.y, ik0.z, ik0.w, ik1.x, ik1.y, ik1.z, ik1.w,
+                          ik2.x, ik2.y, ik2.z, ik2.w, ik3.x, ik3.y, ik3.z, ik3.w};
+    r.ikmax = ik[0];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        r.ik[i] = ik[i];
+        r.ikmax = __builtin_fmaxf(r.ikmax, ik[i]);
+    }
+    r.rl0 = rl0;
+    return r;
+}
+
+__device__ inline void main_block(const f32x16 &a, const EpiRows &rw, float tp, int ql, const EpiSide &sd, bool filter,
+                                  int64_t row0, int q0, const ScanArgs &p, Record *region, uint32_t &wave_cnt)
+{
+    float amax = a[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) amax = __builtin_fmaxf(amax, a[i]);
+    // some element can reach the pre-filter only if amax * ikmax does (thrp > 0); otherwise look closer
+    const bool maybe = !(__builtin_fmaf(amax, rw.ikmax, -tp) < 0.f) || !(tp > 0.f);
+    if (__builtin_amdgcn_ballot_w64(maybe) == 0) return;
+    uint32_t fail = 0;
+    if (maybe) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            fail = __builtin_amdgcn_alignbit(fail, as_u32(__builtin_fmaf(a[i], rw.ik[i], -tp)), 31);
+    }
+    uint32_t pass = maybe ? (~fail & 0xffffu) : 0u;     // element i sits at bit 15 - i
+    if (__builtin_amdgcn_ballot_w64(pass != 0) == 0) return;
+    const float iq = sd.invq[ql];
+    const uint64_t t64 = sd.thr64[ql];
+    const uint64_t qm = filter ? sd.qmask[ql] : 0ull;
+    // every lane runs the loop body (lanes without work compute on element 15 and discard it), so the
+    // wave-wide ballots below sit in uniform control flow
+    while (__builtin_amdgcn_ballot_w64(pass != 0) != 0) {
+        const bool has = pass != 0;
+        const int b = has ? 31 - __builtin_clz(pass) : 0;
+        pass &= ~(1u << b);
+        const int i = 15 - b;
+        const int rl = rw.rl0 + 8 * (i >> 2) + (i & 3);
+        const int64_t row = row0 + rl;
+        const float s = final_score(select16(a, i), sd.invk[rl], iq);
+        const uint64_t cw = pack_candidate(s, (uint32_t)row);
+        bool ok = has && row < p.n_keys && cw >= t64;
+        if (filter) ok = ok && (sd.tag[rl] & qm) != 0;
+        // slot in the wave's own record region: running count + rank among the lanes that append
+        const uint64_t okm = __builtin_amdgcn_ballot_w64(ok);
+        if (ok) {
+            const uint32_t pos = wave_cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(okm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)okm, 0u));
+            if (pos < (uint32_t)p.region_cap) {
+                Record rec;
+                rec.cand = cw;
+                rec.query = (uint32_t)(q0 + ql);
+                rec.pad = 0;
+                region[pos] = rec;
+            } else {
+                p.flag[q0 + ql] = 1u;
+            }
+        }
+        wave_cnt += (uint32_t)__builtin_popcountll(okm);
+    }
+}
+
 template <int IB, int JB>
 __device__ inline void main_epilogue(const f32x16 (&acc)[IB][JB], const EpiSide &sd, bool filter, int wave_row0, int ql0,
                                      int half, int64_t row0, int q0, const ScanArgs &p, Record *region, uint32_t &wave_cnt)
@@ -38,121 +115,56 @@ __device__ inline void main_epilogue(const f32x16 (&acc)[IB][JB], const EpiSide 
     for (int jb = 0; jb < JB; ++jb) thrp[jb] = sd.thrp[ql0 + jb * 32];
 #pragma unroll
     for (int ib = 0; ib < IB; ++ib) {
-        const int rl0 = wave_row0 + ib * 32 + 4 * half;
-        const f32x4 ik0 = *reinterpret_cast<const f32x4 *>(sd.invk + rl0);
-        const f32x4 ik1 = *reinterpret_cast<const f32x4 *>(sd.invk + rl0 + 8);
-        const f32x4 ik2 = *reinterpret_cast<const f32x4 *>(sd.invk + rl0 + 16);
-        const f32x4 ik3 = *reinterpret_cast<const f32x4 *>(sd.invk + rl0 + 24);
-        const float ik[16] = {ik0.x, ik0.y, ik0.z, ik0.w, ik1.x, ik1.y, ik1.z, ik1.w,
-                              ik2.x, ik2.y, ik2.z, ik2.w, ik3.x, ik3.y, ik3.z, ik3.w};
-        float ikmax = ik[0];
+        const EpiRows rw = load_rows(sd, wave_row0 + ib * 32 + 4 * half);
 #pragma unroll
-        for (int i = 1; i < 16; ++i) ikmax = __builtin_fmaxf(ikmax, ik[i]);
-#pragma unroll
-        for (int jb = 0; jb < JB; ++jb) {
-            const f32x16 &a = acc[ib][jb];
-            float amax = a[0];
-#pragma unroll
-            for (int i = 1; i < 16; ++i) amax = __builtin_fmaxf(amax, a[i]);
-            // some element can reach the pre-filter only if amax * ikmax does (thrp > 0); otherwise look closer
-            const float tp = thrp[jb];
-            const bool maybe = !(__builtin_fmaf(amax, ikmax, -tp) < 0.f) || !(tp > 0.f);
-            if (__builtin_amdgcn_ballot_w64(maybe) != 0) {
-                uint32_t fail = 0;
-                if (maybe) {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        fail = __builtin_amdgcn_alignbit(fail, as_u32(__builtin_fmaf(a[i], ik[i], -tp)), 31);
-                }
-                uint32_t pass = maybe ? (~fail & 0xffffu) : 0u;     // element i sits at bit 15 - i
-                if (__builtin_amdgcn_ballot_w64(pass != 0) != 0) {
-                    const int ql = ql0 + jb * 32;
-                    const float iq = sd.invq[ql];
-                    const uint64_t t64 = sd.thr64[ql];
-                    const uint64_t qm = filter ? sd.qmask[ql] : 0ull;
-                    // every lane runs the loop body (lanes without work compute on element 15 and discard it), so
-                    // the wave-wide ballots below sit in uniform control flow
-                    while (__builtin_amdgcn_ballot_w64(pass != 0) != 0) {
-                        const bool has = pass != 0;
-                        const int b = has ? 31 - __builtin_clz(pass) : 0;
-                        pass &= ~(1u << b);
-                        const int i = 15 - b;
-                        const int rl = rl0 + 8 * (i >> 2) + (i & 3);
-                        const int64_t row = row0 + rl;
-                        const float s = final_score(select16(a, i), sd.invk[rl], iq);
-                        const uint64_t cw = pack_candidate(s, (uint32_t)row);
-                        bool ok = has && row < p.n_keys && cw >= t64;
-                        if (filter) ok = ok && (sd.tag[rl] & qm) != 0;
-                        // slot in the wave's own record region: running count + rank among the lanes that append
-                        const uint64_t okm = __builtin_amdgcn_ballot_w64(ok);
-                        if (ok) {
-                            const uint32_t pos = wave_cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(okm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)okm, 0u));
-                            if (pos < (uint32_t)p.region_cap) {
-                                Record rec;
-                                rec.cand = cw;
-                                rec.query = (uint32_t)(q0 + ql);
-                                rec.pad = 0;
-                                region[pos] = rec;
-                            } else {
-                                p.flag[q0 + ql] = 1u;
-                            }
-                        }
-                        wave_cnt += (uint32_t)__builtin_popcountll(okm);
-                    }
-                }
-            }
-        }
+        for (int jb = 0; jb < JB; ++jb)
+            main_block(acc[ib][jb], rw, thrp[jb], ql0 + jb * 32, sd, filter, row0, q0, p, region, wave_cnt);
     }
 }
 
 // Sampling pass: per lane and query column, one qualifying entry of the lane's rows with (nearly) the
 // largest score, as a candidate word with its exact final score.  Any qualifying entry is a valid sample;
 // taking the maximum of dot * inv_k (first one on ties) makes it the group's best or a tie of it.
+__device__ inline void sample_block(const f32x16 &a, int rl0, const EpiSide &sd, bool filter, uint64_t qm, int64_t row0,
+                                    int64_t n_keys, float &best, int &best_rl)
+{
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int rl = rl0 + 8 * (i >> 2) + (i & 3);
+        const float s1 = a[i] * sd.invk[rl];
+        bool ok = row0 + rl < n_keys && s1 > best;
+        if (filter) ok = ok && (sd.tag[rl] & qm) != 0;
+        if (ok) {
+            best = s1;
+            best_rl = rl;
+        }
+    }
+}
+
+__device__ inline void sample_store(float best, int best_rl, int ql, const EpiSide &sd, int64_t row0, int q0, const ScanArgs &p,
+                                    int64_t slot)
+{
+    if (q0 + ql < p.Q) {
+        uint64_t cw = 0ull;
+        if (best_rl >= 0)       // best = dot * inv_k was computed exactly as final_score's first product
+            cw = pack_candidate(best * sd.invq[ql] + 0.0f, (uint32_t)(row0 + best_rl));
+        p.samp[(size_t)(q0 + ql) * p.sample_slots + slot] = cw;
+    }
+}
+
 template <int IB, int JB>
 __device__ inline void sample_epilogue(const f32x16 (&acc)[IB][JB], const EpiSide &sd, bool filter, int wave_row0, int ql0,
                                        int half, int64_t row0, int q0, const ScanArgs &p, int64_t slot)
 {
-    float best[JB];
-    int best_rl[JB];
-    uint64_t qm[JB];
 #pragma unroll
     for (int jb = 0; jb < JB; ++jb) {
-        best[jb] = -__builtin_inff();
-        best_rl[jb] = -1;
-        qm[jb] = filter ? sd.qmask[ql0 + jb * 32] : 0ull;
-    }
+        float best = -__builtin_inff();
+        int best_rl = -1;
+        const uint64_t qm = filter ? sd.qmask[ql0 + jb * 32] : 0ull;
 #pragma unroll
-    for (int ib = 0; ib < IB; ++ib) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int rl = wave_row0 + ib * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-            const float ikv = sd.invk[rl];
-            const bool in = row0 + rl < p.n_keys;
-            const uint64_t tg = filter ? sd.tag[rl] : 0ull;
-#pragma unroll
-            for (int jb = 0; jb < JB; ++jb) {
-                const float s1 = acc[ib][jb][i] * ikv;
-                bool ok = in && s1 > best[jb];
-                if (filter) ok = ok && (tg & qm[jb]) != 0;
-                if (ok) {
-                    best[jb] = s1;
-                    best_rl[jb] = rl;
-                }
-            }
-        }
-    }
-#pragma unroll
-    for (int jb = 0; jb < JB; ++jb) {
-        const int ql = ql0 + jb * 32;
-        if (q0 + ql < p.Q) {
-            uint64_t cw = 0ull;
-            if (best_rl[jb] >= 0) {
-                // best = dot * inv_k was computed exactly as final_score's first product
-                const float s = best[jb] * sd.invq[ql] + 0.0f;
-                cw = pack_candidate(s, (uint32_t)(row0 + best_rl[jb]));
-            }
-            p.samp[(size_t)(q0 + ql) * p.sample_slots + slot] = cw;
-        }
+        for (int ib = 0; ib < IB; ++ib)
+            sample_block(acc[ib][jb], wave_row0 + ib * 32 + 4 * half, sd, filter, qm, row0, p.n_keys, best, best_rl);
+        sample_store(best, best_rl, ql0 + jb * 32, sd, row0, q0, p, slot);
     }
 }
 

@@ -54,10 +54,12 @@ struct Record {  // one candidate that passed the threshold filter of the scan
 struct Plan {
     int32_t Q, k, tq, nqb, qpad;        // queries, tile width in queries, query blocks, padded count
     int32_t config;                     // scan tile configuration id
-    bool ping_pong;                     // which kernel family the configuration belongs to
+    int family;                         // which kernel family the configuration belongs to (ConfigInfo::family)
     int32_t tk;                         // keys per tile
     int32_t groups_per_tile;            // sample groups per key tile
-    int64_t sample_tiles;               // key tiles scored by the sampling pass (0 = no sampling)
+    int32_t sample_config, sample_family, sample_wgpc;   // the sampling pass may use another scan configuration
+    int64_t sample_tiles;               // key tiles (of the sampling configuration) scored by the sampling pass (0 = none)
+    int64_t sample_keys;                // rows they cover
     int32_t sample_slots;               // sample_tiles * groups_per_tile, per query
     int32_t grid;                       // workgroups of the main scan
     int32_t region_cap;                 // records per scan wavefront
@@ -91,12 +93,13 @@ hipError_t launch_scan_f32(int config, bool sample, int grid, const ScanArgs &a,
 hipError_t launch_scan_bf16(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
 hipError_t launch_scan_fp8(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
 hipError_t launch_scan_pp_bf16(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
+hipError_t launch_scan_big_bf16(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
 
 // Static description of a scan configuration (host side planning).
 struct ConfigInfo {
     int tk, tq, threads, groups_per_tile, wg_per_cu;
     int min_row_bytes;      // smallest key row (bytes) the configuration's pipeline is valid for
-    bool ping_pong;         // kb_scan_pp.hpp kernel instead of kb_scan.hpp
+    int family;             // 0: kb_scan.hpp, 1: kb_scan_pp.hpp, 2: kb_scan_big.hpp
 };
 bool scan_config_info(int key_dtype, int config, ConfigInfo *out);   // false if the id does not exist
 int scan_config_for(int key_dtype, int Q, int d);                    // automatic choice
