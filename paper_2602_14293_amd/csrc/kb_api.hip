@@ -78,6 +78,8 @@ constexpr int MAX_CAND_CAP = 8192;     // finalize_kernel likewise
 constexpr int MIN_CAND_CAP = 1024;
 constexpr int CAND_SEGMENTS = 16;     // per-query candidate list = this many independently counted segments
 constexpr size_t WS_ALIGN = 256;
+constexpr int STAT_WORDS = 4;          // candidates, exhaustive queries, sample keys, scan workgroups
+constexpr int STAT_PARTIALS = 64;      // the candidate count is kept as this many partial sums (one hot address would serialise)
 
 int key_bytes(kb_dtype_t t) { return t == KB_F32 ? 4 : t == KB_BF16 ? 2 : 1; }
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -153,7 +155,7 @@ bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, Plan *out)
     p.region_cap = (int32_t)rc;
 
     size_t off = 0;
-    p.off_stats = off;       off = align_up(off + sizeof(uint64_t) * 4);   // always first: kb_query_counters reads it
+    p.off_stats = off;       off = align_up(off + sizeof(uint64_t) * (STAT_WORDS + STAT_PARTIALS));   // always first: kb_query_counters reads it
     p.off_invq = off;        off = align_up(off + sizeof(float) * p.qpad);
     p.off_thr64 = off;       off = align_up(off + sizeof(uint64_t) * p.qpad);
     p.off_thrp = off;        off = align_up(off + sizeof(float) * p.qpad);
@@ -251,7 +253,7 @@ template <int QT> __global__ __launch_bounds__(256) void prep_kernel(const void 
         qmask_pad[t] = (qmask && t < Q) ? qmask[t] : 0ull;
     }
     if (t < regions) region_cnt[t] = 0;
-    if (t < 4) stats[t] = t == 2 ? sample_keys : t == 3 ? (uint64_t)grid : 0ull;
+    if (t < STAT_WORDS + STAT_PARTIALS) stats[t] = t == 2 ? sample_keys : t == 3 ? (uint64_t)grid : 0ull;
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row < qpad) {
@@ -293,17 +295,149 @@ __device__ inline void bitonic_sort_desc(uint64_t *buf, int n, int tid, int nthr
     __syncthreads();
 }
 
+// ------------------------------------------------------------------------------------------------
+// the k largest of n distinct nonzero 64-bit words in LDS, in descending order
+// ------------------------------------------------------------------------------------------------
+// A full sort is a chain of dependent LDS round trips (one per stage) and costs tens of microseconds for a
+// few thousand words.  Selection needs far fewer: a most-significant-digit radix search for the k-th
+// largest word (8-bit digits, starting at the highest bit in which the words differ at all; each pass is
+// one histogram with LDS atomics and one wavefront-wide suffix scan), then the survivors are compacted
+// and ordered by counting, for each, how many survivors are larger.  Zero words are padding: they are
+// never selected, and if fewer than k words are nonzero the result is zero-padded.
+struct SelectScratch {
+    uint64_t sel[KB_K_MAX];
+    uint32_t hist[256];
+    uint32_t ctl[16];      // 0 nonzero words, 1 selected, 2 digit found, 3 still needed, 4 words in that bin, 8..11 AND / OR
+};
+
+__device__ inline uint64_t shr64(uint64_t v, int s) { return s >= 64 ? 0ull : v >> s; }
+
+// buf[0..n) in, buf[0..k) out (the rest of buf is left as it was).  All threads of the workgroup call it.
+__device__ inline void select_topk_desc(uint64_t *buf, int n, int k, SelectScratch *sc, int tid, int nthreads)
+{
+    const int lane = tid & 63;
+    if (tid < 16) sc->ctl[tid] = (tid == 8 || tid == 9) ? 0xffffffffu : 0u;
+    __syncthreads();
+    {
+        uint32_t cnt = 0, alo = ~0u, ahi = ~0u, olo = 0u, ohi = 0u;
+        for (int i = tid; i < n; i += nthreads) {
+            const uint64_t e = buf[i];
+            if (e != 0) {
+                ++cnt;
+                alo &= (uint32_t)e;
+                ahi &= (uint32_t)(e >> 32);
+                olo |= (uint32_t)e;
+                ohi |= (uint32_t)(e >> 32);
+            }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            cnt += __shfl_xor(cnt, o, 64);
+            alo &= __shfl_xor(alo, o, 64);
+            ahi &= __shfl_xor(ahi, o, 64);
+            olo |= __shfl_xor(olo, o, 64);
+            ohi |= __shfl_xor(ohi, o, 64);
+        }
+        if (lane == 0) {
+            atomicAdd(&sc->ctl[0], cnt);
+            atomicAnd(&sc->ctl[8], alo);
+            atomicAnd(&sc->ctl[9], ahi);
+            atomicOr(&sc->ctl[10], olo);
+            atomicOr(&sc->ctl[11], ohi);
+        }
+    }
+    __syncthreads();
+    const int nz = (int)sc->ctl[0];
+    // selected words: nonzero and (word >> shift) >= pref
+    int shift = 0;
+    uint64_t pref = 1;
+    if (nz > k) {
+        const uint64_t all_and = ((uint64_t)sc->ctl[9] << 32) | sc->ctl[8], all_or = ((uint64_t)sc->ctl[11] << 32) | sc->ctl[10];
+        const uint64_t diff = all_and ^ all_or;              // nonzero: the words are distinct
+        int hi = diff ? 64 - __builtin_clzll(diff) : 0;      // bits [hi, 64) are decided and equal pref
+        pref = shr64(all_or, hi);
+        uint32_t need = (uint32_t)k;
+        for (int pass = 0; pass < 9 && hi > 0; ++pass) {
+            const int width = hi < 8 ? hi : 8, lo = hi - width;
+            for (int i = tid; i < 256; i += nthreads) sc->hist[i] = 0u;
+            __syncthreads();
+            for (int i = tid; i < n; i += nthreads) {
+                const uint64_t e = buf[i];
+                if (e != 0 && shr64(e, hi) == pref) atomicAdd(&sc->hist[(uint32_t)(e >> lo) & ((1u << width) - 1u)], 1u);
+            }
+            __syncthreads();
+            if (tid < 64) {
+                // suffix sums over the 256 bins, four bins per lane: the bin in which the need-th largest word lies
+                const uint32_t c0 = sc->hist[4 * lane], c1 = sc->hist[4 * lane + 1], c2 = sc->hist[4 * lane + 2], c3 = sc->hist[4 * lane + 3];
+                const uint32_t mine = c0 + c1 + c2 + c3;
+                uint32_t suffix = mine;
+#pragma unroll
+                for (int o = 1; o < 64; o <<= 1) {
+                    const uint32_t v = __shfl_down(suffix, o, 64);
+                    if (lane + o < 64) suffix += v;
+                }
+                uint32_t above = suffix - mine;
+                if (suffix >= need && above < need) {
+                    const uint32_t c[4] = {c0, c1, c2, c3};
+                    int bin = 0;
+                    uint32_t in_bin = 0;
+#pragma unroll
+                    for (int j = 3; j >= 0; --j) {
+                        if (in_bin == 0 && above + c[j] >= need) {
+                            bin = 4 * lane + j;
+                            in_bin = c[j];
+                        } else if (in_bin == 0) {
+                            above += c[j];
+                        }
+                    }
+                    sc->ctl[2] = (uint32_t)bin;
+                    sc->ctl[3] = need - above;
+                    sc->ctl[4] = in_bin;
+                }
+            }
+            __syncthreads();
+            pref = (width < 64 ? pref << width : 0ull) | sc->ctl[2];
+            need = sc->ctl[3];
+            hi = lo;
+            if (sc->ctl[4] == need) break;       // the whole bin belongs to the result
+        }
+        shift = hi;
+    }
+    for (int i = tid; i < n; i += nthreads) {
+        const uint64_t e = buf[i];
+        if (e != 0 && shr64(e, shift) >= pref) {
+            const uint32_t slot = atomicAdd(&sc->ctl[1], 1u);
+            if (slot < (uint32_t)KB_K_MAX) sc->sel[slot] = e;
+        }
+    }
+    __syncthreads();
+    const int m = (int)sc->ctl[1] < k ? (int)sc->ctl[1] : k;
+    for (int t = tid; t < k; t += nthreads) {
+        if (t < m) {
+            const uint64_t e = sc->sel[t];
+            int rank = 0;
+            for (int j = 0; j < m; ++j) rank += sc->sel[j] > e;
+            buf[rank] = e;
+        } else {
+            buf[t] = 0ull;
+        }
+    }
+    __syncthreads();
+}
+
 // k-th best group maximum of the sampling pass = a lower bound of the k-th best score (k distinct
 // entries reach it).  Also derives the conservative pre-filter on dot * inv_k used by the main pass:
 // whenever fp32((dot*inv_k) * inv_q) >= s_thr holds, dot*inv_k >= thrp holds (2^-20 relative slack
 // covers the three fp32 roundings involved).
-__global__ __launch_bounds__(1024) void threshold_kernel(const uint64_t *samp, int slots, int p2, int k, const float *invq, uint64_t *thr64, float *thrp)
+__global__ __launch_bounds__(1024) void threshold_kernel(const uint64_t *samp, int slots, int k, const float *invq, uint64_t *thr64, float *thrp)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     uint64_t *buf = reinterpret_cast<uint64_t *>(smem_raw);
     const int q = blockIdx.x, tid = threadIdx.x;
-    for (int i = tid; i < p2; i += (int)blockDim.x) buf[i] = i < slots ? samp[(size_t)q * slots + i] : 0ull;
-    bitonic_sort_desc(buf, p2, tid, (int)blockDim.x);
+    SelectScratch *sc = reinterpret_cast<SelectScratch *>(smem_raw + sizeof(uint64_t) * (slots > k ? slots : k));
+    for (int i = tid; i < slots; i += (int)blockDim.x) buf[i] = samp[(size_t)q * slots + i];
+    __syncthreads();
+    select_topk_desc(buf, slots, k, sc, tid, (int)blockDim.x);
     if (tid == 0) {
         const uint64_t t = k <= slots ? buf[k - 1] : 0ull;
         const float iq = invq[q];
@@ -335,7 +469,8 @@ __global__ __launch_bounds__(256) void bucket_kernel(const Record *regions, cons
         else
             flag[rec.query] = 1u;
     }
-    if (threadIdx.x == 0 && n) atomicAdd(reinterpret_cast<unsigned long long *>(stats), (unsigned long long)n);
+    if (threadIdx.x == 0 && n)
+        atomicAdd(reinterpret_cast<unsigned long long *>(stats + STAT_WORDS + blockIdx.x % STAT_PARTIALS), (unsigned long long)n);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -427,6 +562,7 @@ template <int KT> __global__ __launch_bounds__(256) void finalize_kernel(FinalAr
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     uint64_t *buf = reinterpret_cast<uint64_t *>(smem_raw);
     uint32_t *ctl = reinterpret_cast<uint32_t *>(smem_raw + sizeof(uint64_t) * a.cand_cap);
+    SelectScratch *sc = reinterpret_cast<SelectScratch *>(smem_raw + sizeof(uint64_t) * a.cand_cap + 16);
     const int q = blockIdx.x, tid = threadIdx.x;
     if (a.flag[q] != 0 && a.n_keys > 0) {
         exhaustive_query<KT>(a, q, buf, ctl);
@@ -442,14 +578,12 @@ template <int KT> __global__ __launch_bounds__(256) void finalize_kernel(FinalAr
             seg_off[sg] = n;
             n += seg_n[sg];
         }
-        int p2 = KB_K_MAX;
-        while (p2 < (int)n) p2 <<= 1;
-        for (int i = n + tid; i < p2; i += 256) buf[i] = 0ull;
 #pragma unroll
         for (int sg = 0; sg < CAND_SEGMENTS; ++sg)
             for (uint32_t i = tid; i < seg_n[sg]; i += 256)
                 buf[seg_off[sg] + i] = a.cand[(size_t)q * a.cand_cap + sg * seg_cap + i];
-        bitonic_sort_desc(buf, p2, tid, 256);
+        __syncthreads();
+        select_topk_desc(buf, (int)n, a.k, sc, tid, 256);
     }
     if (tid < a.k) {
         const uint64_t cw = tid < a.cand_cap ? buf[tid] : 0ull;
@@ -646,15 +780,16 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
             const int64_t smax = (int64_t)(kb->cu_count > 0 ? kb->cu_count : ASSUMED_CUS) * p.sample_wgpc;
             if (sgrid > smax) sgrid = smax;
             if (launch_scan(kb->dtype, p.sample_config, p.sample_family, true, (int)sgrid, a, s) != hipSuccess) return KB_ERR_DEVICE;
-            const int p2 = (int)pow2_ceil(p.sample_slots < 64 ? 64 : p.sample_slots);
+            const int thr_threads = p.sample_slots > 1024 ? 1024 : p.sample_slots > 512 ? 512 : 256;
+            const size_t thr_lds = sizeof(uint64_t) * (p.sample_slots > k ? p.sample_slots : k) + sizeof(SelectScratch);
             static bool thr_attr = false;
             if (!thr_attr) {
                 if (hipFuncSetAttribute(reinterpret_cast<const void *>(&threshold_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        MAX_SAMPLE_SLOTS * 8) != hipSuccess)
+                                        MAX_SAMPLE_SLOTS * 8 + sizeof(SelectScratch)) != hipSuccess)
                     return KB_ERR_DEVICE;
                 thr_attr = true;
             }
-            hipLaunchKernelGGL(threshold_kernel, dim3(Q), dim3(p2 >= 2048 ? 1024 : p2 >= 1024 ? 512 : 256), (size_t)p2 * 8, s, samp, p.sample_slots, p2, k, invq, thr64, thrp);
+            hipLaunchKernelGGL(threshold_kernel, dim3(Q), dim3(thr_threads), thr_lds, s, samp, p.sample_slots, k, invq, thr64, thrp);
             if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
         }
         a.n_tiles = ceil_div(kb->n, p.tk);
@@ -686,13 +821,13 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
     f.d = kb->d;
     f.k = k;
     f.cand_cap = p.cand_cap;
-    const size_t fin_lds = (size_t)p.cand_cap * 8 + 16;
+    const size_t fin_lds = (size_t)p.cand_cap * 8 + 16 + sizeof(SelectScratch);
     static bool fin_attr[3] = {false, false, false};
     const void *fin_fn = kb->dtype == KB_F32 ? reinterpret_cast<const void *>(&finalize_kernel<KB_F32>)
                        : kb->dtype == KB_BF16 ? reinterpret_cast<const void *>(&finalize_kernel<KB_BF16>)
                                               : reinterpret_cast<const void *>(&finalize_kernel<KB_FP8_E4M3>);
     if (!fin_attr[kb->dtype]) {
-        if (hipFuncSetAttribute(fin_fn, hipFuncAttributeMaxDynamicSharedMemorySize, MAX_CAND_CAP * 8 + 16) != hipSuccess) return KB_ERR_DEVICE;
+        if (hipFuncSetAttribute(fin_fn, hipFuncAttributeMaxDynamicSharedMemorySize, MAX_CAND_CAP * 8 + 16 + sizeof(SelectScratch)) != hipSuccess) return KB_ERR_DEVICE;
         fin_attr[kb->dtype] = true;
     }
     switch (kb->dtype) {
@@ -709,9 +844,10 @@ kb_status_t kb_query_counters(const kb_t *kb, const void *workspace_dev, int64_t
     if (!kb || !workspace_dev || !out) return KB_ERR_NULL;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (hipStreamSynchronize(s) != hipSuccess) return KB_ERR_DEVICE;
-    uint64_t host[4];
+    uint64_t host[STAT_WORDS + STAT_PARTIALS];
     if (hipMemcpy(host, workspace_dev, sizeof host, hipMemcpyDeviceToHost) != hipSuccess) return KB_ERR_DEVICE;
-    for (int i = 0; i < 4; ++i) out[i] = (int64_t)host[i];
+    for (int i = 0; i < STAT_WORDS; ++i) out[i] = (int64_t)host[i];
+    for (int i = 0; i < STAT_PARTIALS; ++i) out[0] += (int64_t)host[STAT_WORDS + i];
     return KB_OK;
 }
 
