@@ -29,3 +29,9 @@
 #define KB_SCAN_BIG_CONFIGS_BF16(XB) \
     XB(9, KB_BF16, 4, 4)             \
     XB(10, KB_BF16, 5, 3)
+
+// Software-pipelined configurations (kb_scan_sp.hpp): XS(id, key dtype, NSA, NSB); 256 x 256 tiles, 512 threads.
+#define KB_SCAN_SP_CONFIGS_BF16(XS) \
+    XS(12, KB_BF16, 5, 4)           \
+    XS(13, KB_BF16, 4, 4)           \
+    XS(14, KB_BF16, 4, 5)

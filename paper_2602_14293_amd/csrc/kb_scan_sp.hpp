@@ -1,0 +1,349 @@
+// The large-batch scan kernel, software-pipelined variant: tile and operand layout of kb_scan_pp.hpp (8
+// wavefronts, 256 key rows x 256 queries per work item), but a wavefront reads its operand fragments from
+// LDS *between its MFMAs* instead of in a phase of their own, and there is ONE workgroup barrier per
+// d-chunk (gfx950 only).
+//
+// A d-chunk (64 bytes of every key row) is two k-groups of 32 bytes.  Fragments live in two register
+// sets, X (k-group 0) and Y (k-group 1); while the MFMAs of one set run, the other set is refilled:
+//
+//   compute part of chunk g:   8 MFMAs on X = kg0(g)   with the 6 reads  Y <- kg1(g)    in between,
+//                              8 MFMAs on Y = kg1(g)   with the 6 reads  X <- kg0(g+1)  in between
+//   load part of chunk g:      epilogue of a finished item, then this wave's share of the direct-to-LDS
+//                              loads of chunk g + NS - 1 (NS = ring depth)
+//
+// Between two barriers every wave runs both parts, waves 0-3 compute first, waves 4-7 load first.  Each
+// SIMD hosts one wave of either kind, so its matrix core is fed by one wave while the other issues loads
+// (a direct-to-LDS load holds the issuing wave for tens of cycles) or runs an epilogue, and nothing but
+// the one barrier forces the two to move in step.  Iteration g reads chunks g and g+1 only, and its
+// loads overwrite the ring slot of chunk g-1, which nobody touches after barrier g.  A wave arrives at
+// barrier g+1 once its share of chunk g+2 has landed (NS-3 younger chunks still in flight).  Key chunks
+// come from HBM and get a ring of 5, query chunks come from L2 and get 4.
+//
+// LDS layout, swizzle and load pattern of a chunk are those of kb_scan_pp.hpp (64-byte rows, 16 rows per
+// load instruction: requests of 64 bytes are what the L2 serves best; 32-byte requests cost 1.6x the L2
+// requests and 1.25x the HBM traffic when measured).  To make room for the deeper ring, the per-query
+// side data has one LDS copy, reloaded in an item's second iteration (every epilogue of the previous item
+// is over by then).
+#pragma once
+#include "kb_scan.hpp"
+
+namespace kbi {
+
+template <int KT_, int NSA_, int NSB_> struct SPCfg {
+    static constexpr int KT = KT_, NSA = NSA_, NSB = NSB_;                 // ring depths in chunks: keys, queries
+    static constexpr int TK = 256, TQ = 256, THREADS = 512, NW = 8;
+    static constexpr int KEY_BYTES = KeyTraits<KT>::KEY_BYTES, QRY_BYTES = KeyTraits<KT>::QRY_BYTES;
+    static_assert(KEY_BYTES == QRY_BYTES, "keys and queries of one element width");
+    static constexpr int RBA = 64;                                         // bytes of a row per chunk
+    static constexpr int IB = 2, JB = TQ / 2 / 32;
+    static constexpr int A_BYTES = TK * RBA, B_BYTES = TQ * RBA;
+    static constexpr int LC = A_BYTES / 1024 / 4;                          // load instructions per loading wave per chunk
+    static constexpr int OFF_B = NSA * A_BYTES;
+    // side data of a key tile, two copies (item parity)
+    static constexpr int AUX_INVK = 0;                       // float  [TK]
+    static constexpr int AUX_TAG = AUX_INVK + TK * 4;        // uint64 [TK]
+    static constexpr int AUX_BYTES = AUX_TAG + TK * 8;
+    // side data of a query block, one copy
+    static constexpr int QAUX_THRP = 0;                      // float  [TQ]
+    static constexpr int QAUX_INVQ = QAUX_THRP + TQ * 4;     // float  [TQ]
+    static constexpr int QAUX_THR64 = QAUX_INVQ + TQ * 4;    // uint64 [TQ]
+    static constexpr int QAUX_QMASK = QAUX_THR64 + TQ * 8;   // uint64 [TQ]
+    static constexpr int QAUX_BYTES = QAUX_QMASK + TQ * 8;
+    static constexpr int OFF_AUX = OFF_B + NSB * B_BYTES;
+    static constexpr int OFF_QAUX = OFF_AUX + 2 * AUX_BYTES;
+    static constexpr int SMEM_BYTES = OFF_QAUX + QAUX_BYTES;
+    static constexpr int GROUPS_PER_TILE = 8;                // sampling groups: 4 row blocks x 2 lane halves
+    static constexpr int MIN_ROW_BYTES = RBA * ((NSA > NSB ? NSA : NSB) + 1);   // the side-data buffers alternate safely only then
+    static_assert(A_BYTES == B_BYTES && LC == 4, "both streams: four instructions per wave and chunk");
+    static_assert(NSA >= 4 && NSA <= 6 && NSB >= 4 && NSB <= 6, "ring depths the waits are written for");
+    static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget");
+};
+
+template <class C, bool SAMPLE>
+__global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
+{
+    constexpr int TK = C::TK, TQ = C::TQ, RBA = C::RBA, IB = C::IB, JB = C::JB, NW = C::NW, LC = C::LC;
+    static_assert(IB == 2 && JB == 4, "the interleaving below is written out for 2 x 4 blocks");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    typedef __attribute__((address_space(3))) void *lds_ptr;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave & 3, group = wave >> 2;
+    const int lrow = lane & 31, half = lane >> 5;
+    const bool filter = p.qmask != nullptr;
+
+    const int nqb = p.nqb;
+    const int64_t n_items = p.n_tiles * nqb;
+    const int my_items = (int64_t)blockIdx.x < n_items ? (int)((n_items - blockIdx.x + gridDim.x - 1) / gridDim.x) : 0;
+    const int NC = p.d * C::KEY_BYTES / RBA;
+    const int total = my_items * NC;
+    const uint32_t row_bytes = (uint32_t)p.d * C::KEY_BYTES;
+    const int step_tile = gridDim.x / nqb, step_qb = gridDim.x % nqb;
+
+    Record *my_region = p.regions + ((size_t)blockIdx.x * NW + wave) * p.region_cap;
+    uint32_t wave_cnt = 0;       // wave-uniform
+
+    // ---- the load stream of this wave: key chunks (role 0) or query chunks (role 1) -------------------
+    // Instruction j of a chunk covers rows [64j + 16 * ridx, +16), four 16-byte pieces each.
+    const int role = wave & 1, ridx = wave >> 1;
+    const int NS = role ? C::NSB : C::NSA;
+    const int D = NS - 1;                                   // chunk g+D is issued in iteration g
+    const int ld_row = (ridx * 64 + lane) / 4;
+    const uint32_t ld_piece = (uint32_t)((((ridx * 64 + lane) % 4) ^ swizzle<4>(ld_row)) * 16);
+    const unsigned char *src_base = role ? static_cast<const unsigned char *>(p.queries) : static_cast<const unsigned char *>(p.keys);
+    unsigned char *ring = smem + (role ? C::OFF_B : 0) + ridx * 1024;
+    int ld_pos = 0;                                         // chunks issued so far
+    int ld_tile = blockIdx.x / nqb, ld_qb = blockIdx.x % nqb;
+    int ld_c = 0, ld_stage = 0, ld_par = 0;
+    uint32_t off[LC];
+    size_t ld_base = 0;                                     // byte offset of the item's first row in the source
+    bool last_full = false;
+    auto ld_setup = [&]() {
+        const int last = role == 0 ? (int)(p.n_keys - (int64_t)ld_tile * TK < TK ? p.n_keys - (int64_t)ld_tile * TK - 1 : TK - 1)
+                                   : p.Q - 1 - ld_qb * TQ;
+#pragma unroll
+        for (int j = 0; j < LC; ++j) {
+            const int r = ld_row + j * 64;
+            off[j] = (uint32_t)(r < last ? r : last) * row_bytes + ld_piece;
+        }
+        ld_base = role == 0 ? (size_t)ld_tile * TK * row_bytes : (size_t)ld_qb * TQ * row_bytes;
+    };
+    // side data of a key tile: 4-byte loads with clamped rows from the caller's arrays
+    auto issue_tile_aux = [&]() {
+        unsigned char *aux = smem + C::OFF_AUX + ld_par * C::AUX_BYTES;
+        const int64_t row0 = (int64_t)ld_tile * TK;
+        if (wave < 4) {
+            int64_t r = row0 + wave * 64 + lane;
+            r = r < p.n_keys ? r : p.n_keys - 1;
+            __builtin_amdgcn_global_load_lds((const void *)(p.inv_norm + r), (lds_ptr)(aux + C::AUX_INVK + wave * 256), 4, 0, 0);
+        }
+        if (filter) {
+            // tags as dwords: wave w covers dwords [64w, 64w+64) = rows [32w, 32w+32)
+            int64_t r = row0 + wave * 32 + (lane >> 1);
+            r = r < p.n_keys ? r : p.n_keys - 1;
+            __builtin_amdgcn_global_load_lds((const void *)(reinterpret_cast<const uint32_t *>(p.tags + r) + (lane & 1)),
+                                             (lds_ptr)(aux + C::AUX_TAG + wave * 256), 4, 0, 0);
+        }
+    };
+    // side data of a query block: 16-byte loads from the library's padded per-query arrays, one array per wave
+    auto issue_query_aux = [&](int qb) {
+        unsigned char *aux = smem + C::OFF_QAUX;
+        const int q0 = qb * TQ;
+        if (wave == 0)
+            __builtin_amdgcn_global_load_lds((const void *)(p.invq + q0 + lane * 4), (lds_ptr)(aux + C::QAUX_INVQ), 16, 0, 0);
+        if (wave == 1 && !SAMPLE)
+            __builtin_amdgcn_global_load_lds((const void *)(p.thrp + q0 + lane * 4), (lds_ptr)(aux + C::QAUX_THRP), 16, 0, 0);
+        if ((wave == 2 || wave == 3) && !SAMPLE)
+            __builtin_amdgcn_global_load_lds((const void *)(p.thr64 + q0 + (wave - 2) * 128 + lane * 2),
+                                             (lds_ptr)(aux + C::QAUX_THR64 + (wave - 2) * 1024), 16, 0, 0);
+        if ((wave == 4 || wave == 5) && filter)
+            __builtin_amdgcn_global_load_lds((const void *)(p.qmask_pad + q0 + (wave - 4) * 128 + lane * 2),
+                                             (lds_ptr)(aux + C::QAUX_QMASK + (wave - 4) * 1024), 16, 0, 0);
+    };
+    // One load phase's issue: this wave's share of the chunk at the cursor, if any is left.
+    auto issue_round = [&]() {
+        last_full = ld_pos < total;
+        if (!last_full) return;
+        if (ld_c == 0) issue_tile_aux();
+        const unsigned char *g = src_base + ld_base + (size_t)ld_c * RBA;
+        unsigned char *dst = ring + ld_stage * C::A_BYTES;
+#pragma unroll
+        for (int j = 0; j < LC; ++j)
+            __builtin_amdgcn_global_load_lds((const void *)(g + off[j]), (lds_ptr)(dst + j * 4096), 16, 0, 0);
+        ++ld_pos;
+        ld_stage = ld_stage + 1 == NS ? 0 : ld_stage + 1;
+        if (++ld_c == NC) {
+            ld_c = 0;
+            ld_par ^= 1;
+            ld_tile += step_tile;
+            ld_qb += step_qb;
+            if (ld_qb >= nqb) {
+                ld_qb -= nqb;
+                ++ld_tile;
+            }
+            if (ld_pos < total) ld_setup();
+        }
+    };
+    // All but the youngest NS-3 chunks of this wave's stream have landed once at most LC * (NS-3) loads are
+    // outstanding (side-data loads only make the wait longer).  Once the stream has run dry, wait for everything.
+    auto wait_landed = [&]() {
+        if (!last_full) __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+        else if (NS == 4) __builtin_amdgcn_s_waitcnt(waitcnt_vm(LC * 1));
+        else if (NS == 5) __builtin_amdgcn_s_waitcnt(waitcnt_vm(LC * 2));
+        else if (NS == 6) __builtin_amdgcn_s_waitcnt(waitcnt_vm(LC * 3));
+        else __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+    };
+
+    // ---- fragment addresses ----------------------------------------------------------------------
+    const int rowA = wm * 64 + lrow;
+    const int rowB = group * (TQ / 2) + lrow;
+    const int fragA = rowA * RBA | ((half ^ swizzle<4>(rowA)) << 4);     // ^ (kg << 5), + ib * 32 * RBA
+    const int fragB = rowB * RBA | ((half ^ swizzle<4>(rowB)) << 4);     // ^ (kg << 5), + jb * 32 * RBA
+    auto read_a = [&](int stage, int kg, int ib) {
+        return *reinterpret_cast<const u32x4 *>(smem + stage * C::A_BYTES + ((fragA ^ (kg << 5)) + ib * 32 * RBA));
+    };
+    auto read_b = [&](int stage, int kg, int jb) {
+        return *reinterpret_cast<const u32x4 *>(smem + C::OFF_B + stage * C::B_BYTES + ((fragB ^ (kg << 5)) + jb * 32 * RBA));
+    };
+
+    f32x16 acc[IB][JB];
+#pragma unroll
+    for (int ib = 0; ib < IB; ++ib)
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[ib][jb][i] = 0.f;
+
+    auto epilogue = [&](int tile, int qb, int par) {
+        const unsigned char *aux = smem + C::OFF_AUX + par * C::AUX_BYTES, *qaux = smem + C::OFF_QAUX;
+        const EpiSide sd{reinterpret_cast<const float *>(aux + C::AUX_INVK), reinterpret_cast<const uint64_t *>(aux + C::AUX_TAG),
+                         reinterpret_cast<const float *>(qaux + C::QAUX_THRP), reinterpret_cast<const float *>(qaux + C::QAUX_INVQ),
+                         reinterpret_cast<const uint64_t *>(qaux + C::QAUX_THR64), reinterpret_cast<const uint64_t *>(qaux + C::QAUX_QMASK)};
+        const int64_t row0 = (int64_t)tile * TK;
+        if (SAMPLE)
+            sample_epilogue<IB, JB>(acc, sd, filter, wm * 64, rowB, half, row0, qb * TQ, p,
+                                    (int64_t)tile * C::GROUPS_PER_TILE + wm * 2 + half);
+        else
+            main_epilogue<IB, JB>(acc, sd, filter, wm * 64, rowB, half, row0, qb * TQ, p, my_region, wave_cnt);
+#pragma unroll
+        for (int ib = 0; ib < IB; ++ib)
+#pragma unroll
+            for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[ib][jb][i] = 0.f;
+    };
+
+    // ---- prologue: chunks 0 .. D-1 issued, chunks 0 and 1 landed, kg0 of chunk 0 read ----------------
+    if (total > 0) {
+        ld_setup();
+        issue_query_aux(blockIdx.x % nqb);
+    }
+    for (int s = 0; s < D; ++s) issue_round();
+    wait_landed();
+    __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
+    bare_barrier();                         // barrier 0
+    u32x4 xa[IB], xb[JB], ya[IB], yb[JB];
+#pragma unroll
+    for (int ib = 0; ib < IB; ++ib) xa[ib] = read_a(0, 0, ib);
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb) xb[jb] = read_b(0, 0, jb);
+    if (group == 1) issue_round();          // waves 4-7 run their load part ahead of the compute part
+
+    int tile = blockIdx.x / nqb, qb = blockIdx.x % nqb, par = 0;
+    int c = 0, stageA = 0, stageB = 0;
+    bool pending = false;                   // an item is complete and waits for its epilogue
+    int e_tile = 0, e_qb = 0, e_par = 0;
+
+#define KB_SP_MFMA(SA, SB, I, J) Mma<C::KT>::run(acc[I][J], SA[I], SB[J], SB[J]); __builtin_amdgcn_sched_barrier(0)
+    for (int g = 0; g < total; ++g) {
+        // Waves 0-3: compute(g), load(g), barrier.  Waves 4-7: [load(g) was done before the previous barrier's
+        // successor, see below] compute(g), barrier, load(g+1).  One code path, two barrier positions.
+        const int c_now = c, qb_now = qb;
+        {
+            const int nA = stageA + 1 == C::NSA ? 0 : stageA + 1, nB = stageB + 1 == C::NSB ? 0 : stageB + 1;
+            // past the last chunk the refill of X reads the current slot again (valid memory, values unused)
+            const int xA = g + 1 < total ? nA : stageA, xB = g + 1 < total ? nB : stageB;
+            __builtin_amdgcn_s_setprio(1);
+            // The reads sit behind the first three MFMAs of each half: the remaining five cover their latency, and the
+            // MFMA order lets the next half start on the fragments that were read first.
+            KB_SP_MFMA(xa, xb, 0, 0);
+            ya[0] = read_a(stageA, 1, 0);
+            yb[0] = read_b(stageB, 1, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            KB_SP_MFMA(xa, xb, 0, 1);
+            yb[1] = read_b(stageB, 1, 1);
+            ya[1] = read_a(stageA, 1, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            KB_SP_MFMA(xa, xb, 1, 0);
+            yb[2] = read_b(stageB, 1, 2);
+            yb[3] = read_b(stageB, 1, 3);
+            __builtin_amdgcn_sched_barrier(0);
+            KB_SP_MFMA(xa, xb, 1, 1);
+            KB_SP_MFMA(xa, xb, 0, 2);
+            KB_SP_MFMA(xa, xb, 1, 2);
+            KB_SP_MFMA(xa, xb, 0, 3);
+            KB_SP_MFMA(xa, xb, 1, 3);
+
+            KB_SP_MFMA(ya, yb, 0, 0);
+            xa[0] = read_a(xA, 0, 0);
+            xb[0] = read_b(xB, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            KB_SP_MFMA(ya, yb, 0, 1);
+            xb[1] = read_b(xB, 0, 1);
+            xa[1] = read_a(xA, 0, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            KB_SP_MFMA(ya, yb, 1, 0);
+            xb[2] = read_b(xB, 0, 2);
+            xb[3] = read_b(xB, 0, 3);
+            __builtin_amdgcn_sched_barrier(0);
+            KB_SP_MFMA(ya, yb, 1, 1);
+            KB_SP_MFMA(ya, yb, 0, 2);
+            KB_SP_MFMA(ya, yb, 1, 2);
+            KB_SP_MFMA(ya, yb, 0, 3);
+            KB_SP_MFMA(ya, yb, 1, 3);
+            __builtin_amdgcn_s_setprio(0);
+
+            stageA = nA;
+            stageB = nB;
+            if (++c == NC) {
+                pending = true;
+                e_tile = tile;
+                e_qb = qb;
+                e_par = par;
+                c = 0;
+                par ^= 1;
+                tile += step_tile;
+                qb += step_qb;
+                if (qb >= nqb) {
+                    qb -= nqb;
+                    ++tile;
+                }
+            }
+        }
+        if (group == 1) {
+            wait_landed();
+            __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
+            __builtin_amdgcn_sched_barrier(0);
+            bare_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // load part: of this iteration (waves 0-3) or of the next one (waves 4-7)
+        if (pending) {
+            epilogue(e_tile, e_qb, e_par);
+            pending = false;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (nqb > 1 && (group == 0 ? c_now == 1 : c == 1)) issue_query_aux(group == 0 ? qb_now : qb);
+        issue_round();
+        __builtin_amdgcn_sched_barrier(0);
+        if (group == 0) {
+            wait_landed();
+            __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
+            __builtin_amdgcn_sched_barrier(0);
+            bare_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+#undef KB_SP_MFMA
+
+    if (!SAMPLE && lane == 0) {
+        const uint32_t cap = (uint32_t)p.region_cap;
+        p.region_cnt[blockIdx.x * NW + wave] = wave_cnt < cap ? wave_cnt : cap;
+    }
+}
+
+template <class C> hipError_t launch_scan_sp_cfg(bool sample, int grid, const ScanArgs &a, hipStream_t s)
+{
+    static bool attr_done[2] = {false, false};
+    auto *fn = sample ? &kb_scan_sp_kernel<C, true> : &kb_scan_sp_kernel<C, false>;
+    if (!attr_done[sample]) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM_BYTES);
+        if (e != hipSuccess) return e;
+        attr_done[sample] = true;
+    }
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(C::THREADS), C::SMEM_BYTES, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace kbi

@@ -1,0 +1,18 @@
+// Software-pipelined scan kernel instantiations for bf16 keys.
+#include "kb_configs.hpp"
+#include "kb_scan_sp.hpp"
+
+namespace kbi {
+
+hipError_t launch_scan_sp_bf16(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s)
+{
+    switch (config) {
+#define XS(ID, KT, NSA, NSB) \
+    case ID: return launch_scan_sp_cfg<SPCfg<KT, NSA, NSB>>(sample, grid, a, s);
+        KB_SCAN_SP_CONFIGS_BF16(XS)
+#undef XS
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace kbi

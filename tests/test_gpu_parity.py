@@ -49,6 +49,15 @@ def test_filtered_bf16_reduced(T, seed):
     assert rep.queries == 256
 
 
+@pytest.mark.parametrize("config", [3, 4, 6, 7, 8, 9, 12, 13, 14])
+def test_every_large_batch_scan_kernel(T, config):
+    """Each scan kernel that handles 256-query blocks (tiled, ping-pong, register-tile, software-pipelined) gives
+    the same oracle-checked result; ragged last tile, 300 queries = two query blocks, masked."""
+    w = W.filtered(seed=7, N=20000 + 131, d=512, Q=300, k=32, centers=32)
+    rep, cnt, _ = T.run_and_check(w, label=f"scan config {config}", tuning={"scan_config": config})
+    assert rep.queries == 300 and cnt["exhaustive_queries"] == 0
+
+
 @pytest.mark.parametrize("seed", [0, 1])
 def test_sparse_filter_exercises_padding(T, seed):
     w = W.filtered(seed=seed, N=12000, d=256, Q=96, k=32, centers=16, p_tag=0.003, single_bit_qmask=True)
