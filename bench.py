@@ -43,6 +43,97 @@ def make_workload(name: str, seed: int, device):
     raise SystemExit(f"unknown workload {name}")
 
 
+def _median(xs):
+    xs = sorted(xs)
+    return xs[len(xs) // 2]
+
+
+def run_growing(args, torch, kbmod, W, dev):
+    """The growing knowledge base: 2^20 rows, then 64 rounds of (append 16384 rows, normalize, 128 masked
+    queries, k = 16).  A step is one round; append + normalize and the query are timed separately."""
+    N0, n_new, rounds, d, Q, k = 1 << 20, 16384, 64, 1024, 128, 16
+    keys0, tags0, centers = W.growing_base(seed=args.seed, device=dev)
+    kb = kbmod.KnowledgeBase(d, kbmod.KB_BF16, N0 + rounds * n_new, tagged=True)
+    kb.keys[:N0].copy_(keys0)
+    kb.tags[:N0].copy_(tags0)
+    del keys0, tags0
+    kb.append_in_place(N0)
+    kb.normalize()
+    for t in args.tune:
+        name, val = t.split("=")
+        kb.set_tuning(name, int(val))
+    out_i = torch.empty((Q, k), dtype=torch.int32, device=dev)
+    out_s = torch.empty((Q, k), dtype=torch.float32, device=dev)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    t_append, t_query = [], []
+    for r in range(rounds):
+        rows, tags, queries, qmask = W.growing_round(args.seed, r, n_new, d, Q, centers, device=dev)
+        if r == 0:      # untimed warm-up of the query path on the initial knowledge base
+            for _ in range(args.warmup):
+                kb.query(queries, k, qmask, out_i, out_s)
+        torch.cuda.synchronize()
+        ev[0].record()
+        kb.append(rows, tags=tags)
+        kb.normalize()
+        ev[1].record()
+        kb.query(queries, k, qmask, out_i, out_s)
+        ev[2].record()
+        torch.cuda.synchronize()
+        t_append.append(ev[0].elapsed_time(ev[1]))
+        t_query.append(ev[1].elapsed_time(ev[2]))
+    n_first, n_last = N0 + n_new, N0 + rounds * n_new
+    row_bytes = d * 2
+    half = rounds // 2
+    q_first, q_last = _median(t_query[:8]), _median(t_query[-8:])
+    print(json.dumps({
+        "metric": "KB top-k queries/sec + key-scan HBM GB/s (% of peak), N=1M d=1024 bf16",
+        "value": Q * rounds / (sum(t_query) * 1e-3), "unit": "queries/s", "n_gpus": 1, "steps": rounds, "warmup": args.warmup,
+        "ms_per_step": (sum(t_query) + sum(t_append)) / rounds, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "growing KB: 1048576 -> 2097152 rows in 64 rounds of +16384, d=1024 bf16, Q=128 masked queries, k=16",
+                   "seed": args.seed},
+        "append_normalize_ms": {"median": _median(t_append), "min": min(t_append), "max": max(t_append),
+                                "GBps_median": n_new * row_bytes / (_median(t_append) * 1e-3) / 1e9},
+        "query_ms": {"first_8_rounds_median": q_first, "last_8_rounds_median": q_last, "min": min(t_query), "max": max(t_query)},
+        "key_scan_GBps": {"first_8_rounds": n_first * row_bytes / (q_first * 1e-3) / 1e9,
+                          "last_8_rounds": n_last * row_bytes / (q_last * 1e-3) / 1e9},
+        "queries_per_s": {"first_8_rounds": Q / (q_first * 1e-3), "last_8_rounds": Q / (q_last * 1e-3)},
+        "counters_last_round": kb.counters(),
+    }))
+
+
+def run_q_sweep(args, torch, kbmod, W, dev):
+    """Query-batch sweep on the N = 2^20, d = 1024 bf16 knowledge base (masked, k = 32): where the path goes from
+    streaming-bound to matrix-core-bound."""
+    w = W.filtered(seed=args.seed, Q=512, device=dev)
+    kb = kbmod.KnowledgeBase(w.d, kbmod.KB_BF16, w.N, tagged=True)
+    kb.keys.copy_(w.keys)
+    kb.tags.copy_(w.tags)
+    kb.append_in_place(w.N)
+    kb.normalize()
+    key_bytes = w.N * w.d * 2
+    rows = []
+    for Q in (1, 8, 32, 64, 128, 256, 512):
+        queries, qmask = w.queries[:Q].contiguous(), w.qmask[:Q].contiguous()
+        out_i = torch.empty((Q, w.k), dtype=torch.int32, device=dev)
+        out_s = torch.empty((Q, w.k), dtype=torch.float32, device=dev)
+        for _ in range(args.warmup):
+            kb.query(queries, w.k, qmask, out_i, out_s)
+        torch.cuda.synchronize()
+        kb.profile_begin(args.steps)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            kb.query(queries, w.k, qmask, out_i, out_s)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        scan_ms, n = kb.profile_end()
+        scan_ms /= max(n, 1)
+        rows.append({"Q": Q, "ms_per_query_batch": ms, "queries_per_s": Q / (ms * 1e-3), "scan_kernel_ms": scan_ms,
+                     "scan_key_GBps": key_bytes / (scan_ms * 1e-3) / 1e9, "scan_TFLOPs": 2.0 * Q * w.N * w.d / (scan_ms * 1e-3) / 1e12})
+    print(json.dumps({"metric": "query-batch sweep, N=1048576 d=1024 bf16 masked k=32", "steps": args.steps, "warmup": args.warmup,
+                      "n_gpus": 1, "data": "synthetic", "sweep": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -56,6 +147,7 @@ def main():
                     help="also run one 1 GiB device-to-device elementwise copy (a dispatch of known traffic that "
                          "calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--tune", action="append", default=[], help="name=value performance knob (repeatable)")
+    ap.add_argument("--q-sweep", action="store_true", help="time query batches of 1..512 on the N=2^20 bf16 knowledge base instead")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU: the retrieval path is built and measured on a single MI355X "
@@ -73,6 +165,10 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    if args.q_sweep:
+        return run_q_sweep(args, torch, kbmod, W, dev)
+    if args.workload == "growing":
+        return run_growing(args, torch, kbmod, W, dev)
     w, desc = make_workload(args.workload, args.seed, dev)
     code = {torch.float32: kbmod.KB_F32, torch.bfloat16: kbmod.KB_BF16, torch.float8_e4m3fn: kbmod.KB_FP8_E4M3}[w.keys.dtype]
     kb = kbmod.KnowledgeBase(w.d, code, w.N, tagged=w.tags is not None)
@@ -139,7 +235,7 @@ def main():
         "key_scan_frac_of_hbm_peak": key_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "mfma_TFLOPs": flops / (ms_per_step * 1e-3) / 1e12,
         "counters": counters,
-        "roofline": {"bound": "hbm", "kernel": "kb_scan_kernel (main pass)", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "kernel": "scan kernel, main pass", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
                      "kernel_ms": scan_ms, "algorithmic_bytes": scan_bytes, "launches_timed": scan_calls},
     }

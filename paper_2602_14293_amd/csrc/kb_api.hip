@@ -59,12 +59,13 @@ bool scan_config_info(int key_dtype, int config, ConfigInfo *out)
     }
     KB_SCAN_BIG_CONFIGS_BF16(XB)
 #undef XB
-#define XS(ID, KT, NSA, NSB)                                                  \
+#define XS(ID, KT, TQ, NSA, NSB)                                              \
     if (key_dtype == KT && config == ID) {                                    \
-        *out = ConfigInfo{256, 256, 512, 8, 1, 64 * ((NSA > NSB ? NSA : NSB) + 1), 3}; \
+        *out = ConfigInfo{256, TQ, 512, 8, 1, 64 * ((NSA > NSB ? NSA : NSB) + 1), 3}; \
         return true;                                                          \
     }
     KB_SCAN_SP_CONFIGS_BF16(XS)
+    KB_SCAN_SP_CONFIGS_FP8(XS)
 #undef XS
     return false;
 }
@@ -72,6 +73,7 @@ bool scan_config_info(int key_dtype, int config, ConfigInfo *out)
 int scan_config_for(int key_dtype, int Q, int d)
 {
     if (key_dtype == KB_BF16 && Q > 128 && d * 2 >= 512) return 6;
+    if (key_dtype == KB_FP8_E4M3 && Q > 128 && d >= 256) return 4;
     return Q <= 32 ? 1 : Q <= 128 ? 2 : 3;
 }
 
@@ -609,7 +611,9 @@ hipError_t launch_scan(kb_dtype_t dt, int config, int family, bool sample, int g
 {
     if (family == 1) return dt == KB_BF16 ? launch_scan_pp_bf16(config, sample, grid, a, s) : hipErrorInvalidValue;
     if (family == 2) return dt == KB_BF16 ? launch_scan_big_bf16(config, sample, grid, a, s) : hipErrorInvalidValue;
-    if (family == 3) return dt == KB_BF16 ? launch_scan_sp_bf16(config, sample, grid, a, s) : hipErrorInvalidValue;
+    if (family == 3)
+        return dt == KB_BF16 ? launch_scan_sp_bf16(config, sample, grid, a, s)
+               : dt == KB_FP8_E4M3 ? launch_scan_sp_fp8(config, sample, grid, a, s) : hipErrorInvalidValue;
     switch (dt) {
     case KB_F32: return launch_scan_f32(config, sample, grid, a, s);
     case KB_BF16: return launch_scan_bf16(config, sample, grid, a, s);

@@ -30,8 +30,12 @@
     XB(9, KB_BF16, 4, 4)             \
     XB(10, KB_BF16, 5, 3)
 
-// Software-pipelined configurations (kb_scan_sp.hpp): XS(id, key dtype, NSA, NSB); 256 x 256 tiles, 512 threads.
+// Software-pipelined configurations (kb_scan_sp.hpp): XS(id, key dtype, TQ, NSA, NSB); 256-row tiles, 512 threads.
 #define KB_SCAN_SP_CONFIGS_BF16(XS) \
-    XS(12, KB_BF16, 5, 4)           \
-    XS(13, KB_BF16, 4, 4)           \
-    XS(14, KB_BF16, 4, 5)
+    XS(12, KB_BF16, 256, 5, 4)      \
+    XS(13, KB_BF16, 256, 4, 4)      \
+    XS(14, KB_BF16, 256, 4, 5)      \
+    XS(15, KB_BF16, 128, 5, 4)      \
+    XS(16, KB_BF16, 128, 6, 4)
+#define KB_SCAN_SP_CONFIGS_FP8(XS)  \
+    XS(4, KB_FP8_E4M3, 256, 3, 3)

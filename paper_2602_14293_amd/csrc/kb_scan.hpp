@@ -2,7 +2,7 @@
 // threshold filter fused into its epilogue (gfx950 only).
 //
 // Work decomposition.  One work item = (key tile of TK rows) x (query block of TQ queries) x all of d.
-// A persistent workgroup walks items blockIdx.x, blockIdx.x + gridDim.x, ... with the query block as
+// A persistent workgroup walks items v, v + gridDim.x, ... (v = item_lane(blockIdx.x)) with the query block as
 // the fastest index, so concurrently running workgroups share a key tile through L2 when Q > TQ.
 // The contraction runs as S^T = K * Q^T: key rows are the MFMA "A" operand (M dimension), queries the
 // "B" operand (N dimension).  In the 32x32 accumulator layout a lane then owns ONE query column and 16
@@ -132,6 +132,17 @@ struct ScanCfg {
 
 constexpr int waitcnt_lgkm0() { return 0xC07F; }   // lgkmcnt(0), nothing else
 
+// Workgroups are dealt to the eight XCDs round-robin by block index, and each XCD has an L2 of its own.  When a
+// key tile is scored against several query blocks (items that differ in the query block only are consecutive),
+// the workgroups of one XCD take consecutive items, so that a tile's re-reads meet in one L2.
+__device__ inline int item_lane(int block, int grid, int nqb)
+{
+    constexpr int XCDS = 8;
+    if (nqb == 1 || grid % XCDS != 0) return block;
+    return (block % XCDS) * (grid / XCDS) + block / XCDS;
+}
+
+
 // Workgroup barrier without the fence semantics of __syncthreads(): the fence would drain every
 // outstanding direct-to-LDS load (vmcnt(0)) and with it the prefetch pipeline.  Callers wait for exactly
 // the counters they need first.
@@ -165,10 +176,11 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
     uint64_t *aux_qmask = reinterpret_cast<uint64_t *>(smem + C::OFF_QMASK);
     float *aux_invq = reinterpret_cast<float *>(smem + C::OFF_INVQ);
 
-    // items: (tile, qb) with qb fastest; this workgroup takes items blockIdx.x + i * gridDim.x
+    // items: (tile, qb) with qb fastest
     const int nqb = p.nqb;
     const int64_t n_items = p.n_tiles * nqb;
-    const int my_items = (int64_t)blockIdx.x < n_items ? (int)((n_items - blockIdx.x + gridDim.x - 1) / gridDim.x) : 0;
+    const int vb = item_lane(blockIdx.x, gridDim.x, nqb);      // this workgroup takes items vb, vb + gridDim.x, ...
+    const int my_items = (int64_t)vb < n_items ? (int)((n_items - vb + gridDim.x - 1) / gridDim.x) : 0;
     const int NC = p.d * C::KEY_BYTES / RBA;          // chunks per row
     const int total = my_items * NC;
     const uint32_t key_row_bytes = (uint32_t)p.d * C::KEY_BYTES, qry_row_bytes = (uint32_t)p.d * C::QRY_BYTES;
@@ -182,7 +194,7 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
     const int ldA_row = (wave * 64 + lane) / C::PPRA, ldB_row = (wave * 64 + lane) / C::PPRB;
     const uint32_t ldA_piece = (uint32_t)((((wave * 64 + lane) % C::PPRA) ^ swizzle<C::PPRA>(ldA_row)) * 16);
     const uint32_t ldB_piece = (uint32_t)((((wave * 64 + lane) % C::PPRB) ^ swizzle<C::PPRB>(ldB_row)) * 16);
-    int ld_tile = blockIdx.x / nqb, ld_qb = blockIdx.x % nqb;
+    int ld_tile = vb / nqb, ld_qb = vb % nqb;
     int ld_c = 0, ld_stage = 0;
     uint32_t offA[LA], offB[LB];
     auto ld_setup = [&]() {
@@ -244,7 +256,7 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
     for (int s = 0; s < C::NSTAGE - 1; ++s)
         if (s < total) issue_next();
 
-    int tile = blockIdx.x / nqb, qb = blockIdx.x % nqb;
+    int tile = vb / nqb, qb = vb % nqb;
     int c = 0, stage = 0;
     // per-item side data, fetched into registers while the item's last chunks are computed
     float my_invk = 0.f, my_invq = 0.f;

@@ -79,7 +79,8 @@ __global__ __launch_bounds__(256, 1) void kb_scan_big_kernel(ScanArgs p)
 
     const int nqb = p.nqb;
     const int64_t n_items = p.n_tiles * nqb;
-    const int my_items = (int64_t)blockIdx.x < n_items ? (int)((n_items - blockIdx.x + gridDim.x - 1) / gridDim.x) : 0;
+    const int vb = item_lane(blockIdx.x, gridDim.x, nqb);      // this workgroup takes items vb, vb + gridDim.x, ...
+    const int my_items = (int64_t)vb < n_items ? (int)((n_items - vb + gridDim.x - 1) / gridDim.x) : 0;
     const int NC = p.d * C::KEY_BYTES / RBA;
     const int total = my_items * NC;
     const uint32_t key_row_bytes = (uint32_t)p.d * C::KEY_BYTES, qry_row_bytes = (uint32_t)p.d * C::QRY_BYTES;
@@ -96,7 +97,7 @@ __global__ __launch_bounds__(256, 1) void kb_scan_big_kernel(ScanArgs p)
                                    : (uint32_t)((((ridx * 64 + lane) % C::PPRA) ^ swizzle<C::PPRA>(ld_row)) * 16);
     constexpr int RSTEP = 2 * 64 / C::PPRA;          // rows between a loading wave's instructions (PPRA == PPRB)
     static_assert(C::PPRA == C::PPRB && RSTEP % 32 == 0, "the swizzle must not change between instructions");
-    int ld_tile = blockIdx.x / nqb, ld_qb = blockIdx.x % nqb;
+    int ld_tile = vb / nqb, ld_qb = vb % nqb;
     int ld_c = 0, ld_stage = 0, ld_par = 0, ld_chunk = 0;        // ld_chunk: index of the chunk the stream is at
     uint32_t off[8];
     auto ld_setup = [&]() {
@@ -273,7 +274,7 @@ __global__ __launch_bounds__(256, 1) void kb_scan_big_kernel(ScanArgs p)
         for (int r = 0; r < 8; ++r) read_frag(0, 0, 0, 0, r);
     }
 
-    int tile = blockIdx.x / nqb, qb = blockIdx.x % nqb, par = 0;
+    int tile = vb / nqb, qb = vb % nqb, par = 0;
     int c = 0, sA = 0, sB = 0;
 
     for (int g = 0; g < total; ++g) {

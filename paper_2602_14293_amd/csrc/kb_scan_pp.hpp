@@ -75,7 +75,8 @@ __global__ __launch_bounds__(512, 1) void kb_scan_pp_kernel(ScanArgs p)
 
     const int nqb = p.nqb;
     const int64_t n_items = p.n_tiles * nqb;
-    const int my_items = (int64_t)blockIdx.x < n_items ? (int)((n_items - blockIdx.x + gridDim.x - 1) / gridDim.x) : 0;
+    const int vb = item_lane(blockIdx.x, gridDim.x, nqb);      // this workgroup takes items vb, vb + gridDim.x, ...
+    const int my_items = (int64_t)vb < n_items ? (int)((n_items - vb + gridDim.x - 1) / gridDim.x) : 0;
     const int NC = p.d * C::KEY_BYTES / RBA;
     const int total = my_items * NC;
     const uint32_t key_row_bytes = (uint32_t)p.d * C::KEY_BYTES, qry_row_bytes = (uint32_t)p.d * C::QRY_BYTES;
@@ -89,7 +90,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_pp_kernel(ScanArgs p)
     const int ld_row = (ridx * 64 + lane) / (role ? C::PPRB : C::PPRA);
     const uint32_t ld_piece = role ? (uint32_t)((((ridx * 64 + lane) % C::PPRB) ^ swizzle<C::PPRB>(ld_row)) * 16)
                                    : (uint32_t)((((ridx * 64 + lane) % C::PPRA) ^ swizzle<C::PPRA>(ld_row)) * 16);
-    int ld_tile = blockIdx.x / nqb, ld_qb = blockIdx.x % nqb;
+    int ld_tile = vb / nqb, ld_qb = vb % nqb;
     int ld_c = 0, ld_stage = 0, ld_par = 0;
     constexpr int LMAX = LA > LB ? LA : LB;
     uint32_t off[LMAX];
@@ -248,7 +249,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_pp_kernel(ScanArgs p)
     bare_barrier();                         // barrier 0
     if (group == 1) bare_barrier();         // group 1 runs one barrier behind
 
-    int tile = blockIdx.x / nqb, qb = blockIdx.x % nqb, par = 0;
+    int tile = vb / nqb, qb = vb % nqb, par = 0;
     int c = 0, stageA = 0, stageB = 0;
     bool pending = false;                   // an item is complete and waits for its epilogue
     int e_tile = 0, e_qb = 0, e_par = 0;

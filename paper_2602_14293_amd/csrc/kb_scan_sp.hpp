@@ -29,15 +29,26 @@
 
 namespace kbi {
 
-template <int KT_, int NSA_, int NSB_> struct SPCfg {
-    static constexpr int KT = KT_, NSA = NSA_, NSB = NSB_;                 // ring depths in chunks: keys, queries
-    static constexpr int TK = 256, TQ = 256, THREADS = 512, NW = 8;
+// bytes 0-7 / 8-15 of a 16-byte run of e4m3 codes as eight bf16 values (exact: see e4m3_pair_to_bf16)
+__device__ inline u32x4 widen_e4m3_lo(u32x4 a)
+{
+    return u32x4{e4m3_pair_to_bf16(a.x, false), e4m3_pair_to_bf16(a.x, true), e4m3_pair_to_bf16(a.y, false), e4m3_pair_to_bf16(a.y, true)};
+}
+__device__ inline u32x4 widen_e4m3_hi(u32x4 a)
+{
+    return u32x4{e4m3_pair_to_bf16(a.z, false), e4m3_pair_to_bf16(a.z, true), e4m3_pair_to_bf16(a.w, false), e4m3_pair_to_bf16(a.w, true)};
+}
+
+template <int KT_, int TQ_, int NSA_, int NSB_> struct SPCfg {
+    static constexpr int KT = KT_, TQ = TQ_, NSA = NSA_, NSB = NSB_;       // query block; ring depths in chunks: keys, queries
+    static constexpr int TK = 256, THREADS = 512, NW = 8;
     static constexpr int KEY_BYTES = KeyTraits<KT>::KEY_BYTES, QRY_BYTES = KeyTraits<KT>::QRY_BYTES;
-    static_assert(KEY_BYTES == QRY_BYTES, "keys and queries of one element width");
-    static constexpr int RBA = 64;                                         // bytes of a row per chunk
+    static constexpr int BMUL = QRY_BYTES / KEY_BYTES;                     // 2 for fp8 keys with bf16 queries
+    static constexpr int RBA = 64, RBB = RBA * BMUL;                       // bytes of a key / query row per chunk
+    static constexpr int PPRB = RBB / 16;
     static constexpr int IB = 2, JB = TQ / 2 / 32;
-    static constexpr int A_BYTES = TK * RBA, B_BYTES = TQ * RBA;
-    static constexpr int LC = A_BYTES / 1024 / 4;                          // load instructions per loading wave per chunk
+    static constexpr int A_BYTES = TK * RBA, B_BYTES = TQ * RBB;
+    static constexpr int LCA = A_BYTES / 1024 / 4, LCB = B_BYTES / 1024 / 4;   // load instructions per loading wave per chunk
     static constexpr int OFF_B = NSA * A_BYTES;
     // side data of a key tile, two copies (item parity)
     static constexpr int AUX_INVK = 0;                       // float  [TK]
@@ -54,16 +65,18 @@ template <int KT_, int NSA_, int NSB_> struct SPCfg {
     static constexpr int SMEM_BYTES = OFF_QAUX + QAUX_BYTES;
     static constexpr int GROUPS_PER_TILE = 8;                // sampling groups: 4 row blocks x 2 lane halves
     static constexpr int MIN_ROW_BYTES = RBA * ((NSA > NSB ? NSA : NSB) + 1);   // the side-data buffers alternate safely only then
-    static_assert(A_BYTES == B_BYTES && LC == 4, "both streams: four instructions per wave and chunk");
-    static_assert(NSA >= 4 && NSA <= 6 && NSB >= 4 && NSB <= 6, "ring depths the waits are written for");
+    static_assert(TQ == 256 || TQ == 128, "query blocks of 256 or 128");
+    static_assert((KT == KB_BF16 && BMUL == 1) || (KT == KB_FP8_E4M3 && BMUL == 2 && TQ == 256), "key types the kernel is written for");
+    static_assert(NSA >= 3 && NSA <= 6 && NSB >= 3 && NSB <= 6, "ring depths the waits are written for");
     static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget");
 };
 
 template <class C, bool SAMPLE>
 __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
 {
-    constexpr int TK = C::TK, TQ = C::TQ, RBA = C::RBA, IB = C::IB, JB = C::JB, NW = C::NW, LC = C::LC;
-    static_assert(IB == 2 && JB == 4, "the interleaving below is written out for 2 x 4 blocks");
+    constexpr int TK = C::TK, TQ = C::TQ, RBA = C::RBA, RBB = C::RBB, IB = C::IB, JB = C::JB, NW = C::NW;
+    constexpr int LC = C::LCA > C::LCB ? C::LCA : C::LCB;
+    static_assert(IB == 2 && (JB == 4 || JB == 2), "the interleaving below is written out for 2 x 4 and 2 x 2 blocks");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     typedef __attribute__((address_space(3))) void *lds_ptr;
 
@@ -75,26 +88,30 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
 
     const int nqb = p.nqb;
     const int64_t n_items = p.n_tiles * nqb;
-    const int my_items = (int64_t)blockIdx.x < n_items ? (int)((n_items - blockIdx.x + gridDim.x - 1) / gridDim.x) : 0;
+    const int vb = item_lane(blockIdx.x, gridDim.x, nqb);      // this workgroup takes items vb, vb + gridDim.x, ...
+    const int my_items = (int64_t)vb < n_items ? (int)((n_items - vb + gridDim.x - 1) / gridDim.x) : 0;
     const int NC = p.d * C::KEY_BYTES / RBA;
     const int total = my_items * NC;
-    const uint32_t row_bytes = (uint32_t)p.d * C::KEY_BYTES;
+    const uint32_t key_row_bytes = (uint32_t)p.d * C::KEY_BYTES, qry_row_bytes = (uint32_t)p.d * C::QRY_BYTES;
     const int step_tile = gridDim.x / nqb, step_qb = gridDim.x % nqb;
 
     Record *my_region = p.regions + ((size_t)blockIdx.x * NW + wave) * p.region_cap;
     uint32_t wave_cnt = 0;       // wave-uniform
 
     // ---- the load stream of this wave: key chunks (role 0) or query chunks (role 1) -------------------
-    // Instruction j of a chunk covers rows [64j + 16 * ridx, +16), four 16-byte pieces each.
+    // Instruction j of a chunk covers 1 KiB of it: 16 rows of four 16-byte pieces (64-byte rows) or 8 rows of eight.
     const int role = wave & 1, ridx = wave >> 1;
     const int NS = role ? C::NSB : C::NSA;
     const int D = NS - 1;                                   // chunk g+D is issued in iteration g
-    const int ld_row = (ridx * 64 + lane) / 4;
-    const uint32_t ld_piece = (uint32_t)((((ridx * 64 + lane) % 4) ^ swizzle<4>(ld_row)) * 16);
+    const int LCr = role ? C::LCB : C::LCA;                 // this wave's load instructions per chunk
+    const int ppr = role ? C::PPRB : 4;                     // 16-byte pieces per row
+    const int ld_row = (ridx * 64 + lane) / ppr, ld_rstep = 256 / ppr;
+    const uint32_t ld_piece = (uint32_t)(((ridx * 64 + lane) % ppr) ^ (role && C::PPRB == 8 ? swizzle<8>(ld_row) : swizzle<4>(ld_row))) * 16;
+    const uint32_t row_bytes = role ? qry_row_bytes : key_row_bytes, chunk_bytes = role ? RBB : RBA;
     const unsigned char *src_base = role ? static_cast<const unsigned char *>(p.queries) : static_cast<const unsigned char *>(p.keys);
     unsigned char *ring = smem + (role ? C::OFF_B : 0) + ridx * 1024;
     int ld_pos = 0;                                         // chunks issued so far
-    int ld_tile = blockIdx.x / nqb, ld_qb = blockIdx.x % nqb;
+    int ld_tile = vb / nqb, ld_qb = vb % nqb;
     int ld_c = 0, ld_stage = 0, ld_par = 0;
     uint32_t off[LC];
     size_t ld_base = 0;                                     // byte offset of the item's first row in the source
@@ -104,7 +121,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
                                    : p.Q - 1 - ld_qb * TQ;
 #pragma unroll
         for (int j = 0; j < LC; ++j) {
-            const int r = ld_row + j * 64;
+            const int r = ld_row + j * ld_rstep;
             off[j] = (uint32_t)(r < last ? r : last) * row_bytes + ld_piece;
         }
         ld_base = role == 0 ? (size_t)ld_tile * TK * row_bytes : (size_t)ld_qb * TQ * row_bytes;
@@ -130,14 +147,15 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
     auto issue_query_aux = [&](int qb) {
         unsigned char *aux = smem + C::OFF_QAUX;
         const int q0 = qb * TQ;
-        if (wave == 0)
+        constexpr int L4 = TQ / 4, W8 = TQ * 8 / 1024;          // lanes that cover a float array; waves that cover a 64-bit array
+        if (wave == 0 && lane < L4)
             __builtin_amdgcn_global_load_lds((const void *)(p.invq + q0 + lane * 4), (lds_ptr)(aux + C::QAUX_INVQ), 16, 0, 0);
-        if (wave == 1 && !SAMPLE)
+        if (wave == 1 && !SAMPLE && lane < L4)
             __builtin_amdgcn_global_load_lds((const void *)(p.thrp + q0 + lane * 4), (lds_ptr)(aux + C::QAUX_THRP), 16, 0, 0);
-        if ((wave == 2 || wave == 3) && !SAMPLE)
+        if (wave >= 2 && wave < 2 + W8 && !SAMPLE)
             __builtin_amdgcn_global_load_lds((const void *)(p.thr64 + q0 + (wave - 2) * 128 + lane * 2),
                                              (lds_ptr)(aux + C::QAUX_THR64 + (wave - 2) * 1024), 16, 0, 0);
-        if ((wave == 4 || wave == 5) && filter)
+        if (wave >= 4 && wave < 4 + W8 && filter)
             __builtin_amdgcn_global_load_lds((const void *)(p.qmask_pad + q0 + (wave - 4) * 128 + lane * 2),
                                              (lds_ptr)(aux + C::QAUX_QMASK + (wave - 4) * 1024), 16, 0, 0);
     };
@@ -146,11 +164,11 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
         last_full = ld_pos < total;
         if (!last_full) return;
         if (ld_c == 0) issue_tile_aux();
-        const unsigned char *g = src_base + ld_base + (size_t)ld_c * RBA;
-        unsigned char *dst = ring + ld_stage * C::A_BYTES;
+        const unsigned char *g = src_base + ld_base + (size_t)ld_c * chunk_bytes;
+        unsigned char *dst = ring + ld_stage * (role ? C::B_BYTES : C::A_BYTES);
 #pragma unroll
         for (int j = 0; j < LC; ++j)
-            __builtin_amdgcn_global_load_lds((const void *)(g + off[j]), (lds_ptr)(dst + j * 4096), 16, 0, 0);
+            if (j < LCr) __builtin_amdgcn_global_load_lds((const void *)(g + off[j]), (lds_ptr)(dst + j * 4096), 16, 0, 0);
         ++ld_pos;
         ld_stage = ld_stage + 1 == NS ? 0 : ld_stage + 1;
         if (++ld_c == NC) {
@@ -165,13 +183,15 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
             if (ld_pos < total) ld_setup();
         }
     };
-    // All but the youngest NS-3 chunks of this wave's stream have landed once at most LC * (NS-3) loads are
+    // All but the youngest NS-3 chunks of this wave's stream have landed once at most LCr * (NS-3) loads are
     // outstanding (side-data loads only make the wait longer).  Once the stream has run dry, wait for everything.
     auto wait_landed = [&]() {
         if (!last_full) __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
-        else if (NS == 4) __builtin_amdgcn_s_waitcnt(waitcnt_vm(LC * 1));
-        else if (NS == 5) __builtin_amdgcn_s_waitcnt(waitcnt_vm(LC * 2));
-        else if (NS == 6) __builtin_amdgcn_s_waitcnt(waitcnt_vm(LC * 3));
+        else if (LCr * (NS - 3) == 2) __builtin_amdgcn_s_waitcnt(waitcnt_vm(2));
+        else if (LCr * (NS - 3) == 4) __builtin_amdgcn_s_waitcnt(waitcnt_vm(4));
+        else if (LCr * (NS - 3) == 6) __builtin_amdgcn_s_waitcnt(waitcnt_vm(6));
+        else if (LCr * (NS - 3) == 8) __builtin_amdgcn_s_waitcnt(waitcnt_vm(8));
+        else if (LCr * (NS - 3) == 12) __builtin_amdgcn_s_waitcnt(waitcnt_vm(12));
         else __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
     };
 
@@ -179,12 +199,15 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
     const int rowA = wm * 64 + lrow;
     const int rowB = group * (TQ / 2) + lrow;
     const int fragA = rowA * RBA | ((half ^ swizzle<4>(rowA)) << 4);     // ^ (kg << 5), + ib * 32 * RBA
-    const int fragB = rowB * RBA | ((half ^ swizzle<4>(rowB)) << 4);     // ^ (kg << 5), + jb * 32 * RBA
+    // query bytes that go with a lane's 16 key bytes: one piece (same element width) or two adjacent ones
+    const int fragB = C::BMUL == 1 ? (rowB * RBB | ((half ^ swizzle<4>(rowB)) << 4))
+                                   : (rowB * RBB | (((2 * half) ^ swizzle<8>(rowB)) << 4));
     auto read_a = [&](int stage, int kg, int ib) {
         return *reinterpret_cast<const u32x4 *>(smem + stage * C::A_BYTES + ((fragA ^ (kg << 5)) + ib * 32 * RBA));
     };
-    auto read_b = [&](int stage, int kg, int jb) {
-        return *reinterpret_cast<const u32x4 *>(smem + C::OFF_B + stage * C::B_BYTES + ((fragB ^ (kg << 5)) + jb * 32 * RBA));
+    auto read_b = [&](int stage, int kg, int jb, int second = 0) {
+        return *reinterpret_cast<const u32x4 *>(smem + C::OFF_B + stage * C::B_BYTES +
+                                                ((fragB ^ (kg * 32 * C::BMUL) ^ (second << 4)) + jb * 32 * RBB));
     };
 
     f32x16 acc[IB][JB];
@@ -217,25 +240,32 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
     // ---- prologue: chunks 0 .. D-1 issued, chunks 0 and 1 landed, kg0 of chunk 0 read ----------------
     if (total > 0) {
         ld_setup();
-        issue_query_aux(blockIdx.x % nqb);
+        issue_query_aux(vb % nqb);
     }
     for (int s = 0; s < D; ++s) issue_round();
     wait_landed();
     __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
     bare_barrier();                         // barrier 0
     u32x4 xa[IB], xb[JB], ya[IB], yb[JB];
+    u32x4 ra[IB];                               // fp8 keys: raw fragments of the k-group whose low half is in X
 #pragma unroll
-    for (int ib = 0; ib < IB; ++ib) xa[ib] = read_a(0, 0, ib);
+    for (int ib = 0; ib < IB; ++ib) {
+        ra[ib] = read_a(0, 0, ib);
+        xa[ib] = C::BMUL == 2 ? widen_e4m3_lo(ra[ib]) : ra[ib];
+    }
 #pragma unroll
     for (int jb = 0; jb < JB; ++jb) xb[jb] = read_b(0, 0, jb);
     if (group == 1) issue_round();          // waves 4-7 run their load part ahead of the compute part
 
-    int tile = blockIdx.x / nqb, qb = blockIdx.x % nqb, par = 0;
+    int tile = vb / nqb, qb = vb % nqb, par = 0;
     int c = 0, stageA = 0, stageB = 0;
     bool pending = false;                   // an item is complete and waits for its epilogue
     int e_tile = 0, e_qb = 0, e_par = 0;
 
-#define KB_SP_MFMA(SA, SB, I, J) Mma<C::KT>::run(acc[I][J], SA[I], SB[J], SB[J]); __builtin_amdgcn_sched_barrier(0)
+#define KB_SP_MFMA(SA, SB, I, J)                                                                                            \
+    acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, SA[I]), __builtin_bit_cast(bf16x8, SB[J]), \
+                                                        acc[I][J], 0, 0, 0);                                                  \
+    __builtin_amdgcn_sched_barrier(0)
     for (int g = 0; g < total; ++g) {
         // Waves 0-3: compute(g), load(g), barrier.  Waves 4-7: [load(g) was done before the previous barrier's
         // successor, see below] compute(g), barrier, load(g+1).  One code path, two barrier positions.
@@ -245,43 +275,102 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
             // past the last chunk the refill of X reads the current slot again (valid memory, values unused)
             const int xA = g + 1 < total ? nA : stageA, xB = g + 1 < total ? nB : stageB;
             __builtin_amdgcn_s_setprio(1);
+            if constexpr (C::BMUL == 2) {
+                // fp8 keys: the 16 key bytes a lane holds per k-group widen to two bf16 operands ("lo" = bytes 0-7,
+                // "hi" = bytes 8-15), each paired with its own 16-byte query piece.  A chunk is therefore four steps of
+                // eight MFMAs (kg0 lo, kg0 hi, kg1 lo, kg1 hi: the accumulation order of every other kernel); X serves
+                // the lo steps, Y the hi steps, and each is refilled while the other is in use.  ra holds the raw key
+                // fragments of the k-group whose lo half is in X.
+#define KB_SP_8MFMA(SA, SB, R0, R1, R2)                                             \
+    KB_SP_MFMA(SA, SB, 0, 0); R0; __builtin_amdgcn_sched_barrier(0);                \
+    KB_SP_MFMA(SA, SB, 0, 1); R1; __builtin_amdgcn_sched_barrier(0);                \
+    KB_SP_MFMA(SA, SB, 1, 0); R2; __builtin_amdgcn_sched_barrier(0);                \
+    KB_SP_MFMA(SA, SB, 1, 1); KB_SP_MFMA(SA, SB, 0, 2); KB_SP_MFMA(SA, SB, 1, 2);   \
+    KB_SP_MFMA(SA, SB, 0, 3); KB_SP_MFMA(SA, SB, 1, 3)
+                // kg0 lo; refill Y with kg0 hi
+                KB_SP_8MFMA(xa, xb, (yb[0] = read_b(stageB, 0, 0, 1), yb[1] = read_b(stageB, 0, 1, 1)),
+                            (yb[2] = read_b(stageB, 0, 2, 1), yb[3] = read_b(stageB, 0, 3, 1)),
+                            (ya[0] = widen_e4m3_hi(ra[0]), ya[1] = widen_e4m3_hi(ra[1])));
+                // kg0 hi; refill X with kg1 lo
+                KB_SP_8MFMA(ya, yb, (ra[0] = read_a(stageA, 1, 0), ra[1] = read_a(stageA, 1, 1)),
+                            (xb[0] = read_b(stageB, 1, 0), xb[1] = read_b(stageB, 1, 1)),
+                            (xb[2] = read_b(stageB, 1, 2), xb[3] = read_b(stageB, 1, 3)));
+                xa[0] = widen_e4m3_lo(ra[0]);
+                xa[1] = widen_e4m3_lo(ra[1]);
+                __builtin_amdgcn_sched_barrier(0);
+                // kg1 lo; refill Y with kg1 hi
+                KB_SP_8MFMA(xa, xb, (yb[0] = read_b(stageB, 1, 0, 1), yb[1] = read_b(stageB, 1, 1, 1)),
+                            (yb[2] = read_b(stageB, 1, 2, 1), yb[3] = read_b(stageB, 1, 3, 1)),
+                            (ya[0] = widen_e4m3_hi(ra[0]), ya[1] = widen_e4m3_hi(ra[1])));
+                // kg1 hi; refill X with kg0 lo of the next chunk
+                KB_SP_8MFMA(ya, yb, (ra[0] = read_a(xA, 0, 0), ra[1] = read_a(xA, 0, 1)),
+                            (xb[0] = read_b(xB, 0, 0), xb[1] = read_b(xB, 0, 1)),
+                            (xb[2] = read_b(xB, 0, 2), xb[3] = read_b(xB, 0, 3)));
+                xa[0] = widen_e4m3_lo(ra[0]);
+                xa[1] = widen_e4m3_lo(ra[1]);
+                __builtin_amdgcn_sched_barrier(0);
+#undef KB_SP_8MFMA
+            } else if constexpr (JB == 4) {
             // The reads sit behind the first three MFMAs of each half: the remaining five cover their latency, and the
-            // MFMA order lets the next half start on the fragments that were read first.
-            KB_SP_MFMA(xa, xb, 0, 0);
-            ya[0] = read_a(stageA, 1, 0);
-            yb[0] = read_b(stageB, 1, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            KB_SP_MFMA(xa, xb, 0, 1);
-            yb[1] = read_b(stageB, 1, 1);
-            ya[1] = read_a(stageA, 1, 1);
-            __builtin_amdgcn_sched_barrier(0);
-            KB_SP_MFMA(xa, xb, 1, 0);
-            yb[2] = read_b(stageB, 1, 2);
-            yb[3] = read_b(stageB, 1, 3);
-            __builtin_amdgcn_sched_barrier(0);
-            KB_SP_MFMA(xa, xb, 1, 1);
-            KB_SP_MFMA(xa, xb, 0, 2);
-            KB_SP_MFMA(xa, xb, 1, 2);
-            KB_SP_MFMA(xa, xb, 0, 3);
-            KB_SP_MFMA(xa, xb, 1, 3);
+                // MFMA order lets the next half start on the fragments that were read first.
+                KB_SP_MFMA(xa, xb, 0, 0);
+                ya[0] = read_a(stageA, 1, 0);
+                yb[0] = read_b(stageB, 1, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                KB_SP_MFMA(xa, xb, 0, 1);
+                yb[1] = read_b(stageB, 1, 1);
+                ya[1] = read_a(stageA, 1, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                KB_SP_MFMA(xa, xb, 1, 0);
+                yb[2] = read_b(stageB, 1, 2);
+                yb[3] = read_b(stageB, 1, 3);
+                __builtin_amdgcn_sched_barrier(0);
+                KB_SP_MFMA(xa, xb, 1, 1);
+                KB_SP_MFMA(xa, xb, 0, 2);
+                KB_SP_MFMA(xa, xb, 1, 2);
+                KB_SP_MFMA(xa, xb, 0, 3);
+                KB_SP_MFMA(xa, xb, 1, 3);
 
-            KB_SP_MFMA(ya, yb, 0, 0);
-            xa[0] = read_a(xA, 0, 0);
-            xb[0] = read_b(xB, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            KB_SP_MFMA(ya, yb, 0, 1);
-            xb[1] = read_b(xB, 0, 1);
-            xa[1] = read_a(xA, 0, 1);
-            __builtin_amdgcn_sched_barrier(0);
-            KB_SP_MFMA(ya, yb, 1, 0);
-            xb[2] = read_b(xB, 0, 2);
-            xb[3] = read_b(xB, 0, 3);
-            __builtin_amdgcn_sched_barrier(0);
-            KB_SP_MFMA(ya, yb, 1, 1);
-            KB_SP_MFMA(ya, yb, 0, 2);
-            KB_SP_MFMA(ya, yb, 1, 2);
-            KB_SP_MFMA(ya, yb, 0, 3);
-            KB_SP_MFMA(ya, yb, 1, 3);
+                KB_SP_MFMA(ya, yb, 0, 0);
+                xa[0] = read_a(xA, 0, 0);
+                xb[0] = read_b(xB, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                KB_SP_MFMA(ya, yb, 0, 1);
+                xb[1] = read_b(xB, 0, 1);
+                xa[1] = read_a(xA, 0, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                KB_SP_MFMA(ya, yb, 1, 0);
+                xb[2] = read_b(xB, 0, 2);
+                xb[3] = read_b(xB, 0, 3);
+                __builtin_amdgcn_sched_barrier(0);
+                KB_SP_MFMA(ya, yb, 1, 1);
+                KB_SP_MFMA(ya, yb, 0, 2);
+                KB_SP_MFMA(ya, yb, 1, 2);
+                KB_SP_MFMA(ya, yb, 0, 3);
+                KB_SP_MFMA(ya, yb, 1, 3);
+            } else {
+                KB_SP_MFMA(xa, xb, 0, 0);
+                ya[0] = read_a(stageA, 1, 0);
+                yb[0] = read_b(stageB, 1, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                KB_SP_MFMA(xa, xb, 0, 1);
+                yb[1] = read_b(stageB, 1, 1);
+                ya[1] = read_a(stageA, 1, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                KB_SP_MFMA(xa, xb, 1, 0);
+                KB_SP_MFMA(xa, xb, 1, 1);
+
+                KB_SP_MFMA(ya, yb, 0, 0);
+                xa[0] = read_a(xA, 0, 0);
+                xb[0] = read_b(xB, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                KB_SP_MFMA(ya, yb, 0, 1);
+                xb[1] = read_b(xB, 0, 1);
+                xa[1] = read_a(xA, 0, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                KB_SP_MFMA(ya, yb, 1, 0);
+                KB_SP_MFMA(ya, yb, 1, 1);
+            }
             __builtin_amdgcn_s_setprio(0);
 
             stageA = nA;

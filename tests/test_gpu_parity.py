@@ -49,7 +49,7 @@ def test_filtered_bf16_reduced(T, seed):
     assert rep.queries == 256
 
 
-@pytest.mark.parametrize("config", [3, 4, 6, 7, 8, 9, 12, 13, 14])
+@pytest.mark.parametrize("config", [3, 4, 6, 7, 8, 9, 12, 13, 14, 15, 16])
 def test_every_large_batch_scan_kernel(T, config):
     """Each scan kernel that handles 256-query blocks (tiled, ping-pong, register-tile, software-pipelined) gives
     the same oracle-checked result; ragged last tile, 300 queries = two query blocks, masked."""
@@ -71,7 +71,14 @@ def test_compressed_fp8_reduced(T, seed):
     T.run_and_check(w, label=f"compressed seed {seed}")
 
 
-@pytest.mark.parametrize("N,d,Q,k", [(3000, 256, 33, 20), (130, 64, 1, 1), (5000, 128, 260, 7)])
+@pytest.mark.parametrize("config", [3, 4])
+def test_every_large_batch_fp8_scan_kernel(T, config):
+    w = W.compressed(seed=11, N=17000 + 77, d=512, Q=300, k=64, centers=32)
+    rep, cnt, _ = T.run_and_check(w, label=f"fp8 scan config {config}", tuning={"scan_config": config})
+    assert rep.queries == 300 and cnt["exhaustive_queries"] == 0
+
+
+@pytest.mark.parametrize("N,d,Q,k", [(3000, 256, 33, 20), (130, 64, 1, 1), (5000, 128, 260, 7), (9000, 256, 260, 16)])
 def test_fp8_shapes(T, N, d, Q, k):
     w = W.compressed(seed=N, N=N, d=d, Q=Q, k=k, centers=8)
     T.run_and_check(w, label=f"fp8 N={N} d={d} Q={Q} k={k}")
