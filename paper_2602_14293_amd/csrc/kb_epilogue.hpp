@@ -26,10 +26,12 @@ __device__ inline float select16(const f32x16 &a, int i)
 // Main pass.  Per block: a bound test (largest dot times largest 1/|k| of the lane's 16 rows against the
 // query's pre-filter) costs one max-reduction and decides whether any lane has to look closer; lanes that
 // do build the 16-bit mask of elements passing the exact pre-filter (sign bit of fma(dot, inv_k, -thrp),
-// collected with one v_alignbit each) and walk its set bits: final score, candidate word, threshold word,
-// tag predicate, append to the wave's private record region (no atomics: slot = the wave's running
-// count + the lane's rank among the appending lanes).  Nothing below is unrolled over elements except the
-// mask, so the code stays small.
+// collected with one v_alignbit each).  Survivors are rare, so the wave then walks them with a
+// wave-uniform element index: it takes the mask of one lane that has work (v_readlane), and for each of
+// its set bits every lane with that bit handles that element: final score, candidate word, threshold
+// word, tag predicate, append to the wave's private record region (no atomics: slot = the wave's running
+// count + the lane's rank among the appending lanes).  A uniform index turns the element selection into
+// an indexed register read instead of a 16-way select per lane.
 struct EpiRows {               // 1/|k| of the 16 key rows a lane holds in one 32-row block
     float ik[16];
     float ikmax;
@@ -71,39 +73,45 @@ __device__ inline void main_block(const f32x16 &a, const EpiRows &rw, float tp, 
             fail = __builtin_amdgcn_alignbit(fail, as_u32(__builtin_fmaf(a[i], rw.ik[i], -tp)), 31);
     }
     uint32_t pass = maybe ? (~fail & 0xffffu) : 0u;     // element i sits at bit 15 - i
-    if (__builtin_amdgcn_ballot_w64(pass != 0) == 0) return;
+    uint64_t lanes = __builtin_amdgcn_ballot_w64(pass != 0);
+    if (lanes == 0) return;
     const float iq = sd.invq[ql];
     const uint64_t t64 = sd.thr64[ql];
     const uint64_t qm = filter ? sd.qmask[ql] : 0ull;
-    // every lane runs the loop body (lanes without work compute on element 15 and discard it), so the
-    // wave-wide ballots below sit in uniform control flow
-    while (__builtin_amdgcn_ballot_w64(pass != 0) != 0) {
-        const bool has = pass != 0;
-        const int b = has ? 31 - __builtin_clz(pass) : 0;
-        pass &= ~(1u << b);
-        const int i = 15 - b;
-        const int rl = rw.rl0 + 8 * (i >> 2) + (i & 3);
-        const int64_t row = row0 + rl;
-        const float s = final_score(select16(a, i), sd.invk[rl], iq);
-        const uint64_t cw = pack_candidate(s, (uint32_t)row);
-        bool ok = has && row < p.n_keys && cw >= t64;
-        if (filter) ok = ok && (sd.tag[rl] & qm) != 0;
-        // slot in the wave's own record region: running count + rank among the lanes that append
-        const uint64_t okm = __builtin_amdgcn_ballot_w64(ok);
-        if (ok) {
-            const uint32_t pos = wave_cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(okm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)okm, 0u));
-            if (pos < (uint32_t)p.region_cap) {
-                Record rec;
-                rec.cand = cw;
-                rec.query = (uint32_t)(q0 + ql);
-                rec.pad = 0;
-                region[pos] = rec;
-            } else {
-                p.flag[q0 + ql] = 1u;
+    do {
+        // the elements one of the lanes wants looked at; every lane that wants any of them joins in
+        uint32_t m = (uint32_t)__builtin_amdgcn_readlane((int)pass, __builtin_ctzll(lanes));
+        const uint32_t mine = pass & m;
+        pass &= ~m;
+        do {
+            const int b = 31 - __builtin_clz(m);
+            m &= ~(1u << b);
+            const int i = 15 - b;                               // wave-uniform
+            const bool has = (mine >> b) & 1u;
+            const int rl = rw.rl0 + 8 * (i >> 2) + (i & 3);
+            const int64_t row = row0 + rl;
+            const float s = final_score(a[i], sd.invk[rl], iq);
+            const uint64_t cw = pack_candidate(s, (uint32_t)row);
+            bool ok = has && row < p.n_keys && cw >= t64;
+            if (filter) ok = ok && (sd.tag[rl] & qm) != 0;
+            // slot in the wave's own record region: running count + rank among the lanes that append
+            const uint64_t okm = __builtin_amdgcn_ballot_w64(ok);
+            if (ok) {
+                const uint32_t pos = wave_cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(okm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)okm, 0u));
+                if (pos < (uint32_t)p.region_cap) {
+                    Record rec;
+                    rec.cand = cw;
+                    rec.query = (uint32_t)(q0 + ql);
+                    rec.pad = 0;
+                    region[pos] = rec;
+                } else {
+                    p.flag[q0 + ql] = 1u;
+                }
             }
-        }
-        wave_cnt += (uint32_t)__builtin_popcountll(okm);
-    }
+            wave_cnt += (uint32_t)__builtin_popcountll(okm);
+        } while (m != 0);
+        lanes = __builtin_amdgcn_ballot_w64(pass != 0);
+    } while (lanes != 0);
 }
 
 template <int IB, int JB>
