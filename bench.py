@@ -23,6 +23,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+# HBM bytes per launch of the main-pass scan kernel on the default workload with the default kernel choice, from
+# rocprofv3 --pmc FETCH_SIZE (x 2.0: what the same counter under-reads on a copy of known size) and WRITE_SIZE (x 1.0).
+# Applies to that workload and kernel only.
+SCAN_TRAFFIC_BYTES_FILTERED = 1173825 * 1024 * 2.0 + 2620 * 1024 * 1.0
 
 
 def make_workload(name: str, seed: int, device):
@@ -236,7 +240,8 @@ def main():
         "mfma_TFLOPs": flops / (ms_per_step * 1e-3) / 1e12,
         "counters": counters,
         "roofline": {"bound": "hbm", "kernel": "scan kernel, main pass", "achieved": achieved, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": SCAN_TRAFFIC_BYTES_FILTERED if (args.workload == "filtered" and not args.tune) else None,
                      "kernel_ms": scan_ms, "algorithmic_bytes": scan_bytes, "launches_timed": scan_calls},
     }
 

@@ -6,7 +6,7 @@
 //                  threshold_kernel           (k-th best group maximum per query)
 //                  scan kernel, main pass     (kb_scan.hpp)
 //                  bucket_kernel              (records of all workgroups -> per-query lists)
-//                  finalize_kernel            (bitonic sort of each query's list, top k; or the
+//                  finalize_kernel            (top k of each query's list by radix selection; or the
 //                                              exhaustive per-query scan when a list overflowed)
 #include <stdlib.h>
 #include <string.h>
@@ -466,26 +466,22 @@ __global__ __launch_bounds__(1024) void threshold_kernel(const uint64_t *samp, i
 __global__ __launch_bounds__(256) void bucket_kernel(const Record *regions, const uint32_t *region_cnt, int region_cap, uint64_t *cand, int cand_cap,
                                                       uint32_t *cnt, uint32_t *flag, uint64_t *stats, int waves_per_wg)
 {
-    // one workgroup per scan workgroup; all its wavefronts' regions feed one segment (a query column is only
-    // seen by some of the waves)
-    const uint32_t seg = blockIdx.x % CAND_SEGMENTS, seg_cap = (uint32_t)cand_cap / CAND_SEGMENTS;
-    uint32_t total = 0;
-    for (int w = 0; w < waves_per_wg; ++w) {
-        const int region = blockIdx.x * waves_per_wg + w;
-        const uint32_t n = region_cnt[region];
-        const Record *r = regions + (size_t)region * region_cap;
-        for (uint32_t i = threadIdx.x; i < n; i += 256) {
-            const Record rec = r[i];
-            const uint32_t slot = atomicAdd(&cnt[rec.query * CAND_SEGMENTS + seg], 1u);
-            if (slot < seg_cap)
-                cand[(size_t)rec.query * cand_cap + seg * seg_cap + slot] = rec.cand;
-            else
-                flag[rec.query] = 1u;
-        }
-        total += n;
+    // one workgroup per wavefront region (many small workgroups hide the latency of the slot-claiming atomics
+    // better than few large ones)
+    const uint32_t n = region_cnt[blockIdx.x];
+    const Record *r = regions + (size_t)blockIdx.x * region_cap;
+    // all regions of a scan workgroup feed one segment (a query column is only seen by some of its waves)
+    const uint32_t seg = (blockIdx.x / waves_per_wg) % CAND_SEGMENTS, seg_cap = (uint32_t)cand_cap / CAND_SEGMENTS;
+    for (uint32_t i = threadIdx.x; i < n; i += 256) {
+        const Record rec = r[i];
+        const uint32_t slot = atomicAdd(&cnt[rec.query * CAND_SEGMENTS + seg], 1u);
+        if (slot < seg_cap)
+            cand[(size_t)rec.query * cand_cap + seg * seg_cap + slot] = rec.cand;
+        else
+            flag[rec.query] = 1u;
     }
-    if (threadIdx.x == 0 && total)
-        atomicAdd(reinterpret_cast<unsigned long long *>(stats + STAT_WORDS + blockIdx.x % STAT_PARTIALS), (unsigned long long)total);
+    if (threadIdx.x == 0 && n)
+        atomicAdd(reinterpret_cast<unsigned long long *>(stats + STAT_WORDS + blockIdx.x % STAT_PARTIALS), (unsigned long long)n);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -818,7 +814,7 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
             if (hipEventRecord(kb->prof_events[2 * kb->prof_used + 1], s) != hipSuccess) return KB_ERR_DEVICE;
             ++kb->prof_used;
         }
-        hipLaunchKernelGGL(bucket_kernel, dim3(p.grid), dim3(256), 0, s, regions, region_cnt, p.region_cap, cand, p.cand_cap, cnt, flag, stats, p.regions / p.grid);
+        hipLaunchKernelGGL(bucket_kernel, dim3(p.regions), dim3(256), 0, s, regions, region_cnt, p.region_cap, cand, p.cand_cap, cnt, flag, stats, p.regions / p.grid);
         if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
     }
 
