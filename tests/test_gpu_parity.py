@@ -210,3 +210,37 @@ def test_empty_kb_returns_padding(T):
     torch.cuda.synchronize()
     assert (gi.cpu().numpy() == -1).all() and np.isneginf(gs.cpu().numpy()).all()
     kb.close()
+
+
+def test_query_replays_from_a_captured_graph(T):
+    """kb_query allocates nothing, never synchronises and records no memset, so it can be captured in a HIP graph.
+    Every replay (with eager work and synchronisations in between, and with new query contents in the captured
+    buffers) must give the bits of an eager call on the same inputs."""
+    w = W.filtered(seed=5, N=30000 + 19, d=512, Q=200, k=24, centers=32)
+    w2 = W.filtered(seed=6, N=30000 + 19, d=512, Q=200, k=24, centers=32)
+    kb = T.build_kb(w)
+    dev = kb.keys.device
+    queries, qmask = w.queries.to(dev).contiguous(), w.qmask.to(dev).contiguous()
+    out_i = torch.empty((w.Q, w.k), dtype=torch.int32, device=dev)
+    out_s = torch.empty((w.Q, w.k), dtype=torch.float32, device=dev)
+    kb.query(queries, w.k, qmask, out_i, out_s)             # warm-up: one-time kernel attributes are set outside the capture
+    torch.cuda.synchronize()
+    graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+    with torch.cuda.graph(graph, stream=side):
+        kb.query(queries, w.k, qmask, out_i, out_s)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        src = w if rep % 2 == 0 else w2
+        queries.copy_(src.queries.to(dev))
+        qmask.copy_(src.qmask.to(dev))
+        ref_i, ref_s = kb.query(queries, w.k, qmask)        # eager, into fresh outputs
+        torch.cuda.synchronize()
+        out_i.fill_(-7)
+        out_s.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_i, ref_i) and torch.equal(out_s, ref_s), f"replay {rep} differs from the eager call"
+    mixed = W.Workload("graph replay", w.keys, w2.queries, w.k, tags=w.tags, qmask=w2.qmask)     # the last replay's inputs
+    T.check_against_oracle(mixed, out_i.cpu().numpy(), out_s.cpu().numpy(), label="graph replay")
+    kb.close()
