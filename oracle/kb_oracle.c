@@ -20,6 +20,22 @@
  *
  * Everything is fp64, plain loops, full sort.  No blocking, no partial
  * selection, no shared code with the GPU path.
+ *
+ * Weighted random selection (second half of this file).  The Optimization
+ * Selector "performs a random weighted selection based on predicted
+ * performance gain ... to select the top-k" (Section 3, same paragraph).  The
+ * paper gives no formula; the model used here: entry i carries a predicted
+ * gain g_i > 0, query r draws k entries WITHOUT replacement from its candidate
+ * set with probability proportional to w_ri = g_i * exp(score_ri / T), T > 0 a
+ * temperature.  By the Gumbel-top-k identity that is the k largest of
+ *     key_ri = score_ri / T + ln g_i + G_ri,    G_ri iid standard Gumbel,
+ * and G_ri comes from the counter-based generator Philox4x32-10 (Salmon,
+ * Moraes, Dror, Shaw, SC'11) keyed by the caller's seed with (entry, query) as
+ * the counter, so the draw is a pure function of (seed, r, i).  Pins: the
+ * generator's published known-answer vectors, moments of the variates, the
+ * closed-form inclusion probabilities for k = 1 and ordered pairs for k = 2,
+ * the T -> 0 limit (plain top-k), determinism.  Fidelity of this model to the
+ * paper is unpinned for the same reason as above.
  */
 #include <math.h>
 #include <stdint.h>
@@ -181,6 +197,8 @@ int64_t oracle_select(const double *scores, int64_t N, const uint64_t *tags, int
     for (int64_t i = 0; i < N; ++i) {
         if (use_mask && (qmask & tags[i]) == 0)
             continue;
+        if (scores[i] == -INFINITY)     /* only selection keys of zero-gain entries: never candidates */
+            continue;
         c[n].score = scores[i];
         c[n].index = i;
         ++n;
@@ -233,6 +251,78 @@ int oracle_query(const void *keys, int key_dtype, const float *row_scale, const 
     if (!scores_out)
         free(scores);
     return rc ? rc : (bad ? 2 : 0);
+}
+
+/* ------------------------------------------------------------------------
+ * Weighted random selection
+ * ------------------------------------------------------------------------ */
+
+/* Philox4x32 with 10 rounds: counter 4 x 32 bit, key 2 x 32 bit.  One round
+ * multiplies counter words 0 and 2 by two odd constants, keeps both halves of
+ * the 64-bit products and mixes in the other two words and the key; the key
+ * is bumped by two Weyl constants between rounds. */
+void oracle_philox4x32_10(const uint32_t ctr_in[4], const uint32_t key_in[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr_in[0], c1 = ctr_in[1], c2 = ctr_in[2], c3 = ctr_in[3];
+    uint32_t k0 = key_in[0], k1 = key_in[1];
+    for (int round = 0; round < 10; ++round) {
+        if (round > 0) {
+            k0 += 0x9E3779B9u;
+            k1 += 0xBB67AE85u;
+        }
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0;
+        c1 = n1;
+        c2 = n2;
+        c3 = n3;
+    }
+    out[0] = c0;
+    out[1] = c1;
+    out[2] = c2;
+    out[3] = c3;
+}
+
+/* The uniform variate of pair (query, entry): generator call with counter
+ * (entry / 4, query, 0, 0) and the seed as key; entry % 4 picks one of the
+ * four output words; its upper 24 bits b give U = (b + 1/2) / 2^24, which is
+ * in (0, 1) and exactly representable in binary32 and binary64. */
+double oracle_uniform(uint64_t seed, uint32_t query, uint64_t entry)
+{
+    uint32_t ctr[4] = {(uint32_t)(entry >> 2), query, 0u, 0u};
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t w[4];
+    oracle_philox4x32_10(ctr, key, w);
+    return ((double)(w[entry & 3] >> 8) + 0.5) / 16777216.0;
+}
+
+/* Standard Gumbel variate by inversion: G = -ln(-ln U). */
+double oracle_gumbel(uint64_t seed, uint32_t query, uint64_t entry)
+{
+    return -log(-log(oracle_uniform(seed, query, entry)));
+}
+
+/* Selection keys of Q queries (global query numbers first_query, ...) from
+ * their [Q, N] score matrix: key = score / T + ln(gain) + Gumbel; an entry
+ * with gain <= 0 gets -infinity (it can never be drawn).  Returns 0 on success. */
+int oracle_selection_keys(const double *scores, int64_t Q, int64_t N, const float *gain, double temperature,
+                          uint64_t seed, int64_t first_query, double *keys_out)
+{
+    if (!scores || !gain || !keys_out || !(temperature > 0.0) || Q < 0 || N < 0)
+        return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < Q; ++r)
+        for (int64_t i = 0; i < N; ++i) {
+            const double g = (double)gain[i];
+            keys_out[r * N + i] = g > 0.0 ? scores[r * N + i] / temperature + log(g) +
+                                                oracle_gumbel(seed, (uint32_t)(first_query + r), (uint64_t)i)
+                                          : -INFINITY;
+        }
+    return 0;
 }
 
 /* Threads the parallel regions above will use (reported beside timings). */

@@ -48,6 +48,14 @@ def lib() -> ctypes.CDLL:
         L.oracle_select.argtypes = [vp, i64, vp, i32, ctypes.c_uint64, i64, vp, vp]
         L.oracle_query.restype = i32
         L.oracle_query.argtypes = [vp, i32, vp, vp, i64, i64, vp, i32, i64, vp, i64, vp, vp, vp]
+        L.oracle_philox4x32_10.restype = None
+        L.oracle_philox4x32_10.argtypes = [vp, vp, vp]
+        L.oracle_uniform.restype = dbl
+        L.oracle_uniform.argtypes = [ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint64]
+        L.oracle_gumbel.restype = dbl
+        L.oracle_gumbel.argtypes = [ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint64]
+        L.oracle_selection_keys.restype = i32
+        L.oracle_selection_keys.argtypes = [vp, i64, i64, vp, dbl, ctypes.c_uint64, i64, vp]
         L.oracle_num_threads.restype = i32
         L.oracle_num_threads.argtypes = []
         _lib = L
@@ -114,6 +122,38 @@ def select(scores, k, tags=None, qmask=None):
     if n < 0:
         raise RuntimeError("oracle_select failed")
     return idx, sc, int(n)
+
+
+def philox4x32_10(ctr, key):
+    """One call of the counter-based generator: four 32-bit words from a 4-word counter and a 2-word key."""
+    c = np.ascontiguousarray(ctr, dtype=np.uint32)
+    kk = np.ascontiguousarray(key, dtype=np.uint32)
+    assert c.shape == (4,) and kk.shape == (2,)
+    out = np.empty(4, dtype=np.uint32)
+    lib().oracle_philox4x32_10(_ptr(c), _ptr(kk), _ptr(out))
+    return out
+
+
+def uniform(seed: int, query: int, entry: int) -> float:
+    return lib().oracle_uniform(seed, query, entry)
+
+
+def gumbel(seed: int, query: int, entry: int) -> float:
+    return lib().oracle_gumbel(seed, query, entry)
+
+
+def selection_keys(scores, gain, temperature: float, seed: int, first_query: int = 0) -> np.ndarray:
+    """Keys of the weighted random selection, float64 [Q, N]: score / T + ln(gain) + Gumbel(seed, query, entry)."""
+    scores = np.ascontiguousarray(scores, dtype=np.float64)
+    assert scores.ndim == 2
+    gain = np.ascontiguousarray(gain, dtype=np.float32)
+    assert gain.shape == (scores.shape[1],)
+    keys = np.empty_like(scores)
+    rc = lib().oracle_selection_keys(_ptr(scores), scores.shape[0], scores.shape[1], _ptr(gain), float(temperature), seed,
+                                     first_query, _ptr(keys))
+    if rc != 0:
+        raise RuntimeError(f"oracle_selection_keys failed ({rc})")
+    return keys
 
 
 def query(keys, key_dtype, queries, q_dtype, k, row_scale=None, tags=None, qmask=None, return_scores=False):

@@ -287,3 +287,93 @@ def test_compare_near_tie_rule(oracle):
     assert rep.near_tie == 1
     with pytest.raises(AssertionError):                         # but a clearly worse entry may not
         compare.check(np.array([[0, 3]], dtype=np.int32), np.array([[1.0, full[0, 3]]], dtype=np.float32), full, 2, 1e-5)
+
+
+# ---- weighted random selection (Section 3: "random weighted selection based on predicted performance gain") ----
+
+def test_philox_known_answer_vectors(oracle):
+    kat = json.load(open(os.path.join(GOLD, "philox4x32_10_kat.json")))
+    for v in kat["vectors"]:
+        out = oracle.philox4x32_10([int(x, 16) for x in v["counter"]], [int(x, 16) for x in v["key"]])
+        assert [f"{int(x):08x}" for x in out] == v["output"]
+
+
+def test_uniform_uses_the_documented_counter_layout(oracle):
+    seed = 0x0123456789ABCDEF
+    for query, entry in [(0, 0), (7, 5), (123, 4096 + 3), (2**31, 2**30 + 2)]:
+        words = oracle.philox4x32_10([entry >> 2, query, 0, 0], [seed & 0xFFFFFFFF, seed >> 32])
+        u = ((int(words[entry & 3]) >> 8) + 0.5) / 2.0**24
+        assert oracle.uniform(seed, query, entry) == u
+        assert oracle.gumbel(seed, query, entry) == -math.log(-math.log(u))
+    assert np.float32(u) == u                                   # exactly representable in binary32
+
+
+def test_variate_moments(oracle):
+    n = 200_000
+    keys = oracle.selection_keys(np.zeros((1, n)), np.ones(n, dtype=np.float32), 1.0, 99)      # pure Gumbel noise
+    g = keys[0]
+    assert abs(g.mean() - 0.5772156649) < 0.012                 # Euler-Mascheroni; sigma/sqrt(n) = 0.0029
+    assert abs(g.var() - math.pi**2 / 6) < 0.03
+    u = np.exp(-np.exp(-g))
+    assert abs(u.mean() - 0.5) < 0.003 and abs(u.var() - 1 / 12) < 0.002
+
+
+def _weights(scores, gain, T):
+    return gain.astype(np.float64) * np.exp(scores / T)
+
+
+def test_single_draw_follows_the_weights(oracle):
+    # k = 1: P(entry i) = w_i / sum(w), w_i = gain_i * exp(score_i / T).  40,000 independent queries, same scores.
+    scores = np.array([0.30, 0.10, 0.25, -0.20, 0.05, 0.28])
+    gain = np.array([1.0, 4.0, 0.5, 8.0, 0.0, 2.0], dtype=np.float32)        # entry 4 has no weight at all
+    T, draws = 0.2, 40_000
+    keys = oracle.selection_keys(np.tile(scores, (draws, 1)), gain, T, seed=2024)
+    first = keys.argmax(axis=1)
+    w = _weights(scores, gain, T)
+    p = w / w.sum()
+    freq = np.bincount(first, minlength=6) / draws
+    assert freq[4] == 0.0 and np.all(np.isneginf(keys[:, 4]))
+    assert np.all(np.abs(freq - p) < 4.5 * np.sqrt(p * (1 - p) / draws) + 1e-12)
+
+
+def test_ordered_pairs_follow_plackett_luce(oracle):
+    # k = 2 without replacement: P(first = i, second = j) = w_i / W * w_j / (W - w_i)
+    scores = np.array([0.2, 0.0, 0.1, -0.1])
+    gain = np.array([1.0, 2.0, 1.0, 3.0], dtype=np.float32)
+    T, draws = 0.25, 60_000
+    keys = oracle.selection_keys(np.tile(scores, (draws, 1)), gain, T, seed=7)
+    order = np.argsort(-keys, axis=1)[:, :2]
+    w = _weights(scores, gain, T)
+    W_ = w.sum()
+    for i in range(4):
+        for j in range(4):
+            if i == j:
+                continue
+            p = w[i] / W_ * w[j] / (W_ - w[i])
+            f = np.mean((order[:, 0] == i) & (order[:, 1] == j))
+            assert abs(f - p) < 4.5 * math.sqrt(p * (1 - p) / draws)
+
+
+def test_selection_limits_and_determinism(oracle):
+    rng = np.random.default_rng(3)
+    scores = rng.uniform(-0.5, 0.9, size=(5, 300))
+    gain = rng.uniform(0.5, 2.0, size=300).astype(np.float32)
+    k1 = oracle.selection_keys(scores, gain, 0.1, seed=11)
+    assert np.array_equal(k1, oracle.selection_keys(scores, gain, 0.1, seed=11))          # pure function of its inputs
+    assert not np.array_equal(k1, oracle.selection_keys(scores, gain, 0.1, seed=12))
+    # rows are numbered from first_query: the draw of query 3 does not depend on how queries are batched
+    assert np.array_equal(k1[3:], oracle.selection_keys(scores[3:], gain, 0.1, seed=11, first_query=3))
+    # temperature -> 0: the noise and the gain prior vanish against score / T, plain top-k is recovered
+    cold = oracle.selection_keys(scores, gain, 1e-7, seed=11)
+    for r in range(5):
+        assert np.array_equal(oracle.select(cold[r], 10)[0], oracle.select(scores[r], 10)[0])
+    # key = score / T + ln(gain) + Gumbel, term by term
+    r, i = 2, 137
+    assert k1[r, i] == scores[r, i] / 0.1 + math.log(float(gain[i])) + oracle.gumbel(11, r, i)
+    # the tag filter applies to keys exactly as to scores, and a zero-gain entry is never a candidate
+    tags = rng.integers(0, 2**16, size=300, dtype=np.uint64)
+    gain0 = gain.copy(); gain0[::3] = 0.0
+    keys = oracle.selection_keys(scores, gain0, 0.1, seed=5)
+    idx, val, n = oracle.select(keys[0], 300, tags=tags, qmask=0x00F0)
+    good = ((tags & np.uint64(0x00F0)) != 0) & (gain0 > 0)
+    assert n == good.sum() and set(idx[:n].tolist()) == set(np.flatnonzero(good).tolist()) and np.all(idx[n:] == -1)
