@@ -289,15 +289,16 @@ void oracle_philox4x32_10(const uint32_t ctr_in[4], const uint32_t key_in[2], ui
 
 /* The uniform variate of pair (query, entry): generator call with counter
  * (entry / 4, query, 0, 0) and the seed as key; entry % 4 picks one of the
- * four output words; its upper 24 bits b give U = (b + 1/2) / 2^24, which is
- * in (0, 1) and exactly representable in binary32 and binary64. */
+ * four output words; its upper 23 bits b give U = (b + 1/2) / 2^23 = (2b + 1) / 2^24,
+ * which is in (0, 1) and exactly representable in binary32 (24-bit significand)
+ * and binary64. */
 double oracle_uniform(uint64_t seed, uint32_t query, uint64_t entry)
 {
     uint32_t ctr[4] = {(uint32_t)(entry >> 2), query, 0u, 0u};
     uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
     uint32_t w[4];
     oracle_philox4x32_10(ctr, key, w);
-    return ((double)(w[entry & 3] >> 8) + 0.5) / 16777216.0;
+    return ((double)(w[entry & 3] >> 9) + 0.5) / 8388608.0;
 }
 
 /* Standard Gumbel variate by inversion: G = -ln(-ln U). */

@@ -302,10 +302,11 @@ def test_uniform_uses_the_documented_counter_layout(oracle):
     seed = 0x0123456789ABCDEF
     for query, entry in [(0, 0), (7, 5), (123, 4096 + 3), (2**31, 2**30 + 2)]:
         words = oracle.philox4x32_10([entry >> 2, query, 0, 0], [seed & 0xFFFFFFFF, seed >> 32])
-        u = ((int(words[entry & 3]) >> 8) + 0.5) / 2.0**24
+        u = ((int(words[entry & 3]) >> 9) + 0.5) / 2.0**23
         assert oracle.uniform(seed, query, entry) == u
         assert oracle.gumbel(seed, query, entry) == -math.log(-math.log(u))
-    assert np.float32(u) == u                                   # exactly representable in binary32
+        assert float(np.float32(u)) == u                        # exactly representable in binary32
+    assert float(np.float32((2.0**23 - 0.5) / 2.0**23)) == (2.0**23 - 0.5) / 2.0**23       # also the largest one
 
 
 def test_variate_moments(oracle):
