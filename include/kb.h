@@ -114,6 +114,28 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
                      size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Weighted random selection (Section 3: the Optimization Selector "performs a random weighted selection based
+ * on predicted performance gain ... to select the top-k").  Entry i carries a predicted gain g_i; query r draws
+ * k entries WITHOUT replacement from its qualifying entries with probability proportional to
+ * g_i * exp(score_ri / temperature).  The draw is the k largest of
+ *     key_ri = score_ri / temperature + ln g_i + G_ri,   G_ri = -ln(-ln U_ri)  (standard Gumbel),
+ * where U_ri = (upper 23 bits of word (i mod 4) of Philox4x32-10(counter = (i div 4, first_query + r, 0, 0),
+ * key = seed) + 1/2) / 2^23, so a result is a pure function of (stored bits, queries, gains, temperature, seed,
+ * first_query): bit-identical from run to run and independent of how queries are batched.
+ *   gain_dev    [kb_size] fp32 device array, 4-byte aligned, borrowed for the call; an entry with gain <= 0 is
+ *               never drawn.  Gains are finite (not checked).
+ *   temperature finite, > 0.  seed: any.  first_query >= 0: global number of query row 0.
+ *   indices_out_dev [Q, k] int32 and keys_out_dev [Q, k] fp32: drawn entries ordered by (key descending, index
+ *               ascending), padded with (-1, -inf) when fewer than k entries qualify.  Keys are computed in fp32
+ *               from the fp32 score of kb_query.
+ * Everything else (queries, q_dtype, qmask, k, workspace = kb_query_workspace_bytes, stream, errors) as kb_query.
+ */
+kb_status_t kb_query_sampled(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int32_t Q, const uint64_t *qmask_dev,
+                             int32_t k, const float *gain_dev, float temperature, uint64_t seed, int32_t first_query,
+                             int32_t *indices_out_dev, float *keys_out_dev, void *workspace_dev, size_t workspace_bytes,
+                             void *hip_stream);
+
+/*
  * Diagnostics of the most recent kb_query that used `workspace_dev`: synchronises `hip_stream`, then copies
  * out[0] = candidates that passed the threshold filter (all queries), out[1] = queries resolved by the
  * exhaustive per-query path, out[2] = keys scored by the sampling pass, out[3] = workgroups of the scan.

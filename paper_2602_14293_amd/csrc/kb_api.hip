@@ -102,7 +102,7 @@ size_t align_up(size_t x) { return (x + WS_ALIGN - 1) / WS_ALIGN * WS_ALIGN; }
 
 // Pure function of (handle settings, row count n, Q, k): which kernels run on what, and where
 // everything lives in the workspace.
-bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, Plan *out)
+bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, bool draw, Plan *out)
 {
     Plan p;
     memset(&p, 0, sizeof p);
@@ -111,6 +111,10 @@ bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, Plan *out)
     p.config = h->tune_config > 0 ? (int)h->tune_config : scan_config_for(h->dtype, Q, h->d);
     ConfigInfo ci;
     if (!scan_config_info(h->dtype, p.config, &ci)) return false;
+    if (draw && ci.family != 0) {       // the weighted random selection exists in the tiled kernel only
+        p.config = Q <= 32 ? 1 : Q <= 128 ? 2 : 3;
+        if (!scan_config_info(h->dtype, p.config, &ci)) return false;
+    }
     if (h->d * key_bytes(h->dtype) < ci.min_row_bytes) {     // a forced configuration the rows are too short for
         p.config = Q <= 32 ? 1 : Q <= 128 ? 2 : 3;
         if (!scan_config_info(h->dtype, p.config, &ci)) return false;
@@ -175,6 +179,7 @@ bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, Plan *out)
     p.off_samp = off;        off = align_up(off + sizeof(uint64_t) * (size_t)p.qpad * (p.sample_slots > 0 ? p.sample_slots : 1));
     p.off_regions = off;     off = align_up(off + sizeof(Record) * (size_t)p.regions * p.region_cap);
     p.off_cand = off;        off = align_up(off + sizeof(uint64_t) * (size_t)p.qpad * p.cand_cap);
+    p.off_lgain = off;       off = align_up(off + sizeof(float) * (size_t)(ceil_div(n, 256) * 256 + 256));   // ln(gain), padded past the last tile
     p.total = off;
     *out = p;
     return true;
@@ -244,6 +249,21 @@ template <int DT> __global__ __launch_bounds__(256) void row_norm_kernel(const v
     if (row >= end) return;
     const float inv = row_inv_norm<DT>(keys, row, d * (DT == KB_F32 ? 4 : DT == KB_BF16 ? 2 : 1), lane);
     if (lane == 0) inv_norm[row] = inv;
+}
+
+// ------------------------------------------------------------------------------------------------
+// weighted random selection: ln(gain) per entry, -inf for entries without weight and for the padding
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void log_gain_kernel(const float *gain, int64_t n, int64_t n_padded, float *log_gain)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n_padded) return;
+    float v = -__builtin_inff();
+    if (i < n) {
+        const float g = gain[i];
+        if (g > 0.f) v = logf(g);
+    }
+    log_gain[i] = v;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -438,7 +458,8 @@ __device__ inline void select_topk_desc(uint64_t *buf, int n, int k, SelectScrat
 // entries reach it).  Also derives the conservative pre-filter on dot * inv_k used by the main pass:
 // whenever fp32((dot*inv_k) * inv_q) >= s_thr holds, dot*inv_k >= thrp holds (2^-20 relative slack
 // covers the three fp32 roundings involved).
-__global__ __launch_bounds__(1024) void threshold_kernel(const uint64_t *samp, int slots, int k, const float *invq, uint64_t *thr64, float *thrp)
+__global__ __launch_bounds__(1024) void threshold_kernel(const uint64_t *samp, int slots, int k, const float *invq, uint64_t *thr64, float *thrp,
+                                                         int draw)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     uint64_t *buf = reinterpret_cast<uint64_t *>(smem_raw);
@@ -451,7 +472,10 @@ __global__ __launch_bounds__(1024) void threshold_kernel(const uint64_t *samp, i
         const uint64_t t = k <= slots ? buf[k - 1] : 0ull;
         const float iq = invq[q];
         float tp = -__builtin_inff();
-        if (t != 0 && iq > 0.f) {
+        if (draw) {
+            // keys are compared as they are: a word at or above t has a key at or above t's key
+            if (t != 0) tp = candidate_score(t);
+        } else if (t != 0 && iq > 0.f) {
             const float x = candidate_score(t) / iq;
             tp = x - fabsf(x) * 0x1p-20f - 1e-30f;
         }
@@ -504,6 +528,7 @@ struct FinalArgs {
     float *out_score;
     int64_t n_keys;
     int32_t d, k, cand_cap;
+    DrawArgs draw;
 };
 
 template <int KT> __device__ void exhaustive_query(const FinalArgs &a, int q, uint64_t *buf, uint32_t *ctl)
@@ -544,8 +569,10 @@ template <int KT> __device__ void exhaustive_query(const FinalArgs &a, int q, ui
         if (lrow < 16) {
             const int64_t row = row0 + wave * 32 + 8 * (lrow >> 2) + 4 * half + (lrow & 3);
             if (row < a.n_keys && (!filter || (a.tags[row] & qm) != 0)) {
-                const uint64_t cw = pack_candidate(final_score(v, a.inv_norm[row], iq), (uint32_t)row);
-                if (cw > *thr_local) {
+                float value = final_score(v, a.inv_norm[row], iq);
+                if (a.draw.enabled) value = draw_key_of(value, a.draw, a.draw.first_query + (uint32_t)q, row);
+                const uint64_t cw = pack_candidate(value, (uint32_t)row);
+                if (cw > *thr_local && value > -__builtin_inff()) {
                     const uint32_t pos = atomicAdd(&ctl[0], 1u);
                     buf[pos] = cw;      // pos < cap: at most 128 appends between compactions
                 }
@@ -707,22 +734,29 @@ size_t kb_query_workspace_bytes(const kb_t *kb, int32_t Q, int32_t k)
     // the plan depends on the row count at query time: take the largest over a ladder of row counts
     for (int64_t n = kb->capacity; n >= 1; n = n / 2) {
         Plan p;
-        if (!make_plan(kb, n, Q, k, &p)) return 0;
-        if (p.total > best) best = p.total;
+        for (int draw = 0; draw < 2; ++draw) {
+            if (!make_plan(kb, n, Q, k, draw != 0, &p)) return 0;
+            if (p.total > best) best = p.total;
+        }
         if (n == 1) break;
     }
     for (int64_t n = 1; n <= kb->capacity && n < (int64_t)1 << 16; n += 61) {   // and the small, irregular sizes
         Plan p;
-        if (!make_plan(kb, n, Q, k, &p)) return 0;
-        if (p.total > best) best = p.total;
+        for (int draw = 0; draw < 2; ++draw) {
+            if (!make_plan(kb, n, Q, k, draw != 0, &p)) return 0;
+            if (p.total > best) best = p.total;
+        }
     }
     return best;
 }
 
-kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int32_t Q, const uint64_t *qmask_dev, int32_t k,
-                     int32_t *indices_out_dev, float *scores_out_dev, void *workspace_dev, size_t workspace_bytes,
-                     void *hip_stream)
+// kb_query and kb_query_sampled: the same pipeline; `gain_dev` != nullptr selects the weighted random selection.
+static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int32_t Q, const uint64_t *qmask_dev, int32_t k,
+                             const float *gain_dev, float temperature, uint64_t seed, int32_t first_query,
+                             int32_t *indices_out_dev, float *scores_out_dev, void *workspace_dev, size_t workspace_bytes,
+                             void *hip_stream)
 {
+    const bool draw = gain_dev != nullptr;
     if (!kb || !queries_dev || !indices_out_dev || !scores_out_dev) return KB_ERR_NULL;
     if (!valid_dtype((int)q_dtype)) return KB_ERR_DTYPE;
     const kb_dtype_t want_q = kb->dtype == KB_F32 ? KB_F32 : KB_BF16;
@@ -739,7 +773,7 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
         kb->cu_count = cus < ASSUMED_CUS ? cus : ASSUMED_CUS;
     }
     Plan p;
-    if (!make_plan(kb, kb->n, Q, k, &p)) return KB_ERR_INVALID_ARG;
+    if (!make_plan(kb, kb->n, Q, k, draw, &p)) return KB_ERR_INVALID_ARG;
     if (workspace_bytes < p.total) return KB_ERR_WORKSPACE;
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -755,6 +789,21 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
     uint64_t *samp = reinterpret_cast<uint64_t *>(ws + p.off_samp);
     Record *regions = reinterpret_cast<Record *>(ws + p.off_regions);
     uint64_t *cand = reinterpret_cast<uint64_t *>(ws + p.off_cand);
+    float *log_gain = reinterpret_cast<float *>(ws + p.off_lgain);
+
+    DrawArgs dr;
+    memset(&dr, 0, sizeof dr);
+    if (draw) {
+        dr.log_gain = log_gain;
+        dr.inv_t = 1.0f / temperature;
+        dr.seed_lo = (uint32_t)seed;
+        dr.seed_hi = (uint32_t)(seed >> 32);
+        dr.first_query = (uint32_t)first_query;
+        dr.enabled = 1;
+        const int64_t n_padded = ceil_div(kb->n > 0 ? kb->n : 1, 256) * 256 + 256;
+        hipLaunchKernelGGL(log_gain_kernel, dim3((unsigned)ceil_div(n_padded, 256)), dim3(256), 0, s, gain_dev, kb->n, n_padded, log_gain);
+        if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
+    }
 
     {
         const int n_init = p.qpad > p.regions ? p.qpad : p.regions;
@@ -788,6 +837,7 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
         a.nqb = p.nqb;
         a.sample_slots = p.sample_slots;
         a.region_cap = p.region_cap;
+        a.draw = dr;
         if (p.sample_tiles > 0) {
             a.n_tiles = p.sample_tiles;
             int64_t sgrid = p.sample_tiles * p.nqb;
@@ -803,7 +853,7 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
                     return KB_ERR_DEVICE;
                 thr_attr = true;
             }
-            hipLaunchKernelGGL(threshold_kernel, dim3(Q), dim3(thr_threads), thr_lds, s, samp, p.sample_slots, k, invq, thr64, thrp);
+            hipLaunchKernelGGL(threshold_kernel, dim3(Q), dim3(thr_threads), thr_lds, s, samp, p.sample_slots, k, invq, thr64, thrp, draw ? 1 : 0);
             if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
         }
         a.n_tiles = ceil_div(kb->n, p.tk);
@@ -835,6 +885,7 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
     f.d = kb->d;
     f.k = k;
     f.cand_cap = p.cand_cap;
+    f.draw = dr;
     const size_t fin_lds = (size_t)p.cand_cap * 8 + 16 + sizeof(SelectScratch);
     static bool fin_attr[3] = {false, false, false};
     const void *fin_fn = kb->dtype == KB_F32 ? reinterpret_cast<const void *>(&finalize_kernel<KB_F32>)
@@ -851,6 +902,26 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
     }
     if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
     return KB_OK;
+}
+
+kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int32_t Q, const uint64_t *qmask_dev, int32_t k,
+                     int32_t *indices_out_dev, float *scores_out_dev, void *workspace_dev, size_t workspace_bytes,
+                     void *hip_stream)
+{
+    return run_query(kb, queries_dev, q_dtype, Q, qmask_dev, k, nullptr, 1.0f, 0, 0, indices_out_dev, scores_out_dev, workspace_dev,
+                     workspace_bytes, hip_stream);
+}
+
+kb_status_t kb_query_sampled(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int32_t Q, const uint64_t *qmask_dev, int32_t k,
+                             const float *gain_dev, float temperature, uint64_t seed, int32_t first_query,
+                             int32_t *indices_out_dev, float *keys_out_dev, void *workspace_dev, size_t workspace_bytes,
+                             void *hip_stream)
+{
+    if (!gain_dev) return KB_ERR_NULL;
+    if (!(temperature > 0.0f) || !(temperature < __builtin_inff()) || first_query < 0) return KB_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(gain_dev) & 3) != 0) return KB_ERR_INVALID_ARG;
+    return run_query(kb, queries_dev, q_dtype, Q, qmask_dev, k, gain_dev, temperature, seed, first_query, indices_out_dev, keys_out_dev,
+                     workspace_dev, workspace_bytes, hip_stream);
 }
 
 kb_status_t kb_query_counters(const kb_t *kb, const void *workspace_dev, int64_t *out, void *hip_stream)

@@ -176,4 +176,169 @@ __device__ inline void sample_epilogue(const f32x16 (&acc)[IB][JB], const EpiSid
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Weighted random selection: the same two epilogues on keys = score / T + ln(gain) + Gumbel noise.
+// ------------------------------------------------------------------------------------------------
+
+// Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, SC'11) on the counter (c0, c1, 0, 0).
+__device__ inline void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t k0, uint32_t k1, uint32_t (&out)[4])
+{
+    uint32_t c2 = 0u, c3 = 0u;
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        if (round > 0) {
+            k0 += 0x9E3779B9u;
+            k1 += 0xBB67AE85u;
+        }
+        const uint32_t h0 = __umulhi(0xD2511F53u, c0), l0 = 0xD2511F53u * c0;
+        const uint32_t h1 = __umulhi(0xCD9E8D57u, c2), l1 = 0xCD9E8D57u * c2;
+        c0 = h1 ^ c1 ^ k0;
+        c1 = l1;
+        c2 = h0 ^ c3 ^ k1;
+        c3 = l0;
+    }
+    out[0] = c0;
+    out[1] = c1;
+    out[2] = c2;
+    out[3] = c3;
+}
+
+// Standard Gumbel variate from one generator word: U = (upper 23 bits + 1/2) / 2^23 (exact in fp32), G = -ln(-ln U).
+__device__ inline float gumbel_of_word(uint32_t w)
+{
+    const float u = __builtin_fmaf((float)(w >> 9), 0x1p-23f, 0x1p-24f);
+    return -__logf(-__logf(u));
+}
+
+// Key of one (query, entry) pair.  Entries 4j .. 4j+3 share one generator call (counter (j, query, 0, 0)); the word
+// is picked by entry % 4.  "+ 0.0f" as in final_score: equal keys have equal bit patterns.
+__device__ inline float draw_key(float score, float log_gain, float gumbel, float inv_t)
+{
+    return (__builtin_fmaf(score, inv_t, log_gain) + gumbel) + 0.0f;
+}
+__device__ inline float draw_key_of(float score, const DrawArgs &dr, uint32_t query, int64_t row)
+{
+    uint32_t w[4];
+    philox4x32_10((uint32_t)(row >> 2), query, dr.seed_lo, dr.seed_hi, w);
+    const uint32_t word = (row & 3) == 0 ? w[0] : (row & 3) == 1 ? w[1] : (row & 3) == 2 ? w[2] : w[3];
+    return draw_key(score, dr.log_gain[row], gumbel_of_word(word), dr.inv_t);
+}
+
+// Keys of the 16 elements a lane holds in one block (four runs of four consecutive rows: four generator calls).
+__device__ inline void block_keys(const f32x16 &a, const EpiRows &rw, float iq, const DrawArgs &dr, uint32_t query, int64_t row0,
+                                  float (&key)[16])
+{
+#pragma unroll
+    for (int run = 0; run < 4; ++run) {
+        const int64_t first = row0 + rw.rl0 + 8 * run;         // a multiple of 4
+        uint32_t w[4];
+        philox4x32_10((uint32_t)(first >> 2), query, dr.seed_lo, dr.seed_hi, w);
+        const f32x4 lg = *reinterpret_cast<const f32x4 *>(dr.log_gain + first);
+        const float lgs[4] = {lg.x, lg.y, lg.z, lg.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int i = 4 * run + e;
+            key[i] = draw_key(final_score(a[i], rw.ik[i], iq), lgs[e], gumbel_of_word(w[e]), dr.inv_t);
+        }
+    }
+}
+
+// Main pass on keys.  There is no cheap bound on a key (the noise is unbounded), so every element's key is
+// computed and compared with the query's threshold key; survivors are then handled exactly like the survivors
+// of the score pass (their keys are recomputed: same inputs, same bits).
+__device__ inline void main_block_draw(const f32x16 &a, const EpiRows &rw, float tp, int ql, const EpiSide &sd, bool filter,
+                                       int64_t row0, int q0, const ScanArgs &p, Record *region, uint32_t &wave_cnt)
+{
+    const float iq = sd.invq[ql];
+    const uint32_t query = p.draw.first_query + (uint32_t)(q0 + ql);
+    float key[16];
+    block_keys(a, rw, iq, p.draw, query, row0, key);
+    uint32_t pass = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) pass = (pass << 1) | (key[i] >= tp && key[i] > -__builtin_inff() ? 1u : 0u);   // element i at bit 15 - i
+    uint64_t lanes = __builtin_amdgcn_ballot_w64(pass != 0);
+    if (lanes == 0) return;
+    const uint64_t t64 = sd.thr64[ql];
+    const uint64_t qm = filter ? sd.qmask[ql] : 0ull;
+    do {
+        uint32_t m = (uint32_t)__builtin_amdgcn_readlane((int)pass, __builtin_ctzll(lanes));
+        const uint32_t mine = pass & m;
+        pass &= ~m;
+        do {
+            const int b = 31 - __builtin_clz(m);
+            m &= ~(1u << b);
+            const int i = 15 - b;                               // wave-uniform
+            const bool has = (mine >> b) & 1u;
+            const int rl = rw.rl0 + 8 * (i >> 2) + (i & 3);
+            const int64_t row = row0 + rl;
+            const float kv = draw_key_of(final_score(a[i], sd.invk[rl], iq), p.draw, query, row);
+            const uint64_t cw = pack_candidate(kv, (uint32_t)row);
+            bool ok = has && row < p.n_keys && kv > -__builtin_inff() && cw >= t64;
+            if (filter) ok = ok && (sd.tag[rl] & qm) != 0;
+            const uint64_t okm = __builtin_amdgcn_ballot_w64(ok);
+            if (ok) {
+                const uint32_t pos = wave_cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(okm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)okm, 0u));
+                if (pos < (uint32_t)p.region_cap) {
+                    Record rec;
+                    rec.cand = cw;
+                    rec.query = (uint32_t)(q0 + ql);
+                    rec.pad = 0;
+                    region[pos] = rec;
+                } else {
+                    p.flag[q0 + ql] = 1u;
+                }
+            }
+            wave_cnt += (uint32_t)__builtin_popcountll(okm);
+        } while (m != 0);
+        lanes = __builtin_amdgcn_ballot_w64(pass != 0);
+    } while (lanes != 0);
+}
+
+template <int IB, int JB>
+__device__ inline void main_epilogue_draw(const f32x16 (&acc)[IB][JB], const EpiSide &sd, bool filter, int wave_row0, int ql0,
+                                          int half, int64_t row0, int q0, const ScanArgs &p, Record *region, uint32_t &wave_cnt)
+{
+#pragma unroll
+    for (int ib = 0; ib < IB; ++ib) {
+        const EpiRows rw = load_rows(sd, wave_row0 + ib * 32 + 4 * half);
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb)
+            main_block_draw(acc[ib][jb], rw, sd.thrp[ql0 + jb * 32], ql0 + jb * 32, sd, filter, row0, q0, p, region, wave_cnt);
+    }
+}
+
+// Sampling pass on keys: per lane and query column the qualifying entry with the largest key.
+template <int IB, int JB>
+__device__ inline void sample_epilogue_draw(const f32x16 (&acc)[IB][JB], const EpiSide &sd, bool filter, int wave_row0, int ql0,
+                                            int half, int64_t row0, int q0, const ScanArgs &p, int64_t slot)
+{
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb) {
+        const int ql = ql0 + jb * 32;
+        const float iq = sd.invq[ql];
+        const uint64_t qm = filter ? sd.qmask[ql] : 0ull;
+        const uint32_t query = p.draw.first_query + (uint32_t)(q0 + ql);
+        float best = -__builtin_inff();
+        int best_rl = -1;
+#pragma unroll
+        for (int ib = 0; ib < IB; ++ib) {
+            const EpiRows rw = load_rows(sd, wave_row0 + ib * 32 + 4 * half);
+            float key[16];
+            block_keys(acc[ib][jb], rw, iq, p.draw, query, row0, key);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int rl = rw.rl0 + 8 * (i >> 2) + (i & 3);
+                bool ok = row0 + rl < p.n_keys && key[i] > best;
+                if (filter) ok = ok && (sd.tag[rl] & qm) != 0;
+                if (ok) {
+                    best = key[i];
+                    best_rl = rl;
+                }
+            }
+        }
+        if (q0 + ql < p.Q)
+            p.samp[(size_t)(q0 + ql) * p.sample_slots + slot] = best_rl >= 0 ? pack_candidate(best, (uint32_t)(row0 + best_rl)) : 0ull;
+    }
+}
+
 }  // namespace kbi

@@ -66,7 +66,18 @@ struct Plan {
     int32_t regions;                    // grid * wavefronts per workgroup
     int32_t cand_cap;                   // candidates per query the final sort can take (power of two)
     size_t off_invq, off_thr64, off_thrp, off_cnt, off_flag, off_region_cnt, off_stats, off_qmask, off_samp, off_regions,
-        off_cand, total;
+        off_cand, off_lgain, total;
+};
+
+// Weighted random selection (the Optimization Selector's "random weighted selection based on predicted
+// performance gain" of Section 3): entries are ranked by key = score / T + ln(gain) + Gumbel noise instead of by
+// score, which draws k entries without replacement with probability proportional to gain * exp(score / T).
+struct DrawArgs {
+    const float *log_gain;    // [rows padded to a multiple of 256]: ln(gain), -inf for entries that are never drawn
+    float inv_t;              // 1 / temperature
+    uint32_t seed_lo, seed_hi;
+    uint32_t first_query;     // the noise of query row r is that of global query number first_query + r
+    int32_t enabled;
 };
 
 struct ScanArgs {
@@ -86,6 +97,7 @@ struct ScanArgs {
     int64_t n_keys;           // rows to scan: [0, n_keys)
     int64_t n_tiles;          // key tiles to scan
     int32_t d, Q, nqb, sample_slots, region_cap;
+    DrawArgs draw;
 };
 
 // Launchers, one translation unit per key dtype.  `sample` selects the sampling epilogue.

@@ -153,7 +153,7 @@ __device__ inline void bare_barrier()
     asm volatile("" ::: "memory");
 }
 
-template <class C, bool SAMPLE>
+template <class C, bool SAMPLE, bool DRAW>
 __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p)
 {
     constexpr int TK = C::TK, TQ = C::TQ, RBA = C::RBA, RBB = C::RBB, IB = C::IB, JB = C::JB, NW = C::NW;
@@ -340,9 +340,14 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
             bare_barrier();
             const int64_t row0 = (int64_t)tile * TK;
             const EpiSide sd{aux_invk, aux_tag, reinterpret_cast<const float *>(smem + C::OFF_THRP), aux_invq, aux_thr64, aux_qmask};
-            if (SAMPLE)
+            if (SAMPLE && DRAW)
+                sample_epilogue_draw<IB, JB>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p,
+                                             (int64_t)tile * C::GROUPS_PER_TILE + wm * 2 + half);
+            else if (SAMPLE)
                 sample_epilogue<IB, JB>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p,
                                         (int64_t)tile * C::GROUPS_PER_TILE + wm * 2 + half);
+            else if (DRAW)
+                main_epilogue_draw<IB, JB>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p, my_region, wave_cnt);
             else
                 main_epilogue<IB, JB>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p, my_region, wave_cnt);
 #pragma unroll
@@ -370,13 +375,16 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
 template <class C> hipError_t launch_scan_cfg(bool sample, int grid, const ScanArgs &a, hipStream_t s)
 {
     // more than 64 KiB of dynamic LDS has to be requested explicitly, once per kernel
-    static bool attr_done[2] = {false, false};
-    auto *fn = sample ? &kb_scan_kernel<C, true> : &kb_scan_kernel<C, false>;
-    if (!attr_done[sample]) {
+    static bool attr_done[4] = {false, false, false, false};
+    const bool draw = a.draw.enabled != 0;
+    auto *fn = draw ? (sample ? &kb_scan_kernel<C, true, true> : &kb_scan_kernel<C, false, true>)
+                    : (sample ? &kb_scan_kernel<C, true, false> : &kb_scan_kernel<C, false, false>);
+    const int which = (draw ? 2 : 0) + (sample ? 1 : 0);
+    if (!attr_done[which]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM_BYTES);
         if (e != hipSuccess) return e;
-        attr_done[sample] = true;
+        attr_done[which] = true;
     }
     hipLaunchKernelGGL(fn, dim3(grid), dim3(C::THREADS), C::SMEM_BYTES, s, a);
     return hipGetLastError();

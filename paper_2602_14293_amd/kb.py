@@ -50,6 +50,8 @@ def lib() -> ctypes.CDLL:
         L.kb_query_workspace_bytes.argtypes = [vp, i32, i32]
         L.kb_query.restype = i32
         L.kb_query.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, vp, sz, vp]
+        L.kb_query_sampled.restype = i32
+        L.kb_query_sampled.argtypes = [vp, vp, i32, i32, vp, i32, vp, ctypes.c_float, ctypes.c_uint64, i32, vp, vp, vp, sz, vp]
         L.kb_query_counters.restype = i32
         L.kb_query_counters.argtypes = [vp, vp, ctypes.POINTER(i64), vp]
         L.kb_set_tuning.restype = i32
@@ -136,6 +138,28 @@ class KnowledgeBase:
         _check(lib().kb_query(self._h, _ptr(queries), _CODE_OF[queries.dtype], Q, _ptr(qmask), k, _ptr(out_index),
                               _ptr(out_score), _ptr(self._workspace), self._workspace.numel(), _stream()), "kb_query")
         return out_index, out_score
+
+    def query_sampled(self, queries: torch.Tensor, k: int, gain: torch.Tensor, temperature: float, seed: int,
+                      qmask: Optional[torch.Tensor] = None, first_query: int = 0,
+                      out_index: Optional[torch.Tensor] = None, out_key: Optional[torch.Tensor] = None):
+        """Weighted random selection: k entries per query drawn without replacement, P ~ gain * exp(score / T)."""
+        Q = queries.shape[0]
+        assert queries.is_contiguous() and queries.shape[1] == self.d
+        assert gain.dtype == torch.float32 and gain.is_contiguous() and gain.numel() >= self.size
+        need = self.workspace_bytes(Q, k)
+        if need == 0:
+            raise KBError(2, "kb_query_workspace_bytes")
+        if self._workspace is None or self._workspace.numel() < need:
+            self._workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
+        if out_index is None:
+            out_index = torch.empty((Q, k), dtype=torch.int32, device=self.device)
+        if out_key is None:
+            out_key = torch.empty((Q, k), dtype=torch.float32, device=self.device)
+        _check(lib().kb_query_sampled(self._h, _ptr(queries), _CODE_OF[queries.dtype], Q, _ptr(qmask), k, _ptr(gain),
+                                      ctypes.c_float(temperature), ctypes.c_uint64(seed & 0xFFFFFFFFFFFFFFFF), first_query,
+                                      _ptr(out_index), _ptr(out_key), _ptr(self._workspace), self._workspace.numel(), _stream()),
+               "kb_query_sampled")
+        return out_index, out_key
 
     def counters(self) -> dict:
         out = (ctypes.c_int64 * 4)()

@@ -32,7 +32,7 @@ def test_every_declared_symbol_is_exported(L):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(kb_[a-z_]+)\s*\(", header))
     assert {"kb_create", "kb_append", "kb_normalize", "kb_query_workspace_bytes", "kb_query", "kb_size",
-            "kb_destroy", "kb_status_string", "kb_query_counters", "kb_set_tuning"} <= names
+            "kb_destroy", "kb_status_string", "kb_query_counters", "kb_set_tuning", "kb_query_sampled"} <= names
     for n in names:
         assert hasattr(L, n), f"{n} is declared in kb.h but not exported by libkb.so"
 
@@ -81,6 +81,15 @@ def test_append_and_query_argument_errors(L):
     assert q(Q=0) == 2 and q(k=0) == 2 and q(k=129) == 2
     assert q(queries=ctypes.c_void_p((1 << 20) + 8)) == 2
     assert q(w=None) == 7 and q(w=ctypes.c_void_p((1 << 20) + 64)) == 7             # KB_ERR_WORKSPACE
+
+    def qs(gain=FAKE, T=0.1, first=0, **kw):
+        return L.kb_query_sampled(kw.get("handle", h), FAKE, kbmod.KB_BF16, kw.get("Q", 8), None, 4, gain, ctypes.c_float(T),
+                                  ctypes.c_uint64(1), first, FAKE, FAKE, FAKE, ws, None)
+
+    assert qs(gain=None) == 1                                                        # the weighted draw needs gains
+    assert qs(T=0.0) == 2 and qs(T=-1.0) == 2 and qs(T=float("nan")) == 2 and qs(T=float("inf")) == 2
+    assert qs(first=-1) == 2 and qs(gain=ctypes.c_void_p((1 << 20) + 2)) == 2
+    assert qs(handle=None) == 1 and qs(Q=0) == 2                                     # then the checks of kb_query
     assert L.kb_destroy(h) == 0 and L.kb_destroy(None) == 1
 
     st, h2 = _create(L, cap=100)                                                      # untagged
