@@ -23,6 +23,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+DRAW_TEMPERATURE = 0.05
+# Vector-ALU roof for the weighted random selection: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second.
+VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+# Lane-instructions per (query, entry) pair of the key computation: a quarter of a 10-round Philox4x32 call (20), the
+# uniform variate (3), two logarithms with their scalings and negations (6), score scaling (3), key (2), test (2).
+DRAW_OPS_PER_PAIR = 36
 # HBM bytes per launch of the main-pass scan kernel on the default workload with the default kernel choice, from
 # rocprofv3 --pmc FETCH_SIZE (x 2.0: what the same counter under-reads on a copy of known size) and WRITE_SIZE (x 1.0).
 # Applies to that workload and kernel only.
@@ -154,6 +160,9 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="capture one kb_query in a HIP graph and time replays (for the launch-latency-bound workloads; "
                          "the scan kernel is then not timed on its own)")
+    ap.add_argument("--draw", action="store_true",
+                    help="time the weighted random selection (kb_query_sampled: gains uniform in [0.25, 4], temperature "
+                         "0.05) instead of the plain top-k")
     ap.add_argument("--q-sweep", action="store_true", help="time query batches of 1..512 on the N=2^20 bf16 knowledge base instead")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -194,6 +203,16 @@ def main():
     Q, k, N, d = w.Q, w.k, w.N, w.d
     out_i = torch.empty((Q, k), dtype=torch.int32, device=dev)
     out_s = torch.empty((Q, k), dtype=torch.float32, device=dev)
+    if args.draw:
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(args.seed + 17)
+        gain = torch.empty(N, dtype=torch.float32, device=dev).uniform_(0.25, 4.0, generator=gen)
+
+        def draw_step(queries, k, qmask, out_i, out_s):
+            return kb.query_sampled(queries, k, gain, DRAW_TEMPERATURE, args.seed, qmask, 0, out_i, out_s)
+
+        kb.query = draw_step      # every call below times the draw
+        desc += f"; weighted random selection, temperature {DRAW_TEMPERATURE}"
 
     for _ in range(args.warmup):
         kb.query(queries, k, qmask, out_i, out_s)
@@ -275,6 +294,13 @@ def main():
                      "kernel_ms": scan_ms, "algorithmic_bytes": scan_bytes, "launches_timed": scan_calls},
     }
 
+    if args.draw:
+        ops = float(DRAW_OPS_PER_PAIR) * Q * N
+        result["roofline"] = {"bound": "alu", "kernel": "scan kernel, main pass, keys of the weighted random selection",
+                              "achieved": ops / (scan_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TOPS, "unit": "Tops/s",
+                              "frac": ops / (scan_ms * 1e-3) / 1e12 / VALU_PEAK_TOPS, "traffic": None, "kernel_ms": scan_ms,
+                              "algorithmic_ops": ops, "launches_timed": scan_calls}
+
     if not args.no_cpu_baseline:
         # the oracle, as it stands, on the first `oracle_queries` queries of the same batch against all N keys
         from oracle import compare, kb_oracle
@@ -290,8 +316,12 @@ def main():
         oi, osc, full = kb_oracle.query(key_bits, okind, q_bits, kb_oracle.F32 if code == kbmod.KB_F32 else kb_oracle.BF16, k,
                                         row_scale=None if w.scale is None else w.scale.cpu().numpy(), tags=tags, qmask=qm,
                                         return_scores=True)
+        if args.draw:       # keys of the same draw from the fp64 scores; selection is part of the timed work
+            full = kb_oracle.selection_keys(full, gain.cpu().numpy(), DRAW_TEMPERATURE, args.seed, 0)
+            for r in range(nq):
+                kb_oracle.select(full[r], k, tags=tags, qmask=None if qm is None else qm[r])
         c1 = time.perf_counter()
-        tau = {kbmod.KB_F32: 1e-5, kbmod.KB_BF16: 2e-3, kbmod.KB_FP8_E4M3: 2e-2}[code]
+        tau = 2e-4 if args.draw else {kbmod.KB_F32: 1e-5, kbmod.KB_BF16: 2e-3, kbmod.KB_FP8_E4M3: 2e-2}[code]
         rep = compare.check(gi[:nq], gs[:nq], full, k, tau, tags=tags, qmask=qm, label="bench parity")   # raises on mismatch
         result["cpu_baseline"] = {"value": nq / (c1 - c0), "unit": "queries/s", "cores": kb_oracle.num_threads(), "kind": "oracle",
                                   "sample": f"first {nq} of the {Q} queries against all {N} keys (fp64 brute force + full sort), "
