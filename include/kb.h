@@ -99,7 +99,10 @@ size_t kb_query_workspace_bytes(const kb_t *kb, int32_t Q, int32_t k);
 /*
  * Retrieval (Section 3: State Selector + top-k of the Optimization Selector).
  *   queries_dev [Q, d] row-major, 16-byte aligned; q_dtype must equal the key dtype, except that
- *               KB_FP8_E4M3 keys take KB_BF16 queries
+ *               KB_FP8_E4M3 keys take KB_BF16 queries, or KB_FP8_E4M3 queries when d >= 384 (else
+ *               KB_ERR_INVALID_ARG).  fp8 queries are e4m3 codes without a scale (a positive factor per query
+ *               row cancels in the cosine); their dot products are formed by the fp8 matrix instruction,
+ *               whose 64-term sums are slightly less precise than fp32 (score error up to about 1e-4).
  *   qmask_dev   [Q] uint64, or NULL = no filtering for any query (a zero mask word qualifies nothing)
  *   k           1 .. KB_K_MAX
  *   indices_out_dev [Q, k] int32, scores_out_dev [Q, k] fp32: the result defined at the top of this file,
@@ -128,7 +131,8 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
  *   indices_out_dev [Q, k] int32 and keys_out_dev [Q, k] fp32: drawn entries ordered by (key descending, index
  *               ascending), padded with (-1, -inf) when fewer than k entries qualify.  Keys are computed in fp32
  *               from the fp32 score of kb_query.
- * Everything else (queries, q_dtype, qmask, k, workspace = kb_query_workspace_bytes, stream, errors) as kb_query.
+ * Everything else (queries, q_dtype, qmask, k, workspace = kb_query_workspace_bytes, stream, errors) as kb_query,
+ * except that KB_FP8_E4M3 queries are not accepted (KB_ERR_DTYPE).
  */
 kb_status_t kb_query_sampled(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int32_t Q, const uint64_t *qmask_dev,
                              int32_t k, const float *gain_dev, float temperature, uint64_t seed, int32_t first_query,

@@ -114,7 +114,8 @@ int oracle_score_matrix(const void *keys, int key_dtype, const float *row_scale,
 {
     if (!keys || !queries || !scores || N < 0 || Q < 0 || d <= 0)
         return 1;
-    if (key_dtype < 0 || key_dtype > 2 || q_dtype < 0 || q_dtype > 1)
+    /* queries in e4m3 carry no row scale: a positive factor per query row cancels in the cosine */
+    if (key_dtype < 0 || key_dtype > 2 || q_dtype < 0 || q_dtype > 2)
         return 1;
     double *qd = (double *)malloc(sizeof(double) * (size_t)(Q > 0 ? Q : 1) * (size_t)d);
     double *qn = (double *)malloc(sizeof(double) * (size_t)(Q > 0 ? Q : 1));

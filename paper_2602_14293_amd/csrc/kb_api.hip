@@ -66,6 +66,7 @@ bool scan_config_info(int key_dtype, int config, ConfigInfo *out)
     }
     KB_SCAN_SP_CONFIGS_BF16(XS)
     KB_SCAN_SP_CONFIGS_FP8(XS)
+    KB_SCAN_SP_CONFIGS_FP8_Q8(XS)
 #undef XS
     return false;
 }
@@ -87,6 +88,7 @@ constexpr int MAX_CAND_CAP = 8192;     // finalize_kernel likewise
 constexpr int MIN_CAND_CAP = 1024;
 constexpr int CAND_SEGMENTS = 16;     // per-query candidate list = this many independently counted segments
 constexpr size_t WS_ALIGN = 256;
+constexpr int FP8_QUERY_CONFIG = 5;    // scan configuration of fp8 keys with fp8 queries (kb_configs.hpp)
 constexpr int STAT_WORDS = 4;          // candidates, exhaustive queries, sample keys, scan workgroups
 constexpr int STAT_PARTIALS = 64;      // the candidate count is kept as this many partial sums (one hot address would serialise)
 
@@ -102,22 +104,29 @@ size_t align_up(size_t x) { return (x + WS_ALIGN - 1) / WS_ALIGN * WS_ALIGN; }
 
 // Pure function of (handle settings, row count n, Q, k): which kernels run on what, and where
 // everything lives in the workspace.
-bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, bool draw, Plan *out)
+bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, bool draw, bool q8, Plan *out)
 {
     Plan p;
     memset(&p, 0, sizeof p);
     p.Q = Q;
     p.k = k;
-    p.config = h->tune_config > 0 ? (int)h->tune_config : scan_config_for(h->dtype, Q, h->d);
     ConfigInfo ci;
-    if (!scan_config_info(h->dtype, p.config, &ci)) return false;
-    if (draw && ci.family != 0) {       // the weighted random selection exists in the tiled kernel only
-        p.config = Q <= 32 ? 1 : Q <= 128 ? 2 : 3;
+    const int generic = Q <= 32 ? 1 : Q <= 128 ? 2 : 3;        // the tiled kernel: every dtype, every row length
+    const size_t row_bytes = (size_t)h->d * key_bytes(h->dtype);
+    if (q8) {       // fp8 queries: only the kernel built on the fp8 matrix instruction takes them
+        if (draw || h->dtype != KB_FP8_E4M3) return false;
+        p.config = FP8_QUERY_CONFIG;
+        if (!scan_config_info(h->dtype, p.config, &ci) || row_bytes < (size_t)ci.min_row_bytes) return false;
+    } else {
+        p.config = h->tune_config > 0 ? (int)h->tune_config : scan_config_for(h->dtype, Q, h->d);
         if (!scan_config_info(h->dtype, p.config, &ci)) return false;
-    }
-    if (h->d * key_bytes(h->dtype) < ci.min_row_bytes) {     // a forced configuration the rows are too short for
-        p.config = Q <= 32 ? 1 : Q <= 128 ? 2 : 3;
-        if (!scan_config_info(h->dtype, p.config, &ci)) return false;
+        // fall back where a (forced) configuration does not apply: the weighted random selection exists in the
+        // tiled kernel only, rows may be too short for a pipelined kernel, and the fp8-query kernel reads fp8 queries
+        if ((draw && ci.family != 0) || row_bytes < (size_t)ci.min_row_bytes ||
+            (h->dtype == KB_FP8_E4M3 && p.config == FP8_QUERY_CONFIG)) {
+            p.config = generic;
+            if (!scan_config_info(h->dtype, p.config, &ci)) return false;
+        }
     }
     p.family = ci.family;
     p.tk = ci.tk;
@@ -286,7 +295,7 @@ template <int QT> __global__ __launch_bounds__(256) void prep_kernel(const void 
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row < qpad) {
-        const float inv = row < Q ? row_inv_norm<QT>(queries, row, d * (QT == KB_F32 ? 4 : 2), lane) : 0.f;
+        const float inv = row < Q ? row_inv_norm<QT>(queries, row, d * (QT == KB_F32 ? 4 : QT == KB_BF16 ? 2 : 1), lane) : 0.f;
         if (lane == 0) invq[row] = inv;
     }
 }
@@ -531,17 +540,22 @@ struct FinalArgs {
     DrawArgs draw;
 };
 
+// KT = KT_FP8_Q8 stands for fp8 keys with fp8 queries (one fp8 matrix instruction per 64-byte chunk, as in the scan).
+constexpr int KT_FP8_Q8 = 3;
+typedef int i32x8 __attribute__((ext_vector_type(8)));
 template <int KT> __device__ void exhaustive_query(const FinalArgs &a, int q, uint64_t *buf, uint32_t *ctl)
 {
-    constexpr int KEY_BYTES = KeyTraits<KT>::KEY_BYTES, BMUL = KeyTraits<KT>::QRY_BYTES / KeyTraits<KT>::KEY_BYTES;
+    constexpr bool Q8 = KT == KT_FP8_Q8;
+    constexpr int KTT = Q8 ? (int)KB_FP8_E4M3 : KT;
+    constexpr int KEY_BYTES = KeyTraits<KTT>::KEY_BYTES, QRY_BYTES = Q8 ? 1 : KeyTraits<KTT>::QRY_BYTES, BMUL = QRY_BYTES / KEY_BYTES;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lrow = lane & 31, half = lane >> 5;
     const int cap = a.cand_cap;
     const bool filter = a.qmask != nullptr;
     const uint64_t qm = filter ? a.qmask[q] : 0;
     const float iq = a.invq[q];
     const size_t key_row_bytes = (size_t)a.d * KEY_BYTES;
-    const unsigned char *qrow = static_cast<const unsigned char *>(a.queries) + (size_t)q * a.d * KeyTraits<KT>::QRY_BYTES;
-    const int n_groups = (int)(key_row_bytes / 32);
+    const unsigned char *qrow = static_cast<const unsigned char *>(a.queries) + (size_t)q * a.d * QRY_BYTES;
+    const int n_groups = (int)(key_row_bytes / (Q8 ? 64 : 32));
     uint64_t *thr_local = reinterpret_cast<uint64_t *>(ctl + 2);   // ctl[0] = count, ctl[2..3] = threshold word
     if (tid == 0) {
         ctl[0] = 0;
@@ -555,12 +569,27 @@ template <int KT> __device__ void exhaustive_query(const FinalArgs &a, int q, ui
         f32x16 acc;
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-        for (int g = 0; g < n_groups; ++g) {
-            const u32x4 av = *reinterpret_cast<const u32x4 *>(krow + (size_t)g * 32);
-            const unsigned char *qp = qrow + (size_t)g * 32 * BMUL + half * 16 * BMUL;
-            const u32x4 b0 = *reinterpret_cast<const u32x4 *>(qp);
-            const u32x4 b1 = BMUL == 2 ? *reinterpret_cast<const u32x4 *>(qp + 16) : b0;
-            Mma<KT>::run(acc, Mma<KT>::prepare(av), b0, b1);
+        if constexpr (Q8) {
+            // one fp8 matrix instruction per 64-byte chunk: lane half h supplies bytes [32h, 32h+32) of its key row
+            // and of the query row, the operand layout the scan uses, so both paths give the same bits
+            const unsigned char *kp = krow + half * 16;
+            for (int g = 0; g < n_groups; ++g) {
+                const u32x4 a0 = *reinterpret_cast<const u32x4 *>(kp + (size_t)g * 64);
+                const u32x4 a1 = *reinterpret_cast<const u32x4 *>(kp + (size_t)g * 64 + 16);
+                const u32x4 b0 = *reinterpret_cast<const u32x4 *>(qrow + (size_t)g * 64 + half * 32);
+                const u32x4 b1 = *reinterpret_cast<const u32x4 *>(qrow + (size_t)g * 64 + half * 32 + 16);
+                const i32x8 av = {(int)a0[0], (int)a0[1], (int)a0[2], (int)a0[3], (int)a1[0], (int)a1[1], (int)a1[2], (int)a1[3]};
+                const i32x8 bv = {(int)b0[0], (int)b0[1], (int)b0[2], (int)b0[3], (int)b1[0], (int)b1[1], (int)b1[2], (int)b1[3]};
+                acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, bv, acc, 0, 0, 0, 0, 0, 0);
+            }
+        } else {
+            for (int g = 0; g < n_groups; ++g) {
+                const u32x4 av = *reinterpret_cast<const u32x4 *>(krow + (size_t)g * 32);
+                const unsigned char *qp = qrow + (size_t)g * 32 * BMUL + half * 16 * BMUL;
+                const u32x4 b0 = *reinterpret_cast<const u32x4 *>(qp);
+                const u32x4 b1 = BMUL == 2 ? *reinterpret_cast<const u32x4 *>(qp + 16) : b0;
+                Mma<KTT>::run(acc, Mma<KTT>::prepare(av), b0, b1);
+            }
         }
         // every column holds the same query; lanes 0..15 of each half own one row each
         float v = acc[0];
@@ -735,17 +764,19 @@ size_t kb_query_workspace_bytes(const kb_t *kb, int32_t Q, int32_t k)
     for (int64_t n = kb->capacity; n >= 1; n = n / 2) {
         Plan p;
         for (int draw = 0; draw < 2; ++draw) {
-            if (!make_plan(kb, n, Q, k, draw != 0, &p)) return 0;
+            if (!make_plan(kb, n, Q, k, draw != 0, false, &p)) return 0;
             if (p.total > best) best = p.total;
         }
+        if (make_plan(kb, n, Q, k, false, true, &p) && p.total > best) best = p.total;     // fp8 queries, where they apply
         if (n == 1) break;
     }
     for (int64_t n = 1; n <= kb->capacity && n < (int64_t)1 << 16; n += 61) {   // and the small, irregular sizes
         Plan p;
         for (int draw = 0; draw < 2; ++draw) {
-            if (!make_plan(kb, n, Q, k, draw != 0, &p)) return 0;
+            if (!make_plan(kb, n, Q, k, draw != 0, false, &p)) return 0;
             if (p.total > best) best = p.total;
         }
+        if (make_plan(kb, n, Q, k, false, true, &p) && p.total > best) best = p.total;
     }
     return best;
 }
@@ -760,9 +791,15 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
     if (!kb || !queries_dev || !indices_out_dev || !scores_out_dev) return KB_ERR_NULL;
     if (!valid_dtype((int)q_dtype)) return KB_ERR_DTYPE;
     const kb_dtype_t want_q = kb->dtype == KB_F32 ? KB_F32 : KB_BF16;
-    if (q_dtype != want_q) return KB_ERR_DTYPE;
+    const bool q8 = kb->dtype == KB_FP8_E4M3 && q_dtype == KB_FP8_E4M3;     // fp8 queries against fp8 keys
+    if (q_dtype != want_q && !q8) return KB_ERR_DTYPE;
+    if (q8 && draw) return KB_ERR_DTYPE;
     if (Q < 1 || k < 1 || k > KB_K_MAX) return KB_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(queries_dev) & 15) != 0) return KB_ERR_INVALID_ARG;
+    if (q8) {       // the one kernel that takes fp8 queries needs rows of at least its ring's length
+        ConfigInfo ci;
+        if (!scan_config_info(KB_FP8_E4M3, FP8_QUERY_CONFIG, &ci) || kb->d < ci.min_row_bytes) return KB_ERR_INVALID_ARG;
+    }
     if (qmask_dev && !kb->tags) return KB_ERR_NO_TAGS;
     if (kb->n_normalized != kb->n) return KB_ERR_NOT_NORMALIZED;
     if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) & (WS_ALIGN - 1)) != 0) return KB_ERR_WORKSPACE;
@@ -773,7 +810,7 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
         kb->cu_count = cus < ASSUMED_CUS ? cus : ASSUMED_CUS;
     }
     Plan p;
-    if (!make_plan(kb, kb->n, Q, k, draw, &p)) return KB_ERR_INVALID_ARG;
+    if (!make_plan(kb, kb->n, Q, k, draw, q8, &p)) return KB_ERR_INVALID_ARG;
     if (workspace_bytes < p.total) return KB_ERR_WORKSPACE;
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -811,6 +848,8 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
         const unsigned grid = blocks_rows > blocks_init ? blocks_rows : blocks_init;
         if (q_dtype == KB_F32)
             hipLaunchKernelGGL(prep_kernel<KB_F32>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, region_cnt, p.regions, stats, (uint64_t)p.sample_keys, qmask_dev, qmask_pad, p.grid);
+        else if (q_dtype == KB_FP8_E4M3)
+            hipLaunchKernelGGL(prep_kernel<KB_FP8_E4M3>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, region_cnt, p.regions, stats, (uint64_t)p.sample_keys, qmask_dev, qmask_pad, p.grid);
         else
             hipLaunchKernelGGL(prep_kernel<KB_BF16>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, region_cnt, p.regions, stats, (uint64_t)p.sample_keys, qmask_dev, qmask_pad, p.grid);
         if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
@@ -887,18 +926,21 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
     f.cand_cap = p.cand_cap;
     f.draw = dr;
     const size_t fin_lds = (size_t)p.cand_cap * 8 + 16 + sizeof(SelectScratch);
-    static bool fin_attr[3] = {false, false, false};
-    const void *fin_fn = kb->dtype == KB_F32 ? reinterpret_cast<const void *>(&finalize_kernel<KB_F32>)
-                       : kb->dtype == KB_BF16 ? reinterpret_cast<const void *>(&finalize_kernel<KB_BF16>)
-                                              : reinterpret_cast<const void *>(&finalize_kernel<KB_FP8_E4M3>);
-    if (!fin_attr[kb->dtype]) {
+    static bool fin_attr[4] = {false, false, false, false};
+    const int fin_kind = q8 ? KT_FP8_Q8 : (int)kb->dtype;
+    const void *fin_fn = fin_kind == KB_F32 ? reinterpret_cast<const void *>(&finalize_kernel<KB_F32>)
+                       : fin_kind == KB_BF16 ? reinterpret_cast<const void *>(&finalize_kernel<KB_BF16>)
+                       : fin_kind == KB_FP8_E4M3 ? reinterpret_cast<const void *>(&finalize_kernel<KB_FP8_E4M3>)
+                                                 : reinterpret_cast<const void *>(&finalize_kernel<KT_FP8_Q8>);
+    if (!fin_attr[fin_kind]) {
         if (hipFuncSetAttribute(fin_fn, hipFuncAttributeMaxDynamicSharedMemorySize, MAX_CAND_CAP * 8 + 16 + sizeof(SelectScratch)) != hipSuccess) return KB_ERR_DEVICE;
-        fin_attr[kb->dtype] = true;
+        fin_attr[fin_kind] = true;
     }
-    switch (kb->dtype) {
+    switch (fin_kind) {
     case KB_F32: hipLaunchKernelGGL(finalize_kernel<KB_F32>, dim3(Q), dim3(256), fin_lds, s, f); break;
     case KB_BF16: hipLaunchKernelGGL(finalize_kernel<KB_BF16>, dim3(Q), dim3(256), fin_lds, s, f); break;
-    default: hipLaunchKernelGGL(finalize_kernel<KB_FP8_E4M3>, dim3(Q), dim3(256), fin_lds, s, f); break;
+    case KB_FP8_E4M3: hipLaunchKernelGGL(finalize_kernel<KB_FP8_E4M3>, dim3(Q), dim3(256), fin_lds, s, f); break;
+    default: hipLaunchKernelGGL(finalize_kernel<KT_FP8_Q8>, dim3(Q), dim3(256), fin_lds, s, f); break;
     }
     if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
     return KB_OK;

@@ -39,3 +39,6 @@
     XS(16, KB_BF16, 128, 6, 4)
 #define KB_SCAN_SP_CONFIGS_FP8(XS)  \
     XS(4, KB_FP8_E4M3, 256, 3, 3)
+// ... with fp8 queries as well (the fp8 matrix instruction): XQ(id, key dtype, TQ, NSA, NSB)
+#define KB_SCAN_SP_CONFIGS_FP8_Q8(XQ) \
+    XQ(5, KB_FP8_E4M3, 256, 5, 4)

@@ -39,10 +39,11 @@ __device__ inline u32x4 widen_e4m3_hi(u32x4 a)
     return u32x4{e4m3_pair_to_bf16(a.z, false), e4m3_pair_to_bf16(a.z, true), e4m3_pair_to_bf16(a.w, false), e4m3_pair_to_bf16(a.w, true)};
 }
 
-template <int KT_, int TQ_, int NSA_, int NSB_> struct SPCfg {
+template <int KT_, int TQ_, int NSA_, int NSB_, bool QF8_ = false> struct SPCfg {
     static constexpr int KT = KT_, TQ = TQ_, NSA = NSA_, NSB = NSB_;       // query block; ring depths in chunks: keys, queries
+    static constexpr bool QF8 = QF8_;                                      // fp8 keys AND fp8 queries: the fp8 matrix instruction
     static constexpr int TK = 256, THREADS = 512, NW = 8;
-    static constexpr int KEY_BYTES = KeyTraits<KT>::KEY_BYTES, QRY_BYTES = KeyTraits<KT>::QRY_BYTES;
+    static constexpr int KEY_BYTES = KeyTraits<KT>::KEY_BYTES, QRY_BYTES = QF8 ? 1 : KeyTraits<KT>::QRY_BYTES;
     static constexpr int BMUL = QRY_BYTES / KEY_BYTES;                     // 2 for fp8 keys with bf16 queries
     static constexpr int RBA = 64, RBB = RBA * BMUL;                       // bytes of a key / query row per chunk
     static constexpr int PPRB = RBB / 16;
@@ -66,7 +67,7 @@ template <int KT_, int TQ_, int NSA_, int NSB_> struct SPCfg {
     static constexpr int GROUPS_PER_TILE = 8;                // sampling groups: 4 row blocks x 2 lane halves
     static constexpr int MIN_ROW_BYTES = RBA * ((NSA > NSB ? NSA : NSB) + 1);   // the side-data buffers alternate safely only then
     static_assert(TQ == 256 || TQ == 128, "query blocks of 256 or 128");
-    static_assert((KT == KB_BF16 && BMUL == 1) || (KT == KB_FP8_E4M3 && BMUL == 2 && TQ == 256), "key types the kernel is written for");
+    static_assert((KT == KB_BF16 && BMUL == 1 && !QF8) || (KT == KB_FP8_E4M3 && TQ == 256 && (BMUL == 2 || QF8)), "key types the kernel is written for");
     static_assert(NSA >= 3 && NSA <= 6 && NSB >= 3 && NSB <= 6, "ring depths the waits are written for");
     static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget");
 };
@@ -248,13 +249,15 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
     bare_barrier();                         // barrier 0
     u32x4 xa[IB], xb[JB], ya[IB], yb[JB];
     u32x4 ra[IB];                               // fp8 keys: raw fragments of the k-group whose low half is in X
+    if constexpr (!C::QF8) {
 #pragma unroll
-    for (int ib = 0; ib < IB; ++ib) {
-        ra[ib] = read_a(0, 0, ib);
-        xa[ib] = C::BMUL == 2 ? widen_e4m3_lo(ra[ib]) : ra[ib];
+        for (int ib = 0; ib < IB; ++ib) {
+            ra[ib] = read_a(0, 0, ib);
+            xa[ib] = C::BMUL == 2 ? widen_e4m3_lo(ra[ib]) : ra[ib];
+        }
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb) xb[jb] = read_b(0, 0, jb);
     }
-#pragma unroll
-    for (int jb = 0; jb < JB; ++jb) xb[jb] = read_b(0, 0, jb);
     if (group == 1) issue_round();          // waves 4-7 run their load part ahead of the compute part
 
     int tile = vb / nqb, qb = vb % nqb, par = 0;
@@ -266,128 +269,22 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
     acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, SA[I]), __builtin_bit_cast(bf16x8, SB[J]), \
                                                         acc[I][J], 0, 0, 0);                                                  \
     __builtin_amdgcn_sched_barrier(0)
-    for (int g = 0; g < total; ++g) {
-        // Waves 0-3: compute(g), load(g), barrier.  Waves 4-7: [load(g) was done before the previous barrier's
-        // successor, see below] compute(g), barrier, load(g+1).  One code path, two barrier positions.
-        const int c_now = c, qb_now = qb;
-        {
-            const int nA = stageA + 1 == C::NSA ? 0 : stageA + 1, nB = stageB + 1 == C::NSB ? 0 : stageB + 1;
-            // past the last chunk the refill of X reads the current slot again (valid memory, values unused)
-            const int xA = g + 1 < total ? nA : stageA, xB = g + 1 < total ? nB : stageB;
-            __builtin_amdgcn_s_setprio(1);
-            if constexpr (C::BMUL == 2) {
-                // fp8 keys: the 16 key bytes a lane holds per k-group widen to two bf16 operands ("lo" = bytes 0-7,
-                // "hi" = bytes 8-15), each paired with its own 16-byte query piece.  A chunk is therefore four steps of
-                // eight MFMAs (kg0 lo, kg0 hi, kg1 lo, kg1 hi: the accumulation order of every other kernel); X serves
-                // the lo steps, Y the hi steps, and each is refilled while the other is in use.  ra holds the raw key
-                // fragments of the k-group whose lo half is in X.
-#define KB_SP_8MFMA(SA, SB, R0, R1, R2)                                             \
-    KB_SP_MFMA(SA, SB, 0, 0); R0; __builtin_amdgcn_sched_barrier(0);                \
-    KB_SP_MFMA(SA, SB, 0, 1); R1; __builtin_amdgcn_sched_barrier(0);                \
-    KB_SP_MFMA(SA, SB, 1, 0); R2; __builtin_amdgcn_sched_barrier(0);                \
-    KB_SP_MFMA(SA, SB, 1, 1); KB_SP_MFMA(SA, SB, 0, 2); KB_SP_MFMA(SA, SB, 1, 2);   \
-    KB_SP_MFMA(SA, SB, 0, 3); KB_SP_MFMA(SA, SB, 1, 3)
-                // kg0 lo; refill Y with kg0 hi
-                KB_SP_8MFMA(xa, xb, (yb[0] = read_b(stageB, 0, 0, 1), yb[1] = read_b(stageB, 0, 1, 1)),
-                            (yb[2] = read_b(stageB, 0, 2, 1), yb[3] = read_b(stageB, 0, 3, 1)),
-                            (ya[0] = widen_e4m3_hi(ra[0]), ya[1] = widen_e4m3_hi(ra[1])));
-                // kg0 hi; refill X with kg1 lo
-                KB_SP_8MFMA(ya, yb, (ra[0] = read_a(stageA, 1, 0), ra[1] = read_a(stageA, 1, 1)),
-                            (xb[0] = read_b(stageB, 1, 0), xb[1] = read_b(stageB, 1, 1)),
-                            (xb[2] = read_b(stageB, 1, 2), xb[3] = read_b(stageB, 1, 3)));
-                xa[0] = widen_e4m3_lo(ra[0]);
-                xa[1] = widen_e4m3_lo(ra[1]);
-                __builtin_amdgcn_sched_barrier(0);
-                // kg1 lo; refill Y with kg1 hi
-                KB_SP_8MFMA(xa, xb, (yb[0] = read_b(stageB, 1, 0, 1), yb[1] = read_b(stageB, 1, 1, 1)),
-                            (yb[2] = read_b(stageB, 1, 2, 1), yb[3] = read_b(stageB, 1, 3, 1)),
-                            (ya[0] = widen_e4m3_hi(ra[0]), ya[1] = widen_e4m3_hi(ra[1])));
-                // kg1 hi; refill X with kg0 lo of the next chunk
-                KB_SP_8MFMA(ya, yb, (ra[0] = read_a(xA, 0, 0), ra[1] = read_a(xA, 0, 1)),
-                            (xb[0] = read_b(xB, 0, 0), xb[1] = read_b(xB, 0, 1)),
-                            (xb[2] = read_b(xB, 0, 2), xb[3] = read_b(xB, 0, 3)));
-                xa[0] = widen_e4m3_lo(ra[0]);
-                xa[1] = widen_e4m3_lo(ra[1]);
-                __builtin_amdgcn_sched_barrier(0);
-#undef KB_SP_8MFMA
-            } else if constexpr (JB == 4) {
-            // The reads sit behind the first three MFMAs of each half: the remaining five cover their latency, and the
-                // MFMA order lets the next half start on the fragments that were read first.
-                KB_SP_MFMA(xa, xb, 0, 0);
-                ya[0] = read_a(stageA, 1, 0);
-                yb[0] = read_b(stageB, 1, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                KB_SP_MFMA(xa, xb, 0, 1);
-                yb[1] = read_b(stageB, 1, 1);
-                ya[1] = read_a(stageA, 1, 1);
-                __builtin_amdgcn_sched_barrier(0);
-                KB_SP_MFMA(xa, xb, 1, 0);
-                yb[2] = read_b(stageB, 1, 2);
-                yb[3] = read_b(stageB, 1, 3);
-                __builtin_amdgcn_sched_barrier(0);
-                KB_SP_MFMA(xa, xb, 1, 1);
-                KB_SP_MFMA(xa, xb, 0, 2);
-                KB_SP_MFMA(xa, xb, 1, 2);
-                KB_SP_MFMA(xa, xb, 0, 3);
-                KB_SP_MFMA(xa, xb, 1, 3);
-
-                KB_SP_MFMA(ya, yb, 0, 0);
-                xa[0] = read_a(xA, 0, 0);
-                xb[0] = read_b(xB, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                KB_SP_MFMA(ya, yb, 0, 1);
-                xb[1] = read_b(xB, 0, 1);
-                xa[1] = read_a(xA, 0, 1);
-                __builtin_amdgcn_sched_barrier(0);
-                KB_SP_MFMA(ya, yb, 1, 0);
-                xb[2] = read_b(xB, 0, 2);
-                xb[3] = read_b(xB, 0, 3);
-                __builtin_amdgcn_sched_barrier(0);
-                KB_SP_MFMA(ya, yb, 1, 1);
-                KB_SP_MFMA(ya, yb, 0, 2);
-                KB_SP_MFMA(ya, yb, 1, 2);
-                KB_SP_MFMA(ya, yb, 0, 3);
-                KB_SP_MFMA(ya, yb, 1, 3);
-            } else {
-                KB_SP_MFMA(xa, xb, 0, 0);
-                ya[0] = read_a(stageA, 1, 0);
-                yb[0] = read_b(stageB, 1, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                KB_SP_MFMA(xa, xb, 0, 1);
-                yb[1] = read_b(stageB, 1, 1);
-                ya[1] = read_a(stageA, 1, 1);
-                __builtin_amdgcn_sched_barrier(0);
-                KB_SP_MFMA(xa, xb, 1, 0);
-                KB_SP_MFMA(xa, xb, 1, 1);
-
-                KB_SP_MFMA(ya, yb, 0, 0);
-                xa[0] = read_a(xA, 0, 0);
-                xb[0] = read_b(xB, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                KB_SP_MFMA(ya, yb, 0, 1);
-                xb[1] = read_b(xB, 0, 1);
-                xa[1] = read_a(xA, 0, 1);
-                __builtin_amdgcn_sched_barrier(0);
-                KB_SP_MFMA(ya, yb, 1, 0);
-                KB_SP_MFMA(ya, yb, 1, 1);
-            }
-            __builtin_amdgcn_s_setprio(0);
-
-            stageA = nA;
-            stageB = nB;
-            if (++c == NC) {
-                pending = true;
-                e_tile = tile;
-                e_qb = qb;
-                e_par = par;
-                c = 0;
-                par ^= 1;
-                tile += step_tile;
-                qb += step_qb;
-                if (qb >= nqb) {
-                    qb -= nqb;
-                    ++tile;
-                }
+    // what follows an iteration's MFMAs: bookkeeping, then (in the order of the wave's kind) barrier and load part
+    auto finish_iteration = [&](int c_now, int qb_now) {
+        stageA = stageA + 1 == C::NSA ? 0 : stageA + 1;
+        stageB = stageB + 1 == C::NSB ? 0 : stageB + 1;
+        if (++c == NC) {
+            pending = true;
+            e_tile = tile;
+            e_qb = qb;
+            e_par = par;
+            c = 0;
+            par ^= 1;
+            tile += step_tile;
+            qb += step_qb;
+            if (qb >= nqb) {
+                qb -= nqb;
+                ++tile;
             }
         }
         if (group == 1) {
@@ -412,6 +309,186 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
             __builtin_amdgcn_sched_barrier(0);
             bare_barrier();
             __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    if constexpr (!C::QF8) {
+        for (int g = 0; g < total; ++g) {
+            // Waves 0-3: compute(g), load(g), barrier.  Waves 4-7: [load(g) was done before the previous barrier's
+            // successor, see below] compute(g), barrier, load(g+1).  One code path, two barrier positions.
+            const int c_now = c, qb_now = qb;
+            {
+                const int nA = stageA + 1 == C::NSA ? 0 : stageA + 1, nB = stageB + 1 == C::NSB ? 0 : stageB + 1;
+                // past the last chunk the refill of X reads the current slot again (valid memory, values unused)
+                const int xA = g + 1 < total ? nA : stageA, xB = g + 1 < total ? nB : stageB;
+                __builtin_amdgcn_s_setprio(1);
+                if constexpr (C::BMUL == 2) {
+                    // fp8 keys: the 16 key bytes a lane holds per k-group widen to two bf16 operands ("lo" = bytes 0-7,
+                    // "hi" = bytes 8-15), each paired with its own 16-byte query piece.  A chunk is therefore four steps of
+                    // eight MFMAs (kg0 lo, kg0 hi, kg1 lo, kg1 hi: the accumulation order of every other kernel); X serves
+                    // the lo steps, Y the hi steps, and each is refilled while the other is in use.  ra holds the raw key
+                    // fragments of the k-group whose lo half is in X.
+#define KB_SP_8MFMA(SA, SB, R0, R1, R2)                                             \
+        KB_SP_MFMA(SA, SB, 0, 0); R0; __builtin_amdgcn_sched_barrier(0);                \
+        KB_SP_MFMA(SA, SB, 0, 1); R1; __builtin_amdgcn_sched_barrier(0);                \
+        KB_SP_MFMA(SA, SB, 1, 0); R2; __builtin_amdgcn_sched_barrier(0);                \
+        KB_SP_MFMA(SA, SB, 1, 1); KB_SP_MFMA(SA, SB, 0, 2); KB_SP_MFMA(SA, SB, 1, 2);   \
+        KB_SP_MFMA(SA, SB, 0, 3); KB_SP_MFMA(SA, SB, 1, 3)
+                    // kg0 lo; refill Y with kg0 hi
+                    KB_SP_8MFMA(xa, xb, (yb[0] = read_b(stageB, 0, 0, 1), yb[1] = read_b(stageB, 0, 1, 1)),
+                                (yb[2] = read_b(stageB, 0, 2, 1), yb[3] = read_b(stageB, 0, 3, 1)),
+                                (ya[0] = widen_e4m3_hi(ra[0]), ya[1] = widen_e4m3_hi(ra[1])));
+                    // kg0 hi; refill X with kg1 lo
+                    KB_SP_8MFMA(ya, yb, (ra[0] = read_a(stageA, 1, 0), ra[1] = read_a(stageA, 1, 1)),
+                                (xb[0] = read_b(stageB, 1, 0), xb[1] = read_b(stageB, 1, 1)),
+                                (xb[2] = read_b(stageB, 1, 2), xb[3] = read_b(stageB, 1, 3)));
+                    xa[0] = widen_e4m3_lo(ra[0]);
+                    xa[1] = widen_e4m3_lo(ra[1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    // kg1 lo; refill Y with kg1 hi
+                    KB_SP_8MFMA(xa, xb, (yb[0] = read_b(stageB, 1, 0, 1), yb[1] = read_b(stageB, 1, 1, 1)),
+                                (yb[2] = read_b(stageB, 1, 2, 1), yb[3] = read_b(stageB, 1, 3, 1)),
+                                (ya[0] = widen_e4m3_hi(ra[0]), ya[1] = widen_e4m3_hi(ra[1])));
+                    // kg1 hi; refill X with kg0 lo of the next chunk
+                    KB_SP_8MFMA(ya, yb, (ra[0] = read_a(xA, 0, 0), ra[1] = read_a(xA, 0, 1)),
+                                (xb[0] = read_b(xB, 0, 0), xb[1] = read_b(xB, 0, 1)),
+                                (xb[2] = read_b(xB, 0, 2), xb[3] = read_b(xB, 0, 3)));
+                    xa[0] = widen_e4m3_lo(ra[0]);
+                    xa[1] = widen_e4m3_lo(ra[1]);
+                    __builtin_amdgcn_sched_barrier(0);
+#undef KB_SP_8MFMA
+                } else if constexpr (JB == 4) {
+                // The reads sit behind the first three MFMAs of each half: the remaining five cover their latency, and the
+                    // MFMA order lets the next half start on the fragments that were read first.
+                    KB_SP_MFMA(xa, xb, 0, 0);
+                    ya[0] = read_a(stageA, 1, 0);
+                    yb[0] = read_b(stageB, 1, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    KB_SP_MFMA(xa, xb, 0, 1);
+                    yb[1] = read_b(stageB, 1, 1);
+                    ya[1] = read_a(stageA, 1, 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    KB_SP_MFMA(xa, xb, 1, 0);
+                    yb[2] = read_b(stageB, 1, 2);
+                    yb[3] = read_b(stageB, 1, 3);
+                    __builtin_amdgcn_sched_barrier(0);
+                    KB_SP_MFMA(xa, xb, 1, 1);
+                    KB_SP_MFMA(xa, xb, 0, 2);
+                    KB_SP_MFMA(xa, xb, 1, 2);
+                    KB_SP_MFMA(xa, xb, 0, 3);
+                    KB_SP_MFMA(xa, xb, 1, 3);
+
+                    KB_SP_MFMA(ya, yb, 0, 0);
+                    xa[0] = read_a(xA, 0, 0);
+                    xb[0] = read_b(xB, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    KB_SP_MFMA(ya, yb, 0, 1);
+                    xb[1] = read_b(xB, 0, 1);
+                    xa[1] = read_a(xA, 0, 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    KB_SP_MFMA(ya, yb, 1, 0);
+                    xb[2] = read_b(xB, 0, 2);
+                    xb[3] = read_b(xB, 0, 3);
+                    __builtin_amdgcn_sched_barrier(0);
+                    KB_SP_MFMA(ya, yb, 1, 1);
+                    KB_SP_MFMA(ya, yb, 0, 2);
+                    KB_SP_MFMA(ya, yb, 1, 2);
+                    KB_SP_MFMA(ya, yb, 0, 3);
+                    KB_SP_MFMA(ya, yb, 1, 3);
+                } else {
+                    KB_SP_MFMA(xa, xb, 0, 0);
+                    ya[0] = read_a(stageA, 1, 0);
+                    yb[0] = read_b(stageB, 1, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    KB_SP_MFMA(xa, xb, 0, 1);
+                    yb[1] = read_b(stageB, 1, 1);
+                    ya[1] = read_a(stageA, 1, 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    KB_SP_MFMA(xa, xb, 1, 0);
+                    KB_SP_MFMA(xa, xb, 1, 1);
+
+                    KB_SP_MFMA(ya, yb, 0, 0);
+                    xa[0] = read_a(xA, 0, 0);
+                    xb[0] = read_b(xB, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    KB_SP_MFMA(ya, yb, 0, 1);
+                    xb[1] = read_b(xB, 0, 1);
+                    xa[1] = read_a(xA, 0, 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    KB_SP_MFMA(ya, yb, 1, 0);
+                    KB_SP_MFMA(ya, yb, 1, 1);
+                }
+                __builtin_amdgcn_s_setprio(0);
+
+            }
+            finish_iteration(c_now, qb_now);
+        }
+    } else {
+        // fp8 keys and fp8 queries: one v_mfma_f32_32x32x64_f8f6f4 per block and d-chunk (a lane supplies 32 bytes of
+        // its row per operand: lane half h owns bytes [32h, 32h+32) of the 64-byte chunk).  Key fragments live in two
+        // sets of whole chunks (the set of chunk g+1 is filled while chunk g is computed; the roles swap every
+        // iteration, hence two iterations per loop trip).  Query fragments rotate through two buffers instead: the
+        // MFMAs run column block by column block, and while block jb is computed the fragment of block jb+1 (or of
+        // block 0 of the next chunk) is read.  That keeps the fragments at 48 registers beside the 128 accumulators.
+        typedef int i32x8 __attribute__((ext_vector_type(8)));
+        typedef int i32x4 __attribute__((ext_vector_type(4)));
+        i32x8 fa0[IB], fa1[IB], fq0, fq1;             // .lo = first 16 bytes of the lane's 32, .hi = second
+        const int fragA8 = rowA * RBA, fragB8 = rowB * RBB, swzA = swizzle<4>(rowA), swzB = swizzle<4>(rowB);
+        auto read_a8 = [&](int stage, int ib, int t) {
+            return *reinterpret_cast<const i32x4 *>(smem + stage * C::A_BYTES + fragA8 + ib * 32 * RBA + (((2 * half + t) ^ swzA) << 4));
+        };
+        auto read_b8 = [&](int stage, int jb, int t) {
+            return *reinterpret_cast<const i32x4 *>(smem + C::OFF_B + stage * C::B_BYTES + fragB8 + jb * 32 * RBB + (((2 * half + t) ^ swzB) << 4));
+        };
+#pragma unroll
+        for (int ib = 0; ib < IB; ++ib) {
+            fa0[ib].lo = read_a8(0, ib, 0);
+            fa0[ib].hi = read_a8(0, ib, 1);
+        }
+        fq0.lo = read_b8(0, 0, 0);
+        fq0.hi = read_b8(0, 0, 1);
+        auto iteration8 = [&](int g, const i32x8 (&ca)[IB], i32x8 (&na)[IB]) {
+            const int c_now = c, qb_now = qb;
+            const int nA = stageA + 1 == C::NSA ? 0 : stageA + 1, nB = stageB + 1 == C::NSB ? 0 : stageB + 1;
+            // past the last chunk the refill reads the current slot again (valid memory, values unused)
+            const int xA = g + 1 < total ? nA : stageA, xB = g + 1 < total ? nB : stageB;
+            __builtin_amdgcn_s_setprio(1);
+#define KB_SP_MFMA8(I, J, FQ)                                                                                      \
+    acc[I][J] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ca[I], FQ, acc[I][J], 0, 0, 0, 0, 0, 0);           \
+    __builtin_amdgcn_sched_barrier(0)
+            KB_SP_MFMA8(0, 0, fq0);
+            fq1.lo = read_b8(stageB, 1, 0);
+            fq1.hi = read_b8(stageB, 1, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            KB_SP_MFMA8(1, 0, fq0);
+            na[0].lo = read_a8(xA, 0, 0);
+            na[0].hi = read_a8(xA, 0, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            KB_SP_MFMA8(0, 1, fq1);
+            fq0.lo = read_b8(stageB, 2, 0);
+            fq0.hi = read_b8(stageB, 2, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            KB_SP_MFMA8(1, 1, fq1);
+            na[1].lo = read_a8(xA, 1, 0);
+            na[1].hi = read_a8(xA, 1, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            KB_SP_MFMA8(0, 2, fq0);
+            fq1.lo = read_b8(stageB, 3, 0);
+            fq1.hi = read_b8(stageB, 3, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            KB_SP_MFMA8(1, 2, fq0);
+            KB_SP_MFMA8(0, 3, fq1);
+            fq0.lo = read_b8(xB, 0, 0);
+            fq0.hi = read_b8(xB, 0, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            KB_SP_MFMA8(1, 3, fq1);
+#undef KB_SP_MFMA8
+            __builtin_amdgcn_s_setprio(0);
+            finish_iteration(c_now, qb_now);
+        };
+        for (int g = 0; g < total; g += 2) {
+            iteration8(g, fa0, fa1);
+            if (g + 1 < total) iteration8(g + 1, fa1, fa0);
         }
     }
 #undef KB_SP_MFMA

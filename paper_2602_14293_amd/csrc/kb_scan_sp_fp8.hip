@@ -11,6 +11,10 @@ hipError_t launch_scan_sp_fp8(int config, bool sample, int grid, const ScanArgs 
     case ID: return launch_scan_sp_cfg<SPCfg<KT, TQ, NSA, NSB>>(sample, grid, a, s);
         KB_SCAN_SP_CONFIGS_FP8(XS)
 #undef XS
+#define XQ(ID, KT, TQ, NSA, NSB) \
+    case ID: return launch_scan_sp_cfg<SPCfg<KT, TQ, NSA, NSB, true>>(sample, grid, a, s);
+        KB_SCAN_SP_CONFIGS_FP8_Q8(XQ)
+#undef XQ
     default: return hipErrorInvalidValue;
     }
 }

@@ -10,7 +10,7 @@ Storage conventions (what the arrays hold):
   keys     torch.float32 / torch.bfloat16 / torch.float8_e4m3fn, row-major [N, d]
   scale    torch.float32 [N] (fp8 workloads only): stored value = scale[i] * code value
   tags     torch.int64 [N] holding the 64 tag bits of each entry (bit pattern, sign is meaningless)
-  queries  torch.float32 / torch.bfloat16 [Q, d]
+  queries  torch.float32 / torch.bfloat16 / torch.float8_e4m3fn [Q, d] (fp8 queries carry no scale: it cancels)
   qmask    torch.int64 [Q] holding each query's 64 filter bits
 """
 from __future__ import annotations
@@ -136,8 +136,9 @@ def filtered(seed: int = 0, N: int = 1 << 20, d: int = 1024, Q: int = 256, k: in
 
 
 def compressed(seed: int = 0, N: int = 1 << 22, d: int = 768, Q: int = 1024, k: int = 64, centers: int = 4096,
-               device="cpu") -> Workload:
-    """E4M3 keys with an fp32 per-row scale, quantised from normalised Gaussian-mixture rows; bf16 queries."""
+               device="cpu", fp8_queries: bool = False) -> Workload:
+    """E4M3 keys with an fp32 per-row scale, quantised from normalised Gaussian-mixture rows; bf16 queries, or
+    (fp8_queries) the same queries quantised to E4M3 row by row like the keys."""
     g = _gen(seed, device)
     center_rows = _unit_rows(torch.randn(centers, d, generator=g, device=device))
     keys = torch.empty(N, d, dtype=torch.float8_e4m3fn, device=device)
@@ -150,7 +151,9 @@ def compressed(seed: int = 0, N: int = 1 << 22, d: int = 768, Q: int = 1024, k: 
     v = torch.randint(0, N, (Q,), generator=g, device=device)
     base = keys[v].float() * scale[v][:, None]
     queries = perturbed_queries(base, 0.05, g).to(torch.bfloat16)
-    return Workload("compressed", keys, queries, k, scale=scale, seed=seed)
+    if fp8_queries:
+        queries = quantize_e4m3_rows(queries.float())[0]
+    return Workload("compressed-q8" if fp8_queries else "compressed", keys, queries, k, scale=scale, seed=seed)
 
 
 def growing_round(seed: int, round_index: int, n_new: int, d: int, Q: int, center_rows: torch.Tensor,

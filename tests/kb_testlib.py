@@ -13,6 +13,9 @@ from paper_2602_14293_amd import workloads as W
 # assert that tighter bound.
 TAU = {kbmod.KB_F32: 1e-5, kbmod.KB_BF16: 2e-3, kbmod.KB_FP8_E4M3: 2e-2}
 TIGHT = 1e-5
+# fp8 queries go through the fp8 matrix instruction, which sums the 64 exact products of a chunk in hardware with
+# less than fp32 precision per addend (measured: about 1e-5 of |q||k| per instruction on Gaussian rows)
+TIGHT_FP8_QUERIES = 1e-4
 ORACLE_DTYPE = {kbmod.KB_F32: kb_oracle.F32, kbmod.KB_BF16: kb_oracle.BF16, kbmod.KB_FP8_E4M3: kb_oracle.FP8_E4M3}
 CODE = {torch.float32: kbmod.KB_F32, torch.bfloat16: kbmod.KB_BF16, torch.float8_e4m3fn: kbmod.KB_FP8_E4M3}
 
@@ -39,7 +42,7 @@ def oracle_scores(w: W.Workload, rows=None):
     """fp64 score matrix of the stored bits (optionally for a subset of query rows)."""
     code = CODE[w.keys.dtype]
     q = w.queries if rows is None else w.queries[rows]
-    qd = kb_oracle.F32 if code == kbmod.KB_F32 else kb_oracle.BF16
+    qd = ORACLE_DTYPE[CODE[q.dtype]]
     return kb_oracle.score_matrix(W.key_bits(w.keys), ORACLE_DTYPE[code], W.key_bits(q), qd,
                                   row_scale=None if w.scale is None else w.scale.cpu().numpy())
 
@@ -53,7 +56,8 @@ def check_against_oracle(w: W.Workload, g_index, g_score, use_mask=True, rows=No
         g_index, g_score = g_index[rows], g_score[rows]
         qm = None if qm is None else qm[rows]
     rep = compare.check(g_index, g_score, full, w.k, TAU[code] if tau is None else tau, tags=tags, qmask=qm, label=label)
-    assert rep.max_score_err <= TIGHT, f"{label}: passes the dtype tolerance but score error {rep.max_score_err:.2e} is suspicious"
+    tight = TIGHT_FP8_QUERIES if w.queries.dtype == torch.float8_e4m3fn else TIGHT
+    assert rep.max_score_err <= tight, f"{label}: passes the dtype tolerance but score error {rep.max_score_err:.2e} is suspicious"
     return rep
 
 

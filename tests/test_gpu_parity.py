@@ -84,6 +84,29 @@ def test_fp8_shapes(T, N, d, Q, k):
     T.run_and_check(w, label=f"fp8 N={N} d={d} Q={Q} k={k}")
 
 
+@pytest.mark.parametrize("N,d,Q,k", [(24000, 768, 100, 64), (17077, 512, 300, 64), (3000, 384, 33, 20), (130, 448, 1, 1),
+                                     (70000, 1024, 700, 128)])
+def test_fp8_queries_on_fp8_keys(T, N, d, Q, k):
+    # both operands in e4m3: scored by the fp8 matrix instruction, checked against the oracle on the same codes
+    w = W.compressed(seed=N + 1, N=N, d=d, Q=Q, k=k, centers=32, fp8_queries=True)
+    assert w.queries.dtype == torch.float8_e4m3fn
+    rep, cnt, (gi, gs) = T.run_and_check(w, label=f"fp8 x fp8 N={N} d={d} Q={Q} k={k}")
+    assert rep.queries == Q
+
+
+def test_fp8_queries_exhaustive_path_and_short_rows(T):
+    # few keys: every query is resolved by the exhaustive path, which must score exactly like the scan
+    w = W.compressed(seed=5, N=700, d=512, Q=40, k=16, centers=8, fp8_queries=True)
+    rep, cnt, _ = T.run_and_check(w, label="fp8 x fp8 small")
+    # rows shorter than the pipelined kernel's ring: refused, not mis-scored
+    w2 = W.compressed(seed=6, N=500, d=256, Q=4, k=4, centers=8, fp8_queries=True)
+    kb = T.build_kb(w2)
+    with pytest.raises(kbmod.KBError) as e:
+        kb.query(w2.queries.cuda(), 4)
+    assert e.value.status == 2
+    kb.close()
+
+
 def test_all_e4m3_codes_decode_like_the_oracle(T):
     # keys whose rows run through every finite e4m3 code; one-hot queries read single elements back
     codes = torch.tensor([c for c in range(256) if c not in (0x7F, 0xFF)], dtype=torch.uint8)

@@ -97,11 +97,21 @@ def test_append_and_query_argument_errors(L):
     L.kb_destroy(h2)
 
 
-def test_fp8_takes_bf16_queries_only(L):
-    st, h = _create(L, dtype=kbmod.KB_FP8_E4M3, scale=FAKE)
+def test_fp8_takes_bf16_or_fp8_queries(L):
+    st, h = _create(L, dtype=kbmod.KB_FP8_E4M3, scale=FAKE)                          # d = 128
     ws = L.kb_query_workspace_bytes(h, 4, 4)
-    assert L.kb_query(h, FAKE, kbmod.KB_FP8_E4M3, 4, None, 4, FAKE, FAKE, FAKE, ws, None) == 3
     assert L.kb_query(h, FAKE, kbmod.KB_F32, 4, None, 4, FAKE, FAKE, FAKE, ws, None) == 3
+    assert L.kb_query(h, FAKE, kbmod.KB_FP8_E4M3, 4, None, 4, FAKE, FAKE, FAKE, ws, None) == 2   # fp8 queries need d >= 384
+    L.kb_destroy(h)
+    st, h = _create(L, d=512, dtype=kbmod.KB_FP8_E4M3, scale=FAKE)
+    ws = L.kb_query_workspace_bytes(h, 4, 4)
+    assert L.kb_query(h, FAKE, kbmod.KB_FP8_E4M3, 4, None, 4, FAKE, FAKE, None, ws, None) == 7   # accepted up to the workspace check
+    assert L.kb_query(h, FAKE, kbmod.KB_BF16, 4, None, 4, FAKE, FAKE, None, ws, None) == 7
+    assert L.kb_query_sampled(h, FAKE, kbmod.KB_FP8_E4M3, 4, None, 4, FAKE, ctypes.c_float(0.1), ctypes.c_uint64(1), 0,
+                              FAKE, FAKE, FAKE, ws, None) == 3                                  # the weighted draw takes bf16 queries
+    L.kb_destroy(h)
+    st, h = _create(L, dtype=kbmod.KB_BF16)                                          # fp8 queries go with fp8 keys only
+    assert L.kb_query(h, FAKE, kbmod.KB_FP8_E4M3, 4, None, 4, FAKE, FAKE, FAKE, 1 << 20, None) == 3
     L.kb_destroy(h)
 
 

@@ -135,6 +135,18 @@ def test_matches_numpy_formulation_bf16_and_fp8_with_mask(oracle, seed):
     assert np.abs(full - S).max() < 1e-12
     for r in range(Q):
         assert idx[r].tolist() == ri[r].tolist()
+    # fp8 queries too (no scale: a per-row factor cancels).  Pinned twice: against numpy on the library's decoding
+    # of the codes, and against the oracle's own bf16 branch (every e4m3 value is a bf16 value)
+    q8, _ = W.quantize_e4m3_rows(qf.float())
+    S, ri, rs = _numpy_reference(Kval, q8.to(torch.float64).numpy(), k)
+    idx, sc, full = oracle.query(W.key_bits(k8), FP8, W.key_bits(q8), FP8, k, row_scale=scale.numpy(), return_scores=True)
+    assert np.abs(full - S).max() < 1e-12
+    for r in range(Q):
+        assert idx[r].tolist() == ri[r].tolist()
+    as_bf16 = q8.to(torch.bfloat16)
+    assert torch.equal(as_bf16.double(), q8.double())
+    full16 = oracle.score_matrix(W.key_bits(k8), FP8, W.key_bits(as_bf16), BF16, row_scale=scale.numpy())
+    assert np.array_equal(full, full16)
 
 
 # ---------------- P4: brute-force rank count on tiny inputs ----------------------------------
