@@ -23,6 +23,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "fp8": 5000.0}     # MI355X dense matrix peaks
 DRAW_TEMPERATURE = 0.05
 # Vector-ALU roof for the weighted random selection: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second.
 VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
@@ -50,6 +51,9 @@ def make_workload(name: str, seed: int, device):
     if name == "compressed":
         return (W.compressed(seed=seed, device=device),
                 "compressed KB: N=4194304 d=768 fp8-e4m3 + row scale, Q=1024 bf16 queries, k=64")
+    if name == "compressed-q8":
+        return (W.compressed(seed=seed, device=device, fp8_queries=True),
+                "compressed KB: N=4194304 d=768 fp8-e4m3 + row scale, Q=1024 fp8-e4m3 queries, k=64")
     raise SystemExit(f"unknown workload {name}")
 
 
@@ -294,6 +298,14 @@ def main():
                      "kernel_ms": scan_ms, "algorithmic_bytes": scan_bytes, "launches_timed": scan_calls},
     }
 
+    # Above the ridge (large Q) the matrix cores, not HBM, bound the scan: report against the dense MFMA peak of the
+    # type the contraction runs in (fp8 keys with bf16 queries are widened to bf16; fp8 with fp8 queries run in fp8).
+    mfma_peak = None if code == kbmod.KB_F32 else MFMA_PEAK_TFLOPS["fp8" if queries.dtype == torch.float8_e4m3fn else "bf16"]
+    if mfma_peak is not None and flops / (mfma_peak * 1e12) > scan_bytes / (HBM_PEAK_GBPS * 1e9):
+        result["roofline"] = {"bound": "mfma", "kernel": "scan kernel, main pass", "achieved": flops / (scan_ms * 1e-3) / 1e12,
+                              "peak": mfma_peak, "unit": "TFLOP/s", "frac": flops / (scan_ms * 1e-3) / 1e12 / mfma_peak,
+                              "traffic": None, "kernel_ms": scan_ms, "algorithmic_flops": flops, "launches_timed": scan_calls}
+
     if args.draw:
         ops = float(DRAW_OPS_PER_PAIR) * Q * N
         result["roofline"] = {"bound": "alu", "kernel": "scan kernel, main pass, keys of the weighted random selection",
@@ -313,7 +325,8 @@ def main():
         qm = W.word_bits(w.qmask[:nq]) if qmask is not None else None
         okind = {kbmod.KB_F32: kb_oracle.F32, kbmod.KB_BF16: kb_oracle.BF16, kbmod.KB_FP8_E4M3: kb_oracle.FP8_E4M3}[code]
         c0 = time.perf_counter()
-        oi, osc, full = kb_oracle.query(key_bits, okind, q_bits, kb_oracle.F32 if code == kbmod.KB_F32 else kb_oracle.BF16, k,
+        qkind = {torch.float32: kb_oracle.F32, torch.bfloat16: kb_oracle.BF16, torch.float8_e4m3fn: kb_oracle.FP8_E4M3}[w.queries.dtype]
+        oi, osc, full = kb_oracle.query(key_bits, okind, q_bits, qkind, k,
                                         row_scale=None if w.scale is None else w.scale.cpu().numpy(), tags=tags, qmask=qm,
                                         return_scores=True)
         if args.draw:       # keys of the same draw from the fp64 scores; selection is part of the timed work

@@ -36,6 +36,14 @@
  * closed-form inclusion probabilities for k = 1 and ordered pairs for k = 2,
  * the T -> 0 limit (plain top-k), determinism.  Fidelity of this model to the
  * paper is unpinned for the same reason as above.
+ *
+ * Row quantisation to E4M3 (end of this file): the storage form of compressed
+ * keys and of fp8 queries in the same numeric model: per row, scale = max|x| /
+ * 448 and every element goes to the nearest e4m3 value of x / scale (ties to
+ * the even code), scale and quotient taken in binary32 because they decide an
+ * integer code.  Written as a search over all 127 non-negative finite codes.
+ * Pins: an independent library's float32 -> e4m3 conversion on random rows,
+ * every midpoint between neighbouring e4m3 values, saturation, zero rows.
  */
 #include <math.h>
 #include <stdint.h>
@@ -331,6 +339,57 @@ int oracle_selection_keys(const double *scores, int64_t Q, int64_t N, const floa
 #ifdef _OPENMP
 #include <omp.h>
 #endif
+/*
+ * The e4m3 code nearest to y: the magnitude goes to the closest of the finite non-negative values (codes 0x00
+ * .. 0x7E, increasing in value with the code), a tie to the even code, anything above 448 to 448; the sign bit
+ * of y is kept (so -0.0 gives 0x80).  y must not be NaN.
+ */
+uint8_t oracle_encode_e4m3(float y)
+{
+    const double a = fabs((double)y);
+    int best = 0;
+    double best_err = a;                       /* code 0 is 0.0 */
+    for (int c = 1; c <= 0x7E; ++c) {
+        const double err = fabs(oracle_decode_e4m3((uint8_t)c) - a);
+        if (err < best_err || (err == best_err && (c & 1) == 0)) {
+            best = c;
+            best_err = err;
+        }
+    }
+    return (uint8_t)(best | (signbit(y) ? 0x80 : 0));
+}
+
+/*
+ * rows [n, d] (ORACLE_F32 or ORACLE_BF16 bits) -> codes [n, d], scale [n] (may be NULL):
+ *   amax = max_j |x_j|;  scale = amax / 448 in binary32, or 1 when the row is all zeros;
+ *   code_j = oracle_encode_e4m3( binary32( x_j / scale ) ).
+ * Returns 0, or 1 on bad arguments.
+ */
+int oracle_quantize_rows(const void *rows, int dtype, int64_t n, int64_t d, uint8_t *codes, float *scale)
+{
+    if (!rows || !codes || n < 0 || d <= 0 || (dtype != ORACLE_F32 && dtype != ORACLE_BF16))
+        return 1;
+    double *x = (double *)malloc(sizeof(double) * (size_t)d);
+    if (!x)
+        return 1;
+    for (int64_t i = 0; i < n; ++i) {
+        decode_row(rows, dtype, NULL, i, d, x);            /* exact: both types are subsets of binary32 */
+        float amax = 0.0f;
+        for (int64_t j = 0; j < d; ++j)
+            if (fabsf((float)x[j]) > amax)
+                amax = fabsf((float)x[j]);
+        const float sc = amax > 0.0f ? amax / 448.0f : 1.0f;
+        if (scale)
+            scale[i] = sc;
+        for (int64_t j = 0; j < d; ++j) {
+            const float y = (float)x[j] / sc;
+            codes[i * d + j] = oracle_encode_e4m3(y);
+        }
+    }
+    free(x);
+    return 0;
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP

@@ -56,6 +56,10 @@ def lib() -> ctypes.CDLL:
         L.oracle_gumbel.argtypes = [ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint64]
         L.oracle_selection_keys.restype = i32
         L.oracle_selection_keys.argtypes = [vp, i64, i64, vp, dbl, ctypes.c_uint64, i64, vp]
+        L.oracle_encode_e4m3.restype = ctypes.c_uint8
+        L.oracle_encode_e4m3.argtypes = [ctypes.c_float]
+        L.oracle_quantize_rows.restype = i32
+        L.oracle_quantize_rows.argtypes = [vp, i32, i64, i64, vp, vp]
         L.oracle_num_threads.restype = i32
         L.oracle_num_threads.argtypes = []
         _lib = L
@@ -83,6 +87,22 @@ def decode_bf16(bits: int) -> float:
 
 def decode_e4m3(code: int) -> float:
     return lib().oracle_decode_e4m3(int(code))
+
+
+def encode_e4m3(y: float) -> int:
+    return lib().oracle_encode_e4m3(float(y))
+
+
+def quantize_rows(rows, dtype: int):
+    """(codes uint8 [n, d], scale float32 [n]) of float32 / bf16-bit rows: per-row scale max|x| / 448, nearest e4m3 code."""
+    rows = _bits(rows, dtype, "rows")
+    n, d = rows.shape
+    codes = np.empty((n, d), dtype=np.uint8)
+    scale = np.empty(n, dtype=np.float32)
+    rc = lib().oracle_quantize_rows(_ptr(rows), dtype, n, d, _ptr(codes), _ptr(scale))
+    if rc:
+        raise RuntimeError(f"oracle_quantize_rows failed ({rc})")
+    return codes, scale
 
 
 def num_threads() -> int:

@@ -390,3 +390,58 @@ def test_selection_limits_and_determinism(oracle):
     idx, val, n = oracle.select(keys[0], 300, tags=tags, qmask=0x00F0)
     good = ((tags & np.uint64(0x00F0)) != 0) & (gain0 > 0)
     assert n == good.sum() and set(idx[:n].tolist()) == set(np.flatnonzero(good).tolist()) and np.all(idx[n:] == -1)
+
+
+# ---------------- row quantisation to e4m3 ------------------------------------------------------
+
+def _finite_e4m3_values(oracle):
+    return [oracle.decode_e4m3(c) for c in range(0x7F)]           # increasing with the code, 0 .. 448
+
+
+def test_e4m3_encoding_is_round_to_nearest_even(oracle):
+    vals = _finite_e4m3_values(oracle)
+    assert vals == sorted(vals) and vals[0] == 0.0 and vals[-1] == 448.0
+    for c, v in enumerate(vals):                                   # every value keeps its code, under both signs
+        assert oracle.encode_e4m3(v) == c and oracle.encode_e4m3(-v) == (c | 0x80)
+    assert oracle.encode_e4m3(-0.0) == 0x80
+    for c in range(0x7E):                                          # midpoints are binary32 numbers: ties go to the even code
+        mid = np.float32((vals[c] + vals[c + 1]) / 2)
+        assert float(mid) == (vals[c] + vals[c + 1]) / 2
+        even = c if c % 2 == 0 else c + 1
+        assert oracle.encode_e4m3(mid) == even, c
+        assert oracle.encode_e4m3(np.nextafter(mid, np.float32(0))) == c
+        assert oracle.encode_e4m3(np.nextafter(mid, np.float32(1e9))) == c + 1
+    for big in (448.0001, 464.0, 480.0, 1e9, 3e38):                 # saturation, no NaN code
+        assert oracle.encode_e4m3(big) == 0x7E and oracle.encode_e4m3(-big) == 0xFE
+
+
+def test_e4m3_encoding_matches_library_conversion(oracle):
+    rng = np.random.default_rng(8)
+    y = np.concatenate([rng.uniform(-448, 448, 20000), rng.normal(0, 1, 20000), rng.normal(0, 0.01, 20000),
+                        rng.uniform(-2.0 ** -5, 2.0 ** -5, 20000)]).astype(np.float32)
+    lib = torch.from_numpy(y).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    mine = np.array([oracle.encode_e4m3(v) for v in y], dtype=np.uint8)
+    assert np.array_equal(lib, mine)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_row_quantisation_matches_library_formulation(oracle, dtype):
+    g = torch.Generator().manual_seed(21)
+    x = (torch.randn(40, 192, generator=g) * torch.logspace(-6, 6, 40)[:, None]).to(dtype)
+    x[3] = 0                                                       # an all-zero row: scale 1, codes 0
+    x[5, 7] = 0
+    codes, scale = oracle.quantize_rows(W.key_bits(x), F32 if dtype == torch.float32 else BF16)
+    xf = x.float()
+    amax = xf.abs().amax(dim=1)
+    ref_scale = torch.where(amax > 0, amax / 448.0, torch.ones_like(amax))
+    ref_codes = (xf / ref_scale[:, None]).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(scale, ref_scale.numpy()) and scale[3] == 1.0
+    assert np.array_equal(codes, ref_codes) and not codes[3].any()
+    # what the encoding promises: the largest element sits at +-448, elements are within 2^-4 relative
+    # (normal range) or 2^-10 scale units (subnormal range) of their value
+    dec = np.array([oracle.decode_e4m3(int(c)) for c in codes.ravel()]).reshape(codes.shape) * scale[:, None].astype(np.float64)
+    err = np.abs(dec - xf.double().numpy())
+    bound = np.maximum(np.abs(xf.double().numpy()) * 2.0 ** -4, scale[:, None].astype(np.float64) * 2.0 ** -10) * (1 + 1e-6)
+    assert np.all(err <= bound)
+    live = [i for i in range(40) if i != 3]
+    assert np.all(np.abs(dec[live]).max(axis=1) == 448.0 * scale[live].astype(np.float64))
