@@ -140,6 +140,20 @@ kb_status_t kb_query_sampled(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
                              void *hip_stream);
 
 /*
+ * Row quantisation to E4M3: the storage form of KB_FP8_E4M3 keys (codes + row scale, as kb_create and kb_append
+ * take them) and of fp8 queries (codes only), in the numeric model of Section 3's retrieval described at the top
+ * of this file.  Independent of any handle.  For every row i of rows_dev [n, d] (KB_F32 or KB_BF16, row-major):
+ *     scale_i = max_j |x_ij| / 448 in fp32, or 1 if the row is all zeros
+ *     code_ij = the e4m3 code nearest to fp32(x_ij / scale_i): ties to the even code, sign kept, never NaN
+ *   codes_out_dev [n, d] bytes; scale_out_dev [n] fp32, or NULL when the scales are not wanted (queries: a
+ *   positive factor per row cancels in the cosine).  rows_dev and codes_out_dev 16-byte aligned, not overlapping.
+ *   d multiple of 16, 16 .. 16384; 0 <= n < 2^31 (n == 0 is a no-op).  Finite inputs are the caller's responsibility.
+ * Errors: KB_ERR_NULL, KB_ERR_DTYPE (rows not KB_F32 / KB_BF16), KB_ERR_INVALID_ARG, KB_ERR_DEVICE.
+ */
+kb_status_t kb_quantize_rows(const void *rows_dev, kb_dtype_t dtype, int64_t n, int32_t d, void *codes_out_dev,
+                             float *scale_out_dev, void *hip_stream);
+
+/*
  * Diagnostics of the most recent kb_query that used `workspace_dev`: synchronises `hip_stream`, then copies
  * out[0] = candidates that passed the threshold filter (all queries), out[1] = queries resolved by the
  * exhaustive per-query path, out[2] = keys scored by the sampling pass, out[3] = workgroups of the scan.

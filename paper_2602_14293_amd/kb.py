@@ -50,6 +50,8 @@ def lib() -> ctypes.CDLL:
         L.kb_query_workspace_bytes.argtypes = [vp, i32, i32]
         L.kb_query.restype = i32
         L.kb_query.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, vp, sz, vp]
+        L.kb_quantize_rows.restype = i32
+        L.kb_quantize_rows.argtypes = [vp, i32, i64, i32, vp, vp, vp]
         L.kb_query_sampled.restype = i32
         L.kb_query_sampled.argtypes = [vp, vp, i32, i32, vp, i32, vp, ctypes.c_float, ctypes.c_uint64, i32, vp, vp, vp, sz, vp]
         L.kb_query_counters.restype = i32
@@ -81,6 +83,16 @@ def _ptr(t: Optional[torch.Tensor]):
 
 def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def quantize_rows(rows: torch.Tensor, want_scale: bool = True):
+    """kb_quantize_rows: float32 / bfloat16 rows [n, d] on the GPU -> (float8_e4m3fn codes [n, d], float32 scale [n] or None)."""
+    assert rows.is_cuda and rows.dim() == 2 and rows.is_contiguous()
+    n, d = rows.shape
+    codes = torch.empty((n, d), dtype=torch.float8_e4m3fn, device=rows.device)
+    scale = torch.empty(n, dtype=torch.float32, device=rows.device) if want_scale else None
+    _check(lib().kb_quantize_rows(_ptr(rows), _CODE_OF[rows.dtype], n, d, _ptr(codes), _ptr(scale), _stream()), "kb_quantize_rows")
+    return codes, scale
 
 
 class KnowledgeBase:

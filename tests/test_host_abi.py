@@ -32,7 +32,8 @@ def test_every_declared_symbol_is_exported(L):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(kb_[a-z_]+)\s*\(", header))
     assert {"kb_create", "kb_append", "kb_normalize", "kb_query_workspace_bytes", "kb_query", "kb_size",
-            "kb_destroy", "kb_status_string", "kb_query_counters", "kb_set_tuning", "kb_query_sampled"} <= names
+            "kb_destroy", "kb_status_string", "kb_query_counters", "kb_set_tuning", "kb_query_sampled",
+            "kb_quantize_rows"} <= names
     for n in names:
         assert hasattr(L, n), f"{n} is declared in kb.h but not exported by libkb.so"
 
@@ -113,6 +114,18 @@ def test_fp8_takes_bf16_or_fp8_queries(L):
     st, h = _create(L, dtype=kbmod.KB_BF16)                                          # fp8 queries go with fp8 keys only
     assert L.kb_query(h, FAKE, kbmod.KB_FP8_E4M3, 4, None, 4, FAKE, FAKE, FAKE, 1 << 20, None) == 3
     L.kb_destroy(h)
+
+
+def test_quantize_rows_argument_errors(L):
+    def qr(rows=FAKE, dt=kbmod.KB_BF16, n=8, d=64, codes=FAKE, scale=FAKE):
+        return L.kb_quantize_rows(rows, dt, n, d, codes, scale, None)
+
+    assert qr(rows=None) == 1 and qr(codes=None) == 1
+    assert qr(dt=kbmod.KB_FP8_E4M3) == 3 and qr(dt=5) == 3
+    assert qr(n=-1) == 2 and qr(n=1 << 31) == 2 and qr(d=0) == 2 and qr(d=24) == 2 and qr(d=16400) == 2
+    assert qr(rows=ctypes.c_void_p((1 << 20) + 8)) == 2 and qr(codes=ctypes.c_void_p((1 << 20) + 4)) == 2
+    assert qr(scale=ctypes.c_void_p((1 << 20) + 2)) == 2
+    assert qr(n=0) == 0 and qr(n=0, scale=None) == 0                                  # nothing to do, nothing launched
 
 
 def test_tuning_knobs(L):
