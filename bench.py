@@ -62,6 +62,33 @@ def _median(xs):
     return xs[len(xs) // 2]
 
 
+def run_quantize(args, torch, kbmod, W, dev):
+    """kb_quantize_rows on 2^20 x 1024 bf16 rows (what building a compressed knowledge base of that size costs) and
+    on a 1024 x 768 bf16 query batch.  Algorithmic traffic: the rows read once, one byte per element and one scale
+    per row written."""
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(args.seed)
+    out = []
+    for n, d in ((1 << 20, 1024), (1024, 768)):
+        x = torch.randn(n, d, generator=gen, device=dev).to(torch.bfloat16)
+        for _ in range(args.warmup):
+            kbmod.quantize_rows(x)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        for e0, e1 in evs:
+            e0.record()
+            kbmod.quantize_rows(x)
+            e1.record()
+        torch.cuda.synchronize()
+        ms = _median([e0.elapsed_time(e1) for e0, e1 in evs])
+        nbytes = n * d * 3 + n * 4
+        out.append({"rows": n, "d": d, "ms": ms, "GBps": nbytes / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS})
+        del x
+    print(json.dumps({"metric": "kb_quantize_rows, bf16 rows to e4m3 codes + row scale", "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+                      "warmup": args.warmup, "dtype": "bf16 -> fp8_e4m3", "data": "synthetic", "shapes": out,
+                      "roofline": {"bound": "hbm", "kernel": "quantize_rows_kernel", "achieved": out[0]["GBps"], "peak": HBM_PEAK_GBPS,
+                                   "unit": "GB/s", "frac": out[0]["frac_of_hbm_peak"], "traffic": None}}))
+
+
 def run_growing(args, torch, kbmod, W, dev):
     """The growing knowledge base: 2^20 rows, then 64 rounds of (append 16384 rows, normalize, 128 masked
     queries, k = 16).  A step is one round; append + normalize and the query are timed separately."""
@@ -167,6 +194,7 @@ def main():
     ap.add_argument("--draw", action="store_true",
                     help="time the weighted random selection (kb_query_sampled: gains uniform in [0.25, 4], temperature "
                          "0.05) instead of the plain top-k")
+    ap.add_argument("--quantize", action="store_true", help="time kb_quantize_rows instead")
     ap.add_argument("--q-sweep", action="store_true", help="time query batches of 1..512 on the N=2^20 bf16 knowledge base instead")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -187,6 +215,8 @@ def main():
 
     if args.q_sweep:
         return run_q_sweep(args, torch, kbmod, W, dev)
+    if args.quantize:
+        return run_quantize(args, torch, kbmod, W, dev)
     if args.workload == "growing":
         return run_growing(args, torch, kbmod, W, dev)
     w, desc = make_workload(args.workload, args.seed, dev)

@@ -14,22 +14,15 @@ constexpr int ROWS_PER_WG = 4;      // one wavefront per row
 constexpr int CACHED = 4;           // 16-byte pieces of the row a lane keeps in registers between the two passes
 constexpr float E4M3_MAX = 448.0f;
 
-// Nearest e4m3 code of y, ties to the even code, saturating at +-448, sign bit kept.  Codes are ordered like
-// the values they stand for, so rounding the magnitude is integer arithmetic on the binary32 bits: the
-// subnormal range (below 2^-6) is the integers 0..8 in units of 2^-9, the normal range keeps three mantissa
-// bits and re-biases the exponent from 127 to 7.
-__device__ inline uint32_t encode_e4m3(float y)
+// Four quotients to four e4m3 codes (nearest, ties to the even code, sign kept) with the conversion instruction
+// of gfx950, which implements exactly that rounding for the OCP e4m3 format, subnormal range included.  No
+// quotient exceeds 448 (1 + 2^-23), which rounds to 448, so the overflow behaviour of the instruction never
+// comes into play.
+__device__ inline uint32_t encode_e4m3_x4(float y0, float y1, float y2, float y3)
 {
-    const uint32_t u = __float_as_uint(y), sign = (u >> 24) & 0x80u, a = u & 0x7FFFFFFFu;
-    uint32_t code;
-    if (a < 0x3C800000u) {          // |y| < 2^-6
-        code = (uint32_t)__builtin_rintf(__uint_as_float(a) * 512.0f);
-    } else {
-        const uint32_t r = a + 0x7FFFFu + ((a >> 20) & 1u);
-        code = (r >> 20) - ((127u - 7u) << 3);
-    }
-    code = code < 0x7Eu ? code : 0x7Eu;
-    return code | sign;
+    int w = __builtin_amdgcn_cvt_pk_fp8_f32(y0, y1, 0, false);
+    w = __builtin_amdgcn_cvt_pk_fp8_f32(y2, y3, w, true);
+    return (uint32_t)w;
 }
 
 template <int DT> struct Piece;     // 16 bytes of a row
@@ -55,9 +48,8 @@ template <int DT> __device__ inline void piece_store(const u32x4 &v, float scale
     uint32_t w[Piece<DT>::ELEMS / 4];
 #pragma unroll
     for (int j = 0; j < Piece<DT>::ELEMS / 4; ++j) {
-        w[j] = 0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) w[j] |= encode_e4m3(Piece<DT>::value(v, 4 * j + i) / scale) << (8 * i);
+        w[j] = encode_e4m3_x4(Piece<DT>::value(v, 4 * j) / scale, Piece<DT>::value(v, 4 * j + 1) / scale,
+                              Piece<DT>::value(v, 4 * j + 2) / scale, Piece<DT>::value(v, 4 * j + 3) / scale);
     }
     if constexpr (Piece<DT>::ELEMS == 8)
         *reinterpret_cast<uint2 *>(dst) = make_uint2(w[0], w[1]);
