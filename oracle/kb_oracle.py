@@ -176,6 +176,42 @@ def selection_keys(scores, gain, temperature: float, seed: int, first_query: int
     return keys
 
 
+# ---- knowledge-base maintenance: the numeric side of the paper's ParameterUpdate step (Section 3, the outer loop of
+# Algorithm 2: after the rollouts the predicted gains in the knowledge base are revised from the measured ones), and
+# removal of entries (knowledge-base management, named as future work in the paper's conclusion).  The paper gives
+# neither a formula; the model: predicted gains move towards observed gains by an exponential moving average, a
+# removed entry is never a candidate again, and compaction closes the gaps without changing the order of the rest.
+
+def update_gain(gain, indices, values, alpha: float) -> np.ndarray:
+    """gain[i] <- (1 - alpha) * gain[i] + alpha * value for each (i, value) pair, in fp64, pairs taken in order;
+    an index outside [0, len(gain)) (the -1 padding of a result list) is skipped.  Returns a float64 copy."""
+    g = np.array(gain, dtype=np.float64)
+    for i, v in zip(np.asarray(indices).tolist(), np.asarray(values, dtype=np.float64).tolist()):
+        if 0 <= i < g.shape[0]:
+            g[i] = (1.0 - alpha) * g[i] + alpha * v
+    return g
+
+
+def without_removed(scores, removed) -> np.ndarray:
+    """Scores (or selection keys) [Q, N] with every removed entry's column at -inf: never a candidate (select skips -inf)."""
+    out = np.array(scores, dtype=np.float64)
+    out[:, np.asarray(removed, dtype=bool)] = -np.inf
+    return out
+
+
+def compact(removed, *arrays):
+    """Stable removal: (index_map int32 [n]: new index of each old entry or -1, [a[live] for a in arrays])."""
+    removed = np.asarray(removed, dtype=bool)
+    index_map = np.full(removed.shape[0], -1, dtype=np.int32)
+    nxt = 0
+    for i in range(removed.shape[0]):
+        if not removed[i]:
+            index_map[i] = nxt
+            nxt += 1
+    live = np.flatnonzero(~removed)
+    return index_map, [np.ascontiguousarray(np.asarray(a)[live]) for a in arrays]
+
+
 def query(keys, key_dtype, queries, q_dtype, k, row_scale=None, tags=None, qmask=None, return_scores=False):
     """Full retrieval.  Returns (index int64[Q,k], score float64[Q,k][, scores float64[Q,N]])."""
     keys = _bits(keys, key_dtype, "keys")

@@ -445,3 +445,68 @@ def test_row_quantisation_matches_library_formulation(oracle, dtype):
     assert np.all(err <= bound)
     live = [i for i in range(40) if i != 3]
     assert np.all(np.abs(dec[live]).max(axis=1) == 448.0 * scale[live].astype(np.float64))
+
+
+# ---------------- maintenance: gain update, removal, compaction ---------------------------------
+
+def test_gain_update_closed_forms(oracle):
+    g0 = np.array([1.0, 2.0, 0.5, 4.0, 3.0], dtype=np.float32)
+    # alpha = 1 overwrites, alpha = 0 changes nothing, untouched entries and out-of-range indices are left alone
+    g = oracle.update_gain(g0, [3, 0, -1, 7], [9.0, 8.0, 5.0, 5.0], 1.0)
+    assert g.tolist() == [8.0, 2.0, 0.5, 9.0, 3.0]
+    assert oracle.update_gain(g0, [1, 2], [100.0, 100.0], 0.0).tolist() == g0.astype(np.float64).tolist()
+    # one step is the convex combination; t steps towards the same value leave (1 - alpha)^t of the distance
+    assert oracle.update_gain(g0, [1], [4.0], 0.25)[1] == 0.75 * 2.0 + 0.25 * 4.0
+    g = g0
+    for t in range(1, 8):
+        g = oracle.update_gain(g, [4], [10.0], 0.3)
+        assert abs((g[4] - 10.0) - (0.7 ** t) * (3.0 - 10.0)) < 1e-12
+    # pairs are taken in order: the same index twice compounds
+    assert oracle.update_gain(g0, [2, 2], [1.5, 2.5], 0.5)[2] == 0.5 * (0.5 * 0.5 + 0.5 * 1.5) + 0.5 * 2.5
+
+
+def test_removed_entries_are_never_candidates(oracle):
+    rng = np.random.default_rng(12)
+    scores = rng.uniform(-1, 1, size=(3, 40))
+    removed = np.zeros(40, dtype=bool)
+    removed[[0, 7, 8, 39]] = True
+    removed[np.argmax(scores[1])] = True                            # the best entry of query 1 goes too
+    cut = oracle.without_removed(scores, removed)
+    for r in range(3):
+        idx, sc, n = oracle.select(cut[r], 40)
+        assert n == 40 - removed.sum() and not set(idx[:n].tolist()) & set(np.flatnonzero(removed).tolist())
+        assert np.all(idx[n:] == -1)
+        # same ranking as a brute-force filter of the untouched scores
+        want = sorted((i for i in range(40) if not removed[i]), key=lambda i: (-scores[r, i], i))
+        assert idx[:n].tolist() == want
+
+
+def test_compaction_is_a_stable_filter(oracle):
+    rng = np.random.default_rng(5)
+    n, d = 57, 8
+    keys = rng.normal(size=(n, d)).astype(np.float32)
+    tags = rng.integers(1, 2 ** 20, size=n).astype(np.uint64)
+    removed = rng.random(n) < 0.3
+    removed[0] = True
+    removed[-1] = False
+    index_map, (k2, t2) = oracle.compact(removed, keys, tags)
+    live = [i for i in range(n) if not removed[i]]
+    assert k2.shape == (len(live), d) and [index_map[i] for i in live] == list(range(len(live)))
+    assert all(index_map[i] == -1 for i in range(n) if removed[i])
+    for new, old in enumerate(live):
+        assert np.array_equal(k2[new], keys[old]) and t2[new] == tags[old]
+    # retrieval commutes with compaction: results on the compacted store, mapped back, equal results on the
+    # original store with the removed entries excluded (order among equal scores included)
+    q = rng.normal(size=(4, d)).astype(np.float32)
+    full = oracle.score_matrix(keys, F32, q, F32)
+    full2 = oracle.score_matrix(k2, F32, q, F32)
+    back = np.array(live)
+    for r in range(4):
+        a_idx, a_sc, a_n = oracle.select(oracle.without_removed(full, removed)[r], 10, tags=tags, qmask=0xF0F0)
+        b_idx, b_sc, b_n = oracle.select(full2[r], 10, tags=t2, qmask=0xF0F0)
+        assert a_n == b_n and a_idx[:a_n].tolist() == back[b_idx[:b_n]].tolist() and np.array_equal(a_sc, b_sc)
+    # nothing removed: identity; everything removed: empty
+    ident, (k3,) = oracle.compact(np.zeros(n, dtype=bool), keys)
+    assert ident.tolist() == list(range(n)) and np.array_equal(k3, keys)
+    none, (k4,) = oracle.compact(np.ones(n, dtype=bool), keys)
+    assert np.all(none == -1) and k4.shape[0] == 0
