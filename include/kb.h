@@ -61,7 +61,8 @@ typedef enum {
  *   keys_dev       [capacity, d] row-major, 16-byte aligned
  *   row_scale_dev  [capacity] fp32, KB_FP8_E4M3 only (stored value = scale * code); else must be NULL.
  *                  Scales must be finite and > 0; under the cosine they cancel and are not read by queries.
- *   inv_norm_dev   [capacity] fp32, written by kb_normalize (1/|K_i| of the stored codes, 0 for a zero row)
+ *   inv_norm_dev   [capacity] fp32, written by kb_normalize (1/|K_i| of the stored codes, 0 for a zero row;
+ *                  kb_remove sets the sign bit of a removed entry's word)
  *   tags_dev       [capacity] uint64, or NULL for an untagged knowledge base
  * The buffers must outlive the handle.  Errors: KB_ERR_NULL, KB_ERR_INVALID_ARG, KB_ERR_DTYPE.
  */
@@ -152,6 +153,44 @@ kb_status_t kb_query_sampled(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
  */
 kb_status_t kb_quantize_rows(const void *rows_dev, kb_dtype_t dtype, int64_t n, int32_t d, void *codes_out_dev,
                              float *scale_out_dev, void *hip_stream);
+
+/*
+ * Revision of predicted gains: the numeric side of the paper's ParameterUpdate step (Section 3; the last step of
+ * the outer loop of Algorithm 2 rewrites the knowledge base from what the rollouts measured).  For j = 0 .. m-1:
+ *     i = indices[j];   gain[i] <- gain[i] + alpha * (values[j] - gain[i])      (fp32: one subtraction, one fma)
+ * an exponential moving average towards the observed gain; alpha = 1 stores values[j] itself.  An index outside [0, n) (the -1
+ * padding of a result list) is skipped.  Indices must be distinct within a call (otherwise one of the pairs wins).
+ *   gain_dev [n] fp32 (the array kb_query_sampled takes), indices_dev [m] int32, values_dev [m] fp32, 0 <= alpha <= 1.
+ * Errors: KB_ERR_NULL, KB_ERR_INVALID_ARG (n or m negative, alpha outside [0, 1] or NaN, misaligned), KB_ERR_DEVICE.
+ */
+kb_status_t kb_update_gain(float *gain_dev, int64_t n, const int32_t *indices_dev, const float *values_dev, int64_t m,
+                           float alpha, void *hip_stream);
+
+/*
+ * Removal (knowledge-base management; the paper's conclusion names it as future work).  The m entries keep their
+ * rows and indices, kb_size does not change, but no kb_query / kb_query_sampled enqueued afterwards returns them.
+ * The mark is the sign bit of the entry's inv_norm word.  Indices outside [0, kb_size) are skipped; repeats are
+ * harmless.  Rows appended but not yet normalised cannot be removed (KB_ERR_NOT_NORMALIZED).
+ * Errors: KB_ERR_NULL, KB_ERR_INVALID_ARG, KB_ERR_NOT_NORMALIZED, KB_ERR_DEVICE.
+ */
+kb_status_t kb_remove(kb_t *kb, const int32_t *indices_dev, int64_t m, void *hip_stream);
+
+/*
+ * Compaction: copies the entries of `src` that have not been removed, in their order, into the EMPTY knowledge
+ * base `dst` (same d, dtype and taggedness, separate storage, capacity >= the number of live entries), with their
+ * norms, scales and tags; dst is then normalised and ready for queries, src is unchanged.
+ *   gain_src_dev / gain_dst_dev  optional per-entry fp32 array carried along ([kb_size(src)] -> [live]); both or neither
+ *   index_map_out_dev            optional [kb_size(src)] int32: new index of each old entry, -1 if removed
+ *   workspace_dev                256-byte aligned, at least kb_compact_workspace_bytes(src)
+ *   live_out                     host, optional: number of entries copied (= kb_size(dst) afterwards)
+ * This call SYNCHRONISES `hip_stream` once (the live count decides the capacity check and dst's size), so it cannot
+ * be captured in a graph.  Errors: KB_ERR_NULL, KB_ERR_INVALID_ARG (shape mismatch, dst not empty, shared storage),
+ * KB_ERR_DTYPE, KB_ERR_NOT_NORMALIZED, KB_ERR_WORKSPACE, KB_ERR_CAPACITY (dst too small; nothing was written),
+ * KB_ERR_DEVICE.
+ */
+size_t kb_compact_workspace_bytes(const kb_t *kb);
+kb_status_t kb_compact(kb_t *src, kb_t *dst, const float *gain_src_dev, float *gain_dst_dev, int32_t *index_map_out_dev,
+                       void *workspace_dev, size_t workspace_bytes, void *hip_stream, int64_t *live_out);
 
 /*
  * Diagnostics of the most recent kb_query that used `workspace_dev`: synchronises `hip_stream`, then copies

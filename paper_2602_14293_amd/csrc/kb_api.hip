@@ -19,18 +19,6 @@
 
 using namespace kbi;
 
-struct kb {
-    int32_t d;
-    kb_dtype_t dtype;
-    int64_t capacity, n, n_normalized;
-    void *keys;
-    float *row_scale, *inv_norm;
-    uint64_t *tags;
-    int64_t tune_sample_keys, tune_config, tune_wg_per_cu;
-    int cu_count;   // 0 until the device has been asked
-    hipEvent_t *prof_events;   // 2 * prof_max events while profiling, else nullptr
-    int prof_max, prof_used;
-};
 
 namespace kbi {
 
@@ -597,7 +585,7 @@ template <int KT> __device__ void exhaustive_query(const FinalArgs &a, int q, ui
         for (int i = 1; i < 16; ++i) v = (lrow == i) ? acc[i] : v;
         if (lrow < 16) {
             const int64_t row = row0 + wave * 32 + 8 * (lrow >> 2) + 4 * half + (lrow & 3);
-            if (row < a.n_keys && (!filter || (a.tags[row] & qm) != 0)) {
+            if (row < a.n_keys && !row_removed(a.inv_norm[row]) && (!filter || (a.tags[row] & qm) != 0)) {
                 float value = final_score(v, a.inv_norm[row], iq);
                 if (a.draw.enabled) value = draw_key_of(value, a.draw, a.draw.first_query + (uint32_t)q, row);
                 const uint64_t cw = pack_candidate(value, (uint32_t)row);

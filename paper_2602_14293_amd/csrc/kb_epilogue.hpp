@@ -90,9 +90,10 @@ __device__ inline void main_block(const f32x16 &a, const EpiRows &rw, float tp, 
             const bool has = (mine >> b) & 1u;
             const int rl = rw.rl0 + 8 * (i >> 2) + (i & 3);
             const int64_t row = row0 + rl;
-            const float s = final_score(a[i], sd.invk[rl], iq);
+            const float ik = sd.invk[rl];
+            const float s = final_score(a[i], ik, iq);
             const uint64_t cw = pack_candidate(s, (uint32_t)row);
-            bool ok = has && row < p.n_keys && cw >= t64;
+            bool ok = has && row < p.n_keys && cw >= t64 && !row_removed(ik);
             if (filter) ok = ok && (sd.tag[rl] & qm) != 0;
             // slot in the wave's own record region: running count + rank among the lanes that append
             const uint64_t okm = __builtin_amdgcn_ballot_w64(ok);
@@ -139,8 +140,9 @@ __device__ inline void sample_block(const f32x16 &a, int rl0, const EpiSide &sd,
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int rl = rl0 + 8 * (i >> 2) + (i & 3);
-        const float s1 = a[i] * sd.invk[rl];
-        bool ok = row0 + rl < n_keys && s1 > best;
+        const float ik = sd.invk[rl];
+        const float s1 = a[i] * ik;
+        bool ok = row0 + rl < n_keys && s1 > best && !row_removed(ik);
         if (filter) ok = ok && (sd.tag[rl] & qm) != 0;
         if (ok) {
             best = s1;
@@ -271,9 +273,10 @@ __device__ inline void main_block_draw(const f32x16 &a, const EpiRows &rw, float
             const bool has = (mine >> b) & 1u;
             const int rl = rw.rl0 + 8 * (i >> 2) + (i & 3);
             const int64_t row = row0 + rl;
-            const float kv = draw_key_of(final_score(a[i], sd.invk[rl], iq), p.draw, query, row);
+            const float ik = sd.invk[rl];
+            const float kv = draw_key_of(final_score(a[i], ik, iq), p.draw, query, row);
             const uint64_t cw = pack_candidate(kv, (uint32_t)row);
-            bool ok = has && row < p.n_keys && kv > -__builtin_inff() && cw >= t64;
+            bool ok = has && row < p.n_keys && kv > -__builtin_inff() && cw >= t64 && !row_removed(ik);
             if (filter) ok = ok && (sd.tag[rl] & qm) != 0;
             const uint64_t okm = __builtin_amdgcn_ballot_w64(ok);
             if (ok) {
@@ -328,7 +331,7 @@ __device__ inline void sample_epilogue_draw(const f32x16 (&acc)[IB][JB], const E
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int rl = rw.rl0 + 8 * (i >> 2) + (i & 3);
-                bool ok = row0 + rl < p.n_keys && key[i] > best;
+                bool ok = row0 + rl < p.n_keys && key[i] > best && !row_removed(rw.ik[i]);
                 if (filter) ok = ok && (sd.tag[rl] & qm) != 0;
                 if (ok) {
                     best = key[i];

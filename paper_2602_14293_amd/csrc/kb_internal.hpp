@@ -5,6 +5,20 @@
 
 #include "kb.h"
 
+// The handle: host-side bookkeeping over caller-owned device storage.
+struct kb {
+    int32_t d;
+    kb_dtype_t dtype;
+    int64_t capacity, n, n_normalized;
+    void *keys;
+    float *row_scale, *inv_norm;
+    uint64_t *tags;
+    int64_t tune_sample_keys, tune_config, tune_wg_per_cu;
+    int cu_count;   // 0 until the device has been asked
+    hipEvent_t *prof_events;   // 2 * prof_max events while profiling, else nullptr
+    int prof_max, prof_used;
+};
+
 namespace kbi {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -43,6 +57,11 @@ __host__ __device__ inline float candidate_score(uint64_t c) { return ordered_to
 // The fp32 score every kernel of the library computes from an fp32 dot product.
 // "+ 0.0f" turns -0.0 into +0.0 so that equal scores have equal bit patterns.
 __device__ inline float final_score(float dot, float inv_k, float inv_q) { return (dot * inv_k) * inv_q + 0.0f; }
+
+// A removed entry keeps its row and its index but is never a candidate again: kb_remove sets the sign bit of its
+// 1/|k| (which is never negative otherwise; a zero row's 0 becomes -0).
+constexpr uint32_t REMOVED_BIT = 0x80000000u;
+__host__ __device__ inline bool row_removed(float inv_k) { return (as_u32(inv_k) & REMOVED_BIT) != 0; }
 
 struct Record {  // one candidate that passed the threshold filter of the scan
     uint64_t cand;

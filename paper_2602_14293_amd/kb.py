@@ -50,6 +50,14 @@ def lib() -> ctypes.CDLL:
         L.kb_query_workspace_bytes.argtypes = [vp, i32, i32]
         L.kb_query.restype = i32
         L.kb_query.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, vp, sz, vp]
+        L.kb_update_gain.restype = i32
+        L.kb_update_gain.argtypes = [vp, i64, vp, vp, i64, ctypes.c_float, vp]
+        L.kb_remove.restype = i32
+        L.kb_remove.argtypes = [vp, vp, i64, vp]
+        L.kb_compact_workspace_bytes.restype = sz
+        L.kb_compact_workspace_bytes.argtypes = [vp]
+        L.kb_compact.restype = i32
+        L.kb_compact.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp, ctypes.POINTER(i64)]
         L.kb_quantize_rows.restype = i32
         L.kb_quantize_rows.argtypes = [vp, i32, i64, i32, vp, vp, vp]
         L.kb_query_sampled.restype = i32
@@ -93,6 +101,14 @@ def quantize_rows(rows: torch.Tensor, want_scale: bool = True):
     scale = torch.empty(n, dtype=torch.float32, device=rows.device) if want_scale else None
     _check(lib().kb_quantize_rows(_ptr(rows), _CODE_OF[rows.dtype], n, d, _ptr(codes), _ptr(scale), _stream()), "kb_quantize_rows")
     return codes, scale
+
+
+def update_gain(gain: torch.Tensor, indices: torch.Tensor, values: torch.Tensor, alpha: float):
+    """kb_update_gain: gain[indices] moves towards values by the factor alpha, in place."""
+    assert gain.dtype == torch.float32 and indices.dtype == torch.int32 and values.dtype == torch.float32
+    assert gain.is_contiguous() and indices.is_contiguous() and values.is_contiguous() and indices.numel() == values.numel()
+    _check(lib().kb_update_gain(_ptr(gain), gain.numel(), _ptr(indices), _ptr(values), indices.numel(), ctypes.c_float(alpha),
+                                _stream()), "kb_update_gain")
 
 
 class KnowledgeBase:
@@ -172,6 +188,21 @@ class KnowledgeBase:
                                       _ptr(out_index), _ptr(out_key), _ptr(self._workspace), self._workspace.numel(), _stream()),
                "kb_query_sampled")
         return out_index, out_key
+
+    def remove(self, indices: torch.Tensor):
+        assert indices.dtype == torch.int32 and indices.is_contiguous()
+        _check(lib().kb_remove(self._h, _ptr(indices), indices.numel(), _stream()), "kb_remove")
+
+    def compact_into(self, dst: "KnowledgeBase", gain: Optional[torch.Tensor] = None, want_index_map: bool = True):
+        """kb_compact: live entries of this knowledge base into the empty `dst`.  Returns (live, index_map, gain of dst)."""
+        need = lib().kb_compact_workspace_bytes(self._h)
+        ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
+        index_map = torch.empty(self.size, dtype=torch.int32, device=self.device) if want_index_map else None
+        gain_dst = torch.empty(dst.capacity, dtype=torch.float32, device=self.device) if gain is not None else None
+        live = ctypes.c_int64(-1)
+        _check(lib().kb_compact(self._h, dst._h, _ptr(gain), _ptr(gain_dst), _ptr(index_map), _ptr(ws), ws.numel(), _stream(),
+                                ctypes.byref(live)), "kb_compact")
+        return live.value, index_map, None if gain_dst is None else gain_dst[:live.value]
 
     def counters(self) -> dict:
         out = (ctypes.c_int64 * 4)()

@@ -47,9 +47,11 @@ def oracle_scores(w: W.Workload, rows=None):
                                   row_scale=None if w.scale is None else w.scale.cpu().numpy())
 
 
-def check_against_oracle(w: W.Workload, g_index, g_score, use_mask=True, rows=None, label="", tau=None):
+def check_against_oracle(w: W.Workload, g_index, g_score, use_mask=True, rows=None, label="", tau=None, removed=None):
     code = CODE[w.keys.dtype]
     full = oracle_scores(w, rows)
+    if removed is not None:                 # removed entries are never candidates
+        full = kb_oracle.without_removed(full, removed)
     tags = W.word_bits(w.tags) if (use_mask and w.qmask is not None) else None
     qm = W.word_bits(w.qmask) if (use_mask and w.qmask is not None) else None
     if rows is not None:

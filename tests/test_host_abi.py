@@ -33,7 +33,7 @@ def test_every_declared_symbol_is_exported(L):
     names = set(re.findall(r"\b(kb_[a-z_]+)\s*\(", header))
     assert {"kb_create", "kb_append", "kb_normalize", "kb_query_workspace_bytes", "kb_query", "kb_size",
             "kb_destroy", "kb_status_string", "kb_query_counters", "kb_set_tuning", "kb_query_sampled",
-            "kb_quantize_rows"} <= names
+            "kb_quantize_rows", "kb_update_gain", "kb_remove", "kb_compact", "kb_compact_workspace_bytes"} <= names
     for n in names:
         assert hasattr(L, n), f"{n} is declared in kb.h but not exported by libkb.so"
 
@@ -126,6 +126,38 @@ def test_quantize_rows_argument_errors(L):
     assert qr(rows=ctypes.c_void_p((1 << 20) + 8)) == 2 and qr(codes=ctypes.c_void_p((1 << 20) + 4)) == 2
     assert qr(scale=ctypes.c_void_p((1 << 20) + 2)) == 2
     assert qr(n=0) == 0 and qr(n=0, scale=None) == 0                                  # nothing to do, nothing launched
+
+
+def test_maintenance_argument_errors(L):
+    def ug(gain=FAKE, n=100, idx=FAKE, val=FAKE, m=4, alpha=0.5):
+        return L.kb_update_gain(gain, n, idx, val, m, ctypes.c_float(alpha), None)
+
+    assert ug(gain=None) == 1 and ug(idx=None) == 1 and ug(val=None) == 1
+    assert ug(n=-1) == 2 and ug(m=-1) == 2 and ug(alpha=-0.1) == 2 and ug(alpha=1.5) == 2 and ug(alpha=float("nan")) == 2
+    assert ug(idx=ctypes.c_void_p((1 << 20) + 2)) == 2 and ug(m=0) == 0
+
+    st, a = _create(L, cap=100, tags=FAKE)
+    st, b = _create(L, cap=100, tags=FAKE, keys=ctypes.c_void_p(2 << 20), inv=ctypes.c_void_p(3 << 20))
+    assert L.kb_remove(None, FAKE, 1, None) == 1 and L.kb_remove(a, None, 1, None) == 1
+    assert L.kb_remove(a, FAKE, -1, None) == 2 and L.kb_remove(a, FAKE, 0, None) == 0
+    assert L.kb_remove(a, FAKE, 3, None) == 0                                        # empty knowledge base: nothing to mark
+    ws = L.kb_compact_workspace_bytes(a)
+    assert ws > 0 and ws % 256 == 0 and L.kb_compact_workspace_bytes(None) == 0
+    live = ctypes.c_int64(-1)
+
+    def cp(src=a, dst=b, gs=None, gd=None, imap=None, w=FAKE, wb=ws):
+        return L.kb_compact(src, dst, gs, gd, imap, w, wb, None, ctypes.byref(live))
+
+    assert cp(src=None) == 1 and cp(dst=None) == 1 and cp(dst=a) == 2               # a store cannot be compacted into itself
+    assert cp(gs=FAKE) == 1 and cp(gd=FAKE) == 1                                     # the gain arrays come in pairs
+    assert cp(w=None) == 7 and cp(wb=0) == 7 and cp(w=ctypes.c_void_p((1 << 20) + 64)) == 7
+    assert cp() == 0 and live.value == 0 and L.kb_size(b) == 0                       # empty source: nothing launched
+    st, c = _create(L, cap=100, keys=ctypes.c_void_p(4 << 20), inv=ctypes.c_void_p(5 << 20))           # untagged
+    st, e = _create(L, d=256, cap=100, tags=FAKE, keys=ctypes.c_void_p(6 << 20), inv=ctypes.c_void_p(7 << 20))
+    st, f = _create(L, dtype=kbmod.KB_F32, cap=100, tags=FAKE, keys=ctypes.c_void_p(8 << 20), inv=ctypes.c_void_p(9 << 20))
+    assert cp(dst=c) == 2 and cp(dst=e) == 2 and cp(dst=f) == 3
+    for h in (a, b, c, e, f):
+        L.kb_destroy(h)
 
 
 def test_tuning_knobs(L):
