@@ -33,7 +33,7 @@ DRAW_OPS_PER_PAIR = 36
 # HBM bytes per launch of the main-pass scan kernel on the default workload with the default kernel choice, from
 # rocprofv3 --pmc FETCH_SIZE (x 2.0: what the same counter under-reads on a copy of known size) and WRITE_SIZE (x 1.0).
 # Applies to that workload and kernel only.
-SCAN_TRAFFIC_BYTES_FILTERED = 1173825 * 1024 * 2.0 + 2620 * 1024 * 1.0
+SCAN_TRAFFIC_BYTES_FILTERED = 1175629 * 1024 * 2.0 + 2621 * 1024 * 1.0
 
 
 def make_workload(name: str, seed: int, device):
@@ -87,6 +87,64 @@ def run_quantize(args, torch, kbmod, W, dev):
                       "warmup": args.warmup, "dtype": "bf16 -> fp8_e4m3", "data": "synthetic", "shapes": out,
                       "roofline": {"bound": "hbm", "kernel": "quantize_rows_kernel", "achieved": out[0]["GBps"], "peak": HBM_PEAK_GBPS,
                                    "unit": "GB/s", "frac": out[0]["frac_of_hbm_peak"], "traffic": None}}))
+
+
+def run_maintain(args, torch, kbmod, W, dev):
+    """Maintenance of the filtered knowledge base (2^20 x 1024 bf16, tagged): revise 8192 gains, remove a random 10 %
+    of the entries, query with the removed entries in place, compact into a second store, query the compacted store."""
+    w, desc = make_workload("filtered", args.seed, dev)
+    N, d, Q, k = w.N, w.d, w.Q, w.k
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(args.seed + 5)
+
+    def timed(fn, reps):
+        for _ in range(2):
+            fn()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for e0, e1 in evs:
+            e0.record()
+            fn()
+            e1.record()
+        torch.cuda.synchronize()
+        return _median([e0.elapsed_time(e1) for e0, e1 in evs])
+
+    src = kbmod.KnowledgeBase(d, kbmod.KB_BF16, N, tagged=True)
+    src.keys.copy_(w.keys)
+    src.tags.copy_(w.tags)
+    src.append_in_place(N)
+    src.normalize()
+    out_i = torch.empty((Q, k), dtype=torch.int32, device=dev)
+    out_s = torch.empty((Q, k), dtype=torch.float32, device=dev)
+    q_before = timed(lambda: src.query(w.queries, k, w.qmask, out_i, out_s), args.steps)
+    gain = torch.empty(N, dtype=torch.float32, device=dev).uniform_(0.25, 4.0, generator=gen)
+    upd_i = torch.randperm(N, generator=gen, device=dev)[:8192].to(torch.int32)
+    upd_v = torch.empty(8192, dtype=torch.float32, device=dev).uniform_(0.0, 8.0, generator=gen)
+    t_update = timed(lambda: kbmod.update_gain(gain, upd_i, upd_v, 0.5), args.steps)
+    rm = torch.randperm(N, generator=gen, device=dev)[:N // 10].to(torch.int32)
+    t_remove = timed(lambda: src.remove(rm), args.steps)
+    q_removed = timed(lambda: src.query(w.queries, k, w.qmask, out_i, out_s), args.steps)
+    live = N - N // 10
+    dsts = []
+
+    def compact_once():
+        dst = kbmod.KnowledgeBase(d, kbmod.KB_BF16, live, tagged=True)
+        dsts.append(dst)
+        while len(dsts) > 1:
+            dsts.pop(0).close()
+        got, _, _ = src.compact_into(dst, gain=gain)
+        assert got == live
+
+    t_compact = timed(compact_once, 5)       # includes the allocation of the destination and the one synchronisation
+    dst = dsts[-1]
+    q_compacted = timed(lambda: dst.query(w.queries, k, w.qmask, out_i, out_s), args.steps)
+    nbytes = live * (2 * d * 2 + 2 * (4 + 8 + 4)) + N * (4 + 4 + 4)
+    print(json.dumps({"metric": "knowledge-base maintenance, N=1M d=1024 bf16", "unit": "ms", "n_gpus": 1, "steps": args.steps,
+                      "dtype": "bf16", "data": "synthetic", "config": {"workload": desc + "; 8192 gains revised, 10 % removed, compacted"},
+                      "update_gain_ms": t_update, "remove_ms": t_remove, "compact_ms": t_compact,
+                      "query_ms": {"before": q_before, "with_removed_entries": q_removed, "compacted": q_compacted},
+                      "roofline": {"bound": "hbm", "kernel": "kb_compact (count + offset scan + gather, with the host synchronisation)",
+                                   "achieved": nbytes / (t_compact * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                   "frac": nbytes / (t_compact * 1e-3) / 1e9 / HBM_PEAK_GBPS, "traffic": None, "algorithmic_bytes": nbytes}}))
 
 
 def run_growing(args, torch, kbmod, W, dev):
@@ -194,6 +252,7 @@ def main():
     ap.add_argument("--draw", action="store_true",
                     help="time the weighted random selection (kb_query_sampled: gains uniform in [0.25, 4], temperature "
                          "0.05) instead of the plain top-k")
+    ap.add_argument("--maintain", action="store_true", help="time kb_update_gain / kb_remove / kb_compact and queries around them instead")
     ap.add_argument("--quantize", action="store_true", help="time kb_quantize_rows instead")
     ap.add_argument("--q-sweep", action="store_true", help="time query batches of 1..512 on the N=2^20 bf16 knowledge base instead")
     args = ap.parse_args()
@@ -217,6 +276,8 @@ def main():
         return run_q_sweep(args, torch, kbmod, W, dev)
     if args.quantize:
         return run_quantize(args, torch, kbmod, W, dev)
+    if args.maintain:
+        return run_maintain(args, torch, kbmod, W, dev)
     if args.workload == "growing":
         return run_growing(args, torch, kbmod, W, dev)
     w, desc = make_workload(args.workload, args.seed, dev)
