@@ -37,6 +37,9 @@
     XS(14, KB_BF16, 256, 4, 5)      \
     XS(15, KB_BF16, 128, 5, 4)      \
     XS(16, KB_BF16, 128, 6, 4)
+// ... with the loads between the MFMAs (IL mode)
+#define KB_SCAN_SP_CONFIGS_BF16_IL(XI) \
+    XI(17, KB_BF16, 256, 5, 4)
 #define KB_SCAN_SP_CONFIGS_FP8(XS)  \
     XS(4, KB_FP8_E4M3, 256, 3, 3)
 // ... with fp8 queries as well (the fp8 matrix instruction): XQ(id, key dtype, TQ, NSA, NSB)

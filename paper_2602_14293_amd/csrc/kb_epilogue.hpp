@@ -91,10 +91,11 @@ __device__ inline void main_block(const f32x16 &a, const EpiRows &rw, float tp, 
             const int rl = rw.rl0 + 8 * (i >> 2) + (i & 3);
             const int64_t row = row0 + rl;
             const float ik = sd.invk[rl];
+            const uint64_t tg = filter ? sd.tag[rl] : 0ull;    // read with ik: one LDS round trip per element, not two
             const float s = final_score(a[i], ik, iq);
             const uint64_t cw = pack_candidate(s, (uint32_t)row);
             bool ok = has && row < p.n_keys && cw >= t64 && !row_removed(ik);
-            if (filter) ok = ok && (sd.tag[rl] & qm) != 0;
+            if (filter) ok = ok && (tg & qm) != 0;
             // slot in the wave's own record region: running count + rank among the lanes that append
             const uint64_t okm = __builtin_amdgcn_ballot_w64(ok);
             if (ok) {

@@ -11,6 +11,10 @@ hipError_t launch_scan_sp_bf16(int config, bool sample, int grid, const ScanArgs
     case ID: return launch_scan_sp_cfg<SPCfg<KT, TQ, NSA, NSB>>(sample, grid, a, s);
         KB_SCAN_SP_CONFIGS_BF16(XS)
 #undef XS
+#define XI(ID, KT, TQ, NSA, NSB) \
+    case ID: return launch_scan_sp_cfg<SPCfg<KT, TQ, NSA, NSB, false, true>>(sample, grid, a, s);
+        KB_SCAN_SP_CONFIGS_BF16_IL(XI)
+#undef XI
     default: return hipErrorInvalidValue;
     }
 }
