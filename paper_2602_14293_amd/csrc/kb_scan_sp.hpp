@@ -19,12 +19,14 @@
 // barrier g+1 once its share of chunk g+2 has landed (NS-3 younger chunks still in flight).  Key chunks
 // come from HBM and get a ring of 5, query chunks come from L2 and get 4.
 //
-// IL mode (bf16, 256-query blocks): no split into compute-first and load-first waves.  Every wave issues its share
-// of the direct-to-LDS loads of chunk g + NS - 1 *between the MFMAs* of chunk g (one load after every fourth MFMA),
-// then waits, meets the one barrier, and runs a finished item's epilogue after it.  Measured on the 2^20 x 1024
-// bf16 workload this is about 3 % faster than the split: a wave stalled in the issue of a direct-to-LDS load does
-// not leave its SIMD's matrix core to the other wave as well as a wave that has MFMAs in flight does (probe: 16
-// MFMAs + 4 loads per wave and chunk take 0.46 ms interleaved, 0.49 ms in two phases, 0.50 ms split).
+// IL mode (256-query blocks of bf16 x bf16 and of fp8 x fp8): no split into compute-first and load-first
+// waves.  Every wave issues its share of the direct-to-LDS loads of chunk g + NS - 1 *between the MFMAs* of
+// chunk g (one load after every fourth bf16 MFMA, after every second fp8 MFMA), then waits, meets the one
+// barrier, and runs a finished item's epilogue after it.  A wave held in the issue of a direct-to-LDS load
+// does not leave its SIMD's matrix core to the other wave as well as a wave with MFMAs in flight does
+// (probe: 16 MFMAs + 4 loads per wave and chunk take 0.46 ms interleaved, 0.49 ms in two phases, 0.50 ms
+// split).  Measured gain over the split: 2-3 % on 2^20 x 1024 bf16 keys with 256 queries, 5 % on 2^22 x 768
+// fp8 keys with 1024 fp8 queries; fp8 keys with bf16 queries (32 MFMAs per chunk) gain nothing and keep it.
 //
 // LDS layout, swizzle and load pattern of a chunk are those of kb_scan_pp.hpp (64-byte rows, 16 rows per
 // load instruction: requests of 64 bytes are what the L2 serves best; 32-byte requests cost 1.6x the L2
@@ -78,7 +80,7 @@ template <int KT_, int TQ_, int NSA_, int NSB_, bool QF8_ = false, bool IL_ = fa
     static_assert((KT == KB_BF16 && BMUL == 1 && !QF8) || (KT == KB_FP8_E4M3 && TQ == 256 && (BMUL == 2 || QF8)), "key types the kernel is written for");
     static_assert(NSA >= 3 && NSA <= 6 && NSB >= 3 && NSB <= 6, "ring depths the waits are written for");
     static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget");
-    static_assert(!IL || (KT == KB_BF16 && TQ == 256), "the interleaved mode is written for bf16 keys and 256-query blocks");
+    static_assert(!IL || (TQ == 256 && (KT == KB_BF16 || QF8)), "the interleaved mode is written for 256-query blocks of bf16 x bf16 and fp8 x fp8");
 };
 
 template <class C, bool SAMPLE>
@@ -356,16 +358,47 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
         }
     };
 
+    // interleaved mode: what precedes and what follows an iteration's MFMAs
+    auto begin_iteration_il = [&]() {
+        if (nqb > 1 && c == 1) issue_query_aux(qb);     // every epilogue of the previous item ended before the last barrier
+        issue_prepare();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto finish_iteration_il = [&]() {
+        issue_finish();
+        stageA = stageA + 1 == C::NSA ? 0 : stageA + 1;
+        stageB = stageB + 1 == C::NSB ? 0 : stageB + 1;
+        if (++c == NC) {
+            pending = true;
+            e_tile = tile;
+            e_qb = qb;
+            e_par = par;
+            c = 0;
+            par ^= 1;
+            tile += step_tile;
+            qb += step_qb;
+            if (qb >= nqb) {
+                qb -= nqb;
+                ++tile;
+            }
+        }
+        wait_landed();
+        __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
+        __builtin_amdgcn_sched_barrier(0);
+        bare_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        if (pending) {
+            epilogue(e_tile, e_qb, e_par);
+            pending = false;
+        }
+    };
+
     if constexpr (!C::QF8) {
         for (int g = 0; g < total; ++g) {
             // Waves 0-3: compute(g), load(g), barrier.  Waves 4-7: [load(g) was done before the previous barrier's
             // successor, see below] compute(g), barrier, load(g+1).  One code path, two barrier positions.
             const int c_now = c, qb_now = qb;
-            if constexpr (C::IL) {
-                if (nqb > 1 && c == 1) issue_query_aux(qb);     // every epilogue of the previous item ended before the last barrier
-                issue_prepare();
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            if constexpr (C::IL) begin_iteration_il();
             {
                 const int nA = stageA + 1 == C::NSA ? 0 : stageA + 1, nB = stageB + 1 == C::NSB ? 0 : stageB + 1;
                 // past the last chunk the refill of X reads the current slot again (valid memory, values unused)
@@ -475,32 +508,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
 
             }
             if constexpr (C::IL) {
-                issue_finish();
-                stageA = stageA + 1 == C::NSA ? 0 : stageA + 1;
-                stageB = stageB + 1 == C::NSB ? 0 : stageB + 1;
-                if (++c == NC) {
-                    pending = true;
-                    e_tile = tile;
-                    e_qb = qb;
-                    e_par = par;
-                    c = 0;
-                    par ^= 1;
-                    tile += step_tile;
-                    qb += step_qb;
-                    if (qb >= nqb) {
-                        qb -= nqb;
-                        ++tile;
-                    }
-                }
-                wait_landed();
-                __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
-                __builtin_amdgcn_sched_barrier(0);
-                bare_barrier();
-                __builtin_amdgcn_sched_barrier(0);
-                if (pending) {
-                    epilogue(e_tile, e_qb, e_par);
-                    pending = false;
-                }
+                finish_iteration_il();
             } else {
                 finish_iteration(c_now, qb_now);
             }
@@ -531,6 +539,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
         fq0.hi = read_b8(0, 0, 1);
         auto iteration8 = [&](int g, const i32x8 (&ca)[IB], i32x8 (&na)[IB]) {
             const int c_now = c, qb_now = qb;
+            if constexpr (C::IL) begin_iteration_il();
             const int nA = stageA + 1 == C::NSA ? 0 : stageA + 1, nB = stageB + 1 == C::NSB ? 0 : stageB + 1;
             // past the last chunk the refill reads the current slot again (valid memory, values unused)
             const int xA = g + 1 < total ? nA : stageA, xB = g + 1 < total ? nB : stageB;
@@ -543,6 +552,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
             fq1.hi = read_b8(stageB, 1, 1);
             __builtin_amdgcn_sched_barrier(0);
             KB_SP_MFMA8(1, 0, fq0);
+            KB_SP_LOAD(0);
             na[0].lo = read_a8(xA, 0, 0);
             na[0].hi = read_a8(xA, 0, 1);
             __builtin_amdgcn_sched_barrier(0);
@@ -551,6 +561,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
             fq0.hi = read_b8(stageB, 2, 1);
             __builtin_amdgcn_sched_barrier(0);
             KB_SP_MFMA8(1, 1, fq1);
+            KB_SP_LOAD(1);
             na[1].lo = read_a8(xA, 1, 0);
             na[1].hi = read_a8(xA, 1, 1);
             __builtin_amdgcn_sched_barrier(0);
@@ -559,14 +570,17 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
             fq1.hi = read_b8(stageB, 3, 1);
             __builtin_amdgcn_sched_barrier(0);
             KB_SP_MFMA8(1, 2, fq0);
+            KB_SP_LOAD(2);
             KB_SP_MFMA8(0, 3, fq1);
             fq0.lo = read_b8(xB, 0, 0);
             fq0.hi = read_b8(xB, 0, 1);
             __builtin_amdgcn_sched_barrier(0);
+            KB_SP_LOAD(3);
             KB_SP_MFMA8(1, 3, fq1);
 #undef KB_SP_MFMA8
             __builtin_amdgcn_s_setprio(0);
-            finish_iteration(c_now, qb_now);
+            if constexpr (C::IL) finish_iteration_il();
+            else finish_iteration(c_now, qb_now);
         };
         for (int g = 0; g < total; g += 2) {
             iteration8(g, fa0, fa1);

@@ -12,7 +12,7 @@ hipError_t launch_scan_sp_fp8(int config, bool sample, int grid, const ScanArgs 
         KB_SCAN_SP_CONFIGS_FP8(XS)
 #undef XS
 #define XQ(ID, KT, TQ, NSA, NSB) \
-    case ID: return launch_scan_sp_cfg<SPCfg<KT, TQ, NSA, NSB, true>>(sample, grid, a, s);
+    case ID: return launch_scan_sp_cfg<SPCfg<KT, TQ, NSA, NSB, true, true>>(sample, grid, a, s);
         KB_SCAN_SP_CONFIGS_FP8_Q8(XQ)
 #undef XQ
     default: return hipErrorInvalidValue;
