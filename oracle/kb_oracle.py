@@ -212,6 +212,51 @@ def compact(removed, *arrays):
     return index_map, [np.ascontiguousarray(np.asarray(a)[live]) for a in arrays]
 
 
+# ---- two-stage retrieval: the paper's knowledge base is a hierarchy, states first and each state's candidate
+# optimizations below it (Section 3, the knowledge-base format figure and the walk through one task: the state is
+# matched first, its optimizations are looked at afterwards).  Numeric model: entries are grouped into clusters
+# ("states"), rows of cluster c are [offsets[c], offsets[c+1]); a query first ranks the cluster centroids like any
+# other keys, keeps the best `nprobe` clusters, and the exact retrieval then runs over the rows of those clusters
+# only.  An approximation of the exact retrieval by construction; its quality is reported as recall@k.
+
+def restricted_to_clusters(scores, cluster_offsets, probe) -> np.ndarray:
+    """scores [Q, N] with, for query r, every row outside the clusters probe[r, :] at -inf (never a candidate).
+    Entries of probe outside [0, C) (the -1 padding of a result list) are skipped."""
+    out = np.full(np.shape(scores), -np.inf, dtype=np.float64)
+    scores = np.asarray(scores, dtype=np.float64)
+    off = np.asarray(cluster_offsets, dtype=np.int64)
+    C = off.shape[0] - 1
+    for r in range(scores.shape[0]):
+        for c in np.asarray(probe[r]).tolist():
+            if 0 <= c < C:
+                out[r, off[c]:off[c + 1]] = scores[r, off[c]:off[c + 1]]
+    return out
+
+
+def two_stage(keys, key_dtype, centroids, centroid_dtype, cluster_offsets, queries, q_dtype, nprobe, k, row_scale=None,
+              tags=None, qmask=None):
+    """(index [Q, k], score [Q, k], probe [Q, nprobe], restricted scores [Q, N]): centroid ranking, then exact
+    retrieval over the rows of the nprobe best clusters."""
+    probe, _ = query(centroids, centroid_dtype, queries, q_dtype, nprobe)
+    full = restricted_to_clusters(score_matrix(keys, key_dtype, queries, q_dtype, row_scale=row_scale), cluster_offsets, probe)
+    Q = full.shape[0]
+    idx = np.empty((Q, k), dtype=np.int64)
+    sc = np.empty((Q, k), dtype=np.float64)
+    for r in range(Q):
+        idx[r], sc[r], _ = select(full[r], k, tags=tags, qmask=None if qmask is None else qmask[r])
+    return idx, sc, probe, full
+
+
+def recall_at_k(found, exact) -> float:
+    """Mean over queries of |found ∩ exact| / |exact| (valid entries only; a query with no exact entry counts as 1)."""
+    tot = 0.0
+    for f, e in zip(np.asarray(found), np.asarray(exact)):
+        e = set(int(x) for x in e if x >= 0)
+        f = set(int(x) for x in f if x >= 0)
+        tot += 1.0 if not e else len(e & f) / len(e)
+    return tot / len(found)
+
+
 def query(keys, key_dtype, queries, q_dtype, k, row_scale=None, tags=None, qmask=None, return_scores=False):
     """Full retrieval.  Returns (index int64[Q,k], score float64[Q,k][, scores float64[Q,N]])."""
     keys = _bits(keys, key_dtype, "keys")

@@ -510,3 +510,57 @@ def test_compaction_is_a_stable_filter(oracle):
     assert ident.tolist() == list(range(n)) and np.array_equal(k3, keys)
     none, (k4,) = oracle.compact(np.ones(n, dtype=bool), keys)
     assert np.all(none == -1) and k4.shape[0] == 0
+
+
+# ---------------- two-stage retrieval -----------------------------------------------------------
+
+def _clustered(rng, C, per, d, spread):
+    centres = rng.normal(size=(C, d))
+    centres /= np.linalg.norm(centres, axis=1, keepdims=True)
+    sizes = rng.integers(per // 2, per * 2, size=C)
+    sizes[3] = 0                                                   # an empty cluster
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    keys = np.concatenate([centres[c] + spread * rng.normal(size=(sizes[c], d)) for c in range(C)]).astype(np.float32)
+    return centres.astype(np.float32), off, keys
+
+
+def test_two_stage_against_brute_force_and_exact(oracle):
+    rng = np.random.default_rng(77)
+    C, d, k = 12, 16, 9
+    centres, off, keys = _clustered(rng, C, 20, d, 0.15)
+    N = keys.shape[0]
+    q = (keys[rng.integers(0, N, size=6)] + 0.05 * rng.normal(size=(6, d))).astype(np.float32)
+    exact_idx, exact_sc = oracle.query(keys, F32, q, F32, k)
+    prev = None
+    for nprobe in (1, 2, 5, C):
+        idx, sc, probe, full = oracle.two_stage(keys, F32, centres, F32, off, q, F32, nprobe, k)
+        # brute force: rank the centroids by cosine, take the rows of the best nprobe clusters, rank those
+        cs = (q / np.linalg.norm(q, axis=1, keepdims=True)) @ (centres / np.linalg.norm(centres, axis=1, keepdims=True)).T
+        S = (q / np.linalg.norm(q, axis=1, keepdims=True)).astype(np.float64) @ (keys / np.linalg.norm(keys, axis=1, keepdims=True)).astype(np.float64).T
+        for r in range(6):
+            best = sorted(range(C), key=lambda c: (-cs[r, c], c))[:nprobe]
+            assert probe[r].tolist() == best
+            rows = [i for c in best for i in range(off[c], off[c + 1])]
+            want = sorted(rows, key=lambda i: (-S[r, i], i))[:k]
+            got = [int(i) for i in idx[r] if i >= 0]
+            assert got == want and np.all(idx[r, len(want):] == -1)
+            assert np.all(np.isneginf(full[r, [i for i in range(N) if i not in rows]]))
+        # what the approximation promises: exact when every cluster is probed, and a recall that never falls as nprobe grows
+        rec = oracle.recall_at_k(idx, exact_idx)
+        if nprobe == C:
+            assert np.array_equal(idx, exact_idx) and np.array_equal(sc, exact_sc) and rec == 1.0
+        assert prev is None or rec >= prev
+        prev = rec
+    # a perturbed copy of a stored key finds that key through its own cluster
+    idx, sc, probe, _ = oracle.two_stage(keys, F32, centres, F32, off, q, F32, 1, 1)
+    assert oracle.recall_at_k(idx, exact_idx[:, :1]) >= 5 / 6
+
+
+def test_recall_metric_and_probe_padding(oracle):
+    assert oracle.recall_at_k([[1, 2, 3, -1]], [[3, 2, 9, -1]]) == 2 / 3
+    assert oracle.recall_at_k([[1, 2], [5, 6]], [[1, 2], [7, 8]]) == 0.5
+    assert oracle.recall_at_k([[-1, -1]], [[-1, -1]]) == 1.0
+    scores = np.arange(12, dtype=np.float64).reshape(2, 6)
+    off = [0, 2, 2, 6]                                             # cluster 1 is empty
+    out = oracle.restricted_to_clusters(scores, off, [[0, -1], [1, 7]])
+    assert out[0].tolist() == [0.0, 1.0] + [-np.inf] * 4 and np.all(np.isneginf(out[1]))
