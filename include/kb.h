@@ -155,6 +155,30 @@ kb_status_t kb_quantize_rows(const void *rows_dev, kb_dtype_t dtype, int64_t n, 
                              float *scale_out_dev, void *hip_stream);
 
 /*
+ * Two-stage retrieval, second stage.  The paper's knowledge base is a hierarchy: states, and below each state its
+ * candidate optimizations (Section 3, knowledge-base format and the walk through one task: the state is matched
+ * first).  Numeric model: the entries are grouped into clusters, rows of cluster c are
+ * [cluster_offsets[c], cluster_offsets[c+1]); a caller first ranks the cluster centroids (an ordinary kb_query on a
+ * knowledge base that holds the centroids; its index output is a probe list), then this call returns, for query r,
+ * the result kb_query defines, restricted to the entries of the clusters probe[r][0 .. nprobe-1].  Scores are
+ * bit-identical to those of kb_query, so the result is exactly the top-k of that subset; how much of the unrestricted
+ * top-k it contains (recall) depends on the clustering and on nprobe.
+ *   cluster_offsets_dev [n_clusters + 1] int64, non-decreasing, within [0, kb_size]; a cluster may be empty
+ *   probe_dev  [Q, nprobe] int32; entries outside [0, n_clusters) (the -1 padding of a result list) are skipped, a
+ *              cluster named twice counts once;  1 <= nprobe <= 64,  1 <= Q <= 65535
+ *   queries, q_dtype, qmask, k, outputs, stream: as kb_query (fp8 queries are accepted for any d here); removed
+ *   entries are never returned
+ *   workspace_dev  256-byte aligned, at least kb_query_probe_workspace_bytes(kb, Q, k, nprobe) (0 on invalid arguments)
+ * Cost is proportional to the rows of the probed clusters, not to kb_size: meant for small batches.
+ * Errors: as kb_query.
+ */
+size_t kb_query_probe_workspace_bytes(const kb_t *kb, int32_t Q, int32_t k, int32_t nprobe);
+kb_status_t kb_query_probe(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int32_t Q, const uint64_t *qmask_dev,
+                           int32_t k, const int64_t *cluster_offsets_dev, int32_t n_clusters, const int32_t *probe_dev,
+                           int32_t nprobe, int32_t *indices_out_dev, float *scores_out_dev, void *workspace_dev,
+                           size_t workspace_bytes, void *hip_stream);
+
+/*
  * Revision of predicted gains: the numeric side of the paper's ParameterUpdate step (Section 3; the last step of
  * the outer loop of Algorithm 2 rewrites the knowledge base from what the rollouts measured).  For j = 0 .. m-1:
  *     i = indices[j];   gain[i] <- gain[i] + alpha * (values[j] - gain[i])      (fp32: one subtraction, one fma)

@@ -532,7 +532,7 @@ struct FinalArgs {
 // KT = KT_FP8_Q8 stands for fp8 keys with fp8 queries (one fp8 matrix instruction per 64-byte chunk, as in the scan).
 constexpr int KT_FP8_Q8 = 3;
 typedef int i32x8 __attribute__((ext_vector_type(8)));
-template <int KT> __device__ void exhaustive_query(const FinalArgs &a, int q, uint64_t *buf, uint32_t *ctl)
+template <int KT> __device__ void exhaustive_query(const FinalArgs &a, int q, uint64_t *buf, uint32_t *ctl, int64_t row_begin, int64_t row_end)
 {
     constexpr bool Q8 = KT == KT_FP8_Q8;
     constexpr int KTT = Q8 ? (int)KB_FP8_E4M3 : KT;
@@ -551,9 +551,9 @@ template <int KT> __device__ void exhaustive_query(const FinalArgs &a, int q, ui
         *thr_local = 0;
     }
     __syncthreads();
-    for (int64_t row0 = 0; row0 < a.n_keys; row0 += 128) {
+    for (int64_t row0 = row_begin; row0 < row_end; row0 += 128) {
         int64_t my_row = row0 + wave * 32 + lrow;
-        if (my_row >= a.n_keys) my_row = a.n_keys - 1;
+        if (my_row >= row_end) my_row = row_end - 1;
         const unsigned char *krow = static_cast<const unsigned char *>(a.keys) + (size_t)my_row * key_row_bytes + half * 16;
         f32x16 acc;
 #pragma unroll
@@ -586,7 +586,7 @@ template <int KT> __device__ void exhaustive_query(const FinalArgs &a, int q, ui
         for (int i = 1; i < 16; ++i) v = (lrow == i) ? acc[i] : v;
         if (lrow < 16) {
             const int64_t row = row0 + wave * 32 + 8 * (lrow >> 2) + 4 * half + (lrow & 3);
-            if (row < a.n_keys && !row_removed(a.inv_norm[row]) && (!filter || (a.tags[row] & qm) != 0)) {
+            if (row < row_end && !row_removed(a.inv_norm[row]) && (!filter || (a.tags[row] & qm) != 0)) {
                 float value = final_score(v, a.inv_norm[row], iq);
                 if (a.draw.enabled) value = draw_key_of(value, a.draw, a.draw.first_query + (uint32_t)q, row);
                 const uint64_t cw = pack_candidate(value, (uint32_t)row);
@@ -621,7 +621,7 @@ template <int KT> __global__ __launch_bounds__(256) void finalize_kernel(FinalAr
     SelectScratch *sc = reinterpret_cast<SelectScratch *>(smem_raw + sizeof(uint64_t) * a.cand_cap + 16);
     const int q = blockIdx.x, tid = threadIdx.x;
     if (a.flag[q] != 0 && a.n_keys > 0) {
-        exhaustive_query<KT>(a, q, buf, ctl);
+        exhaustive_query<KT>(a, q, buf, ctl, 0, a.n_keys);
         if (tid == 0) atomicAdd(reinterpret_cast<unsigned long long *>(a.stats + 1), 1ull);
     } else {
         // gather the query's segments into one contiguous list
@@ -645,6 +645,66 @@ template <int KT> __global__ __launch_bounds__(256) void finalize_kernel(FinalAr
         const uint64_t cw = tid < a.cand_cap ? buf[tid] : 0ull;
         a.out_index[(size_t)q * a.k + tid] = cw ? (int32_t)candidate_index(cw) : -1;
         a.out_score[(size_t)q * a.k + tid] = cw ? candidate_score(cw) : -__builtin_inff();
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Two-stage retrieval, second stage: exact top-k of one query over the rows of the clusters it probes.
+// ------------------------------------------------------------------------------------------------
+constexpr int PROBE_CAP = 1024;        // LDS candidate buffer of a partial scan (words); k <= 128 fits eight times
+constexpr int PROBE_MAX_LISTS = 64;    // partial lists per query that the merge can take: 64 x 128 = MAX_CAND_CAP words
+
+template <int QT> __global__ __launch_bounds__(256) void probe_prep_kernel(const void *queries, int Q, int d, float *invq)
+{
+    const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row < Q) {
+        const float inv = row_inv_norm<QT>(queries, row, d * (QT == KB_F32 ? 4 : QT == KB_BF16 ? 2 : 1), lane);
+        if (lane == 0) invq[row] = inv;
+    }
+}
+
+// Block (p, s, q): part s of `splits` of the rows of cluster probe[q][p], scored exactly as the scan kernels score
+// (same MFMA sequence per element), best k written as a sorted list of candidate words (zero = no entry).
+template <int KT> __global__ __launch_bounds__(256) void probe_scan_kernel(FinalArgs a, const int64_t *cluster_offsets, int n_clusters,
+                                                                         const int32_t *probe, int nprobe, int splits, uint64_t *lists)
+{
+    __shared__ __attribute__((aligned(16))) uint64_t buf[PROBE_CAP];
+    __shared__ uint32_t ctl[4];
+    const int p = blockIdx.x, s = blockIdx.y, q = blockIdx.z, tid = threadIdx.x;
+    uint64_t *out = lists + ((size_t)q * nprobe * splits + (size_t)p * splits + s) * a.k;
+    const int c = probe[(size_t)q * nprobe + p];
+    bool first = true;          // a cluster named twice is scanned once (the merge takes distinct entries)
+    for (int e = 0; e < p; ++e) first = first && probe[(size_t)q * nprobe + e] != c;
+    int64_t begin = 0, end = 0;
+    if (first && c >= 0 && c < n_clusters) {
+        const int64_t cb = cluster_offsets[c], ce = cluster_offsets[c + 1];
+        if (cb >= 0 && ce <= a.n_keys && cb < ce) {
+            const int64_t len = ((ce - cb + splits - 1) / splits + 127) / 128 * 128;    // whole steps of the scorer
+            begin = cb + (int64_t)s * len;
+            end = begin + len < ce ? begin + len : ce;
+        }
+    }
+    if (begin >= end) {         // workgroup-uniform
+        if (tid < a.k) out[tid] = 0ull;
+        return;
+    }
+    exhaustive_query<KT>(a, q, buf, ctl, begin, end);
+    if (tid < a.k) out[tid] = buf[tid];
+}
+
+__global__ __launch_bounds__(256) void probe_merge_kernel(const uint64_t *lists, int n_lists, int k, int32_t *out_index, float *out_score)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    uint64_t *buf = reinterpret_cast<uint64_t *>(smem_raw);
+    const int n = n_lists * k, q = blockIdx.x, tid = threadIdx.x;
+    SelectScratch *sc = reinterpret_cast<SelectScratch *>(smem_raw + sizeof(uint64_t) * (size_t)(n > k ? n : k) + 16);
+    for (int i = tid; i < n; i += 256) buf[i] = lists[(size_t)q * n + i];
+    __syncthreads();
+    select_topk_desc(buf, n, k, sc, tid, 256);
+    if (tid < k) {
+        const uint64_t cw = buf[tid];
+        out_index[(size_t)q * k + tid] = cw ? (int32_t)candidate_index(cw) : -1;
+        out_score[(size_t)q * k + tid] = cw ? candidate_score(cw) : -__builtin_inff();
     }
 }
 
@@ -953,6 +1013,107 @@ kb_status_t kb_query_sampled(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
     if ((reinterpret_cast<uintptr_t>(gain_dev) & 3) != 0) return KB_ERR_INVALID_ARG;
     return run_query(kb, queries_dev, q_dtype, Q, qmask_dev, k, gain_dev, temperature, seed, first_query, indices_out_dev, keys_out_dev,
                      workspace_dev, workspace_bytes, hip_stream);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Two-stage retrieval, second stage (host side)
+// ------------------------------------------------------------------------------------------------
+namespace {
+
+// Parts a cluster's rows are split into, so that a small batch still fills the device: a function of (Q, nprobe) only.
+int probe_splits(int Q, int nprobe)
+{
+    int64_t s = (4 * (int64_t)ASSUMED_CUS + (int64_t)Q * nprobe - 1) / ((int64_t)Q * nprobe);
+    if (s > 16) s = 16;
+    if (s > PROBE_MAX_LISTS / nprobe) s = PROBE_MAX_LISTS / nprobe;
+    return s < 1 ? 1 : (int)s;
+}
+
+struct ProbePlan {
+    int splits;
+    size_t off_invq, off_lists, total;
+};
+
+bool make_probe_plan(int32_t Q, int32_t k, int32_t nprobe, ProbePlan *out)
+{
+    if (Q < 1 || Q > 65535 || k < 1 || k > KB_K_MAX || nprobe < 1 || nprobe > PROBE_MAX_LISTS) return false;
+    ProbePlan p;
+    p.splits = probe_splits(Q, nprobe);
+    p.off_invq = 0;
+    p.off_lists = align_up((size_t)Q * 4);
+    p.total = p.off_lists + align_up((size_t)Q * nprobe * p.splits * k * 8);
+    *out = p;
+    return true;
+}
+
+}  // namespace
+
+size_t kb_query_probe_workspace_bytes(const kb_t *kb, int32_t Q, int32_t k, int32_t nprobe)
+{
+    ProbePlan p;
+    return kb && make_probe_plan(Q, k, nprobe, &p) ? p.total : 0;
+}
+
+kb_status_t kb_query_probe(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int32_t Q, const uint64_t *qmask_dev, int32_t k,
+                           const int64_t *cluster_offsets_dev, int32_t n_clusters, const int32_t *probe_dev, int32_t nprobe,
+                           int32_t *indices_out_dev, float *scores_out_dev, void *workspace_dev, size_t workspace_bytes, void *hip_stream)
+{
+    if (!kb || !queries_dev || !cluster_offsets_dev || !probe_dev || !indices_out_dev || !scores_out_dev) return KB_ERR_NULL;
+    if (!valid_dtype((int)q_dtype)) return KB_ERR_DTYPE;
+    const kb_dtype_t want_q = kb->dtype == KB_F32 ? KB_F32 : KB_BF16;
+    const bool q8 = kb->dtype == KB_FP8_E4M3 && q_dtype == KB_FP8_E4M3;
+    if (q_dtype != want_q && !q8) return KB_ERR_DTYPE;
+    ProbePlan p;
+    if (n_clusters < 1 || !make_probe_plan(Q, k, nprobe, &p)) return KB_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(queries_dev) & 15) != 0 || (reinterpret_cast<uintptr_t>(cluster_offsets_dev) & 7) != 0 ||
+        (reinterpret_cast<uintptr_t>(probe_dev) & 3) != 0)
+        return KB_ERR_INVALID_ARG;
+    if (qmask_dev && !kb->tags) return KB_ERR_NO_TAGS;
+    if (kb->n_normalized != kb->n) return KB_ERR_NOT_NORMALIZED;
+    if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) & (WS_ALIGN - 1)) != 0 || workspace_bytes < p.total) return KB_ERR_WORKSPACE;
+
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    unsigned char *ws = static_cast<unsigned char *>(workspace_dev);
+    float *invq = reinterpret_cast<float *>(ws + p.off_invq);
+    uint64_t *lists = reinterpret_cast<uint64_t *>(ws + p.off_lists);
+    const int pgrid = (Q + 3) / 4;
+    if (q_dtype == KB_F32)
+        hipLaunchKernelGGL(probe_prep_kernel<KB_F32>, dim3(pgrid), dim3(256), 0, s, queries_dev, Q, kb->d, invq);
+    else if (q_dtype == KB_BF16)
+        hipLaunchKernelGGL(probe_prep_kernel<KB_BF16>, dim3(pgrid), dim3(256), 0, s, queries_dev, Q, kb->d, invq);
+    else
+        hipLaunchKernelGGL(probe_prep_kernel<KB_FP8_E4M3>, dim3(pgrid), dim3(256), 0, s, queries_dev, Q, kb->d, invq);
+
+    FinalArgs f;
+    memset(&f, 0, sizeof f);
+    f.keys = kb->keys;
+    f.inv_norm = kb->inv_norm;
+    f.tags = kb->tags;
+    f.queries = queries_dev;
+    f.qmask = qmask_dev;
+    f.invq = invq;
+    f.n_keys = kb->n;
+    f.d = kb->d;
+    f.k = k;
+    f.cand_cap = PROBE_CAP;
+    const dim3 grid(nprobe, p.splits, Q);
+    switch (q8 ? KT_FP8_Q8 : (int)kb->dtype) {
+    case KB_F32: hipLaunchKernelGGL(probe_scan_kernel<KB_F32>, grid, dim3(256), 0, s, f, cluster_offsets_dev, n_clusters, probe_dev, nprobe, p.splits, lists); break;
+    case KB_BF16: hipLaunchKernelGGL(probe_scan_kernel<KB_BF16>, grid, dim3(256), 0, s, f, cluster_offsets_dev, n_clusters, probe_dev, nprobe, p.splits, lists); break;
+    case KB_FP8_E4M3: hipLaunchKernelGGL(probe_scan_kernel<KB_FP8_E4M3>, grid, dim3(256), 0, s, f, cluster_offsets_dev, n_clusters, probe_dev, nprobe, p.splits, lists); break;
+    default: hipLaunchKernelGGL(probe_scan_kernel<KT_FP8_Q8>, grid, dim3(256), 0, s, f, cluster_offsets_dev, n_clusters, probe_dev, nprobe, p.splits, lists); break;
+    }
+    const int n_lists = nprobe * p.splits;
+    const size_t merge_lds = sizeof(uint64_t) * (size_t)(n_lists * k > k ? n_lists * k : k) + 16 + sizeof(SelectScratch);
+    static bool merge_attr = false;
+    if (!merge_attr) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&probe_merge_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                MAX_CAND_CAP * 8 + 16 + sizeof(SelectScratch)) != hipSuccess)
+            return KB_ERR_DEVICE;
+        merge_attr = true;
+    }
+    hipLaunchKernelGGL(probe_merge_kernel, dim3(Q), dim3(256), merge_lds, s, lists, n_lists, k, indices_out_dev, scores_out_dev);
+    return hipGetLastError() == hipSuccess ? KB_OK : KB_ERR_DEVICE;
 }
 
 kb_status_t kb_query_counters(const kb_t *kb, const void *workspace_dev, int64_t *out, void *hip_stream)

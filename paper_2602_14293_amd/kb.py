@@ -50,6 +50,10 @@ def lib() -> ctypes.CDLL:
         L.kb_query_workspace_bytes.argtypes = [vp, i32, i32]
         L.kb_query.restype = i32
         L.kb_query.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, vp, sz, vp]
+        L.kb_query_probe_workspace_bytes.restype = sz
+        L.kb_query_probe_workspace_bytes.argtypes = [vp, i32, i32, i32]
+        L.kb_query_probe.restype = i32
+        L.kb_query_probe.argtypes = [vp, vp, i32, i32, vp, i32, vp, i32, vp, i32, vp, vp, vp, sz, vp]
         L.kb_update_gain.restype = i32
         L.kb_update_gain.argtypes = [vp, i64, vp, vp, i64, ctypes.c_float, vp]
         L.kb_remove.restype = i32
@@ -122,6 +126,7 @@ class KnowledgeBase:
         self.inv_norm = torch.zeros(capacity, dtype=torch.float32, device=self.device)
         self.tags = torch.zeros(capacity, dtype=torch.int64, device=self.device) if tagged else None
         self._workspace = None
+        self._probe_workspace = None
         h = ctypes.c_void_p()
         _check(lib().kb_create(ctypes.byref(h), d, key_dtype, capacity, _ptr(self.keys), _ptr(self.scale),
                                _ptr(self.inv_norm), _ptr(self.tags)), "kb_create")
@@ -188,6 +193,24 @@ class KnowledgeBase:
                                       _ptr(out_index), _ptr(out_key), _ptr(self._workspace), self._workspace.numel(), _stream()),
                "kb_query_sampled")
         return out_index, out_key
+
+    def query_probe(self, queries: torch.Tensor, k: int, cluster_offsets: torch.Tensor, probe: torch.Tensor,
+                    qmask: Optional[torch.Tensor] = None):
+        """kb_query_probe: exact top-k over the rows of the clusters probe[r, :] (cluster c = rows offsets[c] .. offsets[c+1])."""
+        Q, nprobe = probe.shape
+        assert queries.is_contiguous() and queries.shape == (Q, self.d)
+        assert cluster_offsets.dtype == torch.int64 and cluster_offsets.is_contiguous() and probe.dtype == torch.int32 and probe.is_contiguous()
+        need = lib().kb_query_probe_workspace_bytes(self._h, Q, k, nprobe)
+        if need == 0:
+            raise KBError(2, "kb_query_probe_workspace_bytes")
+        if self._probe_workspace is None or self._probe_workspace.numel() < need:
+            self._probe_workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
+        out_index = torch.empty((Q, k), dtype=torch.int32, device=self.device)
+        out_score = torch.empty((Q, k), dtype=torch.float32, device=self.device)
+        _check(lib().kb_query_probe(self._h, _ptr(queries), _CODE_OF[queries.dtype], Q, _ptr(qmask), k, _ptr(cluster_offsets),
+                                    cluster_offsets.numel() - 1, _ptr(probe), nprobe, _ptr(out_index), _ptr(out_score),
+                                    _ptr(self._probe_workspace), self._probe_workspace.numel(), _stream()), "kb_query_probe")
+        return out_index, out_score
 
     def remove(self, indices: torch.Tensor):
         assert indices.dtype == torch.int32 and indices.is_contiguous()

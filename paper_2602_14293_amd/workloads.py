@@ -156,6 +156,35 @@ def compressed(seed: int = 0, N: int = 1 << 22, d: int = 768, Q: int = 1024, k: 
     return Workload("compressed-q8" if fp8_queries else "compressed", keys, queries, k, scale=scale, seed=seed)
 
 
+def grouped(seed: int = 0, C: int = 64, mean_size: int = 300, d: int = 256, spread: float = 0.03, Q: int = 8, k: int = 16,
+            dtype=torch.bfloat16, device="cpu", p_tag: Optional[float] = None):
+    """A knowledge base whose rows are grouped by cluster, for two-stage retrieval: C unit centres, cluster c holds
+    size_c rows = normalised (centre_c + spread * N(0,1) per coordinate), sizes uniform in [mean/4, 7 mean/4] with one
+    empty cluster; queries are perturbed copies of stored rows.  Returns (Workload, centroids [C, d] in `dtype` (fp8:
+    bf16), cluster_offsets int64 [C + 1])."""
+    g = _gen(seed, device)
+    centres = _unit_rows(torch.randn(C, d, generator=g, device=device))
+    sizes = torch.randint(max(mean_size // 4, 1), max(7 * mean_size // 4, 2), (C,), generator=g, device=device)
+    if C > 2:
+        sizes[C // 3] = 0
+    offsets = torch.zeros(C + 1, dtype=torch.int64, device=device)
+    offsets[1:] = torch.cumsum(sizes, 0)
+    N = int(offsets[-1])
+    owner = torch.repeat_interleave(torch.arange(C, device=device), sizes)
+    rows = _unit_rows(centres[owner] + spread * torch.randn(N, d, generator=g, device=device))
+    v = torch.randint(0, N, (Q,), generator=g, device=device)
+    queries = perturbed_queries(rows[v], spread / 2, g)
+    tags = qmask = scale = None
+    if p_tag is not None:
+        tags, qmask = random_bits64(N, p_tag, g, device), random_bits64(Q, p_tag, g, device)
+    if dtype == torch.float8_e4m3fn:
+        keys, scale = quantize_e4m3_rows(rows)
+        queries, cent = queries.to(torch.bfloat16), centres.to(torch.bfloat16)
+    else:
+        keys, queries, cent = rows.to(dtype), queries.to(dtype), centres.to(dtype)
+    return Workload("grouped", keys, queries, k, scale=scale, tags=tags, qmask=qmask, seed=seed), cent, offsets
+
+
 def growing_round(seed: int, round_index: int, n_new: int, d: int, Q: int, center_rows: torch.Tensor,
                   device="cpu", p_tag: float = 0.3):
     """One append round of the growing workload: n_new clustered bf16 rows + tags, and Q masked queries.

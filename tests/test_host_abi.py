@@ -33,7 +33,8 @@ def test_every_declared_symbol_is_exported(L):
     names = set(re.findall(r"\b(kb_[a-z_]+)\s*\(", header))
     assert {"kb_create", "kb_append", "kb_normalize", "kb_query_workspace_bytes", "kb_query", "kb_size",
             "kb_destroy", "kb_status_string", "kb_query_counters", "kb_set_tuning", "kb_query_sampled",
-            "kb_quantize_rows", "kb_update_gain", "kb_remove", "kb_compact", "kb_compact_workspace_bytes"} <= names
+            "kb_quantize_rows", "kb_update_gain", "kb_remove", "kb_compact", "kb_compact_workspace_bytes", "kb_query_probe",
+            "kb_query_probe_workspace_bytes"} <= names
     for n in names:
         assert hasattr(L, n), f"{n} is declared in kb.h but not exported by libkb.so"
 
@@ -158,6 +159,28 @@ def test_maintenance_argument_errors(L):
     assert cp(dst=c) == 2 and cp(dst=e) == 2 and cp(dst=f) == 3
     for h in (a, b, c, e, f):
         L.kb_destroy(h)
+
+
+def test_probe_argument_errors(L):
+    st, h = _create(L, cap=100, tags=FAKE)
+    ws = L.kb_query_probe_workspace_bytes(h, 4, 8, 3)
+    assert ws > 0 and ws % 256 == 0
+    assert L.kb_query_probe_workspace_bytes(h, 0, 8, 3) == 0 and L.kb_query_probe_workspace_bytes(h, 4, 129, 3) == 0
+    assert L.kb_query_probe_workspace_bytes(h, 4, 8, 0) == 0 and L.kb_query_probe_workspace_bytes(h, 4, 8, 65) == 0
+    assert L.kb_query_probe_workspace_bytes(None, 4, 8, 3) == 0
+
+    def qp(handle=h, queries=FAKE, qd=kbmod.KB_BF16, Q=4, qmask=None, k=8, off=FAKE, C=5, probe=FAKE, nprobe=3, oi=FAKE, os_=FAKE, w=FAKE, wb=ws):
+        return L.kb_query_probe(handle, queries, qd, Q, qmask, k, off, C, probe, nprobe, oi, os_, w, wb, None)
+
+    assert qp(handle=None) == 1 and qp(queries=None) == 1 and qp(off=None) == 1 and qp(probe=None) == 1 and qp(oi=None) == 1
+    assert qp(qd=kbmod.KB_F32) == 3 and qp(qd=kbmod.KB_FP8_E4M3) == 3
+    assert qp(Q=0) == 2 and qp(k=0) == 2 and qp(nprobe=0) == 2 and qp(nprobe=65) == 2 and qp(C=0) == 2
+    assert qp(off=ctypes.c_void_p((1 << 20) + 4)) == 2 and qp(probe=ctypes.c_void_p((1 << 20) + 2)) == 2
+    assert qp(w=None) == 7 and qp(wb=ws - 1) == 7
+    L.kb_destroy(h)
+    st, h2 = _create(L, cap=100)
+    assert qp(handle=h2, qmask=FAKE) == 6
+    L.kb_destroy(h2)
 
 
 def test_tuning_knobs(L):
