@@ -89,6 +89,73 @@ def run_quantize(args, torch, kbmod, W, dev):
                                    "unit": "GB/s", "frac": out[0]["frac_of_hbm_peak"], "traffic": None}}))
 
 
+def run_two_stage(args, torch, kbmod, W, dev):
+    """Two-stage retrieval on a grouped knowledge base (2^20 rows in 1024 clusters, d = 1024 bf16): per batch size and
+    nprobe, the latency of centroid ranking + kb_query_probe against the exhaustive kb_query, and the recall@k of the
+    two-stage result against the exhaustive one; the first batch is also checked against the CPU oracle."""
+    C, k = 1024, 32
+    w, cent, off = W.grouped(seed=args.seed, C=C, mean_size=1024, d=1024, spread=0.03, Q=32, k=k, dtype=torch.bfloat16, device=dev)
+    N = w.N
+    kb = kbmod.KnowledgeBase(w.d, kbmod.KB_BF16, N)
+    kb.keys[:N].copy_(w.keys)
+    kb.append_in_place(N)
+    kb.normalize()
+    ckb = kbmod.KnowledgeBase(w.d, kbmod.KB_BF16, C)
+    ckb.append(cent.contiguous())
+    ckb.normalize()
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        for e0, e1 in evs:
+            e0.record()
+            out = fn()
+            e1.record()
+        torch.cuda.synchronize()
+        return _median([e0.elapsed_time(e1) for e0, e1 in evs]), out
+
+    def recall(found, exact):
+        f, e = found.cpu().numpy(), exact.cpu().numpy()
+        return float(sum(len(set(a[a >= 0]) & set(b[b >= 0])) / max(len(set(b[b >= 0])), 1) for a, b in zip(f, e)) / len(f))
+
+    rows = []
+    for Q in (1, 8, 32):
+        q = w.queries[:Q].contiguous()
+        t_full, (ei, es) = timed(lambda: kb.query(q, k))
+        for nprobe in (1, 4, 16):
+            def two():
+                probe, _ = ckb.query(q, nprobe)
+                return kb.query_probe(q, k, off, probe)
+            t_two, (gi, gs) = timed(two)
+            rows.append({"Q": Q, "nprobe": nprobe, "two_stage_ms": t_two, "exhaustive_ms": t_full, "speedup": t_full / t_two,
+                         "recall_at_k": recall(gi, ei), "rows_scored_per_query": nprobe * N // C})
+    result = {"metric": "two-stage retrieval latency and recall@32, N=1M d=1024 bf16, 1024 clusters", "unit": "ms", "n_gpus": 1,
+              "steps": args.steps, "warmup": args.warmup, "dtype": "bf16", "data": "synthetic",
+              "config": {"workload": f"grouped KB: N={N} d=1024 bf16 in 1024 clusters (spread 0.03 per coordinate), k=32", "seed": args.seed},
+              "cases": rows}
+    if not args.no_cpu_baseline:
+        from oracle import compare, kb_oracle
+
+        nq, nprobe = 8, 4
+        q = w.queries[:nq].contiguous()
+        probe, _ = ckb.query(q, nprobe)
+        gi, gs = kb.query_probe(q, k, off, probe)
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        o_idx, o_sc, o_probe, full = kb_oracle.two_stage(W.key_bits(w.keys), kb_oracle.BF16, W.key_bits(cent), kb_oracle.BF16, off.cpu().numpy(),
+                                                         W.key_bits(q), kb_oracle.BF16, nprobe, k)
+        c1 = time.perf_counter()
+        same = [r for r in range(nq) if set(probe[r].cpu().tolist()) == set(o_probe[r].tolist())]
+        rep = compare.check(gi.cpu().numpy()[same], gs.cpu().numpy()[same], full[same], k, 2e-3, label="two-stage bench parity")
+        exact_idx, _ = kb_oracle.query(W.key_bits(w.keys), kb_oracle.BF16, W.key_bits(q), kb_oracle.BF16, k)
+        result["cpu_baseline"] = {"value": nq / (c1 - c0), "unit": "queries/s", "cores": kb_oracle.num_threads(), "kind": "oracle",
+                                  "sample": f"{nq} queries, nprobe {nprobe}: centroid ranking + fp64 scores of all {N} keys restricted to the probed clusters, {c1 - c0:.1f} s"}
+        result["parity"] = {"queries_checked": rep.queries, "same_probe_set": len(same), "max_score_err": rep.max_score_err,
+                            "recall_at_k_vs_oracle_exact": kb_oracle.recall_at_k(gi.cpu().numpy(), exact_idx)}
+    print(json.dumps(result))
+
+
 def run_maintain(args, torch, kbmod, W, dev):
     """Maintenance of the filtered knowledge base (2^20 x 1024 bf16, tagged): revise 8192 gains, remove a random 10 %
     of the entries, query with the removed entries in place, compact into a second store, query the compacted store."""
@@ -252,6 +319,7 @@ def main():
     ap.add_argument("--draw", action="store_true",
                     help="time the weighted random selection (kb_query_sampled: gains uniform in [0.25, 4], temperature "
                          "0.05) instead of the plain top-k")
+    ap.add_argument("--two-stage", action="store_true", help="time centroid ranking + kb_query_probe against the exhaustive query and report recall@k instead")
     ap.add_argument("--maintain", action="store_true", help="time kb_update_gain / kb_remove / kb_compact and queries around them instead")
     ap.add_argument("--quantize", action="store_true", help="time kb_quantize_rows instead")
     ap.add_argument("--q-sweep", action="store_true", help="time query batches of 1..512 on the N=2^20 bf16 knowledge base instead")
@@ -278,6 +346,8 @@ def main():
         return run_quantize(args, torch, kbmod, W, dev)
     if args.maintain:
         return run_maintain(args, torch, kbmod, W, dev)
+    if args.two_stage:
+        return run_two_stage(args, torch, kbmod, W, dev)
     if args.workload == "growing":
         return run_growing(args, torch, kbmod, W, dev)
     w, desc = make_workload(args.workload, args.seed, dev)

@@ -91,6 +91,23 @@ int64_t pow2_ceil(int64_t x)
 }
 size_t align_up(size_t x) { return (x + WS_ALIGN - 1) / WS_ALIGN * WS_ALIGN; }
 
+// Multiplier of the sampling pass's row scatter j -> (j * m) mod n: about n / golden ratio, so that consecutive j
+// land far apart and fill the range evenly, and coprime to n, so that the map is one to one.
+uint64_t scatter_multiplier(int64_t n)
+{
+    if (n < 3) return 1;
+    uint64_t m = (uint64_t)((double)n * 0.6180339887498949) | 1u;
+    for (;; m += 2) {
+        uint64_t a = m, b = (uint64_t)n;
+        while (b) {
+            const uint64_t t = a % b;
+            a = b;
+            b = t;
+        }
+        if (a == 1) return m % (uint64_t)n;
+    }
+}
+
 // Pure function of (handle settings, row count n, Q, k): which kernels run on what, and where
 // everything lives in the workspace.
 bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, bool draw, bool q8, Plan *out)
@@ -492,10 +509,12 @@ __global__ __launch_bounds__(256) void bucket_kernel(const Record *regions, cons
     // better than few large ones)
     const uint32_t n = region_cnt[blockIdx.x];
     const Record *r = regions + (size_t)blockIdx.x * region_cap;
-    // all regions of a scan workgroup feed one segment (a query column is only seen by some of its waves)
-    const uint32_t seg = (blockIdx.x / waves_per_wg) % CAND_SEGMENTS, seg_cap = (uint32_t)cand_cap / CAND_SEGMENTS;
+    // A candidate's segment comes from its row number, so a query's candidates spread over all segments even when
+    // they sit in a few neighbouring tiles (rows grouped by cluster) and were found by a few workgroups.
+    const uint32_t seg_cap = (uint32_t)cand_cap / CAND_SEGMENTS;
     for (uint32_t i = threadIdx.x; i < n; i += 256) {
         const Record rec = r[i];
+        const uint32_t row = candidate_index(rec.cand), seg = (row ^ (row >> 4) ^ (row >> 8)) % CAND_SEGMENTS;
         const uint32_t slot = atomicAdd(&cnt[rec.query * CAND_SEGMENTS + seg], 1u);
         if (slot < seg_cap)
             cand[(size_t)rec.query * cand_cap + seg * seg_cap + slot] = rec.cand;
@@ -926,8 +945,17 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
         a.sample_slots = p.sample_slots;
         a.region_cap = p.region_cap;
         a.draw = dr;
+        a.tile_stride = 1;
+        a.row_mul = 0;
         if (p.sample_tiles > 0) {
+            // the sample is spread evenly over the knowledge base: a prefix says nothing about later rows when
+            // the rows are grouped (by state, by cluster, by age)
             a.n_tiles = p.sample_tiles;
+            a.tile_stride = (int32_t)(ceil_div(kb->n, p.tk) / p.sample_tiles);
+            // ... row by row where the kernel can gather (the weighted selection's keys are generated for runs of
+            // neighbouring rows, the two-phase and register-tile kernels load whole tiles: those take every
+            // tile_stride-th tile instead)
+            a.row_mul = (!draw && (p.sample_family == 0 || p.sample_family == 3)) ? scatter_multiplier(kb->n) : 0;
             int64_t sgrid = p.sample_tiles * p.nqb;
             const int64_t smax = (int64_t)(kb->cu_count > 0 ? kb->cu_count : ASSUMED_CUS) * p.sample_wgpc;
             if (sgrid > smax) sgrid = smax;
@@ -945,6 +973,8 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
             if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
         }
         a.n_tiles = ceil_div(kb->n, p.tk);
+        a.tile_stride = 1;
+        a.row_mul = 0;
         const bool timed = kb->prof_events && kb->prof_used < kb->prof_max;
         if (timed && hipEventRecord(kb->prof_events[2 * kb->prof_used], s) != hipSuccess) return KB_ERR_DEVICE;
         if (launch_scan(kb->dtype, p.config, p.family, false, p.grid, a, s) != hipSuccess) return KB_ERR_DEVICE;

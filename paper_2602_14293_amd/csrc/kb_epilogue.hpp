@@ -158,7 +158,7 @@ __device__ inline void sample_store(float best, int best_rl, int ql, const EpiSi
     if (q0 + ql < p.Q) {
         uint64_t cw = 0ull;
         if (best_rl >= 0)       // best = dot * inv_k was computed exactly as final_score's first product
-            cw = pack_candidate(best * sd.invq[ql] + 0.0f, (uint32_t)(row0 + best_rl));
+            cw = pack_candidate(best * sd.invq[ql] + 0.0f, sample_index(p, row0 + best_rl));
         p.samp[(size_t)(q0 + ql) * p.sample_slots + slot] = cw;
     }
 }

@@ -23,6 +23,7 @@
 // candidate compare, append to the workgroup's private record region (slot from an LDS counter, plain
 // global store).
 #pragma once
+#include <type_traits>
 #include "kb_epilogue.hpp"
 #include "kb_internal.hpp"
 
@@ -178,6 +179,7 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
 
     // items: (tile, qb) with qb fastest
     const int nqb = p.nqb;
+    const int64_t tstride = p.tile_stride;     // 1, or the distance between the tiles of a sampling pass
     const int64_t n_items = p.n_tiles * nqb;
     const int vb = item_lane(blockIdx.x, gridDim.x, nqb);      // this workgroup takes items vb, vb + gridDim.x, ...
     const int my_items = (int64_t)vb < n_items ? (int)((n_items - vb + gridDim.x - 1) / gridDim.x) : 0;
@@ -196,14 +198,17 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
     const uint32_t ldB_piece = (uint32_t)((((wave * 64 + lane) % C::PPRB) ^ swizzle<C::PPRB>(ldB_row)) * 16);
     int ld_tile = vb / nqb, ld_qb = vb % nqb;
     int ld_c = 0, ld_stage = 0;
-    uint32_t offA[LA], offB[LB];
+    typedef typename std::conditional<SAMPLE, uint64_t, uint32_t>::type OffA;   // a sampling pass addresses rows anywhere
+    OffA offA[LA];
+    uint32_t offB[LB];
     auto ld_setup = [&]() {
-        const int64_t left = p.n_keys - (int64_t)ld_tile * TK;      // >= 1 rows in this tile
+        const int64_t left = p.n_keys - ld_tile * tstride * TK;      // >= 1 rows in this tile
         const int last = left < TK ? (int)left - 1 : TK - 1;
 #pragma unroll
         for (int j = 0; j < LA; ++j) {
             const int r = ldA_row + j * RSTEP_A;
-            offA[j] = (uint32_t)(r < last ? r : last) * key_row_bytes + ldA_piece;
+            if constexpr (SAMPLE) offA[j] = (uint64_t)sample_row(p, ld_tile, TK, r) * key_row_bytes + ldA_piece;
+            else offA[j] = (uint32_t)(r < last ? r : last) * key_row_bytes + ldA_piece;
         }
         const int qlast = p.Q - 1 - ld_qb * TQ;
 #pragma unroll
@@ -215,7 +220,7 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
     auto issue_next = [&]() {
         unsigned char *sA = smem + ld_stage * C::STAGE_BYTES + wave * 1024;
         unsigned char *sB = sA + C::A_BYTES;
-        const unsigned char *gA = static_cast<const unsigned char *>(p.keys) + (size_t)ld_tile * TK * key_row_bytes + (size_t)ld_c * RBA;
+        const unsigned char *gA = static_cast<const unsigned char *>(p.keys) + (SAMPLE ? 0 : (size_t)(ld_tile * tstride) * TK * key_row_bytes) + (size_t)ld_c * RBA;
         const unsigned char *gB = static_cast<const unsigned char *>(p.queries) + (size_t)ld_c * RBB;
 #pragma unroll
         for (int j = 0; j < LA; ++j)
@@ -277,8 +282,9 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
             // unconditional loads from clamped / padded indices: nothing here is consumed before the epilogue,
             // so no wait on these loads lands inside the chunk loop
             if (tid < TK) {
-                int64_t r = (int64_t)tile * TK + tid;
+                int64_t r = tile * tstride * TK + tid;
                 r = r < p.n_keys ? r : p.n_keys - 1;
+                if constexpr (SAMPLE) r = sample_row(p, tile, TK, tid);
                 my_invk = p.inv_norm[r];
                 if (filter) my_tag = p.tags[r];
             }
@@ -338,7 +344,7 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
             }
             __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
             bare_barrier();
-            const int64_t row0 = (int64_t)tile * TK;
+            const int64_t row0 = SAMPLE ? sample_row0(p, tile, TK) : tile * tstride * TK;
             const EpiSide sd{aux_invk, aux_tag, reinterpret_cast<const float *>(smem + C::OFF_THRP), aux_invq, aux_thr64, aux_qmask};
             if (SAMPLE && DRAW)
                 sample_epilogue_draw<IB, JB>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p,

@@ -78,6 +78,7 @@ __global__ __launch_bounds__(256, 1) void kb_scan_big_kernel(ScanArgs p)
     const bool filter = p.qmask != nullptr;
 
     const int nqb = p.nqb;
+    const int64_t tstride = p.tile_stride;     // 1, or the distance between the tiles of a sampling pass
     const int64_t n_items = p.n_tiles * nqb;
     const int vb = item_lane(blockIdx.x, gridDim.x, nqb);      // this workgroup takes items vb, vb + gridDim.x, ...
     const int my_items = (int64_t)vb < n_items ? (int)((n_items - vb + gridDim.x - 1) / gridDim.x) : 0;
@@ -102,7 +103,7 @@ __global__ __launch_bounds__(256, 1) void kb_scan_big_kernel(ScanArgs p)
     uint32_t off[8];
     auto ld_setup = [&]() {
         if (role == 0) {
-            const int64_t left = p.n_keys - (int64_t)ld_tile * TK;
+            const int64_t left = p.n_keys - ld_tile * tstride * TK;
             const int last = left < TK ? (int)left - 1 : TK - 1;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
@@ -120,7 +121,7 @@ __global__ __launch_bounds__(256, 1) void kb_scan_big_kernel(ScanArgs p)
     };
     auto issue_aux = [&]() {
         unsigned char *aux = smem + C::OFF_AUX + ld_par * C::AUX_BYTES;
-        const int64_t row0 = (int64_t)ld_tile * TK;
+        const int64_t row0 = ld_tile * tstride * TK;
         {
             int64_t r = row0 + wave * 64 + lane;
             r = r < p.n_keys ? r : p.n_keys - 1;
@@ -157,7 +158,7 @@ __global__ __launch_bounds__(256, 1) void kb_scan_big_kernel(ScanArgs p)
         if (j == 0 && ld_c == 0) issue_aux();
         if (role == 0) {
             unsigned char *dst = smem + ld_stage * C::A_BYTES + ridx * 1024;
-            const unsigned char *g = static_cast<const unsigned char *>(p.keys) + (size_t)ld_tile * TK * key_row_bytes + (size_t)ld_c * RBA;
+            const unsigned char *g = static_cast<const unsigned char *>(p.keys) + (size_t)(ld_tile * tstride) * TK * key_row_bytes + (size_t)ld_c * RBA;
             __builtin_amdgcn_global_load_lds((const void *)(g + off[j]), (lds_ptr)(dst + j * 2048), 16, 0, 0);
         } else {
             unsigned char *dst = smem + C::OFF_B + ld_stage * C::B_BYTES + ridx * 1024;
@@ -206,7 +207,7 @@ __global__ __launch_bounds__(256, 1) void kb_scan_big_kernel(ScanArgs p)
         const EpiSide sd{reinterpret_cast<const float *>(aux + C::AUX_INVK), reinterpret_cast<const uint64_t *>(aux + C::AUX_TAG),
                          reinterpret_cast<const float *>(aux + C::AUX_THRP), reinterpret_cast<const float *>(aux + C::AUX_INVQ),
                          reinterpret_cast<const uint64_t *>(aux + C::AUX_THR64), reinterpret_cast<const uint64_t *>(aux + C::AUX_QMASK)};
-        const int64_t row0 = (int64_t)tile * TK;
+        const int64_t row0 = tile * tstride * TK;
         if (SAMPLE) {
 #pragma unroll
             for (int jb = 0; jb < JB; ++jb) {

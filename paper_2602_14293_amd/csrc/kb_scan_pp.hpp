@@ -74,6 +74,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_pp_kernel(ScanArgs p)
     const bool filter = p.qmask != nullptr;
 
     const int nqb = p.nqb;
+    const int64_t tstride = p.tile_stride;     // 1, or the distance between the tiles of a sampling pass
     const int64_t n_items = p.n_tiles * nqb;
     const int vb = item_lane(blockIdx.x, gridDim.x, nqb);      // this workgroup takes items vb, vb + gridDim.x, ...
     const int my_items = (int64_t)vb < n_items ? (int)((n_items - vb + gridDim.x - 1) / gridDim.x) : 0;
@@ -96,7 +97,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_pp_kernel(ScanArgs p)
     uint32_t off[LMAX];
     auto ld_setup = [&]() {
         if (role == 0) {
-            const int64_t left = p.n_keys - (int64_t)ld_tile * TK;
+            const int64_t left = p.n_keys - ld_tile * tstride * TK;
             const int last = left < TK ? (int)left - 1 : TK - 1;
 #pragma unroll
             for (int j = 0; j < LA; ++j) {
@@ -116,7 +117,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_pp_kernel(ScanArgs p)
     // (inv_norm, tags), 16-byte loads for the library's padded per-query arrays
     auto issue_aux = [&]() {
         unsigned char *aux = smem + C::OFF_AUX + ld_par * C::AUX_BYTES;
-        const int64_t row0 = (int64_t)ld_tile * TK;
+        const int64_t row0 = ld_tile * tstride * TK;
         if (wave < 4) {
             int64_t r = row0 + wave * 64 + lane;
             r = r < p.n_keys ? r : p.n_keys - 1;
@@ -158,7 +159,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_pp_kernel(ScanArgs p)
         if (role == 0) {
             if (j < LA) {
                 unsigned char *dst = smem + ld_stage * C::A_BYTES + ridx * 1024;
-                const unsigned char *g = static_cast<const unsigned char *>(p.keys) + (size_t)ld_tile * TK * key_row_bytes + (size_t)ld_c * RBA;
+                const unsigned char *g = static_cast<const unsigned char *>(p.keys) + (size_t)(ld_tile * tstride) * TK * key_row_bytes + (size_t)ld_c * RBA;
                 __builtin_amdgcn_global_load_lds((const void *)(g + off[j]), (lds_ptr)(dst + j * 4096), 16, 0, 0);
             }
         } else {
@@ -225,7 +226,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_pp_kernel(ScanArgs p)
         const float *aux_invq = reinterpret_cast<const float *>(aux + C::AUX_INVQ);
         const uint64_t *aux_thr64 = reinterpret_cast<const uint64_t *>(aux + C::AUX_THR64);
         const uint64_t *aux_qmask = reinterpret_cast<const uint64_t *>(aux + C::AUX_QMASK);
-        const int64_t row0 = (int64_t)tile * TK;
+        const int64_t row0 = tile * tstride * TK;
         const EpiSide sd{aux_invk, aux_tag, aux_thrp, aux_invq, aux_thr64, aux_qmask};
         if (SAMPLE)
             sample_epilogue<IB, JB>(acc, sd, filter, wm * 64, rowB, half, row0, qb * TQ, p,

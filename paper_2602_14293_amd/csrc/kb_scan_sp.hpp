@@ -99,6 +99,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
     const bool filter = p.qmask != nullptr;
 
     const int nqb = p.nqb;
+    const int64_t tstride = p.tile_stride;     // 1, or the distance between the tiles of a sampling pass
     const int64_t n_items = p.n_tiles * nqb;
     const int vb = item_lane(blockIdx.x, gridDim.x, nqb);      // this workgroup takes items vb, vb + gridDim.x, ...
     const int my_items = (int64_t)vb < n_items ? (int)((n_items - vb + gridDim.x - 1) / gridDim.x) : 0;
@@ -125,32 +126,36 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
     int ld_pos = 0;                                         // chunks issued so far
     int ld_tile = vb / nqb, ld_qb = vb % nqb;
     int ld_c = 0, ld_stage = 0, ld_par = 0;
-    uint32_t off[LC];
+    typedef typename std::conditional<SAMPLE, uint64_t, uint32_t>::type Off;   // a sampling pass addresses key rows anywhere
+    Off off[LC];
     size_t ld_base = 0;                                     // byte offset of the item's first row in the source
     bool last_full = false;
     auto ld_setup = [&]() {
-        const int last = role == 0 ? (int)(p.n_keys - (int64_t)ld_tile * TK < TK ? p.n_keys - (int64_t)ld_tile * TK - 1 : TK - 1)
+        const int last = role == 0 ? (int)(p.n_keys - ld_tile * tstride * TK < TK ? p.n_keys - ld_tile * tstride * TK - 1 : TK - 1)
                                    : p.Q - 1 - ld_qb * TQ;
 #pragma unroll
         for (int j = 0; j < LC; ++j) {
             const int r = ld_row + j * ld_rstep;
-            off[j] = (uint32_t)(r < last ? r : last) * row_bytes + ld_piece;
+            if (SAMPLE && role == 0) off[j] = (Off)((uint64_t)sample_row(p, ld_tile, TK, r) * row_bytes + ld_piece);
+            else off[j] = (uint32_t)(r < last ? r : last) * row_bytes + ld_piece;
         }
-        ld_base = role == 0 ? (size_t)ld_tile * TK * row_bytes : (size_t)ld_qb * TQ * row_bytes;
+        ld_base = role == 0 ? (SAMPLE ? 0 : (size_t)(ld_tile * tstride) * TK * row_bytes) : (size_t)ld_qb * TQ * row_bytes;
     };
     // side data of a key tile: 4-byte loads with clamped rows from the caller's arrays
     auto issue_tile_aux = [&]() {
         unsigned char *aux = smem + C::OFF_AUX + ld_par * C::AUX_BYTES;
-        const int64_t row0 = (int64_t)ld_tile * TK;
+        const int64_t row0 = ld_tile * tstride * TK;
         if (wave < 4) {
             int64_t r = row0 + wave * 64 + lane;
             r = r < p.n_keys ? r : p.n_keys - 1;
+            if constexpr (SAMPLE) r = sample_row(p, ld_tile, TK, wave * 64 + lane);
             __builtin_amdgcn_global_load_lds((const void *)(p.inv_norm + r), (lds_ptr)(aux + C::AUX_INVK + wave * 256), 4, 0, 0);
         }
         if (filter) {
             // tags as dwords: wave w covers dwords [64w, 64w+64) = rows [32w, 32w+32)
             int64_t r = row0 + wave * 32 + (lane >> 1);
             r = r < p.n_keys ? r : p.n_keys - 1;
+            if constexpr (SAMPLE) r = sample_row(p, ld_tile, TK, wave * 32 + (lane >> 1));
             __builtin_amdgcn_global_load_lds((const void *)(reinterpret_cast<const uint32_t *>(p.tags + r) + (lane & 1)),
                                              (lds_ptr)(aux + C::AUX_TAG + wave * 256), 4, 0, 0);
         }
@@ -264,7 +269,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
         const EpiSide sd{reinterpret_cast<const float *>(aux + C::AUX_INVK), reinterpret_cast<const uint64_t *>(aux + C::AUX_TAG),
                          reinterpret_cast<const float *>(qaux + C::QAUX_THRP), reinterpret_cast<const float *>(qaux + C::QAUX_INVQ),
                          reinterpret_cast<const uint64_t *>(qaux + C::QAUX_THR64), reinterpret_cast<const uint64_t *>(qaux + C::QAUX_QMASK)};
-        const int64_t row0 = (int64_t)tile * TK;
+        const int64_t row0 = SAMPLE ? sample_row0(p, tile, TK) : tile * tstride * TK;
         if (SAMPLE)
             sample_epilogue<IB, JB>(acc, sd, filter, wm * 64, rowB, half, row0, qb * TQ, p,
                                     (int64_t)tile * C::GROUPS_PER_TILE + wm * 2 + half);

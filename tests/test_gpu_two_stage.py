@@ -118,3 +118,13 @@ def test_two_stages_end_to_end_and_recall(T, nprobe):
     assert rec_gpu >= {1: 0.5, 4: 0.8, 16: 0.95}[nprobe], rec_gpu
     kb.close()
     ckb.close()
+
+
+@pytest.mark.parametrize("Q,k", [(40, 32), (300, 64)])
+def test_rows_grouped_by_cluster_stay_on_the_fast_path(T, Q, k):
+    # Rows sorted by cluster put a query's thousand near-identical candidates into a few neighbouring tiles and make a
+    # prefix of the rows unrepresentative; the sampling pass takes tiles from all over the rows and candidate lists
+    # are filled by row number, so no query has to be resolved by the exhaustive path.
+    w, cent, off = W.grouped(seed=Q, C=64, mean_size=1000, d=256, spread=0.03, Q=Q, k=k, dtype=torch.bfloat16)
+    rep, cnt, _ = T.run_and_check(w, label=f"grouped rows Q={Q}")
+    assert rep.queries == Q and cnt["exhaustive_queries"] == 0
