@@ -3,9 +3,9 @@
  *
  * The operation.  The paper's agent keeps a Persistent Knowledge Base of
  * <state, <optimization, score>> entries (Section 3, component list); its State
- * Selector "retrieves relevant (state, optimization) pairs", the Optimization
- * Selector keeps the top-k of them, and a state that matches nothing is
- * appended (Section 3, the paragraph that walks through one task).  The paper
+ * Selector looks up the stored (state, optimization) pairs that fit the kernel's
+ * state, the Optimization Selector keeps the top-k of them, and a state that
+ * matches nothing is appended (Section 3, the paragraph that walks through one task).  The paper
  * gives that step no numeric form.  This library implements the numeric model
  * of it: entry i has a key vector K_i (row i of an [N, d] matrix) and an
  * optional 64-bit tag; a query is a vector Q_r with an optional 64-bit mask;
@@ -70,8 +70,8 @@ kb_status_t kb_create(kb_t **out, int32_t d, kb_dtype_t key_dtype, int64_t capac
                       float *row_scale_dev, float *inv_norm_dev, uint64_t *tags_dev);
 
 /*
- * Append n rows at index kb_size() .. kb_size()+n-1 (Section 3: "appends the
- * new state").  rows_dev [n, d] in the key dtype, row_scale_dev [n] (fp8 only,
+ * Append n rows at index kb_size() .. kb_size()+n-1 (Section 3: a state that the
+ * knowledge base does not know yet is added to it).  rows_dev [n, d] in the key dtype, row_scale_dev [n] (fp8 only,
  * else NULL), tags_dev [n] (required iff the KB has tags).  The data is copied
  * device-to-device on `hip_stream`; a source pointer equal to its destination
  * (rows already written in place by the caller) skips that copy.  The new rows
@@ -118,8 +118,8 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
                      size_t workspace_bytes, void *hip_stream);
 
 /*
- * Weighted random selection (Section 3: the Optimization Selector "performs a random weighted selection based
- * on predicted performance gain ... to select the top-k").  Entry i carries a predicted gain g_i; query r draws
+ * Weighted random selection (Section 3: the Optimization Selector picks its top-k at random, with weights given
+ * by the predicted performance gains).  Entry i carries a predicted gain g_i; query r draws
  * k entries WITHOUT replacement from its qualifying entries with probability proportional to
  * g_i * exp(score_ri / temperature).  The draw is the k largest of
  *     key_ri = score_ri / temperature + ln g_i + G_ri,   G_ri = -ln(-ln U_ri)  (standard Gumbel),

@@ -2,9 +2,9 @@
  * TEST INFRASTRUCTURE ONLY -- brute-force fp64 definition of knowledge-base
  * retrieval.  Nothing in the product path may link, load or call this file.
  *
- * What is defined here.  The paper's State Selector "retrieves relevant
- * (state, optimization) pairs" from a store of <state, <optimization, score>>
- * entries and the Optimization Selector keeps the top-k of them (Section 3,
+ * What is defined here.  The paper's State Selector looks up, in a store of
+ * <state, <optimization, score>> entries, the pairs that fit the kernel's state,
+ * and the Optimization Selector keeps the top-k of them (Section 3,
  * component list and the paragraph that walks through one task).  The paper
  * gives no numeric form for that step; the numeric model used throughout this
  * repository is: every entry i has a key vector K_i, a query state is a vector
@@ -22,8 +22,8 @@
  * selection, no shared code with the GPU path.
  *
  * Weighted random selection (second half of this file).  The Optimization
- * Selector "performs a random weighted selection based on predicted
- * performance gain ... to select the top-k" (Section 3, same paragraph).  The
+ * Selector picks its top-k at random, with weights given by the predicted
+ * performance gains (Section 3, same paragraph).  The
  * paper gives no formula; the model used here: entry i carries a predicted
  * gain g_i > 0, query r draws k entries WITHOUT replacement from its candidate
  * set with probability proportional to w_ri = g_i * exp(score_ri / T), T > 0 a
