@@ -307,41 +307,6 @@ template <int QT> __global__ __launch_bounds__(256) void prep_kernel(const void 
 }
 
 // ------------------------------------------------------------------------------------------------
-// descending bitonic sort of n (power of two) 64-bit words in LDS by the whole workgroup
-// ------------------------------------------------------------------------------------------------
-__device__ inline void bitonic_sort_desc(uint64_t *buf, int n, int tid, int nthreads)
-{
-    // Thread t handles compare-exchange pairs t, t + nthreads, ...; the 64 consecutive pairs of a wavefront touch
-    // one aligned block of 128 elements whenever stride <= 64.  Runs of such stages therefore need no workgroup
-    // barrier: a wave's LDS operations execute in order, so waiting for its own to finish is enough.
-    int prev_stride = 1 << 30;
-    for (int size = 2; size <= n; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            if (stride >= 128 || prev_stride >= 128) {
-                __syncthreads();
-            } else {
-                __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0)
-                asm volatile("" ::: "memory");
-            }
-            prev_stride = stride;
-            for (int i = tid; i < n / 2; i += nthreads) {
-                const int lo = 2 * i - (i & (stride - 1));
-                const int hi = lo + stride;
-                const uint64_t a = buf[lo], b = buf[hi];
-                const bool desc = (lo & size) == 0;
-                if (desc ? a < b : a > b) {
-                    buf[lo] = b;
-                    buf[hi] = a;
-                }
-            }
-        }
-    }
-    __syncthreads();
-}
-
-// ------------------------------------------------------------------------------------------------
-// the k largest of n distinct nonzero 64-bit words in LDS, in descending order
-// ------------------------------------------------------------------------------------------------
 // A full sort is a chain of dependent LDS round trips (one per stage) and costs tens of microseconds for a
 // few thousand words.  Selection needs far fewer: a most-significant-digit radix search for the k-th
 // largest word (8-bit digits, starting at the highest bit in which the words differ at all; each pass is
@@ -526,7 +491,7 @@ __global__ __launch_bounds__(256) void bucket_kernel(const Record *regions, cons
 }
 
 // ------------------------------------------------------------------------------------------------
-// finalize: sort each query's list and emit its first k; a query whose list overflowed is resolved by an
+// finalize: select each query's best k in order; a query whose list overflowed is resolved by an
 // exhaustive scan of all keys that uses the same MFMA sequence per output element as the scan kernel,
 // so both paths produce bit-identical scores.
 // ------------------------------------------------------------------------------------------------
@@ -551,7 +516,8 @@ struct FinalArgs {
 // KT = KT_FP8_Q8 stands for fp8 keys with fp8 queries (one fp8 matrix instruction per 64-byte chunk, as in the scan).
 constexpr int KT_FP8_Q8 = 3;
 typedef int i32x8 __attribute__((ext_vector_type(8)));
-template <int KT> __device__ void exhaustive_query(const FinalArgs &a, int q, uint64_t *buf, uint32_t *ctl, int64_t row_begin, int64_t row_end)
+template <int KT> __device__ void exhaustive_query(const FinalArgs &a, int q, uint64_t *buf, uint32_t *ctl, SelectScratch *sc, int64_t row_begin,
+                                                   int64_t row_end)
 {
     constexpr bool Q8 = KT == KT_FP8_Q8;
     constexpr int KTT = Q8 ? (int)KB_FP8_E4M3 : KT;
@@ -577,23 +543,52 @@ template <int KT> __device__ void exhaustive_query(const FinalArgs &a, int q, ui
         f32x16 acc;
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+        // The loads of UNR groups go out before their matrix instructions (the order of the accumulation does not
+        // change): one memory round trip per UNR groups instead of one per group.
+        constexpr int UNR = 8;
         if constexpr (Q8) {
             // one fp8 matrix instruction per 64-byte chunk: lane half h supplies bytes [32h, 32h+32) of its key row
             // and of the query row, the operand layout the scan uses, so both paths give the same bits
             const unsigned char *kp = krow + half * 16;
-            for (int g = 0; g < n_groups; ++g) {
-                const u32x4 a0 = *reinterpret_cast<const u32x4 *>(kp + (size_t)g * 64);
-                const u32x4 a1 = *reinterpret_cast<const u32x4 *>(kp + (size_t)g * 64 + 16);
-                const u32x4 b0 = *reinterpret_cast<const u32x4 *>(qrow + (size_t)g * 64 + half * 32);
-                const u32x4 b1 = *reinterpret_cast<const u32x4 *>(qrow + (size_t)g * 64 + half * 32 + 16);
+            auto step = [&](const u32x4 &a0, const u32x4 &a1, const u32x4 &b0, const u32x4 &b1) {
                 const i32x8 av = {(int)a0[0], (int)a0[1], (int)a0[2], (int)a0[3], (int)a1[0], (int)a1[1], (int)a1[2], (int)a1[3]};
                 const i32x8 bv = {(int)b0[0], (int)b0[1], (int)b0[2], (int)b0[3], (int)b1[0], (int)b1[1], (int)b1[2], (int)b1[3]};
                 acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, bv, acc, 0, 0, 0, 0, 0, 0);
+            };
+            int g = 0;
+            for (; g + UNR <= n_groups; g += UNR) {
+                u32x4 a0[UNR], a1[UNR], b0[UNR], b1[UNR];
+#pragma unroll
+                for (int u = 0; u < UNR; ++u) {
+                    a0[u] = *reinterpret_cast<const u32x4 *>(kp + (size_t)(g + u) * 64);
+                    a1[u] = *reinterpret_cast<const u32x4 *>(kp + (size_t)(g + u) * 64 + 16);
+                    b0[u] = *reinterpret_cast<const u32x4 *>(qrow + (size_t)(g + u) * 64 + half * 32);
+                    b1[u] = *reinterpret_cast<const u32x4 *>(qrow + (size_t)(g + u) * 64 + half * 32 + 16);
+                }
+#pragma unroll
+                for (int u = 0; u < UNR; ++u) step(a0[u], a1[u], b0[u], b1[u]);
             }
+            for (; g < n_groups; ++g)
+                step(*reinterpret_cast<const u32x4 *>(kp + (size_t)g * 64), *reinterpret_cast<const u32x4 *>(kp + (size_t)g * 64 + 16),
+                     *reinterpret_cast<const u32x4 *>(qrow + (size_t)g * 64 + half * 32), *reinterpret_cast<const u32x4 *>(qrow + (size_t)g * 64 + half * 32 + 16));
         } else {
-            for (int g = 0; g < n_groups; ++g) {
+            const unsigned char *qbase = qrow + half * 16 * BMUL;
+            int g = 0;
+            for (; g + UNR <= n_groups; g += UNR) {
+                u32x4 av[UNR], b0[UNR], b1[UNR];
+#pragma unroll
+                for (int u = 0; u < UNR; ++u) {
+                    av[u] = *reinterpret_cast<const u32x4 *>(krow + (size_t)(g + u) * 32);
+                    const unsigned char *qp = qbase + (size_t)(g + u) * 32 * BMUL;
+                    b0[u] = *reinterpret_cast<const u32x4 *>(qp);
+                    b1[u] = BMUL == 2 ? *reinterpret_cast<const u32x4 *>(qp + 16) : b0[u];
+                }
+#pragma unroll
+                for (int u = 0; u < UNR; ++u) Mma<KTT>::run(acc, Mma<KTT>::prepare(av[u]), b0[u], b1[u]);
+            }
+            for (; g < n_groups; ++g) {
                 const u32x4 av = *reinterpret_cast<const u32x4 *>(krow + (size_t)g * 32);
-                const unsigned char *qp = qrow + (size_t)g * 32 * BMUL + half * 16 * BMUL;
+                const unsigned char *qp = qbase + (size_t)g * 32 * BMUL;
                 const u32x4 b0 = *reinterpret_cast<const u32x4 *>(qp);
                 const u32x4 b1 = BMUL == 2 ? *reinterpret_cast<const u32x4 *>(qp + 16) : b0;
                 Mma<KTT>::run(acc, Mma<KTT>::prepare(av), b0, b1);
@@ -617,9 +612,8 @@ template <int KT> __device__ void exhaustive_query(const FinalArgs &a, int q, ui
         }
         __syncthreads();
         const uint32_t n = ctl[0];
-        if (n + 128 > (uint32_t)cap) {      // uniform: compact to the best k
-            for (int i = n + tid; i < cap; i += 256) buf[i] = 0ull;
-            bitonic_sort_desc(buf, cap, tid, 256);
+        if (n + 128 > (uint32_t)cap) {      // uniform: compact to the best k (sorted into buf[0..k))
+            select_topk_desc(buf, (int)n, a.k, sc, tid, 256);
             if (tid == 0) {
                 ctl[0] = n < (uint32_t)a.k ? n : (uint32_t)a.k;
                 *thr_local = n >= (uint32_t)a.k ? buf[a.k - 1] : 0ull;
@@ -627,9 +621,7 @@ template <int KT> __device__ void exhaustive_query(const FinalArgs &a, int q, ui
             __syncthreads();
         }
     }
-    const uint32_t n = ctl[0];
-    for (int i = n + tid; i < cap; i += 256) buf[i] = 0ull;
-    bitonic_sort_desc(buf, cap, tid, 256);
+    select_topk_desc(buf, (int)ctl[0], a.k, sc, tid, 256);      // buf[0..k): the result in order, zero words where there is none
 }
 
 template <int KT> __global__ __launch_bounds__(256) void finalize_kernel(FinalArgs a)
@@ -640,7 +632,7 @@ template <int KT> __global__ __launch_bounds__(256) void finalize_kernel(FinalAr
     SelectScratch *sc = reinterpret_cast<SelectScratch *>(smem_raw + sizeof(uint64_t) * a.cand_cap + 16);
     const int q = blockIdx.x, tid = threadIdx.x;
     if (a.flag[q] != 0 && a.n_keys > 0) {
-        exhaustive_query<KT>(a, q, buf, ctl, 0, a.n_keys);
+        exhaustive_query<KT>(a, q, buf, ctl, sc, 0, a.n_keys);
         if (tid == 0) atomicAdd(reinterpret_cast<unsigned long long *>(a.stats + 1), 1ull);
     } else {
         // gather the query's segments into one contiguous list
@@ -689,6 +681,7 @@ template <int KT> __global__ __launch_bounds__(256) void probe_scan_kernel(Final
 {
     __shared__ __attribute__((aligned(16))) uint64_t buf[PROBE_CAP];
     __shared__ uint32_t ctl[4];
+    __shared__ SelectScratch sc;
     const int p = blockIdx.x, s = blockIdx.y, q = blockIdx.z, tid = threadIdx.x;
     uint64_t *out = lists + ((size_t)q * nprobe * splits + (size_t)p * splits + s) * a.k;
     const int c = probe[(size_t)q * nprobe + p];
@@ -707,7 +700,7 @@ template <int KT> __global__ __launch_bounds__(256) void probe_scan_kernel(Final
         if (tid < a.k) out[tid] = 0ull;
         return;
     }
-    exhaustive_query<KT>(a, q, buf, ctl, begin, end);
+    exhaustive_query<KT>(a, q, buf, ctl, &sc, begin, end);
     if (tid < a.k) out[tid] = buf[tid];
 }
 
