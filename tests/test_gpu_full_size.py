@@ -115,3 +115,75 @@ def test_growing_full(T):
             assert (gi[:, 0] >= first).mean() > 0.9
     assert kb.size == cap
     kb.close()
+
+
+def test_compressed_full_fp8_queries(T):
+    # the fp8 x fp8 kernel at the compressed workload's full size: 2^22 keys, 1024 e4m3 queries, k = 64
+    w = W.compressed(seed=3001, device="cuda", fp8_queries=True)
+    kb = _resident_kb(w)
+    gi, gs = kb.query(w.queries, w.k)
+    torch.cuda.synchronize()
+    gi, gs = gi.cpu().numpy(), gs.cpu().numpy()
+    _properties(gi, gs, w.N)
+    rows = np.sort(np.random.default_rng(2).choice(1024, size=8, replace=False))
+    _check_sample(T, w, gi, gs, rows, "compressed full, fp8 queries")
+    assert kb.counters()["exhaustive_queries"] == 0
+    kb.close()
+
+
+def test_filtered_full_draw(T):
+    # weighted random selection at the filtered workload's full size; sampled queries against the oracle's draw
+    from oracle import compare, kb_oracle
+
+    w = W.filtered(seed=2002, device="cuda")
+    kb = _resident_kb(w)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    gain = torch.empty(w.N, dtype=torch.float32, device="cuda").uniform_(0.25, 4.0, generator=gen)
+    gi, gk = kb.query_sampled(w.queries, w.k, gain, 0.05, 99, w.qmask)
+    torch.cuda.synchronize()
+    gi, gk = gi.cpu().numpy(), gk.cpu().numpy()
+    rows = np.sort(np.random.default_rng(3).choice(256, size=6, replace=False))
+    full = kb_oracle.score_matrix(W.key_bits(w.keys.cpu()), kb_oracle.BF16, W.key_bits(w.queries.cpu()[rows]), kb_oracle.BF16)
+    qm = W.word_bits(w.qmask.cpu())[rows]
+    for j, r in enumerate(rows):        # keys of the oracle for global query number r
+        keys = kb_oracle.selection_keys(full[j:j + 1], gain.cpu().numpy(), 0.05, 99, first_query=int(r))
+        compare.check(gi[r:r + 1], gk[r:r + 1], keys, w.k, 2e-4, tags=W.word_bits(w.tags.cpu()), qmask=qm[j:j + 1], label=f"full draw q{r}")
+    kb.close()
+
+
+def test_filtered_full_remove_and_compact(T):
+    # a tenth of the 2^20 entries removed: queries skip them; the compacted store holds the rest bit for bit
+    from oracle import kb_oracle
+
+    w = W.filtered(seed=2003, device="cuda")
+    kb = _resident_kb(w)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11)
+    rm = torch.randperm(w.N, generator=g, device="cuda")[:w.N // 10].to(torch.int32)
+    kb.remove(rm)
+    removed = np.zeros(w.N, dtype=bool)
+    removed[rm.cpu().numpy()] = True
+    gi, gs = kb.query(w.queries, w.k, w.qmask)
+    torch.cuda.synchronize()
+    gi, gs = gi.cpu().numpy(), gs.cpu().numpy()
+    _properties(gi, gs, w.N)
+    assert not removed[gi[gi >= 0]].any() and kb.counters()["exhaustive_queries"] == 0
+    rows = np.sort(np.random.default_rng(4).choice(256, size=8, replace=False))
+    w_cpu = W.Workload(w.name, w.keys.cpu(), w.queries.cpu(), w.k, tags=w.tags.cpu(), qmask=w.qmask.cpu())
+    T.check_against_oracle(w_cpu, gi, gs, rows=rows, label="filtered full, a tenth removed", removed=removed)
+    dst = kbmod.KnowledgeBase(w.d, kbmod.KB_BF16, w.N - w.N // 10, tagged=True)
+    live, index_map, _ = kb.compact_into(dst)
+    torch.cuda.synchronize()
+    want_map, _ = kb_oracle.compact(removed)
+    assert live == w.N - w.N // 10 and np.array_equal(index_map.cpu().numpy(), want_map)
+    keep = torch.from_numpy(np.flatnonzero(~removed)).cuda()
+    pick = torch.randperm(live, generator=g, device="cuda")[:4096]
+    assert torch.equal(dst.keys[pick].view(torch.int16), w.keys[keep[pick]].view(torch.int16)) and torch.equal(dst.tags[pick], w.tags[keep[pick]])
+    gi2, gs2 = dst.query(w.queries, w.k, w.qmask)
+    torch.cuda.synchronize()
+    back = keep.cpu().numpy()
+    gi2 = gi2.cpu().numpy()
+    assert np.array_equal(np.where(gi2 >= 0, back[np.maximum(gi2, 0)], -1), gi) and np.array_equal(gs2.cpu().numpy(), gs)
+    kb.close()
+    dst.close()
