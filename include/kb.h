@@ -219,7 +219,8 @@ kb_status_t kb_compact(kb_t *src, kb_t *dst, const float *gain_src_dev, float *g
 /*
  * Diagnostics of the most recent kb_query that used `workspace_dev`: synchronises `hip_stream`, then copies
  * out[0] = candidates that passed the threshold filter (all queries), out[1] = queries resolved by the
- * exhaustive per-query path, out[2] = keys scored by the sampling pass, out[3] = workgroups of the scan.
+ * exhaustive per-query path, out[2] = keys scored by the sampling pass, out[3] = workgroups of the scan (a query
+ * that took the small-knowledge-base path reports 0, 0, 0 and its workgroups).
  * `out` is host memory, 4 x int64.  Errors: KB_ERR_NULL, KB_ERR_DEVICE.
  */
 kb_status_t kb_query_counters(const kb_t *kb, const void *workspace_dev, int64_t *out, void *hip_stream);
@@ -229,13 +230,16 @@ kb_status_t kb_query_counters(const kb_t *kb, const void *workspace_dev, int64_t
  *   "sample_keys"   keys scored by the sampling pass (0 = automatic)
  *   "scan_config"   tile configuration of the scan kernel (0 = automatic)
  *   "wg_per_cu"     resident scan workgroups per compute unit (0 = automatic)
+ *   "small_path"    1 (default): a knowledge base of at most 16384 rows, queried with a small batch and no other knob
+ *                   set, is scored whole by three launches (no sampling pass, no candidate lists); 0: always the
+ *                   scan pipeline.  Both produce the same bits.
  */
 kb_status_t kb_set_tuning(kb_t *kb, const char *name, int64_t value);
 
 /*
  * Kernel timing for roofline reports.  After kb_profile_begin, each kb_query records a HIP event pair
- * around its main scan kernel on the query's stream (up to max_calls queries, 1..4096; later ones are not
- * recorded).  kb_profile_end synchronises `hip_stream`, writes the summed duration of the recorded scan
+ * around its main scan kernel (on the small-knowledge-base path: around the kernel that scores the rows) on the
+ * query's stream (up to max_calls queries, 1..4096; later ones are not recorded).  kb_profile_end synchronises `hip_stream`, writes the summed duration of the recorded scan
  * launches in milliseconds and their number, destroys the events and stops recording.
  * Errors: KB_ERR_NULL, KB_ERR_INVALID_ARG (bad max_calls, or end without begin), KB_ERR_DEVICE.
  */

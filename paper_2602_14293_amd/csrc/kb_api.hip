@@ -665,8 +665,10 @@ template <int KT> __global__ __launch_bounds__(256) void finalize_kernel(FinalAr
 constexpr int PROBE_CAP = 1024;        // LDS candidate buffer of a partial scan (words); k <= 128 fits eight times
 constexpr int PROBE_MAX_LISTS = 64;    // partial lists per query that the merge can take: 64 x 128 = MAX_CAND_CAP words
 
-template <int QT> __global__ __launch_bounds__(256) void probe_prep_kernel(const void *queries, int Q, int d, float *invq)
+template <int QT> __global__ __launch_bounds__(256) void probe_prep_kernel(const void *queries, int Q, int d, float *invq, uint64_t *stats, uint64_t blocks)
 {
+    // stats (optional): the diagnostics of a query that took this path: no candidates, no sampling, `blocks` workgroups
+    if (stats && blockIdx.x == 0 && threadIdx.x < STAT_WORDS + STAT_PARTIALS) stats[threadIdx.x] = threadIdx.x == 3 ? blocks : 0ull;
     const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row < Q) {
         const float inv = row_inv_norm<QT>(queries, row, d * (QT == KB_F32 ? 4 : QT == KB_BF16 ? 2 : 1), lane);
@@ -676,6 +678,7 @@ template <int QT> __global__ __launch_bounds__(256) void probe_prep_kernel(const
 
 // Block (p, s, q): part s of `splits` of the rows of cluster probe[q][p], scored exactly as the scan kernels score
 // (same MFMA sequence per element), best k written as a sorted list of candidate words (zero = no entry).
+// Without cluster_offsets the one "cluster" is the whole knowledge base (the path of small knowledge bases).
 template <int KT> __global__ __launch_bounds__(256) void probe_scan_kernel(FinalArgs a, const int64_t *cluster_offsets, int n_clusters,
                                                                          const int32_t *probe, int nprobe, int splits, uint64_t *lists)
 {
@@ -684,12 +687,12 @@ template <int KT> __global__ __launch_bounds__(256) void probe_scan_kernel(Final
     __shared__ SelectScratch sc;
     const int p = blockIdx.x, s = blockIdx.y, q = blockIdx.z, tid = threadIdx.x;
     uint64_t *out = lists + ((size_t)q * nprobe * splits + (size_t)p * splits + s) * a.k;
-    const int c = probe[(size_t)q * nprobe + p];
+    const int c = cluster_offsets ? probe[(size_t)q * nprobe + p] : 0;
     bool first = true;          // a cluster named twice is scanned once (the merge takes distinct entries)
-    for (int e = 0; e < p; ++e) first = first && probe[(size_t)q * nprobe + e] != c;
+    for (int e = 0; cluster_offsets && e < p; ++e) first = first && probe[(size_t)q * nprobe + e] != c;
     int64_t begin = 0, end = 0;
     if (first && c >= 0 && c < n_clusters) {
-        const int64_t cb = cluster_offsets[c], ce = cluster_offsets[c + 1];
+        const int64_t cb = cluster_offsets ? cluster_offsets[c] : 0, ce = cluster_offsets ? cluster_offsets[c + 1] : a.n_keys;
         if (cb >= 0 && ce <= a.n_keys && cb < ce) {
             const int64_t len = ((ce - cb + splits - 1) / splits + 127) / 128 * 128;    // whole steps of the scorer
             begin = cb + (int64_t)s * len;
@@ -766,7 +769,7 @@ kb_status_t kb_create(kb_t **out, int32_t d, kb_dtype_t key_dtype, int64_t capac
     h->row_scale = row_scale_dev;
     h->inv_norm = inv_norm_dev;
     h->tags = tags_dev;
-    h->tune_sample_keys = h->tune_config = h->tune_wg_per_cu = 0;
+    h->tune_sample_keys = h->tune_config = h->tune_wg_per_cu = h->tune_no_small_path = 0;
     h->cu_count = 0;
     h->prof_events = nullptr;
     h->prof_max = h->prof_used = 0;
@@ -817,6 +820,118 @@ kb_status_t kb_normalize(kb_t *kb, void *hip_stream)
     return KB_OK;
 }
 
+// ------------------------------------------------------------------------------------------------
+// Two-stage retrieval, second stage (host side)
+// ------------------------------------------------------------------------------------------------
+namespace {
+
+// Parts a cluster's rows are split into, so that a small batch still fills the device: a function of (Q, nprobe) only.
+int probe_splits(int Q, int nprobe)
+{
+    int64_t s = (4 * (int64_t)ASSUMED_CUS + (int64_t)Q * nprobe - 1) / ((int64_t)Q * nprobe);
+    if (s > 16) s = 16;
+    if (s > PROBE_MAX_LISTS / nprobe) s = PROBE_MAX_LISTS / nprobe;
+    return s < 1 ? 1 : (int)s;
+}
+
+struct ProbePlan {
+    int splits;
+    size_t off_invq, off_lists, total;
+};
+
+bool make_probe_plan(int32_t Q, int32_t k, int32_t nprobe, ProbePlan *out)
+{
+    if (Q < 1 || Q > 65535 || k < 1 || k > KB_K_MAX || nprobe < 1 || nprobe > PROBE_MAX_LISTS) return false;
+    ProbePlan p;
+    p.splits = probe_splits(Q, nprobe);
+    p.off_invq = 0;
+    p.off_lists = align_up((size_t)Q * 4);
+    p.total = p.off_lists + align_up((size_t)Q * nprobe * p.splits * k * 8);
+    *out = p;
+    return true;
+}
+
+
+// The three launches behind kb_query_probe; also the whole pipeline of kb_query on a small knowledge base
+// (cluster_offsets == nullptr: one "cluster" = every row, nprobe = 1, `stats` zeroed for kb_query_counters).
+kb_status_t launch_probe(kb *h, bool timed_scan, const void *queries_dev, kb_dtype_t q_dtype, bool q8, int32_t Q, const uint64_t *qmask_dev, int32_t k,
+                         const int64_t *cluster_offsets_dev, int32_t n_clusters, const int32_t *probe_dev, int32_t nprobe, int splits, float *invq,
+                         uint64_t *lists, uint64_t *stats, int32_t *indices_out_dev, float *scores_out_dev, hipStream_t s)
+{
+    const int pgrid = (Q + 3) / 4;
+    const uint64_t blocks = (uint64_t)nprobe * splits * Q;
+    if (q_dtype == KB_F32)
+        hipLaunchKernelGGL(probe_prep_kernel<KB_F32>, dim3(pgrid), dim3(256), 0, s, queries_dev, Q, h->d, invq, stats, blocks);
+    else if (q_dtype == KB_BF16)
+        hipLaunchKernelGGL(probe_prep_kernel<KB_BF16>, dim3(pgrid), dim3(256), 0, s, queries_dev, Q, h->d, invq, stats, blocks);
+    else
+        hipLaunchKernelGGL(probe_prep_kernel<KB_FP8_E4M3>, dim3(pgrid), dim3(256), 0, s, queries_dev, Q, h->d, invq, stats, blocks);
+
+    FinalArgs f;
+    memset(&f, 0, sizeof f);
+    f.keys = h->keys;
+    f.inv_norm = h->inv_norm;
+    f.tags = h->tags;
+    f.queries = queries_dev;
+    f.qmask = qmask_dev;
+    f.invq = invq;
+    f.n_keys = h->n;
+    f.d = h->d;
+    f.k = k;
+    f.cand_cap = PROBE_CAP;
+    const dim3 grid(nprobe, splits, Q);
+    const bool timed = timed_scan && h->prof_events && h->prof_used < h->prof_max;     // the scoring kernel stands for the scan
+    if (timed && hipEventRecord(h->prof_events[2 * h->prof_used], s) != hipSuccess) return KB_ERR_DEVICE;
+    switch (q8 ? KT_FP8_Q8 : (int)h->dtype) {
+    case KB_F32: hipLaunchKernelGGL(probe_scan_kernel<KB_F32>, grid, dim3(256), 0, s, f, cluster_offsets_dev, n_clusters, probe_dev, nprobe, splits, lists); break;
+    case KB_BF16: hipLaunchKernelGGL(probe_scan_kernel<KB_BF16>, grid, dim3(256), 0, s, f, cluster_offsets_dev, n_clusters, probe_dev, nprobe, splits, lists); break;
+    case KB_FP8_E4M3: hipLaunchKernelGGL(probe_scan_kernel<KB_FP8_E4M3>, grid, dim3(256), 0, s, f, cluster_offsets_dev, n_clusters, probe_dev, nprobe, splits, lists); break;
+    default: hipLaunchKernelGGL(probe_scan_kernel<KT_FP8_Q8>, grid, dim3(256), 0, s, f, cluster_offsets_dev, n_clusters, probe_dev, nprobe, splits, lists); break;
+    }
+    if (timed) {
+        if (hipEventRecord(h->prof_events[2 * h->prof_used + 1], s) != hipSuccess) return KB_ERR_DEVICE;
+        ++h->prof_used;
+    }
+    const int n_lists = nprobe * splits;
+    const size_t merge_lds = sizeof(uint64_t) * (size_t)(n_lists * k > k ? n_lists * k : k) + 16 + sizeof(SelectScratch);
+    static bool merge_attr = false;
+    if (!merge_attr) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&probe_merge_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                MAX_CAND_CAP * 8 + 16 + sizeof(SelectScratch)) != hipSuccess)
+            return KB_ERR_DEVICE;
+        merge_attr = true;
+    }
+    hipLaunchKernelGGL(probe_merge_kernel, dim3(Q), dim3(256), merge_lds, s, lists, n_lists, k, indices_out_dev, scores_out_dev);
+    return hipGetLastError() == hipSuccess ? KB_OK : KB_ERR_DEVICE;
+}
+
+// A small knowledge base is scored whole by the same three launches: parts of 128 or 256 rows (one or two steps of the scorer), no
+// sampling pass, no candidate lists.  Same scores, same order: results do not depend on which path ran.
+constexpr int64_t SMALL_ROWS = 16384;
+constexpr int SMALL_BLOCKS = 1024;
+int small_path_parts(const kb *h, int64_t n, int32_t Q, bool draw)
+{
+    if (draw || h->tune_no_small_path || h->tune_config || h->tune_sample_keys || h->tune_wg_per_cu) return 0;
+    if (n < 1 || n > SMALL_ROWS || Q > 65535) return 0;
+    int64_t parts = (n + 127) / 128;       // one step of the scorer per part up to 8192 rows, two beyond
+    if (parts > PROBE_MAX_LISTS) parts = PROBE_MAX_LISTS;
+    return parts * Q <= SMALL_BLOCKS ? (int)parts : 0;
+}
+
+struct SmallPlan {
+    size_t off_invq, off_lists, total;
+};
+SmallPlan make_small_plan(int32_t Q, int32_t k, int parts)
+{
+    SmallPlan p;
+    p.off_invq = align_up(sizeof(uint64_t) * (STAT_WORDS + STAT_PARTIALS));      // the diagnostics come first, as always
+    p.off_lists = p.off_invq + align_up((size_t)Q * 4);
+    p.total = p.off_lists + align_up((size_t)Q * parts * k * 8);
+    return p;
+}
+
+}  // namespace
+
 size_t kb_query_workspace_bytes(const kb_t *kb, int32_t Q, int32_t k)
 {
     if (!kb || Q < 1 || k < 1 || k > KB_K_MAX) return 0;
@@ -839,7 +954,8 @@ size_t kb_query_workspace_bytes(const kb_t *kb, int32_t Q, int32_t k)
         }
         if (make_plan(kb, n, Q, k, false, true, &p) && p.total > best) best = p.total;
     }
-    return best;
+    const size_t small = make_small_plan(Q, k, PROBE_MAX_LISTS).total;      // the path of small knowledge bases
+    return best > small ? best : small;
 }
 
 // kb_query and kb_query_sampled: the same pipeline; `gain_dev` != nullptr selects the weighted random selection.
@@ -869,6 +985,14 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, 0) != hipSuccess || cus < 1) return KB_ERR_DEVICE;
         // the workspace was sized for ASSUMED_CUS; a larger device just runs the same grid
         kb->cu_count = cus < ASSUMED_CUS ? cus : ASSUMED_CUS;
+    }
+    if (const int parts = small_path_parts(kb, kb->n, Q, draw)) {
+        const SmallPlan sp = make_small_plan(Q, k, parts);
+        if (workspace_bytes < sp.total) return KB_ERR_WORKSPACE;
+        unsigned char *w = static_cast<unsigned char *>(workspace_dev);
+        return launch_probe(kb, true, queries_dev, q_dtype, q8, Q, qmask_dev, k, nullptr, 1, nullptr, 1, parts, reinterpret_cast<float *>(w + sp.off_invq),
+                            reinterpret_cast<uint64_t *>(w + sp.off_lists), reinterpret_cast<uint64_t *>(w), indices_out_dev, scores_out_dev,
+                            static_cast<hipStream_t>(hip_stream));
     }
     Plan p;
     if (!make_plan(kb, kb->n, Q, k, draw, q8, &p)) return KB_ERR_INVALID_ARG;
@@ -1038,39 +1162,6 @@ kb_status_t kb_query_sampled(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
                      workspace_dev, workspace_bytes, hip_stream);
 }
 
-// ------------------------------------------------------------------------------------------------
-// Two-stage retrieval, second stage (host side)
-// ------------------------------------------------------------------------------------------------
-namespace {
-
-// Parts a cluster's rows are split into, so that a small batch still fills the device: a function of (Q, nprobe) only.
-int probe_splits(int Q, int nprobe)
-{
-    int64_t s = (4 * (int64_t)ASSUMED_CUS + (int64_t)Q * nprobe - 1) / ((int64_t)Q * nprobe);
-    if (s > 16) s = 16;
-    if (s > PROBE_MAX_LISTS / nprobe) s = PROBE_MAX_LISTS / nprobe;
-    return s < 1 ? 1 : (int)s;
-}
-
-struct ProbePlan {
-    int splits;
-    size_t off_invq, off_lists, total;
-};
-
-bool make_probe_plan(int32_t Q, int32_t k, int32_t nprobe, ProbePlan *out)
-{
-    if (Q < 1 || Q > 65535 || k < 1 || k > KB_K_MAX || nprobe < 1 || nprobe > PROBE_MAX_LISTS) return false;
-    ProbePlan p;
-    p.splits = probe_splits(Q, nprobe);
-    p.off_invq = 0;
-    p.off_lists = align_up((size_t)Q * 4);
-    p.total = p.off_lists + align_up((size_t)Q * nprobe * p.splits * k * 8);
-    *out = p;
-    return true;
-}
-
-}  // namespace
-
 size_t kb_query_probe_workspace_bytes(const kb_t *kb, int32_t Q, int32_t k, int32_t nprobe)
 {
     ProbePlan p;
@@ -1099,44 +1190,8 @@ kb_status_t kb_query_probe(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype
     unsigned char *ws = static_cast<unsigned char *>(workspace_dev);
     float *invq = reinterpret_cast<float *>(ws + p.off_invq);
     uint64_t *lists = reinterpret_cast<uint64_t *>(ws + p.off_lists);
-    const int pgrid = (Q + 3) / 4;
-    if (q_dtype == KB_F32)
-        hipLaunchKernelGGL(probe_prep_kernel<KB_F32>, dim3(pgrid), dim3(256), 0, s, queries_dev, Q, kb->d, invq);
-    else if (q_dtype == KB_BF16)
-        hipLaunchKernelGGL(probe_prep_kernel<KB_BF16>, dim3(pgrid), dim3(256), 0, s, queries_dev, Q, kb->d, invq);
-    else
-        hipLaunchKernelGGL(probe_prep_kernel<KB_FP8_E4M3>, dim3(pgrid), dim3(256), 0, s, queries_dev, Q, kb->d, invq);
-
-    FinalArgs f;
-    memset(&f, 0, sizeof f);
-    f.keys = kb->keys;
-    f.inv_norm = kb->inv_norm;
-    f.tags = kb->tags;
-    f.queries = queries_dev;
-    f.qmask = qmask_dev;
-    f.invq = invq;
-    f.n_keys = kb->n;
-    f.d = kb->d;
-    f.k = k;
-    f.cand_cap = PROBE_CAP;
-    const dim3 grid(nprobe, p.splits, Q);
-    switch (q8 ? KT_FP8_Q8 : (int)kb->dtype) {
-    case KB_F32: hipLaunchKernelGGL(probe_scan_kernel<KB_F32>, grid, dim3(256), 0, s, f, cluster_offsets_dev, n_clusters, probe_dev, nprobe, p.splits, lists); break;
-    case KB_BF16: hipLaunchKernelGGL(probe_scan_kernel<KB_BF16>, grid, dim3(256), 0, s, f, cluster_offsets_dev, n_clusters, probe_dev, nprobe, p.splits, lists); break;
-    case KB_FP8_E4M3: hipLaunchKernelGGL(probe_scan_kernel<KB_FP8_E4M3>, grid, dim3(256), 0, s, f, cluster_offsets_dev, n_clusters, probe_dev, nprobe, p.splits, lists); break;
-    default: hipLaunchKernelGGL(probe_scan_kernel<KT_FP8_Q8>, grid, dim3(256), 0, s, f, cluster_offsets_dev, n_clusters, probe_dev, nprobe, p.splits, lists); break;
-    }
-    const int n_lists = nprobe * p.splits;
-    const size_t merge_lds = sizeof(uint64_t) * (size_t)(n_lists * k > k ? n_lists * k : k) + 16 + sizeof(SelectScratch);
-    static bool merge_attr = false;
-    if (!merge_attr) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&probe_merge_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                MAX_CAND_CAP * 8 + 16 + sizeof(SelectScratch)) != hipSuccess)
-            return KB_ERR_DEVICE;
-        merge_attr = true;
-    }
-    hipLaunchKernelGGL(probe_merge_kernel, dim3(Q), dim3(256), merge_lds, s, lists, n_lists, k, indices_out_dev, scores_out_dev);
-    return hipGetLastError() == hipSuccess ? KB_OK : KB_ERR_DEVICE;
+    return launch_probe(kb, false, queries_dev, q_dtype, q8, Q, qmask_dev, k, cluster_offsets_dev, n_clusters, probe_dev, nprobe, p.splits, invq, lists, nullptr,
+                        indices_out_dev, scores_out_dev, s);
 }
 
 kb_status_t kb_query_counters(const kb_t *kb, const void *workspace_dev, int64_t *out, void *hip_stream)
@@ -1160,6 +1215,9 @@ kb_status_t kb_set_tuning(kb_t *kb, const char *name, int64_t value)
         ConfigInfo ci;
         if (value != 0 && !scan_config_info(kb->dtype, (int)value, &ci)) return KB_ERR_INVALID_ARG;
         kb->tune_config = value;
+    } else if (!strcmp(name, "small_path")) {
+        if (value > 1) return KB_ERR_INVALID_ARG;
+        kb->tune_no_small_path = value == 0;
     } else if (!strcmp(name, "wg_per_cu")) {
         if (value > 8) return KB_ERR_INVALID_ARG;
         kb->tune_wg_per_cu = value;

@@ -13,7 +13,7 @@ struct kb {
     void *keys;
     float *row_scale, *inv_norm;
     uint64_t *tags;
-    int64_t tune_sample_keys, tune_config, tune_wg_per_cu;
+    int64_t tune_sample_keys, tune_config, tune_wg_per_cu, tune_no_small_path;
     int cu_count;   // 0 until the device has been asked
     hipEvent_t *prof_events;   // 2 * prof_max events while profiling, else nullptr
     int prof_max, prof_used;

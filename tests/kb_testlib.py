@@ -68,6 +68,12 @@ def run_and_check(w: W.Workload, use_mask=True, label="", tuning=None):
     for name, val in (tuning or {}).items():
         kb.set_tuning(name, val)
     gi, gs = gpu_query(kb, w, use_mask)
+    if not tuning:
+        # a small knowledge base is scored whole without sampling and candidate lists; the scan pipeline must give
+        # the same bits (its counters are the ones reported)
+        kb.set_tuning("small_path", 0)
+        gi2, gs2 = gpu_query(kb, w, use_mask)
+        assert np.array_equal(gi, gi2) and np.array_equal(gs.view(np.int32), gs2.view(np.int32)), f"{label}: the two pipelines disagree"
     rep = check_against_oracle(w, gi, gs, use_mask, label=label)
     counters = kb.counters()
     kb.close()
