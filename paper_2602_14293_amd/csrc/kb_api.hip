@@ -75,6 +75,7 @@ constexpr int ASSUMED_CUS = 256;       // MI355X; used for sizing before a devic
 constexpr int MAX_SAMPLE_SLOTS = 8192; // threshold_kernel sorts this many 64-bit words in LDS (64 KiB)
 constexpr int MAX_CAND_CAP = 8192;     // finalize_kernel likewise
 constexpr int MIN_CAND_CAP = 1024;
+constexpr int FALLBACK_PARTS = 32;    // workgroups that share the rows of a query on the exhaustive path
 constexpr int CAND_SEGMENTS = 16;     // per-query candidate list = this many independently counted segments
 constexpr size_t WS_ALIGN = 256;
 constexpr int FP8_QUERY_CONFIG = 5;    // scan configuration of fp8 keys with fp8 queries (kb_configs.hpp)
@@ -189,6 +190,9 @@ bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, bool draw, bool q8,
     p.off_thrp = off;        off = align_up(off + sizeof(float) * p.qpad);
     p.off_cnt = off;         off = align_up(off + sizeof(uint32_t) * p.qpad * CAND_SEGMENTS);
     p.off_flag = off;        off = align_up(off + sizeof(uint32_t) * p.qpad);
+    p.fb_parts = p.cand_cap / KB_K_MAX < FALLBACK_PARTS ? p.cand_cap / KB_K_MAX : FALLBACK_PARTS;     // parts * k words fit the LDS buffer
+    p.off_fb_done = off;     off = align_up(off + sizeof(uint32_t) * p.qpad);
+    p.off_fb_lists = off;    off = align_up(off + sizeof(uint64_t) * (size_t)p.qpad * p.fb_parts * k);
     p.off_region_cnt = off;  off = align_up(off + sizeof(uint32_t) * p.regions);
     p.off_qmask = off;       off = align_up(off + sizeof(uint64_t) * p.qpad);
     p.off_samp = off;        off = align_up(off + sizeof(uint64_t) * (size_t)p.qpad * (p.sample_slots > 0 ? p.sample_slots : 1));
@@ -286,9 +290,10 @@ __global__ __launch_bounds__(256) void log_gain_kernel(const float *gain, int64_
 // ------------------------------------------------------------------------------------------------
 template <int QT> __global__ __launch_bounds__(256) void prep_kernel(const void *queries, int Q, int qpad, int d, float *invq, uint64_t *thr64, float *thrp,
                                                                        uint32_t *cnt, uint32_t *flag, uint32_t *region_cnt, int regions, uint64_t *stats, uint64_t sample_keys,
-                                                                       const uint64_t *qmask, uint64_t *qmask_pad, int grid)
+                                                                       const uint64_t *qmask, uint64_t *qmask_pad, int grid, uint32_t *fb_done)
 {
     const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t < qpad) fb_done[t] = 0;
     if (t < qpad) {     // padding queries (t >= Q) can never pass the filter of the scan
         thr64[t] = t < Q ? 0ull : ~0ull;
         thrp[t] = t < Q ? -__builtin_inff() : __builtin_inff();
@@ -492,8 +497,8 @@ __global__ __launch_bounds__(256) void bucket_kernel(const Record *regions, cons
 
 // ------------------------------------------------------------------------------------------------
 // finalize: select each query's best k in order; a query whose list overflowed is resolved by an
-// exhaustive scan of all keys that uses the same MFMA sequence per output element as the scan kernel,
-// so both paths produce bit-identical scores.
+// exhaustive scan of all keys (shared by fb_parts workgroups) that uses the same MFMA sequence per output
+// element as the scan kernel, so both paths produce bit-identical scores.
 // ------------------------------------------------------------------------------------------------
 struct FinalArgs {
     const void *keys;
@@ -511,6 +516,9 @@ struct FinalArgs {
     int64_t n_keys;
     int32_t d, k, cand_cap;
     DrawArgs draw;
+    uint32_t *fb_done;        // [Q] arrivals of the parts of an exhaustive scan (zero before the launch)
+    uint64_t *fb_lists;       // [Q][fb_parts][k] their partial results
+    int32_t fb_parts;
 };
 
 // KT = KT_FP8_Q8 stands for fp8 keys with fp8 queries (one fp8 matrix instruction per 64-byte chunk, as in the scan).
@@ -630,9 +638,29 @@ template <int KT> __global__ __launch_bounds__(256) void finalize_kernel(FinalAr
     uint64_t *buf = reinterpret_cast<uint64_t *>(smem_raw);
     uint32_t *ctl = reinterpret_cast<uint32_t *>(smem_raw + sizeof(uint64_t) * a.cand_cap);
     SelectScratch *sc = reinterpret_cast<SelectScratch *>(smem_raw + sizeof(uint64_t) * a.cand_cap + 16);
-    const int q = blockIdx.x, tid = threadIdx.x;
-    if (a.flag[q] != 0 && a.n_keys > 0) {
-        exhaustive_query<KT>(a, q, buf, ctl, sc, 0, a.n_keys);
+    const int q = blockIdx.x, part = blockIdx.y, tid = threadIdx.x;
+    const bool flagged = a.flag[q] != 0 && a.n_keys > 0;
+    if (!flagged && part != 0) return;
+    if (flagged) {
+        // The grid has fb_parts workgroups per query; for a flagged query each scans its share of the rows and leaves
+        // its best k as a sorted list, and the one that arrives last merges the lists.  (One workgroup alone would
+        // read the whole knowledge base at the speed of a single compute unit.)
+        const int64_t len = ((a.n_keys + a.fb_parts - 1) / a.fb_parts + 127) / 128 * 128;
+        const int64_t begin = (int64_t)part * len, end = begin + len < a.n_keys ? begin + len : a.n_keys;
+        uint64_t *mine = a.fb_lists + ((size_t)q * a.fb_parts + part) * a.k;
+        if (begin < end) exhaustive_query<KT>(a, q, buf, ctl, sc, begin, end);
+        if (tid < a.k) mine[tid] = begin < end ? buf[tid] : 0ull;
+        __threadfence();                // the list is visible device-wide before the arrival is counted
+        __syncthreads();
+        if (tid == 0) ctl[1] = atomicAdd(&a.fb_done[q], 1u);
+        __syncthreads();
+        if (ctl[1] != (uint32_t)a.fb_parts - 1) return;
+        __threadfence();
+        const int n = a.fb_parts * a.k;                                  // <= cand_cap words
+        const uint64_t *lists = a.fb_lists + (size_t)q * a.fb_parts * a.k;
+        for (int i = tid; i < n; i += 256) buf[i] = __builtin_nontemporal_load(lists + i);
+        __syncthreads();
+        select_topk_desc(buf, n, a.k, sc, tid, 256);
         if (tid == 0) atomicAdd(reinterpret_cast<unsigned long long *>(a.stats + 1), 1ull);
     } else {
         // gather the query's segments into one contiguous list
@@ -1005,6 +1033,7 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
     float *thrp = reinterpret_cast<float *>(ws + p.off_thrp);
     uint32_t *cnt = reinterpret_cast<uint32_t *>(ws + p.off_cnt);
     uint32_t *flag = reinterpret_cast<uint32_t *>(ws + p.off_flag);
+    uint32_t *fb_done = reinterpret_cast<uint32_t *>(ws + p.off_fb_done);
     uint32_t *region_cnt = reinterpret_cast<uint32_t *>(ws + p.off_region_cnt);
     uint64_t *stats = reinterpret_cast<uint64_t *>(ws + p.off_stats);
     uint64_t *qmask_pad = reinterpret_cast<uint64_t *>(ws + p.off_qmask);
@@ -1032,11 +1061,11 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
         const int blocks_rows = (int)ceil_div(p.qpad, 4), blocks_init = (int)ceil_div(n_init, 256);
         const unsigned grid = blocks_rows > blocks_init ? blocks_rows : blocks_init;
         if (q_dtype == KB_F32)
-            hipLaunchKernelGGL(prep_kernel<KB_F32>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, region_cnt, p.regions, stats, (uint64_t)p.sample_keys, qmask_dev, qmask_pad, p.grid);
+            hipLaunchKernelGGL(prep_kernel<KB_F32>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, region_cnt, p.regions, stats, (uint64_t)p.sample_keys, qmask_dev, qmask_pad, p.grid, fb_done);
         else if (q_dtype == KB_FP8_E4M3)
-            hipLaunchKernelGGL(prep_kernel<KB_FP8_E4M3>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, region_cnt, p.regions, stats, (uint64_t)p.sample_keys, qmask_dev, qmask_pad, p.grid);
+            hipLaunchKernelGGL(prep_kernel<KB_FP8_E4M3>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, region_cnt, p.regions, stats, (uint64_t)p.sample_keys, qmask_dev, qmask_pad, p.grid, fb_done);
         else
-            hipLaunchKernelGGL(prep_kernel<KB_BF16>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, region_cnt, p.regions, stats, (uint64_t)p.sample_keys, qmask_dev, qmask_pad, p.grid);
+            hipLaunchKernelGGL(prep_kernel<KB_BF16>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, region_cnt, p.regions, stats, (uint64_t)p.sample_keys, qmask_dev, qmask_pad, p.grid, fb_done);
         if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
     }
 
@@ -1121,6 +1150,9 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
     f.k = k;
     f.cand_cap = p.cand_cap;
     f.draw = dr;
+    f.fb_done = fb_done;
+    f.fb_lists = reinterpret_cast<uint64_t *>(ws + p.off_fb_lists);
+    f.fb_parts = p.fb_parts;
     const size_t fin_lds = (size_t)p.cand_cap * 8 + 16 + sizeof(SelectScratch);
     static bool fin_attr[4] = {false, false, false, false};
     const int fin_kind = q8 ? KT_FP8_Q8 : (int)kb->dtype;
@@ -1133,10 +1165,10 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
         fin_attr[fin_kind] = true;
     }
     switch (fin_kind) {
-    case KB_F32: hipLaunchKernelGGL(finalize_kernel<KB_F32>, dim3(Q), dim3(256), fin_lds, s, f); break;
-    case KB_BF16: hipLaunchKernelGGL(finalize_kernel<KB_BF16>, dim3(Q), dim3(256), fin_lds, s, f); break;
-    case KB_FP8_E4M3: hipLaunchKernelGGL(finalize_kernel<KB_FP8_E4M3>, dim3(Q), dim3(256), fin_lds, s, f); break;
-    default: hipLaunchKernelGGL(finalize_kernel<KT_FP8_Q8>, dim3(Q), dim3(256), fin_lds, s, f); break;
+    case KB_F32: hipLaunchKernelGGL(finalize_kernel<KB_F32>, dim3(Q, p.fb_parts), dim3(256), fin_lds, s, f); break;
+    case KB_BF16: hipLaunchKernelGGL(finalize_kernel<KB_BF16>, dim3(Q, p.fb_parts), dim3(256), fin_lds, s, f); break;
+    case KB_FP8_E4M3: hipLaunchKernelGGL(finalize_kernel<KB_FP8_E4M3>, dim3(Q, p.fb_parts), dim3(256), fin_lds, s, f); break;
+    default: hipLaunchKernelGGL(finalize_kernel<KT_FP8_Q8>, dim3(Q, p.fb_parts), dim3(256), fin_lds, s, f); break;
     }
     if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
     return KB_OK;

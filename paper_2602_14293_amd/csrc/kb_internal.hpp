@@ -84,6 +84,8 @@ struct Plan {
     int32_t region_cap;                 // records per scan wavefront
     int32_t regions;                    // grid * wavefronts per workgroup
     int32_t cand_cap;                   // candidates per query the final sort can take (power of two)
+    size_t off_fb_done, off_fb_lists;       // exhaustive path: per-query arrival counters, per-(query, part) partial lists
+    int32_t fb_parts;                      // parts the rows are split into when a query takes the exhaustive path
     size_t off_invq, off_thr64, off_thrp, off_cnt, off_flag, off_region_cnt, off_stats, off_qmask, off_samp, off_regions,
         off_cand, off_lgain, total;
 };
