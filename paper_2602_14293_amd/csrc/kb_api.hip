@@ -92,11 +92,12 @@ int64_t pow2_ceil(int64_t x)
 }
 size_t align_up(size_t x) { return (x + WS_ALIGN - 1) / WS_ALIGN * WS_ALIGN; }
 
-// Multiplier of the sampling pass's row scatter j -> (j * m) mod n: about n / golden ratio, so that consecutive j
-// land far apart and fill the range evenly, and coprime to n, so that the map is one to one.
+// Multiplier of the sampling pass's scatter j -> (j * m) mod n over the n runs of rows: about n / golden ratio, so
+// that consecutive j land far apart and fill the range evenly, and coprime to n, so that the map is one to one.
+// 0 (no scatter) when there are too few runs.
 uint64_t scatter_multiplier(int64_t n)
 {
-    if (n < 3) return 1;
+    if (n < 3) return 0;
     uint64_t m = (uint64_t)((double)n * 0.6180339887498949) | 1u;
     for (;; m += 2) {
         uint64_t a = m, b = (uint64_t)n;
@@ -1093,15 +1094,16 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
         a.draw = dr;
         a.tile_stride = 1;
         a.row_mul = 0;
+        a.row_run_shift = 0;
         if (p.sample_tiles > 0) {
             // the sample is spread evenly over the knowledge base: a prefix says nothing about later rows when
             // the rows are grouped (by state, by cluster, by age)
             a.n_tiles = p.sample_tiles;
             a.tile_stride = (int32_t)(ceil_div(kb->n, p.tk) / p.sample_tiles);
-            // ... row by row where the kernel can gather (the weighted selection's keys are generated for runs of
-            // neighbouring rows, the two-phase and register-tile kernels load whole tiles: those take every
-            // tile_stride-th tile instead)
-            a.row_mul = (!draw && (p.sample_family == 0 || p.sample_family == 3)) ? scatter_multiplier(kb->n) : 0;
+            // ... row by row where the kernel can gather (the two-phase and register-tile kernels load whole tiles:
+            // they take every tile_stride-th tile instead)
+            a.row_run_shift = draw ? 2 : 0;
+            a.row_mul = (p.sample_family == 0 || p.sample_family == 3) ? scatter_multiplier(kb->n >> a.row_run_shift) : 0;
             int64_t sgrid = p.sample_tiles * p.nqb;
             const int64_t smax = (int64_t)(kb->cu_count > 0 ? kb->cu_count : ASSUMED_CUS) * p.sample_wgpc;
             if (sgrid > smax) sgrid = smax;

@@ -228,12 +228,17 @@ __device__ inline float draw_key_of(float score, const DrawArgs &dr, uint32_t qu
 }
 
 // Keys of the 16 elements a lane holds in one block (four runs of four consecutive rows: four generator calls).
-__device__ inline void block_keys(const f32x16 &a, const EpiRows &rw, float iq, const DrawArgs &dr, uint32_t query, int64_t row0,
+// SAMPLED: the rows are those of a sampling pass (row0 counts sample rows; runs of four map to their place in the
+// knowledge base).
+template <bool SAMPLED>
+__device__ inline void block_keys(const f32x16 &a, const EpiRows &rw, float iq, const ScanArgs &p, uint32_t query, int64_t row0,
                                   float (&key)[16])
 {
+    const DrawArgs &dr = p.draw;
 #pragma unroll
     for (int run = 0; run < 4; ++run) {
-        const int64_t first = row0 + rw.rl0 + 8 * run;         // a multiple of 4
+        const int64_t logical = row0 + rw.rl0 + 8 * run;       // a multiple of 4
+        const int64_t first = SAMPLED ? (int64_t)sample_index(p, logical) : logical;
         uint32_t w[4];
         philox4x32_10((uint32_t)(first >> 2), query, dr.seed_lo, dr.seed_hi, w);
         const f32x4 lg = *reinterpret_cast<const f32x4 *>(dr.log_gain + first);
@@ -255,7 +260,7 @@ __device__ inline void main_block_draw(const f32x16 &a, const EpiRows &rw, float
     const float iq = sd.invq[ql];
     const uint32_t query = p.draw.first_query + (uint32_t)(q0 + ql);
     float key[16];
-    block_keys(a, rw, iq, p.draw, query, row0, key);
+    block_keys<false>(a, rw, iq, p, query, row0, key);
     uint32_t pass = 0;
 #pragma unroll
     for (int i = 0; i < 16; ++i) pass = (pass << 1) | (key[i] >= tp && key[i] > -__builtin_inff() ? 1u : 0u);   // element i at bit 15 - i
@@ -328,7 +333,7 @@ __device__ inline void sample_epilogue_draw(const f32x16 (&acc)[IB][JB], const E
         for (int ib = 0; ib < IB; ++ib) {
             const EpiRows rw = load_rows(sd, wave_row0 + ib * 32 + 4 * half);
             float key[16];
-            block_keys(acc[ib][jb], rw, iq, p.draw, query, row0, key);
+            block_keys<true>(acc[ib][jb], rw, iq, p, query, row0, key);
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int rl = rw.rl0 + 8 * (i >> 2) + (i & 3);
@@ -341,7 +346,7 @@ __device__ inline void sample_epilogue_draw(const f32x16 (&acc)[IB][JB], const E
             }
         }
         if (q0 + ql < p.Q)
-            p.samp[(size_t)(q0 + ql) * p.sample_slots + slot] = best_rl >= 0 ? pack_candidate(best, (uint32_t)(row0 + best_rl)) : 0ull;
+            p.samp[(size_t)(q0 + ql) * p.sample_slots + slot] = best_rl >= 0 ? pack_candidate(best, sample_index(p, row0 + best_rl)) : 0ull;
     }
 }
 

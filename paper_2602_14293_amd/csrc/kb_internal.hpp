@@ -118,24 +118,34 @@ struct ScanArgs {
     int64_t n_keys;           // rows to scan: [0, n_keys)
     int64_t n_tiles;          // key tiles to scan: logical tile t is rows [t * tile_stride * TK, +TK)
     int32_t tile_stride;      // 1 for the main pass; a sampling pass takes every tile_stride-th tile ...
-    uint64_t row_mul;         // ... or, when nonzero, scatters its rows: sample row j is key row (j * row_mul) mod n_keys
+    uint64_t row_mul;         // ... or, when nonzero, scatters its rows in runs of 2^row_run_shift (see sample_row)
+    int32_t row_run_shift;
     int32_t d, Q, nqb, sample_slots, region_cap;
     DrawArgs draw;
 };
 
-// Key row behind row r of logical tile `tile` in a sampling pass.  With row_mul (coprime to n_keys, about 0.618
-// n_keys) consecutive sample rows are far apart in the knowledge base, so every group of rows whose maximum the
-// sampling epilogue keeps mixes rows from all over it: the threshold stays tight when the rows are grouped by
-// cluster.  Without it the tile is tile_stride tiles further on and rows past the end repeat the last row.
+// Key row behind row r of logical tile `tile` in a sampling pass.  With row_mul the sample is scattered in runs of
+// R = 2^row_run_shift rows: run j of the sample is run (j * row_mul) mod (n_keys / R) of the knowledge base (row_mul
+// coprime to the number of runs and about 0.618 of it: one to one, consecutive runs far apart).  Every group of
+// rows whose maximum the sampling epilogue keeps then mixes rows from all over the knowledge base, so the
+// threshold stays tight when the rows are grouped by cluster.  R = 1 for the plain retrieval; the weighted
+// selection takes runs of four, which keep what it shares between neighbouring rows (one generator call, one
+// 16-byte load of gains).  Without row_mul the tile is tile_stride tiles further on and rows past the end repeat
+// the last row.
+__device__ inline int64_t sample_index64(const ScanArgs &p, int64_t row)
+{
+    const int sh = p.row_run_shift;
+    return (int64_t)((((uint64_t)(row >> sh) * p.row_mul) % ((uint64_t)p.n_keys >> sh)) << sh) + (row & ((1 << sh) - 1));
+}
 __device__ inline int64_t sample_row(const ScanArgs &p, int64_t tile, int tk, int r)
 {
-    if (p.row_mul) return (int64_t)(((uint64_t)(tile * tk + r) * p.row_mul) % (uint64_t)p.n_keys);
+    if (p.row_mul) return sample_index64(p, tile * tk + r);
     const int64_t row = tile * p.tile_stride * tk + r;
     return row < p.n_keys ? row : p.n_keys - 1;
 }
 // first row number the sampling epilogues count from: logical when the rows are scattered (see sample_index)
 __device__ inline int64_t sample_row0(const ScanArgs &p, int64_t tile, int tk) { return p.row_mul ? tile * tk : tile * p.tile_stride * tk; }
-__device__ inline uint32_t sample_index(const ScanArgs &p, int64_t row) { return (uint32_t)(p.row_mul ? ((uint64_t)row * p.row_mul) % (uint64_t)p.n_keys : (uint64_t)row); }
+__device__ inline uint32_t sample_index(const ScanArgs &p, int64_t row) { return (uint32_t)(p.row_mul ? sample_index64(p, row) : row); }
 
 // Launchers, one translation unit per key dtype.  `sample` selects the sampling epilogue.
 hipError_t launch_scan_f32(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);

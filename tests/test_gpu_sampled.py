@@ -118,3 +118,10 @@ def test_exhaustive_path_draws_too(T):
     w = W.clustered(seed=28, N=20000, d=64, Q=3, k=5, centers=2)
     w.keys[:] = w.keys[0]
     rep, cnt, gi, gk, keys = _run(T, w, np.ones(w.N, dtype=np.float32), 0.5, seed=3, label="all keys equal, draw")
+
+
+def test_draw_on_rows_grouped_by_cluster(T):
+    # rows sorted by cluster: the sampling pass of the draw scatters its rows too, the lists do not overflow
+    w, cent, off = W.grouped(seed=31, C=64, mean_size=1000, d=256, spread=0.03, Q=40, k=16, dtype=torch.bfloat16)
+    rep, cnt, gi, gk, keys = _run(T, w, _gains(w.N, 6), 0.05, seed=123, label="draw on grouped rows")
+    assert rep.queries == 40 and cnt["exhaustive_queries"] == 0
