@@ -57,6 +57,13 @@ bool scan_config_info(int key_dtype, int config, ConfigInfo *out)
     KB_SCAN_SP_CONFIGS_FP8(XS)
     KB_SCAN_SP_CONFIGS_FP8_Q8(XS)
 #undef XS
+#define XW(ID, KT)                                                            \
+    if (key_dtype == KT && config == ID) {                                    \
+        *out = ConfigInfo{256, 256, 512, 8, 1, 512, 4};                       \
+        return true;                                                          \
+    }
+    KB_SCAN_WIDE_CONFIGS_BF16(XW)
+#undef XW
     return false;
 }
 
@@ -146,9 +153,13 @@ bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, bool draw, bool q8,
     const int64_t n_tiles = ceil_div(n, ci.tk);
 
     // The sampling pass may run another scan configuration than the main pass (same query block width; every
-    // kernel produces bit-identical scores, so thresholds carry over).  Today it uses the same one.
+    // kernel produces bit-identical scores, so thresholds carry over).
     ConfigInfo sci = ci;
     p.sample_config = p.config;
+    if (ci.family == 4) {       // main pass only: the sampling pass takes the interleaved software-pipelined kernel
+        p.sample_config = KB_WIDE_SAMPLE_CONFIG;
+        if (!scan_config_info(h->dtype, p.sample_config, &sci) || sci.tq != ci.tq || row_bytes < (size_t)sci.min_row_bytes) return false;
+    }
     p.sample_family = sci.family;
     p.sample_wgpc = sci.wg_per_cu;
     const int64_t s_tiles_all = ceil_div(n, sci.tk);
@@ -756,6 +767,7 @@ hipError_t launch_scan(kb_dtype_t dt, int config, int family, bool sample, int g
 {
     if (family == 1) return dt == KB_BF16 ? launch_scan_pp_bf16(config, sample, grid, a, s) : hipErrorInvalidValue;
     if (family == 2) return dt == KB_BF16 ? launch_scan_big_bf16(config, sample, grid, a, s) : hipErrorInvalidValue;
+    if (family == 4) return dt == KB_BF16 ? launch_scan_wide_bf16(config, sample, grid, a, s) : hipErrorInvalidValue;
     if (family == 3)
         return dt == KB_BF16 ? launch_scan_sp_bf16(config, sample, grid, a, s)
                : dt == KB_FP8_E4M3 ? launch_scan_sp_fp8(config, sample, grid, a, s) : hipErrorInvalidValue;

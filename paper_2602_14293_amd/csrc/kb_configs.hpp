@@ -45,3 +45,9 @@
 // ... with fp8 queries as well (the fp8 matrix instruction): XQ(id, key dtype, TQ, NSA, NSB)
 #define KB_SCAN_SP_CONFIGS_FP8_Q8(XQ) \
     XQ(5, KB_FP8_E4M3, 256, 5, 4)
+
+// Full-line configurations (kb_scan_wide.hpp): XW(id, key dtype); 256 x 256 tiles, 512 threads, 128-byte row pieces,
+// main pass only (the sampling pass runs KB_WIDE_SAMPLE_CONFIG).
+#define KB_SCAN_WIDE_CONFIGS_BF16(XW) \
+    XW(18, KB_BF16)
+#define KB_WIDE_SAMPLE_CONFIG 17

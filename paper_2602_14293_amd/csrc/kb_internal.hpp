@@ -154,13 +154,14 @@ hipError_t launch_scan_fp8(int config, bool sample, int grid, const ScanArgs &a,
 hipError_t launch_scan_pp_bf16(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
 hipError_t launch_scan_big_bf16(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
 hipError_t launch_scan_sp_bf16(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
+hipError_t launch_scan_wide_bf16(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
 hipError_t launch_scan_sp_fp8(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
 
 // Static description of a scan configuration (host side planning).
 struct ConfigInfo {
     int tk, tq, threads, groups_per_tile, wg_per_cu;
     int min_row_bytes;      // smallest key row (bytes) the configuration's pipeline is valid for
-    int family;             // 0: kb_scan.hpp, 1: kb_scan_pp.hpp, 2: kb_scan_big.hpp, 3: kb_scan_sp.hpp
+    int family;             // 0: kb_scan.hpp, 1: kb_scan_pp.hpp, 2: kb_scan_big.hpp, 3: kb_scan_sp.hpp, 4: kb_scan_wide.hpp
 };
 bool scan_config_info(int key_dtype, int config, ConfigInfo *out);   // false if the id does not exist
 int scan_config_for(int key_dtype, int Q, int d);                    // automatic choice

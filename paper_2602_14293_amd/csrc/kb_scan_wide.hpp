@@ -1,0 +1,388 @@
+// The large-batch scan kernel, full-line version: 256 key rows x 256 queries per work item on eight wavefronts
+// like kb_scan_sp.hpp, but the direct-to-LDS loads fetch 128 bytes of every key row and of every query row at a
+// time (gfx950 only; bf16; main pass only).
+//
+// Why 128-byte rows.  A direct-to-LDS load instruction moves 1 KiB; with 64-byte row pieces it covers half of
+// 16 cache lines and the other halves are asked for again one d-chunk later, with 128-byte pieces it covers 8
+// whole lines once.  Measured with the load pattern and the MFMA count of this kernel and nothing else (256
+// workgroups, 2^20 x 1024 bf16 keys, 256 queries): 64-byte pieces 0.47 ms, 128-byte pieces for the keys only
+// 0.44 ms, for both operands 0.36 ms, which is what streaming the keys alone takes.
+//
+// The price is LDS: a d-chunk is now 64 elements, 32 KiB of keys + 32 KiB of queries, and a key piece issued
+// now lands about two chunk times later (HBM under load).  So the chunk is worked through in two PHASES, one
+// per PIECE of keys (16 KiB: 128 rows x 128 bytes), and the ring is kept in pieces: five of keys (one in use,
+// four in flight) and four of queries (one chunk in use, the next one landing).  In phase f = 2 g + rh a wave
+// (wm, wn) multiplies rows 128 rh + 64 wm + [0, 64) of the tile with queries 64 wn + [0, 64): sixteen MFMAs in
+// four k-steps, fragments in two register sets X and Y (while the MFMAs of one k-step run on one set, the other
+// is refilled), one barrier per phase:
+//
+//   k-step 0 on X, Y <- (f,1);  k-step 1 on Y, X <- (f,2);  k-step 2 on X, Y <- (f,3);
+//   wait for my own loads of key piece f+1 (and, rh = 1, of query chunk g+1) and for my LDS reads; BARRIER f
+//   (publishes those, retires key piece f and, rh = 1, query chunk g);
+//   k-step 3 on Y, X <- (f+1,0).
+//
+// Waves 0-3 load keys: piece f+5 into the slot of piece f, one instruction after each MFMA of the k-step that
+// follows barrier f, so that it has four phases to land.  Waves 4-7 load queries: chunk g+2 into the slots of
+// chunk g, one instruction after each MFMA of the first two k-steps of phase 2g+2.  The two kinds keep separate
+// load counters, so the wait for a query chunk issued a phase ago does not drain the key pieces issued up to
+// four phases ago.
+//
+// Accumulation order over d, lane-to-element mapping and epilogue are those of the other scan kernels, so the
+// scores are bit-identical to theirs.
+#pragma once
+#include "kb_scan.hpp"
+
+namespace kbi {
+
+template <int KT_> struct WideCfg {
+    static constexpr int KT = KT_;
+    static constexpr int TK = 256, TQ = 256, THREADS = 512, NW = 8;
+    static constexpr int KEY_BYTES = KeyTraits<KT>::KEY_BYTES, QRY_BYTES = KeyTraits<KT>::QRY_BYTES;
+    static constexpr int RB = 128;                                   // bytes of a key / query row per d-chunk
+    static constexpr int PIECE_ROWS = 128, PIECE_BYTES = PIECE_ROWS * RB;
+    static constexpr int NPA = 5, NPB = 4;                           // ring depth in pieces: keys, queries
+    static constexpr int IB = 2, JB = 2;                             // 32-row blocks of a wave in one phase
+    static constexpr int OFF_B = NPA * PIECE_BYTES;
+    static constexpr int OFF_AUX = OFF_B + NPB * PIECE_BYTES;
+    // side data of a key tile, two copies (item parity)
+    static constexpr int AUX_INVK = 0;                       // float  [TK]
+    static constexpr int AUX_TAG = AUX_INVK + TK * 4;        // uint64 [TK]
+    static constexpr int AUX_BYTES = AUX_TAG + TK * 8;
+    // side data of a query block, one copy
+    static constexpr int QAUX_THRP = 0;                      // float  [TQ]
+    static constexpr int QAUX_INVQ = QAUX_THRP + TQ * 4;     // float  [TQ]
+    static constexpr int QAUX_THR64 = QAUX_INVQ + TQ * 4;    // uint64 [TQ]
+    static constexpr int QAUX_QMASK = QAUX_THR64 + TQ * 8;   // uint64 [TQ]
+    static constexpr int QAUX_BYTES = QAUX_QMASK + TQ * 8;
+    static constexpr int OFF_QAUX = OFF_AUX + 2 * AUX_BYTES;
+    static constexpr int SMEM_BYTES = OFF_QAUX + QAUX_BYTES;
+    static constexpr int MIN_ROW_BYTES = 4 * RB;             // the key stream runs five pieces ahead of the MFMAs
+    static_assert(KT == KB_BF16 && KEY_BYTES == QRY_BYTES, "written for bf16 keys and queries");
+    static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget");
+};
+
+template <class C>
+__global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
+{
+    constexpr int TK = C::TK, TQ = C::TQ, RB = C::RB, IB = C::IB, JB = C::JB, NW = C::NW, PB = C::PIECE_BYTES;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    typedef __attribute__((address_space(3))) void *lds_ptr;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave & 1, wn = wave >> 1;
+    const int lrow = lane & 31, half = lane >> 5;
+    const bool filter = p.qmask != nullptr;
+
+    const int nqb = p.nqb;
+    const int64_t n_items = p.n_tiles * nqb;
+    const int vb = item_lane(blockIdx.x, gridDim.x, nqb);      // this workgroup takes items vb, vb + gridDim.x, ...
+    const int my_items = (int64_t)vb < n_items ? (int)((n_items - vb + gridDim.x - 1) / gridDim.x) : 0;
+    const int NC = p.d * C::KEY_BYTES / RB;                    // chunks per item
+    const int total = my_items * NC;                           // chunks of this workgroup
+    const int phases = 2 * total;
+    const uint32_t key_row_bytes = (uint32_t)p.d * C::KEY_BYTES, qry_row_bytes = (uint32_t)p.d * C::QRY_BYTES;
+    const int step_tile = gridDim.x / nqb, step_qb = gridDim.x % nqb;
+
+    Record *my_region = p.regions + ((size_t)blockIdx.x * NW + wave) * p.region_cap;
+    uint32_t wave_cnt = 0;
+
+    // ---- the load streams -------------------------------------------------------------------------------
+    // A piece is 16 load instructions of 1 KiB (8 rows x 128 bytes); loading wave ridx issues instructions ridx,
+    // ridx+4, ridx+8, ridx+12 of a piece.  The lane that fills physical 16-byte slot s of row r fetches logical
+    // slot s ^ swizzle<8>(r); the rows of a wave's four instructions are 32 apart, so they share the swizzle.
+    const int role = wave >> 2, ridx = wave & 3;                       // role 0: keys, role 1: queries
+    const int ld_row = ridx * 8 + (lane >> 3);                         // row within the piece, instruction 0
+    const uint32_t ld_slot = (uint32_t)(((lane & 7) ^ swizzle<8>(ld_row)) * 16);
+    // the stream cursor: (tile, query block, chunk) of the next key piece (role 0) / query chunk (role 1) to issue
+    int ld_tile = vb / nqb, ld_qb = vb % nqb, ld_c = 0, ld_h = 0, ld_par = 0, ld_ring = 0;
+    int ld_left = role == 0 ? phases : total;                          // pieces / chunks not yet issued in full
+    uint32_t off[2][4];                                                // [piece of the chunk][instruction]
+    auto ld_setup = [&]() {
+        int last, base;
+        if (role == 0) {
+            const int64_t left = p.n_keys - (int64_t)ld_tile * TK;
+            last = left < TK ? (int)left - 1 : TK - 1;
+            base = 0;
+        } else {
+            last = p.Q - 1 - ld_qb * TQ;
+            base = ld_qb * TQ;
+        }
+        const uint32_t rb = role == 0 ? key_row_bytes : qry_row_bytes;
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int r = h * C::PIECE_ROWS + ld_row + j * 32;
+                off[h][j] = (uint32_t)(base + (r < last ? r : last)) * rb + ld_slot;
+            }
+    };
+    // side data of the key tile the key stream is at: 4-byte loads with clamped rows from the caller's arrays
+    auto issue_tile_aux = [&]() {       // role 0 only
+        unsigned char *aux = smem + C::OFF_AUX + ld_par * C::AUX_BYTES;
+        const int64_t row0 = (int64_t)ld_tile * TK;
+        {
+            int64_t r = row0 + ridx * 64 + lane;
+            r = r < p.n_keys ? r : p.n_keys - 1;
+            __builtin_amdgcn_global_load_lds((const void *)(p.inv_norm + r), (lds_ptr)(aux + C::AUX_INVK + ridx * 256), 4, 0, 0);
+        }
+        if (filter) {
+#pragma unroll
+            for (int h2 = 0; h2 < 2; ++h2) {        // tags as dwords: instruction i covers rows [32 i, 32 i + 32)
+                const int i = ridx * 2 + h2;
+                int64_t r = row0 + i * 32 + (lane >> 1);
+                r = r < p.n_keys ? r : p.n_keys - 1;
+                __builtin_amdgcn_global_load_lds((const void *)(reinterpret_cast<const uint32_t *>(p.tags + r) + (lane & 1)),
+                                                 (lds_ptr)(aux + C::AUX_TAG + i * 256), 4, 0, 0);
+            }
+        }
+    };
+    // side data of a query block: 16-byte loads from the library's padded per-query arrays
+    auto issue_query_aux = [&](int qb) {    // role 1 only
+        unsigned char *aux = smem + C::OFF_QAUX;
+        const int q0 = qb * TQ;
+        if (ridx == 0) {
+            __builtin_amdgcn_global_load_lds((const void *)(p.invq + q0 + lane * 4), (lds_ptr)(aux + C::QAUX_INVQ), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const void *)(p.thrp + q0 + lane * 4), (lds_ptr)(aux + C::QAUX_THRP), 16, 0, 0);
+        } else if (ridx == 1) {
+            __builtin_amdgcn_global_load_lds((const void *)(p.thr64 + q0 + lane * 2), (lds_ptr)(aux + C::QAUX_THR64), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const void *)(p.thr64 + q0 + 128 + lane * 2), (lds_ptr)(aux + C::QAUX_THR64 + 1024), 16, 0, 0);
+        } else if (ridx == 2 && filter) {
+            __builtin_amdgcn_global_load_lds((const void *)(p.qmask_pad + q0 + lane * 2), (lds_ptr)(aux + C::QAUX_QMASK), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const void *)(p.qmask_pad + q0 + 128 + lane * 2), (lds_ptr)(aux + C::QAUX_QMASK + 1024), 16, 0, 0);
+        }
+    };
+    // role 0: load j (0..3) of the key piece at the cursor; key_next() moves the cursor on
+    auto key_issue = [&](int j) {
+        if (ld_left <= 0) return;
+        if (j == 0 && ld_c == 0 && ld_h == 0) issue_tile_aux();
+        const unsigned char *g = static_cast<const unsigned char *>(p.keys) + (size_t)ld_tile * TK * key_row_bytes + (size_t)ld_c * RB;
+        __builtin_amdgcn_global_load_lds((const void *)(g + (ld_h ? off[1][j] : off[0][j])),
+                                         (lds_ptr)(smem + ld_ring * PB + (ridx + 4 * j) * 1024), 16, 0, 0);
+    };
+    auto item_next = [&]() {
+        ld_c = 0;
+        ld_par ^= 1;
+        ld_tile += step_tile;
+        ld_qb += step_qb;
+        if (ld_qb >= nqb) {
+            ld_qb -= nqb;
+            ++ld_tile;
+        }
+        if (ld_left > 0 && (role == 0 || nqb > 1)) ld_setup();
+    };
+    auto key_next = [&]() {
+        if (ld_left <= 0) return;
+        --ld_left;
+        ld_ring = ld_ring + 1 == C::NPA ? 0 : ld_ring + 1;
+        ld_h ^= 1;
+        if (ld_h == 0 && ++ld_c == NC) item_next();
+    };
+    // role 1: load j (0..7) of the query chunk at the cursor: piece j / 4, instruction j % 4
+    auto qry_issue = [&](int j) {
+        if (ld_left <= 0) return;
+        const unsigned char *g = static_cast<const unsigned char *>(p.queries) + (size_t)ld_c * RB;
+        __builtin_amdgcn_global_load_lds((const void *)(g + off[j / 4][j % 4]),
+                                         (lds_ptr)(smem + C::OFF_B + (ld_ring + j / 4) * PB + (ridx + 4 * (j % 4)) * 1024), 16, 0, 0);
+    };
+    auto qry_next = [&]() {
+        if (ld_left <= 0) return;
+        --ld_left;
+        ld_ring ^= 2;
+        if (++ld_c == NC) item_next();
+    };
+
+    // ---- fragment addresses -------------------------------------------------------------------------------
+    // piece-local row = 64 * (wave's half of the piece) + 32 * block + lrow; logical 16-byte slot of k-step kk = 2 kk + half
+    const int baseA = (wm * 64 + lrow) * RB | ((half ^ swizzle<8>(lrow)) << 4);
+    const int baseB = C::OFF_B + (wn >> 1) * PB + (((wn & 1) * 64 + lrow) * RB | ((half ^ swizzle<8>(lrow)) << 4));
+    auto read_a = [&](int ring, int kk, int ib) {
+        return *reinterpret_cast<const u32x4 *>(smem + ring * PB + ((baseA ^ (kk << 5)) + ib * 32 * RB));
+    };
+    auto read_b = [&](int ring, int kk, int jb) {       // ring: slot of the chunk's first piece (0 or 2)
+        return *reinterpret_cast<const u32x4 *>(smem + ring * PB + ((baseB ^ (kk << 5)) + jb * 32 * RB));
+    };
+
+    f32x16 acc[2][IB][JB];
+#pragma unroll
+    for (int rh = 0; rh < 2; ++rh)
+#pragma unroll
+        for (int ib = 0; ib < IB; ++ib)
+#pragma unroll
+            for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[rh][ib][jb][i] = 0.f;
+
+    auto epilogue = [&](int tile, int qb, int par) {
+        const unsigned char *aux = smem + C::OFF_AUX + par * C::AUX_BYTES, *qaux = smem + C::OFF_QAUX;
+        const EpiSide sd{reinterpret_cast<const float *>(aux + C::AUX_INVK), reinterpret_cast<const uint64_t *>(aux + C::AUX_TAG),
+                         reinterpret_cast<const float *>(qaux + C::QAUX_THRP), reinterpret_cast<const float *>(qaux + C::QAUX_INVQ),
+                         reinterpret_cast<const uint64_t *>(qaux + C::QAUX_THR64), reinterpret_cast<const uint64_t *>(qaux + C::QAUX_QMASK)};
+        const int64_t row0 = (int64_t)tile * TK;
+#pragma unroll
+        for (int rh = 0; rh < 2; ++rh) {
+            main_epilogue<IB, JB>(acc[rh], sd, filter, rh * 128 + wm * 64, wn * 64 + lrow, half, row0, qb * TQ, p, my_region, wave_cnt);
+#pragma unroll
+            for (int ib = 0; ib < IB; ++ib)
+#pragma unroll
+                for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[rh][ib][jb][i] = 0.f;
+        }
+    };
+
+    if (total > 0) {        // uniform over the workgroup
+        // ---- prologue ---------------------------------------------------------------------------------------------
+        // keys: pieces 0..4; queries: chunks 0 and 1 (the rings are full then)
+        ld_setup();
+        if (role == 0) {
+#pragma unroll
+            for (int s = 0; s < 5; ++s) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) key_issue(j);
+                key_next();
+            }
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm(16));        // piece 0 (and the side data before it) has landed
+        } else {
+            issue_query_aux(vb % nqb);
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) qry_issue(j);
+                qry_next();
+            }
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm(8));         // chunk 0 (and the side data before it) has landed
+        }
+        __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
+        bare_barrier();
+
+        int tile = vb / nqb, qb = vb % nqb, par = 0, c = 0;
+        int ra = 0, rb = 0;                                    // ring slots: key piece of the phase, first query piece of the chunk
+        u32x4 xa[IB], xb[JB], ya[IB], yb[JB];
+#pragma unroll
+        for (int ib = 0; ib < IB; ++ib) xa[ib] = read_a(0, 0, ib);
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb) xb[jb] = read_b(0, 0, jb);
+
+#define KBW_MFMA(RH, SA, SB, I, J)                                                                                                  \
+    acc[RH][I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, SA[I]), __builtin_bit_cast(bf16x8, SB[J]),   \
+                                                            acc[RH][I][J], 0, 0, 0);                                                \
+    __builtin_amdgcn_sched_barrier(0)
+        // one k-step: four MFMAs on set (SA, SB) while set (DA, DB) is refilled from (ring slots RA_, RB_; k-step KK);
+        // L0 .. L3: what this wave loads after each of the MFMAs
+#define KBW_KSTEP(RH, SA, SB, DA, DB, RA_, RB_, KK, L0, L1, L2, L3) \
+    KBW_MFMA(RH, SA, SB, 0, 0);                                     \
+    DA[0] = read_a(RA_, KK, 0);                                     \
+    DB[0] = read_b(RB_, KK, 0);                                     \
+    L0;                                                             \
+    __builtin_amdgcn_sched_barrier(0);                              \
+    KBW_MFMA(RH, SA, SB, 0, 1);                                     \
+    DB[1] = read_b(RB_, KK, 1);                                     \
+    DA[1] = read_a(RA_, KK, 1);                                     \
+    L1;                                                             \
+    __builtin_amdgcn_sched_barrier(0);                              \
+    KBW_MFMA(RH, SA, SB, 1, 0);                                     \
+    L2;                                                             \
+    __builtin_amdgcn_sched_barrier(0);                              \
+    KBW_MFMA(RH, SA, SB, 1, 1);                                     \
+    L3;                                                             \
+    __builtin_amdgcn_sched_barrier(0)
+#define KBW_NONE (void)0
+
+        int f = 0;                                             // phase index
+        // The wait before barrier f.  Key waves: piece f+1 has landed once at most the pieces f+2 .. f+4 are
+        // outstanding (fewer at the end of the stream).  Query waves: chunk g+1 is needed from barrier 2g+1 on;
+        // they issued nothing since the first half of the phase before, so they wait for everything.
+        auto wait_before_barrier = [&](int rh) {
+            if (role == 0) {
+                const int ahead = phases - f - 2;              // pieces past f+1 that exist
+                if (ahead >= 3) __builtin_amdgcn_s_waitcnt(waitcnt_vm(12));
+                else if (ahead == 2) __builtin_amdgcn_s_waitcnt(waitcnt_vm(8));
+                else if (ahead == 1) __builtin_amdgcn_s_waitcnt(waitcnt_vm(4));
+                else __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+            } else if (rh == 1) {
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+            }
+            __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
+            __builtin_amdgcn_sched_barrier(0);
+            bare_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+        };
+
+        for (int g = 0; g < total; ++g) {
+            // ======== phase 2g: key piece in slot ra, query chunk in slots rb, rb+1 ========
+            {
+                const int ran = ra + 1 == C::NPA ? 0 : ra + 1;
+                const bool qload = role == 1 && g > 0;         // query waves: chunk g+1 into the slots barrier 2g-1 retired
+                __builtin_amdgcn_s_setprio(1);
+                KBW_KSTEP(0, xa, xb, ya, yb, ra, rb, 1, if (qload) qry_issue(0), if (qload) qry_issue(1), if (qload) qry_issue(2), if (qload) qry_issue(3));
+                KBW_KSTEP(0, ya, yb, xa, xb, ra, rb, 2, if (qload) qry_issue(4), if (qload) qry_issue(5), if (qload) qry_issue(6), if (qload) { qry_issue(7); qry_next(); });
+                KBW_KSTEP(0, xa, xb, ya, yb, ra, rb, 3, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
+                __builtin_amdgcn_s_setprio(0);
+                wait_before_barrier(0);
+                // a new query block's side data: every epilogue of the previous item ended before this barrier
+                if (role == 1 && nqb > 1 && c == 0 && g > 0) issue_query_aux(qb);
+                __builtin_amdgcn_s_setprio(1);
+                KBW_KSTEP(0, ya, yb, xa, xb, ran, rb, 0, if (role == 0) key_issue(0), if (role == 0) key_issue(1), if (role == 0) key_issue(2),
+                          if (role == 0) { key_issue(3); key_next(); });
+                __builtin_amdgcn_s_setprio(0);
+                ra = ran;
+                ++f;
+            }
+            // ======== phase 2g+1 ========
+            {
+                const int ran = ra + 1 == C::NPA ? 0 : ra + 1, rbn = rb ^ 2;
+                const bool more = g + 1 < total;
+                __builtin_amdgcn_s_setprio(1);
+                KBW_KSTEP(1, xa, xb, ya, yb, ra, rb, 1, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
+                KBW_KSTEP(1, ya, yb, xa, xb, ra, rb, 2, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
+                KBW_KSTEP(1, xa, xb, ya, yb, ra, rb, 3, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
+                __builtin_amdgcn_s_setprio(0);
+                wait_before_barrier(1);
+                __builtin_amdgcn_s_setprio(1);
+                // past the last chunk the refill of X reads the current slots again (valid memory, values unused)
+                KBW_KSTEP(1, ya, yb, xa, xb, (more ? ran : ra), (more ? rbn : rb), 0, if (role == 0) key_issue(0), if (role == 0) key_issue(1),
+                          if (role == 0) key_issue(2), if (role == 0) { key_issue(3); key_next(); });
+                __builtin_amdgcn_s_setprio(0);
+                ra = ran;
+                rb = rbn;
+                ++f;
+            }
+            if (++c == NC) {
+                epilogue(tile, qb, par);
+                c = 0;
+                par ^= 1;
+                tile += step_tile;
+                qb += step_qb;
+                if (qb >= nqb) {
+                    qb -= nqb;
+                    ++tile;
+                }
+            }
+        }
+#undef KBW_KSTEP
+#undef KBW_NONE
+#undef KBW_MFMA
+    }
+
+    if (lane == 0) {
+        const uint32_t cap = (uint32_t)p.region_cap;
+        p.region_cnt[blockIdx.x * NW + wave] = wave_cnt < cap ? wave_cnt : cap;
+    }
+}
+
+template <class C> hipError_t launch_scan_wide_cfg(bool sample, int grid, const ScanArgs &a, hipStream_t s)
+{
+    if (sample) return hipErrorInvalidValue;        // the sampling pass runs another configuration
+    static bool attr_done = false;
+    auto *fn = &kb_scan_wide_kernel<C>;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM_BYTES);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(C::THREADS), C::SMEM_BYTES, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace kbi
