@@ -69,6 +69,7 @@ bool scan_config_info(int key_dtype, int config, ConfigInfo *out)
 
 int scan_config_for(int key_dtype, int Q, int d)
 {
+    if (key_dtype == KB_BF16 && Q > 128 && d * 2 >= 512) return 18;
     if (key_dtype == KB_BF16 && Q > 128 && d * 2 >= 384) return 17;
     if (key_dtype == KB_FP8_E4M3 && Q > 128 && d >= 256) return 4;
     return Q <= 32 ? 1 : Q <= 128 ? 2 : 3;
