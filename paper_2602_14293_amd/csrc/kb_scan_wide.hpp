@@ -34,6 +34,16 @@
 
 namespace kbi {
 
+// A wave-uniform address pinned to scalar registers at this point of the program: a load from it plus a 32-bit lane
+// offset then needs no 64-bit vector arithmetic (and the compiler cannot fold the lane offset into a per-lane pointer
+// that it keeps alive across the whole kernel).
+__device__ inline const unsigned char *uniform_address(const void *ptr)
+{
+    const uint64_t v = reinterpret_cast<uint64_t>(ptr);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const unsigned char *>(((uint64_t)hi << 32) | lo);
+}
+
 template <int KT_> struct WideCfg {
     static constexpr int KT = KT_;
     static constexpr int TK = 256, TQ = 256, THREADS = 512, NW = 8;
@@ -66,7 +76,12 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
 {
     constexpr int TK = C::TK, TQ = C::TQ, RB = C::RB, IB = C::IB, JB = C::JB, NW = C::NW, PB = C::PIECE_BYTES;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    // LDS addresses are kept as 32-bit pointers of the LDS address space: arithmetic on them is one scalar add, where a
+    // generic pointer costs a conversion (with its null check) at every load
+    typedef __attribute__((address_space(3))) unsigned char lds_u8;
     typedef __attribute__((address_space(3))) void *lds_ptr;
+    typedef const __attribute__((address_space(3))) u32x4 lds_u32x4;
+    lds_u8 *const lds = (lds_u8 *)smem;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -94,9 +109,13 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
     const int role = wave >> 2, ridx = wave & 3;                       // role 0: keys, role 1: queries
     const int ld_row = ridx * 8 + (lane >> 3);                         // row within the piece, instruction 0
     const uint32_t ld_slot = (uint32_t)(((lane & 7) ^ swizzle<8>(ld_row)) * 16);
-    // the stream cursor: (tile, query block, chunk) of the next key piece (role 0) / query chunk (role 1) to issue
-    int ld_tile = vb / nqb, ld_qb = vb % nqb, ld_c = 0, ld_h = 0, ld_par = 0, ld_ring = 0;
-    int ld_left = role == 0 ? phases : total;                          // pieces / chunks not yet issued in full
+    // the stream cursor: (tile, query block, chunk) of the next key piece (role 0) / query chunk (role 1) to issue,
+    // the address of that chunk in row 0 of the tile / of the query block 0, and the ring slot it goes to
+    int ld_tile = vb / nqb, ld_qb = vb % nqb, ld_c = 0, ld_par = 0;
+    const unsigned char *ld_src = nullptr;
+    lds_u8 *const ld_ring0 = lds + (role == 0 ? 0 : C::OFF_B) + ridx * 1024;
+    lds_u8 *ld_dst = ld_ring0;
+    int ld_ring = 0;
     uint32_t off[2][4];                                                // [piece of the chunk][instruction]
     auto ld_setup = [&]() {
         int last, base;
@@ -104,9 +123,11 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
             const int64_t left = p.n_keys - (int64_t)ld_tile * TK;
             last = left < TK ? (int)left - 1 : TK - 1;
             base = 0;
+            ld_src = static_cast<const unsigned char *>(p.keys) + (size_t)ld_tile * TK * key_row_bytes;
         } else {
             last = p.Q - 1 - ld_qb * TQ;
             base = ld_qb * TQ;
+            ld_src = static_cast<const unsigned char *>(p.queries);
         }
         const uint32_t rb = role == 0 ? key_row_bytes : qry_row_bytes;
 #pragma unroll
@@ -118,49 +139,49 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
             }
     };
     // side data of the key tile the key stream is at: 4-byte loads with clamped rows from the caller's arrays
+    // (addresses as a wave-uniform base plus a 32-bit lane offset, the form that needs no 64-bit vector arithmetic)
     auto issue_tile_aux = [&]() {       // role 0 only
-        unsigned char *aux = smem + C::OFF_AUX + ld_par * C::AUX_BYTES;
+        lds_u8 *aux = lds + C::OFF_AUX + ld_par * C::AUX_BYTES;
         const int64_t row0 = (int64_t)ld_tile * TK;
+        const int64_t left = p.n_keys - row0;
+        const uint32_t last = left < TK ? (uint32_t)left - 1 : TK - 1;
         {
-            int64_t r = row0 + ridx * 64 + lane;
-            r = r < p.n_keys ? r : p.n_keys - 1;
-            __builtin_amdgcn_global_load_lds((const void *)(p.inv_norm + r), (lds_ptr)(aux + C::AUX_INVK + ridx * 256), 4, 0, 0);
+            const uint32_t r = (uint32_t)(ridx * 64 + lane);
+            const unsigned char *g = uniform_address(p.inv_norm + row0);
+            __builtin_amdgcn_global_load_lds((const void *)(g + (r < last ? r : last) * 4u), (lds_ptr)(aux + C::AUX_INVK + ridx * 256), 4, 0, 0);
         }
         if (filter) {
+            const unsigned char *g = uniform_address(p.tags + row0);
 #pragma unroll
             for (int h2 = 0; h2 < 2; ++h2) {        // tags as dwords: instruction i covers rows [32 i, 32 i + 32)
                 const int i = ridx * 2 + h2;
-                int64_t r = row0 + i * 32 + (lane >> 1);
-                r = r < p.n_keys ? r : p.n_keys - 1;
-                __builtin_amdgcn_global_load_lds((const void *)(reinterpret_cast<const uint32_t *>(p.tags + r) + (lane & 1)),
+                const uint32_t r = (uint32_t)(i * 32 + (lane >> 1));
+                __builtin_amdgcn_global_load_lds((const void *)(g + ((r < last ? r : last) * 8u + (lane & 1) * 4u)),
                                                  (lds_ptr)(aux + C::AUX_TAG + i * 256), 4, 0, 0);
             }
         }
     };
     // side data of a query block: 16-byte loads from the library's padded per-query arrays
     auto issue_query_aux = [&](int qb) {    // role 1 only
-        unsigned char *aux = smem + C::OFF_QAUX;
+        lds_u8 *aux = lds + C::OFF_QAUX;
         const int q0 = qb * TQ;
+        const uint32_t l16 = (uint32_t)lane * 16u;
         if (ridx == 0) {
-            __builtin_amdgcn_global_load_lds((const void *)(p.invq + q0 + lane * 4), (lds_ptr)(aux + C::QAUX_INVQ), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const void *)(p.thrp + q0 + lane * 4), (lds_ptr)(aux + C::QAUX_THRP), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.invq + q0) + l16), (lds_ptr)(aux + C::QAUX_INVQ), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.thrp + q0) + l16), (lds_ptr)(aux + C::QAUX_THRP), 16, 0, 0);
         } else if (ridx == 1) {
-            __builtin_amdgcn_global_load_lds((const void *)(p.thr64 + q0 + lane * 2), (lds_ptr)(aux + C::QAUX_THR64), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const void *)(p.thr64 + q0 + 128 + lane * 2), (lds_ptr)(aux + C::QAUX_THR64 + 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.thr64 + q0) + l16), (lds_ptr)(aux + C::QAUX_THR64), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.thr64 + q0 + 128) + l16), (lds_ptr)(aux + C::QAUX_THR64 + 1024), 16, 0, 0);
         } else if (ridx == 2 && filter) {
-            __builtin_amdgcn_global_load_lds((const void *)(p.qmask_pad + q0 + lane * 2), (lds_ptr)(aux + C::QAUX_QMASK), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const void *)(p.qmask_pad + q0 + 128 + lane * 2), (lds_ptr)(aux + C::QAUX_QMASK + 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.qmask_pad + q0) + l16), (lds_ptr)(aux + C::QAUX_QMASK), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.qmask_pad + q0 + 128) + l16), (lds_ptr)(aux + C::QAUX_QMASK + 1024), 16, 0, 0);
         }
     };
-    // role 0: load j (0..3) of the key piece at the cursor; key_next() moves the cursor on
-    auto key_issue = [&](int j) {
-        if (ld_left <= 0) return;
-        if (j == 0 && ld_c == 0 && ld_h == 0) issue_tile_aux();
-        const unsigned char *g = static_cast<const unsigned char *>(p.keys) + (size_t)ld_tile * TK * key_row_bytes + (size_t)ld_c * RB;
-        __builtin_amdgcn_global_load_lds((const void *)(g + (ld_h ? off[1][j] : off[0][j])),
-                                         (lds_ptr)(smem + ld_ring * PB + (ridx + 4 * j) * 1024), 16, 0, 0);
+    // role 0: load j (0..3) of the key piece at the cursor, half h of its chunk; key_next(h) moves the cursor on
+    auto key_issue = [&](int h, int j) {
+        __builtin_amdgcn_global_load_lds((const void *)(ld_src + off[h][j]), (lds_ptr)(ld_dst + j * 4096), 16, 0, 0);
     };
-    auto item_next = [&]() {
+    auto item_next = [&](bool more) {
         ld_c = 0;
         ld_par ^= 1;
         ld_tile += step_tile;
@@ -169,39 +190,34 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
             ld_qb -= nqb;
             ++ld_tile;
         }
-        if (ld_left > 0 && (role == 0 || nqb > 1)) ld_setup();
+        if (more && (role == 0 || nqb > 1)) ld_setup();
+        else if (role == 1) ld_src = static_cast<const unsigned char *>(p.queries);
     };
-    auto key_next = [&]() {
-        if (ld_left <= 0) return;
-        --ld_left;
+    auto key_next = [&](int h, bool more) {        // more: another piece follows in the stream
         ld_ring = ld_ring + 1 == C::NPA ? 0 : ld_ring + 1;
-        ld_h ^= 1;
-        if (ld_h == 0 && ++ld_c == NC) item_next();
+        ld_dst = ld_ring0 + ld_ring * PB;
+        if (h == 1) {
+            ld_src += RB;
+            if (++ld_c == NC) item_next(more);
+        }
     };
     // role 1: load j (0..7) of the query chunk at the cursor: piece j / 4, instruction j % 4
     auto qry_issue = [&](int j) {
-        if (ld_left <= 0) return;
-        const unsigned char *g = static_cast<const unsigned char *>(p.queries) + (size_t)ld_c * RB;
-        __builtin_amdgcn_global_load_lds((const void *)(g + off[j / 4][j % 4]),
-                                         (lds_ptr)(smem + C::OFF_B + (ld_ring + j / 4) * PB + (ridx + 4 * (j % 4)) * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const void *)(ld_src + off[j / 4][j % 4]), (lds_ptr)(ld_dst + (j / 4) * PB + (j % 4) * 4096), 16, 0, 0);
     };
-    auto qry_next = [&]() {
-        if (ld_left <= 0) return;
-        --ld_left;
+    auto qry_next = [&](bool more) {
         ld_ring ^= 2;
-        if (++ld_c == NC) item_next();
+        ld_dst = ld_ring0 + ld_ring * PB;
+        ld_src += RB;
+        if (++ld_c == NC) item_next(more);
     };
 
     // ---- fragment addresses -------------------------------------------------------------------------------
     // piece-local row = 64 * (wave's half of the piece) + 32 * block + lrow; logical 16-byte slot of k-step kk = 2 kk + half
+    // (kk << 5 only touches bits 5 and 6, a ring slot is a multiple of 16 KiB: the XOR can follow the addition)
     const int baseA = (wm * 64 + lrow) * RB | ((half ^ swizzle<8>(lrow)) << 4);
     const int baseB = C::OFF_B + (wn >> 1) * PB + (((wn & 1) * 64 + lrow) * RB | ((half ^ swizzle<8>(lrow)) << 4));
-    auto read_a = [&](int ring, int kk, int ib) {
-        return *reinterpret_cast<const u32x4 *>(smem + ring * PB + ((baseA ^ (kk << 5)) + ib * 32 * RB));
-    };
-    auto read_b = [&](int ring, int kk, int jb) {       // ring: slot of the chunk's first piece (0 or 2)
-        return *reinterpret_cast<const u32x4 *>(smem + ring * PB + ((baseB ^ (kk << 5)) + jb * 32 * RB));
-    };
+    auto read_f = [&](int addr, int kk, int blk) { return *(lds_u32x4 *)(lds + ((addr ^ (kk << 5)) + blk * 32 * RB)); };
 
     f32x16 acc[2][IB][JB];
 #pragma unroll
@@ -233,14 +249,15 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
 
     if (total > 0) {        // uniform over the workgroup
         // ---- prologue ---------------------------------------------------------------------------------------------
-        // keys: pieces 0..4; queries: chunks 0 and 1 (the rings are full then)
+        // keys: pieces 0..4; queries: chunks 0 and 1 (the rings are full then; every item has at least four chunks)
         ld_setup();
         if (role == 0) {
+            issue_tile_aux();
 #pragma unroll
             for (int s = 0; s < 5; ++s) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) key_issue(j);
-                key_next();
+                for (int j = 0; j < 4; ++j) key_issue(s & 1, j);
+                key_next(s & 1, true);
             }
             __builtin_amdgcn_s_waitcnt(waitcnt_vm(16));        // piece 0 (and the side data before it) has landed
         } else {
@@ -249,115 +266,132 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
             for (int s = 0; s < 2; ++s) {
 #pragma unroll
                 for (int j = 0; j < 8; ++j) qry_issue(j);
-                qry_next();
+                qry_next(true);
             }
             __builtin_amdgcn_s_waitcnt(waitcnt_vm(8));         // chunk 0 (and the side data before it) has landed
         }
         __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
         bare_barrier();
 
-        int tile = vb / nqb, qb = vb % nqb, par = 0, c = 0;
+        int tile = vb / nqb, qb = vb % nqb, par = 0;
         int ra = 0, rb = 0;                                    // ring slots: key piece of the phase, first query piece of the chunk
+        int f = 0;                                             // phase index
         u32x4 xa[IB], xb[JB], ya[IB], yb[JB];
 #pragma unroll
-        for (int ib = 0; ib < IB; ++ib) xa[ib] = read_a(0, 0, ib);
+        for (int ib = 0; ib < IB; ++ib) xa[ib] = read_f(baseA, 0, ib);
 #pragma unroll
-        for (int jb = 0; jb < JB; ++jb) xb[jb] = read_b(0, 0, jb);
+        for (int jb = 0; jb < JB; ++jb) xb[jb] = read_f(baseB, 0, jb);
 
 #define KBW_MFMA(RH, SA, SB, I, J)                                                                                                  \
     acc[RH][I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, SA[I]), __builtin_bit_cast(bf16x8, SB[J]),   \
                                                             acc[RH][I][J], 0, 0, 0);                                                \
     __builtin_amdgcn_sched_barrier(0)
-        // one k-step: four MFMAs on set (SA, SB) while set (DA, DB) is refilled from (ring slots RA_, RB_; k-step KK);
+        // one k-step: four MFMAs on set (SA, SB) while set (DA, DB) is refilled from the pieces at (AA, AB), k-step KK;
         // L0 .. L3: what this wave loads after each of the MFMAs
-#define KBW_KSTEP(RH, SA, SB, DA, DB, RA_, RB_, KK, L0, L1, L2, L3) \
-    KBW_MFMA(RH, SA, SB, 0, 0);                                     \
-    DA[0] = read_a(RA_, KK, 0);                                     \
-    DB[0] = read_b(RB_, KK, 0);                                     \
-    L0;                                                             \
-    __builtin_amdgcn_sched_barrier(0);                              \
-    KBW_MFMA(RH, SA, SB, 0, 1);                                     \
-    DB[1] = read_b(RB_, KK, 1);                                     \
-    DA[1] = read_a(RA_, KK, 1);                                     \
-    L1;                                                             \
-    __builtin_amdgcn_sched_barrier(0);                              \
-    KBW_MFMA(RH, SA, SB, 1, 0);                                     \
-    L2;                                                             \
-    __builtin_amdgcn_sched_barrier(0);                              \
-    KBW_MFMA(RH, SA, SB, 1, 1);                                     \
-    L3;                                                             \
+#define KBW_KSTEP(RH, SA, SB, DA, DB, AA, AB, KK, L0, L1, L2, L3) \
+    KBW_MFMA(RH, SA, SB, 0, 0);                                   \
+    DA[0] = read_f(AA, KK, 0);                                    \
+    DB[0] = read_f(AB, KK, 0);                                    \
+    L0;                                                           \
+    __builtin_amdgcn_sched_barrier(0);                            \
+    KBW_MFMA(RH, SA, SB, 0, 1);                                   \
+    DB[1] = read_f(AB, KK, 1);                                    \
+    DA[1] = read_f(AA, KK, 1);                                    \
+    L1;                                                           \
+    __builtin_amdgcn_sched_barrier(0);                            \
+    KBW_MFMA(RH, SA, SB, 1, 0);                                   \
+    L2;                                                           \
+    __builtin_amdgcn_sched_barrier(0);                            \
+    KBW_MFMA(RH, SA, SB, 1, 1);                                   \
+    L3;                                                           \
     __builtin_amdgcn_sched_barrier(0)
 #define KBW_NONE (void)0
 
-        int f = 0;                                             // phase index
-        // The wait before barrier f.  Key waves: piece f+1 has landed once at most the pieces f+2 .. f+4 are
-        // outstanding (fewer at the end of the stream).  Query waves: chunk g+1 is needed from barrier 2g+1 on;
-        // they issued nothing since the first half of the phase before, so they wait for everything.
-        auto wait_before_barrier = [&](int rh) {
-            if (role == 0) {
-                const int ahead = phases - f - 2;              // pieces past f+1 that exist
-                if (ahead >= 3) __builtin_amdgcn_s_waitcnt(waitcnt_vm(12));
-                else if (ahead == 2) __builtin_amdgcn_s_waitcnt(waitcnt_vm(8));
-                else if (ahead == 1) __builtin_amdgcn_s_waitcnt(waitcnt_vm(4));
-                else __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
-            } else if (rh == 1) {
-                __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+        // The chunks of one item, for a wave of kind ROLE (the two kinds differ only in what they load and wait for,
+        // and each gets its own copy of the loop so that none of it is decided per load).
+        // Wait before barrier f.  Key waves: piece f+1 has landed once at most the pieces f+2 .. f+4 are outstanding
+        // (fewer at the end of the stream).  Query waves: chunk g+1 is needed from barrier 2g+1 on; they issued
+        // nothing since the first half of the phase before, so they wait for everything.
+        auto item_chunks = [&](auto role_c, int g0) {
+            constexpr int ROLE = decltype(role_c)::value;
+            auto wait_before_barrier = [&](int rh) {
+                if (ROLE == 0) {
+                    const int ahead = phases - f - 2;          // pieces past f+1 that exist
+                    if (ahead >= 3) __builtin_amdgcn_s_waitcnt(waitcnt_vm(12));
+                    else if (ahead == 2) __builtin_amdgcn_s_waitcnt(waitcnt_vm(8));
+                    else if (ahead == 1) __builtin_amdgcn_s_waitcnt(waitcnt_vm(4));
+                    else __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+                } else if (rh == 1) {
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+                }
+                __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
+                __builtin_amdgcn_sched_barrier(0);
+                bare_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            for (int c = 0; c < NC; ++c) {
+                const int g = g0 + c;
+                // ======== phase 2g: key piece in slot ra, query chunk in slots rb, rb+1 ========
+                {
+                    const int ran = ra + 1 == C::NPA ? 0 : ra + 1;
+                    const int aa = baseA + ra * PB, ab = baseB + rb * PB, aan = baseA + ran * PB;
+                    // query waves: chunk g+1 into the slots that barrier 2g-1 retired
+                    const bool qgo = ROLE == 1 && g > 0 && g + 1 < total;
+                    // key waves: piece f+5 (second half of chunk g+2) into the slot that barrier f retires
+                    const bool kgo = ROLE == 0 && f + 5 < phases;
+                    __builtin_amdgcn_s_setprio(1);
+                    KBW_KSTEP(0, xa, xb, ya, yb, aa, ab, 1, if (qgo) qry_issue(0), if (qgo) qry_issue(1), if (qgo) qry_issue(2), if (qgo) qry_issue(3));
+                    KBW_KSTEP(0, ya, yb, xa, xb, aa, ab, 2, if (qgo) qry_issue(4), if (qgo) qry_issue(5), if (qgo) qry_issue(6),
+                              if (qgo) { qry_issue(7); qry_next(g + 2 < total); });
+                    KBW_KSTEP(0, xa, xb, ya, yb, aa, ab, 3, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
+                    __builtin_amdgcn_s_setprio(0);
+                    wait_before_barrier(0);
+                    // a new query block's side data: every epilogue of the previous item ended before this barrier
+                    if (ROLE == 1 && nqb > 1 && c == 0 && g > 0) issue_query_aux(qb);
+                    __builtin_amdgcn_s_setprio(1);
+                    KBW_KSTEP(0, ya, yb, xa, xb, aan, ab, 0, if (kgo) key_issue(1, 0), if (kgo) key_issue(1, 1), if (kgo) key_issue(1, 2),
+                              if (kgo) { key_issue(1, 3); key_next(1, f + 6 < phases); });
+                    __builtin_amdgcn_s_setprio(0);
+                    ra = ran;
+                    ++f;
+                }
+                // ======== phase 2g+1 ========
+                {
+                    const int ran = ra + 1 == C::NPA ? 0 : ra + 1, rbn = rb ^ 2;
+                    const bool more = g + 1 < total;
+                    const int aa = baseA + ra * PB, ab = baseB + rb * PB;
+                    // past the last chunk the refill of X reads the current slots again (valid memory, values unused)
+                    const int aan = baseA + (more ? ran : ra) * PB, abn = baseB + (more ? rbn : rb) * PB;
+                    // key waves: piece f+5 (first half of chunk g+3) and, before it, the side data of a new tile
+                    const bool kgo = ROLE == 0 && f + 5 < phases;
+                    __builtin_amdgcn_s_setprio(1);
+                    KBW_KSTEP(1, xa, xb, ya, yb, aa, ab, 1, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
+                    KBW_KSTEP(1, ya, yb, xa, xb, aa, ab, 2, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
+                    KBW_KSTEP(1, xa, xb, ya, yb, aa, ab, 3, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
+                    __builtin_amdgcn_s_setprio(0);
+                    wait_before_barrier(1);
+                    if (kgo && ld_c == 0) issue_tile_aux();
+                    __builtin_amdgcn_s_setprio(1);
+                    KBW_KSTEP(1, ya, yb, xa, xb, aan, abn, 0, if (kgo) key_issue(0, 0), if (kgo) key_issue(0, 1), if (kgo) key_issue(0, 2),
+                              if (kgo) { key_issue(0, 3); key_next(0, true); });
+                    __builtin_amdgcn_s_setprio(0);
+                    ra = ran;
+                    rb = rbn;
+                    ++f;
+                }
             }
-            __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
-            __builtin_amdgcn_sched_barrier(0);
-            bare_barrier();
-            __builtin_amdgcn_sched_barrier(0);
         };
 
-        for (int g = 0; g < total; ++g) {
-            // ======== phase 2g: key piece in slot ra, query chunk in slots rb, rb+1 ========
-            {
-                const int ran = ra + 1 == C::NPA ? 0 : ra + 1;
-                const bool qload = role == 1 && g > 0;         // query waves: chunk g+1 into the slots barrier 2g-1 retired
-                __builtin_amdgcn_s_setprio(1);
-                KBW_KSTEP(0, xa, xb, ya, yb, ra, rb, 1, if (qload) qry_issue(0), if (qload) qry_issue(1), if (qload) qry_issue(2), if (qload) qry_issue(3));
-                KBW_KSTEP(0, ya, yb, xa, xb, ra, rb, 2, if (qload) qry_issue(4), if (qload) qry_issue(5), if (qload) qry_issue(6), if (qload) { qry_issue(7); qry_next(); });
-                KBW_KSTEP(0, xa, xb, ya, yb, ra, rb, 3, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
-                __builtin_amdgcn_s_setprio(0);
-                wait_before_barrier(0);
-                // a new query block's side data: every epilogue of the previous item ended before this barrier
-                if (role == 1 && nqb > 1 && c == 0 && g > 0) issue_query_aux(qb);
-                __builtin_amdgcn_s_setprio(1);
-                KBW_KSTEP(0, ya, yb, xa, xb, ran, rb, 0, if (role == 0) key_issue(0), if (role == 0) key_issue(1), if (role == 0) key_issue(2),
-                          if (role == 0) { key_issue(3); key_next(); });
-                __builtin_amdgcn_s_setprio(0);
-                ra = ran;
-                ++f;
-            }
-            // ======== phase 2g+1 ========
-            {
-                const int ran = ra + 1 == C::NPA ? 0 : ra + 1, rbn = rb ^ 2;
-                const bool more = g + 1 < total;
-                __builtin_amdgcn_s_setprio(1);
-                KBW_KSTEP(1, xa, xb, ya, yb, ra, rb, 1, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
-                KBW_KSTEP(1, ya, yb, xa, xb, ra, rb, 2, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
-                KBW_KSTEP(1, xa, xb, ya, yb, ra, rb, 3, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
-                __builtin_amdgcn_s_setprio(0);
-                wait_before_barrier(1);
-                __builtin_amdgcn_s_setprio(1);
-                // past the last chunk the refill of X reads the current slots again (valid memory, values unused)
-                KBW_KSTEP(1, ya, yb, xa, xb, (more ? ran : ra), (more ? rbn : rb), 0, if (role == 0) key_issue(0), if (role == 0) key_issue(1),
-                          if (role == 0) key_issue(2), if (role == 0) { key_issue(3); key_next(); });
-                __builtin_amdgcn_s_setprio(0);
-                ra = ran;
-                rb = rbn;
-                ++f;
-            }
-            if (++c == NC) {
-                epilogue(tile, qb, par);
-                c = 0;
-                par ^= 1;
-                tile += step_tile;
-                qb += step_qb;
-                if (qb >= nqb) {
-                    qb -= nqb;
-                    ++tile;
-                }
+        for (int it = 0; it < my_items; ++it) {
+            if (role == 0) item_chunks(std::integral_constant<int, 0>{}, it * NC);
+            else item_chunks(std::integral_constant<int, 1>{}, it * NC);
+            epilogue(tile, qb, par);
+            par ^= 1;
+            tile += step_tile;
+            qb += step_qb;
+            if (qb >= nqb) {
+                qb -= nqb;
+                ++tile;
             }
         }
 #undef KBW_KSTEP
