@@ -181,7 +181,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
     auto key_issue = [&](int h, int j) {
         __builtin_amdgcn_global_load_lds((const void *)(ld_src + off[h][j]), (lds_ptr)(ld_dst + j * 4096), 16, 0, 0);
     };
-    auto item_next = [&](bool more) {
+    auto item_next = [&]() {
         ld_c = 0;
         ld_par ^= 1;
         ld_tile += step_tile;
@@ -190,15 +190,17 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
             ld_qb -= nqb;
             ++ld_tile;
         }
-        if (more && (role == 0 || nqb > 1)) ld_setup();
-        else if (role == 1) ld_src = static_cast<const unsigned char *>(p.queries);
+        if (role == 0 || nqb > 1) ld_setup();
+        else ld_src = static_cast<const unsigned char *>(p.queries);
     };
-    auto key_next = [&](int h, bool more) {        // more: another piece follows in the stream
+    // more: another piece follows in the stream.  Past its end the cursor stays where it is: the loop goes on issuing
+    // loads (of the last piece again) into ring slots that nobody reads any more, so that nothing in it is conditional.
+    auto key_next = [&](int h, bool more) {
         ld_ring = ld_ring + 1 == C::NPA ? 0 : ld_ring + 1;
         ld_dst = ld_ring0 + ld_ring * PB;
-        if (h == 1) {
+        if (more && h == 1) {
             ld_src += RB;
-            if (++ld_c == NC) item_next(more);
+            if (++ld_c == NC) item_next();
         }
     };
     // role 1: load j (0..7) of the query chunk at the cursor: piece j / 4, instruction j % 4
@@ -208,8 +210,10 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
     auto qry_next = [&](bool more) {
         ld_ring ^= 2;
         ld_dst = ld_ring0 + ld_ring * PB;
-        ld_src += RB;
-        if (++ld_c == NC) item_next(more);
+        if (more) {
+            ld_src += RB;
+            if (++ld_c == NC) item_next();
+        }
     };
 
     // ---- fragment addresses -------------------------------------------------------------------------------
@@ -249,7 +253,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
 
     if (total > 0) {        // uniform over the workgroup
         // ---- prologue ---------------------------------------------------------------------------------------------
-        // keys: pieces 0..4; queries: chunks 0 and 1 (the rings are full then; every item has at least four chunks)
+        // keys: pieces 0..4 (every item has at least four chunks); queries: chunk 0
         ld_setup();
         if (role == 0) {
             issue_tile_aux();
@@ -263,12 +267,9 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
         } else {
             issue_query_aux(vb % nqb);
 #pragma unroll
-            for (int s = 0; s < 2; ++s) {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) qry_issue(j);
-                qry_next(true);
-            }
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm(8));         // chunk 0 (and the side data before it) has landed
+            for (int j = 0; j < 8; ++j) qry_issue(j);
+            qry_next(true);
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));         // chunk 0 (and the side data before it) has landed
         }
         __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
         bare_barrier();
@@ -309,21 +310,14 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
 
         // The chunks of one item, for a wave of kind ROLE (the two kinds differ only in what they load and wait for,
         // and each gets its own copy of the loop so that none of it is decided per load).
-        // Wait before barrier f.  Key waves: piece f+1 has landed once at most the pieces f+2 .. f+4 are outstanding
-        // (fewer at the end of the stream).  Query waves: chunk g+1 is needed from barrier 2g+1 on; they issued
-        // nothing since the first half of the phase before, so they wait for everything.
+        // Wait before barrier f.  Key waves: piece f+1 has landed once at most the pieces f+2 .. f+4 are outstanding.
+        // Query waves: chunk g+1 is needed from barrier 2g+1 on; they issued nothing since the first half of the phase
+        // before, so they wait for everything.
         auto item_chunks = [&](auto role_c, int g0) {
             constexpr int ROLE = decltype(role_c)::value;
             auto wait_before_barrier = [&](int rh) {
-                if (ROLE == 0) {
-                    const int ahead = phases - f - 2;          // pieces past f+1 that exist
-                    if (ahead >= 3) __builtin_amdgcn_s_waitcnt(waitcnt_vm(12));
-                    else if (ahead == 2) __builtin_amdgcn_s_waitcnt(waitcnt_vm(8));
-                    else if (ahead == 1) __builtin_amdgcn_s_waitcnt(waitcnt_vm(4));
-                    else __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
-                } else if (rh == 1) {
-                    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
-                }
+                if (ROLE == 0) __builtin_amdgcn_s_waitcnt(waitcnt_vm(12));
+                else if (rh == 1) __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
                 __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
                 __builtin_amdgcn_sched_barrier(0);
                 bare_barrier();
@@ -335,22 +329,21 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
                 {
                     const int ran = ra + 1 == C::NPA ? 0 : ra + 1;
                     const int aa = baseA + ra * PB, ab = baseB + rb * PB, aan = baseA + ran * PB;
-                    // query waves: chunk g+1 into the slots that barrier 2g-1 retired
-                    const bool qgo = ROLE == 1 && g > 0 && g + 1 < total;
-                    // key waves: piece f+5 (second half of chunk g+2) into the slot that barrier f retires
-                    const bool kgo = ROLE == 0 && f + 5 < phases;
+                    // query waves: chunk g+1 into the slots that barrier 2g-1 retired; key waves: piece f+5 (second half
+                    // of chunk g+2) into the slot that barrier f retires
                     __builtin_amdgcn_s_setprio(1);
-                    KBW_KSTEP(0, xa, xb, ya, yb, aa, ab, 1, if (qgo) qry_issue(0), if (qgo) qry_issue(1), if (qgo) qry_issue(2), if (qgo) qry_issue(3));
-                    KBW_KSTEP(0, ya, yb, xa, xb, aa, ab, 2, if (qgo) qry_issue(4), if (qgo) qry_issue(5), if (qgo) qry_issue(6),
-                              if (qgo) { qry_issue(7); qry_next(g + 2 < total); });
+                    KBW_KSTEP(0, xa, xb, ya, yb, aa, ab, 1, if (ROLE == 1) qry_issue(0), if (ROLE == 1) qry_issue(1), if (ROLE == 1) qry_issue(2),
+                              if (ROLE == 1) qry_issue(3));
+                    KBW_KSTEP(0, ya, yb, xa, xb, aa, ab, 2, if (ROLE == 1) qry_issue(4), if (ROLE == 1) qry_issue(5), if (ROLE == 1) qry_issue(6),
+                              if (ROLE == 1) { qry_issue(7); qry_next(g + 2 < total); });
                     KBW_KSTEP(0, xa, xb, ya, yb, aa, ab, 3, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
                     __builtin_amdgcn_s_setprio(0);
                     wait_before_barrier(0);
                     // a new query block's side data: every epilogue of the previous item ended before this barrier
                     if (ROLE == 1 && nqb > 1 && c == 0 && g > 0) issue_query_aux(qb);
                     __builtin_amdgcn_s_setprio(1);
-                    KBW_KSTEP(0, ya, yb, xa, xb, aan, ab, 0, if (kgo) key_issue(1, 0), if (kgo) key_issue(1, 1), if (kgo) key_issue(1, 2),
-                              if (kgo) { key_issue(1, 3); key_next(1, f + 6 < phases); });
+                    KBW_KSTEP(0, ya, yb, xa, xb, aan, ab, 0, if (ROLE == 0) key_issue(1, 0), if (ROLE == 0) key_issue(1, 1), if (ROLE == 0) key_issue(1, 2),
+                              if (ROLE == 0) { key_issue(1, 3); key_next(1, f + 6 < phases); });
                     __builtin_amdgcn_s_setprio(0);
                     ra = ran;
                     ++f;
@@ -363,17 +356,16 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
                     // past the last chunk the refill of X reads the current slots again (valid memory, values unused)
                     const int aan = baseA + (more ? ran : ra) * PB, abn = baseB + (more ? rbn : rb) * PB;
                     // key waves: piece f+5 (first half of chunk g+3) and, before it, the side data of a new tile
-                    const bool kgo = ROLE == 0 && f + 5 < phases;
                     __builtin_amdgcn_s_setprio(1);
                     KBW_KSTEP(1, xa, xb, ya, yb, aa, ab, 1, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
                     KBW_KSTEP(1, ya, yb, xa, xb, aa, ab, 2, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
                     KBW_KSTEP(1, xa, xb, ya, yb, aa, ab, 3, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
                     __builtin_amdgcn_s_setprio(0);
                     wait_before_barrier(1);
-                    if (kgo && ld_c == 0) issue_tile_aux();
+                    if (ROLE == 0 && ld_c == 0 && f + 5 < phases) issue_tile_aux();
                     __builtin_amdgcn_s_setprio(1);
-                    KBW_KSTEP(1, ya, yb, xa, xb, aan, abn, 0, if (kgo) key_issue(0, 0), if (kgo) key_issue(0, 1), if (kgo) key_issue(0, 2),
-                              if (kgo) { key_issue(0, 3); key_next(0, true); });
+                    KBW_KSTEP(1, ya, yb, xa, xb, aan, abn, 0, if (ROLE == 0) key_issue(0, 0), if (ROLE == 0) key_issue(0, 1), if (ROLE == 0) key_issue(0, 2),
+                              if (ROLE == 0) { key_issue(0, 3); key_next(0, true); });
                     __builtin_amdgcn_s_setprio(0);
                     ra = ran;
                     rb = rbn;
@@ -397,6 +389,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
 #undef KBW_KSTEP
 #undef KBW_NONE
 #undef KBW_MFMA
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));             // the loads past the end of the stream
     }
 
     if (lane == 0) {
