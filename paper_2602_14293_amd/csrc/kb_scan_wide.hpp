@@ -277,34 +277,52 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
         int tile = vb / nqb, qb = vb % nqb, par = 0;
         int ra = 0, rb = 0;                                    // ring slots: key piece of the phase, first query piece of the chunk
         int f = 0;                                             // phase index
-        u32x4 xa[IB], xb[JB], ya[IB], yb[JB];
+        // key fragments of one k-step in two sets (one in use, one being refilled); the query fragments of all four
+        // k-steps of the chunk stay in registers for its second phase
+        u32x4 xa[IB], ya[IB], fb[4][JB];
 #pragma unroll
         for (int ib = 0; ib < IB; ++ib) xa[ib] = read_f(baseA, 0, ib);
 #pragma unroll
-        for (int jb = 0; jb < JB; ++jb) xb[jb] = read_f(baseB, 0, jb);
+        for (int jb = 0; jb < JB; ++jb) fb[0][jb] = read_f(baseB, 0, jb);
 
 #define KBW_MFMA(RH, SA, SB, I, J)                                                                                                  \
     acc[RH][I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, SA[I]), __builtin_bit_cast(bf16x8, SB[J]),   \
                                                             acc[RH][I][J], 0, 0, 0);                                                \
     __builtin_amdgcn_sched_barrier(0)
-        // one k-step: four MFMAs on set (SA, SB) while set (DA, DB) is refilled from the pieces at (AA, AB), k-step KK;
-        // L0 .. L3: what this wave loads after each of the MFMAs
-#define KBW_KSTEP(RH, SA, SB, DA, DB, AA, AB, KK, L0, L1, L2, L3) \
-    KBW_MFMA(RH, SA, SB, 0, 0);                                   \
-    DA[0] = read_f(AA, KK, 0);                                    \
-    DB[0] = read_f(AB, KK, 0);                                    \
-    L0;                                                           \
-    __builtin_amdgcn_sched_barrier(0);                            \
-    KBW_MFMA(RH, SA, SB, 0, 1);                                   \
-    DB[1] = read_f(AB, KK, 1);                                    \
-    DA[1] = read_f(AA, KK, 1);                                    \
-    L1;                                                           \
-    __builtin_amdgcn_sched_barrier(0);                            \
-    KBW_MFMA(RH, SA, SB, 1, 0);                                   \
-    L2;                                                           \
-    __builtin_amdgcn_sched_barrier(0);                            \
-    KBW_MFMA(RH, SA, SB, 1, 1);                                   \
-    L3;                                                           \
+        // one k-step: four MFMAs on the key fragments SA and the query fragments fb[KU]; meanwhile the key fragments DA
+        // are refilled from the piece at AA, k-step KR, and (KBW_KSTEP_AB) the query fragments fb[KR] from the chunk at
+        // AB; L0 .. L3: what this wave loads after each of the MFMAs
+#define KBW_KSTEP_AB(RH, SA, KU, DA, AA, AB, KR, L0, L1, L2, L3) \
+    KBW_MFMA(RH, SA, fb[KU], 0, 0);                              \
+    DA[0] = read_f(AA, KR, 0);                                   \
+    fb[KR][0] = read_f(AB, KR, 0);                               \
+    L0;                                                          \
+    __builtin_amdgcn_sched_barrier(0);                           \
+    KBW_MFMA(RH, SA, fb[KU], 0, 1);                              \
+    fb[KR][1] = read_f(AB, KR, 1);                               \
+    DA[1] = read_f(AA, KR, 1);                                   \
+    L1;                                                          \
+    __builtin_amdgcn_sched_barrier(0);                           \
+    KBW_MFMA(RH, SA, fb[KU], 1, 0);                              \
+    L2;                                                          \
+    __builtin_amdgcn_sched_barrier(0);                           \
+    KBW_MFMA(RH, SA, fb[KU], 1, 1);                              \
+    L3;                                                          \
+    __builtin_amdgcn_sched_barrier(0)
+#define KBW_KSTEP_A(RH, SA, KU, DA, AA, KR, L0, L1, L2, L3) \
+    KBW_MFMA(RH, SA, fb[KU], 0, 0);                         \
+    DA[0] = read_f(AA, KR, 0);                              \
+    L0;                                                     \
+    __builtin_amdgcn_sched_barrier(0);                      \
+    KBW_MFMA(RH, SA, fb[KU], 0, 1);                         \
+    DA[1] = read_f(AA, KR, 1);                              \
+    L1;                                                     \
+    __builtin_amdgcn_sched_barrier(0);                      \
+    KBW_MFMA(RH, SA, fb[KU], 1, 0);                         \
+    L2;                                                     \
+    __builtin_amdgcn_sched_barrier(0);                      \
+    KBW_MFMA(RH, SA, fb[KU], 1, 1);                         \
+    L3;                                                     \
     __builtin_amdgcn_sched_barrier(0)
 #define KBW_NONE (void)0
 
@@ -332,18 +350,18 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
                     // query waves: chunk g+1 into the slots that barrier 2g-1 retired; key waves: piece f+5 (second half
                     // of chunk g+2) into the slot that barrier f retires
                     __builtin_amdgcn_s_setprio(1);
-                    KBW_KSTEP(0, xa, xb, ya, yb, aa, ab, 1, if (ROLE == 1) qry_issue(0), if (ROLE == 1) qry_issue(1), if (ROLE == 1) qry_issue(2),
-                              if (ROLE == 1) qry_issue(3));
-                    KBW_KSTEP(0, ya, yb, xa, xb, aa, ab, 2, if (ROLE == 1) qry_issue(4), if (ROLE == 1) qry_issue(5), if (ROLE == 1) qry_issue(6),
-                              if (ROLE == 1) { qry_issue(7); qry_next(g + 2 < total); });
-                    KBW_KSTEP(0, xa, xb, ya, yb, aa, ab, 3, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
+                    KBW_KSTEP_AB(0, xa, 0, ya, aa, ab, 1, if (ROLE == 1) qry_issue(0), if (ROLE == 1) qry_issue(1), if (ROLE == 1) qry_issue(2),
+                                 if (ROLE == 1) qry_issue(3));
+                    KBW_KSTEP_AB(0, ya, 1, xa, aa, ab, 2, if (ROLE == 1) qry_issue(4), if (ROLE == 1) qry_issue(5), if (ROLE == 1) qry_issue(6),
+                                 if (ROLE == 1) { qry_issue(7); qry_next(g + 2 < total); });
+                    KBW_KSTEP_AB(0, xa, 2, ya, aa, ab, 3, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
                     __builtin_amdgcn_s_setprio(0);
                     wait_before_barrier(0);
                     // a new query block's side data: every epilogue of the previous item ended before this barrier
                     if (ROLE == 1 && nqb > 1 && c == 0 && g > 0) issue_query_aux(qb);
                     __builtin_amdgcn_s_setprio(1);
-                    KBW_KSTEP(0, ya, yb, xa, xb, aan, ab, 0, if (ROLE == 0) key_issue(1, 0), if (ROLE == 0) key_issue(1, 1), if (ROLE == 0) key_issue(1, 2),
-                              if (ROLE == 0) { key_issue(1, 3); key_next(1, f + 6 < phases); });
+                    KBW_KSTEP_A(0, ya, 3, xa, aan, 0, if (ROLE == 0) key_issue(1, 0), if (ROLE == 0) key_issue(1, 1), if (ROLE == 0) key_issue(1, 2),
+                                if (ROLE == 0) { key_issue(1, 3); key_next(1, f + 6 < phases); });
                     __builtin_amdgcn_s_setprio(0);
                     ra = ran;
                     ++f;
@@ -352,20 +370,20 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
                 {
                     const int ran = ra + 1 == C::NPA ? 0 : ra + 1, rbn = rb ^ 2;
                     const bool more = g + 1 < total;
-                    const int aa = baseA + ra * PB, ab = baseB + rb * PB;
+                    const int aa = baseA + ra * PB;
                     // past the last chunk the refill of X reads the current slots again (valid memory, values unused)
                     const int aan = baseA + (more ? ran : ra) * PB, abn = baseB + (more ? rbn : rb) * PB;
                     // key waves: piece f+5 (first half of chunk g+3) and, before it, the side data of a new tile
                     __builtin_amdgcn_s_setprio(1);
-                    KBW_KSTEP(1, xa, xb, ya, yb, aa, ab, 1, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
-                    KBW_KSTEP(1, ya, yb, xa, xb, aa, ab, 2, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
-                    KBW_KSTEP(1, xa, xb, ya, yb, aa, ab, 3, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
+                    KBW_KSTEP_A(1, xa, 0, ya, aa, 1, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
+                    KBW_KSTEP_A(1, ya, 1, xa, aa, 2, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
+                    KBW_KSTEP_A(1, xa, 2, ya, aa, 3, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
                     __builtin_amdgcn_s_setprio(0);
                     wait_before_barrier(1);
                     if (ROLE == 0 && ld_c == 0 && f + 5 < phases) issue_tile_aux();
                     __builtin_amdgcn_s_setprio(1);
-                    KBW_KSTEP(1, ya, yb, xa, xb, aan, abn, 0, if (ROLE == 0) key_issue(0, 0), if (ROLE == 0) key_issue(0, 1), if (ROLE == 0) key_issue(0, 2),
-                              if (ROLE == 0) { key_issue(0, 3); key_next(0, true); });
+                    KBW_KSTEP_AB(1, ya, 3, xa, aan, abn, 0, if (ROLE == 0) key_issue(0, 0), if (ROLE == 0) key_issue(0, 1), if (ROLE == 0) key_issue(0, 2),
+                                 if (ROLE == 0) { key_issue(0, 3); key_next(0, true); });
                     __builtin_amdgcn_s_setprio(0);
                     ra = ran;
                     rb = rbn;
@@ -386,7 +404,8 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
                 ++tile;
             }
         }
-#undef KBW_KSTEP
+#undef KBW_KSTEP_AB
+#undef KBW_KSTEP_A
 #undef KBW_NONE
 #undef KBW_MFMA
         __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));             // the loads past the end of the stream
