@@ -91,6 +91,10 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
     static_assert(IB == 2 && (JB == 4 || JB == 2), "the interleaving below is written out for 2 x 4 and 2 x 2 blocks");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     typedef __attribute__((address_space(3))) void *lds_ptr;
+    // load destinations are kept as 32-bit pointers of the LDS address space: a generic pointer would be converted (with
+    // its null check) at every load
+    typedef __attribute__((address_space(3))) unsigned char lds_u8;
+    lds_u8 *const lds = (lds_u8 *)smem;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -122,7 +126,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
     const uint32_t ld_piece = (uint32_t)(((ridx * 64 + lane) % ppr) ^ (role && C::PPRB == 8 ? swizzle<8>(ld_row) : swizzle<4>(ld_row))) * 16;
     const uint32_t row_bytes = role ? qry_row_bytes : key_row_bytes, chunk_bytes = role ? RBB : RBA;
     const unsigned char *src_base = role ? static_cast<const unsigned char *>(p.queries) : static_cast<const unsigned char *>(p.keys);
-    unsigned char *ring = smem + (role ? C::OFF_B : 0) + ridx * 1024;
+    lds_u8 *ring = lds + (role ? C::OFF_B : 0) + ridx * 1024;
     int ld_pos = 0;                                         // chunks issued so far
     int ld_tile = vb / nqb, ld_qb = vb % nqb;
     int ld_c = 0, ld_stage = 0, ld_par = 0;
@@ -143,7 +147,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
     };
     // side data of a key tile: 4-byte loads with clamped rows from the caller's arrays
     auto issue_tile_aux = [&]() {
-        unsigned char *aux = smem + C::OFF_AUX + ld_par * C::AUX_BYTES;
+        lds_u8 *aux = lds + C::OFF_AUX + ld_par * C::AUX_BYTES;
         const int64_t row0 = ld_tile * tstride * TK;
         if (wave < 4) {
             int64_t r = row0 + wave * 64 + lane;
@@ -162,7 +166,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
     };
     // side data of a query block: 16-byte loads from the library's padded per-query arrays, one array per wave
     auto issue_query_aux = [&](int qb) {
-        unsigned char *aux = smem + C::OFF_QAUX;
+        lds_u8 *aux = lds + C::OFF_QAUX;
         const int q0 = qb * TQ;
         constexpr int L4 = TQ / 4, W8 = TQ * 8 / 1024;          // lanes that cover a float array; waves that cover a 64-bit array
         if (wave == 0 && lane < L4)
@@ -182,7 +186,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
         if (!last_full) return;
         if (ld_c == 0) issue_tile_aux();
         const unsigned char *g = src_base + ld_base + (size_t)ld_c * chunk_bytes;
-        unsigned char *dst = ring + ld_stage * (role ? C::B_BYTES : C::A_BYTES);
+        lds_u8 *dst = ring + ld_stage * (role ? C::B_BYTES : C::A_BYTES);
 #pragma unroll
         for (int j = 0; j < LC; ++j)
             if (j < LCr) __builtin_amdgcn_global_load_lds((const void *)(g + off[j]), (lds_ptr)(dst + j * 4096), 16, 0, 0);
@@ -202,7 +206,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
     };
     // The same round in three steps, for the mode that puts the loads between the MFMAs.
     const unsigned char *il_src = nullptr;
-    unsigned char *il_dst = nullptr;
+    lds_u8 *il_dst = ring;
     auto issue_prepare = [&]() {
         last_full = ld_pos < total;
         if (!last_full) return;
