@@ -57,9 +57,9 @@ bool scan_config_info(int key_dtype, int config, ConfigInfo *out)
     KB_SCAN_SP_CONFIGS_FP8(XS)
     KB_SCAN_SP_CONFIGS_FP8_Q8(XS)
 #undef XS
-#define XW(ID, KT)                                                            \
+#define XW(ID, KT, TQ)                                                        \
     if (key_dtype == KT && config == ID) {                                    \
-        *out = ConfigInfo{256, 256, 512, 8, 1, 512, 4};                       \
+        *out = ConfigInfo{256, TQ, 512, 8, 1, 512, 4};                        \
         return true;                                                          \
     }
     KB_SCAN_WIDE_CONFIGS_BF16(XW)
@@ -70,6 +70,7 @@ bool scan_config_info(int key_dtype, int config, ConfigInfo *out)
 int scan_config_for(int key_dtype, int Q, int d)
 {
     if (key_dtype == KB_BF16 && Q > 128 && d * 2 >= 512) return 18;
+    if (key_dtype == KB_BF16 && Q > 32 && d * 2 >= 512) return 19;
     if (key_dtype == KB_BF16 && Q > 128 && d * 2 >= 384) return 17;
     if (key_dtype == KB_FP8_E4M3 && Q > 128 && d >= 256) return 4;
     return Q <= 32 ? 1 : Q <= 128 ? 2 : 3;
@@ -158,7 +159,7 @@ bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, bool draw, bool q8,
     ConfigInfo sci = ci;
     p.sample_config = p.config;
     if (ci.family == 4) {       // main pass only: the sampling pass takes the interleaved software-pipelined kernel
-        p.sample_config = KB_WIDE_SAMPLE_CONFIG;
+        p.sample_config = KB_WIDE_SAMPLE_CONFIG(ci.tq);
         if (!scan_config_info(h->dtype, p.sample_config, &sci) || sci.tq != ci.tq || row_bytes < (size_t)sci.min_row_bytes) return false;
     }
     p.sample_family = sci.family;

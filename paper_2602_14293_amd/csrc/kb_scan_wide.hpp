@@ -10,8 +10,8 @@
 //
 // The price is LDS: a d-chunk is now 64 elements, 32 KiB of keys + 32 KiB of queries, and a key piece issued
 // now lands about two chunk times later (HBM under load).  So the chunk is worked through in two PHASES, one
-// per PIECE of keys (16 KiB: 128 rows x 128 bytes), and the ring is kept in pieces: five of keys (one in use,
-// four in flight) and four of queries (one chunk in use, the next one landing).  In phase f = 2 g + rh a wave
+// per PIECE of keys (16 KiB: 128 rows x 128 bytes), and the ring is kept in pieces: with 256-query blocks five of
+// keys (one in use, four in flight) and four of queries (one chunk in use, the next one landing).  In phase f = 2 g + rh a wave
 // (wm, wn) multiplies rows 128 rh + 64 wm + [0, 64) of the tile with queries 64 wn + [0, 64): sixteen MFMAs in
 // four k-steps, fragments in two register sets X and Y (while the MFMAs of one k-step run on one set, the other
 // is refilled), one barrier per phase:
@@ -21,11 +21,14 @@
 //   (publishes those, retires key piece f and, rh = 1, query chunk g);
 //   k-step 3 on Y, X <- (f+1,0).
 //
-// Waves 0-3 load keys: piece f+5 into the slot of piece f, one instruction after each MFMA of the k-step that
+// Waves 0-3 load keys: piece f+5 (f + the ring depth) into the slot of piece f, one instruction after each MFMA of the k-step that
 // follows barrier f, so that it has four phases to land.  Waves 4-7 load queries: chunk g+2 into the slots of
 // chunk g, one instruction after each MFMA of the first two k-steps of phase 2g+2.  The two kinds keep separate
 // load counters, so the wait for a query chunk issued a phase ago does not drain the key pieces issued up to
 // four phases ago.
+//
+// With 128-query blocks (the second configuration) a query chunk is one piece, the ring holds seven key pieces and
+// two query pieces (six phases for a key piece to land), and a wave multiplies its 64 rows with 32 queries.
 //
 // Accumulation order over d, lane-to-element mapping and epilogue are those of the other scan kernels, so the
 // scores are bit-identical to theirs.
@@ -44,14 +47,15 @@ __device__ inline const unsigned char *uniform_address(const void *ptr)
     return reinterpret_cast<const unsigned char *>(((uint64_t)hi << 32) | lo);
 }
 
-template <int KT_> struct WideCfg {
+template <int KT_, int TQ_> struct WideCfg {
     static constexpr int KT = KT_;
-    static constexpr int TK = 256, TQ = 256, THREADS = 512, NW = 8;
+    static constexpr int TK = 256, TQ = TQ_, THREADS = 512, NW = 8;
     static constexpr int KEY_BYTES = KeyTraits<KT>::KEY_BYTES, QRY_BYTES = KeyTraits<KT>::QRY_BYTES;
     static constexpr int RB = 128;                                   // bytes of a key / query row per d-chunk
     static constexpr int PIECE_ROWS = 128, PIECE_BYTES = PIECE_ROWS * RB;
-    static constexpr int NPA = 5, NPB = 4;                           // ring depth in pieces: keys, queries
-    static constexpr int IB = 2, JB = 2;                             // 32-row blocks of a wave in one phase
+    static constexpr int NB = TQ / PIECE_ROWS;                       // pieces of a query chunk
+    static constexpr int NPB = 2 * NB, NPA = 9 - NPB;                // ring depth in pieces: queries (two chunks), keys (the rest)
+    static constexpr int IB = 2, JB = TQ / 128;                      // 32-row blocks of a wave in one phase: keys, queries
     static constexpr int OFF_B = NPA * PIECE_BYTES;
     static constexpr int OFF_AUX = OFF_B + NPB * PIECE_BYTES;
     // side data of a key tile, two copies (item parity)
@@ -68,6 +72,8 @@ template <int KT_> struct WideCfg {
     static constexpr int SMEM_BYTES = OFF_QAUX + QAUX_BYTES;
     static constexpr int MIN_ROW_BYTES = 4 * RB;             // the key stream runs five pieces ahead of the MFMAs
     static_assert(KT == KB_BF16 && KEY_BYTES == QRY_BYTES, "written for bf16 keys and queries");
+    static_assert(TQ == 256 || TQ == 128, "query blocks of 256 or 128");
+    static_assert(NPA % 2 == 1, "the parity of the piece a phase issues is fixed in the code");
     static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget");
 };
 
@@ -167,14 +173,18 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
         const int q0 = qb * TQ;
         const uint32_t l16 = (uint32_t)lane * 16u;
         if (ridx == 0) {
-            __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.invq + q0) + l16), (lds_ptr)(aux + C::QAUX_INVQ), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.thrp + q0) + l16), (lds_ptr)(aux + C::QAUX_THRP), 16, 0, 0);
+            if (lane < TQ / 4) {        // TQ floats
+                __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.invq + q0) + l16), (lds_ptr)(aux + C::QAUX_INVQ), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.thrp + q0) + l16), (lds_ptr)(aux + C::QAUX_THRP), 16, 0, 0);
+            }
         } else if (ridx == 1) {
             __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.thr64 + q0) + l16), (lds_ptr)(aux + C::QAUX_THR64), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.thr64 + q0 + 128) + l16), (lds_ptr)(aux + C::QAUX_THR64 + 1024), 16, 0, 0);
+            if (TQ == 256)
+                __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.thr64 + q0 + 128) + l16), (lds_ptr)(aux + C::QAUX_THR64 + 1024), 16, 0, 0);
         } else if (ridx == 2 && filter) {
             __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.qmask_pad + q0) + l16), (lds_ptr)(aux + C::QAUX_QMASK), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.qmask_pad + q0 + 128) + l16), (lds_ptr)(aux + C::QAUX_QMASK + 1024), 16, 0, 0);
+            if (TQ == 256)
+                __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.qmask_pad + q0 + 128) + l16), (lds_ptr)(aux + C::QAUX_QMASK + 1024), 16, 0, 0);
         }
     };
     // role 0: load j (0..3) of the key piece at the cursor, half h of its chunk; key_next(h) moves the cursor on
@@ -205,10 +215,11 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
     };
     // role 1: load j (0..7) of the query chunk at the cursor: piece j / 4, instruction j % 4
     auto qry_issue = [&](int j) {
+        if (j >= 4 * C::NB) return;        // a 128-query chunk is one piece
         __builtin_amdgcn_global_load_lds((const void *)(ld_src + off[j / 4][j % 4]), (lds_ptr)(ld_dst + (j / 4) * PB + (j % 4) * 4096), 16, 0, 0);
     };
     auto qry_next = [&](bool more) {
-        ld_ring ^= 2;
+        ld_ring ^= C::NB;
         ld_dst = ld_ring0 + ld_ring * PB;
         if (more) {
             ld_src += RB;
@@ -220,7 +231,8 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
     // piece-local row = 64 * (wave's half of the piece) + 32 * block + lrow; logical 16-byte slot of k-step kk = 2 kk + half
     // (kk << 5 only touches bits 5 and 6, a ring slot is a multiple of 16 KiB: the XOR can follow the addition)
     const int baseA = (wm * 64 + lrow) * RB | ((half ^ swizzle<8>(lrow)) << 4);
-    const int baseB = C::OFF_B + (wn >> 1) * PB + (((wn & 1) * 64 + lrow) * RB | ((half ^ swizzle<8>(lrow)) << 4));
+    const int qrow = wn * (32 * JB) + lrow;                            // this lane's query in block 0 of the wave
+    const int baseB = C::OFF_B + (qrow / C::PIECE_ROWS) * PB + ((qrow % C::PIECE_ROWS) * RB | ((half ^ swizzle<8>(lrow)) << 4));
     auto read_f = [&](int addr, int kk, int blk) { return *(lds_u32x4 *)(lds + ((addr ^ (kk << 5)) + blk * 32 * RB)); };
 
     f32x16 acc[2][IB][JB];
@@ -241,7 +253,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
         const int64_t row0 = (int64_t)tile * TK;
 #pragma unroll
         for (int rh = 0; rh < 2; ++rh) {
-            main_epilogue<IB, JB>(acc[rh], sd, filter, rh * 128 + wm * 64, wn * 64 + lrow, half, row0, qb * TQ, p, my_region, wave_cnt);
+            main_epilogue<IB, JB>(acc[rh], sd, filter, rh * 128 + wm * 64, qrow, half, row0, qb * TQ, p, my_region, wave_cnt);
 #pragma unroll
             for (int ib = 0; ib < IB; ++ib)
 #pragma unroll
@@ -253,17 +265,17 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
 
     if (total > 0) {        // uniform over the workgroup
         // ---- prologue ---------------------------------------------------------------------------------------------
-        // keys: pieces 0..4 (every item has at least four chunks); queries: chunk 0
+        // keys: a full ring of pieces (every item has at least four chunks = eight pieces); queries: chunk 0
         ld_setup();
         if (role == 0) {
             issue_tile_aux();
 #pragma unroll
-            for (int s = 0; s < 5; ++s) {
+            for (int s = 0; s < C::NPA; ++s) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) key_issue(s & 1, j);
                 key_next(s & 1, true);
             }
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm(16));        // piece 0 (and the side data before it) has landed
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm(4 * (C::NPA - 1)));   // piece 0 (and the side data before it) has landed
         } else {
             issue_query_aux(vb % nqb);
 #pragma unroll
@@ -289,7 +301,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
     acc[RH][I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, SA[I]), __builtin_bit_cast(bf16x8, SB[J]),   \
                                                             acc[RH][I][J], 0, 0, 0);                                                \
     __builtin_amdgcn_sched_barrier(0)
-        // one k-step: four MFMAs on the key fragments SA and the query fragments fb[KU]; meanwhile the key fragments DA
+        // one k-step: four MFMAs (two with 128-query blocks) on the key fragments SA and the query fragments fb[KU]; meanwhile the key fragments DA
         // are refilled from the piece at AA, k-step KR, and (KBW_KSTEP_AB) the query fragments fb[KR] from the chunk at
         // AB; L0 .. L3: what this wave loads after each of the MFMAs
 #define KBW_KSTEP_AB(RH, SA, KU, DA, AA, AB, KR, L0, L1, L2, L3) \
@@ -298,15 +310,19 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
     fb[KR][0] = read_f(AB, KR, 0);                               \
     L0;                                                          \
     __builtin_amdgcn_sched_barrier(0);                           \
-    KBW_MFMA(RH, SA, fb[KU], 0, 1);                              \
-    fb[KR][1] = read_f(AB, KR, 1);                               \
+    if constexpr (JB == 2) {                                     \
+        KBW_MFMA(RH, SA, fb[KU], 0, 1);                          \
+        fb[KR][1] = read_f(AB, KR, 1);                           \
+    }                                                            \
     DA[1] = read_f(AA, KR, 1);                                   \
     L1;                                                          \
     __builtin_amdgcn_sched_barrier(0);                           \
     KBW_MFMA(RH, SA, fb[KU], 1, 0);                              \
     L2;                                                          \
     __builtin_amdgcn_sched_barrier(0);                           \
-    KBW_MFMA(RH, SA, fb[KU], 1, 1);                              \
+    if constexpr (JB == 2) {                                     \
+        KBW_MFMA(RH, SA, fb[KU], 1, 1);                          \
+    }                                                            \
     L3;                                                          \
     __builtin_amdgcn_sched_barrier(0)
 #define KBW_KSTEP_A(RH, SA, KU, DA, AA, KR, L0, L1, L2, L3) \
@@ -314,14 +330,18 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
     DA[0] = read_f(AA, KR, 0);                              \
     L0;                                                     \
     __builtin_amdgcn_sched_barrier(0);                      \
-    KBW_MFMA(RH, SA, fb[KU], 0, 1);                         \
+    if constexpr (JB == 2) {                                \
+        KBW_MFMA(RH, SA, fb[KU], 0, 1);                     \
+    }                                                       \
     DA[1] = read_f(AA, KR, 1);                              \
     L1;                                                     \
     __builtin_amdgcn_sched_barrier(0);                      \
     KBW_MFMA(RH, SA, fb[KU], 1, 0);                         \
     L2;                                                     \
     __builtin_amdgcn_sched_barrier(0);                      \
-    KBW_MFMA(RH, SA, fb[KU], 1, 1);                         \
+    if constexpr (JB == 2) {                                \
+        KBW_MFMA(RH, SA, fb[KU], 1, 1);                     \
+    }                                                       \
     L3;                                                     \
     __builtin_amdgcn_sched_barrier(0)
 #define KBW_NONE (void)0
@@ -334,7 +354,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
         auto item_chunks = [&](auto role_c, int g0) {
             constexpr int ROLE = decltype(role_c)::value;
             auto wait_before_barrier = [&](int rh) {
-                if (ROLE == 0) __builtin_amdgcn_s_waitcnt(waitcnt_vm(12));
+                if (ROLE == 0) __builtin_amdgcn_s_waitcnt(waitcnt_vm(4 * (C::NPA - 2)));
                 else if (rh == 1) __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
                 __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
                 __builtin_amdgcn_sched_barrier(0);
@@ -347,7 +367,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
                 {
                     const int ran = ra + 1 == C::NPA ? 0 : ra + 1;
                     const int aa = baseA + ra * PB, ab = baseB + rb * PB, aan = baseA + ran * PB;
-                    // query waves: chunk g+1 into the slots that barrier 2g-1 retired; key waves: piece f+5 (second half
+                    // query waves: chunk g+1 into the slots that barrier 2g-1 retired; key waves: piece f+NPA (second half
                     // of chunk g+2) into the slot that barrier f retires
                     __builtin_amdgcn_s_setprio(1);
                     KBW_KSTEP_AB(0, xa, 0, ya, aa, ab, 1, if (ROLE == 1) qry_issue(0), if (ROLE == 1) qry_issue(1), if (ROLE == 1) qry_issue(2),
@@ -361,26 +381,26 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
                     if (ROLE == 1 && nqb > 1 && c == 0 && g > 0) issue_query_aux(qb);
                     __builtin_amdgcn_s_setprio(1);
                     KBW_KSTEP_A(0, ya, 3, xa, aan, 0, if (ROLE == 0) key_issue(1, 0), if (ROLE == 0) key_issue(1, 1), if (ROLE == 0) key_issue(1, 2),
-                                if (ROLE == 0) { key_issue(1, 3); key_next(1, f + 6 < phases); });
+                                if (ROLE == 0) { key_issue(1, 3); key_next(1, f + C::NPA + 1 < phases); });
                     __builtin_amdgcn_s_setprio(0);
                     ra = ran;
                     ++f;
                 }
                 // ======== phase 2g+1 ========
                 {
-                    const int ran = ra + 1 == C::NPA ? 0 : ra + 1, rbn = rb ^ 2;
+                    const int ran = ra + 1 == C::NPA ? 0 : ra + 1, rbn = rb ^ C::NB;
                     const bool more = g + 1 < total;
                     const int aa = baseA + ra * PB;
                     // past the last chunk the refill of X reads the current slots again (valid memory, values unused)
                     const int aan = baseA + (more ? ran : ra) * PB, abn = baseB + (more ? rbn : rb) * PB;
-                    // key waves: piece f+5 (first half of chunk g+3) and, before it, the side data of a new tile
+                    // key waves: piece f+NPA (the first half of its chunk) and, before it, the side data of a new tile
                     __builtin_amdgcn_s_setprio(1);
                     KBW_KSTEP_A(1, xa, 0, ya, aa, 1, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
                     KBW_KSTEP_A(1, ya, 1, xa, aa, 2, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
                     KBW_KSTEP_A(1, xa, 2, ya, aa, 3, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
                     __builtin_amdgcn_s_setprio(0);
                     wait_before_barrier(1);
-                    if (ROLE == 0 && ld_c == 0 && f + 5 < phases) issue_tile_aux();
+                    if (ROLE == 0 && ld_c == 0 && f + C::NPA < phases) issue_tile_aux();
                     __builtin_amdgcn_s_setprio(1);
                     KBW_KSTEP_AB(1, ya, 3, xa, aan, abn, 0, if (ROLE == 0) key_issue(0, 0), if (ROLE == 0) key_issue(0, 1), if (ROLE == 0) key_issue(0, 2),
                                  if (ROLE == 0) { key_issue(0, 3); key_next(0, true); });
