@@ -67,10 +67,13 @@ bool scan_config_info(int key_dtype, int config, ConfigInfo *out)
     return false;
 }
 
-int scan_config_for(int key_dtype, int Q, int d)
+constexpr int64_t WIDE128_MIN_ROWS = 4 * 65536;     // rows from which the 128-query full-line kernel is the faster one (measured: 2^18)
+
+int scan_config_for(int key_dtype, int Q, int d, int64_t n)
 {
     if (key_dtype == KB_BF16 && Q > 128 && d * 2 >= 512) return 18;
-    if (key_dtype == KB_BF16 && Q > 32 && d * 2 >= 512) return 19;
+    // 33 to 128 queries: the full-line kernel once a workgroup has several tiles to stream (its ring takes longer to fill)
+    if (key_dtype == KB_BF16 && Q > 32 && d * 2 >= 512 && n >= WIDE128_MIN_ROWS) return 19;
     if (key_dtype == KB_BF16 && Q > 128 && d * 2 >= 384) return 17;
     if (key_dtype == KB_FP8_E4M3 && Q > 128 && d >= 256) return 4;
     return Q <= 32 ? 1 : Q <= 128 ? 2 : 3;
@@ -135,7 +138,7 @@ bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, bool draw, bool q8,
         p.config = FP8_QUERY_CONFIG;
         if (!scan_config_info(h->dtype, p.config, &ci) || row_bytes < (size_t)ci.min_row_bytes) return false;
     } else {
-        p.config = h->tune_config > 0 ? (int)h->tune_config : scan_config_for(h->dtype, Q, h->d);
+        p.config = h->tune_config > 0 ? (int)h->tune_config : scan_config_for(h->dtype, Q, h->d, n);
         if (!scan_config_info(h->dtype, p.config, &ci)) return false;
         // fall back where a (forced) configuration does not apply: the weighted random selection exists in the
         // tiled kernel only, rows may be too short for a pipelined kernel, and the fp8-query kernel reads fp8 queries
@@ -996,6 +999,10 @@ size_t kb_query_workspace_bytes(const kb_t *kb, int32_t Q, int32_t k)
             if (p.total > best) best = p.total;
         }
         if (make_plan(kb, n, Q, k, false, true, &p) && p.total > best) best = p.total;
+    }
+    for (int64_t n : {(int64_t)WIDE128_MIN_ROWS - 1, (int64_t)WIDE128_MIN_ROWS}) {     // either side of a kernel choice that depends on the row count
+        Plan p;
+        if (n <= kb->capacity && make_plan(kb, n, Q, k, false, false, &p) && p.total > best) best = p.total;
     }
     const size_t small = make_small_plan(Q, k, PROBE_MAX_LISTS).total;      // the path of small knowledge bases
     return best > small ? best : small;

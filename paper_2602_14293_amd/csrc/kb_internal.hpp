@@ -164,6 +164,6 @@ struct ConfigInfo {
     int family;             // 0: kb_scan.hpp, 1: kb_scan_pp.hpp, 2: kb_scan_big.hpp, 3: kb_scan_sp.hpp, 4: kb_scan_wide.hpp
 };
 bool scan_config_info(int key_dtype, int config, ConfigInfo *out);   // false if the id does not exist
-int scan_config_for(int key_dtype, int Q, int d);                    // automatic choice
+int scan_config_for(int key_dtype, int Q, int d, int64_t n);         // automatic choice for n rows
 
 }  // namespace kbi
