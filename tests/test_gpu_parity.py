@@ -58,6 +58,16 @@ def test_every_large_batch_scan_kernel(T, config):
     assert rep.queries == 300 and cnt["exhaustive_queries"] == 0
 
 
+@pytest.mark.parametrize("config", [17, 18, 19])
+def test_several_items_and_query_blocks_per_workgroup(T, config):
+    """More (key tile, query block) items than workgroups AND more than one query block: a workgroup's stream crosses
+    item boundaries where the query block changes (the per-query side data in LDS is reloaded there), with the
+    shortest rows the pipelined kernels take (four 128-byte chunks) and a ragged last tile."""
+    w = W.filtered(seed=21, N=50000 + 57, d=256, Q=300, k=32, centers=32)
+    rep, cnt, _ = T.run_and_check(w, label=f"many items, scan config {config}", tuning={"scan_config": config})
+    assert rep.queries == 300 and cnt["exhaustive_queries"] == 0 and cnt["scan_workgroups"] == 256
+
+
 @pytest.mark.parametrize("seed", [0, 1])
 def test_sparse_filter_exercises_padding(T, seed):
     w = W.filtered(seed=seed, N=12000, d=256, Q=96, k=32, centers=16, p_tag=0.003, single_bit_qmask=True)
