@@ -68,6 +68,25 @@ def test_several_items_and_query_blocks_per_workgroup(T, config):
     assert rep.queries == 300 and cnt["exhaustive_queries"] == 0 and cnt["scan_workgroups"] == 256
 
 
+@pytest.mark.parametrize("config,Q", [(18, 200), (19, 100)])
+def test_full_line_kernels_without_mask_and_with_removed_rows(T, config, Q):
+    """The full-line kernels on unmasked queries (no tag side data is loaded) with removed entries in the store."""
+    import numpy as np
+
+    w = W.clustered(seed=23, N=30000 + 11, d=320, Q=Q, k=16, centers=16)
+    kb = T.build_kb(w)
+    kb.set_tuning("scan_config", config)
+    before_i, _ = T.gpu_query(kb, w)
+    removed = np.zeros(w.N, dtype=bool)
+    removed[np.unique(before_i[:, :4])] = True                      # the best four of every query, and every 97th row
+    removed[5::97] = True
+    kb.remove(torch.from_numpy(np.flatnonzero(removed).astype(np.int32)).cuda())
+    gi, gs = T.gpu_query(kb, w)
+    rep = T.check_against_oracle(w, gi, gs, label=f"unmasked, removed rows, scan config {config}", removed=removed)
+    assert rep.queries == Q and not removed[gi[gi >= 0]].any() and kb.counters()["exhaustive_queries"] == 0
+    kb.close()
+
+
 @pytest.mark.parametrize("seed", [0, 1])
 def test_sparse_filter_exercises_padding(T, seed):
     w = W.filtered(seed=seed, N=12000, d=256, Q=96, k=32, centers=16, p_tag=0.003, single_bit_qmask=True)
