@@ -265,23 +265,28 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
 
     if (total > 0) {        // uniform over the workgroup
         // ---- prologue ---------------------------------------------------------------------------------------------
-        // keys: a full ring of pieces (every item has at least four chunks = eight pieces); queries: chunk 0
+        // keys: all pieces of the ring but the last, and the first instruction of that one (every item has at least
+        // four chunks = eight pieces); queries: chunk 0 and the first five instructions of chunk 1.  From here on every
+        // wave issues one load per k-step.
         ld_setup();
         if (role == 0) {
             issue_tile_aux();
 #pragma unroll
-            for (int s = 0; s < C::NPA; ++s) {
+            for (int s = 0; s < C::NPA - 1; ++s) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) key_issue(s & 1, j);
                 key_next(s & 1, true);
             }
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm(4 * (C::NPA - 1)));   // piece 0 (and the side data before it) has landed
+            key_issue(0, 0);
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm(4 * (C::NPA - 2) + 1));   // piece 0 (and the side data before it) has landed
         } else {
             issue_query_aux(vb % nqb);
 #pragma unroll
             for (int j = 0; j < 8; ++j) qry_issue(j);
             qry_next(true);
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));         // chunk 0 (and the side data before it) has landed
+#pragma unroll
+            for (int j = 0; j < 5; ++j) qry_issue(j);
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm(C::NB == 2 ? 5 : 4));     // chunk 0 (and the side data before it) has landed
         }
         __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
         bare_barrier();
@@ -355,7 +360,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
             constexpr int ROLE = decltype(role_c)::value;
             auto wait_before_barrier = [&](int rh) {
                 if (ROLE == 0) __builtin_amdgcn_s_waitcnt(waitcnt_vm(4 * (C::NPA - 2)));
-                else if (rh == 1) __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+                else if (rh == 1) __builtin_amdgcn_s_waitcnt(waitcnt_vm(4));
                 __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
                 __builtin_amdgcn_sched_barrier(0);
                 bare_barrier();
@@ -370,18 +375,16 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
                     // query waves: chunk g+1 into the slots that barrier 2g-1 retired; key waves: piece f+NPA (second half
                     // of chunk g+2) into the slot that barrier f retires
                     __builtin_amdgcn_s_setprio(1);
-                    KBW_KSTEP_AB(0, xa, 0, ya, aa, ab, 1, if (ROLE == 1) qry_issue(0), if (ROLE == 1) qry_issue(1), if (ROLE == 1) qry_issue(2),
-                                 if (ROLE == 1) qry_issue(3));
-                    KBW_KSTEP_AB(0, ya, 1, xa, aa, ab, 2, if (ROLE == 1) qry_issue(4), if (ROLE == 1) qry_issue(5), if (ROLE == 1) qry_issue(6),
-                                 if (ROLE == 1) { qry_issue(7); qry_next(g + 2 < total); });
-                    KBW_KSTEP_AB(0, xa, 2, ya, aa, ab, 3, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
+                    KBW_KSTEP_AB(0, xa, 0, ya, aa, ab, 1, KBW_NONE, KBW_NONE, if (ROLE == 0) key_issue(0, 1); else qry_issue(5), KBW_NONE);
+                    KBW_KSTEP_AB(0, ya, 1, xa, aa, ab, 2, KBW_NONE, KBW_NONE, if (ROLE == 0) key_issue(0, 2); else qry_issue(6), KBW_NONE);
+                    KBW_KSTEP_AB(0, xa, 2, ya, aa, ab, 3, KBW_NONE, KBW_NONE,
+                                 if (ROLE == 0) { key_issue(0, 3); key_next(0, true); } else { qry_issue(7); qry_next(g + 2 < total); }, KBW_NONE);
                     __builtin_amdgcn_s_setprio(0);
                     wait_before_barrier(0);
                     // a new query block's side data: every epilogue of the previous item ended before this barrier
                     if (ROLE == 1 && nqb > 1 && c == 0 && g > 0) issue_query_aux(qb);
                     __builtin_amdgcn_s_setprio(1);
-                    KBW_KSTEP_A(0, ya, 3, xa, aan, 0, if (ROLE == 0) key_issue(1, 0), if (ROLE == 0) key_issue(1, 1), if (ROLE == 0) key_issue(1, 2),
-                                if (ROLE == 0) { key_issue(1, 3); key_next(1, f + C::NPA + 1 < phases); });
+                    KBW_KSTEP_A(0, ya, 3, xa, aan, 0, KBW_NONE, KBW_NONE, if (ROLE == 0) key_issue(1, 0); else qry_issue(0), KBW_NONE);
                     __builtin_amdgcn_s_setprio(0);
                     ra = ran;
                     ++f;
@@ -395,15 +398,15 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
                     const int aan = baseA + (more ? ran : ra) * PB, abn = baseB + (more ? rbn : rb) * PB;
                     // key waves: piece f+NPA (the first half of its chunk) and, before it, the side data of a new tile
                     __builtin_amdgcn_s_setprio(1);
-                    KBW_KSTEP_A(1, xa, 0, ya, aa, 1, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
-                    KBW_KSTEP_A(1, ya, 1, xa, aa, 2, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
-                    KBW_KSTEP_A(1, xa, 2, ya, aa, 3, KBW_NONE, KBW_NONE, KBW_NONE, KBW_NONE);
+                    KBW_KSTEP_A(1, xa, 0, ya, aa, 1, KBW_NONE, KBW_NONE, if (ROLE == 0) key_issue(1, 1); else qry_issue(1), KBW_NONE);
+                    KBW_KSTEP_A(1, ya, 1, xa, aa, 2, KBW_NONE, KBW_NONE, if (ROLE == 0) key_issue(1, 2); else qry_issue(2), KBW_NONE);
+                    KBW_KSTEP_A(1, xa, 2, ya, aa, 3, KBW_NONE, KBW_NONE,
+                                if (ROLE == 0) { key_issue(1, 3); key_next(1, f + C::NPA < phases); } else qry_issue(3), KBW_NONE);
                     __builtin_amdgcn_s_setprio(0);
                     wait_before_barrier(1);
                     if (ROLE == 0 && ld_c == 0 && f + C::NPA < phases) issue_tile_aux();
                     __builtin_amdgcn_s_setprio(1);
-                    KBW_KSTEP_AB(1, ya, 3, xa, aan, abn, 0, if (ROLE == 0) key_issue(0, 0), if (ROLE == 0) key_issue(0, 1), if (ROLE == 0) key_issue(0, 2),
-                                 if (ROLE == 0) { key_issue(0, 3); key_next(0, true); });
+                    KBW_KSTEP_AB(1, ya, 3, xa, aan, abn, 0, KBW_NONE, KBW_NONE, if (ROLE == 0) key_issue(0, 0); else qry_issue(4), KBW_NONE);
                     __builtin_amdgcn_s_setprio(0);
                     ra = ran;
                     rb = rbn;
