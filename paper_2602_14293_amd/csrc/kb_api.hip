@@ -161,10 +161,6 @@ bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, bool draw, bool q8,
     // kernel produces bit-identical scores, so thresholds carry over).
     ConfigInfo sci = ci;
     p.sample_config = p.config;
-    if (ci.family == 4) {       // main pass only: the sampling pass takes the interleaved software-pipelined kernel
-        p.sample_config = KB_WIDE_SAMPLE_CONFIG(ci.tq);
-        if (!scan_config_info(h->dtype, p.sample_config, &sci) || sci.tq != ci.tq || row_bytes < (size_t)sci.min_row_bytes) return false;
-    }
     p.sample_family = sci.family;
     p.sample_wgpc = sci.wg_per_cu;
     const int64_t s_tiles_all = ceil_div(n, sci.tk);
@@ -1124,7 +1120,7 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
             // ... row by row where the kernel can gather (the two-phase and register-tile kernels load whole tiles:
             // they take every tile_stride-th tile instead)
             a.row_run_shift = draw ? 2 : 0;
-            a.row_mul = (p.sample_family == 0 || p.sample_family == 3) ? scatter_multiplier(kb->n >> a.row_run_shift) : 0;
+            a.row_mul = (p.sample_family == 0 || p.sample_family == 3 || p.sample_family == 4) ? scatter_multiplier(kb->n >> a.row_run_shift) : 0;
             int64_t sgrid = p.sample_tiles * p.nqb;
             const int64_t smax = (int64_t)(kb->cu_count > 0 ? kb->cu_count : ASSUMED_CUS) * p.sample_wgpc;
             if (sgrid > smax) sgrid = smax;

@@ -46,10 +46,7 @@
 #define KB_SCAN_SP_CONFIGS_FP8_Q8(XQ) \
     XQ(5, KB_FP8_E4M3, 256, 5, 4)
 
-// Full-line configurations (kb_scan_wide.hpp): XW(id, key dtype, TQ); 256-row tiles, 512 threads, 128-byte row pieces,
-// main pass only: the sampling pass runs the software-pipelined configuration with the same query block
-// (KB_WIDE_SAMPLE_CONFIG).
+// Full-line configurations (kb_scan_wide.hpp): XW(id, key dtype, TQ); 256-row tiles, 512 threads, 128-byte row pieces.
 #define KB_SCAN_WIDE_CONFIGS_BF16(XW) \
     XW(18, KB_BF16, 256)              \
     XW(19, KB_BF16, 128)
-#define KB_WIDE_SAMPLE_CONFIG(TQ) ((TQ) == 256 ? 17 : 15)

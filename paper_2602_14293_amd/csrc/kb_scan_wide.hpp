@@ -1,6 +1,6 @@
 // The large-batch scan kernel, full-line version: 256 key rows x 256 queries per work item on eight wavefronts
 // like kb_scan_sp.hpp, but the direct-to-LDS loads fetch 128 bytes of every key row and of every query row at a
-// time (gfx950 only; bf16; main pass only).
+// time (gfx950 only; bf16).
 //
 // Why 128-byte rows.  A direct-to-LDS load instruction moves 1 KiB; with 64-byte row pieces it covers half of
 // 16 cache lines and the other halves are asked for again one d-chunk later, with 128-byte pieces it covers 8
@@ -70,6 +70,7 @@ template <int KT_, int TQ_> struct WideCfg {
     static constexpr int QAUX_BYTES = QAUX_QMASK + TQ * 8;
     static constexpr int OFF_QAUX = OFF_AUX + 2 * AUX_BYTES;
     static constexpr int SMEM_BYTES = OFF_QAUX + QAUX_BYTES;
+    static constexpr int GROUPS_PER_TILE = 8;                // sampling groups: 2 pieces x 2 wave rows x 2 lane halves
     static constexpr int MIN_ROW_BYTES = 4 * RB;             // the key stream runs five pieces ahead of the MFMAs
     static_assert(KT == KB_BF16 && KEY_BYTES == QRY_BYTES, "written for bf16 keys and queries");
     static_assert(TQ == 256 || TQ == 128, "query blocks of 256 or 128");
@@ -77,7 +78,7 @@ template <int KT_, int TQ_> struct WideCfg {
     static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget");
 };
 
-template <class C>
+template <class C, bool SAMPLE>
 __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
 {
     constexpr int TK = C::TK, TQ = C::TQ, RB = C::RB, IB = C::IB, JB = C::JB, NW = C::NW, PB = C::PIECE_BYTES;
@@ -122,14 +123,15 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
     lds_u8 *const ld_ring0 = lds + (role == 0 ? 0 : C::OFF_B) + ridx * 1024;
     lds_u8 *ld_dst = ld_ring0;
     int ld_ring = 0;
-    uint32_t off[2][4];                                                // [piece of the chunk][instruction]
+    typedef typename std::conditional<SAMPLE, uint64_t, uint32_t>::type Off;   // a sampling pass gathers key rows from anywhere
+    Off off[2][4];                                                     // [piece of the chunk][instruction]
     auto ld_setup = [&]() {
         int last, base;
         if (role == 0) {
             const int64_t left = p.n_keys - (int64_t)ld_tile * TK;
             last = left < TK ? (int)left - 1 : TK - 1;
             base = 0;
-            ld_src = static_cast<const unsigned char *>(p.keys) + (size_t)ld_tile * TK * key_row_bytes;
+            ld_src = static_cast<const unsigned char *>(p.keys) + (SAMPLE ? 0 : (size_t)ld_tile * TK * key_row_bytes);
         } else {
             last = p.Q - 1 - ld_qb * TQ;
             base = ld_qb * TQ;
@@ -141,13 +143,28 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int r = h * C::PIECE_ROWS + ld_row + j * 32;
-                off[h][j] = (uint32_t)(base + (r < last ? r : last)) * rb + ld_slot;
+                if (SAMPLE && role == 0) off[h][j] = (Off)((uint64_t)sample_row(p, ld_tile, TK, r) * rb + ld_slot);
+                else off[h][j] = (uint32_t)(base + (r < last ? r : last)) * rb + ld_slot;
             }
     };
     // side data of the key tile the key stream is at: 4-byte loads with clamped rows from the caller's arrays
     // (addresses as a wave-uniform base plus a 32-bit lane offset, the form that needs no 64-bit vector arithmetic)
     auto issue_tile_aux = [&]() {       // role 0 only
         lds_u8 *aux = lds + C::OFF_AUX + ld_par * C::AUX_BYTES;
+        if constexpr (SAMPLE) {
+            const int64_t r = sample_row(p, ld_tile, TK, ridx * 64 + lane);
+            __builtin_amdgcn_global_load_lds((const void *)(p.inv_norm + r), (lds_ptr)(aux + C::AUX_INVK + ridx * 256), 4, 0, 0);
+            if (filter) {
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2) {
+                    const int i = ridx * 2 + h2;
+                    const int64_t rt = sample_row(p, ld_tile, TK, i * 32 + (lane >> 1));
+                    __builtin_amdgcn_global_load_lds((const void *)(reinterpret_cast<const uint32_t *>(p.tags + rt) + (lane & 1)),
+                                                     (lds_ptr)(aux + C::AUX_TAG + i * 256), 4, 0, 0);
+                }
+            }
+            return;
+        }
         const int64_t row0 = (int64_t)ld_tile * TK;
         const int64_t left = p.n_keys - row0;
         const uint32_t last = left < TK ? (uint32_t)left - 1 : TK - 1;
@@ -175,9 +192,10 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
         if (ridx == 0) {
             if (lane < TQ / 4) {        // TQ floats
                 __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.invq + q0) + l16), (lds_ptr)(aux + C::QAUX_INVQ), 16, 0, 0);
-                __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.thrp + q0) + l16), (lds_ptr)(aux + C::QAUX_THRP), 16, 0, 0);
+                if (!SAMPLE)
+                    __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.thrp + q0) + l16), (lds_ptr)(aux + C::QAUX_THRP), 16, 0, 0);
             }
-        } else if (ridx == 1) {
+        } else if (ridx == 1 && !SAMPLE) {
             __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.thr64 + q0) + l16), (lds_ptr)(aux + C::QAUX_THR64), 16, 0, 0);
             if (TQ == 256)
                 __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.thr64 + q0 + 128) + l16), (lds_ptr)(aux + C::QAUX_THR64 + 1024), 16, 0, 0);
@@ -250,10 +268,14 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
         const EpiSide sd{reinterpret_cast<const float *>(aux + C::AUX_INVK), reinterpret_cast<const uint64_t *>(aux + C::AUX_TAG),
                          reinterpret_cast<const float *>(qaux + C::QAUX_THRP), reinterpret_cast<const float *>(qaux + C::QAUX_INVQ),
                          reinterpret_cast<const uint64_t *>(qaux + C::QAUX_THR64), reinterpret_cast<const uint64_t *>(qaux + C::QAUX_QMASK)};
-        const int64_t row0 = (int64_t)tile * TK;
+        const int64_t row0 = SAMPLE ? sample_row0(p, tile, TK) : (int64_t)tile * TK;
 #pragma unroll
         for (int rh = 0; rh < 2; ++rh) {
-            main_epilogue<IB, JB>(acc[rh], sd, filter, rh * 128 + wm * 64, qrow, half, row0, qb * TQ, p, my_region, wave_cnt);
+            if constexpr (SAMPLE)       // sampling groups: (piece, wave row, lane half) = 32 rows each
+                sample_epilogue<IB, JB>(acc[rh], sd, filter, rh * 128 + wm * 64, qrow, half, row0, qb * TQ, p,
+                                        (int64_t)tile * C::GROUPS_PER_TILE + (rh * 2 + wm) * 2 + half);
+            else
+                main_epilogue<IB, JB>(acc[rh], sd, filter, rh * 128 + wm * 64, qrow, half, row0, qb * TQ, p, my_region, wave_cnt);
 #pragma unroll
             for (int ib = 0; ib < IB; ++ib)
 #pragma unroll
@@ -434,7 +456,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
         __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));             // the loads past the end of the stream
     }
 
-    if (lane == 0) {
+    if (!SAMPLE && lane == 0) {
         const uint32_t cap = (uint32_t)p.region_cap;
         p.region_cnt[blockIdx.x * NW + wave] = wave_cnt < cap ? wave_cnt : cap;
     }
@@ -442,13 +464,12 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
 
 template <class C> hipError_t launch_scan_wide_cfg(bool sample, int grid, const ScanArgs &a, hipStream_t s)
 {
-    if (sample) return hipErrorInvalidValue;        // the sampling pass runs another configuration
-    static bool attr_done = false;
-    auto *fn = &kb_scan_wide_kernel<C>;
-    if (!attr_done) {
+    static bool attr_done[2] = {false, false};
+    auto *fn = sample ? &kb_scan_wide_kernel<C, true> : &kb_scan_wide_kernel<C, false>;
+    if (!attr_done[sample]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM_BYTES);
         if (e != hipSuccess) return e;
-        attr_done = true;
+        attr_done[sample] = true;
     }
     hipLaunchKernelGGL(fn, dim3(grid), dim3(C::THREADS), C::SMEM_BYTES, s, a);
     return hipGetLastError();
