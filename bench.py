@@ -33,7 +33,7 @@ DRAW_OPS_PER_PAIR = 36
 # HBM bytes per launch of the main-pass scan kernel on the default workload with the default kernel choice, from
 # rocprofv3 --pmc FETCH_SIZE (x 2.0: what the same counter under-reads on a copy of known size) and WRITE_SIZE (x 1.0).
 # Applies to that workload and kernel only.
-SCAN_TRAFFIC_BYTES_FILTERED = 1086680 * 1024 * 2.0 + 4110 * 1024 * 1.0
+SCAN_TRAFFIC_BYTES_FILTERED = 1086879 * 1024 * 2.0 + 4110 * 1024 * 1.0
 
 
 def make_workload(name: str, seed: int, device):
