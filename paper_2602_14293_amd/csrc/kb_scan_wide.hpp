@@ -10,22 +10,24 @@
 //
 // The price is LDS: a d-chunk is now 64 elements, 32 KiB of keys + 32 KiB of queries, and a key piece issued
 // now lands about two chunk times later (HBM under load).  So the chunk is worked through in two PHASES, one
-// per PIECE of keys (16 KiB: 128 rows x 128 bytes), and the ring is kept in pieces: with 256-query blocks five of
-// keys (one in use, four in flight) and four of queries (one chunk in use, the next one landing).  In phase f = 2 g + rh a wave
-// (wm, wn) multiplies rows 128 rh + 64 wm + [0, 64) of the tile with queries 64 wn + [0, 64): sixteen MFMAs in
-// four k-steps, fragments in two register sets X and Y (while the MFMAs of one k-step run on one set, the other
-// is refilled), one barrier per phase:
+// per PIECE of keys (16 KiB: 128 rows x 128 bytes), and the ring is kept in pieces: with 256-query blocks five
+// of keys (one in use, four in flight) and four of queries (one chunk in use, the next one landing).  In phase
+// f = 2 g + rh a wave (wm, wn) multiplies rows 128 rh + 64 wm + [0, 64) of the tile with queries 64 wn + [0, 64):
+// sixteen MFMAs in four k-steps.  Key fragments live in two register sets X and Y (while the MFMAs of one
+// k-step run on one set, the other is refilled); the query fragments of all four k-steps are read in the
+// chunk's first phase and stay in registers for its second.  One barrier per phase:
 //
 //   k-step 0 on X, Y <- (f,1);  k-step 1 on Y, X <- (f,2);  k-step 2 on X, Y <- (f,3);
 //   wait for my own loads of key piece f+1 (and, rh = 1, of query chunk g+1) and for my LDS reads; BARRIER f
-//   (publishes those, retires key piece f and, rh = 1, query chunk g);
+//   (publishes those, retires key piece f and, rh = 0, query chunk g: its fragments are all in registers);
 //   k-step 3 on Y, X <- (f+1,0).
 //
-// Waves 0-3 load keys: piece f+5 (f + the ring depth) into the slot of piece f, one instruction after each MFMA of the k-step that
-// follows barrier f, so that it has four phases to land.  Waves 4-7 load queries: chunk g+2 into the slots of
-// chunk g, one instruction after each MFMA of the first two k-steps of phase 2g+2.  The two kinds keep separate
-// load counters, so the wait for a query chunk issued a phase ago does not drain the key pieces issued up to
-// four phases ago.
+// Waves 0-3 load keys: piece f+5 (f + the ring depth) into the slot of piece f, from barrier f on.  Waves 4-7
+// load queries: chunk g+2 into the slots of chunk g, from barrier 2g on.  Every wave issues exactly ONE load per
+// k-step (a steady stream for the texture-address unit instead of bursts after the barriers), nothing about a
+// load is decided at run time (past the end of its stream a wave loads its last piece again into slots nobody
+// reads), and the loop exists once per kind of wave.  The two kinds keep separate load counters, so the wait for
+// a query chunk does not drain the key pieces issued up to four phases ago.
 //
 // With 128-query blocks (the second configuration) a query chunk is one piece, the ring holds seven key pieces and
 // two query pieces (six phases for a key piece to land), and a wave multiplies its 64 rows with 32 queries.
