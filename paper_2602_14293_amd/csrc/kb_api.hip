@@ -63,6 +63,7 @@ bool scan_config_info(int key_dtype, int config, ConfigInfo *out)
         return true;                                                          \
     }
     KB_SCAN_WIDE_CONFIGS_BF16(XW)
+    KB_SCAN_WIDE_CONFIGS_FP8_Q8(XW)
 #undef XW
     return false;
 }
@@ -91,6 +92,7 @@ constexpr int FALLBACK_PARTS = 32;    // workgroups that share the rows of a que
 constexpr int CAND_SEGMENTS = 16;     // per-query candidate list = this many independently counted segments
 constexpr size_t WS_ALIGN = 256;
 constexpr int FP8_QUERY_CONFIG = 5;    // scan configuration of fp8 keys with fp8 queries (kb_configs.hpp)
+constexpr int FP8_QUERY_WIDE_CONFIG = 20;     // ... with 128-byte row pieces: rows of a multiple of 128 bytes, 512 at least
 constexpr int STAT_WORDS = 4;          // candidates, exhaustive queries, sample keys, scan workgroups
 constexpr int STAT_PARTIALS = 64;      // the candidate count is kept as this many partial sums (one hot address would serialise)
 
@@ -135,7 +137,8 @@ bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, bool draw, bool q8,
     const size_t row_bytes = (size_t)h->d * key_bytes(h->dtype);
     if (q8) {       // fp8 queries: only the kernel built on the fp8 matrix instruction takes them
         if (draw || h->dtype != KB_FP8_E4M3) return false;
-        p.config = FP8_QUERY_CONFIG;
+        p.config = (row_bytes % 128 == 0 && row_bytes >= 512) ? FP8_QUERY_WIDE_CONFIG : FP8_QUERY_CONFIG;
+        if (h->tune_config == FP8_QUERY_CONFIG) p.config = FP8_QUERY_CONFIG;         // the other one can be asked for
         if (!scan_config_info(h->dtype, p.config, &ci) || row_bytes < (size_t)ci.min_row_bytes) return false;
     } else {
         p.config = h->tune_config > 0 ? (int)h->tune_config : scan_config_for(h->dtype, Q, h->d, n);
@@ -143,7 +146,7 @@ bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, bool draw, bool q8,
         // fall back where a (forced) configuration does not apply: the weighted random selection exists in the
         // tiled kernel only, rows may be too short for a pipelined kernel, and the fp8-query kernel reads fp8 queries
         if ((draw && ci.family != 0) || row_bytes < (size_t)ci.min_row_bytes ||
-            (h->dtype == KB_FP8_E4M3 && p.config == FP8_QUERY_CONFIG)) {
+            (h->dtype == KB_FP8_E4M3 && (p.config == FP8_QUERY_CONFIG || p.config == FP8_QUERY_WIDE_CONFIG))) {
             p.config = generic;
             if (!scan_config_info(h->dtype, p.config, &ci)) return false;
         }
@@ -161,6 +164,10 @@ bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, bool draw, bool q8,
     // kernel produces bit-identical scores, so thresholds carry over).
     ConfigInfo sci = ci;
     p.sample_config = p.config;
+    if (ci.family == 4 && h->dtype == KB_FP8_E4M3) {       // the fp8 full-line kernel is a main pass only
+        p.sample_config = FP8_QUERY_CONFIG;
+        if (!scan_config_info(h->dtype, p.sample_config, &sci) || sci.tq != ci.tq || sci.tk != ci.tk) return false;
+    }
     p.sample_family = sci.family;
     p.sample_wgpc = sci.wg_per_cu;
     const int64_t s_tiles_all = ceil_div(n, sci.tk);
@@ -768,7 +775,9 @@ hipError_t launch_scan(kb_dtype_t dt, int config, int family, bool sample, int g
 {
     if (family == 1) return dt == KB_BF16 ? launch_scan_pp_bf16(config, sample, grid, a, s) : hipErrorInvalidValue;
     if (family == 2) return dt == KB_BF16 ? launch_scan_big_bf16(config, sample, grid, a, s) : hipErrorInvalidValue;
-    if (family == 4) return dt == KB_BF16 ? launch_scan_wide_bf16(config, sample, grid, a, s) : hipErrorInvalidValue;
+    if (family == 4)
+        return dt == KB_BF16 ? launch_scan_wide_bf16(config, sample, grid, a, s)
+               : dt == KB_FP8_E4M3 ? launch_scan_wide_fp8(config, sample, grid, a, s) : hipErrorInvalidValue;
     if (family == 3)
         return dt == KB_BF16 ? launch_scan_sp_bf16(config, sample, grid, a, s)
                : dt == KB_FP8_E4M3 ? launch_scan_sp_fp8(config, sample, grid, a, s) : hipErrorInvalidValue;

@@ -50,3 +50,6 @@
 #define KB_SCAN_WIDE_CONFIGS_BF16(XW) \
     XW(18, KB_BF16, 256)              \
     XW(19, KB_BF16, 128)
+// ... for fp8 keys with fp8 queries
+#define KB_SCAN_WIDE_CONFIGS_FP8_Q8(XW) \
+    XW(20, KB_FP8_E4M3, 256)

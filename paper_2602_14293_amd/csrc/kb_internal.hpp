@@ -155,6 +155,7 @@ hipError_t launch_scan_pp_bf16(int config, bool sample, int grid, const ScanArgs
 hipError_t launch_scan_big_bf16(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
 hipError_t launch_scan_sp_bf16(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
 hipError_t launch_scan_wide_bf16(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
+hipError_t launch_scan_wide_fp8(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
 hipError_t launch_scan_sp_fp8(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
 
 // Static description of a scan configuration (host side planning).

@@ -49,10 +49,11 @@ __device__ inline const unsigned char *uniform_address(const void *ptr)
     return reinterpret_cast<const unsigned char *>(((uint64_t)hi << 32) | lo);
 }
 
-template <int KT_, int TQ_> struct WideCfg {
+template <int KT_, int TQ_, bool QF8_ = false> struct WideCfg {
     static constexpr int KT = KT_;
+    static constexpr bool QF8 = QF8_;                                // fp8 keys AND fp8 queries: the fp8 matrix instruction
     static constexpr int TK = 256, TQ = TQ_, THREADS = 512, NW = 8;
-    static constexpr int KEY_BYTES = KeyTraits<KT>::KEY_BYTES, QRY_BYTES = KeyTraits<KT>::QRY_BYTES;
+    static constexpr int KEY_BYTES = KeyTraits<KT>::KEY_BYTES, QRY_BYTES = QF8 ? 1 : KeyTraits<KT>::QRY_BYTES;
     static constexpr int RB = 128;                                   // bytes of a key / query row per d-chunk
     static constexpr int PIECE_ROWS = 128, PIECE_BYTES = PIECE_ROWS * RB;
     static constexpr int NB = TQ / PIECE_ROWS;                       // pieces of a query chunk
@@ -74,7 +75,9 @@ template <int KT_, int TQ_> struct WideCfg {
     static constexpr int SMEM_BYTES = OFF_QAUX + QAUX_BYTES;
     static constexpr int GROUPS_PER_TILE = 8;                // sampling groups: 2 pieces x 2 wave rows x 2 lane halves
     static constexpr int MIN_ROW_BYTES = 4 * RB;             // the key stream runs five pieces ahead of the MFMAs
-    static_assert(KT == KB_BF16 && KEY_BYTES == QRY_BYTES, "written for bf16 keys and queries");
+    static constexpr int KS = QF8 ? 2 : 4;                           // k-steps per chunk: 32 bytes per lane and MFMA for fp8, 16 for bf16
+    static_assert(((KT == KB_BF16 && !QF8) || (KT == KB_FP8_E4M3 && QF8 && TQ == 256)) && KEY_BYTES == QRY_BYTES,
+                  "written for bf16 keys and queries, and for fp8 keys with fp8 queries in 256-query blocks");
     static_assert(TQ == 256 || TQ == 128, "query blocks of 256 or 128");
     static_assert(NPA % 2 == 1, "the parity of the piece a phase issues is fixed in the code");
     static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget");
@@ -250,10 +253,25 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
     // ---- fragment addresses -------------------------------------------------------------------------------
     // piece-local row = 64 * (wave's half of the piece) + 32 * block + lrow; logical 16-byte slot of k-step kk = 2 kk + half
     // (kk << 5 only touches bits 5 and 6, a ring slot is a multiple of 16 KiB: the XOR can follow the addition)
-    const int baseA = (wm * 64 + lrow) * RB | ((half ^ swizzle<8>(lrow)) << 4);
+    constexpr bool F8 = C::QF8;
+    const int hslot = F8 ? 2 * half : half;                            // a lane's first 16-byte slot within a k-step
+    const int baseA = (wm * 64 + lrow) * RB | ((hslot ^ swizzle<8>(lrow)) << 4);
     const int qrow = wn * (32 * JB) + lrow;                            // this lane's query in block 0 of the wave
-    const int baseB = C::OFF_B + (qrow / C::PIECE_ROWS) * PB + ((qrow % C::PIECE_ROWS) * RB | ((half ^ swizzle<8>(lrow)) << 4));
-    auto read_f = [&](int addr, int kk, int blk) { return *(lds_u32x4 *)(lds + ((addr ^ (kk << 5)) + blk * 32 * RB)); };
+    const int baseB = C::OFF_B + (qrow / C::PIECE_ROWS) * PB + ((qrow % C::PIECE_ROWS) * RB | ((hslot ^ swizzle<8>(lrow)) << 4));
+    // bf16: 16 bytes of the row per lane and k-step (slot 2 kk + half); fp8: 32 bytes (slots 4 kk + 2 half, + 1)
+    typedef int i32x8 __attribute__((ext_vector_type(8)));
+    typedef int i32x4 __attribute__((ext_vector_type(4)));
+    typedef typename std::conditional<F8, i32x8, u32x4>::type Frag;
+    auto read_f = [&](int addr, int kk, int blk) {
+        if constexpr (F8) {
+            i32x8 v;
+            v.lo = __builtin_bit_cast(i32x4, *(lds_u32x4 *)(lds + ((addr ^ (kk << 6)) + blk * 32 * RB)));
+            v.hi = __builtin_bit_cast(i32x4, *(lds_u32x4 *)(lds + (((addr ^ (kk << 6)) ^ 16) + blk * 32 * RB)));
+            return v;
+        } else {
+            return *(lds_u32x4 *)(lds + ((addr ^ (kk << 5)) + blk * 32 * RB));
+        }
+    };
 
     f32x16 acc[2][IB][JB];
 #pragma unroll
@@ -302,15 +320,16 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
                 key_next(s & 1, true);
             }
             key_issue(0, 0);
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm(4 * (C::NPA - 2) + 1));   // piece 0 (and the side data before it) has landed
+            if (F8) key_issue(0, 1);                                   // (two loads per k-step there: two k-steps per phase)
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm(4 * (C::NPA - 2) + (F8 ? 2 : 1)));   // piece 0 (and the side data before it) has landed
         } else {
             issue_query_aux(vb % nqb);
 #pragma unroll
             for (int j = 0; j < 8; ++j) qry_issue(j);
             qry_next(true);
 #pragma unroll
-            for (int j = 0; j < 5; ++j) qry_issue(j);
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm(C::NB == 2 ? 5 : 4));     // chunk 0 (and the side data before it) has landed
+            for (int j = 0; j < (F8 ? 6 : 5); ++j) qry_issue(j);
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm(F8 ? 6 : C::NB == 2 ? 5 : 4));     // chunk 0 (and the side data before it) has landed
         }
         __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
         bare_barrier();
@@ -320,15 +339,18 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
         int f = 0;                                             // phase index
         // key fragments of one k-step in two sets (one in use, one being refilled); the query fragments of all four
         // k-steps of the chunk stay in registers for its second phase
-        u32x4 xa[IB], ya[IB], fb[4][JB];
+        Frag xa[IB], ya[IB], fb[C::KS][JB];
 #pragma unroll
         for (int ib = 0; ib < IB; ++ib) xa[ib] = read_f(baseA, 0, ib);
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb) fb[0][jb] = read_f(baseB, 0, jb);
 
-#define KBW_MFMA(RH, SA, SB, I, J)                                                                                                  \
-    acc[RH][I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, SA[I]), __builtin_bit_cast(bf16x8, SB[J]),   \
-                                                            acc[RH][I][J], 0, 0, 0);                                                \
+#define KBW_MFMA(RH, SA, SB, I, J)                                                                                              \
+    if constexpr (F8)                                                                                                           \
+        acc[RH][I][J] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(SA[I], SB[J], acc[RH][I][J], 0, 0, 0, 0, 0, 0);         \
+    else                                                                                                                        \
+        acc[RH][I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, SA[I]), __builtin_bit_cast(bf16x8, SB[J]), \
+                                                                acc[RH][I][J], 0, 0, 0);                                        \
     __builtin_amdgcn_sched_barrier(0)
         // one k-step: four MFMAs (two with 128-query blocks) on the key fragments SA and the query fragments fb[KU]; meanwhile the key fragments DA
         // are refilled from the piece at AA, k-step KR, and (KBW_KSTEP_AB) the query fragments fb[KR] from the chunk at
@@ -373,6 +395,24 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
     }                                                       \
     L3;                                                     \
     __builtin_amdgcn_sched_barrier(0)
+        // fp8: the MFMAs are twice as long and the fragments twice as wide, so the key fragments have ONE register set:
+        // block ib is refilled (piece at AA, k-step KR) right after its two MFMAs, two MFMAs before it is used again;
+        // two loads per k-step (L0, L1), since a phase has two k-steps
+#define KBW_KSTEP8(RH, KU, AA, KR, RB0, RB1, L0, L1) \
+    KBW_MFMA(RH, xa, fb[KU], 0, 0);                  \
+    RB0;                                             \
+    L0;                                              \
+    __builtin_amdgcn_sched_barrier(0);               \
+    KBW_MFMA(RH, xa, fb[KU], 0, 1);                  \
+    xa[0] = read_f(AA, KR, 0);                       \
+    RB1;                                             \
+    __builtin_amdgcn_sched_barrier(0);               \
+    KBW_MFMA(RH, xa, fb[KU], 1, 0);                  \
+    L1;                                              \
+    __builtin_amdgcn_sched_barrier(0);               \
+    KBW_MFMA(RH, xa, fb[KU], 1, 1);                  \
+    xa[1] = read_f(AA, KR, 1);                       \
+    __builtin_amdgcn_sched_barrier(0)
 #define KBW_NONE (void)0
 
         // The chunks of one item, for a wave of kind ROLE (the two kinds differ only in what they load and wait for,
@@ -399,16 +439,26 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
                     // query waves: chunk g+1 into the slots that barrier 2g-1 retired; key waves: piece f+NPA (second half
                     // of chunk g+2) into the slot that barrier f retires
                     __builtin_amdgcn_s_setprio(1);
-                    KBW_KSTEP_AB(0, xa, 0, ya, aa, ab, 1, KBW_NONE, KBW_NONE, if (ROLE == 0) key_issue(0, 1); else qry_issue(5), KBW_NONE);
-                    KBW_KSTEP_AB(0, ya, 1, xa, aa, ab, 2, KBW_NONE, KBW_NONE, if (ROLE == 0) key_issue(0, 2); else qry_issue(6), KBW_NONE);
-                    KBW_KSTEP_AB(0, xa, 2, ya, aa, ab, 3, KBW_NONE, KBW_NONE,
-                                 if (ROLE == 0) { key_issue(0, 3); key_next(0, true); } else { qry_issue(7); qry_next(g + 2 < total); }, KBW_NONE);
+                    if constexpr (!F8) {
+                        KBW_KSTEP_AB(0, xa, 0, ya, aa, ab, 1, KBW_NONE, KBW_NONE, if (ROLE == 0) key_issue(0, 1); else qry_issue(5), KBW_NONE);
+                        KBW_KSTEP_AB(0, ya, 1, xa, aa, ab, 2, KBW_NONE, KBW_NONE, if (ROLE == 0) key_issue(0, 2); else qry_issue(6), KBW_NONE);
+                        KBW_KSTEP_AB(0, xa, 2, ya, aa, ab, 3, KBW_NONE, KBW_NONE,
+                                     if (ROLE == 0) { key_issue(0, 3); key_next(0, true); } else { qry_issue(7); qry_next(g + 2 < total); }, KBW_NONE);
+                    } else {        // two k-steps per phase and two loads per k-step; the barrier comes after the first k-step
+                        KBW_KSTEP8(0, 0, aa, 1, fb[1][0] = read_f(ab, 1, 0), fb[1][1] = read_f(ab, 1, 1), if (ROLE == 0) key_issue(0, 2); else qry_issue(6),
+                                   if (ROLE == 0) { key_issue(0, 3); key_next(0, true); } else { qry_issue(7); qry_next(g + 2 < total); });
+                    }
                     __builtin_amdgcn_s_setprio(0);
                     wait_before_barrier(0);
                     // a new query block's side data: every epilogue of the previous item ended before this barrier
                     if (ROLE == 1 && nqb > 1 && c == 0 && g > 0) issue_query_aux(qb);
                     __builtin_amdgcn_s_setprio(1);
-                    KBW_KSTEP_A(0, ya, 3, xa, aan, 0, KBW_NONE, KBW_NONE, if (ROLE == 0) key_issue(1, 0); else qry_issue(0), KBW_NONE);
+                    if constexpr (!F8) {
+                        KBW_KSTEP_A(0, ya, 3, xa, aan, 0, KBW_NONE, KBW_NONE, if (ROLE == 0) key_issue(1, 0); else qry_issue(0), KBW_NONE);
+                    } else {
+                        KBW_KSTEP8(0, 1, aan, 0, KBW_NONE, KBW_NONE, if (ROLE == 0) key_issue(1, 0); else qry_issue(0),
+                                   if (ROLE == 0) key_issue(1, 1); else qry_issue(1));
+                    }
                     __builtin_amdgcn_s_setprio(0);
                     ra = ran;
                     ++f;
@@ -422,15 +472,25 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
                     const int aan = baseA + (more ? ran : ra) * PB, abn = baseB + (more ? rbn : rb) * PB;
                     // key waves: piece f+NPA (the first half of its chunk) and, before it, the side data of a new tile
                     __builtin_amdgcn_s_setprio(1);
-                    KBW_KSTEP_A(1, xa, 0, ya, aa, 1, KBW_NONE, KBW_NONE, if (ROLE == 0) key_issue(1, 1); else qry_issue(1), KBW_NONE);
-                    KBW_KSTEP_A(1, ya, 1, xa, aa, 2, KBW_NONE, KBW_NONE, if (ROLE == 0) key_issue(1, 2); else qry_issue(2), KBW_NONE);
-                    KBW_KSTEP_A(1, xa, 2, ya, aa, 3, KBW_NONE, KBW_NONE,
-                                if (ROLE == 0) { key_issue(1, 3); key_next(1, f + C::NPA < phases); } else qry_issue(3), KBW_NONE);
+                    if constexpr (!F8) {
+                        KBW_KSTEP_A(1, xa, 0, ya, aa, 1, KBW_NONE, KBW_NONE, if (ROLE == 0) key_issue(1, 1); else qry_issue(1), KBW_NONE);
+                        KBW_KSTEP_A(1, ya, 1, xa, aa, 2, KBW_NONE, KBW_NONE, if (ROLE == 0) key_issue(1, 2); else qry_issue(2), KBW_NONE);
+                        KBW_KSTEP_A(1, xa, 2, ya, aa, 3, KBW_NONE, KBW_NONE,
+                                    if (ROLE == 0) { key_issue(1, 3); key_next(1, f + C::NPA < phases); } else qry_issue(3), KBW_NONE);
+                    } else {
+                        KBW_KSTEP8(1, 0, aa, 1, KBW_NONE, KBW_NONE, if (ROLE == 0) key_issue(1, 2); else qry_issue(2),
+                                   if (ROLE == 0) { key_issue(1, 3); key_next(1, f + C::NPA < phases); } else qry_issue(3));
+                    }
                     __builtin_amdgcn_s_setprio(0);
                     wait_before_barrier(1);
                     if (ROLE == 0 && ld_c == 0 && f + C::NPA < phases) issue_tile_aux();
                     __builtin_amdgcn_s_setprio(1);
-                    KBW_KSTEP_AB(1, ya, 3, xa, aan, abn, 0, KBW_NONE, KBW_NONE, if (ROLE == 0) key_issue(0, 0); else qry_issue(4), KBW_NONE);
+                    if constexpr (!F8) {
+                        KBW_KSTEP_AB(1, ya, 3, xa, aan, abn, 0, KBW_NONE, KBW_NONE, if (ROLE == 0) key_issue(0, 0); else qry_issue(4), KBW_NONE);
+                    } else {
+                        KBW_KSTEP8(1, 1, aan, 0, fb[0][0] = read_f(abn, 0, 0), fb[0][1] = read_f(abn, 0, 1), if (ROLE == 0) key_issue(0, 0); else qry_issue(4),
+                                   if (ROLE == 0) key_issue(0, 1); else qry_issue(5));
+                    }
                     __builtin_amdgcn_s_setprio(0);
                     ra = ran;
                     rb = rbn;
@@ -452,6 +512,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
             }
         }
 #undef KBW_KSTEP_AB
+#undef KBW_KSTEP8
 #undef KBW_KSTEP_A
 #undef KBW_NONE
 #undef KBW_MFMA
@@ -467,7 +528,8 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
 template <class C> hipError_t launch_scan_wide_cfg(bool sample, int grid, const ScanArgs &a, hipStream_t s)
 {
     static bool attr_done[2] = {false, false};
-    auto *fn = sample ? &kb_scan_wide_kernel<C, true> : &kb_scan_wide_kernel<C, false>;
+    if (C::QF8 && sample) return hipErrorInvalidValue;     // fp8: the sampling pass runs the 64-byte-piece kernel (fewer registers)
+    auto *fn = (sample && !C::QF8) ? &kb_scan_wide_kernel<C, C::QF8 ? false : true> : &kb_scan_wide_kernel<C, false>;
     if (!attr_done[sample]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM_BYTES);
         if (e != hipSuccess) return e;

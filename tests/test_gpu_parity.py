@@ -107,6 +107,15 @@ def test_every_large_batch_fp8_scan_kernel(T, config):
     assert rep.queries == 300 and cnt["exhaustive_queries"] == 0
 
 
+@pytest.mark.parametrize("config", [5, 20])
+def test_every_fp8_query_scan_kernel(T, config):
+    """Both kernels built on the fp8 matrix instruction (64-byte and 128-byte row pieces): several items and query
+    blocks per workgroup, ragged last tile, checked against the oracle on the same codes."""
+    w = W.compressed(seed=29, N=50000 + 57, d=512, Q=600, k=32, centers=32, fp8_queries=True)
+    rep, cnt, _ = T.run_and_check(w, label=f"fp8 x fp8 scan config {config}", tuning={"scan_config": config})
+    assert rep.queries == 600 and cnt["exhaustive_queries"] == 0 and cnt["scan_workgroups"] == 256
+
+
 @pytest.mark.parametrize("N,d,Q,k", [(3000, 256, 33, 20), (130, 64, 1, 1), (5000, 128, 260, 7), (9000, 256, 260, 16)])
 def test_fp8_shapes(T, N, d, Q, k):
     w = W.compressed(seed=N, N=N, d=d, Q=Q, k=k, centers=8)
