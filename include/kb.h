@@ -20,8 +20,9 @@
  * device; everything else is host memory.  The library never allocates or
  * frees device memory: key storage is borrowed from the caller at kb_create
  * and kb_query works in a caller-provided workspace.  All device work is
- * enqueued on the caller's stream and no call synchronises (kb_query_counters
- * excepted).  A handle is not thread-safe.  Calls on one stream are ordered;
+ * enqueued on the caller's stream and no call synchronises, except the three
+ * that return a device value to the host: kb_query_counters, kb_profile_end
+ * and kb_compact.  A handle is not thread-safe.  Calls on one stream are ordered;
  * two kb_query calls may share a workspace only if they are stream-ordered.
  */
 #ifndef KB_H
@@ -76,7 +77,8 @@ kb_status_t kb_create(kb_t **out, int32_t d, kb_dtype_t key_dtype, int64_t capac
  * device-to-device on `hip_stream`; a source pointer equal to its destination
  * (rows already written in place by the caller) skips that copy.  The new rows
  * are not searchable until kb_normalize.  *first_index_out (host, may be NULL)
- * receives the index of the first new row.  n == 0 is a no-op.
+ * receives the index of the first new row; it is written only when the call
+ * returns KB_OK.  n == 0 is a no-op.
  * Errors: KB_ERR_NULL, KB_ERR_INVALID_ARG (n < 0), KB_ERR_CAPACITY, KB_ERR_DEVICE.
  */
 kb_status_t kb_append(kb_t *kb, const void *rows_dev, const float *row_scale_dev, const uint64_t *tags_dev,
@@ -91,11 +93,18 @@ kb_status_t kb_append(kb_t *kb, const void *rows_dev, const float *row_scale_dev
 kb_status_t kb_normalize(kb_t *kb, void *hip_stream);
 
 /*
- * Bytes of device workspace kb_query needs for up to Q queries and this k.
- * Sized for the handle's capacity, so it stays valid while rows are appended.
- * Returns 0 on invalid arguments.
+ * Bytes of device workspace that suffice for kb_query and kb_query_sampled with exactly Q queries and this k, at
+ * EVERY row count from 0 to the handle's capacity (an upper bound, not the need of the current size: it stays
+ * valid while rows are appended) and for every query dtype the handle accepts.  The value depends on the
+ * performance knobs of kb_set_tuning: ask again after changing one.  Returns 0 on invalid arguments.
+ *
+ * kb_query_plan_bytes is the host-side planner behind it: the bytes a query of `kind` (0: kb_query, 1:
+ * kb_query_sampled, 2: kb_query with KB_FP8_E4M3 queries) needs when the knowledge base holds n rows; 0 when the
+ * arguments are invalid or the handle does not take that kind of query.  For every n <= capacity it is at most
+ * kb_query_workspace_bytes(kb, Q, k).  No device work.
  */
 size_t kb_query_workspace_bytes(const kb_t *kb, int32_t Q, int32_t k);
+size_t kb_query_plan_bytes(const kb_t *kb, int64_t n, int32_t Q, int32_t k, int32_t kind);
 
 /*
  * Retrieval (Section 3: State Selector + top-k of the Optimization Selector).

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libkb.so")
-SOURCES = ["kb_api.hip", "kb_quantize.hip", "kb_maintain.hip", "kb_scan_bf16.hip", "kb_scan_f32.hip", "kb_scan_fp8.hip", "kb_scan_pp_bf16.hip", "kb_scan_big_bf16.hip", "kb_scan_sp_bf16.hip", "kb_scan_sp_fp8.hip", "kb_scan_wide_bf16.hip", "kb_scan_wide_fp8.hip"]
+SOURCES = ["kb_api.hip", "kb_quantize.hip", "kb_maintain.hip", "kb_scan_bf16.hip", "kb_scan_f32.hip", "kb_scan_fp8.hip", "kb_scan_sp_bf16.hip", "kb_scan_sp_fp8.hip", "kb_scan_wide_bf16.hip", "kb_scan_wide_fp8.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-I", INCLUDE, "-I", CSRC, "-Wall", "-Wno-unused-value"]

@@ -33,26 +33,11 @@ bool scan_config_info(int key_dtype, int config, ConfigInfo *out)
     KB_SCAN_CONFIGS_F32(X)
     KB_SCAN_CONFIGS_FP8(X)
 #undef X
-#define XP(ID, KT, TQ, NSA, NSB)                                              \
-    if (key_dtype == KT && config == ID) {                                    \
-        *out = ConfigInfo{256, TQ, 512, 8, 1, 64 * 2 * NSA, 1};               \
-        return true;                                                          \
-    }
-    KB_SCAN_PP_CONFIGS_BF16(XP)
-#undef XP
-#define XB(ID, KT, NSA, NSB)                                                  \
-    if (key_dtype == KT && config == ID) {                                    \
-        *out = ConfigInfo{256, 256, 256, 4, 1, 64 * 2 * (NSA > NSB ? NSA : NSB), 2}; \
-        return true;                                                          \
-    }
-    KB_SCAN_BIG_CONFIGS_BF16(XB)
-#undef XB
 #define XS(ID, KT, TQ, NSA, NSB)                                              \
     if (key_dtype == KT && config == ID) {                                    \
         *out = ConfigInfo{256, TQ, 512, 8, 1, 64 * ((NSA > NSB ? NSA : NSB) + 1), 3}; \
         return true;                                                          \
     }
-    KB_SCAN_SP_CONFIGS_BF16(XS)
     KB_SCAN_SP_CONFIGS_BF16_IL(XS)
     KB_SCAN_SP_CONFIGS_FP8(XS)
     KB_SCAN_SP_CONFIGS_FP8_Q8(XS)
@@ -84,7 +69,8 @@ int scan_config_for(int key_dtype, int Q, int d, int64_t n)
 
 namespace {
 
-constexpr int ASSUMED_CUS = 256;       // MI355X; used for sizing before a device is touched
+constexpr int DEVICE_CUS = 256;        // compute units of an MI355X: the scan grids are sized for them (a device with fewer runs the same grid in turns)
+constexpr int MIN_REGION_CAP = 256;    // records per scan wavefront, at least
 constexpr int MAX_SAMPLE_SLOTS = 8192; // threshold_kernel sorts this many 64-bit words in LDS (64 KiB)
 constexpr int MAX_CAND_CAP = 8192;     // finalize_kernel likewise
 constexpr int MIN_CAND_CAP = 1024;
@@ -124,104 +110,209 @@ uint64_t scatter_multiplier(int64_t n)
     }
 }
 
-// Pure function of (handle settings, row count n, Q, k): which kernels run on what, and where
-// everything lives in the workspace.
-bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, bool draw, bool q8, Plan *out)
+// ------------------------------------------------------------------------------------------------
+// Planning: which kernels a query runs, how large its buffers are, where they live in the workspace.
+// ------------------------------------------------------------------------------------------------
+struct Choice {                 // kernels of a query over n rows
+    int config;
+    ConfigInfo ci;
+    int sample_config;          // the sampling pass may run another configuration (same tile, bit-identical scores)
+    ConfigInfo sci;
+};
+
+bool choose_kernels(const kb *h, int64_t n, int32_t Q, bool draw, bool q8, Choice *out)
+{
+    Choice c;
+    const int generic = Q <= 32 ? 1 : Q <= 128 ? 2 : 3;        // the tiled kernel: every dtype, every row length
+    const size_t row_bytes = (size_t)h->d * key_bytes(h->dtype);
+    if (q8) {       // fp8 queries: only the kernels built on the fp8 matrix instruction take them
+        if (draw || h->dtype != KB_FP8_E4M3) return false;
+        c.config = (row_bytes % 128 == 0 && row_bytes >= 512) ? FP8_QUERY_WIDE_CONFIG : FP8_QUERY_CONFIG;
+        if (h->tune_config == FP8_QUERY_CONFIG) c.config = FP8_QUERY_CONFIG;         // the other one can be asked for
+        if (!scan_config_info(h->dtype, c.config, &c.ci) || row_bytes < (size_t)c.ci.min_row_bytes) return false;
+    } else {
+        c.config = h->tune_config > 0 ? (int)h->tune_config : scan_config_for(h->dtype, Q, h->d, n);
+        if (!scan_config_info(h->dtype, c.config, &c.ci)) return false;
+        // fall back where a (forced) configuration does not apply: the weighted random selection exists in the
+        // tiled kernel only, rows may be too short for a pipelined kernel, and the fp8-query kernels read fp8 queries
+        if ((draw && c.ci.family != 0) || row_bytes < (size_t)c.ci.min_row_bytes ||
+            (h->dtype == KB_FP8_E4M3 && (c.config == FP8_QUERY_CONFIG || c.config == FP8_QUERY_WIDE_CONFIG))) {
+            c.config = generic;
+            if (!scan_config_info(h->dtype, c.config, &c.ci)) return false;
+        }
+    }
+    c.sci = c.ci;
+    c.sample_config = c.config;
+    if (c.ci.family == 4 && h->dtype == KB_FP8_E4M3) {       // the fp8 full-line kernel is a main pass only
+        c.sample_config = FP8_QUERY_CONFIG;
+        if (!scan_config_info(h->dtype, c.sample_config, &c.sci) || c.sci.tq != c.ci.tq || c.sci.tk != c.ci.tk) return false;
+    }
+    *out = c;
+    return true;
+}
+
+// Key tiles the sampling pass scores when the knowledge base has nt tiles: max(k, 8) / 512 of them (1/64 of the
+// rows up to k = 8, 1/16 at k = 32, 1/4 at k = 128), at least two samples per wanted result, at most what the
+// threshold kernel sorts and half of the tiles.  0 = no sampling pass (every entry is a candidate).  Depends on the
+// row count through nt only, and never falls as nt grows (`floor` switched off).
+int64_t sample_tiles_for(const kb *h, const ConfigInfo &sci, int64_t nt, int32_t k, bool floor)
+{
+    if (nt < 8) return 0;
+    const int64_t kk = k > 8 ? k : 8;
+    int64_t st = h->tune_sample_keys > 0 ? ceil_div(h->tune_sample_keys, sci.tk) : ceil_div(nt * kk, 512);
+    const int64_t want = ceil_div(2 * (int64_t)k, sci.groups_per_tile);
+    if (st < want) st = want;
+    if (st > MAX_SAMPLE_SLOTS / sci.groups_per_tile) st = MAX_SAMPLE_SLOTS / sci.groups_per_tile;
+    if (st > nt / 2) st = nt / 2;
+    if (floor && st * sci.groups_per_tile < k) st = 0;
+    return st;
+}
+
+int32_t cand_cap_for(int64_t expect, bool sampled)
+{
+    int64_t cc = pow2_ceil(sampled ? 8 * expect : expect);
+    if (cc < MIN_CAND_CAP) cc = MIN_CAND_CAP;
+    if (cc > MAX_CAND_CAP) cc = MAX_CAND_CAP;
+    return (int32_t)cc;
+}
+
+// Sizes of the workspace arrays.  The layout is a function of these alone and its total grows with each of them.
+struct Sizes {
+    int32_t k, qpad, regions, sample_slots, cand_cap;
+    int64_t region_records;     // regions * region_cap
+    int64_t lgain_rows;
+};
+
+void lay_out(const Sizes &z, Plan *p)
+{
+    size_t off = 0;
+    p->off_stats = off;       off = align_up(off + sizeof(uint64_t) * (STAT_WORDS + STAT_PARTIALS));   // always first: kb_query_counters reads it
+    p->off_invq = off;        off = align_up(off + sizeof(float) * z.qpad);
+    p->off_thr64 = off;       off = align_up(off + sizeof(uint64_t) * z.qpad);
+    p->off_thrp = off;        off = align_up(off + sizeof(float) * z.qpad);
+    p->off_cnt = off;         off = align_up(off + sizeof(uint32_t) * z.qpad * CAND_SEGMENTS);
+    p->off_flag = off;        off = align_up(off + sizeof(uint32_t) * z.qpad);
+    p->fb_parts = z.cand_cap / KB_K_MAX < FALLBACK_PARTS ? z.cand_cap / KB_K_MAX : FALLBACK_PARTS;     // parts * k words fit the LDS buffer
+    p->off_fb_done = off;     off = align_up(off + sizeof(uint32_t) * z.qpad);
+    p->off_fb_lists = off;    off = align_up(off + sizeof(uint64_t) * (size_t)z.qpad * p->fb_parts * z.k);
+    p->off_region_cnt = off;  off = align_up(off + sizeof(uint32_t) * z.regions);
+    p->off_qmask = off;       off = align_up(off + sizeof(uint64_t) * z.qpad);
+    p->off_samp = off;        off = align_up(off + sizeof(uint64_t) * (size_t)z.qpad * (z.sample_slots > 0 ? z.sample_slots : 1));
+    p->off_regions = off;     off = align_up(off + sizeof(Record) * (size_t)z.region_records);
+    p->off_cand = off;        off = align_up(off + sizeof(uint64_t) * (size_t)z.qpad * z.cand_cap);
+    p->off_lgain = off;       off = align_up(off + sizeof(float) * (size_t)z.lgain_rows);   // ln(gain), padded past the last tile
+    p->total = off;
+}
+
+// The plan of a query over n rows with the kernels `c`.  Apart from the ln(gain) array it depends on n through the
+// number of key tiles only, which is what lets kb_query_workspace_bytes bound it over all row counts.
+void plan_for(const kb *h, const Choice &c, int64_t n, int32_t Q, int32_t k, Plan *out, Sizes *sizes)
 {
     Plan p;
     memset(&p, 0, sizeof p);
+    const ConfigInfo &ci = c.ci, &sci = c.sci;
     p.Q = Q;
     p.k = k;
-    ConfigInfo ci;
-    const int generic = Q <= 32 ? 1 : Q <= 128 ? 2 : 3;        // the tiled kernel: every dtype, every row length
-    const size_t row_bytes = (size_t)h->d * key_bytes(h->dtype);
-    if (q8) {       // fp8 queries: only the kernel built on the fp8 matrix instruction takes them
-        if (draw || h->dtype != KB_FP8_E4M3) return false;
-        p.config = (row_bytes % 128 == 0 && row_bytes >= 512) ? FP8_QUERY_WIDE_CONFIG : FP8_QUERY_CONFIG;
-        if (h->tune_config == FP8_QUERY_CONFIG) p.config = FP8_QUERY_CONFIG;         // the other one can be asked for
-        if (!scan_config_info(h->dtype, p.config, &ci) || row_bytes < (size_t)ci.min_row_bytes) return false;
-    } else {
-        p.config = h->tune_config > 0 ? (int)h->tune_config : scan_config_for(h->dtype, Q, h->d, n);
-        if (!scan_config_info(h->dtype, p.config, &ci)) return false;
-        // fall back where a (forced) configuration does not apply: the weighted random selection exists in the
-        // tiled kernel only, rows may be too short for a pipelined kernel, and the fp8-query kernel reads fp8 queries
-        if ((draw && ci.family != 0) || row_bytes < (size_t)ci.min_row_bytes ||
-            (h->dtype == KB_FP8_E4M3 && (p.config == FP8_QUERY_CONFIG || p.config == FP8_QUERY_WIDE_CONFIG))) {
-            p.config = generic;
-            if (!scan_config_info(h->dtype, p.config, &ci)) return false;
-        }
-    }
+    p.config = c.config;
     p.family = ci.family;
     p.tk = ci.tk;
     p.tq = ci.tq;
     p.groups_per_tile = ci.groups_per_tile;
     p.nqb = (int32_t)ceil_div(Q, ci.tq);
     p.qpad = p.nqb * ci.tq;
-    if (n < 1) n = 1;
-    const int64_t n_tiles = ceil_div(n, ci.tk);
-
-    // The sampling pass may run another scan configuration than the main pass (same query block width; every
-    // kernel produces bit-identical scores, so thresholds carry over).
-    ConfigInfo sci = ci;
-    p.sample_config = p.config;
-    if (ci.family == 4 && h->dtype == KB_FP8_E4M3) {       // the fp8 full-line kernel is a main pass only
-        p.sample_config = FP8_QUERY_CONFIG;
-        if (!scan_config_info(h->dtype, p.sample_config, &sci) || sci.tq != ci.tq || sci.tk != ci.tk) return false;
-    }
+    p.sample_config = c.sample_config;
     p.sample_family = sci.family;
     p.sample_wgpc = sci.wg_per_cu;
-    const int64_t s_tiles_all = ceil_div(n, sci.tk);
-    int64_t st = 0;
-    if (n_tiles >= 8) {
-        int64_t m = h->tune_sample_keys > 0 ? h->tune_sample_keys : ((int64_t)k * n / 512 > n / 64 ? (int64_t)k * n / 512 : n / 64);
-        st = ceil_div(m, sci.tk);
-        const int64_t want = ceil_div(2 * (int64_t)k, sci.groups_per_tile);
-        if (st < want) st = want;
-        if (st > MAX_SAMPLE_SLOTS / sci.groups_per_tile) st = MAX_SAMPLE_SLOTS / sci.groups_per_tile;
-        if (st > s_tiles_all / 2) st = s_tiles_all / 2;
-        if (st * sci.groups_per_tile < k) st = 0;
-    }
+    if (n < 1) n = 1;
+    const int64_t nt = ceil_div(n, ci.tk);
+
+    const int64_t st = sample_tiles_for(h, sci, nt, k, true);
     p.sample_tiles = st;
     p.sample_slots = (int32_t)(st * sci.groups_per_tile);
     p.sample_keys = st * sci.tk;
+    const int64_t expect = st > 0 ? ceil_div((int64_t)k * nt, st) : nt * ci.tk;      // candidates per query
+    p.cand_cap = cand_cap_for(expect, st > 0);
 
-    const int64_t expect = st > 0 ? ceil_div((int64_t)k * n, st * sci.tk) : n;   // candidates per query
-    int64_t cc = pow2_ceil(st > 0 ? 8 * expect : expect);
-    if (cc < MIN_CAND_CAP) cc = MIN_CAND_CAP;
-    if (cc > MAX_CAND_CAP) cc = MAX_CAND_CAP;
-    p.cand_cap = (int32_t)cc;
-
-    const int cus = h->cu_count > 0 ? h->cu_count : ASSUMED_CUS;
     const int wgpc = h->tune_wg_per_cu > 0 ? (int)h->tune_wg_per_cu : ci.wg_per_cu;
-    int64_t grid = n_tiles * p.nqb;
-    if (grid > (int64_t)cus * wgpc) grid = (int64_t)cus * wgpc;
+    const int64_t items = nt * p.nqb;
+    const int64_t grid = items < (int64_t)DEVICE_CUS * wgpc ? items : (int64_t)DEVICE_CUS * wgpc;
     p.grid = (int32_t)grid;
     const int waves = ci.threads / 64;
     p.regions = (int32_t)(grid * waves);
-    int64_t rc = pow2_ceil(8 * ceil_div(expect * Q, grid * waves));     // per wavefront, 8x the even share
-    if (rc < 256) rc = 256;
-    if (rc > (1 << 22)) rc = 1 << 22;
+    // records per scan wavefront.  With a sampling pass: the share of a query block's lists (8 x the expected number
+    // of candidates) that falls to a wavefront if candidates are spread evenly; a region that overflows flags the
+    // query.  Without one every scored pair is a record: the pairs of the wavefront's part of its workgroup's items.
+    int64_t rc = st > 0 ? pow2_ceil(ceil_div((int64_t)p.cand_cap * Q, p.regions)) : pow2_ceil(ceil_div(items, grid) * ci.tk * ci.tq / waves);
+    if (rc < MIN_REGION_CAP) rc = MIN_REGION_CAP;
     p.region_cap = (int32_t)rc;
 
-    size_t off = 0;
-    p.off_stats = off;       off = align_up(off + sizeof(uint64_t) * (STAT_WORDS + STAT_PARTIALS));   // always first: kb_query_counters reads it
-    p.off_invq = off;        off = align_up(off + sizeof(float) * p.qpad);
-    p.off_thr64 = off;       off = align_up(off + sizeof(uint64_t) * p.qpad);
-    p.off_thrp = off;        off = align_up(off + sizeof(float) * p.qpad);
-    p.off_cnt = off;         off = align_up(off + sizeof(uint32_t) * p.qpad * CAND_SEGMENTS);
-    p.off_flag = off;        off = align_up(off + sizeof(uint32_t) * p.qpad);
-    p.fb_parts = p.cand_cap / KB_K_MAX < FALLBACK_PARTS ? p.cand_cap / KB_K_MAX : FALLBACK_PARTS;     // parts * k words fit the LDS buffer
-    p.off_fb_done = off;     off = align_up(off + sizeof(uint32_t) * p.qpad);
-    p.off_fb_lists = off;    off = align_up(off + sizeof(uint64_t) * (size_t)p.qpad * p.fb_parts * k);
-    p.off_region_cnt = off;  off = align_up(off + sizeof(uint32_t) * p.regions);
-    p.off_qmask = off;       off = align_up(off + sizeof(uint64_t) * p.qpad);
-    p.off_samp = off;        off = align_up(off + sizeof(uint64_t) * (size_t)p.qpad * (p.sample_slots > 0 ? p.sample_slots : 1));
-    p.off_regions = off;     off = align_up(off + sizeof(Record) * (size_t)p.regions * p.region_cap);
-    p.off_cand = off;        off = align_up(off + sizeof(uint64_t) * (size_t)p.qpad * p.cand_cap);
-    p.off_lgain = off;       off = align_up(off + sizeof(float) * (size_t)(ceil_div(n, 256) * 256 + 256));   // ln(gain), padded past the last tile
-    p.total = off;
+    Sizes z;
+    z.k = k;
+    z.qpad = p.qpad;
+    z.regions = p.regions;
+    z.sample_slots = p.sample_slots;
+    z.cand_cap = p.cand_cap;
+    z.region_records = (int64_t)p.regions * rc;
+    z.lgain_rows = ceil_div(n, 256) * 256 + 256;
+    lay_out(z, &p);
     *out = p;
+    if (sizes) *sizes = z;
+}
+
+// Pure function of (handle settings, row count n, Q, k): which kernels run on what, and where everything lives
+// in the workspace.
+bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, bool draw, bool q8, Plan *out)
+{
+    Choice c;
+    if (!choose_kernels(h, n, Q, draw, q8, &c)) return false;
+    plan_for(h, c, n, Q, k, out, nullptr);
     return true;
+}
+
+void max_into(Sizes &m, const Sizes &z)
+{
+    m.k = z.k;
+    if (z.qpad > m.qpad) m.qpad = z.qpad;
+    if (z.regions > m.regions) m.regions = z.regions;
+    if (z.sample_slots > m.sample_slots) m.sample_slots = z.sample_slots;
+    if (z.cand_cap > m.cand_cap) m.cand_cap = z.cand_cap;
+    if (z.region_records > m.region_records) m.region_records = z.region_records;
+    if (z.lgain_rows > m.lgain_rows) m.lgain_rows = z.lgain_rows;
+}
+
+// Upper bound of the Sizes of plan_for(h, c, n, ...) over every n in [1, capacity].
+//   Up to EXACT_TILES key tiles the plans are enumerated (one per tile count; this range contains every case without
+//   a sampling pass: sample_tiles_for gives at least min(2k / groups, nt / 2) tiles, which is k samples once nt >= 256).
+//   Beyond, with st = sample_tiles_for(nt) > 0 and expect = ceil(k nt / st):
+//     st = ceil(nt max(k, 8) / 512), or raised to 2k / groups:  expect <= 512
+//     st = nt / 2 (rounded down):                               expect <= 2k + 1 <= 257
+//     st = MAX_SAMPLE_SLOTS / groups:                           expect grows with nt, largest at the capacity
+//   (with the "sample_keys" knob st does not follow nt: the largest candidate capacity is assumed), so cand_cap is
+//   bounded; regions and sample_slots do not fall as nt grows; and regions * region_cap with
+//   region_cap = max(MIN_REGION_CAP, pow2_ceil(ceil(cand_cap Q / regions))) is below
+//   max(MIN_REGION_CAP regions, 2 (cand_cap Q + regions)).
+constexpr int64_t EXACT_TILES = 256;
+void bound_sizes(const kb *h, const Choice &c, int32_t Q, int32_t k, Sizes &m)
+{
+    const ConfigInfo &ci = c.ci, &sci = c.sci;
+    const int64_t cap_nt = ceil_div(h->capacity, ci.tk);
+    Plan p;
+    Sizes z;
+    for (int64_t nt = 1; nt <= cap_nt && nt <= EXACT_TILES; ++nt) {
+        plan_for(h, c, nt * ci.tk, Q, k, &p, &z);
+        max_into(m, z);
+    }
+    plan_for(h, c, h->capacity, Q, k, &p, &z);       // the ln(gain) array, and the largest grid
+    max_into(m, z);
+    if (cap_nt <= EXACT_TILES) return;
+    int64_t expect = 512;
+    const int64_t at_cap = ceil_div((int64_t)k * cap_nt * sci.groups_per_tile, MAX_SAMPLE_SLOTS);
+    if (at_cap > expect) expect = at_cap;
+    z.cand_cap = h->tune_sample_keys > 0 ? MAX_CAND_CAP : cand_cap_for(expect, true);
+    z.sample_slots = (int32_t)(sample_tiles_for(h, sci, cap_nt, k, false) * sci.groups_per_tile);
+    const int64_t floor_records = (int64_t)MIN_REGION_CAP * z.regions, spread = 2 * ((int64_t)z.cand_cap * Q + z.regions);
+    z.region_records = floor_records > spread ? floor_records : spread;
+    max_into(m, z);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -773,8 +864,6 @@ __global__ __launch_bounds__(256) void probe_merge_kernel(const uint64_t *lists,
 
 hipError_t launch_scan(kb_dtype_t dt, int config, int family, bool sample, int grid, const ScanArgs &a, hipStream_t s)
 {
-    if (family == 1) return dt == KB_BF16 ? launch_scan_pp_bf16(config, sample, grid, a, s) : hipErrorInvalidValue;
-    if (family == 2) return dt == KB_BF16 ? launch_scan_big_bf16(config, sample, grid, a, s) : hipErrorInvalidValue;
     if (family == 4)
         return dt == KB_BF16 ? launch_scan_wide_bf16(config, sample, grid, a, s)
                : dt == KB_FP8_E4M3 ? launch_scan_wide_fp8(config, sample, grid, a, s) : hipErrorInvalidValue;
@@ -821,7 +910,6 @@ kb_status_t kb_create(kb_t **out, int32_t d, kb_dtype_t key_dtype, int64_t capac
     h->inv_norm = inv_norm_dev;
     h->tags = tags_dev;
     h->tune_sample_keys = h->tune_config = h->tune_wg_per_cu = h->tune_no_small_path = 0;
-    h->cu_count = 0;
     h->prof_events = nullptr;
     h->prof_max = h->prof_used = 0;
     *out = h;
@@ -833,8 +921,10 @@ kb_status_t kb_append(kb_t *kb, const void *rows_dev, const float *row_scale_dev
 {
     if (!kb) return KB_ERR_NULL;
     if (n < 0) return KB_ERR_INVALID_ARG;
-    if (first_index_out) *first_index_out = kb->n;
-    if (n == 0) return KB_OK;
+    if (n == 0) {
+        if (first_index_out) *first_index_out = kb->n;
+        return KB_OK;
+    }
     if (!rows_dev) return KB_ERR_NULL;
     if (kb->dtype == KB_FP8_E4M3 && !row_scale_dev) return KB_ERR_NULL;
     if (kb->tags && !tags_dev) return KB_ERR_NULL;
@@ -850,6 +940,7 @@ kb_status_t kb_append(kb_t *kb, const void *rows_dev, const float *row_scale_dev
     if (kb->tags && kb->tags + kb->n != tags_dev &&
         hipMemcpyAsync(kb->tags + kb->n, tags_dev, sizeof(uint64_t) * n, hipMemcpyDeviceToDevice, s) != hipSuccess)
         return KB_ERR_DEVICE;
+    if (first_index_out) *first_index_out = kb->n;
     kb->n += n;
     return KB_OK;
 }
@@ -879,7 +970,7 @@ namespace {
 // Parts a cluster's rows are split into, so that a small batch still fills the device: a function of (Q, nprobe) only.
 int probe_splits(int Q, int nprobe)
 {
-    int64_t s = (4 * (int64_t)ASSUMED_CUS + (int64_t)Q * nprobe - 1) / ((int64_t)Q * nprobe);
+    int64_t s = (4 * (int64_t)DEVICE_CUS + (int64_t)Q * nprobe - 1) / ((int64_t)Q * nprobe);
     if (s > 16) s = 16;
     if (s > PROBE_MAX_LISTS / nprobe) s = PROBE_MAX_LISTS / nprobe;
     return s < 1 ? 1 : (int)s;
@@ -945,13 +1036,9 @@ kb_status_t launch_probe(kb *h, bool timed_scan, const void *queries_dev, kb_dty
     }
     const int n_lists = nprobe * splits;
     const size_t merge_lds = sizeof(uint64_t) * (size_t)(n_lists * k > k ? n_lists * k : k) + 16 + sizeof(SelectScratch);
-    static bool merge_attr = false;
-    if (!merge_attr) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&probe_merge_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                MAX_CAND_CAP * 8 + 16 + sizeof(SelectScratch)) != hipSuccess)
-            return KB_ERR_DEVICE;
-        merge_attr = true;
-    }
+    static LdsAllowed merge_allowed;
+    if (allow_dynamic_lds(reinterpret_cast<const void *>(&probe_merge_kernel), merge_allowed, MAX_CAND_CAP * 8 + 16 + sizeof(SelectScratch)) != hipSuccess)
+        return KB_ERR_DEVICE;
     hipLaunchKernelGGL(probe_merge_kernel, dim3(Q), dim3(256), merge_lds, s, lists, n_lists, k, indices_out_dev, scores_out_dev);
     return hipGetLastError() == hipSuccess ? KB_OK : KB_ERR_DEVICE;
 }
@@ -986,31 +1073,32 @@ SmallPlan make_small_plan(int32_t Q, int32_t k, int parts)
 size_t kb_query_workspace_bytes(const kb_t *kb, int32_t Q, int32_t k)
 {
     if (!kb || Q < 1 || k < 1 || k > KB_K_MAX) return 0;
-    size_t best = 0;
-    // the plan depends on the row count at query time: take the largest over a ladder of row counts
-    for (int64_t n = kb->capacity; n >= 1; n = n / 2) {
-        Plan p;
-        for (int draw = 0; draw < 2; ++draw) {
-            if (!make_plan(kb, n, Q, k, draw != 0, false, &p)) return 0;
-            if (p.total > best) best = p.total;
+    // Every combination of kernels a query on this handle can run (the choice depends on the row count only through
+    // the two sides of WIDE128_MIN_ROWS, and on the kind of query), each bounded over all row counts.
+    Sizes m;
+    memset(&m, 0, sizeof m);
+    bool any = false;
+    const int64_t ns[2] = {1, kb->capacity};
+    for (int64_t n : ns)
+        for (int kind = 0; kind < 3; ++kind) {      // plain, weighted random selection, fp8 queries
+            Choice c;
+            if (!choose_kernels(kb, n, Q, kind == 1, kind == 2, &c)) continue;
+            bound_sizes(kb, c, Q, k, m);
+            any = true;
         }
-        if (make_plan(kb, n, Q, k, false, true, &p) && p.total > best) best = p.total;     // fp8 queries, where they apply
-        if (n == 1) break;
-    }
-    for (int64_t n = 1; n <= kb->capacity && n < (int64_t)1 << 16; n += 61) {   // and the small, irregular sizes
-        Plan p;
-        for (int draw = 0; draw < 2; ++draw) {
-            if (!make_plan(kb, n, Q, k, draw != 0, false, &p)) return 0;
-            if (p.total > best) best = p.total;
-        }
-        if (make_plan(kb, n, Q, k, false, true, &p) && p.total > best) best = p.total;
-    }
-    for (int64_t n : {(int64_t)WIDE128_MIN_ROWS - 1, (int64_t)WIDE128_MIN_ROWS}) {     // either side of a kernel choice that depends on the row count
-        Plan p;
-        if (n <= kb->capacity && make_plan(kb, n, Q, k, false, false, &p) && p.total > best) best = p.total;
-    }
+    if (!any) return 0;
+    Plan p;
+    lay_out(m, &p);
     const size_t small = make_small_plan(Q, k, PROBE_MAX_LISTS).total;      // the path of small knowledge bases
-    return best > small ? best : small;
+    return p.total > small ? p.total : small;
+}
+
+size_t kb_query_plan_bytes(const kb_t *kb, int64_t n, int32_t Q, int32_t k, int32_t kind)
+{
+    if (!kb || n < 0 || n > kb->capacity || Q < 1 || k < 1 || k > KB_K_MAX || kind < 0 || kind > 2) return 0;
+    if (const int parts = small_path_parts(kb, n, Q, kind == 1)) return make_small_plan(Q, k, parts).total;
+    Plan p;
+    return make_plan(kb, n, Q, k, kind == 1, kind == 2, &p) ? p.total : 0;
 }
 
 // kb_query and kb_query_sampled: the same pipeline; `gain_dev` != nullptr selects the weighted random selection.
@@ -1035,12 +1123,6 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
     if (qmask_dev && !kb->tags) return KB_ERR_NO_TAGS;
     if (kb->n_normalized != kb->n) return KB_ERR_NOT_NORMALIZED;
     if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) & (WS_ALIGN - 1)) != 0) return KB_ERR_WORKSPACE;
-    if (kb->cu_count == 0) {
-        int cus = 0;
-        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, 0) != hipSuccess || cus < 1) return KB_ERR_DEVICE;
-        // the workspace was sized for ASSUMED_CUS; a larger device just runs the same grid
-        kb->cu_count = cus < ASSUMED_CUS ? cus : ASSUMED_CUS;
-    }
     if (const int parts = small_path_parts(kb, kb->n, Q, draw)) {
         const SmallPlan sp = make_small_plan(Q, k, parts);
         if (workspace_bytes < sp.total) return KB_ERR_WORKSPACE;
@@ -1131,18 +1213,14 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
             a.row_run_shift = draw ? 2 : 0;
             a.row_mul = (p.sample_family == 0 || p.sample_family == 3 || p.sample_family == 4) ? scatter_multiplier(kb->n >> a.row_run_shift) : 0;
             int64_t sgrid = p.sample_tiles * p.nqb;
-            const int64_t smax = (int64_t)(kb->cu_count > 0 ? kb->cu_count : ASSUMED_CUS) * p.sample_wgpc;
+            const int64_t smax = (int64_t)DEVICE_CUS * p.sample_wgpc;
             if (sgrid > smax) sgrid = smax;
             if (launch_scan(kb->dtype, p.sample_config, p.sample_family, true, (int)sgrid, a, s) != hipSuccess) return KB_ERR_DEVICE;
             const int thr_threads = p.sample_slots > 1024 ? 1024 : p.sample_slots > 512 ? 512 : 256;
             const size_t thr_lds = sizeof(uint64_t) * (p.sample_slots > k ? p.sample_slots : k) + sizeof(SelectScratch);
-            static bool thr_attr = false;
-            if (!thr_attr) {
-                if (hipFuncSetAttribute(reinterpret_cast<const void *>(&threshold_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        MAX_SAMPLE_SLOTS * 8 + sizeof(SelectScratch)) != hipSuccess)
-                    return KB_ERR_DEVICE;
-                thr_attr = true;
-            }
+            static LdsAllowed thr_allowed;
+            if (allow_dynamic_lds(reinterpret_cast<const void *>(&threshold_kernel), thr_allowed, MAX_SAMPLE_SLOTS * 8 + sizeof(SelectScratch)) != hipSuccess)
+                return KB_ERR_DEVICE;
             hipLaunchKernelGGL(threshold_kernel, dim3(Q), dim3(thr_threads), thr_lds, s, samp, p.sample_slots, k, invq, thr64, thrp, draw ? 1 : 0);
             if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
         }
@@ -1182,16 +1260,13 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
     f.fb_lists = reinterpret_cast<uint64_t *>(ws + p.off_fb_lists);
     f.fb_parts = p.fb_parts;
     const size_t fin_lds = (size_t)p.cand_cap * 8 + 16 + sizeof(SelectScratch);
-    static bool fin_attr[4] = {false, false, false, false};
+    static LdsAllowed fin_allowed[4];
     const int fin_kind = q8 ? KT_FP8_Q8 : (int)kb->dtype;
     const void *fin_fn = fin_kind == KB_F32 ? reinterpret_cast<const void *>(&finalize_kernel<KB_F32>)
                        : fin_kind == KB_BF16 ? reinterpret_cast<const void *>(&finalize_kernel<KB_BF16>)
                        : fin_kind == KB_FP8_E4M3 ? reinterpret_cast<const void *>(&finalize_kernel<KB_FP8_E4M3>)
                                                  : reinterpret_cast<const void *>(&finalize_kernel<KT_FP8_Q8>);
-    if (!fin_attr[fin_kind]) {
-        if (hipFuncSetAttribute(fin_fn, hipFuncAttributeMaxDynamicSharedMemorySize, MAX_CAND_CAP * 8 + 16 + sizeof(SelectScratch)) != hipSuccess) return KB_ERR_DEVICE;
-        fin_attr[fin_kind] = true;
-    }
+    if (allow_dynamic_lds(fin_fn, fin_allowed[fin_kind], MAX_CAND_CAP * 8 + 16 + sizeof(SelectScratch)) != hipSuccess) return KB_ERR_DEVICE;
     switch (fin_kind) {
     case KB_F32: hipLaunchKernelGGL(finalize_kernel<KB_F32>, dim3(Q, p.fb_parts), dim3(256), fin_lds, s, f); break;
     case KB_BF16: hipLaunchKernelGGL(finalize_kernel<KB_BF16>, dim3(Q, p.fb_parts), dim3(256), fin_lds, s, f); break;

@@ -6,9 +6,7 @@
 #define KB_SCAN_CONFIGS_BF16(X)                  \
     X(1, KB_BF16, 128, 32, 4, 1, 128, 3, 2)      \
     X(2, KB_BF16, 128, 128, 2, 2, 64, 4, 2)      \
-    X(3, KB_BF16, 128, 256, 2, 2, 64, 3, 2)      \
-    X(4, KB_BF16, 256, 256, 4, 2, 64, 4, 1)      \
-    X(5, KB_BF16, 128, 256, 2, 2, 64, 3, 1)
+    X(3, KB_BF16, 128, 256, 2, 2, 64, 3, 2)
 #define KB_SCAN_CONFIGS_F32(X)                   \
     X(1, KB_F32, 128, 32, 4, 1, 128, 3, 2)       \
     X(2, KB_F32, 128, 128, 2, 2, 64, 4, 2)       \
@@ -18,26 +16,9 @@
     X(2, KB_FP8_E4M3, 128, 128, 2, 2, 64, 3, 2)  \
     X(3, KB_FP8_E4M3, 128, 256, 2, 2, 64, 3, 1)
 
-// Ping-pong configurations (kb_scan_pp.hpp): XP(id, key dtype, TQ, NSA, NSB); 256-row tiles, 512 threads,
+// Software-pipelined configurations (kb_scan_sp.hpp): XS(id, key dtype, TQ, NSA, NSB); 256-row tiles, 512 threads,
 // NSA / NSB = ring depth of key / query chunks in LDS.
-#define KB_SCAN_PP_CONFIGS_BF16(XP) \
-    XP(6, KB_BF16, 256, 4, 4)       \
-    XP(7, KB_BF16, 256, 5, 3)       \
-    XP(8, KB_BF16, 256, 3, 5)
-
-// Register-tile configurations (kb_scan_big.hpp): XB(id, key dtype, NSA, NSB); 256 x 256 tiles, 256 threads.
-#define KB_SCAN_BIG_CONFIGS_BF16(XB) \
-    XB(9, KB_BF16, 4, 4)             \
-    XB(10, KB_BF16, 5, 3)
-
-// Software-pipelined configurations (kb_scan_sp.hpp): XS(id, key dtype, TQ, NSA, NSB); 256-row tiles, 512 threads.
-#define KB_SCAN_SP_CONFIGS_BF16(XS) \
-    XS(12, KB_BF16, 256, 5, 4)      \
-    XS(13, KB_BF16, 256, 4, 4)      \
-    XS(14, KB_BF16, 256, 4, 5)      \
-    XS(15, KB_BF16, 128, 5, 4)      \
-    XS(16, KB_BF16, 128, 6, 4)
-// ... with the loads between the MFMAs (IL mode)
+// bf16: the loads are issued between the MFMAs (IL mode)
 #define KB_SCAN_SP_CONFIGS_BF16_IL(XI) \
     XI(17, KB_BF16, 256, 5, 4)
 #define KB_SCAN_SP_CONFIGS_FP8(XS)  \

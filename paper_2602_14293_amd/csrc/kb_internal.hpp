@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "kb.h"
 
 // The handle: host-side bookkeeping over caller-owned device storage.
@@ -14,7 +16,6 @@ struct kb {
     float *row_scale, *inv_norm;
     uint64_t *tags;
     int64_t tune_sample_keys, tune_config, tune_wg_per_cu, tune_no_small_path;
-    int cu_count;   // 0 until the device has been asked
     hipEvent_t *prof_events;   // 2 * prof_max events while profiling, else nullptr
     int prof_max, prof_used;
 };
@@ -90,8 +91,8 @@ struct Plan {
         off_cand, off_lgain, total;
 };
 
-// Weighted random selection (the Optimization Selector's "random weighted selection based on predicted
-// performance gain" of Section 3): entries are ranked by key = score / T + ln(gain) + Gumbel noise instead of by
+// Weighted random selection (Section 3, Optimization Selector: its top-k is a random draw whose weights are the
+// entries' predicted gains): entries are ranked by key = score / T + ln(gain) + Gumbel noise instead of by
 // score, which draws k entries without replacement with probability proportional to gain * exp(score / T).
 struct DrawArgs {
     const float *log_gain;    // [rows padded to a multiple of 256]: ln(gain), -inf for entries that are never drawn
@@ -147,12 +148,26 @@ __device__ inline int64_t sample_row(const ScanArgs &p, int64_t tile, int tk, in
 __device__ inline int64_t sample_row0(const ScanArgs &p, int64_t tile, int tk) { return p.row_mul ? tile * tk : tile * p.tile_stride * tk; }
 __device__ inline uint32_t sample_index(const ScanArgs &p, int64_t row) { return (uint32_t)(p.row_mul ? sample_index64(p, row) : row); }
 
+// A kernel that uses more than 64 KiB of dynamic LDS must be allowed to, once per device (the attribute belongs to the
+// device's copy of the kernel).  `done` holds one bit per device ordinal; callers keep one such word per kernel.
+// Two threads that race here both set the attribute, which is harmless.
+typedef std::atomic<uint64_t> LdsAllowed;
+inline hipError_t allow_dynamic_lds(const void *kernel, LdsAllowed &done, size_t bytes)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = (dev >= 0 && dev < 64) ? 1ull << dev : 0ull;       // beyond 64 devices: set it on every call
+    if (bit && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess && bit) done.fetch_or(bit, std::memory_order_release);
+    return e;
+}
+
 // Launchers, one translation unit per key dtype.  `sample` selects the sampling epilogue.
 hipError_t launch_scan_f32(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
 hipError_t launch_scan_bf16(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
 hipError_t launch_scan_fp8(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
-hipError_t launch_scan_pp_bf16(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
-hipError_t launch_scan_big_bf16(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
 hipError_t launch_scan_sp_bf16(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
 hipError_t launch_scan_wide_bf16(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
 hipError_t launch_scan_wide_fp8(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);
@@ -162,7 +177,7 @@ hipError_t launch_scan_sp_fp8(int config, bool sample, int grid, const ScanArgs 
 struct ConfigInfo {
     int tk, tq, threads, groups_per_tile, wg_per_cu;
     int min_row_bytes;      // smallest key row (bytes) the configuration's pipeline is valid for
-    int family;             // 0: kb_scan.hpp, 1: kb_scan_pp.hpp, 2: kb_scan_big.hpp, 3: kb_scan_sp.hpp, 4: kb_scan_wide.hpp
+    int family;             // 0: kb_scan.hpp, 3: kb_scan_sp.hpp, 4: kb_scan_wide.hpp
 };
 bool scan_config_info(int key_dtype, int config, ConfigInfo *out);   // false if the id does not exist
 int scan_config_for(int key_dtype, int Q, int d, int64_t n);         // automatic choice for n rows

@@ -381,17 +381,12 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
 template <class C> hipError_t launch_scan_cfg(bool sample, int grid, const ScanArgs &a, hipStream_t s)
 {
     // more than 64 KiB of dynamic LDS has to be requested explicitly, once per kernel
-    static bool attr_done[4] = {false, false, false, false};
+    static LdsAllowed allowed[4];
     const bool draw = a.draw.enabled != 0;
     auto *fn = draw ? (sample ? &kb_scan_kernel<C, true, true> : &kb_scan_kernel<C, false, true>)
                     : (sample ? &kb_scan_kernel<C, true, false> : &kb_scan_kernel<C, false, false>);
     const int which = (draw ? 2 : 0) + (sample ? 1 : 0);
-    if (!attr_done[which]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM_BYTES);
-        if (e != hipSuccess) return e;
-        attr_done[which] = true;
-    }
+    if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(fn), allowed[which], C::SMEM_BYTES); e != hipSuccess) return e;
     hipLaunchKernelGGL(fn, dim3(grid), dim3(C::THREADS), C::SMEM_BYTES, s, a);
     return hipGetLastError();
 }

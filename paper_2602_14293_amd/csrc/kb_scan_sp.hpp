@@ -1,7 +1,6 @@
-// The large-batch scan kernel, software-pipelined variant: tile and operand layout of kb_scan_pp.hpp (8
-// wavefronts, 256 key rows x 256 queries per work item), but a wavefront reads its operand fragments from
-// LDS *between its MFMAs* instead of in a phase of their own, and there is ONE workgroup barrier per
-// d-chunk (gfx950 only).
+// The large-batch scan kernel, software-pipelined variant: 8 wavefronts, 256 key rows x 256 queries per work
+// item, 64-byte row pieces; a wavefront reads its operand fragments from LDS *between its MFMAs* instead of
+// in a phase of their own, and there is ONE workgroup barrier per d-chunk (gfx950 only).
 //
 // A d-chunk (64 bytes of every key row) is two k-groups of 32 bytes.  Fragments live in two register
 // sets, X (k-group 0) and Y (k-group 1); while the MFMAs of one set run, the other set is refilled:
@@ -28,8 +27,8 @@
 // split).  Measured gain over the split: 2-3 % on 2^20 x 1024 bf16 keys with 256 queries, 5 % on 2^22 x 768
 // fp8 keys with 1024 fp8 queries; fp8 keys with bf16 queries (32 MFMAs per chunk) gain nothing and keep it.
 //
-// LDS layout, swizzle and load pattern of a chunk are those of kb_scan_pp.hpp (64-byte rows, 16 rows per
-// load instruction: requests of 64 bytes are what the L2 serves best; 32-byte requests cost 1.6x the L2
+// LDS layout of a chunk: 64-byte rows with the XOR swizzle of kb_scan.hpp, 16 rows per
+// load instruction (requests of 64 bytes are what the L2 serves best; 32-byte requests cost 1.6x the L2
 // requests and 1.25x the HBM traffic when measured).  To make room for the deeper ring, the per-query
 // side data has one LDS copy, reloaded in an item's second iteration (every epilogue of the previous item
 // is over by then).
@@ -607,13 +606,9 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
 
 template <class C> hipError_t launch_scan_sp_cfg(bool sample, int grid, const ScanArgs &a, hipStream_t s)
 {
-    static bool attr_done[2] = {false, false};
+    static LdsAllowed allowed[2];
     auto *fn = sample ? &kb_scan_sp_kernel<C, true> : &kb_scan_sp_kernel<C, false>;
-    if (!attr_done[sample]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM_BYTES);
-        if (e != hipSuccess) return e;
-        attr_done[sample] = true;
-    }
+    if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(fn), allowed[sample], C::SMEM_BYTES); e != hipSuccess) return e;
     hipLaunchKernelGGL(fn, dim3(grid), dim3(C::THREADS), C::SMEM_BYTES, s, a);
     return hipGetLastError();
 }

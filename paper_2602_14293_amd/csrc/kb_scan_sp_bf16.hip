@@ -7,10 +7,6 @@ namespace kbi {
 hipError_t launch_scan_sp_bf16(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s)
 {
     switch (config) {
-#define XS(ID, KT, TQ, NSA, NSB) \
-    case ID: return launch_scan_sp_cfg<SPCfg<KT, TQ, NSA, NSB>>(sample, grid, a, s);
-        KB_SCAN_SP_CONFIGS_BF16(XS)
-#undef XS
 #define XI(ID, KT, TQ, NSA, NSB) \
     case ID: return launch_scan_sp_cfg<SPCfg<KT, TQ, NSA, NSB, false, true>>(sample, grid, a, s);
         KB_SCAN_SP_CONFIGS_BF16_IL(XI)

@@ -527,14 +527,10 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
 
 template <class C> hipError_t launch_scan_wide_cfg(bool sample, int grid, const ScanArgs &a, hipStream_t s)
 {
-    static bool attr_done[2] = {false, false};
+    static LdsAllowed allowed[2];
     if (C::QF8 && sample) return hipErrorInvalidValue;     // fp8: the sampling pass runs the 64-byte-piece kernel (fewer registers)
     auto *fn = (sample && !C::QF8) ? &kb_scan_wide_kernel<C, C::QF8 ? false : true> : &kb_scan_wide_kernel<C, false>;
-    if (!attr_done[sample]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM_BYTES);
-        if (e != hipSuccess) return e;
-        attr_done[sample] = true;
-    }
+    if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(fn), allowed[sample], C::SMEM_BYTES); e != hipSuccess) return e;
     hipLaunchKernelGGL(fn, dim3(grid), dim3(C::THREADS), C::SMEM_BYTES, s, a);
     return hipGetLastError();
 }

@@ -48,6 +48,8 @@ def lib() -> ctypes.CDLL:
         L.kb_normalize.argtypes = [vp, vp]
         L.kb_query_workspace_bytes.restype = sz
         L.kb_query_workspace_bytes.argtypes = [vp, i32, i32]
+        L.kb_query_plan_bytes.restype = sz
+        L.kb_query_plan_bytes.argtypes = [vp, i64, i32, i32, i32]
         L.kb_query.restype = i32
         L.kb_query.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, vp, sz, vp]
         L.kb_query_probe_workspace_bytes.restype = sz

@@ -49,9 +49,9 @@ def test_filtered_bf16_reduced(T, seed):
     assert rep.queries == 256
 
 
-@pytest.mark.parametrize("config", [3, 4, 6, 7, 8, 9, 12, 13, 14, 15, 16, 17, 18, 19])
+@pytest.mark.parametrize("config", [3, 17, 18, 19])
 def test_every_large_batch_scan_kernel(T, config):
-    """Each scan kernel that handles 256-query blocks (tiled, ping-pong, register-tile, software-pipelined, full-line) gives
+    """Each scan kernel that handles 256-query blocks (tiled, software-pipelined, full-line) gives
     the same oracle-checked result; ragged last tile, 300 queries = two query blocks, masked."""
     w = W.filtered(seed=7, N=20000 + 131, d=512, Q=300, k=32, centers=32)
     rep, cnt, _ = T.run_and_check(w, label=f"scan config {config}", tuning={"scan_config": config})

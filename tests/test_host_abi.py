@@ -203,3 +203,61 @@ def test_workspace_size_covers_every_smaller_row_count(L):
             assert L.kb_query_workspace_bytes(small, 128, 16) <= need_big
             L.kb_destroy(small)
         L.kb_destroy(big)
+
+
+def _dense_counts(cap, tile):
+    """Row counts on both sides of every tile boundary near the small end, a stride through the rest, the counts a
+    review found failing with an earlier sizing, and the capacity itself."""
+    ns = set(range(0, min(cap, 70000) + 1, 61)) | {1, 2, cap - 1, cap}
+    for t in range(1, min(cap // tile, 600) + 1):
+        ns |= {t * tile - 1, t * tile, t * tile + 1}
+    ns |= set(range(1, cap + 1, 4099))
+    ns |= {(1 << 20) + j for j in (0, 1, 31, 32, 255, 256, 257)} | {131087, 1970178, (1 << 18) - 1, 1 << 18, (1 << 18) + 1}
+    return sorted(n for n in ns if 0 <= n <= cap)
+
+
+@pytest.mark.parametrize("dtype,d,cap,Q,k", [
+    (kbmod.KB_BF16, 1024, 1 << 21, 128, 16),        # the growing knowledge base: one more row than 2^20 used to fail
+    (kbmod.KB_BF16, 1024, 1 << 20, 256, 32),
+    (kbmod.KB_BF16, 768, 65536, 64, 16),
+    (kbmod.KB_BF16, 256, 3_000_001, 300, 128),
+    (kbmod.KB_BF16, 64, 1 << 22, 1, 1),
+    (kbmod.KB_F32, 256, 4096, 8, 8),
+    (kbmod.KB_F32, 64, 1 << 20, 40, 100),
+    (kbmod.KB_FP8_E4M3, 768, 1 << 22, 1024, 64),
+    (kbmod.KB_FP8_E4M3, 512, 1 << 19, 33, 7),
+])
+def test_workspace_size_bounds_the_plan_of_every_row_count(L, dtype, d, cap, Q, k):
+    st, h = _create(L, d=d, dtype=dtype, cap=cap, scale=FAKE if dtype == kbmod.KB_FP8_E4M3 else None)
+    assert st == 0
+    need = L.kb_query_workspace_bytes(h, Q, k)
+    assert need > 0 and need % 256 == 0
+    worst = 0
+    for kind in (0, 1, 2):
+        for n in _dense_counts(cap, 128):
+            got = L.kb_query_plan_bytes(h, n, Q, k, kind)
+            assert got <= need, f"kind {kind}: {n} rows need {got} bytes, kb_query_workspace_bytes says {need}"
+            worst = max(worst, got)
+    assert worst * 4 >= need, f"the bound {need} is far above the largest plan found ({worst})"
+    assert L.kb_query_plan_bytes(h, cap + 1, Q, k, 0) == 0 and L.kb_query_plan_bytes(h, 5, Q, k, 3) == 0
+    L.kb_destroy(h)
+
+
+def test_workspace_size_follows_the_tuning_knobs(L):
+    st, h = _create(L, d=1024, cap=1 << 20)
+    for name, value in ((b"sample_keys", 4096), (b"scan_config", 3), (b"wg_per_cu", 2), (b"small_path", 0)):
+        assert L.kb_set_tuning(h, name, value) == 0
+        need = L.kb_query_workspace_bytes(h, 256, 32)
+        for kind in (0, 1):
+            for n in _dense_counts(1 << 20, 128)[::7]:
+                assert L.kb_query_plan_bytes(h, n, 256, 32, kind) <= need, (name, n)
+    L.kb_destroy(h)
+
+
+def test_append_reports_the_first_index_only_on_success(L):
+    st, h = _create(L, cap=10)
+    first = ctypes.c_int64(-7)
+    assert L.kb_append(h, FAKE, None, None, 11, None, ctypes.byref(first)) == 4 and first.value == -7     # KB_ERR_CAPACITY
+    assert L.kb_append(h, None, None, None, 3, None, ctypes.byref(first)) == 1 and first.value == -7      # KB_ERR_NULL
+    assert L.kb_append(h, FAKE, None, None, 0, None, ctypes.byref(first)) == 0 and first.value == 0       # a no-op reports the size
+    L.kb_destroy(h)

@@ -301,7 +301,7 @@ def test_compare_near_tie_rule(oracle):
         compare.check(np.array([[0, 3]], dtype=np.int32), np.array([[1.0, full[0, 3]]], dtype=np.float32), full, 2, 1e-5)
 
 
-# ---- weighted random selection (Section 3: "random weighted selection based on predicted performance gain") ----
+# ---- weighted random selection (Section 3, Optimization Selector: a top-k drawn at random, weighted by predicted gain) ----
 
 def test_philox_known_answer_vectors(oracle):
     kat = json.load(open(os.path.join(GOLD, "philox4x32_10_kat.json")))
