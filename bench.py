@@ -30,10 +30,31 @@ VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # Lane-instructions per (query, entry) pair of the key computation: a quarter of a 10-round Philox4x32 call (20), the
 # uniform variate (3), two logarithms with their scalings and negations (6), score scaling (3), key (2), test (2).
 DRAW_OPS_PER_PAIR = 36
-# HBM bytes per launch of the main-pass scan kernel on the default workload with the default kernel choice, from
-# rocprofv3 --pmc FETCH_SIZE (x 2.0: what the same counter under-reads on a copy of known size) and WRITE_SIZE (x 1.0).
-# Applies to that workload and kernel only.
-SCAN_TRAFFIC_BYTES_FILTERED = 1086879 * 1024 * 2.0 + 4110 * 1024 * 1.0
+# HBM bytes per launch of the main-pass scan kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (KiB per dispatch),
+# each scaled by what the same counter reads for a copy of known size.  A record applies to one workload, the default
+# kernel choice and the kernel sources it was taken on: `sources` is scan_sources_digest() at that time, and the
+# figure is reported as null once any of those files has changed.
+SCAN_TRAFFIC = {
+    "filtered": {"fetch_kib": 1086879, "fetch_scale": 2.0, "write_kib": 4110, "write_scale": 1.0, "sources": "ecf0c9f6f9a1b2d4"},
+}
+SCAN_SOURCES = ["kb_scan_wide.hpp", "kb_scan.hpp", "kb_scan_sp.hpp", "kb_epilogue.hpp", "kb_internal.hpp", "kb_configs.hpp"]
+
+
+def scan_sources_digest() -> str:
+    import hashlib
+
+    h = hashlib.sha256()
+    for name in SCAN_SOURCES:
+        with open(os.path.join(ROOT, "paper_2602_14293_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def scan_traffic_bytes(workload: str, tuned: bool):
+    rec = SCAN_TRAFFIC.get(workload)
+    if rec is None or tuned or rec["sources"] != scan_sources_digest():
+        return None
+    return rec["fetch_kib"] * 1024 * rec["fetch_scale"] + rec["write_kib"] * 1024 * rec["write_scale"]
 
 
 def make_workload(name: str, seed: int, device):
@@ -237,6 +258,7 @@ def run_growing(args, torch, kbmod, W, dev):
         if r == 0:      # untimed warm-up of the query path on the initial knowledge base
             for _ in range(args.warmup):
                 kb.query(queries, k, qmask, out_i, out_s)
+            kb.profile_begin(rounds)
         torch.cuda.synchronize()
         ev[0].record()
         kb.append(rows, tags=tags)
@@ -247,11 +269,15 @@ def run_growing(args, torch, kbmod, W, dev):
         torch.cuda.synchronize()
         t_append.append(ev[0].elapsed_time(ev[1]))
         t_query.append(ev[1].elapsed_time(ev[2]))
+    scan_ms_total, scan_calls = kb.profile_end()
     n_first, n_last = N0 + n_new, N0 + rounds * n_new
     row_bytes = d * 2
-    half = rounds // 2
     q_first, q_last = _median(t_query[:8]), _median(t_query[-8:])
-    print(json.dumps({
+    # algorithmic bytes of a round's scan: the rows as of that round (+ norm and tag) and the query block
+    alg = [(N0 + (r + 1) * n_new) * (row_bytes + 12) + Q * row_bytes for r in range(rounds)]
+    call_frac = [alg[r] / (t_query[r] * 1e-3) / 1e9 / HBM_PEAK_GBPS for r in range(rounds)]
+    scan_achieved = sum(alg) / (scan_ms_total * 1e-3) / 1e9 if scan_calls == rounds else None
+    result = {
         "metric": "KB top-k queries/sec + key-scan HBM GB/s (% of peak), N=1M d=1024 bf16",
         "value": Q * rounds / (sum(t_query) * 1e-3), "unit": "queries/s", "n_gpus": 1, "steps": rounds, "warmup": args.warmup,
         "ms_per_step": (sum(t_query) + sum(t_append)) / rounds, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -260,12 +286,25 @@ def run_growing(args, torch, kbmod, W, dev):
                    "seed": args.seed},
         "append_normalize_ms": {"median": _median(t_append), "min": min(t_append), "max": max(t_append),
                                 "GBps_median": n_new * row_bytes / (_median(t_append) * 1e-3) / 1e9},
-        "query_ms": {"first_8_rounds_median": q_first, "last_8_rounds_median": q_last, "min": min(t_query), "max": max(t_query)},
+        "query_ms": {"first_8_rounds_median": q_first, "last_8_rounds_median": q_last, "min": min(t_query), "max": max(t_query),
+                     "per_round": [round(t, 4) for t in t_query]},
         "key_scan_GBps": {"first_8_rounds": n_first * row_bytes / (q_first * 1e-3) / 1e9,
                           "last_8_rounds": n_last * row_bytes / (q_last * 1e-3) / 1e9},
+        "call_frac_of_hbm_peak": {"min": min(call_frac), "median": _median(call_frac), "max": max(call_frac)},
         "queries_per_s": {"first_8_rounds": Q / (q_first * 1e-3), "last_8_rounds": Q / (q_last * 1e-3)},
         "counters_last_round": kb.counters(),
-    }))
+        "roofline": {"bound": "hbm", "kernel": "scan kernel, main pass (all rounds)", "achieved": scan_achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": None if scan_achieved is None else scan_achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel_ms": scan_ms_total / max(scan_calls, 1), "algorithmic_bytes": sum(alg) / rounds, "launches_timed": scan_calls},
+    }
+    if not args.no_cpu_baseline:
+        n = kb.size
+        w = W.Workload("growing", kb.keys[:n], queries, k, tags=kb.tags[:n], qmask=qmask)
+        result["cpu_baseline"], result["parity"] = parity_and_baseline(args, torch, kbmod, W, w, kbmod.KB_BF16, k, out_i.cpu().numpy(),
+                                                                       out_s.cpu().numpy(), None, min(args.oracle_queries, 64))
+        result["cpu_baseline"]["sample"] += " (the last round)"
+    kb.close()
+    return result
 
 
 def run_q_sweep(args, torch, kbmod, W, dev):
@@ -300,57 +339,45 @@ def run_q_sweep(args, torch, kbmod, W, dev):
                       "n_gpus": 1, "data": "synthetic", "sweep": rows}))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="filtered")
-    ap.add_argument("--seed", type=int, default=2000)
-    ap.add_argument("--oracle-queries", type=int, default=256, help="queries of the batch given to the CPU oracle")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--copy-probe", action="store_true",
-                    help="also run one 1 GiB device-to-device elementwise copy (a dispatch of known traffic that "
-                         "calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
-    ap.add_argument("--tune", action="append", default=[], help="name=value performance knob (repeatable)")
-    ap.add_argument("--graph", action="store_true",
-                    help="capture one kb_query in a HIP graph and time replays (for the launch-latency-bound workloads; "
-                         "the scan kernel is then not timed on its own)")
-    ap.add_argument("--draw", action="store_true",
-                    help="time the weighted random selection (kb_query_sampled: gains uniform in [0.25, 4], temperature "
-                         "0.05) instead of the plain top-k")
-    ap.add_argument("--two-stage", action="store_true", help="time centroid ranking + kb_query_probe against the exhaustive query and report recall@k instead")
-    ap.add_argument("--maintain", action="store_true", help="time kb_update_gain / kb_remove / kb_compact and queries around them instead")
-    ap.add_argument("--quantize", action="store_true", help="time kb_quantize_rows instead")
-    ap.add_argument("--q-sweep", action="store_true", help="time query batches of 1..512 on the N=2^20 bf16 knowledge base instead")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        raise SystemExit("bench.py measures one GPU: the retrieval path is built and measured on a single MI355X "
-                         "(--gpus must be 1).")
+TIGHT_TAU = 1e-5            # the error the kernels reach on the same stored bits; fp8 queries: 1e-4; keys of a draw: 2e-5
+ALL_WORKLOADS = ["tiny", "clustered", "filtered", "compressed", "compressed-q8", "filtered-q128", "growing"]
 
-    import numpy as np
-    import torch
 
-    from paper_2602_14293_amd import kb as kbmod
-    from paper_2602_14293_amd import workloads as W
+def parity_and_baseline(args, torch, kbmod, W, w, code, k, gi, gs, gain, nq):
+    """The oracle, as it stands, on the first nq queries of the batch against all keys: timed (cpu_baseline), and
+    the GPU result judged by the acceptance rule at the dtype tolerance and at the tight one.  Raises on a mismatch."""
+    from oracle import compare, kb_oracle
 
-    if not torch.cuda.is_available():
-        raise SystemExit("bench.py needs a GPU")
-    kbmod.lib()     # raises if libkb.so has not been built: there is no fallback path
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
+    N, Q = w.N, w.Q
+    masked = w.qmask is not None
+    key_bits = W.key_bits(w.keys)
+    q_bits = W.key_bits(w.queries[:nq])
+    tags = W.word_bits(w.tags) if masked else None
+    qm = W.word_bits(w.qmask[:nq]) if masked else None
+    okind = {kbmod.KB_F32: kb_oracle.F32, kbmod.KB_BF16: kb_oracle.BF16, kbmod.KB_FP8_E4M3: kb_oracle.FP8_E4M3}[code]
+    qkind = {torch.float32: kb_oracle.F32, torch.bfloat16: kb_oracle.BF16, torch.float8_e4m3fn: kb_oracle.FP8_E4M3}[w.queries.dtype]
+    c0 = time.perf_counter()
+    oi, osc, full = kb_oracle.query(key_bits, okind, q_bits, qkind, k,
+                                    row_scale=None if w.scale is None else w.scale.cpu().numpy(), tags=tags, qmask=qm,
+                                    return_scores=True)
+    if gain is not None:       # keys of the same draw from the fp64 scores; selection is part of the timed work
+        full = kb_oracle.selection_keys(full, gain.cpu().numpy(), DRAW_TEMPERATURE, args.seed, 0)
+        for r in range(nq):
+            kb_oracle.select(full[r], k, tags=tags, qmask=None if qm is None else qm[r])
+    c1 = time.perf_counter()
+    tau = 2e-4 if gain is not None else {kbmod.KB_F32: 1e-5, kbmod.KB_BF16: 2e-3, kbmod.KB_FP8_E4M3: 2e-2}[code]
+    tight_tau = 2e-5 if gain is not None else 1e-4 if w.queries.dtype == torch.float8_e4m3fn else TIGHT_TAU
+    rep, tight = compare.check(gi[:nq], gs[:nq], full, k, tau, tags=tags, qmask=qm, label="bench parity", tight_tau=tight_tau)
+    baseline = {"value": nq / (c1 - c0), "unit": "queries/s", "cores": kb_oracle.num_threads(), "kind": "oracle",
+                "sample": f"first {nq} of the {Q} queries against all {N} keys (fp64 brute force + full sort), {c1 - c0:.1f} s"}
+    parity = {"queries_checked": rep.queries, "tau": tau, "strict": rep.strict, "near_tie": rep.near_tie,
+              "tight_tau": tight_tau, "tight_strict": tight.strict, "tight_near_tie": tight.near_tie,
+              "max_score_err": rep.max_score_err}
+    return baseline, parity
 
-    if args.q_sweep:
-        return run_q_sweep(args, torch, kbmod, W, dev)
-    if args.quantize:
-        return run_quantize(args, torch, kbmod, W, dev)
-    if args.maintain:
-        return run_maintain(args, torch, kbmod, W, dev)
-    if args.two_stage:
-        return run_two_stage(args, torch, kbmod, W, dev)
-    if args.workload == "growing":
-        return run_growing(args, torch, kbmod, W, dev)
-    w, desc = make_workload(args.workload, args.seed, dev)
+
+def run_query_workload(args, torch, kbmod, W, dev, name):
+    w, desc = make_workload(name, args.seed, dev)
     code = {torch.float32: kbmod.KB_F32, torch.bfloat16: kbmod.KB_BF16, torch.float8_e4m3fn: kbmod.KB_FP8_E4M3}[w.keys.dtype]
     kb = kbmod.KnowledgeBase(w.d, code, w.N, tagged=w.tags is not None)
     kb.keys.copy_(w.keys)
@@ -361,13 +388,14 @@ def main():
     kb.append_in_place(w.N)
     kb.normalize()
     for t in args.tune:
-        name, val = t.split("=")
-        kb.set_tuning(name, int(val))
+        tname, val = t.split("=")
+        kb.set_tuning(tname, int(val))
     queries = w.queries.contiguous()
     qmask = w.qmask
     Q, k, N, d = w.Q, w.k, w.N, w.d
     out_i = torch.empty((Q, k), dtype=torch.int32, device=dev)
     out_s = torch.empty((Q, k), dtype=torch.float32, device=dev)
+    gain = None
     if args.draw:
         gen = torch.Generator(device=dev)
         gen.manual_seed(args.seed + 17)
@@ -423,6 +451,22 @@ def main():
         e1.record()
     torch.cuda.synchronize()
     per_call = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    flushed = None
+    if args.flushed:
+        # the same call after 1 GiB of unrelated writes has gone through the caches (keys and queries come from HBM)
+        junk = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+        cold = []
+        for _ in range(min(args.steps, 10)):
+            junk.fill_(1.0)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            kb.query(queries, k, qmask, out_i, out_s)
+            e1.record()
+            torch.cuda.synchronize()
+            cold.append(e0.elapsed_time(e1))
+        del junk
+        cold.sort()
+        flushed = {"median": cold[len(cold) // 2], "min": cold[0], "max": cold[-1], "calls": len(cold)}
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     qps = Q / (ms_per_step * 1e-3)
@@ -433,6 +477,7 @@ def main():
     scan_ms = scan_ms_total / max(scan_calls, 1)
     achieved = scan_bytes / (scan_ms * 1e-3) / 1e9
     flops = 2.0 * Q * N * d
+    small_path = counters["sample_keys"] == 0 and counters["candidates"] == 0 and N <= 16384
     result = {
         "metric": "KB top-k queries/sec + key-scan HBM GB/s (% of peak), N=1M d=1024 bf16",
         "value": qps,
@@ -450,15 +495,18 @@ def main():
         "config": {"workload": desc, "seed": args.seed, "checksum": W.checksum(w.keys[:4096], w.queries)},
         "key_scan_GBps": key_bytes / (ms_per_step * 1e-3) / 1e9,
         "key_scan_frac_of_hbm_peak": key_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "call_frac_of_hbm_peak": scan_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "mfma_TFLOPs": flops / (ms_per_step * 1e-3) / 1e12,
         "counters": counters,
         "launch": "hip graph replay" if args.graph else "eager",
-        "roofline": {"bound": "hbm", "kernel": "scoring kernel of the small-knowledge-base path" if counters["sample_keys"] == 0 and counters["candidates"] == 0 and N <= 16384
-                     else "scan kernel, main pass", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "kernel": "scoring kernel of the small-knowledge-base path" if small_path else "scan kernel, main pass",
+                     "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": SCAN_TRAFFIC_BYTES_FILTERED if (args.workload == "filtered" and not args.tune) else None,
+                     "traffic": scan_traffic_bytes(name, bool(args.tune) or args.draw),
                      "kernel_ms": scan_ms, "algorithmic_bytes": scan_bytes, "launches_timed": scan_calls},
     }
+    if flushed is not None:
+        result["ms_per_call_flushed"] = flushed
 
     # Above the ridge (large Q) the matrix cores, not HBM, bound the scan: report against the dense MFMA peak of the
     # type the contraction runs in (fp8 keys with bf16 queries are widened to bf16; fp8 with fp8 queries run in fp8).
@@ -476,34 +524,71 @@ def main():
                               "algorithmic_ops": ops, "launches_timed": scan_calls}
 
     if not args.no_cpu_baseline:
-        # the oracle, as it stands, on the first `oracle_queries` queries of the same batch against all N keys
-        from oracle import compare, kb_oracle
+        # a bounded sample: the whole batch up to 256 queries of 2^20 keys, 64 queries of the 2^22-key store
+        nq = min(args.oracle_queries, Q, max(8, int(256 * (1 << 20) / max(N, 1))))
+        result["cpu_baseline"], result["parity"] = parity_and_baseline(args, torch, kbmod, W, w, code, k, out_i.cpu().numpy(),
+                                                                       out_s.cpu().numpy(), gain, nq)
+    kb.close()
+    return result
 
-        nq = min(args.oracle_queries, Q)
-        gi, gs = out_i.cpu().numpy(), out_s.cpu().numpy()
-        key_bits = W.key_bits(w.keys)
-        q_bits = W.key_bits(w.queries[:nq])
-        tags = W.word_bits(w.tags) if qmask is not None else None
-        qm = W.word_bits(w.qmask[:nq]) if qmask is not None else None
-        okind = {kbmod.KB_F32: kb_oracle.F32, kbmod.KB_BF16: kb_oracle.BF16, kbmod.KB_FP8_E4M3: kb_oracle.FP8_E4M3}[code]
-        c0 = time.perf_counter()
-        qkind = {torch.float32: kb_oracle.F32, torch.bfloat16: kb_oracle.BF16, torch.float8_e4m3fn: kb_oracle.FP8_E4M3}[w.queries.dtype]
-        oi, osc, full = kb_oracle.query(key_bits, okind, q_bits, qkind, k,
-                                        row_scale=None if w.scale is None else w.scale.cpu().numpy(), tags=tags, qmask=qm,
-                                        return_scores=True)
-        if args.draw:       # keys of the same draw from the fp64 scores; selection is part of the timed work
-            full = kb_oracle.selection_keys(full, gain.cpu().numpy(), DRAW_TEMPERATURE, args.seed, 0)
-            for r in range(nq):
-                kb_oracle.select(full[r], k, tags=tags, qmask=None if qm is None else qm[r])
-        c1 = time.perf_counter()
-        tau = 2e-4 if args.draw else {kbmod.KB_F32: 1e-5, kbmod.KB_BF16: 2e-3, kbmod.KB_FP8_E4M3: 2e-2}[code]
-        rep = compare.check(gi[:nq], gs[:nq], full, k, tau, tags=tags, qmask=qm, label="bench parity")   # raises on mismatch
-        result["cpu_baseline"] = {"value": nq / (c1 - c0), "unit": "queries/s", "cores": kb_oracle.num_threads(), "kind": "oracle",
-                                  "sample": f"first {nq} of the {Q} queries against all {N} keys (fp64 brute force + full sort), "
-                                            f"{c1 - c0:.1f} s"}
-        result["parity"] = {"queries_checked": rep.queries, "strict": rep.strict, "near_tie": rep.near_tie,
-                            "max_score_err": rep.max_score_err}
-    print(json.dumps(result))
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="filtered",
+                    help="tiny | clustered | filtered (default, the workload the metric is quoted on) | compressed | compressed-q8 | "
+                         "filtered-q128 | growing | all (one JSON line per workload, in that order)")
+    ap.add_argument("--seed", type=int, default=2000)
+    ap.add_argument("--oracle-queries", type=int, default=256, help="queries of the batch given to the CPU oracle")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one 1 GiB device-to-device elementwise copy (a dispatch of known traffic that "
+                         "calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
+    ap.add_argument("--tune", action="append", default=[], help="name=value performance knob (repeatable)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one kb_query in a HIP graph and time replays (for the launch-latency-bound workloads; "
+                         "the scan kernel is then not timed on its own)")
+    ap.add_argument("--flushed", action="store_true",
+                    help="also time calls that follow 1 GiB of unrelated writes (caches flushed: the small workloads from HBM)")
+    ap.add_argument("--draw", action="store_true",
+                    help="time the weighted random selection (kb_query_sampled: gains uniform in [0.25, 4], temperature "
+                         "0.05) instead of the plain top-k")
+    ap.add_argument("--two-stage", action="store_true", help="time centroid ranking + kb_query_probe against the exhaustive query and report recall@k instead")
+    ap.add_argument("--maintain", action="store_true", help="time kb_update_gain / kb_remove / kb_compact and queries around them instead")
+    ap.add_argument("--quantize", action="store_true", help="time kb_quantize_rows instead")
+    ap.add_argument("--q-sweep", action="store_true", help="time query batches of 1..512 on the N=2^20 bf16 knowledge base instead")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures one GPU: the retrieval path is built and measured on a single MI355X "
+                         "(--gpus must be 1).")
+
+    import torch
+
+    from paper_2602_14293_amd import kb as kbmod
+    from paper_2602_14293_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    kbmod.lib()     # raises if libkb.so has not been built: there is no fallback path
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    if args.q_sweep:
+        return run_q_sweep(args, torch, kbmod, W, dev)
+    if args.quantize:
+        return run_quantize(args, torch, kbmod, W, dev)
+    if args.maintain:
+        return run_maintain(args, torch, kbmod, W, dev)
+    if args.two_stage:
+        return run_two_stage(args, torch, kbmod, W, dev)
+    for name in (ALL_WORKLOADS if args.workload == "all" else [args.workload]):
+        if args.workload == "all":
+            args.flushed = name in ("tiny", "clustered")        # the two that fit in the caches
+        result = run_growing(args, torch, kbmod, W, dev) if name == "growing" else run_query_workload(args, torch, kbmod, W, dev, name)
+        print(json.dumps(result), flush=True)
+        torch.cuda.empty_cache()
 
 
 if __name__ == "__main__":

@@ -10,9 +10,15 @@ A result G = (index int32[Q,k], score float32[Q,k]) is accepted for query r, wit
   4. order      : G is sorted by (own score desc, index asc), and no later entry beats an earlier one by
                   more than 2 tau in oracle score.
 s*(i) are the oracle's fp64 scores; O is the oracle's own top-k.
+
+The rule is run at two tolerances: the one the storage type is allowed (fp32 1e-5, bf16 2e-3, fp8 2e-2), which
+is the pass/fail bound of the specification, and a tight one at the error the kernels actually reach on the
+same stored bits (about 1e-6), because at the loose one the k-th/(k+1)-th gap of a dense workload is below tau
+for almost every query and rule 3 would accept a result that lost its k-th entry.
 """
 from __future__ import annotations
 
+import concurrent.futures
 import dataclasses
 
 import numpy as np
@@ -29,13 +35,22 @@ class Report:
     exact_order: int = 0     # queries whose index sequence equals the oracle's
 
 
-def check_query(g_index, g_score, s_star, k, tau, tags=None, qmask=None, report: Report | None = None, label=""):
+def check_query(g_index, g_score, s_star, k, tau, tags=None, qmask=None, report: Report | None = None, label="",
+                tight_tau=None, tight_report: Report | None = None):
+    """One query at tolerance tau and, when tight_tau is given, at that tolerance too (one oracle selection for both)."""
     g_index = np.asarray(g_index).astype(np.int64)
     g_score = np.asarray(g_score).astype(np.float64)
     s_star = np.asarray(s_star, dtype=np.float64)
-    N = s_star.shape[0]
     assert g_index.shape == (k,) and g_score.shape == (k,), f"{label}: bad output shape"
-    o_index, o_score, n_cand = kb_oracle.select(s_star, k, tags=tags, qmask=qmask)
+    selected = kb_oracle.select(s_star, k, tags=tags, qmask=qmask)
+    _judge(g_index, g_score, s_star, selected, k, tau, tags, qmask, report, label)
+    if tight_tau is not None:
+        _judge(g_index, g_score, s_star, selected, k, tight_tau, tags, qmask, tight_report, f"{label} [tau {tight_tau:.0e}]")
+
+
+def _judge(g_index, g_score, s_star, selected, k, tau, tags, qmask, report, label):
+    N = s_star.shape[0]
+    o_index, o_score, n_cand = selected
     m = min(k, n_cand)
 
     # 1. structure
@@ -99,11 +114,31 @@ def check_query(g_index, g_score, s_star, k, tau, tags=None, qmask=None, report:
         report.exact_order += int(np.array_equal(gi, o_index[:m]))
 
 
-def check(g_index, g_score, s_star, k, tau, tags=None, qmask=None, label="") -> Report:
-    """All queries.  s_star is the oracle's [Q, N] score matrix."""
-    rep = Report()
+def check(g_index, g_score, s_star, k, tau, tags=None, qmask=None, label="", tight_tau=None):
+    """All queries.  s_star is the oracle's [Q, N] score matrix.  Returns the Report at tau, or with tight_tau the
+    pair (Report at tau, Report at tight_tau)."""
     Q = s_star.shape[0]
-    for r in range(Q):
+
+    def one(r):
+        a, b = Report(), Report()
         check_query(g_index[r], g_score[r], s_star[r], k, tau, tags=tags,
-                    qmask=None if qmask is None else qmask[r], report=rep, label=f"{label} query {r}")
-    return rep
+                    qmask=None if qmask is None else qmask[r], report=a, label=f"{label} query {r}",
+                    tight_tau=tight_tau, tight_report=b)
+        return a, b
+
+    # queries are independent and the work (one full sort and a few passes over N scores each) runs outside the
+    # interpreter lock: large inputs are spread over the host threads, in query order
+    if Q > 1 and s_star.shape[1] >= (1 << 16):
+        with concurrent.futures.ThreadPoolExecutor(max_workers=kb_oracle.num_threads()) as pool:
+            parts = list(pool.map(one, range(Q)))
+    else:
+        parts = [one(r) for r in range(Q)]
+    rep, tight = Report(), Report()
+    for a, b in parts:
+        for total, part in ((rep, a), (tight, b)):
+            total.queries += part.queries
+            total.strict += part.strict
+            total.near_tie += part.near_tie
+            total.exact_order += part.exact_order
+            total.max_score_err = max(total.max_score_err, part.max_score_err)
+    return rep if tight_tau is None else (rep, tight)

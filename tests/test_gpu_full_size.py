@@ -38,10 +38,10 @@ def _properties(gi, gs, N):
         assert np.all((s[:-1] > s[1:]) | ((s[:-1] == s[1:]) & (row[:-1] < row[1:])))
 
 
-def _check_sample(T, w, gi, gs, rows, label):
+def _check_sample(T, w, gi, gs, rows, label, min_strict=None):
     w_cpu = W.Workload(w.name, w.keys.cpu(), w.queries.cpu(), w.k, scale=None if w.scale is None else w.scale.cpu(),
                        tags=None if w.tags is None else w.tags.cpu(), qmask=None if w.qmask is None else w.qmask.cpu())
-    return T.check_against_oracle(w_cpu, gi, gs, rows=rows, label=label)
+    return T.check_against_oracle(w_cpu, gi, gs, rows=rows, label=label, min_strict=min_strict)
 
 
 def test_clustered_full(T):
@@ -51,7 +51,7 @@ def test_clustered_full(T):
     torch.cuda.synchronize()
     gi, gs = gi.cpu().numpy(), gs.cpu().numpy()
     _properties(gi, gs, w.N)
-    rep = _check_sample(T, w, gi, gs, None, "clustered full")
+    rep = _check_sample(T, w, gi, gs, None, "clustered full", min_strict=0.8)
     assert rep.queries == 64 and kb.counters()["exhaustive_queries"] == 0
     kb.close()
 
@@ -63,9 +63,8 @@ def test_filtered_full(T):
     torch.cuda.synchronize()
     gi, gs = gi.cpu().numpy(), gs.cpu().numpy()
     _properties(gi, gs, w.N)
-    rows = np.random.default_rng(0).choice(256, size=24, replace=False)
-    _check_sample(T, w, gi, gs, np.sort(rows), "filtered full")
-    assert kb.counters()["exhaustive_queries"] == 0
+    rep = _check_sample(T, w, gi, gs, None, "filtered full", min_strict=0.9)         # every query of the batch
+    assert rep.queries == 256 and kb.counters()["exhaustive_queries"] == 0
     # self-queries at full size: stored rows as queries come back first with score 1
     pick = torch.tensor([0, 255, 256, 65535, 65536, 524287, 1048575], device="cuda")
     q2 = w.keys[pick].contiguous()
@@ -82,8 +81,9 @@ def test_compressed_full(T):
     torch.cuda.synchronize()
     gi, gs = gi.cpu().numpy(), gs.cpu().numpy()
     _properties(gi, gs, w.N)
-    rows = np.sort(np.random.default_rng(1).choice(1024, size=8, replace=False))
-    _check_sample(T, w, gi, gs, rows, "compressed full")
+    rows = np.sort(np.random.default_rng(1).choice(1024, size=64, replace=False))
+    rep = _check_sample(T, w, gi, gs, rows, "compressed full", min_strict=0.8)
+    assert rep.queries == 64
     assert kb.counters()["exhaustive_queries"] == 0
     kb.close()
 
@@ -109,8 +109,9 @@ def test_growing_full(T):
             gi, gs = gi.cpu().numpy(), gs.cpu().numpy()
             _properties(gi, gs, n)
             w = W.Workload("growing", kb.keys[:n], queries, k, tags=kb.tags[:n], qmask=qmask)
-            sample = np.array([0, 17, 64, 127])
-            _check_sample(T, w, gi, gs, sample, f"growing round {r}")
+            sample = np.sort(np.random.default_rng(10 + r).choice(Q, size=32, replace=False))
+            rep = _check_sample(T, w, gi, gs, sample, f"growing round {r}", min_strict=0.8)
+            assert rep.queries == 32
             # every query is a perturbed row of the newest block: that row must be rank 1
             assert (gi[:, 0] >= first).mean() > 0.9
     assert kb.size == cap
@@ -125,8 +126,10 @@ def test_compressed_full_fp8_queries(T):
     torch.cuda.synchronize()
     gi, gs = gi.cpu().numpy(), gs.cpu().numpy()
     _properties(gi, gs, w.N)
-    rows = np.sort(np.random.default_rng(2).choice(1024, size=8, replace=False))
-    _check_sample(T, w, gi, gs, rows, "compressed full, fp8 queries")
+    rows = np.sort(np.random.default_rng(2).choice(1024, size=64, replace=False))
+    # (the tight tolerance of fp8 queries is 1e-4: fewer k-th gaps exceed it)
+    rep = _check_sample(T, w, gi, gs, rows, "compressed full, fp8 queries", min_strict=0.25)
+    assert rep.queries == 64
     assert kb.counters()["exhaustive_queries"] == 0
     kb.close()
 
@@ -143,12 +146,16 @@ def test_filtered_full_draw(T):
     gi, gk = kb.query_sampled(w.queries, w.k, gain, 0.05, 99, w.qmask)
     torch.cuda.synchronize()
     gi, gk = gi.cpu().numpy(), gk.cpu().numpy()
-    rows = np.sort(np.random.default_rng(3).choice(256, size=6, replace=False))
+    rows = np.sort(np.random.default_rng(3).choice(256, size=32, replace=False))
     full = kb_oracle.score_matrix(W.key_bits(w.keys.cpu()), kb_oracle.BF16, W.key_bits(w.queries.cpu()[rows]), kb_oracle.BF16)
     qm = W.word_bits(w.qmask.cpu())[rows]
+    strict = 0
     for j, r in enumerate(rows):        # keys of the oracle for global query number r
         keys = kb_oracle.selection_keys(full[j:j + 1], gain.cpu().numpy(), 0.05, 99, first_query=int(r))
-        compare.check(gi[r:r + 1], gk[r:r + 1], keys, w.k, 2e-4, tags=W.word_bits(w.tags.cpu()), qmask=qm[j:j + 1], label=f"full draw q{r}")
+        _, tight = compare.check(gi[r:r + 1], gk[r:r + 1], keys, w.k, 2e-4, tags=W.word_bits(w.tags.cpu()), qmask=qm[j:j + 1],
+                                 label=f"full draw q{r}", tight_tau=2e-5)
+        strict += tight.strict
+    assert strict >= 0.8 * len(rows)
     kb.close()
 
 
@@ -169,9 +176,9 @@ def test_filtered_full_remove_and_compact(T):
     gi, gs = gi.cpu().numpy(), gs.cpu().numpy()
     _properties(gi, gs, w.N)
     assert not removed[gi[gi >= 0]].any() and kb.counters()["exhaustive_queries"] == 0
-    rows = np.sort(np.random.default_rng(4).choice(256, size=8, replace=False))
+    rows = np.sort(np.random.default_rng(4).choice(256, size=32, replace=False))
     w_cpu = W.Workload(w.name, w.keys.cpu(), w.queries.cpu(), w.k, tags=w.tags.cpu(), qmask=w.qmask.cpu())
-    T.check_against_oracle(w_cpu, gi, gs, rows=rows, label="filtered full, a tenth removed", removed=removed)
+    T.check_against_oracle(w_cpu, gi, gs, rows=rows, label="filtered full, a tenth removed", removed=removed, min_strict=0.8)
     dst = kbmod.KnowledgeBase(w.d, kbmod.KB_BF16, w.N - w.N // 10, tagged=True)
     live, index_map, _ = kb.compact_into(dst)
     torch.cuda.synchronize()

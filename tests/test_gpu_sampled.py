@@ -13,9 +13,10 @@ pytestmark = pytest.mark.gpu
 # key = score / T + ln(gain) + Gumbel in fp32 against fp64: the score error (about 5e-7 for every key type, see
 # kb_testlib) is divided by T >= 0.02 (2.5e-5), ln(gain) is a correctly rounded logf (1e-7), and the two hardware
 # logarithms of the Gumbel variate contribute a few 1e-7 relative on |G| <= 17 (5e-6).  Acceptance at 2e-4; the
-# tests also assert the measured error stays below 1e-4.
+# whole rule (membership, index set, order) is also run at the error actually reached: 2e-5 for T >= 0.05 (largest
+# measured key error 7e-6), scaled by 0.05 / T below that.
 TAU_KEY = 2e-4
-TIGHT_KEY = 1e-4
+TIGHT_KEY = 2e-5
 
 
 @pytest.fixture(scope="module")
@@ -46,8 +47,10 @@ def _run(T, w, gain, temperature, seed, first_query=0, label="", tuning=None):
     keys = kb_oracle.selection_keys(T.oracle_scores(w), gain, temperature, seed, first_query)
     tags = W.word_bits(w.tags) if w.qmask is not None else None
     qmask = W.word_bits(w.qmask) if w.qmask is not None else None
-    rep = compare.check(gi, gk, keys, w.k, TAU_KEY, tags=tags, qmask=qmask, label=label)
-    assert rep.max_score_err <= TIGHT_KEY, f"{label}: key error {rep.max_score_err:.2e}"
+    tight_tau = TIGHT_KEY * max(1.0, 0.05 / temperature)
+    rep, tight = compare.check(gi, gk, keys, w.k, TAU_KEY, tags=tags, qmask=qmask, label=label, tight_tau=tight_tau)
+    assert rep.max_score_err <= tight_tau, f"{label}: key error {rep.max_score_err:.2e}"
+    rep.tight = tight
     return rep, counters, gi, gk, keys
 
 

@@ -281,6 +281,34 @@ def test_compare_accepts_oracle_and_rejects_planted_mistakes(oracle):
     rejected(i2, s2)
 
 
+def test_compare_at_the_tight_tolerance_rejects_a_lost_kth_entry(oracle):
+    """A result whose k-th entry is replaced by the oracle's (k+1)-th.  On a dense bf16 workload the gap between the
+    two is far below the bf16 tolerance, so the rule at 2e-3 lets most such results through (stated here so that
+    nobody mistakes that run for a membership test); at the tolerance the kernels reach (1e-5) nearly all of them
+    must be rejected, and the run at both tolerances must reject as well."""
+    w = W.filtered(seed=9, N=6000, d=256, Q=24, k=16, centers=8, p_tag=0.3)
+    tags, qm = W.word_bits(w.tags), W.word_bits(w.qmask)
+    idx, sc, full = _oracle_result(oracle, w, 16)
+    loose, tight = compare.check(idx, sc, full, 16, 2e-3, tags=tags, qmask=qm, tight_tau=1e-5)
+    assert loose.queries == tight.queries == 24 and tight.strict >= 20 and loose.strict <= tight.strict
+    let_through = {2e-3: 0, 1e-5: 0}
+    for r in range(24):
+        order = np.argsort(-np.where((tags & qm[r]) != 0, full[r], -np.inf), kind="stable")
+        i2, s2 = idx[r:r + 1].copy(), sc[r:r + 1].copy()
+        i2[0, 15] = order[16]
+        s2[0, 15] = full[r, order[16]]
+        for tau in let_through:
+            try:
+                compare.check(i2, s2, full[r:r + 1], 16, tau, tags=tags, qmask=qm[r:r + 1])
+                let_through[tau] += 1
+            except AssertionError:
+                pass
+        if full[r, order[15]] - full[r, order[16]] > 1e-5:
+            with pytest.raises(AssertionError):
+                compare.check(i2, s2, full[r:r + 1], 16, 2e-3, tags=tags, qmask=qm[r:r + 1], tight_tau=1e-5)
+    assert let_through[2e-3] >= 12 and let_through[1e-5] <= 2, let_through
+
+
 def test_compare_near_tie_rule(oracle):
     # two entries whose oracle scores differ by far less than tau may swap at the k boundary
     d = 64
