@@ -4,8 +4,7 @@
 //   kb_query     : prep_kernel                (query norms, counters reset)
 //                  scan kernel, sampling pass (kb_scan.hpp)
 //                  threshold_kernel           (k-th best group maximum per query)
-//                  scan kernel, main pass     (kb_scan.hpp)
-//                  bucket_kernel              (records of all workgroups -> per-query lists)
+//                  scan kernel, main pass     (kb_scan.hpp; its wavefronts move their records to per-query lists)
 //                  finalize_kernel            (top k of each query's list by radix selection; or the
 //                                              exhaustive per-query scan when a list overflowed)
 #include <stdlib.h>
@@ -70,17 +69,14 @@ int scan_config_for(int key_dtype, int Q, int d, int64_t n)
 namespace {
 
 constexpr int DEVICE_CUS = 256;        // compute units of an MI355X: the scan grids are sized for them (a device with fewer runs the same grid in turns)
-constexpr int MIN_REGION_CAP = 256;    // records per scan wavefront, at least
+constexpr int MAX_REGION_CAP = 8192;   // records a scan wavefront collects at most before it moves them to the lists
 constexpr int MAX_SAMPLE_SLOTS = 8192; // threshold_kernel sorts this many 64-bit words in LDS (64 KiB)
 constexpr int MAX_CAND_CAP = 8192;     // finalize_kernel likewise
 constexpr int MIN_CAND_CAP = 1024;
 constexpr int FALLBACK_PARTS = 32;    // workgroups that share the rows of a query on the exhaustive path
-constexpr int CAND_SEGMENTS = 16;     // per-query candidate list = this many independently counted segments
 constexpr size_t WS_ALIGN = 256;
 constexpr int FP8_QUERY_CONFIG = 5;    // scan configuration of fp8 keys with fp8 queries (kb_configs.hpp)
 constexpr int FP8_QUERY_WIDE_CONFIG = 20;     // ... with 128-byte row pieces: rows of a multiple of 128 bytes, 512 at least
-constexpr int STAT_WORDS = 4;          // candidates, exhaustive queries, sample keys, scan workgroups
-constexpr int STAT_PARTIALS = 64;      // the candidate count is kept as this many partial sums (one hot address would serialise)
 
 int key_bytes(kb_dtype_t t) { return t == KB_F32 ? 4 : t == KB_BF16 ? 2 : 1; }
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -179,7 +175,7 @@ int32_t cand_cap_for(int64_t expect, bool sampled)
 // Sizes of the workspace arrays.  The layout is a function of these alone and its total grows with each of them.
 struct Sizes {
     int32_t k, qpad, regions, sample_slots, cand_cap;
-    int64_t region_records;     // regions * region_cap
+    int64_t region_records;     // scan wavefronts * region_cap
     int64_t lgain_rows;
 };
 
@@ -195,7 +191,6 @@ void lay_out(const Sizes &z, Plan *p)
     p->fb_parts = z.cand_cap / KB_K_MAX < FALLBACK_PARTS ? z.cand_cap / KB_K_MAX : FALLBACK_PARTS;     // parts * k words fit the LDS buffer
     p->off_fb_done = off;     off = align_up(off + sizeof(uint32_t) * z.qpad);
     p->off_fb_lists = off;    off = align_up(off + sizeof(uint64_t) * (size_t)z.qpad * p->fb_parts * z.k);
-    p->off_region_cnt = off;  off = align_up(off + sizeof(uint32_t) * z.regions);
     p->off_qmask = off;       off = align_up(off + sizeof(uint64_t) * z.qpad);
     p->off_samp = off;        off = align_up(off + sizeof(uint64_t) * (size_t)z.qpad * (z.sample_slots > 0 ? z.sample_slots : 1));
     p->off_regions = off;     off = align_up(off + sizeof(Record) * (size_t)z.region_records);
@@ -206,7 +201,7 @@ void lay_out(const Sizes &z, Plan *p)
 
 // The plan of a query over n rows with the kernels `c`.  Apart from the ln(gain) array it depends on n through the
 // number of key tiles only, which is what lets kb_query_workspace_bytes bound it over all row counts.
-void plan_for(const kb *h, const Choice &c, int64_t n, int32_t Q, int32_t k, Plan *out, Sizes *sizes)
+void plan_for(const kb *h, const Choice &c, int64_t n, int32_t Q, int32_t k, bool draw, Plan *out, Sizes *sizes)
 {
     Plan p;
     memset(&p, 0, sizeof p);
@@ -239,11 +234,15 @@ void plan_for(const kb *h, const Choice &c, int64_t n, int32_t Q, int32_t k, Pla
     p.grid = (int32_t)grid;
     const int waves = ci.threads / 64;
     p.regions = (int32_t)(grid * waves);
-    // records per scan wavefront.  With a sampling pass: the share of a query block's lists (8 x the expected number
-    // of candidates) that falls to a wavefront if candidates are spread evenly; a region that overflows flags the
-    // query.  Without one every scored pair is a record: the pairs of the wavefront's part of its workgroup's items.
-    int64_t rc = st > 0 ? pow2_ceil(ceil_div((int64_t)p.cand_cap * Q, p.regions)) : pow2_ceil(ceil_div(items, grid) * ci.tk * ci.tq / waves);
-    if (rc < MIN_REGION_CAP) rc = MIN_REGION_CAP;
+    // Records a scan wavefront collects before it moves them to the per-query lists.  With a sampling pass few pairs
+    // pass the filter (a wavefront sees some tens in a whole scan).  Without one every scored pair is a record: room
+    // for the pairs of the wavefront's part of its workgroup's items, within limits.
+    int64_t rc = REGION_CAP;
+    if (st == 0) {
+        rc = pow2_ceil(ceil_div(items, grid) * ci.tk * ci.tq / waves);
+        if (rc < REGION_CAP) rc = REGION_CAP;
+        if (rc > MAX_REGION_CAP) rc = MAX_REGION_CAP;
+    }
     p.region_cap = (int32_t)rc;
 
     Sizes z;
@@ -253,7 +252,7 @@ void plan_for(const kb *h, const Choice &c, int64_t n, int32_t Q, int32_t k, Pla
     z.sample_slots = p.sample_slots;
     z.cand_cap = p.cand_cap;
     z.region_records = (int64_t)p.regions * rc;
-    z.lgain_rows = ceil_div(n, 256) * 256 + 256;
+    z.lgain_rows = draw ? ceil_div(n, 256) * 256 + 256 : 0;      // the weighted random selection only
     lay_out(z, &p);
     *out = p;
     if (sizes) *sizes = z;
@@ -265,7 +264,7 @@ bool make_plan(const kb *h, int64_t n, int32_t Q, int32_t k, bool draw, bool q8,
 {
     Choice c;
     if (!choose_kernels(h, n, Q, draw, q8, &c)) return false;
-    plan_for(h, c, n, Q, k, out, nullptr);
+    plan_for(h, c, n, Q, k, draw, out, nullptr);
     return true;
 }
 
@@ -288,21 +287,19 @@ void max_into(Sizes &m, const Sizes &z)
 //     st = nt / 2 (rounded down):                               expect <= 2k + 1 <= 257
 //     st = MAX_SAMPLE_SLOTS / groups:                           expect grows with nt, largest at the capacity
 //   (with the "sample_keys" knob st does not follow nt: the largest candidate capacity is assumed), so cand_cap is
-//   bounded; regions and sample_slots do not fall as nt grows; and regions * region_cap with
-//   region_cap = max(MIN_REGION_CAP, pow2_ceil(ceil(cand_cap Q / regions))) is below
-//   max(MIN_REGION_CAP regions, 2 (cand_cap Q + regions)).
+//   bounded; the number of scan wavefronts and sample_slots do not fall as nt grows, and region_cap is REGION_CAP.
 constexpr int64_t EXACT_TILES = 256;
-void bound_sizes(const kb *h, const Choice &c, int32_t Q, int32_t k, Sizes &m)
+void bound_sizes(const kb *h, const Choice &c, int32_t Q, int32_t k, bool draw, Sizes &m)
 {
     const ConfigInfo &ci = c.ci, &sci = c.sci;
     const int64_t cap_nt = ceil_div(h->capacity, ci.tk);
     Plan p;
     Sizes z;
     for (int64_t nt = 1; nt <= cap_nt && nt <= EXACT_TILES; ++nt) {
-        plan_for(h, c, nt * ci.tk, Q, k, &p, &z);
+        plan_for(h, c, nt * ci.tk, Q, k, draw, &p, &z);
         max_into(m, z);
     }
-    plan_for(h, c, h->capacity, Q, k, &p, &z);       // the ln(gain) array, and the largest grid
+    plan_for(h, c, h->capacity, Q, k, draw, &p, &z);       // the ln(gain) array, and the largest grid
     max_into(m, z);
     if (cap_nt <= EXACT_TILES) return;
     int64_t expect = 512;
@@ -310,8 +307,7 @@ void bound_sizes(const kb *h, const Choice &c, int32_t Q, int32_t k, Sizes &m)
     if (at_cap > expect) expect = at_cap;
     z.cand_cap = h->tune_sample_keys > 0 ? MAX_CAND_CAP : cand_cap_for(expect, true);
     z.sample_slots = (int32_t)(sample_tiles_for(h, sci, cap_nt, k, false) * sci.groups_per_tile);
-    const int64_t floor_records = (int64_t)MIN_REGION_CAP * z.regions, spread = 2 * ((int64_t)z.cand_cap * Q + z.regions);
-    z.region_records = floor_records > spread ? floor_records : spread;
+    z.region_records = (int64_t)z.regions * REGION_CAP;
     max_into(m, z);
 }
 
@@ -400,7 +396,7 @@ __global__ __launch_bounds__(256) void log_gain_kernel(const float *gain, int64_
 // prep: query norms + reset of the per-call counters
 // ------------------------------------------------------------------------------------------------
 template <int QT> __global__ __launch_bounds__(256) void prep_kernel(const void *queries, int Q, int qpad, int d, float *invq, uint64_t *thr64, float *thrp,
-                                                                       uint32_t *cnt, uint32_t *flag, uint32_t *region_cnt, int regions, uint64_t *stats, uint64_t sample_keys,
+                                                                       uint32_t *cnt, uint32_t *flag, uint64_t *stats, uint64_t sample_keys,
                                                                        const uint64_t *qmask, uint64_t *qmask_pad, int grid, uint32_t *fb_done)
 {
     const int t = blockIdx.x * 256 + threadIdx.x;
@@ -412,7 +408,6 @@ template <int QT> __global__ __launch_bounds__(256) void prep_kernel(const void 
         flag[t] = 0;
         qmask_pad[t] = (qmask && t < Q) ? qmask[t] : 0ull;
     }
-    if (t < regions) region_cnt[t] = 0;
     if (t < STAT_WORDS + STAT_PARTIALS) stats[t] = t == 2 ? sample_keys : t == 3 ? (uint64_t)grid : 0ull;
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -578,32 +573,6 @@ __global__ __launch_bounds__(1024) void threshold_kernel(const uint64_t *samp, i
         thr64[q] = t;
         thrp[q] = tp;
     }
-}
-
-// Records of every scan wavefront -> one list per query.  A query's list is CAND_SEGMENTS segments with a
-// counter each (the regions of scan workgroup w feed segment w % CAND_SEGMENTS), so that the slot-claiming atomics of one query are
-// spread over that many addresses instead of serialising on one.
-__global__ __launch_bounds__(256) void bucket_kernel(const Record *regions, const uint32_t *region_cnt, int region_cap, uint64_t *cand, int cand_cap,
-                                                      uint32_t *cnt, uint32_t *flag, uint64_t *stats, int waves_per_wg)
-{
-    // one workgroup per wavefront region (many small workgroups hide the latency of the slot-claiming atomics
-    // better than few large ones)
-    const uint32_t n = region_cnt[blockIdx.x];
-    const Record *r = regions + (size_t)blockIdx.x * region_cap;
-    // A candidate's segment comes from its row number, so a query's candidates spread over all segments even when
-    // they sit in a few neighbouring tiles (rows grouped by cluster) and were found by a few workgroups.
-    const uint32_t seg_cap = (uint32_t)cand_cap / CAND_SEGMENTS;
-    for (uint32_t i = threadIdx.x; i < n; i += 256) {
-        const Record rec = r[i];
-        const uint32_t row = candidate_index(rec.cand), seg = (row ^ (row >> 4) ^ (row >> 8)) % CAND_SEGMENTS;
-        const uint32_t slot = atomicAdd(&cnt[rec.query * CAND_SEGMENTS + seg], 1u);
-        if (slot < seg_cap)
-            cand[(size_t)rec.query * cand_cap + seg * seg_cap + slot] = rec.cand;
-        else
-            flag[rec.query] = 1u;
-    }
-    if (threadIdx.x == 0 && n)
-        atomicAdd(reinterpret_cast<unsigned long long *>(stats + STAT_WORDS + blockIdx.x % STAT_PARTIALS), (unsigned long long)n);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1083,7 +1052,7 @@ size_t kb_query_workspace_bytes(const kb_t *kb, int32_t Q, int32_t k)
         for (int kind = 0; kind < 3; ++kind) {      // plain, weighted random selection, fp8 queries
             Choice c;
             if (!choose_kernels(kb, n, Q, kind == 1, kind == 2, &c)) continue;
-            bound_sizes(kb, c, Q, k, m);
+            bound_sizes(kb, c, Q, k, kind == 1, m);
             any = true;
         }
     if (!any) return 0;
@@ -1143,7 +1112,6 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
     uint32_t *cnt = reinterpret_cast<uint32_t *>(ws + p.off_cnt);
     uint32_t *flag = reinterpret_cast<uint32_t *>(ws + p.off_flag);
     uint32_t *fb_done = reinterpret_cast<uint32_t *>(ws + p.off_fb_done);
-    uint32_t *region_cnt = reinterpret_cast<uint32_t *>(ws + p.off_region_cnt);
     uint64_t *stats = reinterpret_cast<uint64_t *>(ws + p.off_stats);
     uint64_t *qmask_pad = reinterpret_cast<uint64_t *>(ws + p.off_qmask);
     uint64_t *samp = reinterpret_cast<uint64_t *>(ws + p.off_samp);
@@ -1166,15 +1134,15 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
     }
 
     {
-        const int n_init = p.qpad > p.regions ? p.qpad : p.regions;
+        const int n_init = p.qpad > STAT_WORDS + STAT_PARTIALS ? p.qpad : STAT_WORDS + STAT_PARTIALS;
         const int blocks_rows = (int)ceil_div(p.qpad, 4), blocks_init = (int)ceil_div(n_init, 256);
         const unsigned grid = blocks_rows > blocks_init ? blocks_rows : blocks_init;
         if (q_dtype == KB_F32)
-            hipLaunchKernelGGL(prep_kernel<KB_F32>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, region_cnt, p.regions, stats, (uint64_t)p.sample_keys, qmask_dev, qmask_pad, p.grid, fb_done);
+            hipLaunchKernelGGL(prep_kernel<KB_F32>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, stats, (uint64_t)p.sample_keys, qmask_dev, qmask_pad, p.grid, fb_done);
         else if (q_dtype == KB_FP8_E4M3)
-            hipLaunchKernelGGL(prep_kernel<KB_FP8_E4M3>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, region_cnt, p.regions, stats, (uint64_t)p.sample_keys, qmask_dev, qmask_pad, p.grid, fb_done);
+            hipLaunchKernelGGL(prep_kernel<KB_FP8_E4M3>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, stats, (uint64_t)p.sample_keys, qmask_dev, qmask_pad, p.grid, fb_done);
         else
-            hipLaunchKernelGGL(prep_kernel<KB_BF16>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, region_cnt, p.regions, stats, (uint64_t)p.sample_keys, qmask_dev, qmask_pad, p.grid, fb_done);
+            hipLaunchKernelGGL(prep_kernel<KB_BF16>, dim3(grid), dim3(256), 0, s, queries_dev, Q, p.qpad, kb->d, invq, thr64, thrp, cnt, flag, stats, (uint64_t)p.sample_keys, qmask_dev, qmask_pad, p.grid, fb_done);
         if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
     }
 
@@ -1191,7 +1159,10 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
         a.thrp = thrp;
         a.samp = samp;
         a.regions = regions;
-        a.region_cnt = region_cnt;
+        a.cand = cand;
+        a.cnt = cnt;
+        a.stats = stats;
+        a.cand_cap = p.cand_cap;
         a.flag = flag;
         a.n_keys = kb->n;
         a.d = kb->d;
@@ -1234,8 +1205,6 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
             if (hipEventRecord(kb->prof_events[2 * kb->prof_used + 1], s) != hipSuccess) return KB_ERR_DEVICE;
             ++kb->prof_used;
         }
-        hipLaunchKernelGGL(bucket_kernel, dim3(p.regions), dim3(256), 0, s, regions, region_cnt, p.region_cap, cand, p.cand_cap, cnt, flag, stats, p.regions / p.grid);
-        if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
     }
 
     FinalArgs f;

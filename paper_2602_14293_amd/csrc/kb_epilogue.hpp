@@ -23,6 +23,32 @@ __device__ inline float select16(const f32x16 &a, int i)
     return v;
 }
 
+// The records a wavefront has collected in its private region go to the per-query candidate lists: one lane per
+// record claims a slot of the record's (query, segment) with a device-wide atomic and stores the candidate word
+// there; a full segment flags the query (it is then resolved exhaustively).  Called when the region is nearly full
+// and when the wavefront ends, by all its lanes.  The region was written by this wavefront's own global stores: they
+// are waited for, and read back past the vector L1 (agent scope), which may hold lines from an earlier call here.
+__device__ inline void flush_records(const ScanArgs &p, Record *region, uint32_t &wave_cnt, uint32_t region_id)
+{
+    if (wave_cnt == 0) return;
+    __builtin_amdgcn_s_waitcnt(0x0070 | 0x0F00);        // vmcnt(0): the stores of the records
+    const uint32_t lane = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    const uint32_t seg_cap = (uint32_t)p.cand_cap / CAND_SEGMENTS;
+    for (uint32_t i = lane; i < wave_cnt; i += 64) {
+        const uint64_t cw = __hip_atomic_load(&region[i].cand, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t q = __hip_atomic_load(&region[i].query, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t seg = candidate_segment(candidate_index(cw));
+        const uint32_t slot = atomicAdd(&p.cnt[q * CAND_SEGMENTS + seg], 1u);
+        if (slot < seg_cap)
+            p.cand[(size_t)q * p.cand_cap + seg * seg_cap + slot] = cw;
+        else
+            p.flag[q] = 1u;
+    }
+    if (lane == 0)
+        atomicAdd(reinterpret_cast<unsigned long long *>(p.stats + STAT_WORDS + region_id % STAT_PARTIALS), (unsigned long long)wave_cnt);
+    wave_cnt = 0;
+}
+
 // Main pass.  Per block: a bound test (largest dot times largest 1/|k| of the lane's 16 rows against the
 // query's pre-filter) costs one max-reduction and decides whether any lane has to look closer; lanes that
 // do build the 16-bit mask of elements passing the exact pre-filter (sign bit of fma(dot, inv_k, -thrp),
@@ -30,8 +56,9 @@ __device__ inline float select16(const f32x16 &a, int i)
 // wave-uniform element index: it takes the mask of one lane that has work (v_readlane), and for each of
 // its set bits every lane with that bit handles that element: final score, candidate word, threshold
 // word, tag predicate, append to the wave's private record region (no atomics: slot = the wave's running
-// count + the lane's rank among the appending lanes).  A uniform index turns the element selection into
-// an indexed register read instead of a 16-way select per lane.
+// count + the lane's rank among the appending lanes; flush_records moves a full region to the per-query
+// lists).  A uniform index turns the element selection into an indexed register read instead of a 16-way
+// select per lane.
 struct EpiRows {               // 1/|k| of the 16 key rows a lane holds in one 32-row block
     float ik[16];
     float ikmax;
@@ -58,7 +85,7 @@ __device__ inline EpiRows load_rows(const EpiSide &sd, int rl0)
 }
 
 __device__ inline void main_block(const f32x16 &a, const EpiRows &rw, float tp, int ql, const EpiSide &sd, bool filter,
-                                  int64_t row0, int q0, const ScanArgs &p, Record *region, uint32_t &wave_cnt)
+                                  int64_t row0, int q0, const ScanArgs &p, Record *region, uint32_t &wave_cnt, uint32_t region_id)
 {
     float amax = a[0];
 #pragma unroll
@@ -96,19 +123,17 @@ __device__ inline void main_block(const f32x16 &a, const EpiRows &rw, float tp, 
             const uint64_t cw = pack_candidate(s, (uint32_t)row);
             bool ok = has && row < p.n_keys && cw >= t64 && !row_removed(ik);
             if (filter) ok = ok && (tg & qm) != 0;
-            // slot in the wave's own record region: running count + rank among the lanes that append
+            // slot in the wave's own record region: running count + rank among the lanes that append (up to 64 of
+            // them: the region is emptied first when fewer slots are left)
             const uint64_t okm = __builtin_amdgcn_ballot_w64(ok);
+            if (okm != 0 && wave_cnt + 64 > (uint32_t)p.region_cap) flush_records(p, region, wave_cnt, region_id);
             if (ok) {
                 const uint32_t pos = wave_cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(okm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)okm, 0u));
-                if (pos < (uint32_t)p.region_cap) {
-                    Record rec;
-                    rec.cand = cw;
-                    rec.query = (uint32_t)(q0 + ql);
-                    rec.pad = 0;
-                    region[pos] = rec;
-                } else {
-                    p.flag[q0 + ql] = 1u;
-                }
+                Record rec;
+                rec.cand = cw;
+                rec.query = (uint32_t)(q0 + ql);
+                rec.pad = 0;
+                region[pos] = rec;
             }
             wave_cnt += (uint32_t)__builtin_popcountll(okm);
         } while (m != 0);
@@ -118,7 +143,7 @@ __device__ inline void main_block(const f32x16 &a, const EpiRows &rw, float tp, 
 
 template <int IB, int JB>
 __device__ inline void main_epilogue(const f32x16 (&acc)[IB][JB], const EpiSide &sd, bool filter, int wave_row0, int ql0,
-                                     int half, int64_t row0, int q0, const ScanArgs &p, Record *region, uint32_t &wave_cnt)
+                                     int half, int64_t row0, int q0, const ScanArgs &p, Record *region, uint32_t &wave_cnt, uint32_t region_id)
 {
     float thrp[JB];
 #pragma unroll
@@ -128,7 +153,7 @@ __device__ inline void main_epilogue(const f32x16 (&acc)[IB][JB], const EpiSide 
         const EpiRows rw = load_rows(sd, wave_row0 + ib * 32 + 4 * half);
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb)
-            main_block(acc[ib][jb], rw, thrp[jb], ql0 + jb * 32, sd, filter, row0, q0, p, region, wave_cnt);
+            main_block(acc[ib][jb], rw, thrp[jb], ql0 + jb * 32, sd, filter, row0, q0, p, region, wave_cnt, region_id);
     }
 }
 
@@ -255,7 +280,7 @@ __device__ inline void block_keys(const f32x16 &a, const EpiRows &rw, float iq, 
 // computed and compared with the query's threshold key; survivors are then handled exactly like the survivors
 // of the score pass (their keys are recomputed: same inputs, same bits).
 __device__ inline void main_block_draw(const f32x16 &a, const EpiRows &rw, float tp, int ql, const EpiSide &sd, bool filter,
-                                       int64_t row0, int q0, const ScanArgs &p, Record *region, uint32_t &wave_cnt)
+                                       int64_t row0, int q0, const ScanArgs &p, Record *region, uint32_t &wave_cnt, uint32_t region_id)
 {
     const float iq = sd.invq[ql];
     const uint32_t query = p.draw.first_query + (uint32_t)(q0 + ql);
@@ -285,17 +310,14 @@ __device__ inline void main_block_draw(const f32x16 &a, const EpiRows &rw, float
             bool ok = has && row < p.n_keys && kv > -__builtin_inff() && cw >= t64 && !row_removed(ik);
             if (filter) ok = ok && (sd.tag[rl] & qm) != 0;
             const uint64_t okm = __builtin_amdgcn_ballot_w64(ok);
+            if (okm != 0 && wave_cnt + 64 > (uint32_t)p.region_cap) flush_records(p, region, wave_cnt, region_id);
             if (ok) {
                 const uint32_t pos = wave_cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(okm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)okm, 0u));
-                if (pos < (uint32_t)p.region_cap) {
-                    Record rec;
-                    rec.cand = cw;
-                    rec.query = (uint32_t)(q0 + ql);
-                    rec.pad = 0;
-                    region[pos] = rec;
-                } else {
-                    p.flag[q0 + ql] = 1u;
-                }
+                Record rec;
+                rec.cand = cw;
+                rec.query = (uint32_t)(q0 + ql);
+                rec.pad = 0;
+                region[pos] = rec;
             }
             wave_cnt += (uint32_t)__builtin_popcountll(okm);
         } while (m != 0);
@@ -305,14 +327,14 @@ __device__ inline void main_block_draw(const f32x16 &a, const EpiRows &rw, float
 
 template <int IB, int JB>
 __device__ inline void main_epilogue_draw(const f32x16 (&acc)[IB][JB], const EpiSide &sd, bool filter, int wave_row0, int ql0,
-                                          int half, int64_t row0, int q0, const ScanArgs &p, Record *region, uint32_t &wave_cnt)
+                                          int half, int64_t row0, int q0, const ScanArgs &p, Record *region, uint32_t &wave_cnt, uint32_t region_id)
 {
 #pragma unroll
     for (int ib = 0; ib < IB; ++ib) {
         const EpiRows rw = load_rows(sd, wave_row0 + ib * 32 + 4 * half);
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb)
-            main_block_draw(acc[ib][jb], rw, sd.thrp[ql0 + jb * 32], ql0 + jb * 32, sd, filter, row0, q0, p, region, wave_cnt);
+            main_block_draw(acc[ib][jb], rw, sd.thrp[ql0 + jb * 32], ql0 + jb * 32, sd, filter, row0, q0, p, region, wave_cnt, region_id);
     }
 }
 

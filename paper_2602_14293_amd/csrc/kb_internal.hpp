@@ -70,6 +70,19 @@ struct Record {  // one candidate that passed the threshold filter of the scan
     uint32_t pad;
 };
 
+// A query's candidate list is CAND_SEGMENTS segments with a counter each, so that the slot-claiming atomics of one
+// query are spread over that many addresses instead of serialising on one.  A candidate's segment comes from its
+// row number: a query's candidates spread over all segments even when they sit in a few neighbouring tiles (rows
+// grouped by cluster) and were found by a few workgroups; consecutive rows take the segments in turn.
+constexpr int CAND_SEGMENTS = 16;
+__host__ __device__ inline uint32_t candidate_segment(uint32_t row) { return (row ^ (row >> 4) ^ (row >> 8)) % CAND_SEGMENTS; }
+// Diagnostics at the start of the workspace: STAT_WORDS words (candidates, exhaustive queries, sample keys, scan
+// workgroups), then the candidate count as STAT_PARTIALS partial sums (one hot address would serialise).
+constexpr int STAT_WORDS = 4;
+constexpr int STAT_PARTIALS = 64;
+// Records a scan wavefront collects before it moves them to the per-query lists (it also does so when it ends).
+constexpr int REGION_CAP = 128;
+
 // Workspace layout (offsets in bytes from a 256-byte aligned base).
 struct Plan {
     int32_t Q, k, tq, nqb, qpad;        // queries, tile width in queries, query blocks, padded count
@@ -82,12 +95,12 @@ struct Plan {
     int64_t sample_keys;                // rows they cover
     int32_t sample_slots;               // sample_tiles * groups_per_tile, per query
     int32_t grid;                       // workgroups of the main scan
-    int32_t region_cap;                 // records per scan wavefront
+    int32_t region_cap;                 // records a scan wavefront collects before it moves them to the lists
     int32_t regions;                    // grid * wavefronts per workgroup
     int32_t cand_cap;                   // candidates per query the final sort can take (power of two)
     size_t off_fb_done, off_fb_lists;       // exhaustive path: per-query arrival counters, per-(query, part) partial lists
     int32_t fb_parts;                      // parts the rows are split into when a query takes the exhaustive path
-    size_t off_invq, off_thr64, off_thrp, off_cnt, off_flag, off_region_cnt, off_stats, off_qmask, off_samp, off_regions,
+    size_t off_invq, off_thr64, off_thrp, off_cnt, off_flag, off_stats, off_qmask, off_samp, off_regions,
         off_cand, off_lgain, total;
 };
 
@@ -114,14 +127,16 @@ struct ScanArgs {
     const float *thrp;        // [qpad] conservative pre-filter on dot * inv_k
     uint64_t *samp;           // sampling pass output [qpad][sample_slots]
     Record *regions;          // [grid * waves per workgroup][region_cap]: one private region per wavefront
-    uint32_t *region_cnt;     // [grid * waves per workgroup]
-    uint32_t *flag;           // [qpad] set to 1 when a query lost a candidate to a full buffer
+    uint64_t *cand;           // [qpad][cand_cap] per-query candidate lists, CAND_SEGMENTS segments each
+    uint32_t *cnt;            // [qpad][CAND_SEGMENTS] entries claimed in each segment (zero before the launch)
+    uint32_t *flag;           // [qpad] set to 1 when a query lost a candidate to a full list
+    uint64_t *stats;          // diagnostics (see STAT_WORDS)
     int64_t n_keys;           // rows to scan: [0, n_keys)
     int64_t n_tiles;          // key tiles to scan: logical tile t is rows [t * tile_stride * TK, +TK)
     int32_t tile_stride;      // 1 for the main pass; a sampling pass takes every tile_stride-th tile ...
     uint64_t row_mul;         // ... or, when nonzero, scatters its rows in runs of 2^row_run_shift (see sample_row)
     int32_t row_run_shift;
-    int32_t d, Q, nqb, sample_slots, region_cap;
+    int32_t d, Q, nqb, sample_slots, region_cap, cand_cap;
     DrawArgs draw;
 };
 

@@ -353,9 +353,9 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
                 sample_epilogue<IB, JB>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p,
                                         (int64_t)tile * C::GROUPS_PER_TILE + wm * 2 + half);
             else if (DRAW)
-                main_epilogue_draw<IB, JB>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p, my_region, wave_cnt);
+                main_epilogue_draw<IB, JB>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p, my_region, wave_cnt, blockIdx.x * NW + wave);
             else
-                main_epilogue<IB, JB>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p, my_region, wave_cnt);
+                main_epilogue<IB, JB>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p, my_region, wave_cnt, blockIdx.x * NW + wave);
 #pragma unroll
             for (int ib = 0; ib < IB; ++ib)
 #pragma unroll
@@ -372,10 +372,7 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
         }
     }
 
-    if (!SAMPLE && lane == 0) {
-        const uint32_t cap = (uint32_t)p.region_cap;
-        p.region_cnt[blockIdx.x * NW + wave] = wave_cnt < cap ? wave_cnt : cap;
-    }
+    if (!SAMPLE) flush_records(p, my_region, wave_cnt, blockIdx.x * NW + wave);      // what is left in the region
 }
 
 template <class C> hipError_t launch_scan_cfg(bool sample, int grid, const ScanArgs &a, hipStream_t s)

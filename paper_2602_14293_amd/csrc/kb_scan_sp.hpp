@@ -277,7 +277,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
             sample_epilogue<IB, JB>(acc, sd, filter, wm * 64, rowB, half, row0, qb * TQ, p,
                                     (int64_t)tile * C::GROUPS_PER_TILE + wm * 2 + half);
         else
-            main_epilogue<IB, JB>(acc, sd, filter, wm * 64, rowB, half, row0, qb * TQ, p, my_region, wave_cnt);
+            main_epilogue<IB, JB>(acc, sd, filter, wm * 64, rowB, half, row0, qb * TQ, p, my_region, wave_cnt, blockIdx.x * NW + wave);
 #pragma unroll
         for (int ib = 0; ib < IB; ++ib)
 #pragma unroll
@@ -598,10 +598,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
 #undef KB_SP_MFMA
 #undef KB_SP_LOAD
 
-    if (!SAMPLE && lane == 0) {
-        const uint32_t cap = (uint32_t)p.region_cap;
-        p.region_cnt[blockIdx.x * NW + wave] = wave_cnt < cap ? wave_cnt : cap;
-    }
+    if (!SAMPLE) flush_records(p, my_region, wave_cnt, blockIdx.x * NW + wave);      // what is left in the region
 }
 
 template <class C> hipError_t launch_scan_sp_cfg(bool sample, int grid, const ScanArgs &a, hipStream_t s)

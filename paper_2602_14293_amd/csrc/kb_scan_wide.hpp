@@ -295,7 +295,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
                 sample_epilogue<IB, JB>(acc[rh], sd, filter, rh * 128 + wm * 64, qrow, half, row0, qb * TQ, p,
                                         (int64_t)tile * C::GROUPS_PER_TILE + (rh * 2 + wm) * 2 + half);
             else
-                main_epilogue<IB, JB>(acc[rh], sd, filter, rh * 128 + wm * 64, qrow, half, row0, qb * TQ, p, my_region, wave_cnt);
+                main_epilogue<IB, JB>(acc[rh], sd, filter, rh * 128 + wm * 64, qrow, half, row0, qb * TQ, p, my_region, wave_cnt, blockIdx.x * NW + wave);
 #pragma unroll
             for (int ib = 0; ib < IB; ++ib)
 #pragma unroll
@@ -519,10 +519,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
         __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));             // the loads past the end of the stream
     }
 
-    if (!SAMPLE && lane == 0) {
-        const uint32_t cap = (uint32_t)p.region_cap;
-        p.region_cnt[blockIdx.x * NW + wave] = wave_cnt < cap ? wave_cnt : cap;
-    }
+    if (!SAMPLE) flush_records(p, my_region, wave_cnt, blockIdx.x * NW + wave);      // what is left in the region
 }
 
 template <class C> hipError_t launch_scan_wide_cfg(bool sample, int grid, const ScanArgs &a, hipStream_t s)
