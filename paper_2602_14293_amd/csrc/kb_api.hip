@@ -1,9 +1,9 @@
 // libkb: C ABI, host-side planning, and the small kernels around the scan (gfx950 only).
 //
 //   kb_normalize : row_norm_kernel            (row L2 norms as a side scale)
-//   kb_query     : prep_kernel                (query norms, counters reset)
-//                  scan kernel, sampling pass (kb_scan.hpp)
-//                  threshold_kernel           (k-th best group maximum per query)
+//   kb_query     : scan kernel, sampling pass (kb_scan.hpp)
+//                  threshold_kernel           (k-th best group maximum per query; query norms, counters reset)
+//                  [prep_kernel               (query norms, counters reset: when no sampling pass runs)]
 //                  scan kernel, main pass     (kb_scan.hpp; its wavefronts move their records to per-query lists)
 //                  finalize_kernel            (top k of each query's list by radix selection; or the
 //                                              exhaustive per-query scan when a list overflowed)
@@ -549,29 +549,82 @@ __device__ inline void select_topk_desc(uint64_t *buf, int n, int k, SelectScrat
 // entries reach it).  Also derives the conservative pre-filter on dot * inv_k used by the main pass:
 // whenever fp32((dot*inv_k) * inv_q) >= s_thr holds, dot*inv_k >= thrp holds (2^-20 relative slack
 // covers the three fp32 roundings involved).
-__global__ __launch_bounds__(1024) void threshold_kernel(const uint64_t *samp, int slots, int k, const float *invq, uint64_t *thr64, float *thrp,
-                                                         int draw)
+//
+// Two modes.  KEYS (weighted random selection; prep_kernel has run): the samples are candidate words of keys and the
+// k-th best word is the threshold as it is.  Otherwise the kernel also does what prep_kernel does (the query's
+// 1/|q|, its counters, flag and padded mask word; one workgroup per PADDED query), so that a plain query has one
+// launch less, and the samples are words of s1 = dot * inv_k, which the sampling pass can form without 1/|q|.  The final
+// score f(s1) = fp32(s1 * inv_q) + 0 never falls as s1 grows, so the k sampled entries with the largest words all
+// have a score >= S = f(s1 of the k-th); those of them whose score equals S have an index <= the largest such
+// index, and the threshold word is (S, that index): k distinct entries reach it.
+struct ThresholdArgs {
+    const uint64_t *samp;       // [qpad][slots]
+    const void *queries;
+    const uint64_t *qmask;      // or nullptr
+    float *invq, *thrp;
+    uint64_t *thr64, *qmask_pad, *stats;
+    uint32_t *cnt, *flag, *fb_done;
+    uint64_t sample_keys;
+    int32_t slots, k, Q, d, grid;
+};
+
+template <int QT, bool KEYS> __global__ __launch_bounds__(1024) void threshold_kernel(ThresholdArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     uint64_t *buf = reinterpret_cast<uint64_t *>(smem_raw);
-    const int q = blockIdx.x, tid = threadIdx.x;
+    const int q = blockIdx.x, tid = threadIdx.x, slots = a.slots, k = a.k;
     SelectScratch *sc = reinterpret_cast<SelectScratch *>(smem_raw + sizeof(uint64_t) * (slots > k ? slots : k));
-    for (int i = tid; i < slots; i += (int)blockDim.x) buf[i] = samp[(size_t)q * slots + i];
+    __shared__ float sh_iq;
+    __shared__ uint32_t sh_low;
+    if constexpr (!KEYS) {
+        if (tid < CAND_SEGMENTS) a.cnt[q * CAND_SEGMENTS + tid] = 0;
+        if (tid == 0) {
+            a.flag[q] = 0;
+            a.fb_done[q] = 0;
+            a.qmask_pad[q] = (a.qmask && q < a.Q) ? a.qmask[q] : 0ull;
+            sh_low = 0xffffffffu;
+        }
+        if (q == 0 && tid < STAT_WORDS + STAT_PARTIALS) a.stats[tid] = tid == 2 ? a.sample_keys : tid == 3 ? (uint64_t)a.grid : 0ull;
+        if (q >= a.Q) {         // a padding query can never pass the filter of the scan
+            if (tid == 0) {
+                a.invq[q] = 0.f;
+                a.thr64[q] = ~0ull;
+                a.thrp[q] = __builtin_inff();
+            }
+            return;
+        }
+        if (tid < 64) {
+            const float inv = row_inv_norm<QT>(a.queries, q, a.d * (QT == KB_F32 ? 4 : QT == KB_BF16 ? 2 : 1), tid);
+            if (tid == 0) {
+                a.invq[q] = inv;
+                sh_iq = inv;
+            }
+        }
+    }
+    for (int i = tid; i < slots; i += (int)blockDim.x) buf[i] = a.samp[(size_t)q * slots + i];
     __syncthreads();
     select_topk_desc(buf, slots, k, sc, tid, (int)blockDim.x);
+    uint64_t t = k <= slots ? buf[k - 1] : 0ull;
+    const float iq = KEYS ? a.invq[q] : sh_iq;
+    if constexpr (!KEYS) {
+        if (t != 0) {
+            const float s = candidate_score(t) * iq + 0.0f;
+            if (tid < k && candidate_score(buf[tid]) * iq + 0.0f == s) atomicMin(&sh_low, (uint32_t)buf[tid]);
+            __syncthreads();
+            t = ((uint64_t)score_to_ordered(s) << 32) | sh_low;
+        }
+    }
     if (tid == 0) {
-        const uint64_t t = k <= slots ? buf[k - 1] : 0ull;
-        const float iq = invq[q];
         float tp = -__builtin_inff();
-        if (draw) {
+        if (KEYS) {
             // keys are compared as they are: a word at or above t has a key at or above t's key
             if (t != 0) tp = candidate_score(t);
         } else if (t != 0 && iq > 0.f) {
             const float x = candidate_score(t) / iq;
             tp = x - fabsf(x) * 0x1p-20f - 1e-30f;
         }
-        thr64[q] = t;
-        thrp[q] = tp;
+        a.thr64[q] = t;
+        a.thrp[q] = tp;
     }
 }
 
@@ -1133,7 +1186,10 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
         if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
     }
 
-    {
+    // Query norms and per-call counters: the threshold kernel sets them when there is a sampling pass on scores;
+    // otherwise (no sampling pass, or the weighted random selection, whose sampling pass needs 1/|q|) this launch does.
+    const bool sampled = kb->n > 0 && p.sample_tiles > 0;
+    if (!sampled || draw) {
         const int n_init = p.qpad > STAT_WORDS + STAT_PARTIALS ? p.qpad : STAT_WORDS + STAT_PARTIALS;
         const int blocks_rows = (int)ceil_div(p.qpad, 4), blocks_init = (int)ceil_div(n_init, 256);
         const unsigned grid = blocks_rows > blocks_init ? blocks_rows : blocks_init;
@@ -1189,10 +1245,32 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
             if (launch_scan(kb->dtype, p.sample_config, p.sample_family, true, (int)sgrid, a, s) != hipSuccess) return KB_ERR_DEVICE;
             const int thr_threads = p.sample_slots > 1024 ? 1024 : p.sample_slots > 512 ? 512 : 256;
             const size_t thr_lds = sizeof(uint64_t) * (p.sample_slots > k ? p.sample_slots : k) + sizeof(SelectScratch);
-            static LdsAllowed thr_allowed;
-            if (allow_dynamic_lds(reinterpret_cast<const void *>(&threshold_kernel), thr_allowed, MAX_SAMPLE_SLOTS * 8 + sizeof(SelectScratch)) != hipSuccess)
+            ThresholdArgs t;
+            t.samp = samp;
+            t.queries = queries_dev;
+            t.qmask = qmask_dev;
+            t.invq = invq;
+            t.thrp = thrp;
+            t.thr64 = thr64;
+            t.qmask_pad = qmask_pad;
+            t.stats = stats;
+            t.cnt = cnt;
+            t.flag = flag;
+            t.fb_done = fb_done;
+            t.sample_keys = (uint64_t)p.sample_keys;
+            t.slots = p.sample_slots;
+            t.k = k;
+            t.Q = Q;
+            t.d = kb->d;
+            t.grid = p.grid;
+            static LdsAllowed thr_allowed[4];
+            const int thr_kind = draw ? 3 : (int)q_dtype;
+            void (*thr_fn)(ThresholdArgs) = draw ? &threshold_kernel<KB_F32, true>
+                                          : q_dtype == KB_F32 ? &threshold_kernel<KB_F32, false>
+                                          : q_dtype == KB_BF16 ? &threshold_kernel<KB_BF16, false> : &threshold_kernel<KB_FP8_E4M3, false>;
+            if (allow_dynamic_lds(reinterpret_cast<const void *>(thr_fn), thr_allowed[thr_kind], MAX_SAMPLE_SLOTS * 8 + sizeof(SelectScratch)) != hipSuccess)
                 return KB_ERR_DEVICE;
-            hipLaunchKernelGGL(threshold_kernel, dim3(Q), dim3(thr_threads), thr_lds, s, samp, p.sample_slots, k, invq, thr64, thrp, draw ? 1 : 0);
+            hipLaunchKernelGGL(thr_fn, dim3(draw ? Q : p.qpad), dim3(thr_threads), thr_lds, s, t);
             if (hipGetLastError() != hipSuccess) return KB_ERR_DEVICE;
         }
         a.n_tiles = ceil_div(kb->n, p.tk);

@@ -157,9 +157,10 @@ __device__ inline void main_epilogue(const f32x16 (&acc)[IB][JB], const EpiSide 
     }
 }
 
-// Sampling pass: per lane and query column, one qualifying entry of the lane's rows with (nearly) the
-// largest score, as a candidate word with its exact final score.  Any qualifying entry is a valid sample;
-// taking the maximum of dot * inv_k (first one on ties) makes it the group's best or a tie of it.
+// Sampling pass: per lane and query column, one qualifying entry of the lane's rows with the largest
+// s1 = dot * inv_k (first one on ties), stored as the candidate word of s1.  The final score is a
+// non-decreasing function of s1 (one more fp32 product with 1/|q| >= 0), which the threshold kernel applies:
+// the sampling pass itself needs no per-query value but the mask word.  Any qualifying entry is a valid sample.
 __device__ inline void sample_block(const f32x16 &a, int rl0, const EpiSide &sd, bool filter, uint64_t qm, int64_t row0,
                                     int64_t n_keys, float &best, int &best_rl)
 {
@@ -183,7 +184,7 @@ __device__ inline void sample_store(float best, int best_rl, int ql, const EpiSi
     if (q0 + ql < p.Q) {
         uint64_t cw = 0ull;
         if (best_rl >= 0)       // best = dot * inv_k was computed exactly as final_score's first product
-            cw = pack_candidate(best * sd.invq[ql] + 0.0f, sample_index(p, row0 + best_rl));
+            cw = pack_candidate(best, sample_index(p, row0 + best_rl));
         p.samp[(size_t)(q0 + ql) * p.sample_slots + slot] = cw;
     }
 }

@@ -290,7 +290,7 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
             }
             if (tid < TQ) {
                 const int q = qb * TQ + tid;            // < qpad: invq, thr64 and thrp are padded arrays
-                my_invq = p.invq[q];
+                if (!SAMPLE || DRAW) my_invq = p.invq[q];      // (a sampling pass on scores runs before 1/|q| exists)
                 if (!SAMPLE) {
                     my_thr64 = p.thr64[q];
                     my_thrp = p.thrp[q];

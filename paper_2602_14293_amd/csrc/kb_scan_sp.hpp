@@ -163,16 +163,29 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
                                              (lds_ptr)(aux + C::AUX_TAG + wave * 256), 4, 0, 0);
         }
     };
-    // side data of a query block: 16-byte loads from the library's padded per-query arrays, one array per wave
+    // side data of a query block: 16-byte loads from the library's padded per-query arrays, one array per wave.  A
+    // sampling pass runs before those exist and needs the mask words only: it takes them from the caller's array as
+    // dwords with clamped query numbers (wave w covers queries [32 w, 32 w + 32), and the next 32 x 8 with 256 queries).
     auto issue_query_aux = [&](int qb) {
         lds_u8 *aux = lds + C::OFF_QAUX;
         const int q0 = qb * TQ;
+        if constexpr (SAMPLE) {
+            if (filter) {
+                const int last = p.Q - 1 - q0;
+                for (int i = wave; i < TQ / 32; i += NW) {
+                    const int r = i * 32 + (lane >> 1);
+                    __builtin_amdgcn_global_load_lds((const void *)(reinterpret_cast<const uint32_t *>(p.qmask + q0 + (r < last ? r : last)) + (lane & 1)),
+                                                     (lds_ptr)(aux + C::QAUX_QMASK + i * 256), 4, 0, 0);
+                }
+            }
+            return;
+        }
         constexpr int L4 = TQ / 4, W8 = TQ * 8 / 1024;          // lanes that cover a float array; waves that cover a 64-bit array
         if (wave == 0 && lane < L4)
             __builtin_amdgcn_global_load_lds((const void *)(p.invq + q0 + lane * 4), (lds_ptr)(aux + C::QAUX_INVQ), 16, 0, 0);
-        if (wave == 1 && !SAMPLE && lane < L4)
+        if (wave == 1 && lane < L4)
             __builtin_amdgcn_global_load_lds((const void *)(p.thrp + q0 + lane * 4), (lds_ptr)(aux + C::QAUX_THRP), 16, 0, 0);
-        if (wave >= 2 && wave < 2 + W8 && !SAMPLE)
+        if (wave >= 2 && wave < 2 + W8)
             __builtin_amdgcn_global_load_lds((const void *)(p.thr64 + q0 + (wave - 2) * 128 + lane * 2),
                                              (lds_ptr)(aux + C::QAUX_THR64 + (wave - 2) * 1024), 16, 0, 0);
         if (wave >= 4 && wave < 4 + W8 && filter)

@@ -189,18 +189,34 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
             }
         }
     };
-    // side data of a query block: 16-byte loads from the library's padded per-query arrays
+    // side data of a query block: 16-byte loads from the library's padded per-query arrays.  A sampling pass runs
+    // before those exist and needs the mask words only: it takes them from the caller's array as dwords with
+    // clamped query numbers (instruction i covers queries [32 i, 32 i + 32), two instructions per loading wave
+    // and 128 queries).
     auto issue_query_aux = [&](int qb) {    // role 1 only
         lds_u8 *aux = lds + C::OFF_QAUX;
         const int q0 = qb * TQ;
+        if constexpr (SAMPLE) {
+            if (filter) {
+                const uint32_t last = (uint32_t)(p.Q - 1 - q0);
+                const unsigned char *g = uniform_address(p.qmask + q0);
+#pragma unroll
+                for (int h2 = 0; h2 < TQ / 128; ++h2) {
+                    const int i = ridx * (TQ / 128) + h2;
+                    const uint32_t r = (uint32_t)(i * 32 + (lane >> 1));
+                    __builtin_amdgcn_global_load_lds((const void *)(g + ((r < last ? r : last) * 8u + (lane & 1) * 4u)),
+                                                     (lds_ptr)(aux + C::QAUX_QMASK + i * 256), 4, 0, 0);
+                }
+            }
+            return;
+        }
         const uint32_t l16 = (uint32_t)lane * 16u;
         if (ridx == 0) {
             if (lane < TQ / 4) {        // TQ floats
                 __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.invq + q0) + l16), (lds_ptr)(aux + C::QAUX_INVQ), 16, 0, 0);
-                if (!SAMPLE)
-                    __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.thrp + q0) + l16), (lds_ptr)(aux + C::QAUX_THRP), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.thrp + q0) + l16), (lds_ptr)(aux + C::QAUX_THRP), 16, 0, 0);
             }
-        } else if (ridx == 1 && !SAMPLE) {
+        } else if (ridx == 1) {
             __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.thr64 + q0) + l16), (lds_ptr)(aux + C::QAUX_THR64), 16, 0, 0);
             if (TQ == 256)
                 __builtin_amdgcn_global_load_lds((const void *)(uniform_address(p.thr64 + q0 + 128) + l16), (lds_ptr)(aux + C::QAUX_THR64 + 1024), 16, 0, 0);
