@@ -127,6 +127,22 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
                      size_t workspace_bytes, void *hip_stream);
 
 /*
+ * kb_query for callers that cannot allocate device memory or hand over a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical results as
+ * kb_query, but the scratch memory is an array of KB_STATIC_SCRATCH_BYTES that is part of the library's device
+ * image (one copy per GPU, held until the process ends).  The call allocates and frees nothing; the first call on a
+ * device looks the array's address up (make one call before capturing a graph).  A query whose plan needs more than
+ * the array holds (kb_query_plan_bytes(kb, kb_size(kb), Q, k, kind) > KB_STATIC_SCRATCH_BYTES: large batches or
+ * k on a large knowledge base) returns KB_ERR_WORKSPACE and runs nothing: use kb_query with a workspace then.
+ * All calls on one GPU share the array, which keeps the last call's contents; every call resets what it needs
+ * zeroed.  Calls that overlap on one GPU (different streams, or threads) race: order them on one stream.
+ * kb_query_counters on this scratch is not offered.  Errors: as kb_query.
+ */
+#define KB_STATIC_SCRATCH_BYTES (32u << 20)
+kb_status_t kb_query_static(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int32_t Q, const uint64_t *qmask_dev,
+                            int32_t k, int32_t *indices_out_dev, float *scores_out_dev, void *hip_stream);
+
+/*
  * Weighted random selection (Section 3: the Optimization Selector picks its top-k at random, with weights given
  * by the predicted performance gains).  Entry i carries a predicted gain g_i; query r draws
  * k entries WITHOUT replacement from its qualifying entries with probability proportional to

@@ -1332,6 +1332,28 @@ kb_status_t kb_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int3
                      workspace_bytes, hip_stream);
 }
 
+// The library's own scratch memory for kb_query_static: one array per device, in device memory for as long as the
+// process lives.  In host code the name `scratch` only stands for the symbol; its device address is asked for once
+// per device (hipGetSymbolAddress, with that device current) and kept in scratch_address[].
+static __device__ __align__(256) unsigned char scratch[KB_STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+static std::atomic<void *> scratch_address[MAX_DEVICES];
+
+kb_status_t kb_query_static(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int32_t Q, const uint64_t *qmask_dev, int32_t k,
+                            int32_t *indices_out_dev, float *scores_out_dev, void *hip_stream)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return KB_ERR_DEVICE;
+    void *ptr = scratch_address[dev].load(std::memory_order_acquire);
+    if (!ptr) {     // first call on this device (two threads racing here get the same address)
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return KB_ERR_DEVICE;
+        scratch_address[dev].store(ptr, std::memory_order_release);
+    }
+    // run_query checks the plan of this call against the size of the array and returns KB_ERR_WORKSPACE beyond it
+    return run_query(kb, queries_dev, q_dtype, Q, qmask_dev, k, nullptr, 1.0f, 0, 0, indices_out_dev, scores_out_dev, ptr,
+                     KB_STATIC_SCRATCH_BYTES, hip_stream);
+}
+
 kb_status_t kb_query_sampled(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int32_t Q, const uint64_t *qmask_dev, int32_t k,
                              const float *gain_dev, float temperature, uint64_t seed, int32_t first_query,
                              int32_t *indices_out_dev, float *keys_out_dev, void *workspace_dev, size_t workspace_bytes,

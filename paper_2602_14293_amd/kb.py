@@ -52,6 +52,8 @@ def lib() -> ctypes.CDLL:
         L.kb_query_plan_bytes.argtypes = [vp, i64, i32, i32, i32]
         L.kb_query.restype = i32
         L.kb_query.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, vp, sz, vp]
+        L.kb_query_static.restype = i32
+        L.kb_query_static.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, vp]
         L.kb_query_probe_workspace_bytes.restype = sz
         L.kb_query_probe_workspace_bytes.argtypes = [vp, i32, i32, i32]
         L.kb_query_probe.restype = i32
@@ -172,6 +174,16 @@ class KnowledgeBase:
             out_score = torch.empty((Q, k), dtype=torch.float32, device=self.device)
         _check(lib().kb_query(self._h, _ptr(queries), _CODE_OF[queries.dtype], Q, _ptr(qmask), k, _ptr(out_index),
                               _ptr(out_score), _ptr(self._workspace), self._workspace.numel(), _stream()), "kb_query")
+        return out_index, out_score
+
+    def query_static(self, queries: torch.Tensor, k: int, qmask: Optional[torch.Tensor], out_index: torch.Tensor,
+                     out_score: torch.Tensor):
+        """kb_query_static: the query in the library's own scratch array; the caller passes inputs and outputs only."""
+        Q = queries.shape[0]
+        assert queries.is_contiguous() and queries.shape[1] == self.d
+        assert out_index.shape == (Q, k) and out_index.dtype == torch.int32 and out_score.shape == (Q, k) and out_score.dtype == torch.float32
+        _check(lib().kb_query_static(self._h, _ptr(queries), _CODE_OF[queries.dtype], Q, _ptr(qmask), k, _ptr(out_index),
+                                     _ptr(out_score), _stream()), "kb_query_static")
         return out_index, out_score
 
     def query_sampled(self, queries: torch.Tensor, k: int, gain: torch.Tensor, temperature: float, seed: int,
