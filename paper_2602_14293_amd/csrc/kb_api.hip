@@ -558,14 +558,14 @@ __device__ inline void select_topk_desc(uint64_t *buf, int n, int k, SelectScrat
 // have a score >= S = f(s1 of the k-th); those of them whose score equals S have an index <= the largest such
 // index, and the threshold word is (S, that index): k distinct entries reach it.
 struct ThresholdArgs {
-    const uint64_t *samp;       // [qpad][slots]
+    const uint64_t *samp;       // see sample_slot_index
     const void *queries;
     const uint64_t *qmask;      // or nullptr
     float *invq, *thrp;
     uint64_t *thr64, *qmask_pad, *stats;
     uint32_t *cnt, *flag, *fb_done;
     uint64_t sample_keys;
-    int32_t slots, k, Q, d, grid;
+    int32_t slots, group_shift, k, Q, qpad, d, grid;
 };
 
 template <int QT, bool KEYS> __global__ __launch_bounds__(1024) void threshold_kernel(ThresholdArgs a)
@@ -601,7 +601,7 @@ template <int QT, bool KEYS> __global__ __launch_bounds__(1024) void threshold_k
             }
         }
     }
-    for (int i = tid; i < slots; i += (int)blockDim.x) buf[i] = a.samp[(size_t)q * slots + i];
+    for (int i = tid; i < slots; i += (int)blockDim.x) buf[i] = a.samp[sample_slot_index(i, a.group_shift, a.qpad, q)];
     __syncthreads();
     select_topk_desc(buf, slots, k, sc, tid, (int)blockDim.x);
     uint64_t t = k <= slots ? buf[k - 1] : 0ull;
@@ -1224,12 +1224,17 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
         a.d = kb->d;
         a.Q = Q;
         a.nqb = p.nqb;
+        a.qpad = p.qpad;
         a.sample_slots = p.sample_slots;
+        a.sample_group_shift = 0;        // groups per tile of the sampling configuration: a power of two
+        while (p.sample_tiles > 0 && ((int64_t)p.sample_tiles << (a.sample_group_shift + 1)) <= p.sample_slots) ++a.sample_group_shift;
         a.region_cap = p.region_cap;
         a.draw = dr;
         a.tile_stride = 1;
         a.row_mul = 0;
         a.row_run_shift = 0;
+        a.row_inv_runs = 0.0;
+        a.row_ratio = 0.f;
         if (p.sample_tiles > 0) {
             // the sample is spread evenly over the knowledge base: a prefix says nothing about later rows when
             // the rows are grouped (by state, by cluster, by age)
@@ -1239,9 +1244,14 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
             // they take every tile_stride-th tile instead)
             a.row_run_shift = draw ? 2 : 0;
             a.row_mul = (p.sample_family == 0 || p.sample_family == 3 || p.sample_family == 4) ? scatter_multiplier(kb->n >> a.row_run_shift) : 0;
+            // (the full-line kernel addresses scattered rows in 32 bits, in units of 16 bytes: up to 64 GiB of keys)
+            if (p.sample_family == 4 && (uint64_t)kb->n * kb->d * key_bytes(kb->dtype) >= ((uint64_t)1 << 36)) a.row_mul = 0;
+            const int64_t runs = (kb->n >> a.row_run_shift) > 0 ? (kb->n >> a.row_run_shift) : 1;
+            a.row_inv_runs = 1.0 / (double)runs;
+            a.row_ratio = (float)((double)a.row_mul / (double)runs);
             int64_t sgrid = p.sample_tiles * p.nqb;
             const int64_t smax = (int64_t)DEVICE_CUS * p.sample_wgpc;
-            if (sgrid > smax) sgrid = smax;
+            if (sgrid > smax && p.sample_family != 4) sgrid = smax;        // (the full-line kernel samples one item per workgroup)
             if (launch_scan(kb->dtype, p.sample_config, p.sample_family, true, (int)sgrid, a, s) != hipSuccess) return KB_ERR_DEVICE;
             const int thr_threads = p.sample_slots > 1024 ? 1024 : p.sample_slots > 512 ? 512 : 256;
             const size_t thr_lds = sizeof(uint64_t) * (p.sample_slots > k ? p.sample_slots : k) + sizeof(SelectScratch);
@@ -1259,8 +1269,10 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
             t.fb_done = fb_done;
             t.sample_keys = (uint64_t)p.sample_keys;
             t.slots = p.sample_slots;
+            t.group_shift = a.sample_group_shift;
             t.k = k;
             t.Q = Q;
+            t.qpad = p.qpad;
             t.d = kb->d;
             t.grid = p.grid;
             static LdsAllowed thr_allowed[4];

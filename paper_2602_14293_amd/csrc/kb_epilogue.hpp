@@ -157,51 +157,80 @@ __device__ inline void main_epilogue(const f32x16 (&acc)[IB][JB], const EpiSide 
     }
 }
 
-// Sampling pass: per lane and query column, one qualifying entry of the lane's rows with the largest
-// s1 = dot * inv_k (first one on ties), stored as the candidate word of s1.  The final score is a
-// non-decreasing function of s1 (one more fp32 product with 1/|q| >= 0), which the threshold kernel applies:
-// the sampling pass itself needs no per-query value but the mask word.  Any qualifying entry is a valid sample.
-__device__ inline void sample_block(const f32x16 &a, int rl0, const EpiSide &sd, bool filter, uint64_t qm, int64_t row0,
-                                    int64_t n_keys, float &best, int &best_rl)
+// Sampling pass: per lane and query column, one qualifying entry of the lane's rows with (nearly) the largest
+// s1 = dot * inv_k, stored as the candidate word of s1.  The final score is a non-decreasing function of s1 (one
+// more fp32 product with 1/|q| >= 0), which the threshold kernel applies: the sampling pass itself needs no
+// per-query value but the mask word.  Any qualifying entry with its exact s1 is a valid sample.
+//
+// Every element is looked at here, so the search is kept to a few instructions per element: s1 is mapped to a
+// signed integer with the same order, the element's number within the lane (5 bits) replaces its low bits, entries
+// that fail the tag filter become the smallest integer, and a running integer maximum leaves the number of an
+// element whose s1 is within 2^-18 relative of the largest; that element's exact s1 is then recomputed.  Removed
+// rows and the repeated rows of a partial tile are not told apart in the search: when one of them wins, its lane
+// records no sample for this group of rows, which is always valid (and rare).  Side data
+// of the rows is read as 16-byte pieces, four rows at a time.  (Registers are scarce here, with 128 accumulators
+// live, and a spilled register costs these kernels dearly: its reload queues behind the stream loads in flight.)
+constexpr int32_t SAMPLE_NONE = (int32_t)0x80000000;
+__device__ inline int32_t order_key(float x)        // signed integers ordered like the floats (-0 below +0)
 {
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int rl = rl0 + 8 * (i >> 2) + (i & 3);
-        const float ik = sd.invk[rl];
-        const float s1 = a[i] * ik;
-        bool ok = row0 + rl < n_keys && s1 > best && !row_removed(ik);
-        if (filter) ok = ok && (sd.tag[rl] & qm) != 0;
-        if (ok) {
-            best = s1;
-            best_rl = rl;
-        }
-    }
+    const int32_t b = (int32_t)as_u32(x);
+    return b ^ ((b >> 31) & 0x7fffffff);
 }
 
-__device__ inline void sample_store(float best, int best_rl, int ql, const EpiSide &sd, int64_t row0, int q0, const ScanArgs &p,
-                                    int64_t slot)
+// one 32x32 block: the best key of the lane's 16 elements joins `best`
+__device__ inline void sample_block(const f32x16 &a, int rl0, int id0, const EpiSide &sd, bool filter, uint32_t qm_lo, uint32_t qm_hi,
+                                    int32_t &best)
 {
-    if (q0 + ql < p.Q) {
-        uint64_t cw = 0ull;
-        if (best_rl >= 0)       // best = dot * inv_k was computed exactly as final_score's first product
-            cw = pack_candidate(best, sample_index(p, row0 + best_rl));
-        p.samp[(size_t)(q0 + ql) * p.sample_slots + slot] = cw;
+#pragma unroll
+    for (int run = 0; run < 4; ++run) {             // four runs of four rows: 16 bytes of 1/|k|, 32 bytes of tags
+        const int rl = rl0 + 8 * run;
+        const f32x4 ik4 = *reinterpret_cast<const f32x4 *>(sd.invk + rl);
+        const float ik[4] = {ik4.x, ik4.y, ik4.z, ik4.w};
+        u32x4 tg[2] = {};
+        if (filter) {
+            tg[0] = *reinterpret_cast<const u32x4 *>(sd.tag + rl);
+            tg[1] = *reinterpret_cast<const u32x4 *>(sd.tag + rl + 2);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int i = 4 * run + e;
+            int32_t key = (order_key(a[i] * ik[e]) & ~31) | (id0 + i);
+            if (filter) {
+                const u32x4 t = tg[e >> 1];
+                const uint32_t lo = (e & 1) ? t.z : t.x, hi = (e & 1) ? t.w : t.y;
+                key = ((lo & qm_lo) | (hi & qm_hi)) != 0 ? key : SAMPLE_NONE;
+            }
+            best = key > best ? key : best;
+        }
     }
 }
 
 template <int IB, int JB>
 __device__ inline void sample_epilogue(const f32x16 (&acc)[IB][JB], const EpiSide &sd, bool filter, int wave_row0, int ql0,
-                                       int half, int64_t row0, int q0, const ScanArgs &p, int64_t slot)
+                                       int half, int64_t row0, int q0, const ScanArgs &p, int64_t slot, int64_t tile_run, int tk)
 {
+    static_assert(IB * 16 <= 32, "element numbers take five bits");
 #pragma unroll
     for (int jb = 0; jb < JB; ++jb) {
-        float best = -__builtin_inff();
-        int best_rl = -1;
-        const uint64_t qm = filter ? sd.qmask[ql0 + jb * 32] : 0ull;
+        const int ql = ql0 + jb * 32;
+        const uint64_t qm = filter ? sd.qmask[ql] : 0ull;
+        int32_t best = SAMPLE_NONE;
 #pragma unroll
         for (int ib = 0; ib < IB; ++ib)
-            sample_block(acc[ib][jb], wave_row0 + ib * 32 + 4 * half, sd, filter, qm, row0, p.n_keys, best, best_rl);
-        sample_store(best, best_rl, ql0 + jb * 32, sd, row0, q0, p, slot);
+            sample_block(acc[ib][jb], wave_row0 + ib * 32 + 4 * half, ib * 16, sd, filter, (uint32_t)qm, (uint32_t)(qm >> 32), best);
+        if (q0 + ql >= p.Q) continue;
+        uint64_t cw = 0ull;
+        if (best != SAMPLE_NONE) {
+            const int e = best & 31, ib = e >> 4, i = e & 15;
+            const int rl = wave_row0 + ib * 32 + 4 * half + 8 * (i >> 2) + (i & 3);
+            float dot = select16(acc[0][jb], i);
+            if (IB > 1 && ib == 1) dot = select16(acc[IB - 1][jb], i);
+            const float ikv = sd.invk[rl];
+            // a removed row, or a row past the end of the knowledge base (the repeated last row of a partial tile): no sample
+            if (!row_removed(ikv) && row0 + rl < p.n_keys)
+                cw = pack_candidate(dot * ikv, sample_index(p, tile_run, row0, tk, rl));     // dot * inv_k exactly as final_score's first product
+        }
+        p.samp[sample_slot_index(slot, p.sample_group_shift, p.qpad, q0 + ql)] = cw;
     }
 }
 
@@ -258,13 +287,13 @@ __device__ inline float draw_key_of(float score, const DrawArgs &dr, uint32_t qu
 // knowledge base).
 template <bool SAMPLED>
 __device__ inline void block_keys(const f32x16 &a, const EpiRows &rw, float iq, const ScanArgs &p, uint32_t query, int64_t row0,
-                                  float (&key)[16])
+                                  float (&key)[16], int64_t tile_run = 0, int tk = 0)
 {
     const DrawArgs &dr = p.draw;
 #pragma unroll
     for (int run = 0; run < 4; ++run) {
         const int64_t logical = row0 + rw.rl0 + 8 * run;       // a multiple of 4
-        const int64_t first = SAMPLED ? (int64_t)sample_index(p, logical) : logical;
+        const int64_t first = SAMPLED ? (int64_t)sample_index(p, tile_run, row0, tk, rw.rl0 + 8 * run) : logical;
         uint32_t w[4];
         philox4x32_10((uint32_t)(first >> 2), query, dr.seed_lo, dr.seed_hi, w);
         const f32x4 lg = *reinterpret_cast<const f32x4 *>(dr.log_gain + first);
@@ -342,7 +371,7 @@ __device__ inline void main_epilogue_draw(const f32x16 (&acc)[IB][JB], const Epi
 // Sampling pass on keys: per lane and query column the qualifying entry with the largest key.
 template <int IB, int JB>
 __device__ inline void sample_epilogue_draw(const f32x16 (&acc)[IB][JB], const EpiSide &sd, bool filter, int wave_row0, int ql0,
-                                            int half, int64_t row0, int q0, const ScanArgs &p, int64_t slot)
+                                            int half, int64_t row0, int q0, const ScanArgs &p, int64_t slot, int64_t tile_run, int tk)
 {
 #pragma unroll
     for (int jb = 0; jb < JB; ++jb) {
@@ -356,7 +385,7 @@ __device__ inline void sample_epilogue_draw(const f32x16 (&acc)[IB][JB], const E
         for (int ib = 0; ib < IB; ++ib) {
             const EpiRows rw = load_rows(sd, wave_row0 + ib * 32 + 4 * half);
             float key[16];
-            block_keys<true>(acc[ib][jb], rw, iq, p, query, row0, key);
+            block_keys<true>(acc[ib][jb], rw, iq, p, query, row0, key, tile_run, tk);
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int rl = rw.rl0 + 8 * (i >> 2) + (i & 3);
@@ -369,7 +398,7 @@ __device__ inline void sample_epilogue_draw(const f32x16 (&acc)[IB][JB], const E
             }
         }
         if (q0 + ql < p.Q)
-            p.samp[(size_t)(q0 + ql) * p.sample_slots + slot] = best_rl >= 0 ? pack_candidate(best, sample_index(p, row0 + best_rl)) : 0ull;
+            p.samp[sample_slot_index(slot, p.sample_group_shift, p.qpad, q0 + ql)] = best_rl >= 0 ? pack_candidate(best, sample_index(p, tile_run, row0, tk, best_rl)) : 0ull;
     }
 }
 

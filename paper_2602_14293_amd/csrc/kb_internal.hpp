@@ -125,7 +125,7 @@ struct ScanArgs {
     const float *invq;        // [qpad]
     const uint64_t *thr64;    // [qpad] candidate words below this cannot be in the result
     const float *thrp;        // [qpad] conservative pre-filter on dot * inv_k
-    uint64_t *samp;           // sampling pass output [qpad][sample_slots]
+    uint64_t *samp;           // sampling pass output [sample tiles][qpad][groups per tile]: see sample_slot_index
     Record *regions;          // [grid * waves per workgroup][region_cap]: one private region per wavefront
     uint64_t *cand;           // [qpad][cand_cap] per-query candidate lists, CAND_SEGMENTS segments each
     uint32_t *cnt;            // [qpad][CAND_SEGMENTS] entries claimed in each segment (zero before the launch)
@@ -135,8 +135,10 @@ struct ScanArgs {
     int64_t n_tiles;          // key tiles to scan: logical tile t is rows [t * tile_stride * TK, +TK)
     int32_t tile_stride;      // 1 for the main pass; a sampling pass takes every tile_stride-th tile ...
     uint64_t row_mul;         // ... or, when nonzero, scatters its rows in runs of 2^row_run_shift (see sample_row)
+    double row_inv_runs;      // 1 / (n_keys >> row_run_shift)
+    float row_ratio;          // row_mul / (n_keys >> row_run_shift)
     int32_t row_run_shift;
-    int32_t d, Q, nqb, sample_slots, region_cap, cand_cap;
+    int32_t d, Q, nqb, qpad, sample_slots, sample_group_shift, region_cap, cand_cap;
     DrawArgs draw;
 };
 
@@ -148,20 +150,55 @@ struct ScanArgs {
 // selection takes runs of four, which keep what it shares between neighbouring rows (one generator call, one
 // 16-byte load of gains).  Without row_mul the tile is tile_stride tiles further on and rows past the end repeat
 // the last row.
-__device__ inline int64_t sample_index64(const ScanArgs &p, int64_t row)
+//
+// The map is linear, so a workgroup maps the first run of its tile once (sample_tile_run: exact 64-bit arithmetic with
+// a quotient estimated in double precision; a 64-bit division would be a software routine of some hundred
+// instructions) and every row of the tile from that (sample_row: the product of a run number below 256 with row_mul
+// has a quotient below 256, which single precision estimates to within one).
+__device__ inline int64_t mulmod_runs(const ScanArgs &p, int64_t run)      // (run * row_mul) mod runs, run < runs < 2^31
 {
-    const int sh = p.row_run_shift;
-    return (int64_t)((((uint64_t)(row >> sh) * p.row_mul) % ((uint64_t)p.n_keys >> sh)) << sh) + (row & ((1 << sh) - 1));
+    const int64_t runs = p.n_keys >> p.row_run_shift, prod = run * (int64_t)p.row_mul;
+    int64_t r = prod - (int64_t)((double)prod * p.row_inv_runs) * runs;
+    r += r < 0 ? runs : 0;
+    r -= r >= runs ? runs : 0;
+    return r;
 }
-__device__ inline int64_t sample_row(const ScanArgs &p, int64_t tile, int tk, int r)
+__device__ inline int64_t sample_tile_run(const ScanArgs &p, int64_t tile, int tk)     // mapped run of the tile's first row
 {
-    if (p.row_mul) return sample_index64(p, tile * tk + r);
+    return p.row_mul ? mulmod_runs(p, (tile * tk) >> p.row_run_shift) : 0;
+}
+__device__ inline int64_t sample_row(const ScanArgs &p, int64_t tile_run, int64_t tile, int tk, int r)     // 0 <= r < tk <= 256
+{
+    if (p.row_mul) {
+        const int sh = p.row_run_shift;
+        const int64_t runs = p.n_keys >> sh;
+        const uint32_t lr = (uint32_t)r >> sh;                                          // run within the tile
+        const uint32_t q = (uint32_t)((float)lr * p.row_ratio);                         // floor(lr * row_mul / runs), or one off
+        int64_t m = (int64_t)((uint64_t)lr * p.row_mul) - (int64_t)((uint64_t)q * (uint64_t)runs);
+        m += m < 0 ? runs : 0;
+        m -= m >= runs ? runs : 0;
+        m += tile_run;
+        m -= m >= runs ? runs : 0;
+        return (m << sh) + (r & ((1 << sh) - 1));
+    }
     const int64_t row = tile * p.tile_stride * tk + r;
     return row < p.n_keys ? row : p.n_keys - 1;
 }
-// first row number the sampling epilogues count from: logical when the rows are scattered (see sample_index)
+// first row number the sampling epilogues count from: logical when the rows are scattered
 __device__ inline int64_t sample_row0(const ScanArgs &p, int64_t tile, int tk) { return p.row_mul ? tile * tk : tile * p.tile_stride * tk; }
-__device__ inline uint32_t sample_index(const ScanArgs &p, int64_t row) { return (uint32_t)(p.row_mul ? sample_index64(p, row) : row); }
+// knowledge-base row of tile-local row rl of a sampling pass whose epilogue counts rows from row0 = sample_row0()
+__device__ inline uint32_t sample_index(const ScanArgs &p, int64_t tile_run, int64_t row0, int tk, int rl)
+{
+    return (uint32_t)(p.row_mul ? sample_row(p, tile_run, 0, tk, rl) : row0 + rl);
+}
+
+// Where sample `slot` (= tile * groups + group) of query q lives.  The groups of one tile are adjacent (64 bytes per
+// query for eight groups) and the queries of a tile follow each other: a sampling wavefront stores words 64 bytes apart
+// inside one 16 KiB run instead of 16 KiB apart, and the threshold kernel reads a query's samples 64 bytes at a time.
+__host__ __device__ inline size_t sample_slot_index(int64_t slot, int group_shift, int qpad, int q)      // groups = 2^group_shift
+{
+    return ((((size_t)slot >> group_shift) * qpad + q) << group_shift) + ((size_t)slot & ((1u << group_shift) - 1));
+}
 
 // A kernel that uses more than 64 KiB of dynamic LDS must be allowed to, once per device (the attribute belongs to the
 // device's copy of the kernel).  `done` holds one bit per device ordinal; callers keep one such word per kernel.

@@ -204,10 +204,11 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
     auto ld_setup = [&]() {
         const int64_t left = p.n_keys - ld_tile * tstride * TK;      // >= 1 rows in this tile
         const int last = left < TK ? (int)left - 1 : TK - 1;
+        const int64_t tile_run = SAMPLE ? sample_tile_run(p, ld_tile, TK) : 0;
 #pragma unroll
         for (int j = 0; j < LA; ++j) {
             const int r = ldA_row + j * RSTEP_A;
-            if constexpr (SAMPLE) offA[j] = (uint64_t)sample_row(p, ld_tile, TK, r) * key_row_bytes + ldA_piece;
+            if constexpr (SAMPLE) offA[j] = (uint64_t)sample_row(p, tile_run, ld_tile, TK, r) * key_row_bytes + ldA_piece;
             else offA[j] = (uint32_t)(r < last ? r : last) * key_row_bytes + ldA_piece;
         }
         const int qlast = p.Q - 1 - ld_qb * TQ;
@@ -284,7 +285,7 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
             if (tid < TK) {
                 int64_t r = tile * tstride * TK + tid;
                 r = r < p.n_keys ? r : p.n_keys - 1;
-                if constexpr (SAMPLE) r = sample_row(p, tile, TK, tid);
+                if constexpr (SAMPLE) r = sample_row(p, sample_tile_run(p, tile, TK), tile, TK, tid);
                 my_invk = p.inv_norm[r];
                 if (filter) my_tag = p.tags[r];
             }
@@ -348,10 +349,10 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
             const EpiSide sd{aux_invk, aux_tag, reinterpret_cast<const float *>(smem + C::OFF_THRP), aux_invq, aux_thr64, aux_qmask};
             if (SAMPLE && DRAW)
                 sample_epilogue_draw<IB, JB>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p,
-                                             (int64_t)tile * C::GROUPS_PER_TILE + wm * 2 + half);
+                                             (int64_t)tile * C::GROUPS_PER_TILE + wm * 2 + half, sample_tile_run(p, tile, TK), TK);
             else if (SAMPLE)
                 sample_epilogue<IB, JB>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p,
-                                        (int64_t)tile * C::GROUPS_PER_TILE + wm * 2 + half);
+                                        (int64_t)tile * C::GROUPS_PER_TILE + wm * 2 + half, sample_tile_run(p, tile, TK), TK);
             else if (DRAW)
                 main_epilogue_draw<IB, JB>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p, my_region, wave_cnt, blockIdx.x * NW + wave);
             else

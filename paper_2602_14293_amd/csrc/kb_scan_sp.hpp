@@ -136,10 +136,11 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
     auto ld_setup = [&]() {
         const int last = role == 0 ? (int)(p.n_keys - ld_tile * tstride * TK < TK ? p.n_keys - ld_tile * tstride * TK - 1 : TK - 1)
                                    : p.Q - 1 - ld_qb * TQ;
+        const int64_t tile_run = (SAMPLE && role == 0) ? sample_tile_run(p, ld_tile, TK) : 0;
 #pragma unroll
         for (int j = 0; j < LC; ++j) {
             const int r = ld_row + j * ld_rstep;
-            if (SAMPLE && role == 0) off[j] = (Off)((uint64_t)sample_row(p, ld_tile, TK, r) * row_bytes + ld_piece);
+            if (SAMPLE && role == 0) off[j] = (Off)((uint64_t)sample_row(p, tile_run, ld_tile, TK, r) * row_bytes + ld_piece);
             else off[j] = (uint32_t)(r < last ? r : last) * row_bytes + ld_piece;
         }
         ld_base = role == 0 ? (SAMPLE ? 0 : (size_t)(ld_tile * tstride) * TK * row_bytes) : (size_t)ld_qb * TQ * row_bytes;
@@ -148,17 +149,18 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
     auto issue_tile_aux = [&]() {
         lds_u8 *aux = lds + C::OFF_AUX + ld_par * C::AUX_BYTES;
         const int64_t row0 = ld_tile * tstride * TK;
+        const int64_t tile_run = SAMPLE ? sample_tile_run(p, ld_tile, TK) : 0;
         if (wave < 4) {
             int64_t r = row0 + wave * 64 + lane;
             r = r < p.n_keys ? r : p.n_keys - 1;
-            if constexpr (SAMPLE) r = sample_row(p, ld_tile, TK, wave * 64 + lane);
+            if constexpr (SAMPLE) r = sample_row(p, tile_run, ld_tile, TK, wave * 64 + lane);
             __builtin_amdgcn_global_load_lds((const void *)(p.inv_norm + r), (lds_ptr)(aux + C::AUX_INVK + wave * 256), 4, 0, 0);
         }
         if (filter) {
             // tags as dwords: wave w covers dwords [64w, 64w+64) = rows [32w, 32w+32)
             int64_t r = row0 + wave * 32 + (lane >> 1);
             r = r < p.n_keys ? r : p.n_keys - 1;
-            if constexpr (SAMPLE) r = sample_row(p, ld_tile, TK, wave * 32 + (lane >> 1));
+            if constexpr (SAMPLE) r = sample_row(p, tile_run, ld_tile, TK, wave * 32 + (lane >> 1));
             __builtin_amdgcn_global_load_lds((const void *)(reinterpret_cast<const uint32_t *>(p.tags + r) + (lane & 1)),
                                              (lds_ptr)(aux + C::AUX_TAG + wave * 256), 4, 0, 0);
         }
@@ -288,7 +290,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
         const int64_t row0 = SAMPLE ? sample_row0(p, tile, TK) : tile * tstride * TK;
         if (SAMPLE)
             sample_epilogue<IB, JB>(acc, sd, filter, wm * 64, rowB, half, row0, qb * TQ, p,
-                                    (int64_t)tile * C::GROUPS_PER_TILE + wm * 2 + half);
+                                    (int64_t)tile * C::GROUPS_PER_TILE + wm * 2 + half, sample_tile_run(p, tile, TK), TK);
         else
             main_epilogue<IB, JB>(acc, sd, filter, wm * 64, rowB, half, row0, qb * TQ, p, my_region, wave_cnt, blockIdx.x * NW + wave);
 #pragma unroll

@@ -104,7 +104,10 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
     const int nqb = p.nqb;
     const int64_t n_items = p.n_tiles * nqb;
     const int vb = item_lane(blockIdx.x, gridDim.x, nqb);      // this workgroup takes items vb, vb + gridDim.x, ...
-    const int my_items = (int64_t)vb < n_items ? (int)((n_items - vb + gridDim.x - 1) / gridDim.x) : 0;
+    // A sampling pass is launched with one workgroup per item: nothing of the item loop stays live in its epilogue,
+    // which looks at every element and needs the registers (a spilled register costs this kernel dearly: its
+    // reload queues behind the stream loads in flight).
+    const int my_items = SAMPLE ? ((int64_t)vb < n_items ? 1 : 0) : ((int64_t)vb < n_items ? (int)((n_items - vb + gridDim.x - 1) / gridDim.x) : 0);
     const int NC = p.d * C::KEY_BYTES / RB;                    // chunks per item
     const int total = my_items * NC;                           // chunks of this workgroup
     const int phases = 2 * total;
@@ -128,28 +131,33 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
     lds_u8 *const ld_ring0 = lds + (role == 0 ? 0 : C::OFF_B) + ridx * 1024;
     lds_u8 *ld_dst = ld_ring0;
     int ld_ring = 0;
-    typedef typename std::conditional<SAMPLE, uint64_t, uint32_t>::type Off;   // a sampling pass gathers key rows from anywhere
-    Off off[2][4];                                                     // [piece of the chunk][instruction]
+    // [piece of the chunk][instruction]: bytes from the tile's (the query block's) first row; a sampling pass gathers
+    // key rows from anywhere and counts in units of 16 bytes from the first key (the host scatters the sample only
+    // when that fits 32 bits)
+    constexpr int OSH = SAMPLE ? 4 : 0;
+    uint32_t off[2][4];
     auto ld_setup = [&]() {
         int last, base;
         if (role == 0) {
-            const int64_t left = p.n_keys - (int64_t)ld_tile * TK;
+            const int64_t tile_row0 = (int64_t)ld_tile * (SAMPLE ? p.tile_stride : 1) * TK;      // (unless the sample is scattered)
+            const int64_t left = p.n_keys - tile_row0;
             last = left < TK ? (int)left - 1 : TK - 1;
             base = 0;
-            ld_src = static_cast<const unsigned char *>(p.keys) + (SAMPLE ? 0 : (size_t)ld_tile * TK * key_row_bytes);
+            ld_src = static_cast<const unsigned char *>(p.keys) + ((SAMPLE && p.row_mul) ? 0 : (size_t)tile_row0 * key_row_bytes);
         } else {
             last = p.Q - 1 - ld_qb * TQ;
             base = ld_qb * TQ;
             ld_src = static_cast<const unsigned char *>(p.queries);
         }
         const uint32_t rb = role == 0 ? key_row_bytes : qry_row_bytes;
+        const int64_t tile_run = (SAMPLE && role == 0) ? sample_tile_run(p, ld_tile, TK) : 0;
 #pragma unroll
         for (int h = 0; h < 2; ++h)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int r = h * C::PIECE_ROWS + ld_row + j * 32;
-                if (SAMPLE && role == 0) off[h][j] = (Off)((uint64_t)sample_row(p, ld_tile, TK, r) * rb + ld_slot);
-                else off[h][j] = (uint32_t)(base + (r < last ? r : last)) * rb + ld_slot;
+                if (SAMPLE && role == 0 && p.row_mul) off[h][j] = (uint32_t)(((uint64_t)sample_row(p, tile_run, ld_tile, TK, r) * rb + ld_slot) >> 4);
+                else off[h][j] = ((uint32_t)(base + (r < last ? r : last)) * rb + ld_slot) >> (role == 0 ? OSH : 0);
             }
     };
     // side data of the key tile the key stream is at: 4-byte loads with clamped rows from the caller's arrays
@@ -157,13 +165,14 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
     auto issue_tile_aux = [&]() {       // role 0 only
         lds_u8 *aux = lds + C::OFF_AUX + ld_par * C::AUX_BYTES;
         if constexpr (SAMPLE) {
-            const int64_t r = sample_row(p, ld_tile, TK, ridx * 64 + lane);
+            const int64_t tile_run = sample_tile_run(p, ld_tile, TK);
+            const int64_t r = sample_row(p, tile_run, ld_tile, TK, ridx * 64 + lane);
             __builtin_amdgcn_global_load_lds((const void *)(p.inv_norm + r), (lds_ptr)(aux + C::AUX_INVK + ridx * 256), 4, 0, 0);
             if (filter) {
 #pragma unroll
                 for (int h2 = 0; h2 < 2; ++h2) {
                     const int i = ridx * 2 + h2;
-                    const int64_t rt = sample_row(p, ld_tile, TK, i * 32 + (lane >> 1));
+                    const int64_t rt = sample_row(p, tile_run, ld_tile, TK, i * 32 + (lane >> 1));
                     __builtin_amdgcn_global_load_lds((const void *)(reinterpret_cast<const uint32_t *>(p.tags + rt) + (lane & 1)),
                                                      (lds_ptr)(aux + C::AUX_TAG + i * 256), 4, 0, 0);
                 }
@@ -228,9 +237,10 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
     };
     // role 0: load j (0..3) of the key piece at the cursor, half h of its chunk; key_next(h) moves the cursor on
     auto key_issue = [&](int h, int j) {
-        __builtin_amdgcn_global_load_lds((const void *)(ld_src + off[h][j]), (lds_ptr)(ld_dst + j * 4096), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const void *)(ld_src + ((uint64_t)off[h][j] << OSH)), (lds_ptr)(ld_dst + j * 4096), 16, 0, 0);
     };
     auto item_next = [&]() {
+        if constexpr (SAMPLE) return;       // one item per workgroup: the stream ends with it
         ld_c = 0;
         ld_par ^= 1;
         ld_tile += step_tile;
@@ -305,11 +315,12 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
                          reinterpret_cast<const float *>(qaux + C::QAUX_THRP), reinterpret_cast<const float *>(qaux + C::QAUX_INVQ),
                          reinterpret_cast<const uint64_t *>(qaux + C::QAUX_THR64), reinterpret_cast<const uint64_t *>(qaux + C::QAUX_QMASK)};
         const int64_t row0 = SAMPLE ? sample_row0(p, tile, TK) : (int64_t)tile * TK;
+        const int64_t tile_run = SAMPLE ? sample_tile_run(p, tile, TK) : 0;
 #pragma unroll
         for (int rh = 0; rh < 2; ++rh) {
             if constexpr (SAMPLE)       // sampling groups: (piece, wave row, lane half) = 32 rows each
                 sample_epilogue<IB, JB>(acc[rh], sd, filter, rh * 128 + wm * 64, qrow, half, row0, qb * TQ, p,
-                                        (int64_t)tile * C::GROUPS_PER_TILE + (rh * 2 + wm) * 2 + half);
+                                        (int64_t)tile * C::GROUPS_PER_TILE + (rh * 2 + wm) * 2 + half, tile_run, TK);
             else
                 main_epilogue<IB, JB>(acc[rh], sd, filter, rh * 128 + wm * 64, qrow, half, row0, qb * TQ, p, my_region, wave_cnt, blockIdx.x * NW + wave);
 #pragma unroll
@@ -518,7 +529,14 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
         for (int it = 0; it < my_items; ++it) {
             if (role == 0) item_chunks(std::integral_constant<int, 0>{}, it * NC);
             else item_chunks(std::integral_constant<int, 1>{}, it * NC);
-            epilogue(tile, qb, par);
+            {
+                // What the epilogue derives from the item's coordinates (addresses of its outputs, row numbers) is
+                // computed here and not, as the compiler would have it when a workgroup has a single item, before
+                // the chunks, where it would sit in registers the contraction needs.
+                int tile_e = tile, qb_e = qb, par_e = par;
+                asm volatile("" : "+s"(tile_e), "+s"(qb_e), "+s"(par_e));
+                epilogue(tile_e, qb_e, par_e);
+            }
             par ^= 1;
             tile += step_tile;
             qb += step_qb;
