@@ -262,10 +262,12 @@ kb_status_t kb_query_counters(const kb_t *kb, const void *workspace_dev, int64_t
 kb_status_t kb_set_tuning(kb_t *kb, const char *name, int64_t value);
 
 /*
- * Kernel timing for roofline reports.  After kb_profile_begin, each kb_query records a HIP event pair
- * around its main scan kernel (on the small-knowledge-base path: around the kernel that scores the rows) on the
- * query's stream (up to max_calls queries, 1..4096; later ones are not recorded).  kb_profile_end synchronises `hip_stream`, writes the summed duration of the recorded scan
- * launches in milliseconds and their number, destroys the events and stops recording.
+ * Kernel timing for roofline reports.  After kb_profile_begin, each kb_query attaches a HIP event pair to the
+ * dispatch of its main scan kernel (on the small-knowledge-base path an event pair is recorded around the kernel
+ * that scores the rows), up to max_calls queries, 1..4096; later ones are not timed.  The pair travels with the
+ * kernel's own dispatch packet, so timing a launch puts nothing between it and its neighbours on the stream.
+ * kb_profile_end synchronises `hip_stream`, writes the summed duration of the timed scan launches in milliseconds and
+ * their number, destroys the events and stops recording.
  * Errors: KB_ERR_NULL, KB_ERR_INVALID_ARG (bad max_calls, or end without begin), KB_ERR_DEVICE.
  */
 kb_status_t kb_profile_begin(kb_t *kb, int32_t max_calls);

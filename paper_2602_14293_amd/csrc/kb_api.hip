@@ -21,6 +21,8 @@ using namespace kbi;
 
 namespace kbi {
 
+thread_local ScanTiming scan_timing;
+
 bool scan_config_info(int key_dtype, int config, ConfigInfo *out)
 {
 #define X(ID, KT, TK, TQ, WM, WN, RBA, NSTAGE, WGPC)                          \
@@ -1289,12 +1291,14 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
         a.tile_stride = 1;
         a.row_mul = 0;
         const bool timed = kb->prof_events && kb->prof_used < kb->prof_max;
-        if (timed && hipEventRecord(kb->prof_events[2 * kb->prof_used], s) != hipSuccess) return KB_ERR_DEVICE;
-        if (launch_scan(kb->dtype, p.config, p.family, false, p.grid, a, s) != hipSuccess) return KB_ERR_DEVICE;
         if (timed) {
-            if (hipEventRecord(kb->prof_events[2 * kb->prof_used + 1], s) != hipSuccess) return KB_ERR_DEVICE;
-            ++kb->prof_used;
+            scan_timing.start = kb->prof_events[2 * kb->prof_used];
+            scan_timing.stop = kb->prof_events[2 * kb->prof_used + 1];
         }
+        const hipError_t launched = launch_scan(kb->dtype, p.config, p.family, false, p.grid, a, s);
+        scan_timing = ScanTiming();
+        if (launched != hipSuccess) return KB_ERR_DEVICE;
+        if (timed) ++kb->prof_used;
     }
 
     FinalArgs f;

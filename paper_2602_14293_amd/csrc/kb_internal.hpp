@@ -1,6 +1,7 @@
 // Internal declarations shared by the translation units of libkb (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include <atomic>
@@ -215,6 +216,15 @@ inline hipError_t allow_dynamic_lds(const void *kernel, LdsAllowed &done, size_t
     if (e == hipSuccess && bit) done.fetch_or(bit, std::memory_order_release);
     return e;
 }
+
+// Kernel timing for roofline reports (kb_profile_begin): while `start` is set, the next scan launch of this thread
+// carries the two events on its own dispatch packet (hipExtLaunchKernelGGL), so that their difference is the
+// kernel's duration and no extra packets sit between it and its neighbours (events recorded around a launch cost
+// about 7 us each).
+struct ScanTiming {
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+extern thread_local ScanTiming scan_timing;
 
 // Launchers, one translation unit per key dtype.  `sample` selects the sampling epilogue.
 hipError_t launch_scan_f32(int config, bool sample, int grid, const ScanArgs &a, hipStream_t s);

@@ -385,7 +385,7 @@ template <class C> hipError_t launch_scan_cfg(bool sample, int grid, const ScanA
                     : (sample ? &kb_scan_kernel<C, true, false> : &kb_scan_kernel<C, false, false>);
     const int which = (draw ? 2 : 0) + (sample ? 1 : 0);
     if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(fn), allowed[which], C::SMEM_BYTES); e != hipSuccess) return e;
-    hipLaunchKernelGGL(fn, dim3(grid), dim3(C::THREADS), C::SMEM_BYTES, s, a);
+    hipExtLaunchKernelGGL(fn, dim3(grid), dim3(C::THREADS), C::SMEM_BYTES, s, scan_timing.start, scan_timing.stop, 0, a);
     return hipGetLastError();
 }
 

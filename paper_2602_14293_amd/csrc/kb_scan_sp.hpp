@@ -621,7 +621,7 @@ template <class C> hipError_t launch_scan_sp_cfg(bool sample, int grid, const Sc
     static LdsAllowed allowed[2];
     auto *fn = sample ? &kb_scan_sp_kernel<C, true> : &kb_scan_sp_kernel<C, false>;
     if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(fn), allowed[sample], C::SMEM_BYTES); e != hipSuccess) return e;
-    hipLaunchKernelGGL(fn, dim3(grid), dim3(C::THREADS), C::SMEM_BYTES, s, a);
+    hipExtLaunchKernelGGL(fn, dim3(grid), dim3(C::THREADS), C::SMEM_BYTES, s, scan_timing.start, scan_timing.stop, 0, a);
     return hipGetLastError();
 }
 

@@ -562,7 +562,7 @@ template <class C> hipError_t launch_scan_wide_cfg(bool sample, int grid, const 
     if (C::QF8 && sample) return hipErrorInvalidValue;     // fp8: the sampling pass runs the 64-byte-piece kernel (fewer registers)
     auto *fn = (sample && !C::QF8) ? &kb_scan_wide_kernel<C, C::QF8 ? false : true> : &kb_scan_wide_kernel<C, false>;
     if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(fn), allowed[sample], C::SMEM_BYTES); e != hipSuccess) return e;
-    hipLaunchKernelGGL(fn, dim3(grid), dim3(C::THREADS), C::SMEM_BYTES, s, a);
+    hipExtLaunchKernelGGL(fn, dim3(grid), dim3(C::THREADS), C::SMEM_BYTES, s, scan_timing.start, scan_timing.stop, 0, a);
     return hipGetLastError();
 }
 
