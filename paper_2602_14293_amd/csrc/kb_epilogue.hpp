@@ -205,7 +205,21 @@ __device__ inline void sample_block(const f32x16 &a, int rl0, int id0, const Epi
     }
 }
 
-template <int IB, int JB>
+// The same search with the fewest registers: one element at a time, its side data read from LDS when it is needed
+// (32 reads per block instead of 12).  For the kernels that keep a software pipeline's fragments live across the
+// epilogue and have no registers to spare: there the version above spills, and loses more than it gains.
+__device__ inline void sample_block_lean(const f32x16 &a, int rl0, int id0, const EpiSide &sd, bool filter, uint64_t qm, int32_t &best)
+{
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int rl = rl0 + 8 * (i >> 2) + (i & 3);
+        int32_t key = (order_key(a[i] * sd.invk[rl]) & ~31) | (id0 + i);
+        if (filter) key = (sd.tag[rl] & qm) != 0 ? key : SAMPLE_NONE;
+        best = key > best ? key : best;
+    }
+}
+
+template <int IB, int JB, bool LEAN = false>
 __device__ inline void sample_epilogue(const f32x16 (&acc)[IB][JB], const EpiSide &sd, bool filter, int wave_row0, int ql0,
                                        int half, int64_t row0, int q0, const ScanArgs &p, int64_t slot, int64_t tile_run, int tk)
 {
@@ -216,8 +230,13 @@ __device__ inline void sample_epilogue(const f32x16 (&acc)[IB][JB], const EpiSid
         const uint64_t qm = filter ? sd.qmask[ql] : 0ull;
         int32_t best = SAMPLE_NONE;
 #pragma unroll
-        for (int ib = 0; ib < IB; ++ib)
-            sample_block(acc[ib][jb], wave_row0 + ib * 32 + 4 * half, ib * 16, sd, filter, (uint32_t)qm, (uint32_t)(qm >> 32), best);
+        for (int ib = 0; ib < IB; ++ib) {
+            // the side data is read again for every column: kept from one column to the next it would take a
+            // hundred registers that the kernels with a software pipeline do not have
+            asm volatile("" ::: "memory");
+            if constexpr (LEAN) sample_block_lean(acc[ib][jb], wave_row0 + ib * 32 + 4 * half, ib * 16, sd, filter, qm, best);
+            else sample_block(acc[ib][jb], wave_row0 + ib * 32 + 4 * half, ib * 16, sd, filter, (uint32_t)qm, (uint32_t)(qm >> 32), best);
+        }
         if (q0 + ql >= p.Q) continue;
         uint64_t cw = 0ull;
         if (best != SAMPLE_NONE) {

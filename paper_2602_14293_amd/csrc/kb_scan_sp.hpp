@@ -289,7 +289,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
                          reinterpret_cast<const uint64_t *>(qaux + C::QAUX_THR64), reinterpret_cast<const uint64_t *>(qaux + C::QAUX_QMASK)};
         const int64_t row0 = SAMPLE ? sample_row0(p, tile, TK) : tile * tstride * TK;
         if (SAMPLE)
-            sample_epilogue<IB, JB>(acc, sd, filter, wm * 64, rowB, half, row0, qb * TQ, p,
+            sample_epilogue<IB, JB, true>(acc, sd, filter, wm * 64, rowB, half, row0, qb * TQ, p,
                                     (int64_t)tile * C::GROUPS_PER_TILE + wm * 2 + half, sample_tile_run(p, tile, TK), TK);
         else
             main_epilogue<IB, JB>(acc, sd, filter, wm * 64, rowB, half, row0, qb * TQ, p, my_region, wave_cnt, blockIdx.x * NW + wave);
