@@ -299,17 +299,9 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
         }
     };
 
-    f32x16 acc[2][IB][JB];
-#pragma unroll
-    for (int rh = 0; rh < 2; ++rh)
-#pragma unroll
-        for (int ib = 0; ib < IB; ++ib)
-#pragma unroll
-            for (int jb = 0; jb < JB; ++jb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[rh][ib][jb][i] = 0.f;
+    f32x16 acc[2][IB][JB];      // (never cleared: every item's first MFMAs start from zero)
 
-    auto epilogue = [&](int tile, int qb, int par) {
+    auto epilogue = [&](int tile, int qb, int par, int qrow, int half) {
         const unsigned char *aux = smem + C::OFF_AUX + par * C::AUX_BYTES, *qaux = smem + C::OFF_QAUX;
         const EpiSide sd{reinterpret_cast<const float *>(aux + C::AUX_INVK), reinterpret_cast<const uint64_t *>(aux + C::AUX_TAG),
                          reinterpret_cast<const float *>(qaux + C::QAUX_THRP), reinterpret_cast<const float *>(qaux + C::QAUX_INVQ),
@@ -323,12 +315,6 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
                                         (int64_t)tile * C::GROUPS_PER_TILE + (rh * 2 + wm) * 2 + half, tile_run, TK);
             else
                 main_epilogue<IB, JB>(acc[rh], sd, filter, rh * 128 + wm * 64, qrow, half, row0, qb * TQ, p, my_region, wave_cnt, blockIdx.x * NW + wave);
-#pragma unroll
-            for (int ib = 0; ib < IB; ++ib)
-#pragma unroll
-                for (int jb = 0; jb < JB; ++jb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[rh][ib][jb][i] = 0.f;
         }
     };
 
@@ -372,53 +358,55 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb) fb[0][jb] = read_f(baseB, 0, jb);
 
-#define KBW_MFMA(RH, SA, SB, I, J)                                                                                              \
-    if constexpr (F8)                                                                                                           \
-        acc[RH][I][J] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(SA[I], SB[J], acc[RH][I][J], 0, 0, 0, 0, 0, 0);         \
-    else                                                                                                                        \
-        acc[RH][I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, SA[I]), __builtin_bit_cast(bf16x8, SB[J]), \
-                                                                acc[RH][I][J], 0, 0, 0);                                        \
+        // (KU: the k-step.  In an item's first chunk, the MFMAs of k-step 0 start from the constant zero instead of the
+        // accumulator: nothing has to clear 128 registers between two items)
+#define KBW_MFMA(RH, SA, KU, I, J)                                                                                                  \
+    if constexpr (F8)                                                                                                               \
+        acc[RH][I][J] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(SA[I], fb[KU][J], (FIRST && KU == 0) ? zero16 : acc[RH][I][J], 0, 0, 0, 0, 0, 0); \
+    else                                                                                                                            \
+        acc[RH][I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, SA[I]), __builtin_bit_cast(bf16x8, fb[KU][J]), \
+                                                                (FIRST && KU == 0) ? zero16 : acc[RH][I][J], 0, 0, 0);             \
     __builtin_amdgcn_sched_barrier(0)
         // one k-step: four MFMAs (two with 128-query blocks) on the key fragments SA and the query fragments fb[KU]; meanwhile the key fragments DA
         // are refilled from the piece at AA, k-step KR, and (KBW_KSTEP_AB) the query fragments fb[KR] from the chunk at
         // AB; L0 .. L3: what this wave loads after each of the MFMAs
 #define KBW_KSTEP_AB(RH, SA, KU, DA, AA, AB, KR, L0, L1, L2, L3) \
-    KBW_MFMA(RH, SA, fb[KU], 0, 0);                              \
+    KBW_MFMA(RH, SA, KU, 0, 0);                              \
     DA[0] = read_f(AA, KR, 0);                                   \
     fb[KR][0] = read_f(AB, KR, 0);                               \
     L0;                                                          \
     __builtin_amdgcn_sched_barrier(0);                           \
     if constexpr (JB == 2) {                                     \
-        KBW_MFMA(RH, SA, fb[KU], 0, 1);                          \
+        KBW_MFMA(RH, SA, KU, 0, 1);                          \
         fb[KR][1] = read_f(AB, KR, 1);                           \
     }                                                            \
     DA[1] = read_f(AA, KR, 1);                                   \
     L1;                                                          \
     __builtin_amdgcn_sched_barrier(0);                           \
-    KBW_MFMA(RH, SA, fb[KU], 1, 0);                              \
+    KBW_MFMA(RH, SA, KU, 1, 0);                              \
     L2;                                                          \
     __builtin_amdgcn_sched_barrier(0);                           \
     if constexpr (JB == 2) {                                     \
-        KBW_MFMA(RH, SA, fb[KU], 1, 1);                          \
+        KBW_MFMA(RH, SA, KU, 1, 1);                          \
     }                                                            \
     L3;                                                          \
     __builtin_amdgcn_sched_barrier(0)
 #define KBW_KSTEP_A(RH, SA, KU, DA, AA, KR, L0, L1, L2, L3) \
-    KBW_MFMA(RH, SA, fb[KU], 0, 0);                         \
+    KBW_MFMA(RH, SA, KU, 0, 0);                         \
     DA[0] = read_f(AA, KR, 0);                              \
     L0;                                                     \
     __builtin_amdgcn_sched_barrier(0);                      \
     if constexpr (JB == 2) {                                \
-        KBW_MFMA(RH, SA, fb[KU], 0, 1);                     \
+        KBW_MFMA(RH, SA, KU, 0, 1);                     \
     }                                                       \
     DA[1] = read_f(AA, KR, 1);                              \
     L1;                                                     \
     __builtin_amdgcn_sched_barrier(0);                      \
-    KBW_MFMA(RH, SA, fb[KU], 1, 0);                         \
+    KBW_MFMA(RH, SA, KU, 1, 0);                         \
     L2;                                                     \
     __builtin_amdgcn_sched_barrier(0);                      \
     if constexpr (JB == 2) {                                \
-        KBW_MFMA(RH, SA, fb[KU], 1, 1);                     \
+        KBW_MFMA(RH, SA, KU, 1, 1);                     \
     }                                                       \
     L3;                                                     \
     __builtin_amdgcn_sched_barrier(0)
@@ -426,18 +414,18 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
         // block ib is refilled (piece at AA, k-step KR) right after its two MFMAs, two MFMAs before it is used again;
         // two loads per k-step (L0, L1), since a phase has two k-steps
 #define KBW_KSTEP8(RH, KU, AA, KR, RB0, RB1, L0, L1) \
-    KBW_MFMA(RH, xa, fb[KU], 0, 0);                  \
+    KBW_MFMA(RH, xa, KU, 0, 0);                  \
     RB0;                                             \
     L0;                                              \
     __builtin_amdgcn_sched_barrier(0);               \
-    KBW_MFMA(RH, xa, fb[KU], 0, 1);                  \
+    KBW_MFMA(RH, xa, KU, 0, 1);                  \
     xa[0] = read_f(AA, KR, 0);                       \
     RB1;                                             \
     __builtin_amdgcn_sched_barrier(0);               \
-    KBW_MFMA(RH, xa, fb[KU], 1, 0);                  \
+    KBW_MFMA(RH, xa, KU, 1, 0);                  \
     L1;                                              \
     __builtin_amdgcn_sched_barrier(0);               \
-    KBW_MFMA(RH, xa, fb[KU], 1, 1);                  \
+    KBW_MFMA(RH, xa, KU, 1, 1);                  \
     xa[1] = read_f(AA, KR, 1);                       \
     __builtin_amdgcn_sched_barrier(0)
 #define KBW_NONE (void)0
@@ -457,7 +445,9 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
                 bare_barrier();
                 __builtin_amdgcn_sched_barrier(0);
             };
-            for (int c = 0; c < NC; ++c) {
+            auto chunk = [&](auto first_c, int c) {
+                constexpr bool FIRST = decltype(first_c)::value;
+                const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
                 const int g = g0 + c;
                 // ======== phase 2g: key piece in slot ra, query chunk in slots rb, rb+1 ========
                 {
@@ -523,7 +513,9 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
                     rb = rbn;
                     ++f;
                 }
-            }
+            };
+            chunk(std::true_type{}, 0);
+            for (int c = 1; c < NC; ++c) chunk(std::false_type{}, c);
         };
 
         for (int it = 0; it < my_items; ++it) {
@@ -533,9 +525,12 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
                 // What the epilogue derives from the item's coordinates (addresses of its outputs, row numbers) is
                 // computed here and not, as the compiler would have it when a workgroup has a single item, before
                 // the chunks, where it would sit in registers the contraction needs.
-                int tile_e = tile, qb_e = qb, par_e = par;
-                asm volatile("" : "+s"(tile_e), "+s"(qb_e), "+s"(par_e));
-                epilogue(tile_e, qb_e, par_e);
+                // The same for what it derives from the lane's place in the tile (LDS addresses of the lane's query
+                // and rows): kept across the chunks these cost registers that end up spilled, and a reload
+                // queues behind the stream loads in flight.
+                int tile_e = tile, qb_e = qb, par_e = par, qrow_e = qrow, half_e = half;
+                asm volatile("" : "+s"(tile_e), "+s"(qb_e), "+s"(par_e), "+v"(qrow_e), "+v"(half_e));
+                epilogue(tile_e, qb_e, par_e, qrow_e, half_e);
             }
             par ^= 1;
             tile += step_tile;
