@@ -283,6 +283,13 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
             for (int i = 0; i < 16; ++i) acc[ib][jb][i] = 0.f;
 
     auto epilogue = [&](int tile, int qb, int par) {
+        // What the epilogue derives from the item's coordinates and from the lane's place in the tile (addresses of
+        // its outputs, LDS addresses of the lane's query and rows) is computed here: kept across the chunks it
+        // sits in registers the software pipeline needs, gets spilled, and a reload queues behind the stream
+        // loads in flight.
+        int rowB_e = rowB, half_e = half;
+        asm volatile("" : "+s"(tile), "+s"(qb), "+s"(par), "+v"(rowB_e), "+v"(half_e));
+        const int rowB = rowB_e, half = half_e;
         const unsigned char *aux = smem + C::OFF_AUX + par * C::AUX_BYTES, *qaux = smem + C::OFF_QAUX;
         const EpiSide sd{reinterpret_cast<const float *>(aux + C::AUX_INVK), reinterpret_cast<const uint64_t *>(aux + C::AUX_TAG),
                          reinterpret_cast<const float *>(qaux + C::QAUX_THRP), reinterpret_cast<const float *>(qaux + C::QAUX_INVQ),

@@ -164,6 +164,10 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
     // (addresses as a wave-uniform base plus a 32-bit lane offset, the form that needs no 64-bit vector arithmetic)
     auto issue_tile_aux = [&]() {       // role 0 only
         lds_u8 *aux = lds + C::OFF_AUX + ld_par * C::AUX_BYTES;
+        // the lane's row numbers are formed here each time (two shifts): kept in registers across the chunks they
+        // get spilled, and their reload waits for every stream load in flight
+        int lane = threadIdx.x & 63;
+        asm volatile("" : "+v"(lane));
         if constexpr (SAMPLE) {
             const int64_t tile_run = sample_tile_run(p, ld_tile, TK);
             const int64_t r = sample_row(p, tile_run, ld_tile, TK, ridx * 64 + lane);
@@ -204,6 +208,8 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
     // and 128 queries).
     auto issue_query_aux = [&](int qb) {    // role 1 only
         lds_u8 *aux = lds + C::OFF_QAUX;
+        int lane = threadIdx.x & 63;            // (formed here each time, as in issue_tile_aux)
+        asm volatile("" : "+v"(lane));
         const int q0 = qb * TQ;
         if constexpr (SAMPLE) {
             if (filter) {
