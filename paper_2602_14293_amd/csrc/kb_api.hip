@@ -654,6 +654,8 @@ struct FinalArgs {
     uint32_t *fb_done;        // [Q] arrivals of the parts of an exhaustive scan (zero before the launch)
     uint64_t *fb_lists;       // [Q][fb_parts][k] their partial results
     int32_t fb_parts;
+    const uint64_t *thr64;    // [Q] threshold words of the scan
+    int32_t raw;              // the lists hold raw dot products (plain queries), not finished candidate words
 };
 
 // KT = KT_FP8_Q8 stands for fp8 keys with fp8 queries (one fp8 matrix instruction per 64-byte chunk, as in the scan).
@@ -813,6 +815,25 @@ template <int KT> __global__ __launch_bounds__(256) void finalize_kernel(FinalAr
             for (uint32_t i = tid; i < seg_n[sg]; i += 256)
                 buf[seg_off[sg] + i] = a.cand[(size_t)q * a.cand_cap + sg * seg_cap + i];
         __syncthreads();
+        if (a.raw) {
+            // A plain scan leaves (dot product, row): finish each candidate as the scan's exact test would have:
+            // the final score from the same three fp32 operations every kernel uses, no removed or out-of-range
+            // row, nothing below the threshold word.  What fails becomes a zero word, which sorts last.
+            const float iq = a.invq[q];
+            const uint64_t t64 = a.thr64[q];
+            for (uint32_t i = tid; i < n; i += 256) {
+                const uint64_t w = buf[i];
+                const uint32_t row = candidate_index(w);
+                uint64_t cw = 0ull;
+                if ((int64_t)row < a.n_keys) {
+                    const float ik = a.inv_norm[row];
+                    const uint64_t c = pack_candidate(final_score(raw_candidate_dot(w), ik, iq), row);
+                    if (!row_removed(ik) && c >= t64) cw = c;
+                }
+                buf[i] = cw;
+            }
+            __syncthreads();
+        }
         select_topk_desc(buf, (int)n, a.k, sc, tid, 256);
     }
     if (tid < a.k) {
@@ -1322,6 +1343,8 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
     f.fb_done = fb_done;
     f.fb_lists = reinterpret_cast<uint64_t *>(ws + p.off_fb_lists);
     f.fb_parts = p.fb_parts;
+    f.thr64 = thr64;
+    f.raw = draw ? 0 : 1;
     const size_t fin_lds = (size_t)p.cand_cap * 8 + 16 + sizeof(SelectScratch);
     static LdsAllowed fin_allowed[4];
     const int fin_kind = q8 ? KT_FP8_Q8 : (int)kb->dtype;

@@ -52,13 +52,15 @@ __device__ inline void flush_records(const ScanArgs &p, Record *region, uint32_t
 // Main pass.  Per block: a bound test (largest dot times largest 1/|k| of the lane's 16 rows against the
 // query's pre-filter) costs one max-reduction and decides whether any lane has to look closer; lanes that
 // do build the 16-bit mask of elements passing the exact pre-filter (sign bit of fma(dot, inv_k, -thrp),
-// collected with one v_alignbit each).  Survivors are rare, so the wave then walks them with a
-// wave-uniform element index: it takes the mask of one lane that has work (v_readlane), and for each of
-// its set bits every lane with that bit handles that element: final score, candidate word, threshold
-// word, tag predicate, append to the wave's private record region (no atomics: slot = the wave's running
-// count + the lane's rank among the appending lanes; flush_records moves a full region to the per-query
-// lists).  A uniform index turns the element selection into an indexed register read instead of a 16-way
-// select per lane.
+// collected with one v_alignbit each).  Survivors are rare (a handful per wave and item), and a wave spends
+// their cost with its matrix core idle, so as little as possible is done for them here: every lane with a
+// survivor picks its own element (a 16-way select, no wave-uniform walk and no exchange between lanes), checks
+// the tag predicate (the one test that can thin the records out by orders of magnitude) and appends
+// (raw dot, row, query) to the wave's private record region (no atomics: slot = the wave's running count + the
+// lane's rank among the appending lanes; flush_records moves a full region to the per-query lists).  The final
+// score, the removed-row test and the ordering are left to the kernel that selects from the lists: the
+// pre-filter admits an element whenever its final score can reach the threshold (and almost only then), so the
+// lists hold what they would hold after an exact test here.
 struct EpiRows {               // 1/|k| of the 16 key rows a lane holds in one 32-row block
     float ik[16];
     float ikmax;
@@ -84,8 +86,8 @@ __device__ inline EpiRows load_rows(const EpiSide &sd, int rl0)
     return r;
 }
 
-__device__ inline void main_block(const f32x16 &a, const EpiRows &rw, float tp, int ql, const EpiSide &sd, bool filter,
-                                  int64_t row0, int q0, const ScanArgs &p, Record *region, uint32_t &wave_cnt, uint32_t region_id)
+__device__ inline void main_block(const f32x16 &a, const EpiRows &rw, float tp, uint64_t qm, uint32_t query, const EpiSide &sd, bool filter,
+                                  int64_t row0, const ScanArgs &p, Record *region, uint32_t &wave_cnt, uint32_t region_id)
 {
     float amax = a[0];
 #pragma unroll
@@ -100,45 +102,31 @@ __device__ inline void main_block(const f32x16 &a, const EpiRows &rw, float tp, 
             fail = __builtin_amdgcn_alignbit(fail, as_u32(__builtin_fmaf(a[i], rw.ik[i], -tp)), 31);
     }
     uint32_t pass = maybe ? (~fail & 0xffffu) : 0u;     // element i sits at bit 15 - i
-    uint64_t lanes = __builtin_amdgcn_ballot_w64(pass != 0);
-    if (lanes == 0) return;
-    const float iq = sd.invq[ql];
-    const uint64_t t64 = sd.thr64[ql];
-    const uint64_t qm = filter ? sd.qmask[ql] : 0ull;
-    do {
-        // the elements one of the lanes wants looked at; every lane that wants any of them joins in
-        uint32_t m = (uint32_t)__builtin_amdgcn_readlane((int)pass, __builtin_ctzll(lanes));
-        const uint32_t mine = pass & m;
-        pass &= ~m;
-        do {
-            const int b = 31 - __builtin_clz(m);
-            m &= ~(1u << b);
-            const int i = 15 - b;                               // wave-uniform
-            const bool has = (mine >> b) & 1u;
-            const int rl = rw.rl0 + 8 * (i >> 2) + (i & 3);
-            const int64_t row = row0 + rl;
-            const float ik = sd.invk[rl];
-            const uint64_t tg = filter ? sd.tag[rl] : 0ull;    // read with ik: one LDS round trip per element, not two
-            const float s = final_score(a[i], ik, iq);
-            const uint64_t cw = pack_candidate(s, (uint32_t)row);
-            bool ok = has && row < p.n_keys && cw >= t64 && !row_removed(ik);
-            if (filter) ok = ok && (tg & qm) != 0;
-            // slot in the wave's own record region: running count + rank among the lanes that append (up to 64 of
-            // them: the region is emptied first when fewer slots are left)
-            const uint64_t okm = __builtin_amdgcn_ballot_w64(ok);
-            if (okm != 0 && wave_cnt + 64 > (uint32_t)p.region_cap) flush_records(p, region, wave_cnt, region_id);
-            if (ok) {
-                const uint32_t pos = wave_cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(okm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)okm, 0u));
-                Record rec;
-                rec.cand = cw;
-                rec.query = (uint32_t)(q0 + ql);
-                rec.pad = 0;
-                region[pos] = rec;
-            }
-            wave_cnt += (uint32_t)__builtin_popcountll(okm);
-        } while (m != 0);
-        lanes = __builtin_amdgcn_ballot_w64(pass != 0);
-    } while (lanes != 0);
+    while (__builtin_amdgcn_ballot_w64(pass != 0) != 0) {
+        const bool has = pass != 0;
+        const int b = 31 - __builtin_clz(has ? pass : 1u);
+        pass &= ~(1u << b);
+        const int i = 15 - b;
+        const int rl = rw.rl0 + 8 * (i >> 2) + (i & 3);
+        const uint64_t tg = filter ? sd.tag[rl] : 0ull;         // (in flight during the select)
+        const float dot = select16(a, i);
+        const int64_t row = row0 + rl;
+        bool ok = has && row < p.n_keys;
+        if (filter) ok = ok && (tg & qm) != 0;
+        // slot in the wave's own record region: running count + rank among the lanes that append (up to 64 of
+        // them: the region is emptied first when fewer slots are left)
+        const uint64_t okm = __builtin_amdgcn_ballot_w64(ok);
+        if (okm != 0 && wave_cnt + 64 > (uint32_t)p.region_cap) flush_records(p, region, wave_cnt, region_id);
+        if (ok) {
+            const uint32_t pos = wave_cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(okm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)okm, 0u));
+            Record rec;
+            rec.cand = pack_raw_candidate(dot, (uint32_t)row);
+            rec.query = query;
+            rec.pad = 0;
+            region[pos] = rec;
+        }
+        wave_cnt += (uint32_t)__builtin_popcountll(okm);
+    }
 }
 
 template <int IB, int JB>
@@ -146,14 +134,18 @@ __device__ inline void main_epilogue(const f32x16 (&acc)[IB][JB], const EpiSide 
                                      int half, int64_t row0, int q0, const ScanArgs &p, Record *region, uint32_t &wave_cnt, uint32_t region_id)
 {
     float thrp[JB];
+    uint64_t qm[JB];
 #pragma unroll
-    for (int jb = 0; jb < JB; ++jb) thrp[jb] = sd.thrp[ql0 + jb * 32];
+    for (int jb = 0; jb < JB; ++jb) {
+        thrp[jb] = sd.thrp[ql0 + jb * 32];
+        qm[jb] = filter ? sd.qmask[ql0 + jb * 32] : 0ull;
+    }
 #pragma unroll
     for (int ib = 0; ib < IB; ++ib) {
         const EpiRows rw = load_rows(sd, wave_row0 + ib * 32 + 4 * half);
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb)
-            main_block(acc[ib][jb], rw, thrp[jb], ql0 + jb * 32, sd, filter, row0, q0, p, region, wave_cnt, region_id);
+            main_block(acc[ib][jb], rw, thrp[jb], qm[jb], (uint32_t)(q0 + ql0 + jb * 32), sd, filter, row0, p, region, wave_cnt, region_id);
     }
 }
 
