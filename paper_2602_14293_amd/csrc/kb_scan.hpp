@@ -62,12 +62,13 @@ template <> struct Mma<KB_F32> {
     }
 };
 
-// e4m3 has 3 mantissa bits and a 4-bit exponent, so every code is exactly a bf16 value: convert with the
-// hardware fp8 -> fp32 instruction and keep the upper 16 bits of each fp32.
+// e4m3 has 3 mantissa bits and a 4-bit exponent, so every code is exactly a bf16 value: one gfx950 conversion
+// instruction (v_cvt_scalef32_pk_bf16_fp8, scale 1) turns two codes into a packed pair of bf16 values.
 __device__ inline uint32_t e4m3_pair_to_bf16(uint32_t word, bool upper)
 {
-    f32x2 f = upper ? __builtin_amdgcn_cvt_pk_f32_fp8(word, true) : __builtin_amdgcn_cvt_pk_f32_fp8(word, false);
-    return __builtin_amdgcn_perm(as_u32(f.y), as_u32(f.x), 0x07060302u);
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const bf16x2 v = upper ? __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(word, 1.0f, true) : __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(word, 1.0f, false);
+    return __builtin_bit_cast(uint32_t, v);
 }
 
 template <> struct Mma<KB_FP8_E4M3> {
