@@ -99,7 +99,7 @@ kb_status_t kb_normalize(kb_t *kb, void *hip_stream);
  * performance knobs of kb_set_tuning: ask again after changing one.  Returns 0 on invalid arguments.
  *
  * kb_query_plan_bytes is the host-side planner behind it: the bytes a query of `kind` (0: kb_query, 1:
- * kb_query_sampled, 2: kb_query with KB_FP8_E4M3 queries) needs when the knowledge base holds n rows; 0 when the
+ * kb_query_sampled, 2: kb_query with KB_FP8_E4M3 queries, 3: kb_query_sampled with them) needs when the knowledge base holds n rows; 0 when the
  * arguments are invalid or the handle does not take that kind of query.  For every n <= capacity it is at most
  * kb_query_workspace_bytes(kb, Q, k).  No device work.
  */
@@ -109,8 +109,7 @@ size_t kb_query_plan_bytes(const kb_t *kb, int64_t n, int32_t Q, int32_t k, int3
 /*
  * Retrieval (Section 3: State Selector + top-k of the Optimization Selector).
  *   queries_dev [Q, d] row-major, 16-byte aligned; q_dtype must equal the key dtype, except that
- *               KB_FP8_E4M3 keys take KB_BF16 queries, or KB_FP8_E4M3 queries when d >= 384 (else
- *               KB_ERR_INVALID_ARG).  fp8 queries are e4m3 codes without a scale (a positive factor per query
+ *               KB_FP8_E4M3 keys take KB_BF16 or KB_FP8_E4M3 queries.  fp8 queries are e4m3 codes without a scale (a positive factor per query
  *               row cancels in the cosine); their dot products are formed by the fp8 matrix instruction,
  *               whose 64-term sums are slightly less precise than fp32 (score error up to about 1e-4).
  *   qmask_dev   [Q] uint64, or NULL = no filtering for any query (a zero mask word qualifies nothing)
@@ -157,8 +156,7 @@ kb_status_t kb_query_static(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtyp
  *   indices_out_dev [Q, k] int32 and keys_out_dev [Q, k] fp32: drawn entries ordered by (key descending, index
  *               ascending), padded with (-1, -inf) when fewer than k entries qualify.  Keys are computed in fp32
  *               from the fp32 score of kb_query.
- * Everything else (queries, q_dtype, qmask, k, workspace = kb_query_workspace_bytes, stream, errors) as kb_query,
- * except that KB_FP8_E4M3 queries are not accepted (KB_ERR_DTYPE).
+ * Everything else (queries, q_dtype, qmask, k, workspace = kb_query_workspace_bytes, stream, errors) as kb_query.
  */
 kb_status_t kb_query_sampled(kb_t *kb, const void *queries_dev, kb_dtype_t q_dtype, int32_t Q, const uint64_t *qmask_dev,
                              int32_t k, const float *gain_dev, float temperature, uint64_t seed, int32_t first_query,

@@ -34,6 +34,13 @@ bool scan_config_info(int key_dtype, int config, ConfigInfo *out)
     KB_SCAN_CONFIGS_F32(X)
     KB_SCAN_CONFIGS_FP8(X)
 #undef X
+#define X(ID, KT, TK, TQ, WM, WN, RBA, NSTAGE, WGPC)                          \
+    if (key_dtype == KB_FP8_E4M3 && config == ID) {                           \
+        *out = ConfigInfo{TK, TQ, 64 * WM * WN, WM * 2, WGPC, RBA, 0};    \
+        return true;                                                          \
+    }
+    KB_SCAN_CONFIGS_FP8_Q8(X)
+#undef X
 #define XS(ID, KT, TQ, NSA, NSB)                                              \
     if (key_dtype == KT && config == ID) {                                    \
         *out = ConfigInfo{256, TQ, 512, 8, 1, 64 * ((NSA > NSB ? NSA : NSB) + 1), 3}; \
@@ -79,6 +86,11 @@ constexpr int FALLBACK_PARTS = 32;    // workgroups that share the rows of a que
 constexpr size_t WS_ALIGN = 256;
 constexpr int FP8_QUERY_CONFIG = 5;    // scan configuration of fp8 keys with fp8 queries (kb_configs.hpp)
 constexpr int FP8_QUERY_WIDE_CONFIG = 20;     // ... with 128-byte row pieces: rows of a multiple of 128 bytes, 512 at least
+constexpr int FP8_QUERY_TILED_CONFIG = 6;     // ... the tiled kernel: 6, 7, 8 for query blocks of 64, 128, 256; every row length
+bool is_fp8_query_config(int config)
+{
+    return config == FP8_QUERY_CONFIG || config == FP8_QUERY_WIDE_CONFIG || (config >= FP8_QUERY_TILED_CONFIG && config <= FP8_QUERY_TILED_CONFIG + 2);
+}
 
 int key_bytes(kb_dtype_t t) { return t == KB_F32 ? 4 : t == KB_BF16 ? 2 : 1; }
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -124,17 +136,23 @@ bool choose_kernels(const kb *h, int64_t n, int32_t Q, bool draw, bool q8, Choic
     const int generic = Q <= 32 ? 1 : Q <= 128 ? 2 : 3;        // the tiled kernel: every dtype, every row length
     const size_t row_bytes = (size_t)h->d * key_bytes(h->dtype);
     if (q8) {       // fp8 queries: only the kernels built on the fp8 matrix instruction take them
-        if (draw || h->dtype != KB_FP8_E4M3) return false;
-        c.config = (row_bytes % 128 == 0 && row_bytes >= 512) ? FP8_QUERY_WIDE_CONFIG : FP8_QUERY_CONFIG;
-        if (h->tune_config == FP8_QUERY_CONFIG) c.config = FP8_QUERY_CONFIG;         // the other one can be asked for
-        if (!scan_config_info(h->dtype, c.config, &c.ci) || row_bytes < (size_t)c.ci.min_row_bytes) return false;
+        if (h->dtype != KB_FP8_E4M3) return false;
+        const int generic8 = Q <= 64 ? FP8_QUERY_TILED_CONFIG : Q <= 128 ? FP8_QUERY_TILED_CONFIG + 1 : FP8_QUERY_TILED_CONFIG + 2;
+        // large batches: the pipelined kernels (256-query blocks); smaller ones would pad their query columns there
+        c.config = Q <= 128 ? generic8 : (row_bytes % 128 == 0 && row_bytes >= 512) ? FP8_QUERY_WIDE_CONFIG : FP8_QUERY_CONFIG;
+        if (is_fp8_query_config((int)h->tune_config)) c.config = (int)h->tune_config;         // another one can be asked for
+        if (!scan_config_info(h->dtype, c.config, &c.ci)) return false;
+        // the weighted random selection exists in the tiled kernel only, and rows may be too short for a pipelined kernel
+        if ((draw && c.ci.family != 0) || row_bytes < (size_t)c.ci.min_row_bytes) {
+            c.config = generic8;
+            if (!scan_config_info(h->dtype, c.config, &c.ci)) return false;
+        }
     } else {
         c.config = h->tune_config > 0 ? (int)h->tune_config : scan_config_for(h->dtype, Q, h->d, n);
         if (!scan_config_info(h->dtype, c.config, &c.ci)) return false;
         // fall back where a (forced) configuration does not apply: the weighted random selection exists in the
         // tiled kernel only, rows may be too short for a pipelined kernel, and the fp8-query kernels read fp8 queries
-        if ((draw && c.ci.family != 0) || row_bytes < (size_t)c.ci.min_row_bytes ||
-            (h->dtype == KB_FP8_E4M3 && (c.config == FP8_QUERY_CONFIG || c.config == FP8_QUERY_WIDE_CONFIG))) {
+        if ((draw && c.ci.family != 0) || row_bytes < (size_t)c.ci.min_row_bytes || (h->dtype == KB_FP8_E4M3 && is_fp8_query_config(c.config))) {
             c.config = generic;
             if (!scan_config_info(h->dtype, c.config, &c.ci)) return false;
         }
@@ -1125,10 +1143,10 @@ size_t kb_query_workspace_bytes(const kb_t *kb, int32_t Q, int32_t k)
     bool any = false;
     const int64_t ns[2] = {1, kb->capacity};
     for (int64_t n : ns)
-        for (int kind = 0; kind < 3; ++kind) {      // plain, weighted random selection, fp8 queries
+        for (int kind = 0; kind < 4; ++kind) {      // plain, weighted random selection, fp8 queries, both
             Choice c;
-            if (!choose_kernels(kb, n, Q, kind == 1, kind == 2, &c)) continue;
-            bound_sizes(kb, c, Q, k, kind == 1, m);
+            if (!choose_kernels(kb, n, Q, (kind & 1) != 0, (kind & 2) != 0, &c)) continue;
+            bound_sizes(kb, c, Q, k, (kind & 1) != 0, m);
             any = true;
         }
     if (!any) return 0;
@@ -1140,10 +1158,10 @@ size_t kb_query_workspace_bytes(const kb_t *kb, int32_t Q, int32_t k)
 
 size_t kb_query_plan_bytes(const kb_t *kb, int64_t n, int32_t Q, int32_t k, int32_t kind)
 {
-    if (!kb || n < 0 || n > kb->capacity || Q < 1 || k < 1 || k > KB_K_MAX || kind < 0 || kind > 2) return 0;
-    if (const int parts = small_path_parts(kb, n, Q, kind == 1)) return make_small_plan(Q, k, parts).total;
+    if (!kb || n < 0 || n > kb->capacity || Q < 1 || k < 1 || k > KB_K_MAX || kind < 0 || kind > 3) return 0;
+    if (const int parts = small_path_parts(kb, n, Q, (kind & 1) != 0)) return make_small_plan(Q, k, parts).total;
     Plan p;
-    return make_plan(kb, n, Q, k, kind == 1, kind == 2, &p) ? p.total : 0;
+    return make_plan(kb, n, Q, k, (kind & 1) != 0, (kind & 2) != 0, &p) ? p.total : 0;
 }
 
 // kb_query and kb_query_sampled: the same pipeline; `gain_dev` != nullptr selects the weighted random selection.
@@ -1158,13 +1176,8 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
     const kb_dtype_t want_q = kb->dtype == KB_F32 ? KB_F32 : KB_BF16;
     const bool q8 = kb->dtype == KB_FP8_E4M3 && q_dtype == KB_FP8_E4M3;     // fp8 queries against fp8 keys
     if (q_dtype != want_q && !q8) return KB_ERR_DTYPE;
-    if (q8 && draw) return KB_ERR_DTYPE;
     if (Q < 1 || k < 1 || k > KB_K_MAX) return KB_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(queries_dev) & 15) != 0) return KB_ERR_INVALID_ARG;
-    if (q8) {       // the one kernel that takes fp8 queries needs rows of at least its ring's length
-        ConfigInfo ci;
-        if (!scan_config_info(KB_FP8_E4M3, FP8_QUERY_CONFIG, &ci) || kb->d < ci.min_row_bytes) return KB_ERR_INVALID_ARG;
-    }
     if (qmask_dev && !kb->tags) return KB_ERR_NO_TAGS;
     if (kb->n_normalized != kb->n) return KB_ERR_NOT_NORMALIZED;
     if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) & (WS_ALIGN - 1)) != 0) return KB_ERR_WORKSPACE;

@@ -15,6 +15,11 @@
     X(1, KB_FP8_E4M3, 128, 32, 4, 1, 64, 3, 2)   \
     X(2, KB_FP8_E4M3, 128, 128, 2, 2, 64, 3, 2)  \
     X(3, KB_FP8_E4M3, 128, 256, 2, 2, 64, 3, 1)
+// ... with fp8 queries as well (key type KB_FP8_Q8 inside the kernels): every row length, every batch size
+#define KB_SCAN_CONFIGS_FP8_Q8(X)                \
+    X(6, KB_FP8_Q8, 128, 64, 2, 2, 64, 3, 2)     \
+    X(7, KB_FP8_Q8, 128, 128, 2, 2, 64, 3, 2)    \
+    X(8, KB_FP8_Q8, 128, 256, 2, 2, 64, 3, 1)
 
 // Software-pipelined configurations (kb_scan_sp.hpp): XS(id, key dtype, TQ, NSA, NSB); 256-row tiles, 512 threads,
 // NSA / NSB = ring depth of key / query chunks in LDS.

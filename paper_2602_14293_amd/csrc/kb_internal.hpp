@@ -72,6 +72,10 @@ __device__ inline float final_score(float dot, float inv_k, float inv_q) { retur
 constexpr uint32_t REMOVED_BIT = 0x80000000u;
 __host__ __device__ inline bool row_removed(float inv_k) { return (as_u32(inv_k) & REMOVED_BIT) != 0; }
 
+// Kernel-side name of "fp8 keys with fp8 queries" where a kernel template is selected by key type: the keys are
+// KB_FP8_E4M3 either way, but both operands go to the fp8 matrix instruction as they are stored.
+constexpr int KB_FP8_Q8 = 3;
+
 struct Record {  // one candidate that passed the threshold filter of the scan
     uint64_t cand;
     uint32_t query;

@@ -33,12 +33,15 @@ template <int KT> struct KeyTraits;
 template <> struct KeyTraits<KB_F32> { static constexpr int KEY_BYTES = 4, QRY_BYTES = 4; };
 template <> struct KeyTraits<KB_BF16> { static constexpr int KEY_BYTES = 2, QRY_BYTES = 2; };
 template <> struct KeyTraits<KB_FP8_E4M3> { static constexpr int KEY_BYTES = 1, QRY_BYTES = 2; };
+template <> struct KeyTraits<KB_FP8_Q8> { static constexpr int KEY_BYTES = 1, QRY_BYTES = 1; };
 
 // One k-group = 32 bytes of a key row: lane half h owns bytes [16h, 16h+16) of it.
 //   bf16: 16 elements, one 32x32x16 MFMA.          query bytes [16h, +16) of the group's 32
 //   f32 :  8 elements, four 32x32x2 MFMAs.         query bytes [16h, +16) of the group's 32
 //   fp8 : 32 elements, two 32x32x16 bf16 MFMAs after an exact e4m3 -> bf16 widening;
 //         query bytes [32h, +32) of the group's 64 (two 16-byte pieces).
+// fp8 keys with fp8 queries: one k-group = 64 bytes of a key row and of a query row, one 32x32x64 fp8 MFMA; lane half
+// h owns bytes [32h, 32h+32) of either (two 16-byte pieces), the operand layout of every kernel that takes fp8 queries.
 template <int KT> struct Mma;
 
 template <> struct Mma<KB_BF16> {
@@ -93,6 +96,19 @@ template <> struct Mma<KB_FP8_E4M3> {
     }
 };
 
+template <> struct Mma<KB_FP8_Q8> {
+    struct PrepA {
+        u32x4 lo, hi;
+    };
+    static __device__ inline void run(f32x16 &acc, const PrepA &a, u32x4 b0, u32x4 b1)
+    {
+        typedef int i32x8 __attribute__((ext_vector_type(8)));
+        const i32x8 av = {(int)a.lo[0], (int)a.lo[1], (int)a.lo[2], (int)a.lo[3], (int)a.hi[0], (int)a.hi[1], (int)a.hi[2], (int)a.hi[3]};
+        const i32x8 bv = {(int)b0[0], (int)b0[1], (int)b0[2], (int)b0[3], (int)b1[0], (int)b1[1], (int)b1[2], (int)b1[3]};
+        acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, bv, acc, 0, 0, 0, 0, 0, 0);
+    }
+};
+
 // XOR swizzle of the 16-byte slots of a row with PPR slots: 16 consecutive rows at one logical slot
 // touch 16 different slots modulo 256 bytes, i.e. all 64 LDS banks once.
 template <int PPR> __device__ inline int swizzle(int row)
@@ -110,7 +126,8 @@ struct ScanCfg {
     static constexpr int BMUL = QRY_BYTES / KEY_BYTES;
     static constexpr int RBB = RBA * BMUL;
     static constexpr int PPRA = RBA / 16, PPRB = RBB / 16;
-    static constexpr int KG = RBA / 32;
+    static constexpr bool Q8 = KT == KB_FP8_Q8;
+    static constexpr int KG = RBA / (Q8 ? 64 : 32);
     static constexpr int NW = WM * WN, THREADS = 64 * NW;
     static constexpr int IB = TK / WM / 32, JB = TQ / WN / 32;
     static constexpr int A_BYTES = TK * RBA, B_BYTES = TQ * RBB, STAGE_BYTES = A_BYTES + B_BYTES;
@@ -246,8 +263,8 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
     // ---- fragment addresses (bytes inside a stage) ----------------------------------------------
     const int rowA = wm * (TK / C::WM) + lrow;
     const int rowB = wn * (TQ / C::WN) + lrow;
-    const int baseA = rowA * RBA | ((half ^ swizzle<C::PPRA>(rowA)) << 4);
-    const int baseB = C::BMUL == 1 ? (rowB * RBB | ((half ^ swizzle<C::PPRB>(rowB)) << 4))
+    const int baseA = C::Q8 ? (rowA * RBA | (((2 * half) ^ swizzle<C::PPRA>(rowA)) << 4)) : (rowA * RBA | ((half ^ swizzle<C::PPRA>(rowA)) << 4));
+    const int baseB = C::BMUL == 1 && !C::Q8 ? (rowB * RBB | ((half ^ swizzle<C::PPRB>(rowB)) << 4))
                                    : (rowB * RBB | (((2 * half) ^ swizzle<C::PPRB>(rowB)) << 4));
 
     f32x16 acc[IB][JB];
@@ -310,12 +327,18 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
                 typename Mma<C::KT>::PrepA a[IB];
                 u32x4 b0[JB], b1[JB];
 #pragma unroll
-                for (int ib = 0; ib < IB; ++ib)
-                    a[ib] = Mma<C::KT>::prepare(
-                        *reinterpret_cast<const u32x4 *>(sA + ((baseA ^ (kg << 5)) + ib * 32 * RBA)));
+                for (int ib = 0; ib < IB; ++ib) {
+                    if constexpr (C::Q8) {
+                        a[ib].lo = *reinterpret_cast<const u32x4 *>(sA + ((baseA ^ (kg << 6)) + ib * 32 * RBA));
+                        a[ib].hi = *reinterpret_cast<const u32x4 *>(sA + ((baseA ^ (kg << 6) ^ 16) + ib * 32 * RBA));
+                    } else {
+                        a[ib] = Mma<C::KT>::prepare(
+                            *reinterpret_cast<const u32x4 *>(sA + ((baseA ^ (kg << 5)) + ib * 32 * RBA)));
+                    }
+                }
 #pragma unroll
                 for (int jb = 0; jb < JB; ++jb) {
-                    if (C::BMUL == 1) {
+                    if (C::BMUL == 1 && !C::Q8) {
                         b0[jb] = *reinterpret_cast<const u32x4 *>(sB + ((baseB ^ (kg << 5)) + jb * 32 * RBB));
                         b1[jb] = b0[jb];
                     } else {

@@ -116,6 +116,15 @@ def test_every_fp8_query_scan_kernel(T, config):
     assert rep.queries == 600 and cnt["exhaustive_queries"] == 0 and cnt["scan_workgroups"] == 256
 
 
+@pytest.mark.parametrize("config,Q", [(6, 50), (7, 130), (8, 600)])
+def test_every_tiled_fp8_query_scan_kernel(T, config, Q):
+    """The tiled kernel on the fp8 matrix instruction (query blocks of 64, 128 and 256), forced for a batch that spans
+    several query blocks: ragged last tile, ragged last block."""
+    w = W.compressed(seed=31, N=30000 + 41, d=512, Q=Q, k=32, centers=32, fp8_queries=True)
+    rep, cnt, _ = T.run_and_check(w, label=f"fp8 x fp8 tiled scan config {config}", tuning={"scan_config": config})
+    assert rep.queries == Q and cnt["exhaustive_queries"] == 0
+
+
 @pytest.mark.parametrize("N,d,Q,k", [(3000, 256, 33, 20), (130, 64, 1, 1), (5000, 128, 260, 7), (9000, 256, 260, 16)])
 def test_fp8_shapes(T, N, d, Q, k):
     w = W.compressed(seed=N, N=N, d=d, Q=Q, k=k, centers=8)
@@ -123,7 +132,8 @@ def test_fp8_shapes(T, N, d, Q, k):
 
 
 @pytest.mark.parametrize("N,d,Q,k", [(24000, 768, 100, 64), (17077, 512, 300, 64), (3000, 384, 33, 20), (130, 448, 1, 1),
-                                     (70000, 1024, 700, 128)])
+                                     (70000, 1024, 700, 128), (3000, 256, 33, 20), (130, 64, 1, 1), (5000, 128, 260, 7),
+                                     (40000, 192, 100, 16), (33000, 320, 20, 8)])
 def test_fp8_queries_on_fp8_keys(T, N, d, Q, k):
     # both operands in e4m3: scored by the fp8 matrix instruction, checked against the oracle on the same codes
     w = W.compressed(seed=N + 1, N=N, d=d, Q=Q, k=k, centers=32, fp8_queries=True)
@@ -136,13 +146,9 @@ def test_fp8_queries_exhaustive_path_and_short_rows(T):
     # few keys: every query is resolved by the exhaustive path, which must score exactly like the scan
     w = W.compressed(seed=5, N=700, d=512, Q=40, k=16, centers=8, fp8_queries=True)
     rep, cnt, _ = T.run_and_check(w, label="fp8 x fp8 small")
-    # rows shorter than the pipelined kernel's ring: refused, not mis-scored
+    # rows shorter than the pipelined kernels' rings go to the tiled kernel
     w2 = W.compressed(seed=6, N=500, d=256, Q=4, k=4, centers=8, fp8_queries=True)
-    kb = T.build_kb(w2)
-    with pytest.raises(kbmod.KBError) as e:
-        kb.query(w2.queries.cuda(), 4)
-    assert e.value.status == 2
-    kb.close()
+    T.run_and_check(w2, label="fp8 x fp8 small, short rows")
 
 
 def test_all_e4m3_codes_decode_like_the_oracle(T):

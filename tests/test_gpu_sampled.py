@@ -34,7 +34,7 @@ def _gains(n, seed, zero_every=0):
     return g
 
 
-def _run(T, w, gain, temperature, seed, first_query=0, label="", tuning=None):
+def _run(T, w, gain, temperature, seed, first_query=0, label="", tuning=None, tight_scale=1.0):
     kb = T.build_kb(w)
     for name, val in (tuning or {}).items():
         kb.set_tuning(name, val)
@@ -47,7 +47,7 @@ def _run(T, w, gain, temperature, seed, first_query=0, label="", tuning=None):
     keys = kb_oracle.selection_keys(T.oracle_scores(w), gain, temperature, seed, first_query)
     tags = W.word_bits(w.tags) if w.qmask is not None else None
     qmask = W.word_bits(w.qmask) if w.qmask is not None else None
-    tight_tau = TIGHT_KEY * max(1.0, 0.05 / temperature)
+    tight_tau = TIGHT_KEY * max(1.0, 0.05 / temperature) * tight_scale
     rep, tight = compare.check(gi, gk, keys, w.k, TAU_KEY, tags=tags, qmask=qmask, label=label, tight_tau=tight_tau)
     assert rep.max_score_err <= tight_tau, f"{label}: key error {rep.max_score_err:.2e}"
     rep.tight = tight
@@ -72,6 +72,15 @@ def test_f32_and_fp8_draws(T):
     _run(T, w, _gains(w.N, 3), 0.2, seed=5, label="f32 draw")
     w = W.compressed(seed=24, N=9000, d=256, Q=40, k=24, centers=32)
     _run(T, w, _gains(w.N, 4, zero_every=5), 0.05, seed=6, label="fp8 draw")
+
+
+@pytest.mark.parametrize("N,d,Q,k", [(9000, 256, 40, 24), (20000 + 5, 512, 300, 16), (700, 64, 3, 8)])
+def test_draw_with_fp8_queries(T, N, d, Q, k):
+    # e4m3 queries on e4m3 keys: scores from the fp8 matrix instruction (error up to 2e-6 on the codes, ten times the
+    # fp32 chain's: the tight tolerance is scaled accordingly), then the same keys
+    w = W.compressed(seed=N + 2, N=N, d=d, Q=Q, k=k, centers=32, fp8_queries=True)
+    rep, cnt, gi, gk, keys = _run(T, w, _gains(w.N, 6, zero_every=9), 0.1, seed=11, label=f"fp8 x fp8 draw N={N} d={d} Q={Q}", tight_scale=10.0)
+    assert rep.queries == Q
 
 
 def test_sparse_mask_and_few_weighted_entries_pad(T):

@@ -103,14 +103,14 @@ def test_fp8_takes_bf16_or_fp8_queries(L):
     st, h = _create(L, dtype=kbmod.KB_FP8_E4M3, scale=FAKE)                          # d = 128
     ws = L.kb_query_workspace_bytes(h, 4, 4)
     assert L.kb_query(h, FAKE, kbmod.KB_F32, 4, None, 4, FAKE, FAKE, FAKE, ws, None) == 3
-    assert L.kb_query(h, FAKE, kbmod.KB_FP8_E4M3, 4, None, 4, FAKE, FAKE, FAKE, ws, None) == 2   # fp8 queries need d >= 384
+    assert L.kb_query(h, FAKE, kbmod.KB_FP8_E4M3, 4, None, 4, FAKE, FAKE, None, ws, None) == 7   # short rows too: accepted up to the workspace check
     L.kb_destroy(h)
     st, h = _create(L, d=512, dtype=kbmod.KB_FP8_E4M3, scale=FAKE)
     ws = L.kb_query_workspace_bytes(h, 4, 4)
     assert L.kb_query(h, FAKE, kbmod.KB_FP8_E4M3, 4, None, 4, FAKE, FAKE, None, ws, None) == 7   # accepted up to the workspace check
     assert L.kb_query(h, FAKE, kbmod.KB_BF16, 4, None, 4, FAKE, FAKE, None, ws, None) == 7
     assert L.kb_query_sampled(h, FAKE, kbmod.KB_FP8_E4M3, 4, None, 4, FAKE, ctypes.c_float(0.1), ctypes.c_uint64(1), 0,
-                              FAKE, FAKE, FAKE, ws, None) == 3                                  # the weighted draw takes bf16 queries
+                              FAKE, FAKE, None, ws, None) == 7                                  # the weighted draw takes them as well
     L.kb_destroy(h)
     st, h = _create(L, dtype=kbmod.KB_BF16)                                          # fp8 queries go with fp8 keys only
     assert L.kb_query(h, FAKE, kbmod.KB_FP8_E4M3, 4, None, 4, FAKE, FAKE, FAKE, 1 << 20, None) == 3
@@ -233,13 +233,13 @@ def test_workspace_size_bounds_the_plan_of_every_row_count(L, dtype, d, cap, Q, 
     need = L.kb_query_workspace_bytes(h, Q, k)
     assert need > 0 and need % 256 == 0
     worst = 0
-    for kind in (0, 1, 2):
+    for kind in (0, 1, 2, 3):
         for n in _dense_counts(cap, 128):
             got = L.kb_query_plan_bytes(h, n, Q, k, kind)
             assert got <= need, f"kind {kind}: {n} rows need {got} bytes, kb_query_workspace_bytes says {need}"
             worst = max(worst, got)
     assert worst * 4 >= need, f"the bound {need} is far above the largest plan found ({worst})"
-    assert L.kb_query_plan_bytes(h, cap + 1, Q, k, 0) == 0 and L.kb_query_plan_bytes(h, 5, Q, k, 3) == 0
+    assert L.kb_query_plan_bytes(h, cap + 1, Q, k, 0) == 0 and L.kb_query_plan_bytes(h, 5, Q, k, 4) == 0
     L.kb_destroy(h)
 
 
