@@ -256,14 +256,19 @@ kb_status_t kb_query_counters(const kb_t *kb, const void *workspace_dev, int64_t
  *   "small_path"    1 (default): a knowledge base of at most 16384 rows, queried with a small batch and no other knob
  *                   set, is scored whole by three launches (no sampling pass, no candidate lists); 0: always the
  *                   scan pipeline.  Both produce the same bits.
+ *   "profile_stride" of a kb_profile_begin session, every value-th scan launch is timed: launch value/2 of each run of
+ *                   `value` launches (0 or 1: every one).  A timed
+ *                   launch costs the stream about 12 us of idle time around it; a stride spreads the timed launches
+ *                   evenly over the session and keeps that cost small.
  */
 kb_status_t kb_set_tuning(kb_t *kb, const char *name, int64_t value);
 
 /*
  * Kernel timing for roofline reports.  After kb_profile_begin, each kb_query attaches a HIP event pair to the
  * dispatch of its main scan kernel (on the small-knowledge-base path an event pair is recorded around the kernel
- * that scores the rows), up to max_calls queries, 1..4096; later ones are not timed.  The pair travels with the
- * kernel's own dispatch packet, so timing a launch puts nothing between it and its neighbours on the stream.
+ * that scores the rows), up to max_calls timed queries, 1..4096; later ones are not timed (see "profile_stride"
+ * above to time every n-th query only).  The pair travels with the kernel's own dispatch packet; a timed dispatch is
+ * still preceded and followed by a few microseconds in which the stream runs nothing.
  * kb_profile_end synchronises `hip_stream`, writes the summed duration of the timed scan launches in milliseconds and
  * their number, destroys the events and stops recording.
  * Errors: KB_ERR_NULL, KB_ERR_INVALID_ARG (bad max_calls, or end without begin), KB_ERR_DEVICE.

@@ -975,6 +975,8 @@ kb_status_t kb_create(kb_t **out, int32_t d, kb_dtype_t key_dtype, int64_t capac
     h->tune_sample_keys = h->tune_config = h->tune_wg_per_cu = h->tune_no_small_path = 0;
     h->prof_events = nullptr;
     h->prof_max = h->prof_used = 0;
+    h->prof_stride = 1;
+    h->prof_seen = 0;
     *out = h;
     return KB_OK;
 }
@@ -1085,7 +1087,7 @@ kb_status_t launch_probe(kb *h, bool timed_scan, const void *queries_dev, kb_dty
     f.k = k;
     f.cand_cap = PROBE_CAP;
     const dim3 grid(nprobe, splits, Q);
-    const bool timed = timed_scan && h->prof_events && h->prof_used < h->prof_max;     // the scoring kernel stands for the scan
+    const bool timed = timed_scan && h->prof_events && h->prof_used < h->prof_max && h->prof_seen++ % h->prof_stride == h->prof_stride / 2;     // the scoring kernel stands for the scan
     if (timed && hipEventRecord(h->prof_events[2 * h->prof_used], s) != hipSuccess) return KB_ERR_DEVICE;
     switch (q8 ? KT_FP8_Q8 : (int)h->dtype) {
     case KB_F32: hipLaunchKernelGGL(probe_scan_kernel<KB_F32>, grid, dim3(256), 0, s, f, cluster_offsets_dev, n_clusters, probe_dev, nprobe, splits, lists); break;
@@ -1324,7 +1326,7 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
         a.n_tiles = ceil_div(kb->n, p.tk);
         a.tile_stride = 1;
         a.row_mul = 0;
-        const bool timed = kb->prof_events && kb->prof_used < kb->prof_max;
+        const bool timed = kb->prof_events && kb->prof_used < kb->prof_max && kb->prof_seen++ % kb->prof_stride == kb->prof_stride / 2;
         if (timed) {
             scan_timing.start = kb->prof_events[2 * kb->prof_used];
             scan_timing.stop = kb->prof_events[2 * kb->prof_used + 1];
@@ -1474,6 +1476,8 @@ kb_status_t kb_set_tuning(kb_t *kb, const char *name, int64_t value)
     } else if (!strcmp(name, "small_path")) {
         if (value > 1) return KB_ERR_INVALID_ARG;
         kb->tune_no_small_path = value == 0;
+    } else if (!strcmp(name, "profile_stride")) {       // of a profiling session, every value-th scan launch is timed, the middle one of each run of `value` (0 = every one)
+        kb->prof_stride = value > 0 ? (int)value : 1;
     } else if (!strcmp(name, "wg_per_cu")) {
         if (value > 8) return KB_ERR_INVALID_ARG;
         kb->tune_wg_per_cu = value;
@@ -1501,6 +1505,7 @@ kb_status_t kb_profile_begin(kb_t *kb, int32_t max_calls)
     kb->prof_events = static_cast<hipEvent_t *>(calloc(2 * (size_t)max_calls, sizeof(hipEvent_t)));
     if (!kb->prof_events) return KB_ERR_INVALID_ARG;
     kb->prof_max = max_calls;
+    kb->prof_seen = 0;
     for (int i = 0; i < 2 * max_calls; ++i)
         if (hipEventCreate(&kb->prof_events[i]) != hipSuccess) {
             drop_events(kb);

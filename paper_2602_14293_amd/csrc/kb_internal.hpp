@@ -19,6 +19,7 @@ struct kb {
     int64_t tune_sample_keys, tune_config, tune_wg_per_cu, tune_no_small_path;
     hipEvent_t *prof_events;   // 2 * prof_max events while profiling, else nullptr
     int prof_max, prof_used;
+    int prof_stride, prof_seen;   // every prof_stride-th scan launch of a profiling session is timed
 };
 
 namespace kbi {
