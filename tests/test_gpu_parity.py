@@ -311,3 +311,34 @@ def test_query_replays_from_a_captured_graph(T):
     mixed = W.Workload("graph replay", w.keys, w2.queries, w.k, tags=w.tags, qmask=w2.qmask)     # the last replay's inputs
     T.check_against_oracle(mixed, out_i.cpu().numpy(), out_s.cpu().numpy(), label="graph replay")
     kb.close()
+
+
+def test_scan_timing_counts_the_launches_it_times(T):
+    """kb_profile_begin / kb_profile_end: every scan launch is timed by default, every n-th (the middle one of each run
+    of n) with the "profile_stride" knob, never more than max_calls; timing changes no result."""
+    w = W.filtered(seed=9, N=40000 + 7, d=512, Q=200, k=16, centers=32)
+    kb = T.build_kb(w)
+    dev = kb.keys.device
+    queries, qmask = w.queries.to(dev).contiguous(), w.qmask.to(dev).contiguous()
+    ref_i, ref_s = kb.query(queries, w.k, qmask)
+    kb.profile_begin(16)
+    for _ in range(10):
+        gi, gs = kb.query(queries, w.k, qmask)
+    ms, n = kb.profile_end()
+    assert n == 10 and 0.0 < ms < 100.0 and torch.equal(gi, ref_i) and torch.equal(gs, ref_s)
+    kb.set_tuning("profile_stride", 4)
+    kb.profile_begin(16)
+    for _ in range(10):
+        gi, gs = kb.query(queries, w.k, qmask)
+    ms4, n4 = kb.profile_end()
+    assert n4 == 2 and 0.0 < ms4 < ms and torch.equal(gi, ref_i)         # launches 2 and 6 of 0..9
+    kb.profile_begin(1)
+    for _ in range(10):
+        kb.query(queries, w.k, qmask)
+    assert kb.profile_end()[1] == 1
+    kb.set_tuning("profile_stride", 0)
+    kb.profile_begin(4)
+    for _ in range(3):
+        kb.query(queries, w.k, qmask)
+    assert kb.profile_end()[1] == 3
+    kb.close()
