@@ -220,6 +220,7 @@ def _dense_counts(cap, tile):
     (kbmod.KB_BF16, 1024, 1 << 21, 128, 16),        # the growing knowledge base: one more row than 2^20 used to fail
     (kbmod.KB_BF16, 1024, 1 << 20, 256, 32),
     (kbmod.KB_BF16, 768, 65536, 64, 16),
+    (kbmod.KB_BF16, 512, 1 << 19, 50, 24),          # 64-row tiles below 2^18 rows, the full-line kernel above
     (kbmod.KB_BF16, 256, 3_000_001, 300, 128),
     (kbmod.KB_BF16, 64, 1 << 22, 1, 1),
     (kbmod.KB_F32, 256, 4096, 8, 8),
