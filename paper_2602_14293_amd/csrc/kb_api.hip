@@ -72,7 +72,8 @@ int scan_config_for(int key_dtype, int Q, int d, int64_t n)
     if (key_dtype == KB_FP8_E4M3 && Q > 128 && d >= 256) return 4;
     // below that size a query is bound by the latency of its launches: tiles of 64 rows (twice the workgroups, half the
     // chunks each) finish sooner: 62 against 71 us per call on 65,536 rows of 768 bf16 values with 64 queries
-    if (key_dtype == KB_BF16 && Q > 32 && Q <= 64 && n < WIDE128_MIN_ROWS) return 12;
+    // (and 64 against 70 us with 128 queries)
+    if (key_dtype == KB_BF16 && Q > 32 && Q <= 128 && n < WIDE128_MIN_ROWS) return Q <= 64 ? 12 : 16;
     return Q <= 32 ? 1 : Q <= 128 ? 2 : 3;
 }
 

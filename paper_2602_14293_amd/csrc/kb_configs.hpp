@@ -2,14 +2,15 @@
 //   TK x TQ      keys x queries per work item         WM x WN  wavefront grid inside the workgroup
 //   RBA          bytes of each key row per d-chunk    NSTAGE   chunk buffers in LDS
 //   WGPC         workgroups resident per compute unit (LDS and registers are budgeted for it)
-// (12: small tiles for knowledge bases of some ten thousand rows, where a query is bound by the latency of its
+// (12, 16: small tiles for knowledge bases of some ten thousand rows, where a query is bound by the latency of its
 //  launches and more, shorter work items finish sooner)
 #pragma once
 #define KB_SCAN_CONFIGS_BF16(X)                  \
     X(1, KB_BF16, 128, 32, 4, 1, 128, 3, 2)      \
     X(2, KB_BF16, 128, 128, 2, 2, 64, 4, 2)      \
     X(3, KB_BF16, 128, 256, 2, 2, 64, 3, 2)      \
-    X(12, KB_BF16, 64, 64, 2, 2, 128, 4, 2)
+    X(12, KB_BF16, 64, 64, 2, 2, 128, 4, 2)      \
+    X(16, KB_BF16, 64, 128, 2, 2, 128, 3, 2)
 #define KB_SCAN_CONFIGS_F32(X)                   \
     X(1, KB_F32, 128, 32, 4, 1, 128, 3, 2)       \
     X(2, KB_F32, 128, 128, 2, 2, 64, 4, 2)       \

@@ -49,7 +49,7 @@ def test_filtered_bf16_reduced(T, seed):
     assert rep.queries == 256
 
 
-@pytest.mark.parametrize("config", [3, 12, 17, 18, 19])
+@pytest.mark.parametrize("config", [3, 12, 16, 17, 18, 19])
 def test_every_large_batch_scan_kernel(T, config):
     """Each scan kernel that handles 256-query blocks (tiled, software-pipelined, full-line) gives
     the same oracle-checked result; ragged last tile, 300 queries = two query blocks, masked."""
