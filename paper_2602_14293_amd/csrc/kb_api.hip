@@ -173,15 +173,27 @@ bool choose_kernels(const kb *h, int64_t n, int32_t Q, bool draw, bool q8, Choic
 
 // Key tiles the sampling pass scores when the knowledge base has nt tiles: max(k, 8) / 512 of them (1/64 of the
 // rows up to k = 8, 1/16 at k = 32, 1/4 at k = 128), at least two samples per wanted result, at most what the
-// threshold kernel sorts and half of the tiles.  0 = no sampling pass (every entry is a candidate).  Depends on the
-// row count through nt only, and never falls as nt grows (`floor` switched off).
-int64_t sample_tiles_for(const kb *h, const ConfigInfo &sci, int64_t nt, int32_t k, bool floor)
+// threshold kernel sorts and half of the tiles.  A sampling pass of few tiles is bound by the latency of one tile, not
+// by its bytes: as long as the sample stays small (FREE_SAMPLE_BYTES of keys, a quarter of the tiles) it takes as many
+// tiles as the device runs side by side, which costs no time and thins the candidates of the main pass.
+// 0 = no sampling pass (every entry is a candidate).  Depends on the row count through nt only, and never falls as
+// nt grows (`floor` switched off).
+constexpr int64_t FREE_SAMPLE_BYTES = 32 << 20;
+int64_t sample_tiles_for(const kb *h, const ConfigInfo &sci, int64_t nt, int32_t Q, int32_t k, bool floor)
 {
     if (nt < 8) return 0;
     const int64_t kk = k > 8 ? k : 8;
     int64_t st = h->tune_sample_keys > 0 ? ceil_div(h->tune_sample_keys, sci.tk) : ceil_div(nt * kk, 512);
     const int64_t want = ceil_div(2 * (int64_t)k, sci.groups_per_tile);
     if (st < want) st = want;
+    if (h->tune_sample_keys <= 0) {
+        const int64_t nqb = ceil_div(Q, sci.tq);
+        int64_t free_tiles = (int64_t)DEVICE_CUS * sci.wg_per_cu / nqb;
+        const int64_t by_bytes = FREE_SAMPLE_BYTES / ((int64_t)sci.tk * h->d * key_bytes(h->dtype));
+        if (free_tiles > by_bytes) free_tiles = by_bytes;
+        if (free_tiles > nt / 4) free_tiles = nt / 4;
+        if (st < free_tiles) st = free_tiles;
+    }
     if (st > MAX_SAMPLE_SLOTS / sci.groups_per_tile) st = MAX_SAMPLE_SLOTS / sci.groups_per_tile;
     if (st > nt / 2) st = nt / 2;
     if (floor && st * sci.groups_per_tile < k) st = 0;
@@ -245,7 +257,7 @@ void plan_for(const kb *h, const Choice &c, int64_t n, int32_t Q, int32_t k, boo
     if (n < 1) n = 1;
     const int64_t nt = ceil_div(n, ci.tk);
 
-    const int64_t st = sample_tiles_for(h, sci, nt, k, true);
+    const int64_t st = sample_tiles_for(h, sci, nt, Q, k, true);
     p.sample_tiles = st;
     p.sample_slots = (int32_t)(st * sci.groups_per_tile);
     p.sample_keys = st * sci.tk;
@@ -330,7 +342,7 @@ void bound_sizes(const kb *h, const Choice &c, int32_t Q, int32_t k, bool draw, 
     const int64_t at_cap = ceil_div((int64_t)k * cap_nt * sci.groups_per_tile, MAX_SAMPLE_SLOTS);
     if (at_cap > expect) expect = at_cap;
     z.cand_cap = h->tune_sample_keys > 0 ? MAX_CAND_CAP : cand_cap_for(expect, true);
-    z.sample_slots = (int32_t)(sample_tiles_for(h, sci, cap_nt, k, false) * sci.groups_per_tile);
+    z.sample_slots = (int32_t)(sample_tiles_for(h, sci, cap_nt, Q, k, false) * sci.groups_per_tile);
     z.region_records = (int64_t)z.regions * REGION_CAP;
     max_into(m, z);
 }
