@@ -844,30 +844,47 @@ template <int KT> __global__ __launch_bounds__(256) void finalize_kernel(FinalAr
             seg_off[sg] = n;
             n += seg_n[sg];
         }
+        // Thread t takes positions t, t + 256, ... of the gathered list, four at a time: their loads (and, for a plain
+        // scan, the loads of 1/|k| that depend on them) are in flight together, where a loop over the segments would
+        // wait for one segment's words before asking for the next.
+        // A plain scan leaves (dot product, row): each candidate is finished here as the scan's exact test would have:
+        // the final score from the same three fp32 operations every kernel uses, no removed or out-of-range
+        // row, nothing below the threshold word.  What fails becomes a zero word, which sorts last.
+        const float iq = a.invq[q];
+        const uint64_t t64 = a.raw ? a.thr64[q] : 0ull;
+        const uint64_t *lists = a.cand + (size_t)q * a.cand_cap;
+        for (uint32_t j0 = tid; j0 < n; j0 += 4 * 256) {
+            uint64_t w[4];
+            float ik[4];
 #pragma unroll
-        for (int sg = 0; sg < CAND_SEGMENTS; ++sg)
-            for (uint32_t i = tid; i < seg_n[sg]; i += 256)
-                buf[seg_off[sg] + i] = a.cand[(size_t)q * a.cand_cap + sg * seg_cap + i];
-        __syncthreads();
-        if (a.raw) {
-            // A plain scan leaves (dot product, row): finish each candidate as the scan's exact test would have:
-            // the final score from the same three fp32 operations every kernel uses, no removed or out-of-range
-            // row, nothing below the threshold word.  What fails becomes a zero word, which sorts last.
-            const float iq = a.invq[q];
-            const uint64_t t64 = a.thr64[q];
-            for (uint32_t i = tid; i < n; i += 256) {
-                const uint64_t w = buf[i];
-                const uint32_t row = candidate_index(w);
-                uint64_t cw = 0ull;
-                if ((int64_t)row < a.n_keys) {
-                    const float ik = a.inv_norm[row];
-                    const uint64_t c = pack_candidate(final_score(raw_candidate_dot(w), ik, iq), row);
-                    if (!row_removed(ik) && c >= t64) cw = c;
+            for (int u = 0; u < 4; ++u) {
+                const uint32_t j = j0 + u * 256;
+                uint32_t sg = 0, off = 0;
+#pragma unroll
+                for (int s2 = 1; s2 < CAND_SEGMENTS; ++s2) {
+                    const bool past = j >= seg_off[s2];
+                    sg += past ? 1u : 0u;
+                    off = past ? seg_off[s2] : off;
                 }
-                buf[i] = cw;
+                w[u] = j < n ? lists[sg * seg_cap + (j - off)] : 0ull;
             }
-            __syncthreads();
+            if (a.raw) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t row = candidate_index(w[u]);
+                    ik[u] = (w[u] != 0ull && (int64_t)row < a.n_keys) ? a.inv_norm[row] : -1.0f;     // (negative: dropped below)
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint64_t c = pack_candidate(final_score(raw_candidate_dot(w[u]), ik[u], iq), candidate_index(w[u]));
+                    w[u] = (!row_removed(ik[u]) && c >= t64) ? c : 0ull;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (j0 + u * 256 < n) buf[j0 + u * 256] = w[u];
         }
+        __syncthreads();
         select_topk_desc(buf, (int)n, a.k, sc, tid, 256);
     }
     if (tid < a.k) {

@@ -11,7 +11,7 @@ struct EpiSide {               // side data of the item, in LDS
     const uint64_t *tag;       // [TK]
     const float *thrp;         // [TQ]  pre-filter on dot * inv_k
     const float *invq;         // [TQ]
-    const uint64_t *thr64;     // [TQ]  candidate words below this cannot be in the result
+    const uint64_t *thr64;     // [TQ]  candidate words below this cannot be in the result (read by the weighted selection only)
     const uint64_t *qmask;     // [TQ]
 };
 

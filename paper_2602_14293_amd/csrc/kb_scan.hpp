@@ -19,9 +19,9 @@
 // Epilogue.  The sampling pass keeps, per lane and query, the best qualifying candidate of the lane's
 // rows (one "group") and stores it; the k-th best group maximum is a valid lower bound of the k-th best
 // score.  The main pass tests dot * inv_k against a per-query pre-filter with one FMA + max per element,
-// and only blocks in which some lane passes run the exact path: final score, tag predicate, 64-bit
-// candidate compare, append to the workgroup's private record region (slot from an LDS counter, plain
-// global store).
+// and only in blocks in which some lane passes do the passing lanes apply the tag predicate and append
+// (raw dot product, row, query) to their wave's private record region (slot = the wave's running count +
+// the lane's rank, plain global store); the wave moves its records to the per-query lists itself.
 #pragma once
 #include <type_traits>
 #include "kb_epilogue.hpp"
@@ -139,8 +139,7 @@ struct ScanCfg {
     static constexpr int OFF_QMASK = OFF_THR64 + TQ * 8;
     static constexpr int OFF_INVQ = OFF_QMASK + TQ * 8;
     static constexpr int OFF_THRP = OFF_INVQ + TQ * 4;
-    static constexpr int OFF_CNT = OFF_THRP + TQ * 4;
-    static constexpr int SMEM_BYTES = OFF_CNT + 16;
+    static constexpr int SMEM_BYTES = OFF_THRP + TQ * 4;
     static constexpr int GROUPS_PER_TILE = WM * 2;
     static_assert(TK % (WM * 32) == 0 && TQ % (WN * 32) == 0, "wave tiles are made of 32x32 blocks");
     static_assert(A_BYTES % 1024 == 0 && B_BYTES % 1024 == 0, "chunk buffers are filled 1 KiB per wave instruction");
