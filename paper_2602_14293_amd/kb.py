@@ -131,6 +131,7 @@ class KnowledgeBase:
         self.tags = torch.zeros(capacity, dtype=torch.int64, device=self.device) if tagged else None
         self._workspace = None
         self._probe_workspace = None
+        self._workspace_need = {}      # (Q, k) -> kb_query_workspace_bytes: a function of the handle's settings only
         h = ctypes.c_void_p()
         _check(lib().kb_create(ctypes.byref(h), d, key_dtype, capacity, _ptr(self.keys), _ptr(self.scale),
                                _ptr(self.inv_norm), _ptr(self.tags)), "kb_create")
@@ -157,7 +158,12 @@ class KnowledgeBase:
         _check(lib().kb_normalize(self._h, _stream()), "kb_normalize")
 
     def workspace_bytes(self, Q: int, k: int) -> int:
-        return lib().kb_query_workspace_bytes(self._h, Q, k)
+        # (asked once per batch shape: the planner behind it walks every plan the handle can run, some tens of
+        # microseconds of host time that a small query would otherwise pay on every call)
+        need = self._workspace_need.get((Q, k))
+        if need is None:
+            need = self._workspace_need[(Q, k)] = lib().kb_query_workspace_bytes(self._h, Q, k)
+        return need
 
     def query(self, queries: torch.Tensor, k: int, qmask: Optional[torch.Tensor] = None,
               out_index: Optional[torch.Tensor] = None, out_score: Optional[torch.Tensor] = None):
@@ -257,6 +263,7 @@ class KnowledgeBase:
 
     def set_tuning(self, name: str, value: int):
         _check(lib().kb_set_tuning(self._h, name.encode(), value), "kb_set_tuning")
+        self._workspace_need.clear()        # the size depends on the knobs
 
     @property
     def size(self) -> int:
