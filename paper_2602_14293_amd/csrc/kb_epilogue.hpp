@@ -86,14 +86,27 @@ __device__ inline EpiRows load_rows(const EpiSide &sd, int rl0)
     return r;
 }
 
+// EXACT: the block test takes the largest dot * inv_k of the lane's elements itself (16 products) instead of the
+// product of the two maxima.  For stores whose rows have norms of one size (normalised bf16 or f32 rows) the
+// cheap bound is as good; for fp8 codes, whose norms differ by a factor of two from row to row, it lets nine
+// blocks in ten through where two in ten hold a survivor.
+template <bool EXACT>
 __device__ inline void main_block(const f32x16 &a, const EpiRows &rw, float tp, uint64_t qm, uint32_t query, const EpiSide &sd, bool filter,
                                   int64_t row0, const ScanArgs &p, Record *region, uint32_t &wave_cnt, uint32_t region_id)
 {
-    float amax = a[0];
+    bool maybe;
+    if constexpr (EXACT) {
+        float smax = a[0] * rw.ik[0];
 #pragma unroll
-    for (int i = 1; i < 16; ++i) amax = __builtin_fmaxf(amax, a[i]);
-    // some element can reach the pre-filter only if amax * ikmax does (thrp > 0); otherwise look closer
-    const bool maybe = !(__builtin_fmaf(amax, rw.ikmax, -tp) < 0.f) || !(tp > 0.f);
+        for (int i = 1; i < 16; ++i) smax = __builtin_fmaxf(smax, a[i] * rw.ik[i]);
+        maybe = !(smax < tp);       // (the survivors' mask below repeats the products as fused ones: never stricter than this)
+    } else {
+        float amax = a[0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) amax = __builtin_fmaxf(amax, a[i]);
+        // some element can reach the pre-filter only if amax * ikmax does (thrp > 0); otherwise look closer
+        maybe = !(__builtin_fmaf(amax, rw.ikmax, -tp) < 0.f) || !(tp > 0.f);
+    }
     if (__builtin_amdgcn_ballot_w64(maybe) == 0) return;
     uint32_t fail = 0;
     if (maybe) {
@@ -129,7 +142,7 @@ __device__ inline void main_block(const f32x16 &a, const EpiRows &rw, float tp, 
     }
 }
 
-template <int IB, int JB>
+template <int IB, int JB, bool EXACT = false>
 __device__ inline void main_epilogue(const f32x16 (&acc)[IB][JB], const EpiSide &sd, bool filter, int wave_row0, int ql0,
                                      int half, int64_t row0, int q0, const ScanArgs &p, Record *region, uint32_t &wave_cnt, uint32_t region_id)
 {
@@ -145,7 +158,7 @@ __device__ inline void main_epilogue(const f32x16 (&acc)[IB][JB], const EpiSide 
         const EpiRows rw = load_rows(sd, wave_row0 + ib * 32 + 4 * half);
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb)
-            main_block(acc[ib][jb], rw, thrp[jb], qm[jb], (uint32_t)(q0 + ql0 + jb * 32), sd, filter, row0, p, region, wave_cnt, region_id);
+            main_block<EXACT>(acc[ib][jb], rw, thrp[jb], qm[jb], (uint32_t)(q0 + ql0 + jb * 32), sd, filter, row0, p, region, wave_cnt, region_id);
     }
 }
 

@@ -379,7 +379,7 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
             else if (DRAW)
                 main_epilogue_draw<IB, JB>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p, my_region, wave_cnt, blockIdx.x * NW + wave);
             else
-                main_epilogue<IB, JB>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p, my_region, wave_cnt, blockIdx.x * NW + wave);
+                main_epilogue<IB, JB, C::KEY_BYTES == 1>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p, my_region, wave_cnt, blockIdx.x * NW + wave);
 #pragma unroll
             for (int ib = 0; ib < IB; ++ib)
 #pragma unroll

@@ -299,7 +299,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
             sample_epilogue<IB, JB, true>(acc, sd, filter, wm * 64, rowB, half, row0, qb * TQ, p,
                                     (int64_t)tile * C::GROUPS_PER_TILE + wm * 2 + half, sample_tile_run(p, tile, TK), TK);
         else
-            main_epilogue<IB, JB>(acc, sd, filter, wm * 64, rowB, half, row0, qb * TQ, p, my_region, wave_cnt, blockIdx.x * NW + wave);
+            main_epilogue<IB, JB, C::KEY_BYTES == 1>(acc, sd, filter, wm * 64, rowB, half, row0, qb * TQ, p, my_region, wave_cnt, blockIdx.x * NW + wave);
 #pragma unroll
         for (int ib = 0; ib < IB; ++ib)
 #pragma unroll

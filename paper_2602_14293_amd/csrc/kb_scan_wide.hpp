@@ -320,7 +320,7 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
                 sample_epilogue<IB, JB>(acc[rh], sd, filter, rh * 128 + wm * 64, qrow, half, row0, qb * TQ, p,
                                         (int64_t)tile * C::GROUPS_PER_TILE + (rh * 2 + wm) * 2 + half, tile_run, TK);
             else
-                main_epilogue<IB, JB>(acc[rh], sd, filter, rh * 128 + wm * 64, qrow, half, row0, qb * TQ, p, my_region, wave_cnt, blockIdx.x * NW + wave);
+                main_epilogue<IB, JB, F8>(acc[rh], sd, filter, rh * 128 + wm * 64, qrow, half, row0, qb * TQ, p, my_region, wave_cnt, blockIdx.x * NW + wave);
         }
     };
 
