@@ -167,20 +167,21 @@ __device__ inline void main_epilogue(const f32x16 (&acc)[IB][JB], const EpiSide 
 // more fp32 product with 1/|q| >= 0), which the threshold kernel applies: the sampling pass itself needs no
 // per-query value but the mask word.  Any qualifying entry with its exact s1 is a valid sample.
 //
-// Every element is looked at here, so the search is kept to a few instructions per element: s1 is mapped to a
-// signed integer with the same order, the element's number within the lane (5 bits) replaces its low bits, entries
+// Every element is looked at here, so the search is kept to a few instructions per element: the bits of s1 are read
+// as a signed integer (order_key below), the element's number within the lane (5 bits) replaces its low bits, entries
 // that fail the tag filter become the smallest integer, and a running integer maximum leaves the number of an
-// element whose s1 is within 2^-18 relative of the largest; that element's exact s1 is then recomputed.  Removed
+// element whose s1 is within 2^-18 relative of the largest (when that is not negative); that element's exact s1 is
+// then recomputed.  Removed
 // rows and the repeated rows of a partial tile are not told apart in the search: when one of them wins, its lane
 // records no sample for this group of rows, which is always valid (and rare).  Side data
 // of the rows is read as 16-byte pieces, four rows at a time.  (Registers are scarce here, with 128 accumulators
 // live, and a spilled register costs these kernels dearly: its reload queues behind the stream loads in flight.)
 constexpr int32_t SAMPLE_NONE = (int32_t)0x80000000;
-__device__ inline int32_t order_key(float x)        // signed integers ordered like the floats (-0 below +0)
-{
-    const int32_t b = (int32_t)as_u32(x);
-    return b ^ ((b >> 31) & 0x7fffffff);
-}
+// The integer the search compares: the bits of the float as they are.  Non-negative floats keep their order, every
+// negative one lies below them, and among negative ones the order is reversed, which costs nothing: a group whose
+// best product is negative then records another of its entries, and any qualifying entry with its exact product is a
+// valid sample (only the thresholds of queries with fewer than k positive groups could be lower than necessary).
+__device__ inline int32_t order_key(float x) { return (int32_t)as_u32(x); }
 
 // one 32x32 block: the best key of the lane's 16 elements joins `best`
 __device__ inline void sample_block(const f32x16 &a, int rl0, int id0, const EpiSide &sd, bool filter, uint32_t qm_lo, uint32_t qm_hi,
@@ -210,17 +211,22 @@ __device__ inline void sample_block(const f32x16 &a, int rl0, int id0, const Epi
     }
 }
 
-// The same search with the fewest registers: one element at a time, its side data read from LDS when it is needed
-// (32 reads per block instead of 12).  For the kernels that keep a software pipeline's fragments live across the
+// The same search with few registers: four elements at a time, their side data read from LDS when it is needed.  For the kernels that keep a software pipeline's fragments live across the
 // epilogue and have no registers to spare: there the version above spills, and loses more than it gains.
 __device__ inline void sample_block_lean(const f32x16 &a, int rl0, int id0, const EpiSide &sd, bool filter, uint64_t qm, int32_t &best)
 {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int rl = rl0 + 8 * (i >> 2) + (i & 3);
-        int32_t key = (order_key(a[i] * sd.invk[rl]) & ~31) | (id0 + i);
-        if (filter) key = (sd.tag[rl] & qm) != 0 ? key : SAMPLE_NONE;
-        best = key > best ? key : best;
+    for (int run = 0; run < 4; ++run) {         // four runs of four rows: one 16-byte read of 1/|k| each
+        const int rl = rl0 + 8 * run;
+        const f32x4 ik4 = *reinterpret_cast<const f32x4 *>(sd.invk + rl);
+        const float ik[4] = {ik4.x, ik4.y, ik4.z, ik4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int i = 4 * run + e;
+            int32_t key = (order_key(a[i] * ik[e]) & ~31) | (id0 + i);
+            if (filter) key = (sd.tag[rl + e] & qm) != 0 ? key : SAMPLE_NONE;
+            best = key > best ? key : best;
+        }
     }
 }
 
