@@ -224,7 +224,10 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
         const int64_t tile_run = SAMPLE ? sample_tile_run(p, ld_tile, TK) : 0;
 #pragma unroll
         for (int j = 0; j < LA; ++j) {
-            const int r = ldA_row + j * RSTEP_A;
+            int r = ldA_row + j * RSTEP_A;
+            // (opaque in a sampling pass: the tile-independent part of the scattered-row arithmetic would otherwise be kept
+            // per lane and load across the items, in registers that end up spilled)
+            if constexpr (SAMPLE) asm volatile("" : "+v"(r));
             if constexpr (SAMPLE) offA[j] = (uint64_t)sample_row(p, tile_run, ld_tile, TK, r) * key_row_bytes + ldA_piece;
             else offA[j] = (uint32_t)(r < last ? r : last) * key_row_bytes + ldA_piece;
         }
@@ -302,7 +305,11 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
             if (tid < TK) {
                 int64_t r = tile * tstride * TK + tid;
                 r = r < p.n_keys ? r : p.n_keys - 1;
-                if constexpr (SAMPLE) r = sample_row(p, sample_tile_run(p, tile, TK), tile, TK, tid);
+                if constexpr (SAMPLE) {
+                    int rl = tid;
+                    asm volatile("" : "+v"(rl));
+                    r = sample_row(p, sample_tile_run(p, tile, TK), tile, TK, rl);
+                }
                 my_invk = p.inv_norm[r];
                 if (filter) my_tag = p.tags[r];
             }

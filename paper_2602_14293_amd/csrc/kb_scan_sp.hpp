@@ -139,7 +139,11 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
         const int64_t tile_run = (SAMPLE && role == 0) ? sample_tile_run(p, ld_tile, TK) : 0;
 #pragma unroll
         for (int j = 0; j < LC; ++j) {
-            const int r = ld_row + j * ld_rstep;
+            int r = ld_row + j * ld_rstep;
+            // (a sampling pass maps r to a scattered row with some 64-bit arithmetic whose first part does not depend on
+            // the tile: computed once per lane and load and kept across the items, those values are spilled and each
+            // reload waits for every stream load in flight; r is therefore opaque here and the map is computed per tile)
+            if constexpr (SAMPLE) asm volatile("" : "+v"(r));
             if (SAMPLE && role == 0) off[j] = (Off)((uint64_t)sample_row(p, tile_run, ld_tile, TK, r) * row_bytes + ld_piece);
             else off[j] = (uint32_t)(r < last ? r : last) * row_bytes + ld_piece;
         }
@@ -153,14 +157,22 @@ __global__ __launch_bounds__(512, 1) void kb_scan_sp_kernel(ScanArgs p)
         if (wave < 4) {
             int64_t r = row0 + wave * 64 + lane;
             r = r < p.n_keys ? r : p.n_keys - 1;
-            if constexpr (SAMPLE) r = sample_row(p, tile_run, ld_tile, TK, wave * 64 + lane);
+            if constexpr (SAMPLE) {
+                int rl = wave * 64 + lane;
+                asm volatile("" : "+v"(rl));
+                r = sample_row(p, tile_run, ld_tile, TK, rl);
+            }
             __builtin_amdgcn_global_load_lds((const void *)(p.inv_norm + r), (lds_ptr)(aux + C::AUX_INVK + wave * 256), 4, 0, 0);
         }
         if (filter) {
             // tags as dwords: wave w covers dwords [64w, 64w+64) = rows [32w, 32w+32)
             int64_t r = row0 + wave * 32 + (lane >> 1);
             r = r < p.n_keys ? r : p.n_keys - 1;
-            if constexpr (SAMPLE) r = sample_row(p, tile_run, ld_tile, TK, wave * 32 + (lane >> 1));
+            if constexpr (SAMPLE) {
+                int rl = wave * 32 + (lane >> 1);
+                asm volatile("" : "+v"(rl));
+                r = sample_row(p, tile_run, ld_tile, TK, rl);
+            }
             __builtin_amdgcn_global_load_lds((const void *)(reinterpret_cast<const uint32_t *>(p.tags + r) + (lane & 1)),
                                              (lds_ptr)(aux + C::AUX_TAG + wave * 256), 4, 0, 0);
         }
