@@ -381,7 +381,7 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
                 sample_epilogue_draw<IB, JB>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p,
                                              (int64_t)tile * C::GROUPS_PER_TILE + wm * 2 + half, sample_tile_run(p, tile, TK), TK);
             else if (SAMPLE)
-                sample_epilogue<IB, JB>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p,
+                sample_epilogue<IB, JB, (IB * JB >= 8)>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p,      // (128 accumulators: the search that needs few registers)
                                         (int64_t)tile * C::GROUPS_PER_TILE + wm * 2 + half, sample_tile_run(p, tile, TK), TK);
             else if (DRAW)
                 main_epilogue_draw<IB, JB>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p, my_region, wave_cnt, blockIdx.x * NW + wave);
