@@ -3,6 +3,7 @@
 // column lrow and key rows 8*(i/4) + 4*half + (i%4), i = 0..15.
 #pragma once
 #include "kb_internal.hpp"
+#include <utility>
 
 namespace kbi {
 
@@ -13,6 +14,7 @@ struct EpiSide {               // side data of the item, in LDS
     const float *invq;         // [TQ]
     const uint64_t *thr64;     // [TQ]  candidate words below this cannot be in the result (read by the weighted selection only)
     const uint64_t *qmask;     // [TQ]
+    const float *lgain = nullptr;   // [TK]  ln(gain) of the tile's rows (weighted random selection only)
 };
 
 __device__ inline float select16(const f32x16 &a, int i)
@@ -292,10 +294,16 @@ __device__ inline void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t k0, uint
 }
 
 // Standard Gumbel variate from one generator word: U = (upper 23 bits + 1/2) / 2^23 (exact in fp32), G = -ln(-ln U).
+// Both logarithms are the hardware's base-2 logarithm times ln 2: U and -ln U are normal numbers (2^-24 <= U < 1,
+// 6e-8 <= -ln U <= 16.7), so the library logarithm's handling of denormals and its extended-precision product (three
+// quarters of this function's instructions) buy nothing.  Over all 2^23 values of U the result is within 1.7e-6 of
+// the exact variate and non-decreasing in U.
 __device__ inline float gumbel_of_word(uint32_t w)
 {
+    constexpr float LN2 = 0.6931471805599453f;
     const float u = __builtin_fmaf((float)(w >> 9), 0x1p-23f, 0x1p-24f);
-    return -__logf(-__logf(u));
+    const float l1 = __builtin_amdgcn_logf(u) * LN2;
+    return -(__builtin_amdgcn_logf(-l1) * LN2);
 }
 
 // Key of one (query, entry) pair.  Entries 4j .. 4j+3 share one generator call (counter (j, query, 0, 0)); the word
@@ -304,12 +312,16 @@ __device__ inline float draw_key(float score, float log_gain, float gumbel, floa
 {
     return (__builtin_fmaf(score, inv_t, log_gain) + gumbel) + 0.0f;
 }
-__device__ inline float draw_key_of(float score, const DrawArgs &dr, uint32_t query, int64_t row)
+__device__ inline float draw_key_of(float score, float log_gain, const DrawArgs &dr, uint32_t query, int64_t row)
 {
     uint32_t w[4];
     philox4x32_10((uint32_t)(row >> 2), query, dr.seed_lo, dr.seed_hi, w);
     const uint32_t word = (row & 3) == 0 ? w[0] : (row & 3) == 1 ? w[1] : (row & 3) == 2 ? w[2] : w[3];
-    return draw_key(score, dr.log_gain[row], gumbel_of_word(word), dr.inv_t);
+    return draw_key(score, log_gain, gumbel_of_word(word), dr.inv_t);
+}
+__device__ inline float draw_key_of(float score, const DrawArgs &dr, uint32_t query, int64_t row)
+{
+    return draw_key_of(score, dr.log_gain[row], dr, query, row);
 }
 
 // Keys of the 16 elements a lane holds in one block (four runs of four consecutive rows: four generator calls).
@@ -317,7 +329,7 @@ __device__ inline float draw_key_of(float score, const DrawArgs &dr, uint32_t qu
 // knowledge base).
 template <bool SAMPLED>
 __device__ inline void block_keys(const f32x16 &a, const EpiRows &rw, float iq, const ScanArgs &p, uint32_t query, int64_t row0,
-                                  float (&key)[16], int64_t tile_run = 0, int tk = 0)
+                                  const EpiSide &sd, float (&key)[16], int64_t tile_run = 0, int tk = 0)
 {
     const DrawArgs &dr = p.draw;
 #pragma unroll
@@ -326,7 +338,7 @@ __device__ inline void block_keys(const f32x16 &a, const EpiRows &rw, float iq, 
         const int64_t first = SAMPLED ? (int64_t)sample_index(p, tile_run, row0, tk, rw.rl0 + 8 * run) : logical;
         uint32_t w[4];
         philox4x32_10((uint32_t)(first >> 2), query, dr.seed_lo, dr.seed_hi, w);
-        const f32x4 lg = *reinterpret_cast<const f32x4 *>(dr.log_gain + first);
+        const f32x4 lg = *reinterpret_cast<const f32x4 *>(sd.lgain + rw.rl0 + 8 * run);
         const float lgs[4] = {lg.x, lg.y, lg.z, lg.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -336,53 +348,91 @@ __device__ inline void block_keys(const f32x16 &a, const EpiRows &rw, float iq, 
     }
 }
 
-// Main pass on keys.  There is no cheap bound on a key (the noise is unbounded), so every element's key is
-// computed and compared with the query's threshold key; survivors are then handled exactly like the survivors
-// of the score pass (their keys are recomputed: same inputs, same bits).
+// The largest generator word (its upper 23 bits, as an integer) with which an element whose noise-free part is at
+// most xmax still has a key below the threshold key tp; -1 if there is none.  The noise is a non-decreasing function
+// of those bits and the two additions of draw_key are monotone, so every element of the block with bits at or below
+// the returned value fails "key >= tp" however its own key rounds.  The value is found from the inverse of the
+// Gumbel transform with a margin (fast exponentials, 2 % on the inner one, two steps on the integer) and then checked
+// with the very operations of draw_key; a value that fails the check is replaced by a more careful one, then by -1.
+__device__ inline int noise_floor(float xmax, float tp)
+{
+    if (!(tp > -__builtin_inff())) return -1;
+    float t = __expf(xmax - tp) * 1.02f;       // e^-c, c = the noise an element at xmax needs
+    int m = -1;
+#pragma unroll 1
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        const float mf = __builtin_fmaf(__expf(-t), 0x1p23f, -2.0f);
+        const int cand = mf >= 0.f ? (int)__builtin_fminf(mf, 8388607.f) : -1;
+        if (cand < 0) break;
+        const float key = (xmax + gumbel_of_word((uint32_t)cand << 9)) + 0.0f;
+        if (key < tp) {
+            m = cand;
+            break;
+        }
+        t *= 8.f;
+    }
+    return m;
+}
+
+// Main pass on keys.  Computing a key costs a generator call per four elements and two logarithms per element; the
+// test against the query's threshold key does not need them: with the largest noise-free part of the lane's 16
+// elements, noise_floor gives the generator word below which no element of the block can pass, and the per-element
+// test is one integer compare on the generator's output.  What passes (the elements whose key can reach the
+// threshold, and as many again) is handled like the survivors of the score pass, each lane walking its own
+// elements, with the exact key and the exact tests.
 __device__ inline void main_block_draw(const f32x16 &a, const EpiRows &rw, float tp, int ql, const EpiSide &sd, bool filter,
                                        int64_t row0, int q0, const ScanArgs &p, Record *region, uint32_t &wave_cnt, uint32_t region_id)
 {
+    const DrawArgs &dr = p.draw;
     const float iq = sd.invq[ql];
-    const uint32_t query = p.draw.first_query + (uint32_t)(q0 + ql);
-    float key[16];
-    block_keys<false>(a, rw, iq, p, query, row0, key);
+    const uint32_t query = dr.first_query + (uint32_t)(q0 + ql);
+    float xmax = -__builtin_inff();
+#pragma unroll
+    for (int run = 0; run < 4; ++run) {
+        const f32x4 lg = *reinterpret_cast<const f32x4 *>(sd.lgain + rw.rl0 + 8 * run);
+        const float lgs[4] = {lg.x, lg.y, lg.z, lg.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            xmax = __builtin_fmaxf(xmax, __builtin_fmaf(final_score(a[4 * run + e], rw.ik[4 * run + e], iq), dr.inv_t, lgs[e]));
+    }
+    const int floor_m = noise_floor(xmax, tp);
+    const uint32_t floor_w = floor_m < 0 ? 0u : ((uint32_t)floor_m << 9) | 0x1ffu;
     uint32_t pass = 0;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) pass = (pass << 1) | (key[i] >= tp && key[i] > -__builtin_inff() ? 1u : 0u);   // element i at bit 15 - i
-    uint64_t lanes = __builtin_amdgcn_ballot_w64(pass != 0);
-    if (lanes == 0) return;
+    for (int run = 0; run < 4; ++run) {
+        uint32_t w[4];
+        philox4x32_10((uint32_t)((row0 + rw.rl0 + 8 * run) >> 2), query, dr.seed_lo, dr.seed_hi, w);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pass = (pass << 1) | (w[e] > floor_w ? 1u : 0u);       // element i at bit 15 - i
+    }
+    if (floor_m < 0) pass = 0xffffu;
+    if (__builtin_amdgcn_ballot_w64(pass != 0) == 0) return;
     const uint64_t t64 = sd.thr64[ql];
     const uint64_t qm = filter ? sd.qmask[ql] : 0ull;
     do {
-        uint32_t m = (uint32_t)__builtin_amdgcn_readlane((int)pass, __builtin_ctzll(lanes));
-        const uint32_t mine = pass & m;
-        pass &= ~m;
-        do {
-            const int b = 31 - __builtin_clz(m);
-            m &= ~(1u << b);
-            const int i = 15 - b;                               // wave-uniform
-            const bool has = (mine >> b) & 1u;
-            const int rl = rw.rl0 + 8 * (i >> 2) + (i & 3);
-            const int64_t row = row0 + rl;
-            const float ik = sd.invk[rl];
-            const float kv = draw_key_of(final_score(a[i], ik, iq), p.draw, query, row);
-            const uint64_t cw = pack_candidate(kv, (uint32_t)row);
-            bool ok = has && row < p.n_keys && kv > -__builtin_inff() && cw >= t64 && !row_removed(ik);
-            if (filter) ok = ok && (sd.tag[rl] & qm) != 0;
-            const uint64_t okm = __builtin_amdgcn_ballot_w64(ok);
-            if (okm != 0 && wave_cnt + 64 > (uint32_t)p.region_cap) flush_records(p, region, wave_cnt, region_id);
-            if (ok) {
-                const uint32_t pos = wave_cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(okm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)okm, 0u));
-                Record rec;
-                rec.cand = cw;
-                rec.query = (uint32_t)(q0 + ql);
-                rec.pad = 0;
-                region[pos] = rec;
-            }
-            wave_cnt += (uint32_t)__builtin_popcountll(okm);
-        } while (m != 0);
-        lanes = __builtin_amdgcn_ballot_w64(pass != 0);
-    } while (lanes != 0);
+        const bool has = pass != 0;
+        const int b = 31 - __builtin_clz(has ? pass : 1u);
+        pass &= ~(1u << b);
+        const int i = 15 - b;
+        const int rl = rw.rl0 + 8 * (i >> 2) + (i & 3);
+        const int64_t row = row0 + rl;
+        const float ik = sd.invk[rl];
+        const float kv = draw_key_of(final_score(select16(a, i), ik, iq), sd.lgain[rl], dr, query, row);
+        const uint64_t cw = pack_candidate(kv, (uint32_t)row);
+        bool ok = has && row < p.n_keys && kv > -__builtin_inff() && cw >= t64 && !row_removed(ik);
+        if (filter) ok = ok && (sd.tag[rl] & qm) != 0;
+        const uint64_t okm = __builtin_amdgcn_ballot_w64(ok);
+        if (okm != 0 && wave_cnt + 64 > (uint32_t)p.region_cap) flush_records(p, region, wave_cnt, region_id);
+        if (ok) {
+            const uint32_t pos = wave_cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(okm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)okm, 0u));
+            Record rec;
+            rec.cand = cw;
+            rec.query = (uint32_t)(q0 + ql);
+            rec.pad = 0;
+            region[pos] = rec;
+        }
+        wave_cnt += (uint32_t)__builtin_popcountll(okm);
+    } while (__builtin_amdgcn_ballot_w64(pass != 0) != 0);
 }
 
 template <int IB, int JB>
@@ -398,38 +448,56 @@ __device__ inline void main_epilogue_draw(const f32x16 (&acc)[IB][JB], const Epi
     }
 }
 
-// Sampling pass on keys: per lane and query column the qualifying entry with the largest key.
+// Sampling pass on keys: per lane and query column the qualifying entry with the largest key.  One function per
+// query column of the wave's tile, expanded at compile time: as a loop over the columns the body (eight generator
+// calls and 32 keys per column) is too large to be unrolled, and the accumulators, indexed by a loop counter, would
+// live in scratch memory.
+template <int IB, int JB, int JBX>
+__device__ inline void sample_column_draw(const f32x16 (&acc)[IB][JB], const EpiSide &sd, bool filter, int wave_row0, int ql0,
+                                          int half, int64_t row0, int q0, const ScanArgs &p, int64_t slot, int64_t tile_run, int tk)
+{
+    const int ql = ql0 + JBX * 32;
+    const float iq = sd.invq[ql];
+    const uint64_t qm = filter ? sd.qmask[ql] : 0ull;
+    const uint32_t query = p.draw.first_query + (uint32_t)(q0 + ql);
+    float best = -__builtin_inff();
+    int best_rl = -1;
+#pragma unroll
+    for (int ib = 0; ib < IB; ++ib) {
+        // (the row number is opaque per block: otherwise the side data and the scattered-row arithmetic of all the
+        // wave's rows, which do not depend on the column, are kept in registers across the columns and spilled)
+        int rl0 = wave_row0 + ib * 32 + 4 * half;
+        asm volatile("" : "+v"(rl0));
+        const EpiRows rw = load_rows(sd, rl0);
+        float key[16];
+        block_keys<true>(acc[ib][JBX], rw, iq, p, query, row0, sd, key, tile_run, tk);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int rl = rw.rl0 + 8 * (i >> 2) + (i & 3);
+            bool ok = row0 + rl < p.n_keys && key[i] > best && !row_removed(rw.ik[i]);
+            if (filter) ok = ok && (sd.tag[rl] & qm) != 0;
+            if (ok) {
+                best = key[i];
+                best_rl = rl;
+            }
+        }
+    }
+    if (q0 + ql < p.Q)
+        p.samp[sample_slot_index(slot, p.sample_group_shift, p.qpad, q0 + ql)] = best_rl >= 0 ? pack_candidate(best, sample_index(p, tile_run, row0, tk, best_rl)) : 0ull;
+}
+
+template <int IB, int JB, int... JBX>
+__device__ inline void sample_columns_draw(const f32x16 (&acc)[IB][JB], const EpiSide &sd, bool filter, int wave_row0, int ql0, int half, int64_t row0,
+                                           int q0, const ScanArgs &p, int64_t slot, int64_t tile_run, int tk, std::integer_sequence<int, JBX...>)
+{
+    (sample_column_draw<IB, JB, JBX>(acc, sd, filter, wave_row0, ql0, half, row0, q0, p, slot, tile_run, tk), ...);
+}
+
 template <int IB, int JB>
 __device__ inline void sample_epilogue_draw(const f32x16 (&acc)[IB][JB], const EpiSide &sd, bool filter, int wave_row0, int ql0,
                                             int half, int64_t row0, int q0, const ScanArgs &p, int64_t slot, int64_t tile_run, int tk)
 {
-#pragma unroll
-    for (int jb = 0; jb < JB; ++jb) {
-        const int ql = ql0 + jb * 32;
-        const float iq = sd.invq[ql];
-        const uint64_t qm = filter ? sd.qmask[ql] : 0ull;
-        const uint32_t query = p.draw.first_query + (uint32_t)(q0 + ql);
-        float best = -__builtin_inff();
-        int best_rl = -1;
-#pragma unroll
-        for (int ib = 0; ib < IB; ++ib) {
-            const EpiRows rw = load_rows(sd, wave_row0 + ib * 32 + 4 * half);
-            float key[16];
-            block_keys<true>(acc[ib][jb], rw, iq, p, query, row0, key, tile_run, tk);
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int rl = rw.rl0 + 8 * (i >> 2) + (i & 3);
-                bool ok = row0 + rl < p.n_keys && key[i] > best && !row_removed(rw.ik[i]);
-                if (filter) ok = ok && (sd.tag[rl] & qm) != 0;
-                if (ok) {
-                    best = key[i];
-                    best_rl = rl;
-                }
-            }
-        }
-        if (q0 + ql < p.Q)
-            p.samp[sample_slot_index(slot, p.sample_group_shift, p.qpad, q0 + ql)] = best_rl >= 0 ? pack_candidate(best, sample_index(p, tile_run, row0, tk, best_rl)) : 0ull;
-    }
+    sample_columns_draw<IB, JB>(acc, sd, filter, wave_row0, ql0, half, row0, q0, p, slot, tile_run, tk, std::make_integer_sequence<int, JB>{});
 }
 
 }  // namespace kbi

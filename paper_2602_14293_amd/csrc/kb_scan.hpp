@@ -139,7 +139,8 @@ struct ScanCfg {
     static constexpr int OFF_QMASK = OFF_THR64 + TQ * 8;
     static constexpr int OFF_INVQ = OFF_QMASK + TQ * 8;
     static constexpr int OFF_THRP = OFF_INVQ + TQ * 4;
-    static constexpr int SMEM_BYTES = OFF_THRP + TQ * 4;
+    static constexpr int OFF_LGAIN = OFF_THRP + TQ * 4;
+    static constexpr int SMEM_BYTES = OFF_LGAIN + TK * 4;
     static constexpr int GROUPS_PER_TILE = WM * 2;
     static_assert(TK % (WM * 32) == 0 && TQ % (WN * 32) == 0, "wave tiles are made of 32x32 blocks");
     static_assert(A_BYTES % 1024 == 0 && B_BYTES % 1024 == 0, "chunk buffers are filled 1 KiB per wave instruction");
@@ -193,6 +194,7 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
     uint64_t *aux_thr64 = reinterpret_cast<uint64_t *>(smem + C::OFF_THR64);
     uint64_t *aux_qmask = reinterpret_cast<uint64_t *>(smem + C::OFF_QMASK);
     float *aux_invq = reinterpret_cast<float *>(smem + C::OFF_INVQ);
+    float *aux_lgain = reinterpret_cast<float *>(smem + C::OFF_LGAIN);
 
     // items: (tile, qb) with qb fastest
     const int nqb = p.nqb;
@@ -285,7 +287,7 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
     int tile = vb / nqb, qb = vb % nqb;
     int c = 0, stage = 0;
     // per-item side data, fetched into registers while the item's last chunks are computed
-    float my_invk = 0.f, my_invq = 0.f;
+    float my_invk = 0.f, my_invq = 0.f, my_lgain = 0.f;
     uint64_t my_tag = 0, my_thr64 = 0, my_qmask = 0;
     float my_thrp = __builtin_inff();
     const int aux_chunk = NC >= 2 ? NC - 2 : 0;
@@ -312,6 +314,7 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
                 }
                 my_invk = p.inv_norm[r];
                 if (filter) my_tag = p.tags[r];
+                if constexpr (DRAW) my_lgain = p.draw.log_gain[r];
             }
             if (tid < TQ) {
                 const int q = qb * TQ + tid;            // < qpad: invq, thr64 and thrp are padded arrays
@@ -366,6 +369,7 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
             if (tid < TK) {
                 aux_invk[tid] = my_invk;
                 aux_tag[tid] = my_tag;
+                if constexpr (DRAW) aux_lgain[tid] = my_lgain;
             }
             if (tid < TQ) {
                 aux_invq[tid] = my_invq;
@@ -376,7 +380,7 @@ __global__ __launch_bounds__(C::THREADS, C::WGPC) void kb_scan_kernel(ScanArgs p
             __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
             bare_barrier();
             const int64_t row0 = SAMPLE ? sample_row0(p, tile, TK) : tile * tstride * TK;
-            const EpiSide sd{aux_invk, aux_tag, reinterpret_cast<const float *>(smem + C::OFF_THRP), aux_invq, aux_thr64, aux_qmask};
+            const EpiSide sd{aux_invk, aux_tag, reinterpret_cast<const float *>(smem + C::OFF_THRP), aux_invq, aux_thr64, aux_qmask, aux_lgain};
             if (SAMPLE && DRAW)
                 sample_epilogue_draw<IB, JB>(acc, sd, filter, rowA - lrow, rowB, half, row0, qb * TQ, p,
                                              (int64_t)tile * C::GROUPS_PER_TILE + wm * 2 + half, sample_tile_run(p, tile, TK), TK);
