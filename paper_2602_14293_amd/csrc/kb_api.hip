@@ -155,8 +155,10 @@ bool choose_kernels(const kb *h, int64_t n, int32_t Q, bool draw, bool q8, Choic
         c.config = h->tune_config > 0 ? (int)h->tune_config : scan_config_for(h->dtype, Q, h->d, n);
         if (!scan_config_info(h->dtype, c.config, &c.ci)) return false;
         // fall back where a (forced) configuration does not apply: the weighted random selection exists in the
-        // tiled kernel only, rows may be too short for a pipelined kernel, and the fp8-query kernels read fp8 queries
-        if ((draw && c.ci.family != 0) || row_bytes < (size_t)c.ci.min_row_bytes || (h->dtype == KB_FP8_E4M3 && is_fp8_query_config(c.config))) {
+        // tiled kernel and in the main pass of the bf16 full-line kernel, rows may be too short for a pipelined kernel,
+        // and the fp8-query kernels read fp8 queries
+        const bool draws = c.ci.family == 0 || (c.ci.family == 4 && h->dtype == KB_BF16);
+        if ((draw && !draws) || row_bytes < (size_t)c.ci.min_row_bytes || (h->dtype == KB_FP8_E4M3 && is_fp8_query_config(c.config))) {
             c.config = generic;
             if (!scan_config_info(h->dtype, c.config, &c.ci)) return false;
         }
@@ -166,6 +168,10 @@ bool choose_kernels(const kb *h, int64_t n, int32_t Q, bool draw, bool q8, Choic
     if (c.ci.family == 4 && h->dtype == KB_FP8_E4M3) {       // the fp8 full-line kernel is a main pass only
         c.sample_config = FP8_QUERY_CONFIG;
         if (!scan_config_info(h->dtype, c.sample_config, &c.sci) || c.sci.tq != c.ci.tq || c.sci.tk != c.ci.tk) return false;
+    }
+    if (draw && c.ci.family == 4) {     // so is the full-line kernel on keys: the tiled kernel with the same query blocks samples
+        c.sample_config = c.ci.tq == 128 ? 2 : 3;
+        if (!scan_config_info(h->dtype, c.sample_config, &c.sci) || c.sci.tq != c.ci.tq || c.sci.family != 0) return false;
     }
     *out = c;
     return true;
@@ -255,13 +261,14 @@ void plan_for(const kb *h, const Choice &c, int64_t n, int32_t Q, int32_t k, boo
     p.sample_family = sci.family;
     p.sample_wgpc = sci.wg_per_cu;
     if (n < 1) n = 1;
-    const int64_t nt = ceil_div(n, ci.tk);
+    const int64_t nt = ceil_div(n, ci.tk), nts = ceil_div(n, sci.tk);     // key tiles of the main pass, of the sampling pass
 
-    const int64_t st = sample_tiles_for(h, sci, nt, Q, k, true);
+    const int64_t st = sample_tiles_for(h, sci, nts, Q, k, true);
+    p.sample_tk = sci.tk;
     p.sample_tiles = st;
     p.sample_slots = (int32_t)(st * sci.groups_per_tile);
     p.sample_keys = st * sci.tk;
-    const int64_t expect = st > 0 ? ceil_div((int64_t)k * nt, st) : nt * ci.tk;      // candidates per query
+    const int64_t expect = st > 0 ? ceil_div((int64_t)k * nts, st) : nt * ci.tk;      // candidates per query
     p.cand_cap = cand_cap_for(expect, st > 0);
 
     const int wgpc = h->tune_wg_per_cu > 0 ? (int)h->tune_wg_per_cu : ci.wg_per_cu;
@@ -315,9 +322,12 @@ void max_into(Sizes &m, const Sizes &z)
     if (z.lgain_rows > m.lgain_rows) m.lgain_rows = z.lgain_rows;
 }
 
-// Upper bound of the Sizes of plan_for(h, c, n, ...) over every n in [1, capacity].
-//   Up to EXACT_TILES key tiles the plans are enumerated (one per tile count; this range contains every case without
-//   a sampling pass: sample_tiles_for gives at least min(2k / groups, nt / 2) tiles, which is k samples once nt >= 256).
+// Upper bound of the Sizes of plan_for(h, c, n, ...) over every n in [1, capacity].  nt counts the key tiles of the
+// sampling configuration (its tiles may be lower than the main pass's; both counts are constant between multiples of
+// the lower tile height).
+//   Up to EXACT_TILES key tiles the plans are enumerated (one per pair of tile counts; this range contains every case
+//   without a sampling pass: sample_tiles_for gives at least min(2k / groups, nt / 2) tiles, which is k samples once
+//   nt >= 256).
 //   Beyond, with st = sample_tiles_for(nt) > 0 and expect = ceil(k nt / st):
 //     st = ceil(nt max(k, 8) / 512), or raised to 2k / groups:  expect <= 512
 //     st = nt / 2 (rounded down):                               expect <= 2k + 1 <= 257
@@ -328,11 +338,12 @@ constexpr int64_t EXACT_TILES = 256;
 void bound_sizes(const kb *h, const Choice &c, int32_t Q, int32_t k, bool draw, Sizes &m)
 {
     const ConfigInfo &ci = c.ci, &sci = c.sci;
-    const int64_t cap_nt = ceil_div(h->capacity, ci.tk);
+    const int64_t step = ci.tk < sci.tk ? ci.tk : sci.tk;
+    const int64_t cap_nt = ceil_div(h->capacity, sci.tk);
     Plan p;
     Sizes z;
-    for (int64_t nt = 1; nt <= cap_nt && nt <= EXACT_TILES; ++nt) {
-        plan_for(h, c, nt * ci.tk, Q, k, draw, &p, &z);
+    for (int64_t n = step; n < h->capacity + step && ceil_div(n, sci.tk) <= EXACT_TILES; n += step) {
+        plan_for(h, c, n, Q, k, draw, &p, &z);
         max_into(m, z);
     }
     plan_for(h, c, h->capacity, Q, k, draw, &p, &z);       // the ln(gain) array, and the largest grid
@@ -1310,7 +1321,7 @@ static kb_status_t run_query(kb_t *kb, const void *queries_dev, kb_dtype_t q_dty
             // the sample is spread evenly over the knowledge base: a prefix says nothing about later rows when
             // the rows are grouped (by state, by cluster, by age)
             a.n_tiles = p.sample_tiles;
-            a.tile_stride = (int32_t)(ceil_div(kb->n, p.tk) / p.sample_tiles);
+            a.tile_stride = (int32_t)(ceil_div(kb->n, p.sample_tk) / p.sample_tiles);
             // ... row by row where the kernel can gather (the two-phase and register-tile kernels load whole tiles:
             // they take every tile_stride-th tile instead)
             a.row_run_shift = draw ? 2 : 0;

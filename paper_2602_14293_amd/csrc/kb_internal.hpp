@@ -103,7 +103,7 @@ struct Plan {
     int family;                         // which kernel family the configuration belongs to (ConfigInfo::family)
     int32_t tk;                         // keys per tile
     int32_t groups_per_tile;            // sample groups per key tile
-    int32_t sample_config, sample_family, sample_wgpc;   // the sampling pass may use another scan configuration
+    int32_t sample_config, sample_family, sample_wgpc, sample_tk;   // the sampling pass may use another scan configuration (and tile height)
     int64_t sample_tiles;               // key tiles (of the sampling configuration) scored by the sampling pass (0 = none)
     int64_t sample_keys;                // rows they cover
     int32_t sample_slots;               // sample_tiles * groups_per_tile, per query

@@ -64,7 +64,8 @@ template <int KT_, int TQ_, bool QF8_ = false> struct WideCfg {
     // side data of a key tile, two copies (item parity)
     static constexpr int AUX_INVK = 0;                       // float  [TK]
     static constexpr int AUX_TAG = AUX_INVK + TK * 4;        // uint64 [TK]
-    static constexpr int AUX_BYTES = AUX_TAG + TK * 8;
+    static constexpr int AUX_LGAIN = AUX_TAG + TK * 8;       // float  [TK]  (weighted random selection only)
+    static constexpr int AUX_BYTES = AUX_LGAIN + TK * 4;
     // side data of a query block, one copy
     static constexpr int QAUX_THRP = 0;                      // float  [TQ]
     static constexpr int QAUX_INVQ = QAUX_THRP + TQ * 4;     // float  [TQ]
@@ -83,9 +84,10 @@ template <int KT_, int TQ_, bool QF8_ = false> struct WideCfg {
     static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget");
 };
 
-template <class C, bool SAMPLE>
+template <class C, bool SAMPLE, bool DRAW = false>
 __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
 {
+    static_assert(!DRAW || (!SAMPLE && !C::QF8), "keys of the weighted random selection: main pass, bf16");
     constexpr int TK = C::TK, TQ = C::TQ, RB = C::RB, IB = C::IB, JB = C::JB, NW = C::NW, PB = C::PIECE_BYTES;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     // LDS addresses are kept as 32-bit pointers of the LDS address space: arithmetic on them is one scalar add, where a
@@ -190,6 +192,11 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
             const uint32_t r = (uint32_t)(ridx * 64 + lane);
             const unsigned char *g = uniform_address(p.inv_norm + row0);
             __builtin_amdgcn_global_load_lds((const void *)(g + (r < last ? r : last) * 4u), (lds_ptr)(aux + C::AUX_INVK + ridx * 256), 4, 0, 0);
+        }
+        if constexpr (DRAW) {
+            const uint32_t r = (uint32_t)(ridx * 64 + lane);
+            const unsigned char *g = uniform_address(p.draw.log_gain + row0);
+            __builtin_amdgcn_global_load_lds((const void *)(g + (r < last ? r : last) * 4u), (lds_ptr)(aux + C::AUX_LGAIN + ridx * 256), 4, 0, 0);
         }
         if (filter) {
             const unsigned char *g = uniform_address(p.tags + row0);
@@ -311,7 +318,8 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
         const unsigned char *aux = smem + C::OFF_AUX + par * C::AUX_BYTES, *qaux = smem + C::OFF_QAUX;
         const EpiSide sd{reinterpret_cast<const float *>(aux + C::AUX_INVK), reinterpret_cast<const uint64_t *>(aux + C::AUX_TAG),
                          reinterpret_cast<const float *>(qaux + C::QAUX_THRP), reinterpret_cast<const float *>(qaux + C::QAUX_INVQ),
-                         reinterpret_cast<const uint64_t *>(qaux + C::QAUX_THR64), reinterpret_cast<const uint64_t *>(qaux + C::QAUX_QMASK)};
+                         reinterpret_cast<const uint64_t *>(qaux + C::QAUX_THR64), reinterpret_cast<const uint64_t *>(qaux + C::QAUX_QMASK),
+                         reinterpret_cast<const float *>(aux + C::AUX_LGAIN)};
         const int64_t row0 = SAMPLE ? sample_row0(p, tile, TK) : (int64_t)tile * TK;
         const int64_t tile_run = SAMPLE ? sample_tile_run(p, tile, TK) : 0;
 #pragma unroll
@@ -319,6 +327,8 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
             if constexpr (SAMPLE)       // sampling groups: (piece, wave row, lane half) = 32 rows each
                 sample_epilogue<IB, JB>(acc[rh], sd, filter, rh * 128 + wm * 64, qrow, half, row0, qb * TQ, p,
                                         (int64_t)tile * C::GROUPS_PER_TILE + (rh * 2 + wm) * 2 + half, tile_run, TK);
+            else if constexpr (DRAW)
+                main_epilogue_draw<IB, JB>(acc[rh], sd, filter, rh * 128 + wm * 64, qrow, half, row0, qb * TQ, p, my_region, wave_cnt, blockIdx.x * NW + wave);
             else
                 main_epilogue<IB, JB, F8>(acc[rh], sd, filter, rh * 128 + wm * 64, qrow, half, row0, qb * TQ, p, my_region, wave_cnt, blockIdx.x * NW + wave);
         }
@@ -559,10 +569,13 @@ __global__ __launch_bounds__(512, 1) void kb_scan_wide_kernel(ScanArgs p)
 
 template <class C> hipError_t launch_scan_wide_cfg(bool sample, int grid, const ScanArgs &a, hipStream_t s)
 {
-    static LdsAllowed allowed[2];
-    if (C::QF8 && sample) return hipErrorInvalidValue;     // fp8: the sampling pass runs the 64-byte-piece kernel (fewer registers)
-    auto *fn = (sample && !C::QF8) ? &kb_scan_wide_kernel<C, C::QF8 ? false : true> : &kb_scan_wide_kernel<C, false>;
-    if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(fn), allowed[sample], C::SMEM_BYTES); e != hipSuccess) return e;
+    static LdsAllowed allowed[3];
+    const bool draw = a.draw.enabled != 0;
+    if (C::QF8 && (sample || draw)) return hipErrorInvalidValue;     // fp8: the sampling pass runs the 64-byte-piece kernel (fewer registers)
+    if (draw && sample) return hipErrorInvalidValue;                 // keys of the weighted random selection: main pass only
+    auto *fn = (sample && !C::QF8) ? &kb_scan_wide_kernel<C, C::QF8 ? false : true>
+               : (draw && !C::QF8) ? &kb_scan_wide_kernel<C, false, C::QF8 ? false : true> : &kb_scan_wide_kernel<C, false>;
+    if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(fn), allowed[draw ? 2 : sample], C::SMEM_BYTES); e != hipSuccess) return e;
     hipExtLaunchKernelGGL(fn, dim3(grid), dim3(C::THREADS), C::SMEM_BYTES, s, scan_timing.start, scan_timing.stop, 0, a);
     return hipGetLastError();
 }
