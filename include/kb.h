@@ -254,7 +254,7 @@ kb_status_t kb_query_counters(const kb_t *kb, const void *workspace_dev, int64_t
  *   "scan_config"   tile configuration of the scan kernel (0 = automatic)
  *   "wg_per_cu"     resident scan workgroups per compute unit (0 = automatic)
  *   "small_path"    1 (default): a knowledge base of at most 16384 rows, queried with a small batch and no other knob
- *                   set, is scored whole by three launches (no sampling pass, no candidate lists); 0: always the
+ *                   set, is scored whole by two launches (no sampling pass, no candidate lists); 0: always the
  *                   scan pipeline.  Both produce the same bits.
  *   "profile_stride" of a kb_profile_begin session, every value-th scan launch is timed: launch value/2 of each run of
  *                   `value` launches (0 or 1: every one).  A timed

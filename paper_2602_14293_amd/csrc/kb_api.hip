@@ -707,7 +707,7 @@ struct FinalArgs {
 constexpr int KT_FP8_Q8 = 3;
 typedef int i32x8 __attribute__((ext_vector_type(8)));
 template <int KT> __device__ void exhaustive_query(const FinalArgs &a, int q, uint64_t *buf, uint32_t *ctl, SelectScratch *sc, int64_t row_begin,
-                                                   int64_t row_end)
+                                                   int64_t row_end, const float *inv_q = nullptr)
 {
     constexpr bool Q8 = KT == KT_FP8_Q8;
     constexpr int KTT = Q8 ? (int)KB_FP8_E4M3 : KT;
@@ -716,7 +716,7 @@ template <int KT> __device__ void exhaustive_query(const FinalArgs &a, int q, ui
     const int cap = a.cand_cap;
     const bool filter = a.qmask != nullptr;
     const uint64_t qm = filter ? a.qmask[q] : 0;
-    const float iq = a.invq[q];
+    const float iq = inv_q ? *inv_q : a.invq[q];
     const size_t key_row_bytes = (size_t)a.d * KEY_BYTES;
     const unsigned char *qrow = static_cast<const unsigned char *>(a.queries) + (size_t)q * a.d * QRY_BYTES;
     const int n_groups = (int)(key_row_bytes / (Q8 ? 64 : 32));
@@ -911,27 +911,23 @@ template <int KT> __global__ __launch_bounds__(256) void finalize_kernel(FinalAr
 constexpr int PROBE_CAP = 1024;        // LDS candidate buffer of a partial scan (words); k <= 128 fits eight times
 constexpr int PROBE_MAX_LISTS = 64;    // partial lists per query that the merge can take: 64 x 128 = MAX_CAND_CAP words
 
-template <int QT> __global__ __launch_bounds__(256) void probe_prep_kernel(const void *queries, int Q, int d, float *invq, uint64_t *stats, uint64_t blocks)
-{
-    // stats (optional): the diagnostics of a query that took this path: no candidates, no sampling, `blocks` workgroups
-    if (stats && blockIdx.x == 0 && threadIdx.x < STAT_WORDS + STAT_PARTIALS) stats[threadIdx.x] = threadIdx.x == 3 ? blocks : 0ull;
-    const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row < Q) {
-        const float inv = row_inv_norm<QT>(queries, row, d * (QT == KB_F32 ? 4 : QT == KB_BF16 ? 2 : 1), lane);
-        if (lane == 0) invq[row] = inv;
-    }
-}
-
 // Block (p, s, q): part s of `splits` of the rows of cluster probe[q][p], scored exactly as the scan kernels score
 // (same MFMA sequence per element), best k written as a sorted list of candidate words (zero = no entry).
 // Without cluster_offsets the one "cluster" is the whole knowledge base (the path of small knowledge bases).
+// Every block computes 1/|q| of its query itself (one wavefront, the row-norm routine every path uses: the same bits),
+// which saves the launch that would do it once per query: these calls are bound by the latency of their launches.
+// stats (optional): the diagnostics of a query that took this path: no candidates, no sampling, one workgroup per block.
 template <int KT> __global__ __launch_bounds__(256) void probe_scan_kernel(FinalArgs a, const int64_t *cluster_offsets, int n_clusters,
-                                                                         const int32_t *probe, int nprobe, int splits, uint64_t *lists)
+                                                                         const int32_t *probe, int nprobe, int splits, uint64_t *lists, uint64_t *stats)
 {
+    constexpr int QT = KT == KB_F32 ? (int)KB_F32 : KT == KT_FP8_Q8 ? (int)KB_FP8_E4M3 : (int)KB_BF16;     // type of the queries
     __shared__ __attribute__((aligned(16))) uint64_t buf[PROBE_CAP];
     __shared__ uint32_t ctl[4];
     __shared__ SelectScratch sc;
+    __shared__ float inv_q;
     const int p = blockIdx.x, s = blockIdx.y, q = blockIdx.z, tid = threadIdx.x;
+    if (stats && p == 0 && s == 0 && q == 0 && tid < STAT_WORDS + STAT_PARTIALS)
+        stats[tid] = tid == 3 ? (uint64_t)gridDim.x * gridDim.y * gridDim.z : 0ull;
     uint64_t *out = lists + ((size_t)q * nprobe * splits + (size_t)p * splits + s) * a.k;
     const int c = cluster_offsets ? probe[(size_t)q * nprobe + p] : 0;
     bool first = true;          // a cluster named twice is scanned once (the merge takes distinct entries)
@@ -949,7 +945,12 @@ template <int KT> __global__ __launch_bounds__(256) void probe_scan_kernel(Final
         if (tid < a.k) out[tid] = 0ull;
         return;
     }
-    exhaustive_query<KT>(a, q, buf, ctl, &sc, begin, end);
+    if (tid < 64) {
+        const float inv = row_inv_norm<QT>(a.queries, q, a.d * (QT == KB_F32 ? 4 : QT == KB_BF16 ? 2 : 1), tid);
+        if (tid == 0) inv_q = inv;
+    }
+    __syncthreads();
+    exhaustive_query<KT>(a, q, buf, ctl, &sc, begin, end, &inv_q);
     if (tid < a.k) out[tid] = buf[tid];
 }
 
@@ -1103,21 +1104,12 @@ bool make_probe_plan(int32_t Q, int32_t k, int32_t nprobe, ProbePlan *out)
 }
 
 
-// The three launches behind kb_query_probe; also the whole pipeline of kb_query on a small knowledge base
+// The two launches behind kb_query_probe; also the whole pipeline of kb_query on a small knowledge base
 // (cluster_offsets == nullptr: one "cluster" = every row, nprobe = 1, `stats` zeroed for kb_query_counters).
 kb_status_t launch_probe(kb *h, bool timed_scan, const void *queries_dev, kb_dtype_t q_dtype, bool q8, int32_t Q, const uint64_t *qmask_dev, int32_t k,
                          const int64_t *cluster_offsets_dev, int32_t n_clusters, const int32_t *probe_dev, int32_t nprobe, int splits, float *invq,
                          uint64_t *lists, uint64_t *stats, int32_t *indices_out_dev, float *scores_out_dev, hipStream_t s)
 {
-    const int pgrid = (Q + 3) / 4;
-    const uint64_t blocks = (uint64_t)nprobe * splits * Q;
-    if (q_dtype == KB_F32)
-        hipLaunchKernelGGL(probe_prep_kernel<KB_F32>, dim3(pgrid), dim3(256), 0, s, queries_dev, Q, h->d, invq, stats, blocks);
-    else if (q_dtype == KB_BF16)
-        hipLaunchKernelGGL(probe_prep_kernel<KB_BF16>, dim3(pgrid), dim3(256), 0, s, queries_dev, Q, h->d, invq, stats, blocks);
-    else
-        hipLaunchKernelGGL(probe_prep_kernel<KB_FP8_E4M3>, dim3(pgrid), dim3(256), 0, s, queries_dev, Q, h->d, invq, stats, blocks);
-
     FinalArgs f;
     memset(&f, 0, sizeof f);
     f.keys = h->keys;
@@ -1134,10 +1126,10 @@ kb_status_t launch_probe(kb *h, bool timed_scan, const void *queries_dev, kb_dty
     const bool timed = timed_scan && h->prof_events && h->prof_used < h->prof_max && h->prof_seen++ % h->prof_stride == h->prof_stride / 2;     // the scoring kernel stands for the scan
     if (timed && hipEventRecord(h->prof_events[2 * h->prof_used], s) != hipSuccess) return KB_ERR_DEVICE;
     switch (q8 ? KT_FP8_Q8 : (int)h->dtype) {
-    case KB_F32: hipLaunchKernelGGL(probe_scan_kernel<KB_F32>, grid, dim3(256), 0, s, f, cluster_offsets_dev, n_clusters, probe_dev, nprobe, splits, lists); break;
-    case KB_BF16: hipLaunchKernelGGL(probe_scan_kernel<KB_BF16>, grid, dim3(256), 0, s, f, cluster_offsets_dev, n_clusters, probe_dev, nprobe, splits, lists); break;
-    case KB_FP8_E4M3: hipLaunchKernelGGL(probe_scan_kernel<KB_FP8_E4M3>, grid, dim3(256), 0, s, f, cluster_offsets_dev, n_clusters, probe_dev, nprobe, splits, lists); break;
-    default: hipLaunchKernelGGL(probe_scan_kernel<KT_FP8_Q8>, grid, dim3(256), 0, s, f, cluster_offsets_dev, n_clusters, probe_dev, nprobe, splits, lists); break;
+    case KB_F32: hipLaunchKernelGGL(probe_scan_kernel<KB_F32>, grid, dim3(256), 0, s, f, cluster_offsets_dev, n_clusters, probe_dev, nprobe, splits, lists, stats); break;
+    case KB_BF16: hipLaunchKernelGGL(probe_scan_kernel<KB_BF16>, grid, dim3(256), 0, s, f, cluster_offsets_dev, n_clusters, probe_dev, nprobe, splits, lists, stats); break;
+    case KB_FP8_E4M3: hipLaunchKernelGGL(probe_scan_kernel<KB_FP8_E4M3>, grid, dim3(256), 0, s, f, cluster_offsets_dev, n_clusters, probe_dev, nprobe, splits, lists, stats); break;
+    default: hipLaunchKernelGGL(probe_scan_kernel<KT_FP8_Q8>, grid, dim3(256), 0, s, f, cluster_offsets_dev, n_clusters, probe_dev, nprobe, splits, lists, stats); break;
     }
     if (timed) {
         if (hipEventRecord(h->prof_events[2 * h->prof_used + 1], s) != hipSuccess) return KB_ERR_DEVICE;
@@ -1152,7 +1144,7 @@ kb_status_t launch_probe(kb *h, bool timed_scan, const void *queries_dev, kb_dty
     return hipGetLastError() == hipSuccess ? KB_OK : KB_ERR_DEVICE;
 }
 
-// A small knowledge base is scored whole by the same three launches: parts of 128 or 256 rows (one or two steps of the scorer), no
+// A small knowledge base is scored whole by the same two launches: parts of 128 or 256 rows (one or two steps of the scorer), no
 // sampling pass, no candidate lists.  Same scores, same order: results do not depend on which path ran.
 constexpr int64_t SMALL_ROWS = 16384;
 constexpr int SMALL_BLOCKS = 1024;
