@@ -240,6 +240,17 @@ kb_status_t kb_compact(kb_t *src, kb_t *dst, const float *gain_src_dev, float *g
                        void *workspace_dev, size_t workspace_bytes, void *hip_stream, int64_t *live_out);
 
 /*
+ * Self-check of a property the main pass of kb_query_sampled relies on (Section 3, Optimization Selector: the
+ * weighted random choice): it rejects most (query, entry) pairs by comparing the random generator's word with a bound,
+ * without computing the pair's key, which is exact as long as the noise G = -ln(-ln U) that the device computes is a
+ * non-decreasing function of the 23 bits of the word that make U.  The call enqueues on `hip_stream` a kernel that
+ * evaluates G for all 2^23 values and writes out_dev[0] = values whose G is below that of the value before (0 on a
+ * device the library is valid for), out_dev[1] = values looked at (2^23).  `out_dev`: device memory, 2 x int64, the
+ * caller's; read it after synchronising the stream.  Errors: KB_ERR_NULL, KB_ERR_DEVICE.
+ */
+kb_status_t kb_check_draw_noise(int64_t *out_dev, void *hip_stream);
+
+/*
  * Diagnostics of the most recent kb_query that used `workspace_dev`: synchronises `hip_stream`, then copies
  * out[0] = candidates that passed the threshold filter (all queries), out[1] = queries resolved by the
  * exhaustive per-query path, out[2] = keys scored by the sampling pass, out[3] = workgroups of the scan (a query

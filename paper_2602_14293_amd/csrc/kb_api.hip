@@ -1500,6 +1500,34 @@ kb_status_t kb_query_counters(const kb_t *kb, const void *workspace_dev, int64_t
     return KB_OK;
 }
 
+namespace {
+// out[0]: values m of the generator word's upper 23 bits whose variate is below that of m - 1; out[1]: values looked at
+__global__ __launch_bounds__(256) void draw_noise_check_kernel(unsigned long long *out)
+{
+    const uint32_t m = blockIdx.x * 256u + threadIdx.x;      // < 2^23
+    const bool falls = m > 0 && gumbel_of_word(m << 9) < gumbel_of_word((m - 1) << 9);
+    const unsigned long long bad = __builtin_amdgcn_ballot_w64(falls);
+    if ((threadIdx.x & 63) == 0) {
+        if (bad) atomicAdd(out, (unsigned long long)__builtin_popcountll(bad));
+        atomicAdd(out + 1, 64ull);
+    }
+}
+__global__ void zero_words_kernel(unsigned long long *out, int n)
+{
+    if ((int)threadIdx.x < n) out[threadIdx.x] = 0ull;
+}
+}  // namespace
+
+kb_status_t kb_check_draw_noise(int64_t *out_dev, void *hip_stream)
+{
+    if (!out_dev) return KB_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    unsigned long long *out = reinterpret_cast<unsigned long long *>(out_dev);
+    hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(64), 0, s, out, 2);
+    hipLaunchKernelGGL(draw_noise_check_kernel, dim3((1u << 23) / 256), dim3(256), 0, s, out);
+    return hipGetLastError() == hipSuccess ? KB_OK : KB_ERR_DEVICE;
+}
+
 kb_status_t kb_set_tuning(kb_t *kb, const char *name, int64_t value)
 {
     if (!kb || !name) return KB_ERR_NULL;

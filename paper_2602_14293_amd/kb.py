@@ -70,6 +70,8 @@ def lib() -> ctypes.CDLL:
         L.kb_quantize_rows.argtypes = [vp, i32, i64, i32, vp, vp, vp]
         L.kb_query_sampled.restype = i32
         L.kb_query_sampled.argtypes = [vp, vp, i32, i32, vp, i32, vp, ctypes.c_float, ctypes.c_uint64, i32, vp, vp, vp, sz, vp]
+        L.kb_check_draw_noise.restype = i32
+        L.kb_check_draw_noise.argtypes = [vp, vp]
         L.kb_query_counters.restype = i32
         L.kb_query_counters.argtypes = [vp, vp, ctypes.POINTER(i64), vp]
         L.kb_set_tuning.restype = i32
@@ -117,6 +119,14 @@ def update_gain(gain: torch.Tensor, indices: torch.Tensor, values: torch.Tensor,
     assert gain.is_contiguous() and indices.is_contiguous() and values.is_contiguous() and indices.numel() == values.numel()
     _check(lib().kb_update_gain(_ptr(gain), gain.numel(), _ptr(indices), _ptr(values), indices.numel(), ctypes.c_float(alpha),
                                 _stream()), "kb_update_gain")
+
+
+def check_draw_noise():
+    """kb_check_draw_noise: (generator values whose noise falls below the previous value's, values looked at)."""
+    out = torch.empty(2, dtype=torch.int64, device="cuda")
+    _check(lib().kb_check_draw_noise(_ptr(out), _stream()), "kb_check_draw_noise")
+    torch.cuda.synchronize()
+    return int(out[0]), int(out[1])
 
 
 class KnowledgeBase:

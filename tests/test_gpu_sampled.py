@@ -155,3 +155,10 @@ def test_full_line_and_tiled_main_pass_draw_the_same(T, N, d, Q, k, tiled):
     torch.cuda.synchronize()
     kb.close()
     assert np.array_equal(ti.cpu().numpy(), gi) and np.array_equal(tk.cpu().numpy().view(np.uint32), gk.view(np.uint32))
+
+
+def test_the_noise_is_monotone_in_the_generator_word():
+    # the main pass rejects pairs by an integer compare on the generator's word; exact only if the device's
+    # -ln(-ln U) never falls as U grows: all 2^23 values
+    falls, looked_at = kbmod.check_draw_noise()
+    assert looked_at == 1 << 23 and falls == 0

@@ -190,6 +190,7 @@ def test_tuning_knobs(L):
     assert L.kb_set_tuning(h, b"wg_per_cu", 2) == 0 and L.kb_set_tuning(h, b"wg_per_cu", 64) == 2
     assert L.kb_set_tuning(h, b"small_path", 0) == 0 and L.kb_set_tuning(h, b"small_path", 1) == 0 and L.kb_set_tuning(h, b"small_path", 2) == 2
     assert L.kb_set_tuning(h, b"nonsense", 1) == 2 and L.kb_set_tuning(h, None, 1) == 1
+    assert L.kb_check_draw_noise(None, None) == 1                                    # nowhere to write the result
     L.kb_destroy(h)
 
 
