@@ -139,19 +139,21 @@ def test_draw_on_rows_grouped_by_cluster(T):
     assert rep.queries == 40 and cnt["exhaustive_queries"] == 0
 
 
-@pytest.mark.parametrize("N,d,Q,k,tiled", [(30000 + 3, 512, 300, 32, 3), ((1 << 18) + 77, 256, 100, 16, 2)])
-def test_full_line_and_tiled_main_pass_draw_the_same(T, N, d, Q, k, tiled):
+@pytest.mark.parametrize("N,d,Q,k,tiled,masked", [(30000 + 3, 512, 300, 32, 3, True), ((1 << 18) + 77, 256, 100, 16, 2, True),
+                                                  (1000, 256, 200, 8, 3, False), (70000 + 129, 1024, 256, 32, 3, False)])
+def test_full_line_and_tiled_main_pass_draw_the_same(T, N, d, Q, k, tiled, masked):
     # large batches run the main pass of the draw in the full-line kernel (256-query blocks, and 128-query blocks
     # from 2^18 rows on) behind a sampling pass of the tiled kernel with lower tiles; forced onto the tiled kernel
     # the same call returns the same bits (the keys are the same fp32 operations everywhere), and the first agrees
     # with the oracle
-    w = W.filtered(seed=N % 1000, N=N, d=d, Q=Q, k=k, centers=32)
+    w = W.filtered(seed=N % 1000, N=N, d=d, Q=Q, k=k, centers=32) if masked else W.clustered(seed=N % 1000, N=N, d=d, Q=Q, k=k, centers=32)
     gain = _gains(w.N, 8, zero_every=13)
     rep, cnt, gi, gk, keys = _run(T, w, gain, 0.05, seed=4242, label=f"draw, full-line main pass Q={Q}")
     assert rep.queries == Q and cnt["exhaustive_queries"] == 0
     kb = T.build_kb(w)
     kb.set_tuning("scan_config", tiled)
-    ti, tk = kb.query_sampled(w.queries.cuda().contiguous(), w.k, torch.from_numpy(gain).cuda(), 0.05, 4242, w.qmask.cuda())
+    qm = w.qmask.cuda() if masked else None
+    ti, tk = kb.query_sampled(w.queries.cuda().contiguous(), w.k, torch.from_numpy(gain).cuda(), 0.05, 4242, qm)
     torch.cuda.synchronize()
     kb.close()
     assert np.array_equal(ti.cpu().numpy(), gi) and np.array_equal(tk.cpu().numpy().view(np.uint32), gk.view(np.uint32))
