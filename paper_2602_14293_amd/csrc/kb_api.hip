@@ -467,91 +467,145 @@ template <int QT> __global__ __launch_bounds__(256) void prep_kernel(const void 
 // ------------------------------------------------------------------------------------------------
 // A full sort is a chain of dependent LDS round trips (one per stage) and costs tens of microseconds for a
 // few thousand words.  Selection needs far fewer: a most-significant-digit radix search for the k-th
-// largest word (8-bit digits, starting at the highest bit in which the words differ at all; each pass is
-// one histogram with LDS atomics and one wavefront-wide suffix scan), then the survivors are compacted
-// and ordered by counting, for each, how many survivors are larger.  Zero words are padding: they are
+// largest word (8-bit digits, starting at the highest bit in which the words' upper halves differ; each pass is
+// one histogram with LDS atomics and one wavefront-wide scan), then the survivors are compacted
+// and ordered by counting, for each, how many survivors are larger.  The selection runs in kernels whose whole
+// length is a few microseconds, so its own fixed costs count: the reductions and scans across lanes are
+// data-parallel-primitive moves (a shuffle is an LDS round trip each), the wavefronts exchange their partial
+// results through LDS without atomics, and a pass has two barriers.  Zero words are padding: they are
 // never selected, and if fewer than k words are nonzero the result is zero-padded.
 struct SelectScratch {
     uint64_t sel[KB_K_MAX];
     uint32_t hist[256];
-    uint32_t ctl[16];      // 0 nonzero words, 1 selected, 2 digit found, 3 still needed, 4 words in that bin, 8..11 AND / OR
+    uint32_t part[16][4];  // per wavefront: its nonzero words, AND and OR of their upper halves
+    uint32_t ctl[8];       // 1 selected, 2 digit found, 3 still needed, 4 words in that bin
 };
 
 __device__ inline uint64_t shr64(uint64_t v, int s) { return s >= 64 ? 0ull : v >> s; }
 
-// buf[0..n) in, buf[0..k) out (the rest of buf is left as it was).  All threads of the workgroup call it.
+// Cross-lane steps as data-parallel-primitive moves (one vector instruction each, no LDS round trip): `x` of the lane
+// `shr` places down its row of 16, or lane 15 / 31 of the rows before (row_bcast), or `idle` where there is none.
+template <int CTRL, int ROW_MASK> __device__ inline uint32_t dpp_or(uint32_t idle, uint32_t x)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)idle, (int)x, CTRL, ROW_MASK, 0xf, false);
+}
+// Inclusive scans over the 64 lanes of a (fully active) wavefront; lane 63 ends up with the total.
+__device__ inline uint32_t wave_scan_add(uint32_t x)
+{
+    x += dpp_or<0x111, 0xf>(0u, x);
+    x += dpp_or<0x112, 0xf>(0u, x);
+    x += dpp_or<0x114, 0xf>(0u, x);
+    x += dpp_or<0x118, 0xf>(0u, x);
+    x += dpp_or<0x142, 0xa>(0u, x);
+    x += dpp_or<0x143, 0xc>(0u, x);
+    return x;
+}
+__device__ inline uint32_t wave_scan_and(uint32_t x)
+{
+    x &= dpp_or<0x111, 0xf>(~0u, x);
+    x &= dpp_or<0x112, 0xf>(~0u, x);
+    x &= dpp_or<0x114, 0xf>(~0u, x);
+    x &= dpp_or<0x118, 0xf>(~0u, x);
+    x &= dpp_or<0x142, 0xa>(~0u, x);
+    x &= dpp_or<0x143, 0xc>(~0u, x);
+    return x;
+}
+__device__ inline uint32_t wave_scan_or(uint32_t x)
+{
+    x |= dpp_or<0x111, 0xf>(0u, x);
+    x |= dpp_or<0x112, 0xf>(0u, x);
+    x |= dpp_or<0x114, 0xf>(0u, x);
+    x |= dpp_or<0x118, 0xf>(0u, x);
+    x |= dpp_or<0x142, 0xa>(0u, x);
+    x |= dpp_or<0x143, 0xc>(0u, x);
+    return x;
+}
+
+// buf[0..n) in, buf[0..k) out (the rest of buf is left as it was).  All threads of the workgroup call it (at most 16
+// wavefronts), converged.
 __device__ inline void select_topk_desc(uint64_t *buf, int n, int k, SelectScratch *sc, int tid, int nthreads)
 {
-    const int lane = tid & 63;
-    if (tid < 16) sc->ctl[tid] = (tid == 8 || tid == 9) ? 0xffffffffu : 0u;
-    __syncthreads();
+    const int lane = tid & 63, wave = tid >> 6, nwaves = nthreads >> 6;
+    // ---- how many words there are, and the highest bit in which their upper halves differ ----
     {
-        uint32_t cnt = 0, alo = ~0u, ahi = ~0u, olo = 0u, ohi = 0u;
+        uint32_t cnt = 0, ahi = ~0u, ohi = 0u;
         for (int i = tid; i < n; i += nthreads) {
             const uint64_t e = buf[i];
             if (e != 0) {
                 ++cnt;
-                alo &= (uint32_t)e;
                 ahi &= (uint32_t)(e >> 32);
-                olo |= (uint32_t)e;
                 ohi |= (uint32_t)(e >> 32);
             }
         }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            cnt += __shfl_xor(cnt, o, 64);
-            alo &= __shfl_xor(alo, o, 64);
-            ahi &= __shfl_xor(ahi, o, 64);
-            olo |= __shfl_xor(olo, o, 64);
-            ohi |= __shfl_xor(ohi, o, 64);
+        cnt = wave_scan_add(cnt);
+        ahi = wave_scan_and(ahi);
+        ohi = wave_scan_or(ohi);
+        if (lane == 63) {
+            sc->part[wave][0] = cnt;
+            sc->part[wave][1] = ahi;
+            sc->part[wave][2] = ohi;
         }
-        if (lane == 0) {
-            atomicAdd(&sc->ctl[0], cnt);
-            atomicAnd(&sc->ctl[8], alo);
-            atomicAnd(&sc->ctl[9], ahi);
-            atomicOr(&sc->ctl[10], olo);
-            atomicOr(&sc->ctl[11], ohi);
-        }
+        for (int i = tid; i < 256; i += nthreads) sc->hist[i] = 0u;
+        if (tid == 0) sc->ctl[1] = 0u;
     }
     __syncthreads();
-    const int nz = (int)sc->ctl[0];
+    uint32_t nz, all_and, all_or;
+    {
+        // every wavefront adds the wavefronts' parts up for itself: lanes 0..15 take one each, lane 15 gets the totals
+        const int w = lane & 15;
+        const bool have = w < nwaves;
+        uint32_t c = have ? sc->part[w][0] : 0u, a = have ? sc->part[w][1] : ~0u, o = have ? sc->part[w][2] : 0u;
+        c += dpp_or<0x111, 0xf>(0u, c);
+        c += dpp_or<0x112, 0xf>(0u, c);
+        c += dpp_or<0x114, 0xf>(0u, c);
+        c += dpp_or<0x118, 0xf>(0u, c);
+        a &= dpp_or<0x111, 0xf>(~0u, a);
+        a &= dpp_or<0x112, 0xf>(~0u, a);
+        a &= dpp_or<0x114, 0xf>(~0u, a);
+        a &= dpp_or<0x118, 0xf>(~0u, a);
+        o |= dpp_or<0x111, 0xf>(0u, o);
+        o |= dpp_or<0x112, 0xf>(0u, o);
+        o |= dpp_or<0x114, 0xf>(0u, o);
+        o |= dpp_or<0x118, 0xf>(0u, o);
+        nz = (uint32_t)__builtin_amdgcn_readlane((int)c, 15);
+        all_and = (uint32_t)__builtin_amdgcn_readlane((int)a, 15);
+        all_or = (uint32_t)__builtin_amdgcn_readlane((int)o, 15);
+    }
     // selected words: nonzero and (word >> shift) >= pref
     int shift = 0;
     uint64_t pref = 1;
-    if (nz > k) {
-        const uint64_t all_and = ((uint64_t)sc->ctl[9] << 32) | sc->ctl[8], all_or = ((uint64_t)sc->ctl[11] << 32) | sc->ctl[10];
-        const uint64_t diff = all_and ^ all_or;              // nonzero: the words are distinct
-        int hi = diff ? 64 - __builtin_clzll(diff) : 0;      // bits [hi, 64) are decided and equal pref
-        pref = shr64(all_or, hi);
+    if ((int)nz > k) {
+        const uint32_t diff = all_and ^ all_or;              // (the lower halves, row numbers, differ anyway)
+        int hi = diff ? 64 - __builtin_clz(diff) : 32;       // bits [hi, 64) are decided and equal pref
+        pref = hi >= 64 ? 0ull : (uint64_t)(all_or >> (hi - 32));
         uint32_t need = (uint32_t)k;
         for (int pass = 0; pass < 9 && hi > 0; ++pass) {
             const int width = hi < 8 ? hi : 8, lo = hi - width;
-            for (int i = tid; i < 256; i += nthreads) sc->hist[i] = 0u;
-            __syncthreads();
             for (int i = tid; i < n; i += nthreads) {
                 const uint64_t e = buf[i];
                 if (e != 0 && shr64(e, hi) == pref) atomicAdd(&sc->hist[(uint32_t)(e >> lo) & ((1u << width) - 1u)], 1u);
             }
             __syncthreads();
             if (tid < 64) {
-                // suffix sums over the 256 bins, four bins per lane: the bin in which the need-th largest word lies
-                const uint32_t c0 = sc->hist[4 * lane], c1 = sc->hist[4 * lane + 1], c2 = sc->hist[4 * lane + 2], c3 = sc->hist[4 * lane + 3];
+                // lane l owns bins 4 (63 - l) .. + 3, so the scan over the lanes counts the words in higher bins; it
+                // clears its bins for the next pass
+                const int base = 4 * (63 - lane);
+                const uint32_t c0 = sc->hist[base], c1 = sc->hist[base + 1], c2 = sc->hist[base + 2], c3 = sc->hist[base + 3];
+                sc->hist[base] = 0u;
+                sc->hist[base + 1] = 0u;
+                sc->hist[base + 2] = 0u;
+                sc->hist[base + 3] = 0u;
                 const uint32_t mine = c0 + c1 + c2 + c3;
-                uint32_t suffix = mine;
-#pragma unroll
-                for (int o = 1; o < 64; o <<= 1) {
-                    const uint32_t v = __shfl_down(suffix, o, 64);
-                    if (lane + o < 64) suffix += v;
-                }
-                uint32_t above = suffix - mine;
-                if (suffix >= need && above < need) {
+                const uint32_t incl = wave_scan_add(mine);
+                uint32_t above = incl - mine;
+                if (incl >= need && above < need) {
                     const uint32_t c[4] = {c0, c1, c2, c3};
                     int bin = 0;
                     uint32_t in_bin = 0;
 #pragma unroll
                     for (int j = 3; j >= 0; --j) {
                         if (in_bin == 0 && above + c[j] >= need) {
-                            bin = 4 * lane + j;
+                            bin = base + j;
                             in_bin = c[j];
                         } else if (in_bin == 0) {
                             above += c[j];
@@ -583,6 +637,7 @@ __device__ inline void select_topk_desc(uint64_t *buf, int n, int k, SelectScrat
         if (t < m) {
             const uint64_t e = sc->sel[t];
             int rank = 0;
+#pragma unroll 8
             for (int j = 0; j < m; ++j) rank += sc->sel[j] > e;
             buf[rank] = e;
         } else {
