@@ -755,7 +755,7 @@ struct FinalArgs {
     uint64_t *fb_lists;       // [Q][fb_parts][k] their partial results
     int32_t fb_parts;
     const uint64_t *thr64;    // [Q] threshold words of the scan
-    int32_t raw;              // the lists hold raw dot products (plain queries), not finished candidate words
+    int32_t raw;              // the lists hold dot * inv_k products (plain queries), not finished candidate words
 };
 
 // KT = KT_FP8_Q8 stands for fp8 keys with fp8 queries (one fp8 matrix instruction per 64-byte chunk, as in the scan).
@@ -876,6 +876,20 @@ template <int KT> __global__ __launch_bounds__(256) void finalize_kernel(FinalAr
     uint32_t *ctl = reinterpret_cast<uint32_t *>(smem_raw + sizeof(uint64_t) * a.cand_cap);
     SelectScratch *sc = reinterpret_cast<SelectScratch *>(smem_raw + sizeof(uint64_t) * a.cand_cap + 16);
     const int q = blockIdx.x, part = blockIdx.y, tid = threadIdx.x;
+    // (the segment counters are asked for together with the flag: one memory round trip instead of two on the path
+    // of every query; the parts that turn out to have nothing to do have read 64 bytes in vain)
+    uint32_t seg_cnt[CAND_SEGMENTS];
+    {
+        const u32x4 *cp = reinterpret_cast<const u32x4 *>(a.cnt + (size_t)q * CAND_SEGMENTS);
+#pragma unroll
+        for (int v = 0; v < CAND_SEGMENTS / 4; ++v) {
+            const u32x4 c4 = cp[v];
+            seg_cnt[4 * v] = c4[0];
+            seg_cnt[4 * v + 1] = c4[1];
+            seg_cnt[4 * v + 2] = c4[2];
+            seg_cnt[4 * v + 3] = c4[3];
+        }
+    }
     const bool flagged = a.flag[q] != 0 && a.n_keys > 0;
     if (!flagged && part != 0) return;
     if (flagged) {
@@ -905,23 +919,21 @@ template <int KT> __global__ __launch_bounds__(256) void finalize_kernel(FinalAr
         uint32_t seg_n[CAND_SEGMENTS], seg_off[CAND_SEGMENTS], n = 0;
 #pragma unroll
         for (int sg = 0; sg < CAND_SEGMENTS; ++sg) {
-            uint32_t c = a.n_keys > 0 ? a.cnt[q * CAND_SEGMENTS + sg] : 0;
+            uint32_t c = a.n_keys > 0 ? seg_cnt[sg] : 0;
             seg_n[sg] = c < seg_cap ? c : seg_cap;
             seg_off[sg] = n;
             n += seg_n[sg];
         }
-        // Thread t takes positions t, t + 256, ... of the gathered list, four at a time: their loads (and, for a plain
-        // scan, the loads of 1/|k| that depend on them) are in flight together, where a loop over the segments would
-        // wait for one segment's words before asking for the next.
-        // A plain scan leaves (dot product, row): each candidate is finished here as the scan's exact test would have:
-        // the final score from the same three fp32 operations every kernel uses, no removed or out-of-range
-        // row, nothing below the threshold word.  What fails becomes a zero word, which sorts last.
+        // Thread t takes positions t, t + 256, ... of the gathered list, four at a time: their loads are in flight
+        // together, where a loop over the segments would wait for one segment's words before asking for the next.
+        // A plain scan leaves (dot * inv_k, row) of live rows: each candidate is finished here as the scan's exact test
+        // would have: the final score from the same three fp32 operations every kernel uses, nothing below the
+        // threshold word.  What fails becomes a zero word, which sorts last.
         const float iq = a.invq[q];
         const uint64_t t64 = a.raw ? a.thr64[q] : 0ull;
         const uint64_t *lists = a.cand + (size_t)q * a.cand_cap;
         for (uint32_t j0 = tid; j0 < n; j0 += 4 * 256) {
             uint64_t w[4];
-            float ik[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const uint32_t j = j0 + u * 256;
@@ -937,13 +949,8 @@ template <int KT> __global__ __launch_bounds__(256) void finalize_kernel(FinalAr
             if (a.raw) {
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    const uint32_t row = candidate_index(w[u]);
-                    ik[u] = (w[u] != 0ull && (int64_t)row < a.n_keys) ? a.inv_norm[row] : -1.0f;     // (negative: dropped below)
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const uint64_t c = pack_candidate(final_score(raw_candidate_dot(w[u]), ik[u], iq), candidate_index(w[u]));
-                    w[u] = (!row_removed(ik[u]) && c >= t64) ? c : 0ull;
+                    const uint64_t c = pack_candidate(raw_candidate_product(w[u]) * iq + 0.0f, candidate_index(w[u]));
+                    w[u] = (w[u] != 0ull && c >= t64) ? c : 0ull;
                 }
             }
 #pragma unroll

@@ -57,12 +57,13 @@ __device__ inline void flush_records(const ScanArgs &p, Record *region, uint32_t
 // collected with one v_alignbit each).  Survivors are rare (a handful per wave and item), and a wave spends
 // their cost with its matrix core idle, so as little as possible is done for them here: every lane with a
 // survivor picks its own element (a 16-way select, no wave-uniform walk and no exchange between lanes), checks
-// the tag predicate (the one test that can thin the records out by orders of magnitude) and appends
-// (raw dot, row, query) to the wave's private record region (no atomics: slot = the wave's running count + the
-// lane's rank among the appending lanes; flush_records moves a full region to the per-query lists).  The final
-// score, the removed-row test and the ordering are left to the kernel that selects from the lists: the
-// pre-filter admits an element whenever its final score can reach the threshold (and almost only then), so the
-// lists hold what they would hold after an exact test here.
+// the tag predicate (the one test that can thin the records out by orders of magnitude), drops removed rows and
+// appends (dot * inv_k, row, query) to the wave's private record region (no atomics: slot = the wave's running count +
+// the lane's rank among the appending lanes; flush_records moves a full region to the per-query lists).  The
+// second product of the final score, the exact threshold test and the ordering are left to the kernel that
+// selects from the lists, which needs nothing but the query's 1/|q| for them: the pre-filter admits an element
+// whenever its final score can reach the threshold (and almost only then), so the lists hold what they would hold
+// after an exact test here.
 struct EpiRows {               // 1/|k| of the 16 key rows a lane holds in one 32-row block
     float ik[16];
     float ikmax;
@@ -124,9 +125,10 @@ __device__ inline void main_block(const f32x16 &a, const EpiRows &rw, float tp, 
         const int i = 15 - b;
         const int rl = rw.rl0 + 8 * (i >> 2) + (i & 3);
         const uint64_t tg = filter ? sd.tag[rl] : 0ull;         // (in flight during the select)
+        const float ikv = sd.invk[rl];
         const float dot = select16(a, i);
         const int64_t row = row0 + rl;
-        bool ok = has && row < p.n_keys;
+        bool ok = has && row < p.n_keys && !row_removed(ikv);
         if (filter) ok = ok && (tg & qm) != 0;
         // slot in the wave's own record region: running count + rank among the lanes that append (up to 64 of
         // them: the region is emptied first when fewer slots are left)
@@ -135,7 +137,7 @@ __device__ inline void main_block(const f32x16 &a, const EpiRows &rw, float tp, 
         if (ok) {
             const uint32_t pos = wave_cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(okm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)okm, 0u));
             Record rec;
-            rec.cand = pack_raw_candidate(dot, (uint32_t)row);
+            rec.cand = pack_raw_candidate(dot * ikv, (uint32_t)row);       // final_score's first product
             rec.query = query;
             rec.pad = 0;
             region[pos] = rec;

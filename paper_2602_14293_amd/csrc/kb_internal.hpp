@@ -55,13 +55,14 @@ __host__ __device__ inline uint64_t pack_candidate(float score, uint32_t index)
     return ((uint64_t)score_to_ordered(score) << 32) | (uint32_t)(~index);
 }
 __host__ __device__ inline uint32_t candidate_index(uint64_t c) { return ~(uint32_t)c; }
-// What the main pass of a scan leaves in the candidate lists of a plain query: the fp32 dot product as it left the
-// matrix core instead of the ordered score (the kernel that selects from the lists derives the score), the same low word.
-__host__ __device__ inline uint64_t pack_raw_candidate(float dot, uint32_t index)
+// What the main pass of a scan leaves in the candidate lists of a plain query: the bits of dot * inv_k (the first
+// product of final_score) instead of the ordered score, which the kernel that selects from the lists derives with the
+// query's 1/|q|; the same low word.
+__host__ __device__ inline uint64_t pack_raw_candidate(float dot_inv_k, uint32_t index)
 {
-    return ((uint64_t)__builtin_bit_cast(uint32_t, dot) << 32) | (uint32_t)(~index);
+    return ((uint64_t)__builtin_bit_cast(uint32_t, dot_inv_k) << 32) | (uint32_t)(~index);
 }
-__host__ __device__ inline float raw_candidate_dot(uint64_t c) { return __builtin_bit_cast(float, (uint32_t)(c >> 32)); }
+__host__ __device__ inline float raw_candidate_product(uint64_t c) { return __builtin_bit_cast(float, (uint32_t)(c >> 32)); }
 __host__ __device__ inline float candidate_score(uint64_t c) { return ordered_to_score((uint32_t)(c >> 32)); }
 
 // The fp32 score every kernel of the library computes from an fp32 dot product.
