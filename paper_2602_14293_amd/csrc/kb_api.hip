@@ -678,12 +678,21 @@ template <int QT, bool KEYS> __global__ __launch_bounds__(1024) void threshold_k
     SelectScratch *sc = reinterpret_cast<SelectScratch *>(smem_raw + sizeof(uint64_t) * (slots > k ? slots : k));
     __shared__ float sh_iq;
     __shared__ uint32_t sh_low;
+    // Everything the kernel reads from global memory is asked for before anything waits: the query's mask word, the
+    // first two samples of every thread and (first wavefront) the query row are one memory round trip, not three.
+    const int bd = (int)blockDim.x;
+    uint64_t mask_word = 0ull, first0 = 0ull, first1 = 0ull;
+    if (!KEYS && tid == 0 && a.qmask && q < a.Q) mask_word = a.qmask[q];
+    if (KEYS || q < a.Q) {
+        if (tid < slots) first0 = a.samp[sample_slot_index(tid, a.group_shift, a.qpad, q)];
+        if (tid + bd < slots) first1 = a.samp[sample_slot_index(tid + bd, a.group_shift, a.qpad, q)];
+    }
     if constexpr (!KEYS) {
         if (tid < CAND_SEGMENTS) a.cnt[q * CAND_SEGMENTS + tid] = 0;
         if (tid == 0) {
             a.flag[q] = 0;
             a.fb_done[q] = 0;
-            a.qmask_pad[q] = (a.qmask && q < a.Q) ? a.qmask[q] : 0ull;
+            a.qmask_pad[q] = mask_word;
             sh_low = 0xffffffffu;
         }
         if (q == 0 && tid < STAT_WORDS + STAT_PARTIALS) a.stats[tid] = tid == 2 ? a.sample_keys : tid == 3 ? (uint64_t)a.grid : 0ull;
@@ -703,9 +712,11 @@ template <int QT, bool KEYS> __global__ __launch_bounds__(1024) void threshold_k
             }
         }
     }
-    for (int i = tid; i < slots; i += (int)blockDim.x) buf[i] = a.samp[sample_slot_index(i, a.group_shift, a.qpad, q)];
+    if (tid < slots) buf[tid] = first0;
+    if (tid + bd < slots) buf[tid + bd] = first1;
+    for (int i = tid + 2 * bd; i < slots; i += bd) buf[i] = a.samp[sample_slot_index(i, a.group_shift, a.qpad, q)];
     __syncthreads();
-    select_topk_desc(buf, slots, k, sc, tid, (int)blockDim.x);
+    select_topk_desc(buf, slots, k, sc, tid, bd);
     uint64_t t = k <= slots ? buf[k - 1] : 0ull;
     const float iq = KEYS ? a.invq[q] : sh_iq;
     if constexpr (!KEYS) {
@@ -789,8 +800,9 @@ template <int KT> __device__ void exhaustive_query(const FinalArgs &a, int q, ui
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[i] = 0.f;
         // The loads of UNR groups go out before their matrix instructions (the order of the accumulation does not
-        // change): one memory round trip per UNR groups instead of one per group.
-        constexpr int UNR = 8;
+        // change): one memory round trip per UNR groups instead of one per group (16 where a group is two registers
+        // quadruples, 8 where it is three or four).
+        constexpr int UNR = (Q8 || BMUL == 2) ? 8 : 16;
         if constexpr (Q8) {
             // one fp8 matrix instruction per 64-byte chunk: lane half h supplies bytes [32h, 32h+32) of its key row
             // and of the query row, the operand layout the scan uses, so both paths give the same bits
